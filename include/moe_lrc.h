@@ -1,0 +1,161 @@
+/*
+ * moe_lrc — one MoE layer's forward pass with router-guided low-rank compensation, for MI355X.
+ *
+ * The layer follows the paper's statement of the problem:
+ *   routing        w = softmax(G(x)), the k highest-scored experts are activated     (Section 2.1)
+ *   Top-n marking  the n < k highest-scored of those k take the compensator          (Section 3.2)
+ *   expert weights W_hat_e = Qinv(Q(W_e)) + U_e V_e for a Top-n (token, expert) pair,
+ *                  Qinv(Q(W_e)) for every other activated pair                       (Sections 2.3, 3.2)
+ *   output         y = sum_{i in TopK} w_i E_i(x), plus always-on shared experts      (Section 2.1, Table 1)
+ *   transfer       packed low-bit experts of every activated expert and the factors of
+ *                  Top-n experts only are brought host -> device on demand           (Sections 3.2, 4.3 case 1)
+ *
+ * Conventions
+ *   - plain C ABI; every call returns 0 on success or a negative MOE_LRC_E* code; the text of the
+ *     last error on the calling thread is available from moe_lrc_last_error().
+ *   - "host" / "device" in a parameter comment says where the memory lives.  Device buffers are
+ *     owned by the caller (activations, indices, outputs, workspace); the library owns the layer
+ *     object, its packed weights, the pinned host pool and the device slot pool.  set_* calls copy
+ *     out of the caller's host memory before they return and keep no pointer.
+ *   - hot-path calls are asynchronous on `stream` (a hipStream_t passed as void*, NULL = default
+ *     stream), allocate nothing and do not synchronise, with one exception: a layer created with
+ *     residency = MOE_LRC_STAGED reads the per-expert counts back (<= 2 KiB) inside
+ *     moe_lrc_expert_ffn / moe_lrc_forward to decide which experts to copy, and therefore
+ *     synchronises `stream` once per call.
+ *   - argument errors are reported before any device work is issued.
+ *   - matrices are input-dim-major: W[K_in][N_out], y = x W.  mat 0 = W1 (gate projection,
+ *     [H][F]), 1 = W3 (up projection, [H][F]), 2 = W2 (down projection, [F][H]);
+ *     E_i(x) = (silu(x W1) * (x W3)) W2.
+ *   - bf16 / fp16 values cross the ABI as their uint16_t bit patterns.
+ */
+#ifndef MOE_LRC_H
+#define MOE_LRC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOE_LRC_OK       0
+#define MOE_LRC_EINVAL  -1   /* null pointer or value out of range                      */
+#define MOE_LRC_ESHAPE  -2   /* shape not supported by the kernels                       */
+#define MOE_LRC_ESTATE  -3   /* call order: gate or an expert not uploaded, T too large  */
+#define MOE_LRC_ENOMEM  -4   /* allocation failed, or workspace too small                */
+#define MOE_LRC_EHIP    -5   /* a HIP runtime call failed (no device, launch error)      */
+
+#define MOE_LRC_RESIDENT 0   /* packed experts live in device memory                      */
+#define MOE_LRC_STAGED   1   /* packed experts live in pinned host memory and are copied  */
+                             /* per call through a device slot pool on a side stream      */
+
+typedef struct {
+  int32_t hidden;       /* H, multiple of 64                                              */
+  int32_t ffn;          /* F, multiple of 64                                              */
+  int32_t n_experts;    /* E routed experts, 1..256                                       */
+  int32_t n_shared;     /* S always-on shared experts (Table 1 note), 0..8                */
+  int32_t top_k;        /* k, 1..min(E,16)                                                */
+  int32_t top_n;        /* n, 0..k: slots 0..n-1 of a token's sorted list are compensated */
+  int32_t bits;         /* code width of routed experts: 2, 3 or 4                        */
+  int32_t shared_bits;  /* code width of shared experts: 2, 3 or 4 (ignored if S == 0)    */
+  int32_t group;        /* quantization group along the input dim: 64, 128 or 256         */
+  int32_t rank;         /* compensator rank r >= 0, multiple of 8, <= 256                 */
+  int32_t renormalize;  /* 0: routing weights are the softmax-over-all scores (Section 2.1)
+                           1: divided by their sum over the k selected                    */
+  int32_t max_tokens;   /* largest T any call will pass                                   */
+  int32_t residency;    /* MOE_LRC_RESIDENT or MOE_LRC_STAGED                             */
+} moe_lrc_config;
+
+typedef struct moe_lrc_layer moe_lrc_layer;
+
+/* Thread-local text of the last error returned on this thread ("" if none). */
+const char* moe_lrc_last_error(void);
+
+/* Creates a layer on the current HIP device.  Allocates the packed-weight storage (device, or
+ * pinned host + device slots when staged).  *out is set only on success. */
+int moe_lrc_layer_create(const moe_lrc_config* cfg, moe_lrc_layer** out);
+int moe_lrc_layer_destroy(moe_lrc_layer* layer);
+
+/* Gate G(x) = x Wg^T (+ bias) of Section 2.1.  wg_bf16: host [E][H].  bias_f32: host [E] or NULL
+ * (added to the logits before the softmax). */
+int moe_lrc_set_gate(moe_lrc_layer* layer, const uint16_t* wg_bf16, const float* bias_f32);
+
+/* Stored artefacts of one projection of one expert (Sections 2.3, 3.1 step 2), all host memory:
+ *   codes      one code per byte, [K][N], each < 2^bits
+ *   scale_f16  [K/group][N];  zero_f16 [K/group][N];  Qinv(q) = (q - zero) * scale
+ *   A_bf16     [K][r] = U sqrt(S);  B_bf16 [r][N] = sqrt(S) V^T   (both NULL when rank == 0 or the
+ *              expert is shared; shared experts are never compensated)
+ * expert in [0,E) is routed, [E,E+S) shared.  The library repacks into its private bit-packed
+ * layout (dense `bits` per weight); moe_lrc_debug_unpack reads it back. */
+int moe_lrc_set_expert(moe_lrc_layer* layer, int expert, int mat, const uint8_t* codes,
+                       const uint16_t* scale_f16, const uint16_t* zero_f16,
+                       const uint16_t* A_bf16, const uint16_t* B_bf16);
+
+/* Bytes of device workspace the hot-path calls need for T tokens (the largest over all calls). */
+size_t moe_lrc_workspace_bytes(const moe_lrc_layer* layer, int T);
+
+/* Routing (Section 2.1) and Top-n order (Section 3.2).
+ *   x_bf16    device [T][H]
+ *   topk_idx  device [T][k] int32, experts in descending score order, ties to the lower index;
+ *             slots 0..n-1 are the token's Top-n experts
+ *   topk_w    device [T][k] float, the routing weights of those experts
+ * The gate dot products are accumulated in fp64 so that the selection equals the exact one. */
+int moe_lrc_route(moe_lrc_layer* layer, const void* x_bf16, int T,
+                  int32_t* topk_idx, float* topk_w, void* stream);
+
+/* Groups the T*k (token, slot) pairs by expert; rows are sorted by (expert asc, token asc).
+ * All arrays device int32: counts[E], offsets[E+1] (exclusive scan, offsets[E] = T*k),
+ * row_pair[T*k] (row -> t*k+j), pair_row[T*k] (inverse), comp_counts[E] (pairs with j < n). */
+int moe_lrc_permute(moe_lrc_layer* layer, const int32_t* topk_idx, int T,
+                    int32_t* counts, int32_t* offsets, int32_t* row_pair, int32_t* pair_row,
+                    int32_t* comp_counts, void* stream);
+
+/* Expert FFN on the grouped rows (Sections 2.3, 3.2): for row p holding pair (t, j) of expert e,
+ *   y_rows[p] = E_e(x_t) with W_hat = Qinv(Q(W)) + [j < n] A B for each of the three projections,
+ * the low-rank term applied as (x A) B.  y_rows_bf16: device [T*k][H].  ws: device workspace of
+ * at least moe_lrc_workspace_bytes(layer, T) bytes, 256-byte aligned. */
+int moe_lrc_expert_ffn(moe_lrc_layer* layer, const void* x_bf16, int T,
+                       const int32_t* offsets, const int32_t* row_pair,
+                       void* y_rows_bf16, void* ws, size_t ws_bytes, void* stream);
+
+/* out[t] = sum_j topk_w[t][j] * y_rows[pair_row[t*k+j]]  (+ sum over shared experts of E_s(x_t),
+ * weight 1, which is why x is passed).  Fixed summation order, no atomics.  out_bf16: device [T][H]. */
+int moe_lrc_combine(moe_lrc_layer* layer, const void* y_rows_bf16, const float* topk_w,
+                    const int32_t* pair_row, const void* x_bf16, int T,
+                    void* out_bf16, void* ws, size_t ws_bytes, void* stream);
+
+/* The whole layer: route -> permute -> (stage) -> expert_ffn -> combine, intermediates in ws.
+ * Indices equal those of the four separate calls; `out` equals theirs bit for bit. */
+int moe_lrc_forward(moe_lrc_layer* layer, const void* x_bf16, int T, void* out_bf16,
+                    void* ws, size_t ws_bytes, void* stream);
+
+/* ---- evidence and test hooks ------------------------------------------------------------- */
+
+/* Unpacks the layer's private copy of one projection back to one code per byte, device [K][N]. */
+int moe_lrc_debug_unpack(moe_lrc_layer* layer, int expert, int mat, uint8_t* codes_dev, void* stream);
+
+/* Host-only packing round trip (no device needed): packs codes [K][N] into the private layout
+ * (packed must hold moe_lrc_packed_bytes(bits, K, N) bytes) and back. */
+size_t moe_lrc_packed_bytes(int bits, int K, int N);
+int moe_lrc_pack_codes(int bits, int K, int N, const uint8_t* codes, void* packed);
+int moe_lrc_unpack_codes(int bits, int K, int N, const void* packed, uint8_t* codes);
+
+typedef struct {
+  uint64_t bytes_codes;    /* packed code bytes of experts with at least one routed pair         */
+  uint64_t bytes_meta;     /* fp16 scale+zero bytes of those experts                             */
+  uint64_t bytes_factors;  /* bf16 factor bytes of experts with at least one Top-n pair          */
+  int32_t  active_experts;
+  int32_t  comp_experts;
+  int32_t  path;           /* kernel path of the last expert_ffn: 0 = skinny (decode), 1 = tiled */
+  float    stage_ms;       /* staged mode: time of the last call's host->device copies, else 0   */
+} moe_lrc_stats;
+
+/* Counters of the last moe_lrc_expert_ffn / moe_lrc_forward on this layer.  In staged mode they
+ * are exact (the counts are read back anyway); in resident mode this call synchronises the device
+ * and reads the counts of the last call. */
+int moe_lrc_get_stats(moe_lrc_layer* layer, moe_lrc_stats* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_LRC_H */

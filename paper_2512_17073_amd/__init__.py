@@ -1,0 +1,5 @@
+"""MI355X-native MoE layer with router-guided low-rank compensation: HIP kernels behind a C ABI
+(libmoe_lrc.so) and a thin ctypes binding.  Importing the package does not load the library;
+the first call does, and raises if it has not been built."""
+from .binding import (RESIDENT, STAGED, Config, Layer, MoeLrcError, Stats, bf16_tensor, lib,  # noqa: F401
+                      pack_codes, unpack_codes)

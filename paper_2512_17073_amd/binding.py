@@ -1,0 +1,253 @@
+"""Thin ctypes binding of libmoe_lrc.so: argument marshalling only.
+
+Every step of the layer runs in the library's HIP kernels; PyTorch appears here only as the owner
+of device buffers and the source of the current HIP stream.  There is no fallback: if the shared
+library is missing, importing a symbol raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmoe_lrc.so")
+
+RESIDENT, STAGED = 0, 1
+
+# every symbol include/moe_lrc.h declares
+EXPORTS = [
+    "moe_lrc_last_error", "moe_lrc_layer_create", "moe_lrc_layer_destroy", "moe_lrc_set_gate",
+    "moe_lrc_set_expert", "moe_lrc_workspace_bytes", "moe_lrc_route", "moe_lrc_permute",
+    "moe_lrc_expert_ffn", "moe_lrc_combine", "moe_lrc_forward", "moe_lrc_debug_unpack",
+    "moe_lrc_packed_bytes", "moe_lrc_pack_codes", "moe_lrc_unpack_codes", "moe_lrc_get_stats",
+]
+
+
+class Config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "hidden", "ffn", "n_experts", "n_shared", "top_k", "top_n", "bits", "shared_bits", "group",
+        "rank", "renormalize", "max_tokens", "residency")]
+
+
+class Stats(C.Structure):
+    _fields_ = [("bytes_codes", C.c_uint64), ("bytes_meta", C.c_uint64), ("bytes_factors", C.c_uint64),
+                ("active_experts", C.c_int32), ("comp_experts", C.c_int32), ("path", C.c_int32),
+                ("stage_ms", C.c_float)]
+
+
+class MoeLrcError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"moe_lrc error {code}: {text}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads the built library (raises if it has not been built: there is no other path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is not built; run `python -m paper_2512_17073_amd.build` "
+                                    "(or __graft_entry__.build()) first")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, sz = C.c_void_p, C.c_int, C.c_size_t
+        L.moe_lrc_last_error.restype = C.c_char_p
+        L.moe_lrc_layer_create.argtypes = [C.POINTER(Config), C.POINTER(vp)]
+        L.moe_lrc_layer_destroy.argtypes = [vp]
+        L.moe_lrc_set_gate.argtypes = [vp, vp, vp]
+        L.moe_lrc_set_expert.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp]
+        L.moe_lrc_workspace_bytes.argtypes = [vp, i32]
+        L.moe_lrc_workspace_bytes.restype = sz
+        L.moe_lrc_route.argtypes = [vp, vp, i32, vp, vp, vp]
+        L.moe_lrc_permute.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp, vp]
+        L.moe_lrc_expert_ffn.argtypes = [vp, vp, i32, vp, vp, vp, vp, sz, vp]
+        L.moe_lrc_combine.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
+        L.moe_lrc_forward.argtypes = [vp, vp, i32, vp, vp, sz, vp]
+        L.moe_lrc_debug_unpack.argtypes = [vp, i32, i32, vp, vp]
+        L.moe_lrc_packed_bytes.argtypes = [i32, i32, i32]
+        L.moe_lrc_packed_bytes.restype = sz
+        L.moe_lrc_pack_codes.argtypes = [i32, i32, i32, vp, vp]
+        L.moe_lrc_unpack_codes.argtypes = [i32, i32, i32, vp, vp]
+        L.moe_lrc_get_stats.argtypes = [vp, C.POINTER(Stats)]
+        _lib = L
+    return _lib
+
+
+def last_error() -> str:
+    return lib().moe_lrc_last_error().decode()
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise MoeLrcError(rc, last_error())
+
+
+def _host(a: Optional[np.ndarray], dtype) -> Optional[np.ndarray]:
+    if a is None:
+        return None
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def _hp(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+# ---- host-only helpers (no device) ----------------------------------------------------------
+def pack_codes(bits: int, codes: np.ndarray) -> np.ndarray:
+    codes = _host(codes, np.uint8)
+    K, N = codes.shape
+    nbytes = lib().moe_lrc_packed_bytes(bits, K, N)
+    if nbytes == 0:
+        raise MoeLrcError(-2, "unsupported shape for packing")
+    out = np.zeros(nbytes, dtype=np.uint8)
+    _check(lib().moe_lrc_pack_codes(bits, K, N, _hp(codes), _hp(out)))
+    return out
+
+
+def unpack_codes(bits: int, K: int, N: int, packed: np.ndarray) -> np.ndarray:
+    packed = _host(packed, np.uint8)
+    out = np.empty((K, N), dtype=np.uint8)
+    _check(lib().moe_lrc_unpack_codes(bits, K, N, _hp(packed), _hp(out)))
+    return out
+
+
+class Layer:
+    """One MoE layer object of the library.  Methods mirror the C calls one to one."""
+
+    def __init__(self, *, hidden, ffn, n_experts, top_k, top_n, bits, group, rank, max_tokens,
+                 n_shared=0, shared_bits=4, renormalize=0, residency=RESIDENT):
+        self.cfg = Config(hidden, ffn, n_experts, n_shared, top_k, top_n, bits, shared_bits, group,
+                          rank, renormalize, max_tokens, residency)
+        self._h = C.c_void_p()
+        _check(lib().moe_lrc_layer_create(C.byref(self.cfg), C.byref(self._h)))
+        self._ws = None
+
+    @classmethod
+    def from_config(cls, cfg, max_tokens=None, residency=RESIDENT) -> "Layer":
+        """cfg: any object with the workload fields (hidden, ffn, n_experts, ...)."""
+        return cls(hidden=cfg.hidden, ffn=cfg.ffn, n_experts=cfg.n_experts, top_k=cfg.top_k,
+                   top_n=cfg.top_n, bits=cfg.bits, group=cfg.group, rank=cfg.rank,
+                   max_tokens=max_tokens or cfg.tokens, n_shared=cfg.n_shared,
+                   shared_bits=cfg.shared_bits, renormalize=cfg.renormalize, residency=residency)
+
+    def close(self) -> None:
+        if self._h:
+            lib().moe_lrc_layer_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- uploads (host arrays) ----
+    def set_gate(self, wg_bf16: np.ndarray, bias: Optional[np.ndarray] = None) -> None:
+        wg = _host(wg_bf16, np.uint16)
+        b = _host(bias, np.float32)
+        _check(lib().moe_lrc_set_gate(self._h, _hp(wg), _hp(b)))
+
+    def set_expert(self, expert: int, mat: int, codes, scale_f16, zero_f16, A_bf16=None, B_bf16=None) -> None:
+        arrs = [_host(codes, np.uint8), _host(scale_f16, np.uint16), _host(zero_f16, np.uint16),
+                _host(A_bf16, np.uint16), _host(B_bf16, np.uint16)]
+        _check(lib().moe_lrc_set_expert(self._h, expert, mat, *[_hp(a) for a in arrs]))
+
+    def load(self, layer: dict) -> None:
+        """layer = {"wg", "bias", "experts": [{mat: {"codes","scale","zero","A","B"}}]}."""
+        self.set_gate(layer["wg"], layer.get("bias"))
+        for e, ex in enumerate(layer["experts"]):
+            for mat in (0, 1, 2):
+                a = ex[mat]
+                self.set_expert(e, mat, a["codes"], a["scale"], a["zero"], a.get("A"), a.get("B"))
+
+    # ---- workspace ----
+    def workspace_bytes(self, T: int) -> int:
+        return lib().moe_lrc_workspace_bytes(self._h, T)
+
+    def workspace(self, T: int):
+        import torch
+        need = self.workspace_bytes(T)
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+        return self._ws
+
+    # ---- hot path (torch CUDA tensors in, torch CUDA tensors out) ----
+    def route(self, x):
+        import torch
+        T, k = x.shape[0], self.cfg.top_k
+        idx = torch.empty((T, k), dtype=torch.int32, device=x.device)
+        w = torch.empty((T, k), dtype=torch.float32, device=x.device)
+        _check(lib().moe_lrc_route(self._h, x.data_ptr(), T, idx.data_ptr(), w.data_ptr(), _stream()))
+        return idx, w
+
+    def permute(self, topk_idx):
+        import torch
+        T, k, E = topk_idx.shape[0], self.cfg.top_k, self.cfg.n_experts
+        dev = topk_idx.device
+        counts = torch.empty(E, dtype=torch.int32, device=dev)
+        offsets = torch.empty(E + 1, dtype=torch.int32, device=dev)
+        row_pair = torch.empty(T * k, dtype=torch.int32, device=dev)
+        pair_row = torch.empty(T * k, dtype=torch.int32, device=dev)
+        comp = torch.empty(E, dtype=torch.int32, device=dev)
+        _check(lib().moe_lrc_permute(self._h, topk_idx.data_ptr(), T, counts.data_ptr(), offsets.data_ptr(),
+                                     row_pair.data_ptr(), pair_row.data_ptr(), comp.data_ptr(), _stream()))
+        return counts, offsets, row_pair, pair_row, comp
+
+    def expert_ffn(self, x, offsets, row_pair):
+        import torch
+        T = x.shape[0]
+        y = torch.empty((T * self.cfg.top_k, self.cfg.hidden), dtype=torch.bfloat16, device=x.device)
+        ws = self.workspace(T)
+        _check(lib().moe_lrc_expert_ffn(self._h, x.data_ptr(), T, offsets.data_ptr(), row_pair.data_ptr(),
+                                        y.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
+        return y
+
+    def combine(self, y_rows, topk_w, pair_row, x):
+        import torch
+        T = x.shape[0]
+        out = torch.empty((T, self.cfg.hidden), dtype=torch.bfloat16, device=x.device)
+        ws = self.workspace(T)
+        _check(lib().moe_lrc_combine(self._h, y_rows.data_ptr(), topk_w.data_ptr(), pair_row.data_ptr(),
+                                     x.data_ptr(), T, out.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
+        return out
+
+    def forward(self, x, out=None):
+        import torch
+        T = x.shape[0]
+        if out is None:
+            out = torch.empty((T, self.cfg.hidden), dtype=torch.bfloat16, device=x.device)
+        ws = self.workspace(T)
+        _check(lib().moe_lrc_forward(self._h, x.data_ptr(), T, out.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
+        return out
+
+    def forward_raw(self, x_ptr: int, T: int, out_ptr: int, ws_ptr: int, ws_bytes: int, stream: int) -> None:
+        _check(lib().moe_lrc_forward(self._h, x_ptr, T, out_ptr, ws_ptr, ws_bytes, stream))
+
+    # ---- hooks ----
+    def debug_unpack(self, expert: int, mat: int):
+        import torch
+        K, N = (self.cfg.ffn, self.cfg.hidden) if mat == 2 else (self.cfg.hidden, self.cfg.ffn)
+        codes = torch.empty((K, N), dtype=torch.uint8, device="cuda")
+        _check(lib().moe_lrc_debug_unpack(self._h, expert, mat, codes.data_ptr(), _stream()))
+        return codes
+
+    def stats(self) -> dict:
+        s = Stats()
+        _check(lib().moe_lrc_get_stats(self._h, C.byref(s)))
+        return {n: getattr(s, n) for n, _ in Stats._fields_}
+
+
+def bf16_tensor(bits: np.ndarray, device="cuda"):
+    """uint16 bf16 bit patterns -> torch.bfloat16 tensor on `device` (a reinterpretation, no arithmetic)."""
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).to(device)

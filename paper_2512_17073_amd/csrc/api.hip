@@ -1,0 +1,472 @@
+// Host side of the C ABI declared in include/moe_lrc.h: argument checking, the layer object and its
+// packed-weight storage, workspace carving, the router-guided staging of packed experts and
+// factors from the pinned pool (Sections 3.2 and 4.3 case 1), and the launch sequence.
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "internal.h"
+#include "pack.h"
+
+using namespace lrc;
+
+namespace lrc {
+
+static thread_local std::string g_last_error;
+
+int set_error(int code, const std::string& msg) {
+  g_last_error = msg;
+  return code;
+}
+
+#define LRC_HIP(expr)                                                                       \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess)                                                                   \
+      return set_error(MOE_LRC_EHIP, std::string(#expr) + ": " + hipGetErrorString(e_));    \
+  } while (0)
+
+static BlobLayout make_blob(const moe_lrc_config& c, int bits, int rank) {
+  BlobLayout b{};
+  size_t w = 0, f = 0;
+  for (int mat = 0; mat < 3; ++mat) {
+    const int K = mat == 2 ? c.ffn : c.hidden, N = mat == 2 ? c.hidden : c.ffn;
+    b.mat[mat] = make_layout(K, N, bits, c.group, rank);
+    b.off_codes[mat] = w; w += b.mat[mat].codes_bytes;
+    b.off_meta[mat] = w;  w += b.mat[mat].meta_bytes;
+    if (rank > 0) {
+      b.off_af[mat] = f; f += b.mat[mat].af_bytes;
+      b.off_bf[mat] = f; f += b.mat[mat].bf_bytes;
+    }
+  }
+  b.w_bytes = w;
+  b.f_bytes = f;
+  return b;
+}
+
+static int check_config(const moe_lrc_config& c) {
+  auto bad = [](const char* what) { return set_error(MOE_LRC_EINVAL, std::string("config: ") + what); };
+  auto shape = [](const char* what) { return set_error(MOE_LRC_ESHAPE, std::string("config: ") + what); };
+  if (c.hidden <= 0 || c.ffn <= 0) return bad("hidden and ffn must be positive");
+  if (c.n_experts < 1 || c.n_experts > 256) return bad("n_experts must be in 1..256");
+  if (c.n_shared < 0 || c.n_shared > 8) return bad("n_shared must be in 0..8");
+  if (c.top_k < 1 || c.top_k > 16 || c.top_k > c.n_experts) return bad("top_k must be in 1..min(n_experts,16)");
+  if (c.top_n < 0 || c.top_n > c.top_k) return bad("top_n must be in 0..top_k");
+  if (c.bits < 2 || c.bits > 4) return bad("bits must be 2, 3 or 4");
+  if (c.n_shared > 0 && (c.shared_bits < 2 || c.shared_bits > 4)) return bad("shared_bits must be 2, 3 or 4");
+  if (c.rank < 0 || c.rank > 256 || c.rank % 8) return bad("rank must be a multiple of 8 in 0..256");
+  if (c.renormalize != 0 && c.renormalize != 1) return bad("renormalize must be 0 or 1");
+  if (c.max_tokens < 1 || (long long)c.max_tokens * c.top_k > (1 << 24)) return bad("max_tokens out of range");
+  if (c.residency != MOE_LRC_RESIDENT && c.residency != MOE_LRC_STAGED) return bad("residency must be 0 or 1");
+  if (c.group != 64 && c.group != 128 && c.group != 256) return shape("group must be 64, 128 or 256");
+  if (c.hidden % 64 || c.ffn % 64) return shape("hidden and ffn must be multiples of 64");
+  if (c.hidden % c.group || c.ffn % c.group) return shape("hidden and ffn must be multiples of group");
+  return MOE_LRC_OK;
+}
+
+Workspace plan_workspace(const moe_lrc_layer* L, int T) {
+  const moe_lrc_config& c = L->cfg;
+  const size_t P = size_t(T) * c.top_k, E = c.n_experts;
+  const size_t rpad = L->routed.mat[0].rpad;
+  Workspace w{};
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o += align256(bytes); return at; };
+  w.topk_idx = take(P * 4);  w.topk_w = take(P * 4);
+  w.counts = take(E * 4);    w.offsets = take((E + 1) * 4);  w.comp_counts = take(E * 4);
+  w.row_pair = take(P * 4);  w.pair_row = take(P * 4);
+  w.y_rows = take(P * c.hidden * 2);
+  w.xh = take(size_t(T) * c.hidden * 2);
+  w.h = take(P * c.ffn * 2);
+  w.p13 = take(size_t(L->ksplit13) * P * 2 * rpad * 4);
+  w.p2 = take(size_t(L->ksplit2) * P * rpad * 4);
+  w.sh_h = take(size_t(c.n_shared) * T * c.ffn * 2);
+  w.sh_y = take(size_t(c.n_shared) * T * c.hidden * 2);
+  w.total = o;
+  return w;
+}
+
+static const BlobLayout& blob_of(const moe_lrc_layer* L, int expert) {
+  return expert < L->cfg.n_experts ? L->routed : L->shared;
+}
+
+static int check_hot(const moe_lrc_layer* L, int T, const char* fn) {
+  if (!L) return set_error(MOE_LRC_EINVAL, std::string(fn) + ": layer is null");
+  if (T < 0 || T > L->cfg.max_tokens)
+    return set_error(MOE_LRC_ESTATE, std::string(fn) + ": T outside 0..max_tokens");
+  return MOE_LRC_OK;
+}
+
+static int check_uploaded(const moe_lrc_layer* L, const char* fn, bool routed, bool shared) {
+  const int E = L->cfg.n_experts;
+  for (int e = routed ? 0 : E; e < (shared ? L->n_total : E); ++e)
+    for (int m = 0; m < 3; ++m)
+      if (!L->mat_set[e * 3 + m])
+        return set_error(MOE_LRC_ESTATE, std::string(fn) + ": expert " + std::to_string(e) +
+                                             " projection " + std::to_string(m) + " not uploaded");
+  return MOE_LRC_OK;
+}
+
+static int check_ws(const moe_lrc_layer* L, int T, const void* ws, size_t ws_bytes, const char* fn) {
+  if (!ws) return set_error(MOE_LRC_EINVAL, std::string(fn) + ": workspace is null");
+  if ((uintptr_t)ws & 255) return set_error(MOE_LRC_EINVAL, std::string(fn) + ": workspace must be 256-byte aligned");
+  if (ws_bytes < plan_workspace(L, T).total)
+    return set_error(MOE_LRC_ENOMEM, std::string(fn) + ": workspace smaller than moe_lrc_workspace_bytes");
+  return MOE_LRC_OK;
+}
+
+static void fill_algorithmic_stats(moe_lrc_layer* L, const int32_t* stat) {
+  const moe_lrc_config& c = L->cfg;
+  const uint64_t P = 3ull * c.hidden * c.ffn;
+  moe_lrc_stats& s = L->stats;
+  s.active_experts = stat[0];
+  s.comp_experts = (c.rank > 0 && c.top_n > 0) ? stat[1] : 0;
+  s.bytes_codes = uint64_t(stat[0]) * (P * c.bits / 8) + uint64_t(c.n_shared) * (P * c.shared_bits / 8);
+  s.bytes_meta = uint64_t(stat[0] + c.n_shared) * (P / c.group * 4);
+  s.bytes_factors = uint64_t(s.comp_experts) * 3ull * c.rank * (c.hidden + c.ffn) * 2;
+  L->stats_valid = true;
+}
+
+// Copies the packed blobs of every expert that received a row, and the factor blobs of every expert
+// that received a Top-n row, from the pinned pool into the device slots on the side stream.
+static int stage_selected(moe_lrc_layer* L, hipStream_t stream) {
+  const moe_lrc_config& c = L->cfg;
+  const int E = c.n_experts;
+  LRC_HIP(hipMemcpyAsync(L->h_stat, L->d_stat, (2 + 2 * E) * 4, hipMemcpyDeviceToHost, stream));
+  LRC_HIP(hipStreamSynchronize(stream));       // the one host read-back: which experts are needed
+  fill_algorithmic_stats(L, L->h_stat);
+  LRC_HIP(hipEventRecord(L->ev_t0, L->side));
+  for (int e = 0; e < L->n_total; ++e) {
+    const bool shared = e >= E;
+    const BlobLayout& b = blob_of(L, e);
+    if (shared || L->h_stat[2 + e] > 0)
+      LRC_HIP(hipMemcpyAsync(L->d_w + L->w_off[e], L->h_w + L->w_off[e], b.w_bytes, hipMemcpyHostToDevice, L->side));
+    if (!shared && b.f_bytes && c.top_n > 0 && L->h_stat[2 + E + e] > 0)
+      LRC_HIP(hipMemcpyAsync(L->d_f + L->f_off[e], L->h_f + L->f_off[e], b.f_bytes, hipMemcpyHostToDevice, L->side));
+  }
+  LRC_HIP(hipEventRecord(L->ev_t1, L->side));
+  LRC_HIP(hipStreamWaitEvent(stream, L->ev_t1, 0));
+  return MOE_LRC_OK;
+}
+
+static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t* offsets,
+                          const int32_t* row_pair, void* y_rows, uint8_t* ws, hipStream_t stream) {
+  const moe_lrc_config& c = L->cfg;
+  const Workspace w = plan_workspace(L, T);
+  _Float16* xh = reinterpret_cast<_Float16*>(ws + w.xh);
+  LRC_HIP(launch_convert_x(L, x, T, xh, offsets, row_pair, L->d_stat, stream));
+  L->stats_valid = false;
+  L->stats.stage_ms = 0.f;
+  if (c.residency == MOE_LRC_STAGED) {
+    const int rc = stage_selected(L, stream);
+    if (rc) return rc;
+  }
+  FfnArgs a{};
+  a.desc = L->d_desc; a.n_exp = c.n_experts; a.bits = c.bits; a.group = c.group;
+  a.rank = c.rank; a.rpad = L->routed.mat[0].rpad;
+  a.H = c.hidden; a.F = c.ffn; a.top_k = c.top_k; a.top_n = c.top_n; a.T = T;
+  a.offsets = offsets; a.row_pair = row_pair; a.xh = xh;
+  a.h = reinterpret_cast<_Float16*>(ws + w.h);
+  a.p13 = reinterpret_cast<float*>(ws + w.p13); a.p2 = reinterpret_cast<float*>(ws + w.p2);
+  a.y_rows = y_rows; a.ksplit13 = L->ksplit13; a.ksplit2 = L->ksplit2; a.total_rows = T * c.top_k;
+  LRC_HIP(launch_expert_ffn(a, stream));
+  L->stats.path = 0;
+  return MOE_LRC_OK;
+}
+
+static int run_shared(moe_lrc_layer* L, const void* x, int T, uint8_t* ws, bool xh_ready, hipStream_t stream) {
+  const moe_lrc_config& c = L->cfg;
+  const Workspace w = plan_workspace(L, T);
+  _Float16* xh = reinterpret_cast<_Float16*>(ws + w.xh);
+  if (!xh_ready) LRC_HIP(launch_convert_x(L, x, T, xh, nullptr, nullptr, nullptr, stream));
+  FfnArgs a{};
+  a.desc = L->d_desc + c.n_experts; a.n_exp = c.n_shared; a.bits = c.shared_bits; a.group = c.group;
+  a.rank = 0; a.rpad = 0; a.H = c.hidden; a.F = c.ffn; a.top_k = c.top_k; a.top_n = 0; a.T = T;
+  a.offsets = nullptr; a.row_pair = nullptr; a.xh = xh;
+  a.h = reinterpret_cast<_Float16*>(ws + w.sh_h);
+  a.y_rows = ws + w.sh_y; a.ksplit13 = 1; a.ksplit2 = 1; a.total_rows = T * c.n_shared;
+  LRC_HIP(launch_expert_ffn(a, stream));
+  return MOE_LRC_OK;
+}
+
+}  // namespace lrc
+
+extern "C" {
+
+const char* moe_lrc_last_error(void) { return g_last_error.c_str(); }
+
+int moe_lrc_layer_create(const moe_lrc_config* cfg, moe_lrc_layer** out) {
+  if (!cfg || !out) return set_error(MOE_LRC_EINVAL, "layer_create: null argument");
+  int rc = check_config(*cfg);
+  if (rc) return rc;
+  int dev = 0;
+  LRC_HIP(hipGetDevice(&dev));
+  moe_lrc_layer* L = new (std::nothrow) moe_lrc_layer();
+  if (!L) return set_error(MOE_LRC_ENOMEM, "layer_create: out of host memory");
+  L->cfg = *cfg;
+  L->device = dev;
+  L->n_total = cfg->n_experts + cfg->n_shared;
+  L->routed = make_blob(*cfg, cfg->bits, cfg->rank);
+  L->shared = make_blob(*cfg, cfg->n_shared ? cfg->shared_bits : cfg->bits, 0);
+  L->ksplit13 = std::max(1, std::min(8, cfg->hidden / 512));
+  L->ksplit2 = std::max(1, std::min(16, cfg->ffn / 512));
+  L->mat_set.assign(size_t(L->n_total) * 3, 0);
+  size_t w = 0, f = 0;
+  for (int e = 0; e < L->n_total; ++e) {
+    L->w_off.push_back(w); L->f_off.push_back(f);
+    w += blob_of(L, e).w_bytes; f += blob_of(L, e).f_bytes;
+  }
+  auto fail = [&](int code) { moe_lrc_layer_destroy(L); return code; };
+#define LRC_TRY(expr)                                                                             \
+  do {                                                                                            \
+    hipError_t e_ = (expr);                                                                       \
+    if (e_ != hipSuccess)                                                                         \
+      return fail(set_error(e_ == hipErrorOutOfMemory ? MOE_LRC_ENOMEM : MOE_LRC_EHIP,            \
+                            std::string(#expr) + ": " + hipGetErrorString(e_)));                  \
+  } while (0)
+  LRC_TRY(hipMalloc((void**)&L->d_w, std::max<size_t>(w, 256)));
+  LRC_TRY(hipMalloc((void**)&L->d_f, std::max<size_t>(f, 256)));
+  if (cfg->residency == MOE_LRC_STAGED) {
+    LRC_TRY(hipHostMalloc((void**)&L->h_w, std::max<size_t>(w, 256), hipHostMallocDefault));
+    LRC_TRY(hipHostMalloc((void**)&L->h_f, std::max<size_t>(f, 256), hipHostMallocDefault));
+    LRC_TRY(hipStreamCreateWithFlags(&L->side, hipStreamNonBlocking));
+    LRC_TRY(hipEventCreate(&L->ev_t0));
+    LRC_TRY(hipEventCreate(&L->ev_t1));
+  }
+  LRC_TRY(hipMalloc((void**)&L->d_desc, sizeof(ExpertDesc) * L->n_total));
+  LRC_TRY(hipMalloc((void**)&L->d_wg, size_t(cfg->n_experts) * cfg->hidden * 2));
+  LRC_TRY(hipMalloc((void**)&L->d_bias, size_t(cfg->n_experts) * 4));
+  LRC_TRY(hipMalloc((void**)&L->d_stat, (2 + 2 * cfg->n_experts) * 4));
+  LRC_TRY(hipMemset(L->d_stat, 0, (2 + 2 * cfg->n_experts) * 4));
+  LRC_TRY(hipHostMalloc((void**)&L->h_stat, (2 + 2 * cfg->n_experts) * 4, hipHostMallocDefault));
+  L->h_desc.resize(L->n_total);
+  for (int e = 0; e < L->n_total; ++e) {
+    const BlobLayout& b = blob_of(L, e);
+    ExpertDesc& d = L->h_desc[e];
+    std::memset(&d, 0, sizeof(d));
+    for (int m = 0; m < 3; ++m) {
+      d.codes[m] = reinterpret_cast<const uint32_t*>(L->d_w + L->w_off[e] + b.off_codes[m]);
+      d.meta[m] = reinterpret_cast<const uint32_t*>(L->d_w + L->w_off[e] + b.off_meta[m]);
+      if (b.f_bytes) {
+        d.af[m] = reinterpret_cast<const _Float16*>(L->d_f + L->f_off[e] + b.off_af[m]);
+        d.bf[m] = reinterpret_cast<const _Float16*>(L->d_f + L->f_off[e] + b.off_bf[m]);
+      }
+      d.lambda[m] = d.inv_lambda[m] = 1.f;
+    }
+    d.has_factors = b.f_bytes ? 1 : 0;
+  }
+  LRC_TRY(hipMemcpy(L->d_desc, L->h_desc.data(), sizeof(ExpertDesc) * L->n_total, hipMemcpyHostToDevice));
+#undef LRC_TRY
+  *out = L;
+  return MOE_LRC_OK;
+}
+
+int moe_lrc_layer_destroy(moe_lrc_layer* L) {
+  if (!L) return MOE_LRC_OK;
+  (void)hipDeviceSynchronize();
+  if (L->d_w) (void)hipFree(L->d_w);
+  if (L->d_f) (void)hipFree(L->d_f);
+  if (L->h_w) (void)hipHostFree(L->h_w);
+  if (L->h_f) (void)hipHostFree(L->h_f);
+  if (L->d_desc) (void)hipFree(L->d_desc);
+  if (L->d_wg) (void)hipFree(L->d_wg);
+  if (L->d_bias) (void)hipFree(L->d_bias);
+  if (L->d_stat) (void)hipFree(L->d_stat);
+  if (L->h_stat) (void)hipHostFree(L->h_stat);
+  if (L->side) (void)hipStreamDestroy(L->side);
+  if (L->ev_t0) (void)hipEventDestroy(L->ev_t0);
+  if (L->ev_t1) (void)hipEventDestroy(L->ev_t1);
+  delete L;
+  return MOE_LRC_OK;
+}
+
+int moe_lrc_set_gate(moe_lrc_layer* L, const uint16_t* wg, const float* bias) {
+  if (!L || !wg) return set_error(MOE_LRC_EINVAL, "set_gate: null argument");
+  const moe_lrc_config& c = L->cfg;
+  LRC_HIP(hipMemcpy(L->d_wg, wg, size_t(c.n_experts) * c.hidden * 2, hipMemcpyHostToDevice));
+  if (bias) LRC_HIP(hipMemcpy(L->d_bias, bias, size_t(c.n_experts) * 4, hipMemcpyHostToDevice));
+  L->has_bias = bias != nullptr;
+  L->gate_set = true;
+  return MOE_LRC_OK;
+}
+
+int moe_lrc_set_expert(moe_lrc_layer* L, int expert, int mat, const uint8_t* codes,
+                       const uint16_t* scale, const uint16_t* zero, const uint16_t* A, const uint16_t* B) {
+  if (!L || !codes || !scale || !zero) return set_error(MOE_LRC_EINVAL, "set_expert: null argument");
+  if (expert < 0 || expert >= L->n_total) return set_error(MOE_LRC_EINVAL, "set_expert: expert out of range");
+  if (mat < 0 || mat > 2) return set_error(MOE_LRC_EINVAL, "set_expert: mat must be 0, 1 or 2");
+  const moe_lrc_config& c = L->cfg;
+  const BlobLayout& b = blob_of(L, expert);
+  const MatLayout& m = b.mat[mat];
+  const bool wants = b.f_bytes > 0;
+  if (wants && (!A || !B)) return set_error(MOE_LRC_EINVAL, "set_expert: factors required when rank > 0");
+  if (!wants && (A || B)) return set_error(MOE_LRC_EINVAL, "set_expert: factors given for rank 0 or a shared expert");
+  const uint32_t limit = 1u << m.bits;
+  for (size_t i = 0; i < size_t(m.K) * m.N; ++i)
+    if (codes[i] >= limit) return set_error(MOE_LRC_EINVAL, "set_expert: code out of range for the bit width");
+
+  std::vector<uint8_t> wbuf(m.codes_bytes + m.meta_bytes);
+  pack_codes(m, codes, reinterpret_cast<uint32_t*>(wbuf.data()));
+  const float lambda = pack_meta(m, scale, zero, reinterpret_cast<uint32_t*>(wbuf.data() + m.codes_bytes));
+  // codes and meta sections of one projection are adjacent in the blob
+  const size_t woff = L->w_off[expert] + b.off_codes[mat];
+  std::vector<uint8_t> fbuf;
+  size_t foff = 0;
+  if (wants) {
+    fbuf.resize(m.af_bytes + m.bf_bytes);
+    pack_factor_a(m, c.rank, A, reinterpret_cast<uint16_t*>(fbuf.data()));
+    pack_factor_b(m, c.rank, B, reinterpret_cast<uint16_t*>(fbuf.data() + m.af_bytes));
+    foff = L->f_off[expert] + b.off_af[mat];
+  }
+  if (c.residency == MOE_LRC_STAGED) {
+    std::memcpy(L->h_w + woff, wbuf.data(), wbuf.size());
+    if (wants) std::memcpy(L->h_f + foff, fbuf.data(), fbuf.size());
+  } else {
+    LRC_HIP(hipMemcpy(L->d_w + woff, wbuf.data(), wbuf.size(), hipMemcpyHostToDevice));
+    if (wants) LRC_HIP(hipMemcpy(L->d_f + foff, fbuf.data(), fbuf.size(), hipMemcpyHostToDevice));
+  }
+  L->h_desc[expert].lambda[mat] = lambda;
+  L->h_desc[expert].inv_lambda[mat] = 1.0f / lambda;
+  LRC_HIP(hipMemcpy(L->d_desc + expert, &L->h_desc[expert], sizeof(ExpertDesc), hipMemcpyHostToDevice));
+  L->mat_set[expert * 3 + mat] = 1;
+  return MOE_LRC_OK;
+}
+
+size_t moe_lrc_workspace_bytes(const moe_lrc_layer* L, int T) {
+  if (!L || T < 0) return 0;
+  return plan_workspace(L, T).total;
+}
+
+int moe_lrc_route(moe_lrc_layer* L, const void* x, int T, int32_t* idx, float* w, void* stream) {
+  int rc = check_hot(L, T, "route");
+  if (rc) return rc;
+  if (!x || !idx || !w) return set_error(MOE_LRC_EINVAL, "route: null argument");
+  if (!L->gate_set) return set_error(MOE_LRC_ESTATE, "route: gate not uploaded");
+  if (T == 0) return MOE_LRC_OK;
+  LRC_HIP(launch_route(L, x, T, idx, w, nullptr, (hipStream_t)stream));
+  return MOE_LRC_OK;
+}
+
+int moe_lrc_permute(moe_lrc_layer* L, const int32_t* idx, int T, int32_t* counts, int32_t* offsets,
+                    int32_t* row_pair, int32_t* pair_row, int32_t* comp_counts, void* stream) {
+  int rc = check_hot(L, T, "permute");
+  if (rc) return rc;
+  if (!idx || !counts || !offsets || !row_pair || !pair_row || !comp_counts)
+    return set_error(MOE_LRC_EINVAL, "permute: null argument");
+  LRC_HIP(launch_permute(L, idx, T, counts, offsets, row_pair, pair_row, comp_counts, (hipStream_t)stream));
+  return MOE_LRC_OK;
+}
+
+int moe_lrc_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t* offsets,
+                       const int32_t* row_pair, void* y_rows, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_hot(L, T, "expert_ffn");
+  if (rc) return rc;
+  if (!x || !offsets || !row_pair || !y_rows) return set_error(MOE_LRC_EINVAL, "expert_ffn: null argument");
+  if ((rc = check_ws(L, T, ws, ws_bytes, "expert_ffn"))) return rc;
+  if ((rc = check_uploaded(L, "expert_ffn", true, false))) return rc;
+  if (T == 0) return MOE_LRC_OK;
+  return run_expert_ffn(L, x, T, offsets, row_pair, y_rows, (uint8_t*)ws, (hipStream_t)stream);
+}
+
+int moe_lrc_combine(moe_lrc_layer* L, const void* y_rows, const float* w, const int32_t* pair_row,
+                    const void* x, int T, void* out, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_hot(L, T, "combine");
+  if (rc) return rc;
+  if (!y_rows || !w || !pair_row || !out) return set_error(MOE_LRC_EINVAL, "combine: null argument");
+  const bool shared = L->cfg.n_shared > 0;
+  if (shared) {
+    if (!x) return set_error(MOE_LRC_EINVAL, "combine: x is required when the layer has shared experts");
+    if ((rc = check_ws(L, T, ws, ws_bytes, "combine"))) return rc;
+    if ((rc = check_uploaded(L, "combine", false, true))) return rc;
+  }
+  if (T == 0) return MOE_LRC_OK;
+  const void* y_shared = nullptr;
+  if (shared) {
+    if (L->cfg.residency == MOE_LRC_STAGED && (rc = check_uploaded(L, "combine", true, true))) return rc;
+    if ((rc = run_shared(L, x, T, (uint8_t*)ws, false, (hipStream_t)stream))) return rc;
+    y_shared = (uint8_t*)ws + plan_workspace(L, T).sh_y;
+  }
+  LRC_HIP(launch_combine(L, y_rows, w, pair_row, y_shared, T, out, (hipStream_t)stream));
+  return MOE_LRC_OK;
+}
+
+int moe_lrc_forward(moe_lrc_layer* L, const void* x, int T, void* out, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_hot(L, T, "forward");
+  if (rc) return rc;
+  if (!x || !out) return set_error(MOE_LRC_EINVAL, "forward: null argument");
+  if ((rc = check_ws(L, T, ws, ws_bytes, "forward"))) return rc;
+  if (!L->gate_set) return set_error(MOE_LRC_ESTATE, "forward: gate not uploaded");
+  if ((rc = check_uploaded(L, "forward", true, true))) return rc;
+  if (T == 0) return MOE_LRC_OK;
+  hipStream_t s = (hipStream_t)stream;
+  uint8_t* b = (uint8_t*)ws;
+  const Workspace w = plan_workspace(L, T);
+  int32_t* idx = (int32_t*)(b + w.topk_idx);
+  float* tw = (float*)(b + w.topk_w);
+  int32_t* offsets = (int32_t*)(b + w.offsets);
+  int32_t* row_pair = (int32_t*)(b + w.row_pair);
+  int32_t* pair_row = (int32_t*)(b + w.pair_row);
+  LRC_HIP(launch_route(L, x, T, idx, tw, nullptr, s));
+  LRC_HIP(launch_permute(L, idx, T, (int32_t*)(b + w.counts), offsets, row_pair, pair_row,
+                         (int32_t*)(b + w.comp_counts), s));
+  if ((rc = run_expert_ffn(L, x, T, offsets, row_pair, b + w.y_rows, b, s))) return rc;
+  const void* y_shared = nullptr;
+  if (L->cfg.n_shared > 0) {
+    if ((rc = run_shared(L, x, T, b, true, s))) return rc;
+    y_shared = b + w.sh_y;
+  }
+  LRC_HIP(launch_combine(L, b + w.y_rows, tw, pair_row, y_shared, T, out, s));
+  return MOE_LRC_OK;
+}
+
+int moe_lrc_debug_unpack(moe_lrc_layer* L, int expert, int mat, uint8_t* codes_dev, void* stream) {
+  if (!L || !codes_dev) return set_error(MOE_LRC_EINVAL, "debug_unpack: null argument");
+  if (expert < 0 || expert >= L->n_total || mat < 0 || mat > 2)
+    return set_error(MOE_LRC_EINVAL, "debug_unpack: expert or mat out of range");
+  if (!L->mat_set[expert * 3 + mat]) return set_error(MOE_LRC_ESTATE, "debug_unpack: projection not uploaded");
+  const BlobLayout& b = blob_of(L, expert);
+  const size_t off = L->w_off[expert] + b.off_codes[mat];
+  if (L->cfg.residency == MOE_LRC_STAGED)   // bring the packed codes into the expert's slot first
+    LRC_HIP(hipMemcpyAsync(L->d_w + off, L->h_w + off, b.mat[mat].codes_bytes, hipMemcpyHostToDevice,
+                           (hipStream_t)stream));
+  LRC_HIP(launch_debug_unpack(reinterpret_cast<const uint32_t*>(L->d_w + off), b.mat[mat], codes_dev,
+                              (hipStream_t)stream));
+  return MOE_LRC_OK;
+}
+
+size_t moe_lrc_packed_bytes(int bits, int K, int N) {
+  if (bits < 2 || bits > 4 || K <= 0 || N <= 0 || N % 16) return 0;
+  return make_layout(K, N, bits, 64, 0).codes_bytes;
+}
+
+int moe_lrc_pack_codes(int bits, int K, int N, const uint8_t* codes, void* packed) {
+  if (!codes || !packed) return set_error(MOE_LRC_EINVAL, "pack_codes: null argument");
+  if (bits < 2 || bits > 4 || K <= 0 || N <= 0 || N % 16) return set_error(MOE_LRC_ESHAPE, "pack_codes: unsupported shape");
+  for (size_t i = 0; i < size_t(K) * N; ++i)
+    if (codes[i] >> bits) return set_error(MOE_LRC_EINVAL, "pack_codes: code out of range for the bit width");
+  pack_codes(make_layout(K, N, bits, 64, 0), codes, (uint32_t*)packed);
+  return MOE_LRC_OK;
+}
+
+int moe_lrc_unpack_codes(int bits, int K, int N, const void* packed, uint8_t* codes) {
+  if (!codes || !packed) return set_error(MOE_LRC_EINVAL, "unpack_codes: null argument");
+  if (bits < 2 || bits > 4 || K <= 0 || N <= 0 || N % 16) return set_error(MOE_LRC_ESHAPE, "unpack_codes: unsupported shape");
+  unpack_codes(make_layout(K, N, bits, 64, 0), (const uint32_t*)packed, codes);
+  return MOE_LRC_OK;
+}
+
+int moe_lrc_get_stats(moe_lrc_layer* L, moe_lrc_stats* out) {
+  if (!L || !out) return set_error(MOE_LRC_EINVAL, "get_stats: null argument");
+  if (L->cfg.residency == MOE_LRC_STAGED && L->stats_valid) {
+    float ms = 0.f;
+    if (hipEventSynchronize(L->ev_t1) == hipSuccess && hipEventElapsedTime(&ms, L->ev_t0, L->ev_t1) == hipSuccess)
+      L->stats.stage_ms = ms;
+  } else {
+    LRC_HIP(hipDeviceSynchronize());
+    LRC_HIP(hipMemcpy(L->h_stat, L->d_stat, (2 + 2 * L->cfg.n_experts) * 4, hipMemcpyDeviceToHost));
+    fill_algorithmic_stats(L, L->h_stat);
+  }
+  *out = L->stats;
+  return MOE_LRC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,101 @@
+// Internal declarations shared by the host API and the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/moe_lrc.h"
+#include "layout.h"
+
+namespace lrc {
+
+// Device-visible description of one expert: where its packed projections live.
+struct ExpertDesc {
+  const uint32_t* codes[3];
+  const uint32_t* meta[3];
+  const _Float16* af[3];      // packed A factor (null if none)
+  const _Float16* bf[3];      // packed B factor
+  float lambda[3];            // power-of-two pre-scale folded into the metadata
+  float inv_lambda[3];
+  int32_t has_factors;
+  int32_t pad_;
+};
+
+// Byte offsets of the sections of an expert's two blobs (weights: codes+meta; factors: A+B).
+struct BlobLayout {
+  MatLayout mat[3];
+  size_t off_codes[3], off_meta[3], off_af[3], off_bf[3];
+  size_t w_bytes, f_bytes;
+};
+
+struct Workspace {       // carved out of the caller's buffer; all offsets 256-byte aligned
+  size_t topk_idx, topk_w, counts, offsets, comp_counts, row_pair, pair_row;
+  size_t y_rows, xh, h, p13, p2, sh_h, sh_y, total;
+};
+
+}  // namespace lrc
+
+struct moe_lrc_layer {
+  moe_lrc_config cfg;
+  int device;
+  lrc::BlobLayout routed, shared;
+  int n_total;                         // E + S
+  uint8_t* d_w = nullptr;              // device: weight blobs (resident) or slot pool (staged)
+  uint8_t* d_f = nullptr;              // device: factor blobs / slots
+  uint8_t* h_w = nullptr;              // pinned host pool (staged only)
+  uint8_t* h_f = nullptr;
+  std::vector<size_t> w_off, f_off;    // per-expert offsets into the pools
+  lrc::ExpertDesc* d_desc = nullptr;
+  std::vector<lrc::ExpertDesc> h_desc;
+  uint16_t* d_wg = nullptr;
+  float* d_bias = nullptr;
+  bool gate_set = false, has_bias = false;
+  std::vector<uint8_t> mat_set;        // [n_total*3]
+  int32_t* d_stat = nullptr;           // [2 + 2E]: active, comp-active, counts, comp counts
+  int32_t* h_stat = nullptr;           // pinned mirror
+  hipStream_t side = nullptr;
+  hipEvent_t ev_t0 = nullptr, ev_t1 = nullptr;   // bracket the staged copies on the side stream
+  moe_lrc_stats stats{};
+  bool stats_valid = false;
+  int ksplit13 = 1, ksplit2 = 1;
+};
+
+namespace lrc {
+
+int set_error(int code, const std::string& msg);
+Workspace plan_workspace(const moe_lrc_layer* L, int T);
+
+// ---- kernel launchers (each returns hipError_t of the launch) ------------------------------
+hipError_t launch_route(const moe_lrc_layer* L, const void* x, int T, int32_t* idx, float* w,
+                        _Float16* xh /*may be null*/, hipStream_t s);
+hipError_t launch_permute(const moe_lrc_layer* L, const int32_t* idx, int T, int32_t* counts,
+                          int32_t* offsets, int32_t* row_pair, int32_t* pair_row,
+                          int32_t* comp_counts, hipStream_t s);
+hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _Float16* xh,
+                            const int32_t* offsets, const int32_t* row_pair, int32_t* stat,
+                            hipStream_t s);
+
+struct FfnArgs {
+  const ExpertDesc* desc;     // device array, already offset to the first expert of this launch
+  int n_exp;                  // experts in this launch (grid.y)
+  int bits, group, rank, rpad;
+  int H, F, top_k, top_n, T;
+  const int32_t* offsets;     // [n_exp+1] or null: shared experts, rows e*T .. e*T+T-1
+  const int32_t* row_pair;    // null for shared experts (row -> token = row % T)
+  const _Float16* xh;         // [T][H] fp16
+  _Float16* h;                // [rows][F] fp16
+  float* p13;                 // [ksplit13][rows][2*rpad]
+  float* p2;                  // [ksplit2][rows][rpad]
+  void* y_rows;               // [rows][H] bf16
+  int ksplit13, ksplit2, total_rows;
+};
+hipError_t launch_expert_ffn(const FfnArgs& a, hipStream_t s);
+hipError_t launch_combine(const moe_lrc_layer* L, const void* y_rows, const float* w,
+                          const int32_t* pair_row, const void* y_shared, int T, void* out,
+                          hipStream_t s);
+hipError_t launch_debug_unpack(const uint32_t* packed, const MatLayout& m, uint8_t* codes_dev,
+                               hipStream_t s);
+
+}  // namespace lrc

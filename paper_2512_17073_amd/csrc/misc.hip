@@ -1,0 +1,146 @@
+// Weighted combine (Section 2.1: y = sum_{i in TopK} w_i E_i(x)), the fp16 activation copy with the
+// per-call expert statistics, and the unpack hook that reads the private packed layout back.
+#include "internal.h"
+#include "unpack.h"
+
+namespace lrc {
+
+namespace {
+
+__device__ inline float bf16_lo(uint32_t v) { return __uint_as_float(v << 16); }
+__device__ inline float bf16_hi(uint32_t v) { return __uint_as_float(v & 0xffff0000u); }
+__device__ inline uint32_t pack_bf16(float a, float b) {
+  uint32_t ua = __float_as_uint(a), ub = __float_as_uint(b);
+  ua += 0x7fffu + ((ua >> 16) & 1u);
+  ub += 0x7fffu + ((ub >> 16) & 1u);
+  return (ua >> 16) | (ub & 0xffff0000u);
+}
+
+// out[t] = sum_j w[t][j] * y_rows[pair_row[t*k+j]] + sum_s y_shared[s*T+t]; slots in order j = 0..k-1,
+// then the shared experts: a fixed order, so two runs give identical bits.
+__global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict__ y_rows,
+                                                      const float* __restrict__ w,
+                                                      const int32_t* __restrict__ pair_row,
+                                                      const uint16_t* __restrict__ y_shared, int T, int H,
+                                                      int top_k, int n_shared, uint16_t* __restrict__ out) {
+  const int t = blockIdx.x;
+  for (int ch = threadIdx.x; ch < H / 8; ch += 256) {
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int j = 0; j < top_k; ++j) {
+      const int row = pair_row[t * top_k + j];
+      const float wj = w[t * top_k + j];
+      const uint4 v = reinterpret_cast<const uint4*>(y_rows + size_t(row) * H)[ch];
+      const uint32_t a[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        acc[2 * i] = fmaf(wj, bf16_lo(a[i]), acc[2 * i]);
+        acc[2 * i + 1] = fmaf(wj, bf16_hi(a[i]), acc[2 * i + 1]);
+      }
+    }
+    for (int s = 0; s < n_shared; ++s) {
+      const uint4 v = reinterpret_cast<const uint4*>(y_shared + (size_t(s) * T + t) * H)[ch];
+      const uint32_t a[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        acc[2 * i] += bf16_lo(a[i]);
+        acc[2 * i + 1] += bf16_hi(a[i]);
+      }
+    }
+    reinterpret_cast<uint4*>(out + size_t(t) * H)[ch] =
+        make_uint4(pack_bf16(acc[0], acc[1]), pack_bf16(acc[2], acc[3]), pack_bf16(acc[4], acc[5]),
+                   pack_bf16(acc[6], acc[7]));
+  }
+}
+
+// Blocks 0..T-1 write the fp16 copy of their token; one extra block counts, per expert, the routed
+// rows and the rows that take the rank-r term (what the router-guided transfer must bring in).
+// stat = [active experts, comp-active experts, rows[E], comp rows[E]].
+__global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ x, int T, int H,
+                                                   _Float16* __restrict__ xh,
+                                                   const int32_t* __restrict__ offsets,
+                                                   const int32_t* __restrict__ row_pair, int E, int top_k,
+                                                   int top_n, int32_t* __restrict__ stat) {
+  if ((int)blockIdx.x == T) {
+    __shared__ int n_active, n_comp;
+    if (threadIdx.x == 0) { n_active = 0; n_comp = 0; }
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += 256) {
+      const int b = offsets[e], n = offsets[e + 1] - b;
+      int comp = 0;
+      for (int r = 0; r < n; ++r) comp += (row_pair[b + r] % top_k) < top_n;
+      stat[2 + e] = n;
+      stat[2 + E + e] = comp;
+      if (n > 0) atomicAdd(&n_active, 1);
+      if (comp > 0) atomicAdd(&n_comp, 1);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) { stat[0] = n_active; stat[1] = n_comp; }
+    return;
+  }
+  const int t = blockIdx.x;
+  const uint4* xrow = reinterpret_cast<const uint4*>(x + size_t(t) * H);
+  for (int c = threadIdx.x; c < H / 8; c += 256) {
+    const uint4 v = xrow[c];
+    const uint32_t in[4] = {v.x, v.y, v.z, v.w};
+    uint32_t o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const _Float16 lo = (_Float16)bf16_lo(in[i]);
+      const _Float16 hi = (_Float16)bf16_hi(in[i]);
+      o[i] = uint32_t(__builtin_bit_cast(uint16_t, lo)) | (uint32_t(__builtin_bit_cast(uint16_t, hi)) << 16);
+    }
+    reinterpret_cast<uint4*>(xh + size_t(t) * H)[c] = make_uint4(o[0], o[1], o[2], o[3]);
+  }
+}
+
+// One wavefront per packed tile: runs the same field extraction as the FFN kernels and writes the
+// integer codes back as one byte each.
+template <int BITS>
+__global__ __launch_bounds__(64) void unpack_kernel(const uint32_t* __restrict__ packed, int K, int N,
+                                                    int KS, uint8_t* __restrict__ codes) {
+  const int tile = blockIdx.x, nt = tile / KS, ks = tile % KS, lane = threadIdx.x;
+  uint32_t w[2 * BITS], f[32];
+  load_codes<BITS>(packed + size_t(tile) * kWave * 2 * BITS, lane, w);
+  Extract<BITS>::run(w, f);
+  const int n = nt * kTileN + (lane & 15), kbase = ks * kTileK + (lane >> 4) * kLaneK;
+#pragma unroll
+  for (int pi = 0; pi < 32; ++pi) {
+    const int k = kbase + 2 * pi;
+    if (k < K) codes[size_t(k) * N + n] = (uint8_t)((f[pi] & 0xffffu) >> (10 - BITS));
+    if (k + 1 < K) codes[size_t(k + 1) * N + n] = (uint8_t)((f[pi] >> 16) >> (10 - BITS));
+  }
+}
+
+}  // namespace
+
+hipError_t launch_combine(const moe_lrc_layer* L, const void* y_rows, const float* w,
+                          const int32_t* pair_row, const void* y_shared, int T, void* out,
+                          hipStream_t s) {
+  const moe_lrc_config& c = L->cfg;
+  hipLaunchKernelGGL(combine_kernel, dim3(T), dim3(256), 0, s, (const uint16_t*)y_rows, w, pair_row,
+                     (const uint16_t*)y_shared, T, c.hidden, c.top_k, c.n_shared, (uint16_t*)out);
+  return hipGetLastError();
+}
+
+hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _Float16* xh,
+                            const int32_t* offsets, const int32_t* row_pair, int32_t* stat,
+                            hipStream_t s) {
+  const moe_lrc_config& c = L->cfg;
+  hipLaunchKernelGGL(prep_kernel, dim3(T + (stat ? 1 : 0)), dim3(256), 0, s, (const uint16_t*)x_bf16, T, c.hidden, xh,
+                     offsets, row_pair, c.n_experts, c.top_k, c.top_n, stat);
+  return hipGetLastError();
+}
+
+hipError_t launch_debug_unpack(const uint32_t* packed, const MatLayout& m, uint8_t* codes_dev,
+                               hipStream_t s) {
+  const dim3 grid(m.NT * m.KS), block(64);
+  switch (m.bits) {
+    case 2: hipLaunchKernelGGL(unpack_kernel<2>, grid, block, 0, s, packed, m.K, m.N, m.KS, codes_dev); break;
+    case 3: hipLaunchKernelGGL(unpack_kernel<3>, grid, block, 0, s, packed, m.K, m.N, m.KS, codes_dev); break;
+    case 4: hipLaunchKernelGGL(unpack_kernel<4>, grid, block, 0, s, packed, m.K, m.N, m.KS, codes_dev); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace lrc

@@ -1,0 +1,209 @@
+// Routing (Section 2.1: w = softmax(G(x)), Top-k; Section 3.2: Top-n = first n of the sorted list)
+// and the grouping of (token, slot) pairs by expert.
+#include "internal.h"
+
+namespace lrc {
+
+namespace {
+
+__device__ inline double bf16_to_double(uint32_t bits16) {
+  return (double)__uint_as_float(bits16 << 16);
+}
+
+__device__ inline double wave_sum(double v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+  return v;
+}
+
+// One workgroup (4 wavefronts) per token.  Wavefront w accumulates, in fp64, the gate dot products
+// of experts w, w+4, ...: every bf16 x bf16 product is exact in fp64, so the logits differ from the
+// exact ones by ~1e-13 and the selection equals the exact selection.  The same instruction
+// sequence runs for every expert row, so duplicated gate rows give bit-identical logits.
+// Wavefront 0 then takes the Top-k with a shuffle arg-max (ties to the lower index) and the
+// softmax weights of the selected experts.
+constexpr int kMaxExperts = 256;
+
+__global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__ x,
+                                                    const uint16_t* __restrict__ wg,
+                                                    const float* __restrict__ bias, int T, int H, int E,
+                                                    int top_k, int renorm, int32_t* __restrict__ idx,
+                                                    float* __restrict__ w, _Float16* __restrict__ xh) {
+  __shared__ double logit[kMaxExperts];
+  const int t = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint4* xrow = reinterpret_cast<const uint4*>(x + size_t(t) * H);
+  const int chunks = H / 8;
+
+  if (xh != nullptr) {     // fp16 copy of the token for the expert kernels (exact for |x| < 65504)
+    for (int c = threadIdx.x; c < chunks; c += 256) {
+      const uint4 v = xrow[c];
+      const uint32_t in[4] = {v.x, v.y, v.z, v.w};
+      uint32_t o[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const _Float16 lo = (_Float16)__uint_as_float(in[i] << 16);
+        const _Float16 hi = (_Float16)__uint_as_float(in[i] & 0xffff0000u);
+        o[i] = uint32_t(__builtin_bit_cast(uint16_t, lo)) | (uint32_t(__builtin_bit_cast(uint16_t, hi)) << 16);
+      }
+      reinterpret_cast<uint4*>(xh + size_t(t) * H)[c] = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+  }
+
+  for (int e = wave; e < E; e += 4) {
+    const uint4* wrow = reinterpret_cast<const uint4*>(wg + size_t(e) * H);
+    double acc = 0.0;
+    for (int c = lane; c < chunks; c += 64) {
+      const uint4 xv = xrow[c], wv = wrow[c];
+      const uint32_t xa[4] = {xv.x, xv.y, xv.z, xv.w}, wa[4] = {wv.x, wv.y, wv.z, wv.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        acc = fma(bf16_to_double(xa[i] & 0xffffu), bf16_to_double(wa[i] & 0xffffu), acc);
+        acc = fma(bf16_to_double(xa[i] >> 16), bf16_to_double(wa[i] >> 16), acc);
+      }
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) logit[e] = acc + (bias ? (double)bias[e] : 0.0);
+  }
+  __syncthreads();
+  if (wave != 0) return;
+
+  // lane holds experts lane, lane+64, lane+128, lane+192
+  double v[4];
+  uint32_t taken = 0;
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    const int e = lane + 64 * m;
+    v[m] = e < E ? logit[e] : 0.0;
+    if (e >= E) taken |= 1u << m;
+  }
+  double vmax = 0.0, den = 0.0, sel_sum = 0.0, my_w = 0.0;
+  int my_idx = 0;
+  for (int j = 0; j < top_k; ++j) {
+    double bv = 0.0;
+    int bi = 0x7fffffff;
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+      if (!(taken & (1u << m)) && (bi == 0x7fffffff || v[m] > bv)) { bv = v[m]; bi = lane + 64 * m; }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      const double ov = __shfl_xor(bv, off);
+      const int oi = __shfl_xor(bi, off);
+      const bool take = oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi));
+      if (take) { bv = ov; bi = oi; }
+    }
+    if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
+    if (j == 0) {
+      vmax = bv;
+      double part = 0.0;
+#pragma unroll
+      for (int m = 0; m < 4; ++m)
+        if (lane + 64 * m < E) part += exp(v[m] - vmax);
+      den = wave_sum(part);
+    }
+    const double score = exp(bv - vmax) / den;
+    sel_sum += score;
+    if (lane == j) { my_w = score; my_idx = bi; }
+  }
+  if (lane < top_k) {
+    idx[size_t(t) * top_k + lane] = my_idx;
+    w[size_t(t) * top_k + lane] = (float)(renorm ? my_w / sel_sum : my_w);
+  }
+}
+
+// Grouping: one workgroup of 16 wavefronts.  Wavefront w owns a contiguous run of pair ids, so
+// pair order (= token order) is kept by walking the run in order and ranking equal experts inside
+// each 64-pair step with ballots; per-(wavefront, expert) counters in LDS carry the positions.
+constexpr int kPermWaves = 16;
+
+__global__ __launch_bounds__(1024) void permute_kernel(const int32_t* __restrict__ idx, int P, int E,
+                                                       int top_k, int top_n,
+                                                       int32_t* __restrict__ counts,
+                                                       int32_t* __restrict__ offsets,
+                                                       int32_t* __restrict__ row_pair,
+                                                       int32_t* __restrict__ pair_row,
+                                                       int32_t* __restrict__ comp_counts) {
+  __shared__ int32_t hist[kPermWaves][kMaxExperts];
+  __shared__ int32_t comp[kMaxExperts];
+  __shared__ int32_t total[kMaxExperts];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int i = threadIdx.x; i < kPermWaves * kMaxExperts; i += 1024) (&hist[0][0])[i] = 0;
+  for (int i = threadIdx.x; i < kMaxExperts; i += 1024) comp[i] = 0;
+  __syncthreads();
+
+  const int per_wave = ((P + kPermWaves - 1) / kPermWaves + 63) / 64 * 64;
+  const int begin = wave * per_wave, end = min(P, begin + per_wave);
+  for (int i = begin + lane; i < end; i += 64) {
+    const int e = idx[i];
+    atomicAdd(&hist[wave][e], 1);
+    if (i % top_k < top_n) atomicAdd(&comp[e], 1);
+  }
+  __syncthreads();
+
+  if (threadIdx.x < E) {
+    int run = 0;
+    for (int wv = 0; wv < kPermWaves; ++wv) {
+      const int c = hist[wv][threadIdx.x];
+      hist[wv][threadIdx.x] = run;
+      run += c;
+    }
+    total[threadIdx.x] = run;
+    counts[threadIdx.x] = run;
+    comp_counts[threadIdx.x] = comp[threadIdx.x];
+  }
+  __syncthreads();
+  if (threadIdx.x < E) {
+    int off = 0;
+    for (int e = 0; e < (int)threadIdx.x; ++e) off += total[e];
+    offsets[threadIdx.x] = off;
+    if ((int)threadIdx.x == E - 1) offsets[E] = off + total[threadIdx.x];
+    for (int wv = 0; wv < kPermWaves; ++wv) hist[wv][threadIdx.x] += off;
+  }
+  __syncthreads();
+
+  int nbits = 0;
+  while ((1 << nbits) < E) ++nbits;
+  for (int base = begin; base < end; base += 64) {
+    const int i = base + lane;
+    const bool valid = i < end;
+    const int e = valid ? idx[i] : 0;
+    unsigned long long same = __ballot(valid);
+    for (int b = 0; b < nbits; ++b) {
+      const bool bit = (e >> b) & 1;
+      const unsigned long long bb = __ballot(valid && bit);
+      same &= bit ? bb : ~bb;
+    }
+    const int rank = __popcll(same & ((1ull << lane) - 1ull));
+    const int cnt = __popcll(same);
+    int pos = 0;
+    if (valid) pos = hist[wave][e] + rank;
+    __builtin_amdgcn_wave_barrier();
+    if (valid && rank == 0) hist[wave][e] = pos + cnt;
+    __builtin_amdgcn_wave_barrier();
+    if (valid) {
+      row_pair[pos] = i;
+      pair_row[i] = pos;
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_route(const moe_lrc_layer* L, const void* x, int T, int32_t* idx, float* w,
+                        _Float16* xh, hipStream_t s) {
+  const moe_lrc_config& c = L->cfg;
+  hipLaunchKernelGGL(route_kernel, dim3(T), dim3(256), 0, s, (const uint16_t*)x, L->d_wg,
+                     L->has_bias ? L->d_bias : nullptr, T, c.hidden, c.n_experts, c.top_k,
+                     c.renormalize, idx, w, xh);
+  return hipGetLastError();
+}
+
+hipError_t launch_permute(const moe_lrc_layer* L, const int32_t* idx, int T, int32_t* counts,
+                          int32_t* offsets, int32_t* row_pair, int32_t* pair_row,
+                          int32_t* comp_counts, hipStream_t s) {
+  const moe_lrc_config& c = L->cfg;
+  hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(1024), 0, s, idx, T * c.top_k, c.n_experts,
+                     c.top_k, c.top_n, counts, offsets, row_pair, pair_row, comp_counts);
+  return hipGetLastError();
+}
+
+}  // namespace lrc

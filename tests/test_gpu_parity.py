@@ -1,0 +1,241 @@
+"""GPU parity: the HIP library against the fp64 CPU oracle, element by element, through the C ABI.
+
+Bars (written here, from the benchmark spec): routing indices, counts, permutation and unpacked
+codes bit-exact; layer outputs within 5e-3 relative Frobenius error.
+"""
+import numpy as np
+import pytest
+
+from oracle import fixtures
+from oracle import moe_lrc_oracle as orc
+from workload import configs, synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = 5e-3
+
+
+@pytest.fixture(scope="module")
+def amd():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2512_17073_amd as amd
+    amd.lib()          # raises if the HIP library is not built: no fallback
+    return amd
+
+
+def _to_np(t):
+    import torch
+    if t.dtype == torch.bfloat16:
+        return t.float().cpu().numpy().astype(np.float64)
+    return t.cpu().numpy()
+
+
+def _build(amd, cfg, method="exact", residency=0, **kw):
+    layer = fixtures.build_layer(cfg, method=method, **kw)
+    L = amd.Layer.from_config(cfg, residency=residency)
+    L.load(layer)
+    return layer, L
+
+
+SMALL = {
+    "tiny": configs.TINY,
+    "tiny_b2": configs.TINY.with_(bits=2, name="tiny_b2"),
+    "tiny_b4_n2": configs.TINY.with_(bits=4, top_n=2, rank=16, name="tiny_b4_n2"),
+    # > 32 rows per expert: exercises two row tiles and the row-chunk loop, ragged tails
+    "tiny_T200": configs.TINY.with_(tokens=200, name="tiny_T200"),
+    "tiny_T1": configs.TINY.with_(tokens=1, name="tiny_T1"),
+    "tiny_renorm": configs.TINY.with_(renormalize=1, tokens=33, name="tiny_renorm"),
+    # DeepSeek-shaped: shared experts at 4 bit, FFN 1408 (not a multiple of the 256-row k-step), k=6
+    "deepseek_small": configs.DEEPSEEK.with_(hidden=512, n_experts=16, tokens=70, name="deepseek_small"),
+    # Qwen3-shaped: group 128, many experts, k=8, Zipf-skewed routing
+    "qwen3_small": configs.QWEN3.with_(hidden=512, ffn=768, tokens=48, name="qwen3_small"),
+}
+
+
+@pytest.fixture(scope="module", params=list(SMALL))
+def case(request, amd):
+    cfg = SMALL[request.param]
+    print(f"\n[case {cfg.name}] building fixture", flush=True)
+    layer, L = _build(amd, cfg)
+    x_bits = synth.make_tokens(cfg)
+    ref = fixtures.oracle_forward(cfg, layer, x_bits)
+    assert (ref["route"]["margin"] > 1e-9).all(), "fixture has a near-tie; routing would be undecidable"
+    x = amd.bf16_tensor(x_bits)
+    yield cfg, layer, L, x_bits, x, ref
+    L.close()
+
+
+def test_unpacked_codes_bit_exact(case, amd):
+    cfg, layer, L, *_ = case
+    for e in range(cfg.n_experts + cfg.n_shared):
+        for mat in (0, 1, 2):
+            got = _to_np(L.debug_unpack(e, mat))
+            np.testing.assert_array_equal(got, layer["experts"][e][mat]["codes"], err_msg=f"expert {e} mat {mat}")
+
+
+def test_route_bit_exact(case):
+    cfg, layer, L, x_bits, x, ref = case
+    idx, w = L.route(x)
+    np.testing.assert_array_equal(_to_np(idx), ref["route"]["idx"])
+    np.testing.assert_allclose(_to_np(w), ref["route"]["w"], rtol=2e-6, atol=1e-30)
+
+
+def test_permute_bit_exact(case):
+    cfg, layer, L, x_bits, x, ref = case
+    idx, _ = L.route(x)
+    counts, offsets, row_pair, pair_row, comp = L.permute(idx)
+    p = ref["perm"]
+    np.testing.assert_array_equal(_to_np(counts), p["counts"])
+    np.testing.assert_array_equal(_to_np(offsets), p["offsets"])
+    np.testing.assert_array_equal(_to_np(row_pair), p["row_pair"])
+    np.testing.assert_array_equal(_to_np(pair_row), p["pair_row"])
+    np.testing.assert_array_equal(_to_np(comp), p["comp_counts"])
+
+
+def test_expert_ffn_and_combine(case):
+    cfg, layer, L, x_bits, x, ref = case
+    idx, w = L.route(x)
+    counts, offsets, row_pair, pair_row, comp = L.permute(idx)
+    y = L.expert_ffn(x, offsets, row_pair)
+    err_rows = orc.rel_frobenius(_to_np(y), ref["y_rows"])
+    out = L.combine(y, w, pair_row, x)
+    err_out = orc.rel_frobenius(_to_np(out), ref["out"])
+    per_tok = np.linalg.norm(_to_np(out) - ref["out"], axis=1) / np.linalg.norm(ref["out"], axis=1)
+    print(f"[{cfg.name}] y_rows rel err {err_rows:.2e}, out rel err {err_out:.2e}, worst token {per_tok.max():.2e}")
+    assert err_rows <= TOL and err_out <= TOL
+    st = L.stats()
+    from oracle import compress
+    want = compress.staged_bytes(ref["perm"]["counts"], ref["perm"]["comp_counts"], cfg.hidden, cfg.ffn,
+                                 cfg.bits, cfg.group, cfg.rank)
+    P = 3 * cfg.hidden * cfg.ffn
+    assert st["active_experts"] == want["active_experts"]
+    assert st["comp_experts"] == (want["comp_experts"] if cfg.rank and cfg.top_n else 0)
+    assert st["bytes_codes"] == want["bytes_codes"] + cfg.n_shared * P * cfg.shared_bits // 8
+    assert st["bytes_meta"] == want["bytes_meta"] + cfg.n_shared * (P // cfg.group * 4)
+    assert st["bytes_factors"] == (want["bytes_factors"] if cfg.top_n else 0)
+
+
+def test_forward_matches_four_calls_and_is_deterministic(case):
+    import torch
+    cfg, layer, L, x_bits, x, ref = case
+    idx, w = L.route(x)
+    counts, offsets, row_pair, pair_row, comp = L.permute(idx)
+    y = L.expert_ffn(x, offsets, row_pair)
+    out4 = L.combine(y, w, pair_row, x).clone()
+    out_a = L.forward(x).clone()
+    out_b = L.forward(x).clone()
+    assert torch.equal(out_a.view(torch.int16), out_b.view(torch.int16)), "two runs differ"
+    assert torch.equal(out_a.view(torch.int16), out4.view(torch.int16)), "forward differs from the four calls"
+    assert orc.rel_frobenius(_to_np(out_a), ref["out"]) <= TOL
+
+
+def test_constructed_ties(amd):
+    # duplicated gate rows and an all-zero token: lower index wins, on the GPU as in the oracle
+    cfg = configs.TINY.with_(top_k=3, top_n=1, tokens=40, rank=0, name="ties")
+    rng = np.random.default_rng(3)
+    wg = rng.normal(size=(cfg.n_experts, cfg.hidden)).astype(np.float32)
+    wg[5] = wg[2]; wg[7] = wg[2]
+    xf = rng.normal(size=(cfg.tokens, cfg.hidden)).astype(np.float32)
+    xf[0] = 0.0
+    wg_bits, x_bits = synth.f32_to_bf16_bits(wg), synth.f32_to_bf16_bits(xf)
+    ref = orc.route(x_bits, wg_bits, cfg.top_k)
+    assert (ref["margin"] == 0).any()
+    L = amd.Layer.from_config(cfg)
+    L.set_gate(wg_bits)
+    idx, w = L.route(amd.bf16_tensor(x_bits))
+    np.testing.assert_array_equal(_to_np(idx), ref["idx"])
+    np.testing.assert_allclose(_to_np(w), ref["w"], rtol=2e-6)
+    assert list(_to_np(idx)[0]) == [0, 1, 2]
+    L.close()
+
+
+def test_n0_equals_rank0_layer_bitwise(amd):
+    import torch
+    cfg = configs.TINY.with_(top_n=0, name="n0")
+    layer, L = _build(amd, cfg)
+    cfg0 = configs.TINY.with_(rank=0, name="r0")
+    layer0 = {"wg": layer["wg"], "bias": layer["bias"],
+              "experts": [{m: dict(ex[m], A=None, B=None) for m in (0, 1, 2)} for ex in layer["experts"]]}
+    L0 = amd.Layer.from_config(cfg0)
+    L0.load(layer0)
+    x_bits = synth.make_tokens(cfg)
+    x = amd.bf16_tensor(x_bits)
+    a, b = L.forward(x).clone(), L0.forward(x).clone()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    ref = fixtures.oracle_forward(cfg, layer, x_bits)
+    assert orc.rel_frobenius(_to_np(a), ref["out"]) <= TOL
+    L.close(); L0.close()
+
+
+def test_large_scale_and_degenerate_groups(amd):
+    # scales >= 1 (constant groups get scale 1) must not overflow the fp16 metadata
+    cfg = configs.TINY.with_(rank=0, top_n=0, bits=2, name="degenerate")
+    layer = fixtures.build_layer(cfg)
+    ex = layer["experts"][0]
+    for m in (0, 1, 2):
+        ex[m]["codes"][:64, :] = 0
+        s = ex[m]["scale"].view(np.float16).copy(); z = ex[m]["zero"].view(np.float16).copy()
+        s[0, :] = 1.0; z[0, :] = 0.01
+        s[1, ::2] = 3.0
+        ex[m]["scale"], ex[m]["zero"] = s.view(np.uint16), z.view(np.uint16)
+    L = amd.Layer.from_config(cfg)
+    L.load(layer)
+    x_bits = synth.make_tokens(cfg)
+    ref = fixtures.oracle_forward(cfg, layer, x_bits)
+    out = L.forward(amd.bf16_tensor(x_bits))
+    assert np.isfinite(_to_np(out)).all()
+    assert orc.rel_frobenius(_to_np(out), ref["out"]) <= TOL
+    L.close()
+
+
+def test_staged_mode_matches_resident(amd):
+    import torch
+    cfg = configs.TINY.with_(tokens=5, name="staged")     # few tokens: some experts stay on the host
+    layer, Lr = _build(amd, cfg)
+    Ls = amd.Layer.from_config(cfg, residency=amd.STAGED)
+    Ls.load(layer)
+    x_bits = synth.make_tokens(cfg)
+    x = amd.bf16_tensor(x_bits)
+    a, b = Lr.forward(x).clone(), Ls.forward(x).clone()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    ref = fixtures.oracle_forward(cfg, layer, x_bits)
+    from oracle import compress
+    want = compress.staged_bytes(ref["perm"]["counts"], ref["perm"]["comp_counts"], cfg.hidden, cfg.ffn,
+                                 cfg.bits, cfg.group, cfg.rank)
+    st = Ls.stats()
+    assert want["active_experts"] < cfg.n_experts
+    for k in ("active_experts", "comp_experts", "bytes_codes", "bytes_meta", "bytes_factors"):
+        assert st[k] == want[k], k
+    assert st["stage_ms"] > 0
+    # a second batch that routes elsewhere must bring in its own experts
+    cfg2 = cfg.with_(seed=99, tokens=7)
+    x2_bits = synth.make_tokens(cfg2)
+    x2 = amd.bf16_tensor(x2_bits)
+    assert torch.equal(Lr.forward(x2).view(torch.int16), Ls.forward(x2).view(torch.int16))
+    np.testing.assert_array_equal(_to_np(Ls.debug_unpack(3, 1)), layer["experts"][3][1]["codes"])
+    Lr.close(); Ls.close()
+
+
+def test_hot_path_argument_errors(amd):
+    import torch
+    cfg = configs.TINY
+    L = amd.Layer.from_config(cfg)
+    x = amd.bf16_tensor(synth.make_tokens(cfg))
+    with pytest.raises(amd.MoeLrcError) as ei:
+        L.route(x)                                # gate not uploaded
+    assert ei.value.code == -3
+    wg, _ = synth.make_gate(cfg)
+    L.set_gate(wg)
+    with pytest.raises(amd.MoeLrcError) as ei:
+        L.forward(x)                              # experts not uploaded
+    assert ei.value.code == -3
+    big = torch.zeros((cfg.tokens + 1, cfg.hidden), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(amd.MoeLrcError) as ei:
+        L.route(big)                              # T > max_tokens
+    assert ei.value.code == -3
+    with pytest.raises(amd.MoeLrcError) as ei:
+        L.set_expert(0, 0, np.full((256, 512), 9, np.uint8), np.zeros((4, 512), np.uint16),
+                     np.zeros((4, 512), np.uint16), np.zeros((256, 8), np.uint16), np.zeros((8, 512), np.uint16))
+    assert ei.value.code == -1                    # code out of range for 3 bits
+    L.close()
