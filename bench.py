@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of one MoE layer's forward pass (route -> permute -> expert FFN -> combine) on one MI355X.
+
+A step is one moe_lrc_forward over one batch of synthetic tokens, with packed experts, factors and
+tokens already resident in HBM.  The timed calls rotate over several independent layer instances
+so that every call streams weights that are cold in the 256 MB last-level cache, as in a real
+multi-layer model.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload mixtral_decode_T64_b2]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16/bf16 MFMA, published
+
+
+def algorithmic_bytes(cfg, T, active, comp):
+    """Bytes each kernel must move per launch: packed codes + fp16 scale/zero of active experts,
+    factor bytes of comp-active experts, activations in and out."""
+    H, F, b, g, r, k = cfg.hidden, cfg.ffn, cfg.bits, cfg.group, cfg.rank, cfg.top_k
+    per_w = b / 8 + 4 / g                       # bytes per weight incl. scale/zero
+    rows = T * k
+    w13 = active * 2 * H * F * per_w + comp * 2 * r * F * 2 + T * H * 2 + rows * F * 2
+    w2 = active * H * F * per_w + comp * r * H * 2 + rows * F * 2 + rows * H * 2
+    xa13 = comp * 2 * H * r * 2
+    xa2 = comp * F * r * 2
+    shared = cfg.n_shared * 3 * H * F * (cfg.shared_bits / 8 + 4 / g)
+    total = w13 + w2 + xa13 + xa2 + shared + T * H * 2 * 2
+    return {"w13": w13, "w2": w2, "xa13": xa13, "xa2": xa2, "shared": shared, "total": total}
+
+
+def algorithmic_flops(cfg, T):
+    H, F, r, k, n = cfg.hidden, cfg.ffn, cfg.rank, cfg.top_k, cfg.top_n
+    return T * k * 2 * 3 * H * F + T * n * 2 * 3 * r * (H + F) + T * cfg.n_shared * 2 * 3 * H * F
+
+
+def cpu_baseline(cfg, layer, x_bits, budget_tokens=8):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload on the host cores."""
+    from oracle import fixtures
+    from oracle import moe_lrc_oracle as orc
+    r = orc.route(x_bits, layer["wg"], cfg.top_k, cfg.renormalize, layer["bias"])
+    mask = np.zeros(x_bits.shape[0], bool)
+    mask[:min(budget_tokens, x_bits.shape[0])] = True
+    t0 = time.perf_counter()
+    fixtures.oracle_forward(cfg, layer, x_bits, token_mask=mask)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    n = int(mask.sum())
+    return {"value": n / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"numpy fp64 oracle, routing of all {x_bits.shape[0]} tokens, expert FFN + combine of the "
+                      f"first {n} tokens ({dt:.1f} s); tokens/s = {n} / time (extrapolates linearly in tokens)",
+            "active_experts_full_batch": int((np.bincount(r['idx'].ravel(), minlength=cfg.n_experts) > 0).sum())}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="mixtral_decode_T64_b2")
+    ap.add_argument("--layers", type=int, default=0, help="layer instances to rotate over (0: enough for > 2 GB)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-tokens", type=int, default=8)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2512_17073_amd as amd
+    from workload import configs, synth
+    amd.lib()
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+
+    cfg = configs.get(args.workload)
+    T = cfg.tokens
+    t_setup = time.time()
+    print(f"[bench] workload {cfg.name}: generating artefacts", file=sys.stderr, flush=True)
+    wg, bias = synth.make_gate(cfg)
+    n_all = cfg.n_experts + cfg.n_shared
+    experts = [{m: synth.sample_artifacts(cfg, e, m) for m in (0, 1, 2)} for e in range(n_all)]
+    layer = {"wg": wg, "bias": bias, "experts": experts}
+    x_bits = synth.make_tokens(cfg)
+
+    per_layer = sum(a["codes"].size * synth.expert_bits(cfg, e) / 8 for e, ex in enumerate(experts) for a in ex.values())
+    n_layers = args.layers or max(2, min(16, int(np.ceil(2.2e9 / per_layer))))
+    layers = []
+    E = cfg.n_experts
+    for i in range(n_layers):
+        L = amd.Layer.from_config(cfg)
+        L.set_gate(wg, bias)
+        for e in range(n_all):
+            src = experts[(e + i) % E] if e < E else experts[e]     # rotate the routed experts per instance
+            for m in (0, 1, 2):
+                a = src[m]
+                L.set_expert(e, m, a["codes"], a["scale"], a["zero"], a["A"], a["B"])
+        layers.append(L)
+        print(f"[bench] layer instance {i + 1}/{n_layers} uploaded ({time.time() - t_setup:.0f}s)", file=sys.stderr, flush=True)
+
+    x = amd.bf16_tensor(x_bits)
+    out = torch.empty((T, cfg.hidden), dtype=torch.bfloat16, device="cuda")
+    ws_bytes = layers[0].workspace_bytes(T)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step(i):
+        layers[i % n_layers].forward_raw(x.data_ptr(), T, out.data_ptr(), ws.data_ptr(), ws_bytes, stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    # per-kernel durations: the same calls again with HIP events recorded on the stream between kernels
+    for L in layers:
+        L.profile_enable(True)
+    stage_ms = {}
+    reps = max(20, min(args.steps, 100))
+    for i in range(reps):
+        step(i)
+        prof = layers[i % n_layers].profile_read()
+        for k, v in prof.items():
+            stage_ms.setdefault(k, []).append(v)
+    for L in layers:
+        L.profile_enable(False)
+    stage_avg = {k: float(np.mean(v)) for k, v in stage_ms.items()}
+
+    st = layers[0].stats()
+    ab = algorithmic_bytes(cfg, T, st["active_experts"], st["comp_experts"])
+    flops = algorithmic_flops(cfg, T)
+    dom = "w13"
+    achieved = ab[dom] / (stage_avg[dom] * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "qgemm_kernel<bits,dual> (packed W1|W3 + SwiGLU)",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "bytes_per_launch": int(ab[dom]), "avg_ms": round(stage_avg[dom], 5)}
+    path_kernel_ms = sum(stage_avg.values())
+    result = {
+        "metric": "MoE-layer tokens/s (one layer forward, weights resident in HBM)",
+        "value": round(T / (ms_per_step * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "tokens": T, "hidden": cfg.hidden, "ffn": cfg.ffn,
+                   "experts": cfg.n_experts, "shared": cfg.n_shared, "top_k": cfg.top_k, "top_n": cfg.top_n,
+                   "bits": cfg.bits, "group": cfg.group, "rank": cfg.rank, "layer_instances": n_layers,
+                   "active_experts": st["active_experts"], "comp_experts": st["comp_experts"]},
+        "roofline": roofline,
+        "whole_path": {"algorithmic_bytes": int(ab["total"]), "hbm_gbs_wall": round(ab["total"] / (ms_per_step * 1e-3) / 1e9, 1),
+                       "hbm_frac_wall": round(ab["total"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                       "hbm_gbs_kernels": round(ab["total"] / (path_kernel_ms * 1e-3) / 1e9, 1),
+                       "tflops": round(flops / (ms_per_step * 1e-3) / 1e12, 2),
+                       "mfma_frac": round(flops / (ms_per_step * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4),
+                       "stage_ms": {k: round(v, 5) for k, v in stage_avg.items()}},
+    }
+    if not args.no_cpu_baseline:
+        print("[bench] timing the CPU oracle on a bounded sample", file=sys.stderr, flush=True)
+        result["cpu_baseline"] = cpu_baseline(cfg, layer, x_bits, args.cpu_tokens)
+    else:
+        result["cpu_baseline"] = None
+    for L in layers:
+        L.close()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

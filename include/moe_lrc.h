@@ -155,6 +155,24 @@ typedef struct {
  * and reads the counts of the last call. */
 int moe_lrc_get_stats(moe_lrc_layer* layer, moe_lrc_stats* out);
 
+/* Per-stage timing of moe_lrc_forward with HIP events recorded on the caller's stream between the
+ * kernels (measurement hook for the roofline figures; off by default, adds ~10 event records per
+ * call when on).  Stages, in launch order: */
+#define MOE_LRC_STAGE_ROUTE    0   /* gate + softmax + Top-k                          */
+#define MOE_LRC_STAGE_PERMUTE  1   /* grouping of pairs by expert                     */
+#define MOE_LRC_STAGE_PREP     2   /* fp16 activation copy, per-expert counters, staging */
+#define MOE_LRC_STAGE_XA13     3   /* (x A1 | x A3) for Top-n rows                    */
+#define MOE_LRC_STAGE_W13      4   /* packed W1|W3 projections + SwiGLU               */
+#define MOE_LRC_STAGE_XA2      5   /* (h A2) for Top-n rows                           */
+#define MOE_LRC_STAGE_W2       6   /* packed W2 projection                            */
+#define MOE_LRC_STAGE_SHARED   7   /* shared experts                                  */
+#define MOE_LRC_STAGE_COMBINE  8   /* weighted sum                                    */
+#define MOE_LRC_N_STAGES       9
+int moe_lrc_profile_enable(moe_lrc_layer* layer, int on);
+/* Waits for the last moe_lrc_forward of this layer and writes its stage durations in
+ * milliseconds to ms[MOE_LRC_N_STAGES] (host). */
+int moe_lrc_profile_read(moe_lrc_layer* layer, float* ms);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,9 @@ EXPORTS = [
     "moe_lrc_set_expert", "moe_lrc_workspace_bytes", "moe_lrc_route", "moe_lrc_permute",
     "moe_lrc_expert_ffn", "moe_lrc_combine", "moe_lrc_forward", "moe_lrc_debug_unpack",
     "moe_lrc_packed_bytes", "moe_lrc_pack_codes", "moe_lrc_unpack_codes", "moe_lrc_get_stats",
+    "moe_lrc_profile_enable", "moe_lrc_profile_read",
 ]
+STAGES = ["route", "permute", "prep", "xa13", "w13", "xa2", "w2", "shared", "combine"]
 
 
 class Config(C.Structure):
@@ -54,6 +56,9 @@ def lib() -> C.CDLL:
         if not os.path.exists(LIB_PATH):
             raise FileNotFoundError(f"{LIB_PATH} is not built; run `python -m paper_2512_17073_amd.build` "
                                     "(or __graft_entry__.build()) first")
+        # torch ships its own HIP runtime; load it first so that this library binds to the same
+        # runtime instance (two runtimes in one process do not share the device)
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         vp, i32, sz = C.c_void_p, C.c_int, C.c_size_t
         L.moe_lrc_last_error.restype = C.c_char_p
@@ -74,6 +79,8 @@ def lib() -> C.CDLL:
         L.moe_lrc_pack_codes.argtypes = [i32, i32, i32, vp, vp]
         L.moe_lrc_unpack_codes.argtypes = [i32, i32, i32, vp, vp]
         L.moe_lrc_get_stats.argtypes = [vp, C.POINTER(Stats)]
+        L.moe_lrc_profile_enable.argtypes = [vp, i32]
+        L.moe_lrc_profile_read.argtypes = [vp, C.POINTER(C.c_float)]
         _lib = L
     return _lib
 
@@ -240,6 +247,14 @@ class Layer:
         codes = torch.empty((K, N), dtype=torch.uint8, device="cuda")
         _check(lib().moe_lrc_debug_unpack(self._h, expert, mat, codes.data_ptr(), _stream()))
         return codes
+
+    def profile_enable(self, on: bool = True) -> None:
+        _check(lib().moe_lrc_profile_enable(self._h, int(on)))
+
+    def profile_read(self) -> dict:
+        ms = (C.c_float * len(STAGES))()
+        _check(lib().moe_lrc_profile_read(self._h, ms))
+        return dict(zip(STAGES, list(ms)))
 
     def stats(self) -> dict:
         s = Stats()

@@ -149,7 +149,8 @@ static int stage_selected(moe_lrc_layer* L, hipStream_t stream) {
 }
 
 static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t* offsets,
-                          const int32_t* row_pair, void* y_rows, uint8_t* ws, hipStream_t stream) {
+                          const int32_t* row_pair, void* y_rows, uint8_t* ws, hipStream_t stream,
+                          bool mark = false) {
   const moe_lrc_config& c = L->cfg;
   const Workspace w = plan_workspace(L, T);
   _Float16* xh = reinterpret_cast<_Float16*>(ws + w.xh);
@@ -160,6 +161,7 @@ static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t*
     const int rc = stage_selected(L, stream);
     if (rc) return rc;
   }
+  if (mark) LRC_HIP(hipEventRecord(L->marks[MOE_LRC_STAGE_XA13], stream));
   FfnArgs a{};
   a.desc = L->d_desc; a.n_exp = c.n_experts; a.bits = c.bits; a.group = c.group;
   a.rank = c.rank; a.rpad = L->routed.mat[0].rpad;
@@ -168,6 +170,7 @@ static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t*
   a.h = reinterpret_cast<_Float16*>(ws + w.h);
   a.p13 = reinterpret_cast<float*>(ws + w.p13); a.p2 = reinterpret_cast<float*>(ws + w.p2);
   a.y_rows = y_rows; a.ksplit13 = L->ksplit13; a.ksplit2 = L->ksplit2; a.total_rows = T * c.top_k;
+  a.marks = mark ? &L->marks[MOE_LRC_STAGE_W13] : nullptr;
   LRC_HIP(launch_expert_ffn(a, stream));
   L->stats.path = 0;
   return MOE_LRC_OK;
@@ -275,6 +278,8 @@ int moe_lrc_layer_destroy(moe_lrc_layer* L) {
   if (L->side) (void)hipStreamDestroy(L->side);
   if (L->ev_t0) (void)hipEventDestroy(L->ev_t0);
   if (L->ev_t1) (void)hipEventDestroy(L->ev_t1);
+  for (auto ev : L->marks)
+    if (ev) (void)hipEventDestroy(ev);
   delete L;
   return MOE_LRC_OK;
 }
@@ -405,16 +410,26 @@ int moe_lrc_forward(moe_lrc_layer* L, const void* x, int T, void* out, void* ws,
   int32_t* offsets = (int32_t*)(b + w.offsets);
   int32_t* row_pair = (int32_t*)(b + w.row_pair);
   int32_t* pair_row = (int32_t*)(b + w.pair_row);
+  const bool mk = L->profile;
+  L->profile_valid = false;
+  if (mk) LRC_HIP(hipEventRecord(L->marks[MOE_LRC_STAGE_ROUTE], s));
   LRC_HIP(launch_route(L, x, T, idx, tw, nullptr, s));
+  if (mk) LRC_HIP(hipEventRecord(L->marks[MOE_LRC_STAGE_PERMUTE], s));
   LRC_HIP(launch_permute(L, idx, T, (int32_t*)(b + w.counts), offsets, row_pair, pair_row,
                          (int32_t*)(b + w.comp_counts), s));
-  if ((rc = run_expert_ffn(L, x, T, offsets, row_pair, b + w.y_rows, b, s))) return rc;
+  if (mk) LRC_HIP(hipEventRecord(L->marks[MOE_LRC_STAGE_PREP], s));
+  if ((rc = run_expert_ffn(L, x, T, offsets, row_pair, b + w.y_rows, b, s, mk))) return rc;
   const void* y_shared = nullptr;
   if (L->cfg.n_shared > 0) {
     if ((rc = run_shared(L, x, T, b, true, s))) return rc;
     y_shared = b + w.sh_y;
   }
+  if (mk) LRC_HIP(hipEventRecord(L->marks[MOE_LRC_STAGE_COMBINE], s));
   LRC_HIP(launch_combine(L, b + w.y_rows, tw, pair_row, y_shared, T, out, s));
+  if (mk) {
+    LRC_HIP(hipEventRecord(L->marks[MOE_LRC_N_STAGES], s));
+    L->profile_valid = true;
+  }
   return MOE_LRC_OK;
 }
 
@@ -451,6 +466,23 @@ int moe_lrc_unpack_codes(int bits, int K, int N, const void* packed, uint8_t* co
   if (!codes || !packed) return set_error(MOE_LRC_EINVAL, "unpack_codes: null argument");
   if (bits < 2 || bits > 4 || K <= 0 || N <= 0 || N % 16) return set_error(MOE_LRC_ESHAPE, "unpack_codes: unsupported shape");
   unpack_codes(make_layout(K, N, bits, 64, 0), (const uint32_t*)packed, codes);
+  return MOE_LRC_OK;
+}
+
+int moe_lrc_profile_enable(moe_lrc_layer* L, int on) {
+  if (!L) return set_error(MOE_LRC_EINVAL, "profile_enable: layer is null");
+  if (on && !L->marks[0])
+    for (auto& ev : L->marks) LRC_HIP(hipEventCreate(&ev));
+  L->profile = on != 0;
+  L->profile_valid = false;
+  return MOE_LRC_OK;
+}
+
+int moe_lrc_profile_read(moe_lrc_layer* L, float* ms) {
+  if (!L || !ms) return set_error(MOE_LRC_EINVAL, "profile_read: null argument");
+  if (!L->profile_valid) return set_error(MOE_LRC_ESTATE, "profile_read: no profiled forward call yet");
+  LRC_HIP(hipEventSynchronize(L->marks[MOE_LRC_N_STAGES]));
+  for (int i = 0; i < MOE_LRC_N_STAGES; ++i) LRC_HIP(hipEventElapsedTime(&ms[i], L->marks[i], L->marks[i + 1]));
   return MOE_LRC_OK;
 }
 

@@ -282,13 +282,17 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s) {
   a.KS = padded_k(f.H) / kTileK; a.G = padded_k(f.H) / f.group;
   a.p = f.p13; a.ksplit = f.ksplit13;
   if (comp) hipLaunchKernelGGL(xa_kernel<true>, dim3(a.ksplit, f.n_exp), dim3(256), 0, s, a);
+  if (f.marks) (void)hipEventRecord(f.marks[0], s);
   hipLaunchKernelGGL((qgemm_kernel<BITS, true>), dim3(f.F / (kTileN * kBlockWaves), f.n_exp), dim3(256), 0, s, a);
+  if (f.marks) (void)hipEventRecord(f.marks[1], s);
   // W2
   a.in = f.h; a.out = f.y_rows; a.K = f.F; a.N = f.H;
   a.KS = padded_k(f.F) / kTileK; a.G = padded_k(f.F) / f.group;
   a.p = f.p2; a.ksplit = f.ksplit2;
   if (comp) hipLaunchKernelGGL(xa_kernel<false>, dim3(a.ksplit, f.n_exp), dim3(256), 0, s, a);
+  if (f.marks) (void)hipEventRecord(f.marks[2], s);
   hipLaunchKernelGGL((qgemm_kernel<BITS, false>), dim3(f.H / (kTileN * kBlockWaves), f.n_exp), dim3(256), 0, s, a);
+  if (f.marks) (void)hipEventRecord(f.marks[3], s);
   return hipGetLastError();
 }
 

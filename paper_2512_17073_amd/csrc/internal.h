@@ -60,6 +60,8 @@ struct moe_lrc_layer {
   moe_lrc_stats stats{};
   bool stats_valid = false;
   int ksplit13 = 1, ksplit2 = 1;
+  bool profile = false, profile_valid = false;
+  hipEvent_t marks[MOE_LRC_N_STAGES + 1] = {};   // stage i runs between marks[i] and marks[i+1]
 };
 
 namespace lrc {
@@ -90,6 +92,7 @@ struct FfnArgs {
   float* p2;                  // [ksplit2][rows][rpad]
   void* y_rows;               // [rows][H] bf16
   int ksplit13, ksplit2, total_rows;
+  hipEvent_t* marks;          // null, or 4 events recorded after xa13, w13, xa2, w2
 };
 hipError_t launch_expert_ffn(const FfnArgs& a, hipStream_t s);
 hipError_t launch_combine(const moe_lrc_layer* L, const void* y_rows, const float* w,

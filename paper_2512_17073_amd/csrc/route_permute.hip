@@ -133,7 +133,7 @@ __global__ __launch_bounds__(1024) void permute_kernel(const int32_t* __restrict
   const int per_wave = ((P + kPermWaves - 1) / kPermWaves + 63) / 64 * 64;
   const int begin = wave * per_wave, end = min(P, begin + per_wave);
   for (int i = begin + lane; i < end; i += 64) {
-    const int e = idx[i];
+    const int e = min(max(idx[i], 0), E - 1);     // out-of-range ids cannot leave the LDS tables
     atomicAdd(&hist[wave][e], 1);
     if (i % top_k < top_n) atomicAdd(&comp[e], 1);
   }
@@ -165,7 +165,7 @@ __global__ __launch_bounds__(1024) void permute_kernel(const int32_t* __restrict
   for (int base = begin; base < end; base += 64) {
     const int i = base + lane;
     const bool valid = i < end;
-    const int e = valid ? idx[i] : 0;
+    const int e = valid ? min(max(idx[i], 0), E - 1) : 0;
     unsigned long long same = __ballot(valid);
     for (int b = 0; b < nbits; ++b) {
       const bool bit = (e >> b) & 1;

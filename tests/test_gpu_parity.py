@@ -192,9 +192,10 @@ def test_large_scale_and_degenerate_groups(amd):
 def test_staged_mode_matches_resident(amd):
     import torch
     cfg = configs.TINY.with_(tokens=5, name="staged")     # few tokens: some experts stay on the host
-    layer, Lr = _build(amd, cfg)
-    Ls = amd.Layer.from_config(cfg, residency=amd.STAGED)
-    Ls.load(layer)
+    layer = fixtures.build_layer(cfg)
+    Lr = amd.Layer.from_config(cfg, max_tokens=16)
+    Ls = amd.Layer.from_config(cfg, max_tokens=16, residency=amd.STAGED)
+    Lr.load(layer); Ls.load(layer)
     x_bits = synth.make_tokens(cfg)
     x = amd.bf16_tensor(x_bits)
     a, b = Lr.forward(x).clone(), Ls.forward(x).clone()
