@@ -13,7 +13,7 @@ from typing import Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libmoe_lrc.so")
+LIB_PATH = os.environ.get("MOE_LRC_LIB") or os.path.join(_HERE, "libmoe_lrc.so")   # override: kernel-variant sweeps
 
 RESIDENT, STAGED = 0, 1
 

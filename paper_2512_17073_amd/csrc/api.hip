@@ -75,11 +75,15 @@ Workspace plan_workspace(const moe_lrc_layer* L, int T) {
   w.counts = take(E * 4);    w.offsets = take((E + 1) * 4);  w.comp_counts = take(E * 4);
   w.row_pair = take(P * 4);  w.pair_row = take(P * 4);
   w.y_rows = take(P * c.hidden * 2);
-  w.xh = take(size_t(T) * c.hidden * 2);
-  w.h = take(P * c.ffn * 2);
+  // activations in operand order: whole k-steps (256 columns) and kActPadRows rows of slack
+  const size_t Hp = padded_k(c.hidden), Fp = padded_k(c.ffn);
+  w.xh = take((P + kActPadRows) * Hp * 2);
+  w.xh_sh = take(c.n_shared ? (size_t(T) + kActPadRows) * Hp * 2 : 0);
+  w.h = take((P + kActPadRows) * Fp * 2);
   w.p13 = take(size_t(L->ksplit13) * P * 2 * rpad * 4);
   w.p2 = take(size_t(L->ksplit2) * P * rpad * 4);
-  w.sh_h = take(size_t(c.n_shared) * T * c.ffn * 2);
+  w.y_part = take(size_t(kMaxKBlocks) * std::max<size_t>(P, size_t(c.n_shared) * T) * c.hidden * 4);
+  w.sh_h = take(c.n_shared ? (size_t(c.n_shared) * T + kActPadRows) * Fp * 2 : 0);
   w.sh_y = take(size_t(c.n_shared) * T * c.hidden * 2);
   w.total = o;
   return w;
@@ -154,7 +158,8 @@ static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t*
   const moe_lrc_config& c = L->cfg;
   const Workspace w = plan_workspace(L, T);
   _Float16* xh = reinterpret_cast<_Float16*>(ws + w.xh);
-  LRC_HIP(launch_convert_x(L, x, T, xh, offsets, row_pair, L->d_stat, stream));
+  const int P = T * c.top_k;
+  LRC_HIP(launch_convert_x(L, x, T, xh, P + kActPadRows, offsets, row_pair, L->d_stat, stream));
   L->stats_valid = false;
   L->stats.stage_ms = 0.f;
   if (c.residency == MOE_LRC_STAGED) {
@@ -168,7 +173,9 @@ static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t*
   a.H = c.hidden; a.F = c.ffn; a.top_k = c.top_k; a.top_n = c.top_n; a.T = T;
   a.offsets = offsets; a.row_pair = row_pair; a.xh = xh;
   a.h = reinterpret_cast<_Float16*>(ws + w.h);
+  a.x_rt = P + kActPadRows; a.h_rt = P + kActPadRows;
   a.p13 = reinterpret_cast<float*>(ws + w.p13); a.p2 = reinterpret_cast<float*>(ws + w.p2);
+  a.y_part = reinterpret_cast<float*>(ws + w.y_part);
   a.y_rows = y_rows; a.ksplit13 = L->ksplit13; a.ksplit2 = L->ksplit2; a.total_rows = T * c.top_k;
   a.marks = mark ? &L->marks[MOE_LRC_STAGE_W13] : nullptr;
   LRC_HIP(launch_expert_ffn(a, stream));
@@ -176,16 +183,18 @@ static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t*
   return MOE_LRC_OK;
 }
 
-static int run_shared(moe_lrc_layer* L, const void* x, int T, uint8_t* ws, bool xh_ready, hipStream_t stream) {
+static int run_shared(moe_lrc_layer* L, const void* x, int T, uint8_t* ws, hipStream_t stream) {
   const moe_lrc_config& c = L->cfg;
   const Workspace w = plan_workspace(L, T);
-  _Float16* xh = reinterpret_cast<_Float16*>(ws + w.xh);
-  if (!xh_ready) LRC_HIP(launch_convert_x(L, x, T, xh, nullptr, nullptr, nullptr, stream));
+  _Float16* xh = reinterpret_cast<_Float16*>(ws + w.xh_sh);
+  LRC_HIP(launch_convert_x(L, x, T, xh, T + kActPadRows, nullptr, nullptr, nullptr, stream));
   FfnArgs a{};
   a.desc = L->d_desc + c.n_experts; a.n_exp = c.n_shared; a.bits = c.shared_bits; a.group = c.group;
   a.rank = 0; a.rpad = 0; a.H = c.hidden; a.F = c.ffn; a.top_k = c.top_k; a.top_n = 0; a.T = T;
   a.offsets = nullptr; a.row_pair = nullptr; a.xh = xh;
   a.h = reinterpret_cast<_Float16*>(ws + w.sh_h);
+  a.x_rt = T + kActPadRows; a.h_rt = c.n_shared * T + kActPadRows;
+  a.y_part = reinterpret_cast<float*>(ws + w.y_part);
   a.y_rows = ws + w.sh_y; a.ksplit13 = 1; a.ksplit2 = 1; a.total_rows = T * c.n_shared;
   LRC_HIP(launch_expert_ffn(a, stream));
   return MOE_LRC_OK;
@@ -387,7 +396,7 @@ int moe_lrc_combine(moe_lrc_layer* L, const void* y_rows, const float* w, const 
   const void* y_shared = nullptr;
   if (shared) {
     if (L->cfg.residency == MOE_LRC_STAGED && (rc = check_uploaded(L, "combine", true, true))) return rc;
-    if ((rc = run_shared(L, x, T, (uint8_t*)ws, false, (hipStream_t)stream))) return rc;
+    if ((rc = run_shared(L, x, T, (uint8_t*)ws, (hipStream_t)stream))) return rc;
     y_shared = (uint8_t*)ws + plan_workspace(L, T).sh_y;
   }
   LRC_HIP(launch_combine(L, y_rows, w, pair_row, y_shared, T, out, (hipStream_t)stream));
@@ -421,7 +430,7 @@ int moe_lrc_forward(moe_lrc_layer* L, const void* x, int T, void* out, void* ws,
   if ((rc = run_expert_ffn(L, x, T, offsets, row_pair, b + w.y_rows, b, s, mk))) return rc;
   const void* y_shared = nullptr;
   if (L->cfg.n_shared > 0) {
-    if ((rc = run_shared(L, x, T, b, true, s))) return rc;
+    if ((rc = run_shared(L, x, T, b, s))) return rc;
     y_shared = b + w.sh_y;
   }
   if (mk) LRC_HIP(hipEventRecord(L->marks[MOE_LRC_STAGE_COMBINE], s));

@@ -1,0 +1,98 @@
+// Shared device helpers and argument block of the expert-FFN kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "internal.h"
+#include "unpack.h"
+
+namespace lrc {
+namespace ffn {
+
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+
+// Tunables of the decode flavour (overridable at build time for sweeps).
+#ifndef LRC_LDS_UNITS
+#define LRC_LDS_UNITS 4096
+#endif
+#ifndef LRC_DECODE_WAVES
+#define LRC_DECODE_WAVES 6
+#endif
+#ifndef LRC_DECODE_MINW
+#define LRC_DECODE_MINW 3
+#endif
+#ifndef LRC_RING
+#define LRC_RING 4
+#endif
+#ifndef LRC_RING_WIDE
+#define LRC_RING_WIDE 3
+#endif
+constexpr int kLdsUnits = LRC_LDS_UNITS;   // LDS for activations in 16-byte units (4096 = 64 KB)
+// k-steps of packed tiles a wavefront keeps in registers (one being unpacked, the rest in flight);
+// 3- and 4-bit tiles of two projections are larger, three of them fill the register budget
+__host__ __device__ constexpr int ring_depth(int bits, bool dual) { return dual && bits > 2 ? LRC_RING_WIDE : LRC_RING; }
+
+// wavefronts per block: 6 (two blocks = 12 wavefronts per CU at <= 168 registers) for the decode
+// flavour, 8 (one block per CU at <= 256 registers) when many rows share one unpack
+__host__ __device__ constexpr int block_waves(int maxmt) { return maxmt <= 2 ? LRC_DECODE_WAVES : 8; }
+
+__device__ inline uint32_t pk_fma(uint32_t q, uint32_t s, uint32_t c) {
+  const half2_t r = __builtin_elementwise_fma(__builtin_bit_cast(half2_t, q),
+                                              __builtin_bit_cast(half2_t, s),
+                                              __builtin_bit_cast(half2_t, c));
+  return __builtin_bit_cast(uint32_t, r);
+}
+__device__ inline uint32_t pk_mul(uint32_t a, uint32_t b) {
+  const half2_t r = __builtin_bit_cast(half2_t, a) * __builtin_bit_cast(half2_t, b);
+  return __builtin_bit_cast(uint32_t, r);
+}
+
+struct KArgs {
+  const ExpertDesc* desc;
+  const int32_t* offsets;    // null: shared experts, expert e owns rows e*T .. e*T+T-1
+  const int32_t* row_pair;   // null: rows are tokens
+  const _Float16* in;        // activations in operand order (act_unit), in_rt rows: gathered x, or h
+  void* out;                 // DUAL: h in operand order (out_rt rows); else y_rows [rows][N] bf16
+  int in_rt, out_rt;         // row counts (incl. padding) of the operand-order buffers
+  const float* p;            // split-K partials of (in A): [ksplit][total_rows][PW]
+  int K, N, KS, G, NT, group_shift, top_k, top_n, T, rank, rpad, ksplit, total_rows;
+  int kw;                    // wavefronts that share one n-tile, each taking every kw-th k-step
+  int kb_steps;              // decode flavour: k-steps per K-block (grid.z blocks split K; KS if one)
+  float* partial;            // decode flavour, more than one K-block: fp32 partial outputs [kb][rows][N]
+};
+
+__device__ inline uint32_t f32x2_to_bf16x2(float a, float b) {
+  uint32_t ua = __float_as_uint(a), ub = __float_as_uint(b);
+  ua += 0x7fffu + ((ua >> 16) & 1u);
+  ub += 0x7fffu + ((ub >> 16) & 1u);
+  return (ua >> 16) | (ub & 0xffff0000u);
+}
+
+
+// Operand-order activations: the 8 consecutive elements k8*8 .. k8*8+7 of row R form one 16-byte
+// unit at index ((ks*8 + s)*4 + q) * rt + R, where k8 = ks*32 + q*8 + s.  For a fixed (ks, s, q) the
+// rows are contiguous, so the 16 rows x 4 q of one MFMA B-operand fragment are four 256-byte runs
+// and staging a fragment into LDS is a lane-linear copy.
+__device__ inline size_t act_unit(int k8, int R, int rt) {
+  const int ks = k8 >> 5, q = (k8 >> 3) & 3, s = k8 & 7;
+  return size_t((ks * 8 + s) * 4 + q) * rt + R;
+}
+
+// Codes and metadata of one k-step of one wavefront (both projections when DUAL), in registers.
+template <int BITS, int NM> struct Slot {
+  uint32_t cw[NM][2 * BITS];
+  uint32_t mw[NM];
+};
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+}  // namespace ffn
+
+// decode flavour (ffn_decode.hip): few rows per expert, one 16-wavefront block per CU
+hipError_t launch_decode_ffn(const FfnArgs& f, hipStream_t s);
+
+}  // namespace lrc

@@ -32,7 +32,7 @@ struct BlobLayout {
 
 struct Workspace {       // carved out of the caller's buffer; all offsets 256-byte aligned
   size_t topk_idx, topk_w, counts, offsets, comp_counts, row_pair, pair_row;
-  size_t y_rows, xh, h, p13, p2, sh_h, sh_y, total;
+  size_t y_rows, xh, xh_sh, h, p13, p2, y_part, sh_h, sh_y, total;
 };
 
 }  // namespace lrc
@@ -75,9 +75,13 @@ hipError_t launch_route(const moe_lrc_layer* L, const void* x, int T, int32_t* i
 hipError_t launch_permute(const moe_lrc_layer* L, const int32_t* idx, int T, int32_t* counts,
                           int32_t* offsets, int32_t* row_pair, int32_t* pair_row,
                           int32_t* comp_counts, hipStream_t s);
-hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _Float16* xh,
+// fp16 copy of the activations in operand order: one row per routed pair (row_pair given) or one
+// per token (row_pair null); with `stat`, one more block counts the per-expert rows
+hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _Float16* xg, int rt,
                             const int32_t* offsets, const int32_t* row_pair, int32_t* stat,
                             hipStream_t s);
+constexpr int kMaxKBlocks = 8;    // most K-blocks the decode W2 kernel splits into
+constexpr int kActPadRows = 32;   // rows past the last one that a 32-row staging pass may read
 
 struct FfnArgs {
   const ExpertDesc* desc;     // device array, already offset to the first expert of this launch
@@ -86,11 +90,13 @@ struct FfnArgs {
   int H, F, top_k, top_n, T;
   const int32_t* offsets;     // [n_exp+1] or null: shared experts, rows e*T .. e*T+T-1
   const int32_t* row_pair;    // null for shared experts (row -> token = row % T)
-  const _Float16* xh;         // [T][H] fp16
-  _Float16* h;                // [rows][F] fp16
+  const _Float16* xh;         // gathered activations in operand order, x_rt rows (routed: one per pair)
+  _Float16* h;                // SwiGLU output in operand order, h_rt rows
+  int x_rt, h_rt;
   float* p13;                 // [ksplit13][rows][2*rpad]
   float* p2;                  // [ksplit2][rows][rpad]
   void* y_rows;               // [rows][H] bf16
+  float* y_part;              // fp32 partial outputs of the W2 K-blocks (decode flavour), or null
   int ksplit13, ksplit2, total_rows;
   hipEvent_t* marks;          // null, or 4 events recorded after xa13, w13, xa2, w2
 };

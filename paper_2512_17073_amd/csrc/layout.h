@@ -16,16 +16,20 @@
 //          spare); pairs 30 and 31 are spread over the spare bits: bit j of the code of pair 30+t
 //          lives in bit 0 (low half) / bit 16 (high half) of dword 3*t + j.
 //
-// Tiles are stored n-tile-major, k-steps consecutive, so a wavefront streams a contiguous run of
-// memory.  Inside a tile, dwords 0..3 of all lanes come first ([lane][4], one 16-byte load per lane),
-// then the remaining 2*bits-4 dwords ([lane][2*bits-4]).
+// Tiles are stored k-step-major: tile (ks, nt) sits at index ks * NT + nt.  The wavefronts of a
+// launch advance through the k-steps at about the same pace, each on its own n-tile, so at any
+// moment the tiles being read form one contiguous sweep of memory that spreads evenly over the HBM
+// channels (an n-tile-major order would have every wavefront read at the same large stride).
+// Inside a tile, dwords 0..3 of all lanes come first ([lane][4], one 16-byte load per lane), then
+// the remaining 2*bits-4 dwords ([lane][2*bits-4]).
 //
-// Per-group metadata is stored per n-tile as [K/group][16 columns] pairs of fp16:
+// Per-group metadata is stored group-major as [K/group][NT][16 columns] pairs of fp16:
 //   lo = scale * lambda * 2^(14+bits),  hi = -zero * scale * lambda
 // so that fma(field, lo, hi) on the fp16 *subnormal* whose mantissa holds the code at its top bits
 // (value code * 2^-(14+bits)) gives lambda * (code - zero) * scale in one packed instruction.
-// lambda is a power of two chosen per projection so that lo stays finite; the kernels multiply the
-// accumulators by 1/lambda at the end.
+// Codes that sit lower in the mantissa use lo * 2^(their distance from the top) instead.
+// lambda is a power of two chosen per projection so that every such multiple of lo stays finite;
+// the kernels multiply the accumulators by 1/lambda at the end.
 #pragma once
 #include <stddef.h>
 #include <stdint.h>

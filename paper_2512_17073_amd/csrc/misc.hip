@@ -52,15 +52,17 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict
   }
 }
 
-// Blocks 0..T-1 write the fp16 copy of their token; one extra block counts, per expert, the routed
+// Blocks 0..rows-1 write the fp16 copy of their row's token in operand order (the layout the FFN
+// kernels stage from, see act_unit in ffn_common.h): row R of the routed rows is the token of pair
+// row_pair[R]; without row_pair, row R is token R.  One extra block counts, per expert, the routed
 // rows and the rows that take the rank-r term (what the router-guided transfer must bring in).
 // stat = [active experts, comp-active experts, rows[E], comp rows[E]].
-__global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ x, int T, int H,
-                                                   _Float16* __restrict__ xh,
+__global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ x, int rows, int H,
+                                                   uint4* __restrict__ xg, int rt,
                                                    const int32_t* __restrict__ offsets,
                                                    const int32_t* __restrict__ row_pair, int E, int top_k,
                                                    int top_n, int32_t* __restrict__ stat) {
-  if ((int)blockIdx.x == T) {
+  if ((int)blockIdx.x == rows) {
     __shared__ int n_active, n_comp;
     if (threadIdx.x == 0) { n_active = 0; n_comp = 0; }
     __syncthreads();
@@ -77,10 +79,11 @@ __global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ 
     if (threadIdx.x == 0) { stat[0] = n_active; stat[1] = n_comp; }
     return;
   }
-  const int t = blockIdx.x;
+  const int R = blockIdx.x;
+  const int t = row_pair ? row_pair[R] / top_k : R;
   const uint4* xrow = reinterpret_cast<const uint4*>(x + size_t(t) * H);
-  for (int c = threadIdx.x; c < H / 8; c += 256) {
-    const uint4 v = xrow[c];
+  for (int k8 = threadIdx.x; k8 < H / 8; k8 += 256) {
+    const uint4 v = xrow[k8];
     const uint32_t in[4] = {v.x, v.y, v.z, v.w};
     uint32_t o[4];
 #pragma unroll
@@ -89,7 +92,8 @@ __global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ 
       const _Float16 hi = (_Float16)bf16_hi(in[i]);
       o[i] = uint32_t(__builtin_bit_cast(uint16_t, lo)) | (uint32_t(__builtin_bit_cast(uint16_t, hi)) << 16);
     }
-    reinterpret_cast<uint4*>(xh + size_t(t) * H)[c] = make_uint4(o[0], o[1], o[2], o[3]);
+    const int ks = k8 >> 5, q = (k8 >> 3) & 3, s = k8 & 7;
+    xg[size_t((ks * 8 + s) * 4 + q) * rt + R] = make_uint4(o[0], o[1], o[2], o[3]);
   }
 }
 
@@ -98,16 +102,16 @@ __global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ 
 template <int BITS>
 __global__ __launch_bounds__(64) void unpack_kernel(const uint32_t* __restrict__ packed, int K, int N,
                                                     int KS, uint8_t* __restrict__ codes) {
-  const int tile = blockIdx.x, nt = tile / KS, ks = tile % KS, lane = threadIdx.x;
-  uint32_t w[2 * BITS], f[32];
+  const int tile = blockIdx.x, NT = N / kTileN, ks = tile / NT, nt = tile % NT, lane = threadIdx.x;
+  uint32_t w[2 * BITS];
   load_codes<BITS>(packed + size_t(tile) * kWave * 2 * BITS, lane, w);
-  Extract<BITS>::run(w, f);
   const int n = nt * kTileN + (lane & 15), kbase = ks * kTileK + (lane >> 4) * kLaneK;
 #pragma unroll
   for (int pi = 0; pi < 32; ++pi) {
+    const uint32_t f = Extract<BITS>::field(w, pi);
     const int k = kbase + 2 * pi;
-    if (k < K) codes[size_t(k) * N + n] = (uint8_t)((f[pi] & 0xffffu) >> (10 - BITS));
-    if (k + 1 < K) codes[size_t(k + 1) * N + n] = (uint8_t)((f[pi] >> 16) >> (10 - BITS));
+    if (k < K) codes[size_t(k) * N + n] = (uint8_t)field_code<BITS>(f & 0xffffu, pi);
+    if (k + 1 < K) codes[size_t(k + 1) * N + n] = (uint8_t)field_code<BITS>(f >> 16, pi);
   }
 }
 
@@ -122,12 +126,14 @@ hipError_t launch_combine(const moe_lrc_layer* L, const void* y_rows, const floa
   return hipGetLastError();
 }
 
-hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _Float16* xh,
+hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _Float16* xg, int rt,
                             const int32_t* offsets, const int32_t* row_pair, int32_t* stat,
                             hipStream_t s) {
   const moe_lrc_config& c = L->cfg;
-  hipLaunchKernelGGL(prep_kernel, dim3(T + (stat ? 1 : 0)), dim3(256), 0, s, (const uint16_t*)x_bf16, T, c.hidden, xh,
-                     offsets, row_pair, c.n_experts, c.top_k, c.top_n, stat);
+  const int rows = row_pair ? T * c.top_k : T;
+  hipLaunchKernelGGL(prep_kernel, dim3(rows + (stat ? 1 : 0)), dim3(256), 0, s, (const uint16_t*)x_bf16, rows,
+                     c.hidden, reinterpret_cast<uint4*>(xg), rt, offsets, row_pair, c.n_experts, c.top_k, c.top_n,
+                     stat);
   return hipGetLastError();
 }
 

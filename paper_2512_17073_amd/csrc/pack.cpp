@@ -63,7 +63,7 @@ void pack_codes(const MatLayout& m, const uint8_t* codes, uint32_t* out) {
         for (int n = 0; n < m.N; ++n) {
           const uint32_t code = row[n];
           const int nt = n >> 4, lane = q * 16 + (n & 15);
-          uint32_t* tile = out + (size_t(nt) * m.KS + ks) * tdw;
+          uint32_t* tile = out + (size_t(ks) * m.NT + nt) * tdw;
           for (int p = 0; p < np; ++p) {
             const uint32_t piece = (code >> pc[p].src_shift) & ((1u << pc[p].width) - 1u);
             tile[tile_dword_index(bits, lane, pc[p].dword)] |= piece << pc[p].bit;
@@ -85,7 +85,7 @@ void unpack_codes(const MatLayout& m, const uint32_t* packed, uint8_t* codes) {
         uint8_t* row = codes + size_t(k) * m.N;
         for (int n = 0; n < m.N; ++n) {
           const int nt = n >> 4, lane = q * 16 + (n & 15);
-          const uint32_t* tile = packed + (size_t(nt) * m.KS + ks) * tdw;
+          const uint32_t* tile = packed + (size_t(ks) * m.NT + nt) * tdw;
           uint32_t code = 0;
           for (int p = 0; p < np; ++p) {
             const uint32_t w = tile[tile_dword_index(bits, lane, pc[p].dword)];
@@ -106,8 +106,11 @@ float pack_meta(const MatLayout& m, const uint16_t* scale_f16, const uint16_t* z
     if (std::isfinite(s)) smax = std::max(smax, s);
   }
   const double up = std::ldexp(1.0, 14 + m.bits);
+  // the kernels also form scale * 2^(class shift) for codes that sit lower in the mantissa:
+  // up to 2^4 (2 bit) or 2^6 (3 and 4 bit) times the stored value must stay finite in fp16
+  const double class_max = m.bits == 2 ? 16.0 : 64.0;
   int j = 0;
-  while (smax * up * std::ldexp(1.0, -j) > 32768.0) ++j;
+  while (smax * up * class_max * std::ldexp(1.0, -j) > 32768.0) ++j;
   const double lambda = std::ldexp(1.0, -j);
   std::memset(out, 0, m.meta_bytes);
   for (int nt = 0; nt < m.NT; ++nt)
@@ -117,7 +120,7 @@ float pack_meta(const MatLayout& m, const uint16_t* scale_f16, const uint16_t* z
         const double s = f16_bits_to_float(scale_f16[src]), z = f16_bits_to_float(zero_f16[src]);
         const uint32_t lo = float_to_f16_bits(s * lambda * up);
         const uint32_t hi = float_to_f16_bits(-z * s * lambda);
-        out[(size_t(nt) * m.G + g) * kTileN + c] = lo | (hi << 16);
+        out[(size_t(g) * m.NT + nt) * kTileN + c] = lo | (hi << 16);
       }
   return (float)lambda;
 }
