@@ -12,7 +12,8 @@
 //     ring of register slots walked by straight-line code: a load past the end of the resource returns
 //     zeros, so refills are unconditional and the number of loads in flight is static;
 //   - codes are unpacked in registers (unpack.h) straight into MFMA A-operands; the rank-r term is
-//     r/16 more MFMA steps on the pre-computed (x A), which xa_final_kernel leaves in fp16.
+//     r/16 more MFMA steps on the pre-computed (x A): xa_split_kernel leaves K-block partial sums,
+//     which a block adds in a fixed order into LDS when it starts.
 #include <algorithm>
 
 #include "ffn_common.h"
@@ -139,6 +140,24 @@ __global__ __launch_bounds__(64 * kDecodeWaves, 4) void qgemm_decode_kernel(KArg
       flag[mt] = false;
       if (lowrank && mt < mt_n && row < cnt) flag[mt] = (a.row_pair[r0 + row] % a.top_k) < a.top_n;
     }
+    // (in A) of this pass's rows: the K-block partial sums of xa_split_kernel are added here, in
+    // K-block order, and kept in LDS as fp16 behind the activations (zero for rows without the term)
+    const int PW = DUAL ? 2 * a.rpad : a.rpad;
+    _Float16* p_lds = reinterpret_cast<_Float16*>(xs + kDecodeLdsUnits);
+    auto load_p = [&]() {
+      for (int e2 = th; e2 < 16 * PW; e2 += 64 * kDecodeWaves) {      // pairs of adjacent columns
+        const int row = (2 * e2) / PW, col = (2 * e2) - row * PW;
+        float sx = 0.f, sy = 0.f;
+        if (r + row < cnt && (a.row_pair[r0 + r + row] % a.top_k) < a.top_n) {
+          const float* pp = a.p + size_t(r0 + r + row) * PW + col;
+          for (int kb2 = 0; kb2 < a.ksplit; ++kb2) {
+            const float2 v = *reinterpret_cast<const float2*>(pp + size_t(kb2) * a.total_rows * PW);
+            sx += v.x; sy += v.y;
+          }
+        }
+        *reinterpret_cast<half2_t*>(p_lds + 2 * e2) = half2_t{(_Float16)sx, (_Float16)sy};
+      }
+    };
     // The B-factor tiles of this wavefront's n-tiles are needed only after the last k-step, by loads
     // that would then miss every cache: touch their lines now (one dword per 64 bytes, one lane per
     // line) so that they wait in L2.  The value is only kept alive, never used.
@@ -230,6 +249,7 @@ __global__ __launch_bounds__(64 * kDecodeWaves, 4) void qgemm_decode_kernel(KArg
     for (int ph = 0; ph < n_ph; ++ph) {
       const int nk = min(KP, KSl - ph * KP);
       if (ph > 0 || r > 0) __syncthreads();   // everyone is done with the previous phase
+      if (ph == 0 && lowrank) load_p();
       if (ph < 5) LRC_STAMP(1 + 2 * ph);
       stage(ph, nk);
       __syncthreads();
@@ -275,9 +295,7 @@ __global__ __launch_bounds__(64 * kDecodeWaves, 4) void qgemm_decode_kernel(KArg
 
     // ---- rank-r term: r/16 more MFMA steps on (in A), two at a time with every load of the pair
     //      of steps (B-factor tiles of both n-tiles, (in A) fragments of both row tiles) issued first
-    const int PW = DUAL ? 2 * a.rpad : a.rpad;
     const int rs = a.rpad / 16;
-    const _Float16* pbase = reinterpret_cast<const _Float16*>(a.p);
     bool any = false;
 #pragma unroll
     for (int mt = 0; mt < kDMT; ++mt) any = any || __ballot(flag[mt]) != 0ull;
@@ -300,7 +318,7 @@ __global__ __launch_bounds__(64 * kDecodeWaves, 4) void qgemm_decode_kernel(KArg
             for (int mt = 0; mt < kDMT; ++mt) {
               pf[mt][m][j] = half4_t{0, 0, 0, 0};
               if (flag[mt] && st < rs)
-                pf[mt][m][j] = *reinterpret_cast<const half4_t*>(pbase + size_t(r0 + r + 16 * mt + c) * PW + m * a.rpad + 16 * st + 4 * q);
+                pf[mt][m][j] = *reinterpret_cast<const half4_t*>(p_lds + (16 * mt + c) * PW + m * a.rpad + 16 * st + 4 * q);
             }
           }
 #pragma unroll
@@ -357,13 +375,14 @@ __global__ __launch_bounds__(64 * kDecodeWaves, 4) void qgemm_decode_kernel(KArg
   }
 }
 
-// p[row][rho] = sum_k in[row][k] * A[k][rho] in fp16, for the rows that take the rank-r term.
-// grid = (16-column tiles of the factor(s), experts); the 8 wavefronts of a block split K and add
-// their parts through LDS in a fixed order.
+// Partial (in A): pk[kb2][row][rho] = sum over K-block kb2 of in[row][k] * A[k][rho] in fp32, for the
+// rows that take the rank-r term.  grid = (16-column tiles of the factor(s), experts, K-blocks); the
+// 8 wavefronts of a block split their K-block and add their parts through LDS in a fixed order.
+// The FFN kernel adds the K-blocks (in order) when it starts.
 template <bool DUAL>
-__global__ __launch_bounds__(512) void xa_final_kernel(KArgs a) {
+__global__ __launch_bounds__(512) void xa_split_kernel(KArgs a) {
   __shared__ float4_t red[8][64];
-  const int e = blockIdx.y, tile = blockIdx.x;
+  const int e = blockIdx.y, tile = blockIdx.x, kb2 = blockIdx.z;
   const int r0 = a.offsets[e], cnt = a.offsets[e + 1] - r0;
   const ExpertDesc& d = a.desc[e];
   if (cnt == 0 || !d.has_factors) return;
@@ -372,34 +391,30 @@ __global__ __launch_bounds__(512) void xa_final_kernel(KArgs a) {
   const int rt = a.rpad / 16, PW = (DUAL ? 2 : 1) * a.rpad;
   const int mat = DUAL ? (tile >= rt ? 1 : 0) : 2;
   const int tl = DUAL && tile >= rt ? tile - rt : tile;
-  const _Float16* af = d.af[mat];
-  const int k32 = a.K / 32, per = (k32 + 7) / 8;
-  const int kk0 = wave * per, kk1 = min(k32, kk0 + per);
-  _Float16* pout = reinterpret_cast<_Float16*>(const_cast<float*>(a.p));
+  const half8_t* af = reinterpret_cast<const half8_t*>(d.af[mat]);
+  const int k32 = a.K / 32, per_b = (k32 + a.ksplit - 1) / a.ksplit, per = (per_b + 7) / 8;
+  const int kk0 = kb2 * per_b + wave * per, kk1 = min(min(k32, (kb2 + 1) * per_b), kk0 + per);
+  float* pout = const_cast<float*>(a.p) + size_t(kb2) * a.total_rows * PW;
+  const half8_t* src = reinterpret_cast<const half8_t*>(a.in);   // operand order: unit (k8, row)
   for (int r = 0; r < cnt; r += 16) {
     const int row = r + c;
     bool flagged = false;
     if (row < cnt) flagged = (a.row_pair[r0 + row] % a.top_k) < a.top_n;
     if (__ballot(flagged) == 0ull) continue;      // same rows in every wavefront: block-uniform
-    const half8_t* src = reinterpret_cast<const half8_t*>(a.in);   // operand order: unit (k8, row)
     float4_t acc = float4_t{0.f, 0.f, 0.f, 0.f};
-    int kk = kk0;
-    for (; kk + 4 <= kk1; kk += 4) {               // four steps of loads in flight
-      half8_t wf[4], xf[4];
+    for (int kk = kk0; kk < kk1; kk += 8) {        // eight steps of loads in flight
+      half8_t wf[8], xf[8];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        wf[u] = *reinterpret_cast<const half8_t*>(af + ((size_t(kk + u) * rt + tl) * kWave + lane) * 8);
+      for (int u = 0; u < 8; ++u) {
+        wf[u] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
         xf[u] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
-        if (flagged) xf[u] = src[act_unit(4 * (kk + u) + q, r0 + row, a.in_rt)];
+        if (kk + u < kk1) {
+          wf[u] = af[(size_t(kk + u) * rt + tl) * kWave + lane];
+          if (flagged) xf[u] = src[act_unit(4 * (kk + u) + q, r0 + row, a.in_rt)];
+        }
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[u], xf[u], acc, 0, 0, 0);
-    }
-    for (; kk < kk1; ++kk) {
-      const half8_t wf = *reinterpret_cast<const half8_t*>(af + ((size_t(kk) * rt + tl) * kWave + lane) * 8);
-      half8_t xf = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
-      if (flagged) xf = src[act_unit(4 * kk + q, r0 + row, a.in_rt)];
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf, xf, acc, 0, 0, 0);
+      for (int u = 0; u < 8; ++u) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[u], xf[u], acc, 0, 0, 0);
     }
     red[wave][lane] = acc;
     __syncthreads();
@@ -407,8 +422,7 @@ __global__ __launch_bounds__(512) void xa_final_kernel(KArgs a) {
       float4_t sum = red[0][lane];
 #pragma unroll
       for (int w = 1; w < 8; ++w) sum += red[w][lane];
-      const half4_t hv = half4_t{(_Float16)sum[0], (_Float16)sum[1], (_Float16)sum[2], (_Float16)sum[3]};
-      *reinterpret_cast<half4_t*>(pout + size_t(r0 + row) * PW + 16 * tile + 4 * q) = hv;
+      *reinterpret_cast<float4_t*>(pout + size_t(r0 + row) * PW + 16 * tile + 4 * q) = sum;
     }
     __syncthreads();
   }
@@ -431,10 +445,11 @@ template <int BITS>
 hipError_t launch_bits(const FfnArgs& f, hipStream_t s) {
   static bool attr_set = false;
   if (!attr_set) {
+    // 128 KB of activations + up to 32 KB of (in A) for 32 rows at rank 256 = all 160 KB of a CU
     hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(&qgemm_decode_kernel<BITS, true>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, kDecodeLdsUnits * 16);
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, kDecodeLdsUnits * 16 + 32768);
     hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(&qgemm_decode_kernel<BITS, false>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, kDecodeLdsUnits * 16);
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, kDecodeLdsUnits * 16 + 32768);
     if (e1 != hipSuccess) return e1;
     if (e2 != hipSuccess) return e2;
     attr_set = true;
@@ -454,25 +469,26 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s) {
     g = std::max(g, (NT + 16 * kTPW - 1) / (16 * kTPW));
     return std::min(g, NT);
   };
-  const size_t lds = size_t(kDecodeLdsUnits) * 16;
+  auto lds_bytes = [&](int pw) { return size_t(kDecodeLdsUnits) * 16 + (comp ? size_t(32) * pw * 2 : 0); };
+  auto xa_blocks = [](int K) { return std::max(1, std::min(8, K / 1024)); };   // K-blocks of the (in A) kernels
 
   // W1 | W3 with the SwiGLU epilogue
   a.in = f.xh; a.out = f.h; a.K = f.H; a.N = f.F; a.NT = f.F / kTileN;
   a.in_rt = f.x_rt; a.out_rt = f.h_rt;
   a.KS = padded_k(f.H) / kTileK; a.G = padded_k(f.H) / f.group;
-  a.p = f.p13;
-  if (comp) hipLaunchKernelGGL(xa_final_kernel<true>, dim3(2 * f.rpad / 16, f.n_exp), dim3(512), 0, s, a);
+  a.p = f.p13; a.ksplit = std::min(f.ksplit13, xa_blocks(f.H));
+  if (comp) hipLaunchKernelGGL(xa_split_kernel<true>, dim3(2 * f.rpad / 16, f.n_exp, a.ksplit), dim3(512), 0, s, a);
   if (f.marks) (void)hipEventRecord(f.marks[0], s);
   a.kb_steps = a.KS; a.partial = nullptr;
   hipLaunchKernelGGL((qgemm_decode_kernel<BITS, true>), dim3(blocks_per_expert(a.NT, 1), f.n_exp, 1),
-                     dim3(64 * kDecodeWaves), lds, s, a);
+                     dim3(64 * kDecodeWaves), lds_bytes(2 * f.rpad), s, a);
   if (f.marks) (void)hipEventRecord(f.marks[1], s);
   // W2
   a.in = f.h; a.out = f.y_rows; a.K = f.F; a.N = f.H; a.NT = f.H / kTileN;
   a.in_rt = f.h_rt; a.out_rt = 0;
   a.KS = padded_k(f.F) / kTileK; a.G = padded_k(f.F) / f.group;
-  a.p = f.p2;
-  if (comp) hipLaunchKernelGGL(xa_final_kernel<false>, dim3(f.rpad / 16, f.n_exp), dim3(512), 0, s, a);
+  a.p = f.p2; a.ksplit = std::min(f.ksplit2, xa_blocks(f.F));
+  if (comp) hipLaunchKernelGGL(xa_split_kernel<false>, dim3(f.rpad / 16, f.n_exp, a.ksplit), dim3(512), 0, s, a);
   if (f.marks) (void)hipEventRecord(f.marks[2], s);
   // a long K (many phases of staged activations) is split into K-blocks of one 16-k-step phase each;
   // their fp32 partial outputs are added by reduce_kernel
@@ -480,7 +496,7 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s) {
   a.kb_steps = (a.KS + kblocks - 1) / kblocks;
   a.partial = kblocks > 1 ? f.y_part : nullptr;
   hipLaunchKernelGGL((qgemm_decode_kernel<BITS, false>), dim3(blocks_per_expert(a.NT, kblocks), f.n_exp, kblocks),
-                     dim3(64 * kDecodeWaves), lds, s, a);
+                     dim3(64 * kDecodeWaves), lds_bytes(f.rpad), s, a);
   if (kblocks > 1) {
     const size_t units = size_t(f.total_rows) * f.H / 4;
     hipLaunchKernelGGL(reduce_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, s, f.y_part, kblocks,

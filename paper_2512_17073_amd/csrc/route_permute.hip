@@ -52,13 +52,23 @@ __global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__
   for (int e = wave; e < E; e += 4) {
     const uint4* wrow = reinterpret_cast<const uint4*>(wg + size_t(e) * H);
     double acc = 0.0;
-    for (int c = lane; c < chunks; c += 64) {
-      const uint4 xv = xrow[c], wv = wrow[c];
-      const uint32_t xa[4] = {xv.x, xv.y, xv.z, xv.w}, wa[4] = {wv.x, wv.y, wv.z, wv.w};
+    for (int c0 = lane; c0 < chunks; c0 += 64 * 8) {      // eight chunks of both rows in flight
+      uint4 xv[8], wv[8];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        acc = fma(bf16_to_double(xa[i] & 0xffffu), bf16_to_double(wa[i] & 0xffffu), acc);
-        acc = fma(bf16_to_double(xa[i] >> 16), bf16_to_double(wa[i] >> 16), acc);
+      for (int u = 0; u < 8; ++u) {
+        const int c = c0 + 64 * u;
+        xv[u] = make_uint4(0, 0, 0, 0);
+        wv[u] = make_uint4(0, 0, 0, 0);
+        if (c < chunks) { xv[u] = xrow[c]; wv[u] = wrow[c]; }
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {                       // same accumulation order as a plain loop
+        const uint32_t xa[4] = {xv[u].x, xv[u].y, xv[u].z, xv[u].w}, wa[4] = {wv[u].x, wv[u].y, wv[u].z, wv[u].w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          acc = fma(bf16_to_double(xa[i] & 0xffffu), bf16_to_double(wa[i] & 0xffffu), acc);
+          acc = fma(bf16_to_double(xa[i] >> 16), bf16_to_double(wa[i] >> 16), acc);
+        }
       }
     }
     acc = wave_sum(acc);
