@@ -76,7 +76,8 @@ def main():
     ap.add_argument("--workload", default="mixtral_decode_T64_b2")
     ap.add_argument("--layers", type=int, default=0, help="layer instances to rotate over (0: enough for > 2 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-tokens", type=int, default=8)
+    ap.add_argument("--graph", action="store_true", help="replay one captured HIP graph per layer instance instead of launching eagerly")
+    ap.add_argument("--cpu-tokens", type=int, default=64, help="tokens whose expert FFN the CPU oracle evaluates")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1", file=sys.stderr)
@@ -123,9 +124,37 @@ def main():
     def step(i):
         layers[i % n_layers].forward_raw(x.data_ptr(), T, out.data_ptr(), ws.data_ptr(), ws_bytes, stream)
 
-    for i in range(args.warmup):
+    for i in range(max(args.warmup, n_layers)):     # eager warm-up (every instance at least once)
         step(i)
     torch.cuda.synchronize()
+    eager_step = step
+    use_graph = args.graph
+    if use_graph:
+        # one captured forward per layer instance: the launch sequence is fixed (no allocation, no
+        # host synchronisation, no memset inside moe_lrc_forward), so a replay is the same work
+        graphs = []
+        cap_stream = torch.cuda.Stream()
+        with torch.cuda.stream(cap_stream):
+            for L in layers:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=cap_stream):
+                    L.forward_raw(x.data_ptr(), T, out.data_ptr(), ws.data_ptr(), ws_bytes,
+                                  torch.cuda.current_stream().cuda_stream)
+                graphs.append(g)
+        torch.cuda.synchronize()
+        ref_out = out.clone()
+        eager_step(n_layers - 1)
+        torch.cuda.synchronize()
+        ref_out.copy_(out)
+        graphs[n_layers - 1].replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ref_out.view(torch.int16), out.view(torch.int16)), "graph replay differs from eager"
+
+        def step(i):
+            graphs[i % n_layers].replay()
+        for i in range(args.warmup):
+            step(i)
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(i)
@@ -139,7 +168,7 @@ def main():
     stage_ms = {}
     reps = max(20, min(args.steps, 100))
     for i in range(reps):
-        step(i)
+        eager_step(i)
         prof = layers[i % n_layers].profile_read()
         for k, v in prof.items():
             stage_ms.setdefault(k, []).append(v)
@@ -166,7 +195,8 @@ def main():
         "config": {"workload": cfg.name, "tokens": T, "hidden": cfg.hidden, "ffn": cfg.ffn,
                    "experts": cfg.n_experts, "shared": cfg.n_shared, "top_k": cfg.top_k, "top_n": cfg.top_n,
                    "bits": cfg.bits, "group": cfg.group, "rank": cfg.rank, "layer_instances": n_layers,
-                   "active_experts": st["active_experts"], "comp_experts": st["comp_experts"]},
+                   "active_experts": st["active_experts"], "comp_experts": st["comp_experts"],
+                   "launch": "hip_graph" if use_graph else "eager"},
         "roofline": roofline,
         "whole_path": {"algorithmic_bytes": int(ab["total"]), "hbm_gbs_wall": round(ab["total"] / (ms_per_step * 1e-3) / 1e9, 1),
                        "hbm_frac_wall": round(ab["total"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),

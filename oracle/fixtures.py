@@ -16,33 +16,74 @@ from . import compress
 from . import moe_lrc_oracle as orc
 
 
+def _compress_one(args):
+    cfg, e, mat, method, keep_weights, keep_fp64_factors = args
+    return _compress_job(cfg, e, mat, method, keep_weights, keep_fp64_factors)
+
+
+def _compress_one_single_thread(args):
+    # worker processes: one BLAS thread each, the pool provides the parallelism
+    try:
+        from threadpoolctl import threadpool_limits
+        with threadpool_limits(limits=1):
+            return _compress_one(args)
+    except ImportError:
+        return _compress_one(args)
+
+
+def _compress_job(cfg, e, mat, method, keep_weights, keep_fp64_factors):
+    shared = e >= cfg.n_experts
+    W = synth.make_expert_weight(cfg, e, mat)
+    art = compress.compress_matrix(W, synth.expert_bits(cfg, e), cfg.group, 0 if shared else cfg.rank,
+                                   method=method, seed=cfg.seed + 31 * e + mat,
+                                   keep_fp64_factors=keep_fp64_factors)
+    art.pop("sigma", None)
+    if keep_weights:
+        art["W"] = W
+    return e, mat, art
+
+
 def build_layer(cfg: LayerConfig, method: str = "exact", keep_weights: bool = False,
-                keep_fp64_factors: bool = False, progress: bool = False) -> dict:
+                keep_fp64_factors: bool = False, progress: bool = False, workers: int = 0) -> dict:
     """Quantize-then-compensate every expert of `cfg` (Section 3.1 step 2, uniform rank).
 
     Returns {"wg", "bias", "experts": [ {mat: artefacts} ... routed then shared ]}.
-    Shared experts use cfg.shared_bits and carry no factors.
+    Shared experts use cfg.shared_bits and carry no factors.  `workers` > 1 compresses the
+    projections in that many processes (each one is independent and seeded on its own).
     """
     wg, bias = synth.make_gate(cfg)
-    experts = []
+    n_all = cfg.n_experts + cfg.n_shared
+    jobs = [(cfg, e, mat, method, keep_weights, keep_fp64_factors)
+            for e in range(n_all) for mat in (synth.MAT_W1, synth.MAT_W3, synth.MAT_W2)]
+    experts = [dict() for _ in range(n_all)]
     t0 = time.time()
-    for e in range(cfg.n_experts + cfg.n_shared):
-        shared = e >= cfg.n_experts
-        ex = {}
-        for mat in (synth.MAT_W1, synth.MAT_W3, synth.MAT_W2):
-            W = synth.make_expert_weight(cfg, e, mat)
-            art = compress.compress_matrix(W, synth.expert_bits(cfg, e), cfg.group,
-                                           0 if shared else cfg.rank, method=method,
-                                           seed=cfg.seed + 31 * e + mat,
-                                           keep_fp64_factors=keep_fp64_factors)
-            if keep_weights:
-                art["W"] = W
-            ex[mat] = art
-        experts.append(ex)
-        if progress:
-            print(f"[fixture {cfg.name}] expert {e + 1}/{cfg.n_experts + cfg.n_shared} "
-                  f"compressed ({time.time() - t0:.0f}s)", flush=True, file=sys.stderr)
+    done = 0
+
+    def note():
+        if progress and (done % max(1, len(jobs) // 8) == 0 or done == len(jobs)):
+            print(f"[fixture {cfg.name}] {done}/{len(jobs)} projections compressed "
+                  f"({time.time() - t0:.0f}s)", flush=True, file=sys.stderr)
+
+    if workers > 1:
+        import multiprocessing as mp
+        with mp.get_context("fork").Pool(workers) as pool:
+            for e, mat, art in pool.imap_unordered(_compress_one_single_thread, jobs):
+                experts[e][mat] = art
+                done += 1
+                note()
+    else:
+        for job in jobs:
+            e, mat, art = _compress_one(job)
+            experts[e][mat] = art
+            done += 1
+            note()
     return {"wg": wg, "bias": bias, "experts": experts}
+
+
+def default_workers() -> int:
+    """Process count for full-size fixtures: the host's cores, at most 16."""
+    import os
+    return max(1, min(16, os.cpu_count() or 1))
 
 
 def sample_layer(cfg: LayerConfig) -> dict:

@@ -1,0 +1,140 @@
+"""GPU parity at the full sizes of the benchmark configurations (Mixtral-, DeepSeek-MoE- and
+Qwen3-MoE-shaped layers), in the launch configuration bench.py times.
+
+Routing, counts and permutation are compared for every token (bit-exact).  The expert FFN is
+O(T * 3HF) in fp64 on the CPU, so the layer output is compared on a deterministic token subset that
+touches every active expert in both flag classes (compensated / not), as a relative Frobenius
+error over that subset (bar: 5e-3).  Unpacked codes are compared for a sample of projections.
+Fixtures are the real recipe (N(0,0.02) weights with outliers, group-wise quantizer, residual
+factors); at these sizes the factors come from the randomized truncated SVD of the oracle's
+compressor, which the forward pass does not care about (it is checked on whatever is stored).
+"""
+import sys
+import time
+
+import numpy as np
+import pytest
+
+from oracle import compress, fixtures
+from oracle import moe_lrc_oracle as orc
+from workload import configs, synth
+
+pytestmark = pytest.mark.gpu
+TOL = 5e-3
+
+
+def _say(msg):
+    print(f"[full-size] {msg}", flush=True, file=sys.stderr)
+
+
+@pytest.fixture(scope="module")
+def amd():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2512_17073_amd as amd
+    amd.lib()
+    return amd
+
+
+def _to_np(t):
+    import torch
+    if t.dtype == torch.bfloat16:
+        return t.float().cpu().numpy().astype(np.float64)
+    return t.cpu().numpy()
+
+
+def _make(amd, cfg, max_tokens):
+    t0 = time.time()
+    layer = fixtures.build_layer(cfg, method="randomized", progress=True, workers=fixtures.default_workers())
+    _say(f"{cfg.name}: fixture built in {time.time() - t0:.0f}s")
+    L = amd.Layer.from_config(cfg, max_tokens=max_tokens)
+    L.load(layer)
+    _say(f"{cfg.name}: uploaded ({time.time() - t0:.0f}s)")
+    return layer, L
+
+
+def _with_rank(layer, rank):
+    """The same layer with its factors truncated to the leading `rank` components."""
+    ex = [{m: dict(a, A=None if a["A"] is None else np.ascontiguousarray(a["A"][:, :rank]),
+                   B=None if a["B"] is None else np.ascontiguousarray(a["B"][:rank])) for m, a in e.items()}
+          for e in layer["experts"]]
+    return {"wg": layer["wg"], "bias": layer["bias"], "experts": ex}
+
+
+def _check(amd, cfg, layer, L, sample_mats=((0, 0), (1, 2))):
+    import torch
+    T = cfg.tokens
+    x_bits = synth.make_tokens(cfg)
+    x = amd.bf16_tensor(x_bits)
+    _say(f"{cfg.name}: T={T} routing + permutation")
+    r = orc.route(x_bits, layer["wg"], cfg.top_k, cfg.renormalize, layer["bias"])
+    assert (r["margin"] > 1e-9).all(), "near-tie in the fixture"
+    idx, w = L.route(x)
+    np.testing.assert_array_equal(_to_np(idx), r["idx"])
+    np.testing.assert_allclose(_to_np(w), r["w"], rtol=2e-6, atol=1e-30)
+    p = orc.permute(r["idx"], cfg.n_experts, cfg.top_n)
+    counts, offsets, row_pair, pair_row, comp = L.permute(idx)
+    for got, key in ((counts, "counts"), (offsets, "offsets"), (row_pair, "row_pair"), (pair_row, "pair_row"),
+                     (comp, "comp_counts")):
+        np.testing.assert_array_equal(_to_np(got), p[key], err_msg=key)
+    for e, mat in sample_mats:
+        np.testing.assert_array_equal(_to_np(L.debug_unpack(e, mat)), layer["experts"][e][mat]["codes"])
+    mask = fixtures.covering_token_mask(cfg, r["idx"], min_tokens=min(T, 24))
+    _say(f"{cfg.name}: T={T} oracle FFN on {int(mask.sum())} tokens")
+    t0 = time.time()
+    ref = fixtures.oracle_forward(cfg, layer, x_bits, token_mask=mask)
+    _say(f"{cfg.name}: oracle done in {time.time() - t0:.0f}s; GPU forward")
+    out = L.forward(x)
+    out2 = L.forward(x)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), out2.view(torch.int16)), "two runs differ"
+    got = _to_np(out)
+    assert np.isfinite(got).all()
+    err = orc.rel_frobenius(got, ref["out"])
+    _say(f"{cfg.name}: T={T} output rel. Frobenius error {err:.2e} on {int(mask.sum())} tokens")
+    assert err <= TOL
+    st = L.stats()
+    want = compress.staged_bytes(p["counts"], p["comp_counts"], cfg.hidden, cfg.ffn, cfg.bits, cfg.group, cfg.rank)
+    P = 3 * cfg.hidden * cfg.ffn
+    assert st["active_experts"] == want["active_experts"] and st["comp_experts"] == want["comp_experts"]
+    assert st["bytes_codes"] == want["bytes_codes"] + cfg.n_shared * P * cfg.shared_bits // 8
+    assert st["bytes_factors"] == want["bytes_factors"]
+
+
+def test_mixtral_decode_2bit(amd):
+    base = configs.get("mixtral_decode_T64_b2")
+    layer, L = _make(amd, base, max_tokens=64)
+    for T in (1, 8, 32, 64):
+        _check(amd, base.with_(tokens=T, name=f"mixtral_decode_T{T}_b2"), layer, L)
+    L.close()
+
+
+def test_mixtral_3bit_decode_and_prefill(amd):
+    # one 3-bit fixture with rank-64 factors serves the prefill case and, truncated to its leading
+    # 32 components (a truncated SVD is nested), the 3-bit decode cases
+    pre = configs.MIXTRAL_PREFILL
+    layer64, L64 = _make(amd, pre, max_tokens=2048)
+    _check(amd, pre, layer64, L64)
+    L64.close()
+    dec = configs.get("mixtral_decode_T64_b3").with_(seed=pre.seed, gate_kind=pre.gate_kind, gate_std=pre.gate_std)
+    layer32 = _with_rank(layer64, 32)
+    L32 = amd.Layer.from_config(dec, max_tokens=64)
+    L32.load(layer32)
+    for T in (1, 64):
+        _check(amd, dec.with_(tokens=T, name=f"mixtral_decode_T{T}_b3"), layer32, L32)
+    L32.close()
+
+
+def test_deepseek_shape(amd):
+    cfg = configs.DEEPSEEK
+    layer, L = _make(amd, cfg, max_tokens=cfg.tokens)
+    _check(amd, cfg, layer, L, sample_mats=((0, 0), (63, 2), (64, 1), (65, 2)))
+    L.close()
+
+
+def test_qwen3_shape(amd):
+    cfg = configs.QWEN3
+    layer, L = _make(amd, cfg, max_tokens=4096)
+    _check(amd, cfg.with_(tokens=64, name="qwen3_T64"), layer, L, sample_mats=((0, 0), (127, 2)))
+    _check(amd, cfg.with_(tokens=4096, name="qwen3_T4096"), layer, L, sample_mats=((5, 1),))
+    L.close()
