@@ -78,6 +78,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true", help="replay one captured HIP graph per layer instance instead of launching eagerly")
     ap.add_argument("--cpu-tokens", type=int, default=64, help="tokens whose expert FFN the CPU oracle evaluates")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="after the timed region run an elementwise kernel that reads and writes 256 MiB, "
+                         "so that a counter run can scale FETCH_SIZE / WRITE_SIZE by a known transfer")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1", file=sys.stderr)
@@ -205,6 +208,13 @@ def main():
                        "mfma_frac": round(flops / (ms_per_step * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4),
                        "stage_ms": {k: round(v, 5) for k, v in stage_avg.items()}},
     }
+    if args.calib_copy:
+        src = torch.zeros(64 << 20, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)        # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_cpu_baseline:
         print("[bench] timing the CPU oracle on a bounded sample", file=sys.stderr, flush=True)
         result["cpu_baseline"] = cpu_baseline(cfg, layer, x_bits, args.cpu_tokens)
