@@ -25,6 +25,12 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16/bf16 MFMA, published
 
+# HBM bytes per launch of the dominant kernel from hardware counters (FETCH_SIZE + WRITE_SIZE, each
+# scaled by what the same counter reads for an elementwise kernel of known size; two separate
+# profiler runs of this script, summarised in profiles/).  Counters cannot be read from inside a
+# timed run, so the figure is carried here per workload; workloads not profiled report null.
+MEASURED_TRAFFIC_BYTES = {"mixtral_decode_T64_b2": 343.8e6}
+
 
 def algorithmic_bytes(cfg, T, active, comp):
     """Bytes each kernel must move per launch: packed codes + fp16 scale/zero of active experts,
@@ -184,9 +190,9 @@ def main():
     flops = algorithmic_flops(cfg, T)
     dom = "w13"
     achieved = ab[dom] / (stage_avg[dom] * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "qgemm_kernel<bits,dual> (packed W1|W3 + SwiGLU)",
+    roofline = {"bound": "hbm", "kernel": "packed W1|W3 product + SwiGLU (qgemm_decode_kernel<bits,true> at decode sizes)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
                 "bytes_per_launch": int(ab[dom]), "avg_ms": round(stage_avg[dom], 5)}
     path_kernel_ms = sum(stage_avg.values())
     result = {
