@@ -237,8 +237,10 @@ __device__ inline void ffn_pass(const KArgs& a, const ExpertDesc& d, uint4* xs, 
           }
           const half4_t pf = half4_t{(_Float16)(pv[0] * lam), (_Float16)(pv[1] * lam),
                                      (_Float16)(pv[2] * lam), (_Float16)(pv[3] * lam)};
+          // B factor: [N/16][ceil(rank/32)][lane][8], 32 rank indices per unit row; this step's 16
+          const int ls = (a.rank + 31) / 32;
           const half4_t bfr = *reinterpret_cast<const half4_t*>(
-              d.bf[mat] + ((size_t(nt) * rs + st) * kWave + lane) * 4);
+              d.bf[mat] + ((size_t(nt) * ls + (st >> 1)) * kWave + (2 * (st & 1) + (q >> 1)) * 16 + c) * 8 + 4 * (q & 1));
           acc[mt][m] = __builtin_amdgcn_mfma_f32_16x16x16f16(bfr, pf, acc[mt][m], 0, 0, 0);
         }
       }

@@ -15,6 +15,7 @@
 //     r/16 more MFMA steps on the pre-computed (x A): xa_split_kernel leaves K-block partial sums,
 //     which a block adds in a fixed order into LDS when it starts.
 #include <algorithm>
+#include <type_traits>
 
 #include "ffn_common.h"
 
@@ -27,20 +28,24 @@ using namespace ffn;
 constexpr int kDecodeWaves = 16;
 constexpr int kDecodeLdsUnits = 8192;     // 128 KB in 16-byte units
 constexpr int kTPW = 2;                   // n-tiles per wavefront (at most)
-constexpr int kDMT = 2;                   // row tiles per pass
 // packed tiles a wavefront holds in registers (one being unpacked, the others in flight), chosen
-// per kernel so that it stays within 128 registers at 16 wavefronts per CU
-#ifndef LRC_DRING_DUAL2
-#define LRC_DRING_DUAL2 2
+// per kernel so that it stays within 128 registers at 16 wavefronts per CU.  Blocks with more in
+// flight take a larger share of a saturated memory system, so the depths are the same for one
+// and two row tiles per pass (measured: deeper rings for one row tile slow the whole kernel down)
+#ifndef LRC_RING_D1
+#define LRC_RING_D1(bits) 2
 #endif
-#ifndef LRC_DRING_DUALW
-#define LRC_DRING_DUALW 2
+#ifndef LRC_RING_D2
+#define LRC_RING_D2(bits) 2
 #endif
-#ifndef LRC_DRING_SINGLE
-#define LRC_DRING_SINGLE 4
+#ifndef LRC_RING_S1
+#define LRC_RING_S1(bits) 4
 #endif
-__host__ __device__ constexpr int decode_ring(int bits, bool dual) {
-  return dual ? (bits == 2 ? LRC_DRING_DUAL2 : LRC_DRING_DUALW) : LRC_DRING_SINGLE;
+#ifndef LRC_RING_S2
+#define LRC_RING_S2(bits) 4
+#endif
+__host__ __device__ constexpr int decode_ring(int bits, bool dual, int mt) {
+  return dual ? (mt == 1 ? LRC_RING_D1(bits) : LRC_RING_D2(bits)) : (mt == 1 ? LRC_RING_S1(bits) : LRC_RING_S2(bits));
 }
 
 #ifdef LRC_TIMELINE
@@ -55,17 +60,37 @@ __device__ long long g_timeline[2][4096][16];
 #define LRC_STAMP(slot) do {} while (0)
 #endif
 
-template <int BITS, bool DUAL>
-__global__ __launch_bounds__(64 * kDecodeWaves, 4) void qgemm_decode_kernel(KArgs a) {
-  extern __shared__ uint4 xs[];
+// One expert's share of a block: MT = row tiles per pass (1 when the expert has at most 16 rows: fewer
+// accumulators, so a deeper ring of packed tiles in flight).
+#ifndef LRC_BODY_INLINE
+#define LRC_BODY_INLINE __forceinline__
+#endif
+// LDS read of one 16-byte unit per lane whose result is awaited by lds_wait, not by the compiler.
+template <int OFF> __device__ inline half8_t lds_read16(uint32_t addr) {
+  half8_t v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+  return v;
+}
+// Waits until at most N LDS operations issued after the wanted ones are outstanding (LDS returns in
+// order), and ties the wanted registers to the wait so that their uses stay behind it.
+template <int N> __device__ inline void lds_wait(half8_t& a) { asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a) : "n"(N)); }
+template <int N> __device__ inline void lds_wait(half8_t& a, half8_t& b) {
+  asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
+}
+
+template <class T> __device__ inline const T* uniform_ptr(const T* p) {
+  const uint64_t v = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane(uint32_t(v)), hi = __builtin_amdgcn_readfirstlane(uint32_t(v >> 32));
+  return reinterpret_cast<const T*>((uint64_t(hi) << 32) | lo);
+}
+
+template <int BITS, bool DUAL, int MT>
+__device__ LRC_BODY_INLINE void decode_body(const KArgs& a, uint4* xs, const int e, const int r0, const int cnt) {
   constexpr int NM = DUAL ? 2 : 1;
   constexpr int DW = 2 * BITS;
   constexpr int NC = Extract<BITS>::kClasses;
-  constexpr int RING = decode_ring(BITS, DUAL);
-  const int e = blockIdx.y;
-  const int r0 = a.offsets ? a.offsets[e] : e * a.T;
-  const int cnt = a.offsets ? a.offsets[e + 1] - r0 : a.T;
-  if (cnt == 0) return;
+  constexpr int RING = decode_ring(BITS, DUAL, MT);
+  constexpr int kDMT = MT;
   const ExpertDesc& d = a.desc[e];
   const int th = threadIdx.x, lane = th & 63;
   const int wave = __builtin_amdgcn_readfirstlane(th >> 6);
@@ -90,33 +115,66 @@ __global__ __launch_bounds__(64 * kDecodeWaves, 4) void qgemm_decode_kernel(KArg
 #pragma unroll
   for (int m = 0; m < NM; ++m) {
     const int mat = DUAL ? m : 2;
-    code_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(d.codes[mat]), 0, code_bytes, 0x00020000);
-    meta_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(d.meta[mat]), 0, meta_bytes, 0x00020000);
+    // (the pointers are read once, into scalar registers: a buffer resource must be wave-uniform)
+    code_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(uniform_ptr(d.codes[mat])), 0, code_bytes, 0x00020000);
+    meta_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(uniform_ptr(d.meta[mat])), 0, meta_bytes, 0x00020000);
   }
+  // The rank-r term rides the same stream: the B factor of an n-tile is LS more steps of 32 rank
+  // indices, whose 16-byte units (fp16, MFMA operand order) take the place of the packed codes in a
+  // ring slot and go into the MFMA as they are, against (in A) instead of the activations.  A
+  // resource of size zero (no factors, or not this K-block's job) makes those steps read zeros.
+  const bool has_factors = __builtin_amdgcn_readfirstlane(d.has_factors) != 0;
+#ifdef LRC_EXP_NOLOWRANK
+  const bool lowrank = false;
+#else
+  const bool lowrank = a.rank > 0 && has_factors && a.row_pair != nullptr && blockIdx.z == 0;
+#endif
+  const int LS = lowrank ? a.ls : 0;
+  float lam[NM];
+#pragma unroll
+  for (int m = 0; m < NM; ++m) lam[m] = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(d.lambda[DUAL ? m : 2])));
+  __amdgpu_buffer_rsrc_t bf_rs[NM];
+#pragma unroll
+  for (int m = 0; m < NM; ++m)
+    bf_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<_Float16*>(uniform_ptr(d.bf[DUAL ? m : 2])), 0,
+                                                 lowrank ? a.NT * a.ls * 1024 : 0, 0x00020000);
+  const int bf_bytes = a.NT * a.ls * 1024;
   const int gps = kTileK >> a.group_shift;           // groups per k-step
   const int meta_lane = ((q * kLaneK) >> a.group_shift) * (a.NT * kTileN * 4) + c * 4;
+  const int PW = DUAL ? 2 * a.rpad : a.rpad;
+  uint4* p_lds = xs + kDecodeLdsUnits;               // (in A) fragments: [m][rank step][row tile][lane]
 
   for (int r = 0; r < cnt; r += 16 * kDMT) {
-    const int mt_n = min(kDMT, (cnt - r + 15) >> 4);
-    const int KP = (kDecodeLdsUnits / 512) / mt_n;   // k-steps per phase: 16 or 8
+    // every pass computes all MT row tiles (a last pass with fewer rows computes columns nobody stores)
+    constexpr int KP = (kDecodeLdsUnits / 512) / kDMT;   // k-steps per phase: 16 or 8
     const int n_ph = (KSl + KP - 1) / KP;
-    const int spw = (KP + kw - 1) / kw;              // own steps per (tile, phase) segment
-    const int SP = (spw + RING - 1) / RING * RING;   // padded to the ring depth: slot indices stay static
-    const int n_total = n_ph * kTPW * SP;
+    // A wavefront's steps, in order: [phase][tile slot][own k-step], then [own rank step][tile slot].
+    // Each segment is padded to a multiple of the ring depth, so that slot indices stay static.
+    const int spw = (KP + kw - 1) / kw;                  // own k-steps per (tile, phase) segment
+    const int SP = (spw + RING - 1) / RING * RING;
+    const int n_reg = n_ph * kTPW * SP;
+    static_assert(RING % kTPW == 0, "the rank steps alternate between the tile slots: even ring depths only");
+    const int LSP = (kTPW * ((LS + kw - 1) / kw) + RING - 1) / RING * RING;
 
-    // flat step n -> (phase, tile slot, own step); a step that does not exist loads from past the
-    // end of the resources and gets zeros
+    // step n -> (phase, tile slot, own step); a step that does not exist loads from past the end of
+    // the resources and gets zeros
     auto fetch = [&](int n, Slot<BITS, NM>& sl) {
-      const int seg = n / SP, si = n - seg * SP, ph = seg / kTPW, ts = seg - ph * kTPW;
-      const int kl = si * kw + kwi, ksl = ph * KP + kl, ks = ks_lo + ksl, tile = t0 + grp + ts * groups;
-      const bool ok = n < n_total && kl < KP && ksl < KSl && tile < t1;
+      const bool reg = n < n_reg;
+      const int l = n - n_reg;                                           // index among the rank steps
+      const int seg = n / SP, si = n - seg * SP, ph = seg / kTPW;
+      const int ts = reg ? seg - ph * kTPW : l % kTPW;
+      const int kl = si * kw + kwi, tile = t0 + grp + ts * groups;
+      const int st = (l / kTPW) * kw + kwi;                              // rank step
+      const bool ok = reg && tile < t1 && kl < KP && ph * KP + kl < KSl;     // a k-step of packed codes
+      const bool lr = !reg && l < LSP && tile < t1 && st < LS;               // a rank step of the B factor
+      const int ks = ks_lo + ph * KP + kl;
       // the offsets go into the per-lane offset operand: that is the one the hardware range-checks
-      const int tile_off = (ok ? (ks * a.NT + tile) * (tdw * 4) : code_bytes) + lane * 16;
+      const int tile_off = (ok ? (ks * a.NT + tile) * (tdw * 4) : lr ? (tile * a.ls + st) * 1024 : max(code_bytes, bf_bytes)) + lane * 16;
       const int tile_off2 = (ok ? (ks * a.NT + tile) * (tdw * 4) : code_bytes) + 1024 + lane * (BITS == 3 ? 8 : 16);
       const int meta_off = (ok ? (ks * gps * a.NT + tile) * (kTileN * 4) : meta_bytes) + meta_lane;
 #pragma unroll
       for (int m = 0; m < NM; ++m) {
-        const u32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(code_rs[m], tile_off, 0, 0);
+        const u32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(lr ? bf_rs[m] : code_rs[m], tile_off, 0, 0);
         sl.cw[m][0] = v0[0]; sl.cw[m][1] = v0[1]; sl.cw[m][2] = v0[2]; sl.cw[m][3] = v0[3];
         if constexpr (BITS == 3) {
           const u32x2 v1 = __builtin_amdgcn_raw_buffer_load_b64(code_rs[m], tile_off2, 0, 0);
@@ -129,77 +187,85 @@ __global__ __launch_bounds__(64 * kDecodeWaves, 4) void qgemm_decode_kernel(KArg
       }
     };
 
-    // first input row of this pass (shared experts all read the token rows 0..T-1), and whether
-    // this lane's token column (th%16 of each row tile) takes the rank-r term
+    // first input row of this pass (shared experts all read the token rows 0..T-1)
     const int rin = ((DUAL && !a.offsets) ? 0 : r0) + r;
-    bool flag[kDMT];
-    const bool lowrank = a.rank > 0 && d.has_factors && a.row_pair != nullptr && kb == 0;
-#pragma unroll
-    for (int mt = 0; mt < kDMT; ++mt) {
-      const int row = r + 16 * mt + rowl;
-      flag[mt] = false;
-      if (lowrank && mt < mt_n && row < cnt) flag[mt] = (a.row_pair[r0 + row] % a.top_k) < a.top_n;
-    }
-    // (in A) of this pass's rows: the K-block partial sums of xa_split_kernel are added here, in
-    // K-block order, and kept in LDS as fp16 behind the activations (zero for rows without the term)
-    const int PW = DUAL ? 2 * a.rpad : a.rpad;
-    _Float16* p_lds = reinterpret_cast<_Float16*>(xs + kDecodeLdsUnits);
-    auto load_p = [&]() {
-      for (int e2 = th; e2 < 16 * PW; e2 += 64 * kDecodeWaves) {      // pairs of adjacent columns
-        const int row = (2 * e2) / PW, col = (2 * e2) - row * PW;
-        float sx = 0.f, sy = 0.f;
-        if (r + row < cnt && (a.row_pair[r0 + r + row] % a.top_k) < a.top_n) {
-          const float* pp = a.p + size_t(r0 + r + row) * PW + col;
-          for (int kb2 = 0; kb2 < a.ksplit; ++kb2) {
-            const float2 v = *reinterpret_cast<const float2*>(pp + size_t(kb2) * a.total_rows * PW);
-            sx += v.x; sy += v.y;
-          }
-        }
-        *reinterpret_cast<half2_t*>(p_lds + 2 * e2) = half2_t{(_Float16)sx, (_Float16)sy};
-      }
-    };
-    // The B-factor tiles of this wavefront's n-tiles are needed only after the last k-step, by loads
-    // that would then miss every cache: touch their lines now (one dword per 64 bytes, one lane per
-    // line) so that they wait in L2.  The value is only kept alive, never used.
-    uint32_t touch = 0;
-    if (lowrank && kwi == 0) {
-      const int rs_ = a.rpad / 16, lines = rs_ * 8;           // 64-byte lines per (tile, projection)
-      const int per = (64 / (kTPW * NM));                     // lanes available per (tile, projection)
-      const int ts = lane / (per * NM), m = (lane / per) % NM, line = lane % per;
-      const int tile = t0 + grp + ts * groups;
-      if (tile < t1 && line < lines)
-        touch = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(d.bf[DUAL ? m : 2]) +
-                                                   size_t(tile) * rs_ * 512 + line * 64);
-    }
-    // A phase is mt_n * nk * 8 fragments of 64 units (16 rows x 4 column groups of one MFMA sub-step);
-    // wavefront w copies fragments w, w + 16, ...: four 256-byte runs of the operand-order buffer
-    // into 1 KB of LDS, lane-linear.  Rows past the expert's last one read whatever follows (other
-    // rows or the padding): their output columns are never stored.  Columns past K read as zero.
+
+    // A phase is MT * nk * 8 fragments of 64 units (16 rows x 4 column groups of one MFMA sub-step);
+    // four 256-byte runs of the operand-order buffer become 1 KB of LDS, lane-linear.  Rows past the
+    // expert's last one read whatever follows (other rows or the padding): their output columns are
+    // never stored.  The copy is asynchronous and takes no registers:
+    // each lane's 16 bytes go from global memory straight to LDS (wave-uniform LDS base + 16 * lane),
+    // counted by vmcnt like any other load.
     const uint4* in_units = reinterpret_cast<const uint4*>(a.in);
-    auto stage = [&](int ph, int nk) {
-      const int nfrag = mt_n * nk * 8;
-      uint4 reg[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int fb = wave + i * kDecodeWaves;
-        reg[i] = make_uint4(0, 0, 0, 0);
-        if (fb < nfrag) {
-          const int s = fb & 7, mk = fb >> 3, mt = mk / nk, kl = mk - mt * nk;
-          const int k8 = (ks_lo + ph * KP + kl) * 32 + q * 8 + s;
-          if (k8 * 8 < a.K) reg[i] = in_units[act_unit(k8, rin + 16 * mt + rowl, a.in_rt)];
+    auto stage_issue = [&](int ph, int nk) {
+      const int s = wave & 7;                  // fragment (mt, kl, s): wavefront w takes s = w % 8, kl = w / 8, w / 8 + 2, ...
+      for (int mt = 0; mt < kDMT; ++mt)
+        for (int kl = wave >> 3; kl < nk; kl += 2) {
+          // (columns past K: the padded weights there are exact zeros, any finite value will do)
+          const int k8 = min((ks_lo + ph * KP + kl) * 32 + q * 8 + s, a.K / 8 - 1);
+          uint4* dst = xs + ((mt * KP + kl) * 8 + s) * 64;
+          __builtin_amdgcn_global_load_lds(
+              reinterpret_cast<const __attribute__((address_space(1))) void*>(
+                  reinterpret_cast<uintptr_t>(in_units + act_unit(k8, rin + 16 * mt + rowl, a.in_rt))),
+              reinterpret_cast<__attribute__((address_space(3))) void*>(reinterpret_cast<uintptr_t>(dst)), 16, 0, 0);
         }
-      }
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int fb = wave + i * kDecodeWaves;
-        if (fb < nfrag) {
-          const int s = fb & 7, mk = fb >> 3, mt = mk / nk, kl = mk - mt * nk;
-          xs[((mt * KP + kl) * 8 + s) * 64 + lane] = reg[i];
-        }
-      }
     };
 
+    // ---- start of a pass.  The K-block partial sums of (in A) are read and added first (a few KB,
+    //      one round trip); then the activations of phase 0 (straight to LDS) and the first packed
+    //      tiles are issued, and only the packed tiles are still in flight when the first barrier is
+    //      passed.
     LRC_STAMP(11);
+    if (r > 0) __syncthreads();               // everyone is done with the previous pass's LDS
+    // (in A) of this pass's rows, times the projection's power-of-two pre-scale, as fp16 in MFMA
+    // operand order: unit ((m * LS + st) * MT + mt) * 64 + lane holds columns 32 st + 8 q .. + 7 of
+    // row 16 mt + lane % 16 (zero for rows without the term and past the rank).  The partial sums of
+    // xa_split_kernel are added in K-block order.  They are read whether or not the row takes the
+    // term (a row inside the expert's range is always inside the buffer) and selected afterwards,
+    // so that the loads do not wait for the flag.
+    const int p_pairs = NM * LS * kDMT * 64 * 4;     // pairs of adjacent columns
+    auto p_load = [&](int e2, int& rp, float2 (&v)[4], int kb0) {
+      const int u = e2 >> 2, ln = u & 63, g = u >> 6, mt = g % kDMT, st = (g / kDMT) % max(LS, 1), m = g / (kDMT * max(LS, 1));
+      const int rho = 32 * st + 8 * (ln >> 4) + 2 * (e2 & 3);
+      const int rr = r0 + min(r + 16 * mt + (ln & 15), cnt - 1);
+      rp = a.row_pair[rr];
+      const float* pp = a.p + size_t(rr) * PW + m * a.rpad + min(rho, a.rpad - 2);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        v[j] = make_float2(0.f, 0.f);
+        if (kb0 + j < a.ksplit) v[j] = *reinterpret_cast<const float2*>(pp + size_t(kb0 + j) * a.total_rows * PW);
+      }
+    };
+    auto p_store = [&](int e2, int rp, float sx, float sy) {
+      const int u = e2 >> 2, ln = u & 63, g = u >> 6, mt = g % kDMT, st = (g / kDMT) % max(LS, 1), m = g / (kDMT * max(LS, 1));
+      const int rho = 32 * st + 8 * (ln >> 4) + 2 * (e2 & 3);
+      const bool on = r + 16 * mt + (ln & 15) < cnt && (rp % a.top_k) < a.top_n && rho < a.rpad;
+      const float lm = NM == 2 && m == 1 ? lam[NM - 1] : lam[0];
+      reinterpret_cast<half2_t*>(p_lds)[e2] = on ? half2_t{(_Float16)(sx * lm), (_Float16)(sy * lm)} : half2_t{0, 0};
+    };
+    for (int e2 = th; e2 < p_pairs; e2 += 64 * kDecodeWaves) {
+      float sx = 0.f, sy = 0.f;
+      int rp = 0;
+      for (int kb0 = 0; kb0 < a.ksplit; kb0 += 4) {       // four K-blocks' loads in flight, added in order
+        float2 v[4];
+        p_load(e2, rp, v, kb0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { sx += v[j].x; sy += v[j].y; }
+      }
+      p_store(e2, rp, sx, sy);
+    }
+    const int nk0 = min(KP, KSl);
+    stage_issue(0, nk0);                      // (no registers)
+    Slot<BITS, NM> ring[RING];
+#pragma unroll
+    for (int i = 0; i < RING; ++i) fetch(i, ring[i]);
+    LRC_STAMP(12);
+    // everything but the packed tiles issued last has arrived: the activations are in LDS
+    // The barrier is written out: a __syncthreads() here would first wait for every load in flight,
+    // the packed tiles included.  LDS writes of this wavefront are awaited by lgkmcnt(0).
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(RING * NM * (BITS == 2 ? 2 : 3)) : "memory");
+    LRC_STAMP(2);
+
     float4_t acc[kTPW][kDMT][NM];
 #pragma unroll
     for (int ts = 0; ts < kTPW; ++ts)
@@ -208,7 +274,34 @@ __global__ __launch_bounds__(64 * kDecodeWaves, 4) void qgemm_decode_kernel(KArg
 #pragma unroll
         for (int m = 0; m < NM; ++m) acc[ts][mt][m] = float4_t{0.f, 0.f, 0.f, 0.f};
 
+    // a rank step of one n-tile: the slot holds B-factor units, which meet (in A) as they are
+    auto compute_lr = [&](const Slot<BITS, NM>& cur, int st, float4_t (&ac)[kDMT][NM]) {
+      const uint4* pk = p_lds + size_t(st) * kDMT * 64 + lane;
+#pragma unroll
+      for (int m = 0; m < NM; ++m) {
+        const half8_t bfrag = __builtin_bit_cast(half8_t, make_uint4(cur.cw[m][0], cur.cw[m][1], cur.cw[m][2], cur.cw[m][3]));
+#pragma unroll
+        for (int mt = 0; mt < kDMT; ++mt) {
+          const half8_t pf = __builtin_bit_cast(half8_t, pk[(size_t(m) * LS * kDMT + mt) * 64]);
+          ac[mt][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(bfrag, pf, ac[mt][m], 0, 0, 0);
+        }
+      }
+    };
+    // a k-step of packed codes of one n-tile
     auto compute = [&](const Slot<BITS, NM>& cur, int kl, float4_t (&ac)[kDMT][NM]) {
+#ifdef LRC_EXP_NOCOMPUTE
+      {
+        uint32_t t = 0;
+#pragma unroll
+        for (int m = 0; m < NM; ++m) {
+          t ^= cur.mw[m];
+#pragma unroll
+          for (int j = 0; j < DW; ++j) t ^= cur.cw[m][j];
+        }
+        ac[0][0][0] += __uint_as_float(t & 0x3f800000u);
+        return;
+      }
+#endif
       const uint4* xk = xs + size_t(kl) * 8 * 64 + lane;
       uint32_t s2[NM][NC], c2[NM];
 #pragma unroll
@@ -219,41 +312,75 @@ __global__ __launch_bounds__(64 * kDecodeWaves, 4) void qgemm_decode_kernel(KArg
 #pragma unroll
         for (int p = 1; p < NC; ++p) s2[m][p] = pk_mul(s2[m][p - 1], step);
       }
+      // One sub-step: 32 rows of the weight tile are unpacked into the MFMA operand while the
+      // activation fragments wait in registers.  Where the registers allow (XB == 2) the fragments of
+      // sub-step s + 1 are requested from LDS before sub-step s is unpacked; the reads and the waits
+      // are written out, because the compiler would move each read down to its use.
+      constexpr int XB = (kDMT == 1 || BITS == 2) ? 2 : 1;
+      half8_t xf[XB][kDMT];
+      uint32_t xaddr[kDMT];
 #pragma unroll
-      for (int s = 0; s < 8; ++s) {
+      for (int mt = 0; mt < kDMT; ++mt) xaddr[mt] = uint32_t(reinterpret_cast<uintptr_t>(xk)) + mt * KP * 8 * 1024;
+      if constexpr (XB == 2) {
+#pragma unroll
+        for (int mt = 0; mt < kDMT; ++mt) xf[0][mt] = lds_read16<0>(xaddr[mt]);
+      }
+      auto substep = [&](auto S) {
+        constexpr int s = decltype(S)::value;
+        if constexpr (XB == 2) {
+          if constexpr (s < 7) {
+#pragma unroll
+            for (int mt = 0; mt < kDMT; ++mt) xf[(s + 1) & 1][mt] = lds_read16<(s + 1) * 1024>(xaddr[mt]);
+          }
+        } else {
+#pragma unroll
+          for (int mt = 0; mt < kDMT; ++mt) xf[0][mt] = __builtin_bit_cast(half8_t, xk[(size_t(mt) * KP * 8 + s) * 64]);
+        }
         half8_t wf[NM];
 #pragma unroll
         for (int m = 0; m < NM; ++m) {
           uint32_t v[4];
+#ifdef LRC_EXP_NOVALU
+#pragma unroll
+          for (int j = 0; j < 4; ++j) v[j] = cur.cw[m][(4 * s + j) % DW] ^ c2[m];
+          if (false)
+#endif
 #pragma unroll
           for (int j = 0; j < 4; ++j)
             v[j] = pk_fma(Extract<BITS>::field(cur.cw[m], 4 * s + j), s2[m][Extract<BITS>::cls(4 * s + j)], c2[m]);
           wf[m] = __builtin_bit_cast(half8_t, make_uint4(v[0], v[1], v[2], v[3]));
         }
+        if constexpr (XB == 2) {
+          // the fragments of this sub-step are older than the kDMT reads just issued
+          if constexpr (kDMT == 1) lds_wait<(s < 7 ? 1 : 0)>(xf[s & 1][0]);
+          else lds_wait<(s < 7 ? 2 : 0)>(xf[s & 1][0], xf[s & 1][kDMT - 1]);
+        }
+#ifdef LRC_EXP_NOMFMA
+#pragma unroll
+        for (int m = 0; m < NM; ++m) { ac[0][m][0] += (float)wf[m][0]; ac[0][m][1] += (float)wf[m][2]; ac[0][m][2] += (float)wf[m][4]; ac[0][m][3] += (float)wf[m][6]; }
+#else
 #pragma unroll
         for (int mt = 0; mt < kDMT; ++mt)
-          if (mt < mt_n) {
-            const half8_t xf = __builtin_bit_cast(half8_t, xk[(size_t(mt) * KP * 8 + s) * 64]);
 #pragma unroll
-            for (int m = 0; m < NM; ++m)
-              ac[mt][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[m], xf, ac[mt][m], 0, 0, 0);
-          }
-      }
+          for (int m = 0; m < NM; ++m)
+            ac[mt][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[m], xf[XB == 2 ? (s & 1) : 0][mt], ac[mt][m], 0, 0, 0);
+#endif
+      };
+      substep(std::integral_constant<int, 0>{}); substep(std::integral_constant<int, 1>{});
+      substep(std::integral_constant<int, 2>{}); substep(std::integral_constant<int, 3>{});
+      substep(std::integral_constant<int, 4>{}); substep(std::integral_constant<int, 5>{});
+      substep(std::integral_constant<int, 6>{}); substep(std::integral_constant<int, 7>{});
     };
 
-    Slot<BITS, NM> ring[RING];
-#pragma unroll
-    for (int i = 0; i < RING; ++i) fetch(i, ring[i]);
-    LRC_STAMP(12);
     int n = 0;
     for (int ph = 0; ph < n_ph; ++ph) {
       const int nk = min(KP, KSl - ph * KP);
-      if (ph > 0 || r > 0) __syncthreads();   // everyone is done with the previous phase
-      if (ph == 0 && lowrank) load_p();
-      if (ph < 5) LRC_STAMP(1 + 2 * ph);
-      stage(ph, nk);
-      __syncthreads();
-      if (ph < 5) LRC_STAMP(2 + 2 * ph);
+      if (ph > 0) {
+        __syncthreads();                      // everyone is done with the previous phase
+        stage_issue(ph, nk);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+      }
 #pragma unroll
       for (int ts = 0; ts < kTPW; ++ts) {
         const bool tile_ok = t0 + grp + ts * groups < t1;
@@ -267,6 +394,15 @@ __global__ __launch_bounds__(64 * kDecodeWaves, 4) void qgemm_decode_kernel(KArg
         }
       }
     }
+    for (int l0 = 0; l0 < LSP; l0 += RING) {   // the rank steps (none unless this block adds the term)
+#pragma unroll
+      for (int i = 0; i < RING; ++i) {
+        const int st = ((l0 + i) / kTPW) * kw + kwi;
+        if (t0 + grp + (i % kTPW) * groups < t1 && st < LS) compute_lr(ring[i], st, acc[i % kTPW]);
+        fetch(n + i + RING, ring[i]);
+      }
+      n += RING;
+    }
 
     LRC_STAMP(13);
     // ---- wavefronts that shared an n-tile add up their partial sums through LDS ----
@@ -276,65 +412,20 @@ __global__ __launch_bounds__(64 * kDecodeWaves, 4) void qgemm_decode_kernel(KArg
       if (kwi != 0) {
 #pragma unroll
         for (int mt = 0; mt < kDMT; ++mt)
-          if (mt < mt_n)
 #pragma unroll
-            for (int m = 0; m < NM; ++m) red[((wave * kDMT + mt) * NM + m) * 64 + lane] = acc[0][mt][m];
+          for (int m = 0; m < NM; ++m) red[((wave * kDMT + mt) * NM + m) * 64 + lane] = acc[0][mt][m];
       }
       __syncthreads();
       if (kwi == 0) {
         for (int j = 1; j < kw; ++j)
 #pragma unroll
           for (int mt = 0; mt < kDMT; ++mt)
-            if (mt < mt_n)
 #pragma unroll
-              for (int m = 0; m < NM; ++m) acc[0][mt][m] += red[(((wave + j) * kDMT + mt) * NM + m) * 64 + lane];
+            for (int m = 0; m < NM; ++m) acc[0][mt][m] += red[(((wave + j) * kDMT + mt) * NM + m) * 64 + lane];
       }
     }
     LRC_STAMP(14);
     if (kwi != 0) continue;                  // (the next pass starts with a barrier every wavefront reaches)
-
-    // ---- rank-r term: r/16 more MFMA steps on (in A), two at a time with every load of the pair
-    //      of steps (B-factor tiles of both n-tiles, (in A) fragments of both row tiles) issued first
-    const int rs = a.rpad / 16;
-    bool any = false;
-#pragma unroll
-    for (int mt = 0; mt < kDMT; ++mt) any = any || __ballot(flag[mt]) != 0ull;
-    if (any) {
-      for (int st0 = 0; st0 < rs; st0 += 2) {
-        half4_t bfr[kTPW][NM][2], pf[kDMT][NM][2];
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-          for (int m = 0; m < NM; ++m) {
-            const int mat = DUAL ? m : 2, st = st0 + j;
-#pragma unroll
-            for (int ts = 0; ts < kTPW; ++ts) {
-              const int tile = t0 + grp + ts * groups;
-              bfr[ts][m][j] = half4_t{0, 0, 0, 0};
-              if (tile < t1 && st < rs)
-                bfr[ts][m][j] = *reinterpret_cast<const half4_t*>(d.bf[mat] + ((size_t(tile) * rs + st) * kWave + lane) * 4);
-            }
-#pragma unroll
-            for (int mt = 0; mt < kDMT; ++mt) {
-              pf[mt][m][j] = half4_t{0, 0, 0, 0};
-              if (flag[mt] && st < rs)
-                pf[mt][m][j] = *reinterpret_cast<const half4_t*>(p_lds + (16 * mt + c) * PW + m * a.rpad + 16 * st + 4 * q);
-            }
-          }
-#pragma unroll
-        for (int m = 0; m < NM; ++m) {
-          const _Float16 lam = (_Float16)d.lambda[DUAL ? m : 2];
-#pragma unroll
-          for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int ts = 0; ts < kTPW; ++ts)
-#pragma unroll
-              for (int mt = 0; mt < kDMT; ++mt)
-                if (mt < mt_n)
-                  acc[ts][mt][m] = __builtin_amdgcn_mfma_f32_16x16x16f16(bfr[ts][m][j], pf[mt][m][j] * lam, acc[ts][mt][m], 0, 0, 0);
-        }
-      }
-    }
 
     // ---- epilogue: lane holds output columns 16*tile + 4*q .. +3 of token column c ----
 #pragma unroll
@@ -344,7 +435,7 @@ __global__ __launch_bounds__(64 * kDecodeWaves, 4) void qgemm_decode_kernel(KArg
 #pragma unroll
       for (int mt = 0; mt < kDMT; ++mt) {
         const int row = r + 16 * mt + c;
-        if (mt >= mt_n || row >= cnt) continue;
+        if (row >= cnt) continue;
         const size_t o = size_t(r0 + row) * a.N + tile * kTileN + 4 * q;
         if constexpr (DUAL) {
           const float i1 = d.inv_lambda[0], i3 = d.inv_lambda[1];
@@ -370,9 +461,23 @@ __global__ __launch_bounds__(64 * kDecodeWaves, 4) void qgemm_decode_kernel(KArg
         }
       }
     }
-    asm volatile("" ::"v"(touch));
     LRC_STAMP(15);
   }
+}
+
+template <int BITS, bool DUAL>
+__global__ __launch_bounds__(64 * kDecodeWaves, 4) void qgemm_decode_kernel(KArgs a) {
+  extern __shared__ uint4 xs[];
+  const int e = blockIdx.y;
+  const int r0 = a.offsets ? a.offsets[e] : e * a.T;
+  const int cnt = a.offsets ? a.offsets[e + 1] - r0 : a.T;
+  if (cnt == 0) return;
+#if defined(LRC_FORCE_MT)
+  decode_body<BITS, DUAL, LRC_FORCE_MT>(a, xs, e, r0, cnt);
+#else
+  if (cnt <= 16) decode_body<BITS, DUAL, 1>(a, xs, e, r0, cnt);
+  else decode_body<BITS, DUAL, 2>(a, xs, e, r0, cnt);
+#endif
 }
 
 // Partial (in A): pk[kb2][row][rho] = sum over K-block kb2 of in[row][k] * A[k][rho] in fp32, for the
@@ -459,7 +564,7 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s) {
   KArgs a{};
   a.desc = f.desc; a.offsets = f.offsets; a.row_pair = f.row_pair;
   a.group_shift = gs; a.top_k = f.top_k; a.top_n = f.top_n; a.T = f.T;
-  a.rank = f.rank; a.rpad = f.rpad; a.total_rows = f.total_rows; a.kw = 1; a.ksplit = 1;
+  a.rank = f.rank; a.rpad = f.rpad; a.ls = (f.rank + 31) / 32; a.total_rows = f.total_rows; a.kw = 1; a.ksplit = 1;
   const bool comp = f.rank > 0 && f.top_n > 0 && f.row_pair != nullptr;
   // experts that can be active at all: at most one per routed pair; the blocks of the active
   // experts alone should cover the 256 CUs, and a block takes at most 32 n-tiles
@@ -469,7 +574,8 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s) {
     g = std::max(g, (NT + 16 * kTPW - 1) / (16 * kTPW));
     return std::min(g, NT);
   };
-  auto lds_bytes = [&](int pw) { return size_t(kDecodeLdsUnits) * 16 + (comp ? size_t(32) * pw * 2 : 0); };
+  // activations + the (in A) fragments: [projections][rank steps][2 row tiles] KB
+  auto lds_bytes = [&](int nm) { return size_t(kDecodeLdsUnits) * 16 + (comp ? size_t(nm) * a.ls * 2 * 1024 : 0); };
   auto xa_blocks = [](int K) { return std::max(1, std::min(8, K / 1024)); };   // K-blocks of the (in A) kernels
 
   // W1 | W3 with the SwiGLU epilogue
@@ -481,7 +587,7 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s) {
   if (f.marks) (void)hipEventRecord(f.marks[0], s);
   a.kb_steps = a.KS; a.partial = nullptr;
   hipLaunchKernelGGL((qgemm_decode_kernel<BITS, true>), dim3(blocks_per_expert(a.NT, 1), f.n_exp, 1),
-                     dim3(64 * kDecodeWaves), lds_bytes(2 * f.rpad), s, a);
+                     dim3(64 * kDecodeWaves), lds_bytes(2), s, a);
   if (f.marks) (void)hipEventRecord(f.marks[1], s);
   // W2
   a.in = f.h; a.out = f.y_rows; a.K = f.F; a.N = f.H; a.NT = f.H / kTileN;
@@ -496,7 +602,7 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s) {
   a.kb_steps = (a.KS + kblocks - 1) / kblocks;
   a.partial = kblocks > 1 ? f.y_part : nullptr;
   hipLaunchKernelGGL((qgemm_decode_kernel<BITS, false>), dim3(blocks_per_expert(a.NT, kblocks), f.n_exp, kblocks),
-                     dim3(64 * kDecodeWaves), lds_bytes(f.rpad), s, a);
+                     dim3(64 * kDecodeWaves), lds_bytes(1), s, a);
   if (kblocks > 1) {
     const size_t units = size_t(f.total_rows) * f.H / 4;
     hipLaunchKernelGGL(reduce_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, s, f.y_part, kblocks,

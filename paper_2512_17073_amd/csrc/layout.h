@@ -82,7 +82,8 @@ LRC_HD int tile_dword_index(int bits, int lane, int d) {
 
 // Shape-derived sizes of one packed projection.
 struct MatLayout {
-  int K, N, Kp, KS, NT, G, bits, group, rpad;
+  int K, N, Kp, KS, NT, G, bits, group, rpad;   // rpad: rank rounded up to 16 (A factor, (in A))
+  int ls;                                        // rank steps of 32 of the B factor: ceil(rank / 32)
   size_t codes_bytes, meta_bytes, af_bytes, bf_bytes;
 };
 
@@ -93,10 +94,11 @@ inline MatLayout make_layout(int K, int N, int bits, int group, int rank) {
   m.K = K; m.N = N; m.bits = bits; m.group = group;
   m.Kp = padded_k(K); m.KS = m.Kp / kTileK; m.NT = N / kTileN; m.G = m.Kp / group;
   m.rpad = (rank + 15) / 16 * 16;
+  m.ls = (rank + 31) / 32;
   m.codes_bytes = align256(size_t(m.NT) * m.KS * tile_dwords(bits) * 4);
   m.meta_bytes = align256(size_t(m.NT) * m.G * kTileN * 4);
   m.af_bytes = align256(size_t(K) * m.rpad * 2);
-  m.bf_bytes = align256(size_t(m.rpad) * N * 2);
+  m.bf_bytes = align256(size_t(m.ls) * 32 * N * 2);
   return m;
 }
 

@@ -141,16 +141,16 @@ void pack_factor_a(const MatLayout& m, int rank, const uint16_t* A_bf16, uint16_
 }
 
 void pack_factor_b(const MatLayout& m, int rank, const uint16_t* B_bf16, uint16_t* out) {
-  // [N/16][rpad/16][lane][4]: lane (c, q) holds B[16*st + 4*q + j][16*nt + c], j = 0..3
-  const int rs = m.rpad / 16;
+  // [N/16][ceil(rank/32)][lane][8]: lane (c, q) holds B[32*st + 8*q + j][16*nt + c], j = 0..7 (zero past
+  // the rank): one 16-byte unit per lane, the A operand of a 16x16x32 MFMA step over 32 rank indices
   std::memset(out, 0, m.bf_bytes);
   for (int nt = 0; nt < m.NT; ++nt)
-    for (int st = 0; st < rs; ++st)
+    for (int st = 0; st < m.ls; ++st)
       for (int lane = 0; lane < kWave; ++lane) {
         const int c = lane & 15, q = lane >> 4;
-        uint16_t* dst = out + ((size_t(nt) * rs + st) * kWave + lane) * 4;
-        for (int j = 0; j < 4; ++j) {
-          const int rho = 16 * st + 4 * q + j;
+        uint16_t* dst = out + ((size_t(nt) * m.ls + st) * kWave + lane) * 8;
+        for (int j = 0; j < 8; ++j) {
+          const int rho = 32 * st + 8 * q + j;
           if (rho < rank)
             dst[j] = float_to_f16_bits(bf16_bits_to_float(B_bf16[size_t(rho) * m.N + nt * kTileN + c]));
         }
