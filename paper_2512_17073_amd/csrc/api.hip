@@ -80,8 +80,10 @@ Workspace plan_workspace(const moe_lrc_layer* L, int T) {
   w.xh = take((P + kActPadRows) * Hp * 2);
   w.xh_sh = take(c.n_shared ? (size_t(T) + kActPadRows) * Hp * 2 : 0);
   w.h = take((P + kActPadRows) * Fp * 2);
-  w.p13 = take(size_t(L->ksplit13) * P * 2 * rpad * 4);
-  w.p2 = take(size_t(L->ksplit2) * P * rpad * 4);
+  // (in A): K-block partial sums in fp32 and, in the many-rows flavour, the fp16 result in front of
+  // them, both with the columns padded to a multiple of 32
+  w.p13 = take(size_t(L->ksplit13 + 1) * P * 2 * (rpad + 16) * 4 + 256);
+  w.p2 = take(size_t(L->ksplit2 + 1) * P * (rpad + 16) * 4 + 256);
   w.y_part = take(size_t(kMaxKBlocks) * std::max<size_t>(P, size_t(c.n_shared) * T) * c.hidden * 4);
   w.sh_h = take(c.n_shared ? (size_t(c.n_shared) * T + kActPadRows) * Fp * 2 : 0);
   w.sh_y = take(size_t(c.n_shared) * T * c.hidden * 2);

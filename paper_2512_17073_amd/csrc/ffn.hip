@@ -1,17 +1,26 @@
-// Expert FFN on grouped rows (Sections 2.3 and 3.2):
+// Expert FFN on grouped rows (Sections 2.3 and 3.2), many-rows flavour (prefill):
 //   g = x D1 + c (x A1) B1,  u = x D3 + c (x A3) B3,  h = silu(g) * u,  y = h D2 + c (h A2) B2
 // with D = Qinv(Q(W)) unpacked from the bit-packed codes inside the wavefront's registers and
 // c = 1 only for rows that hold a Top-n (token, expert) pair.
 //
-// Kernel design (gfx950): the packed weights are the large, read-once operand, so they never touch
-// LDS.  A wavefront owns one n-tile (16 output columns) of a projection and streams its k-steps
-// from HBM; each lane unpacks the 64 codes it loaded into packed fp16 pairs with one mask and one
-// v_pk_fma_f16 per pair (scale and zero folded into the fma, see unpack.h), which are exactly the
-// A-operand registers of v_mfma_f32_16x16x32_f16.  The activations (a few rows, re-used by every
-// wavefront) are the operand staged through LDS, already in B-operand register order.
-// The rank-r term is appended as r/16 extra MFMA steps on (x A), which a small MFMA kernel
-// computes beforehand as split-K partial sums that are added in a fixed order (no atomics).
+// With hundreds of rows per expert the work is a grouped GEMM and the matrix cores are the bound.
+// Kernel design (gfx950):
+//   - a block of 8 wavefronts owns 128 rows of one expert x 256 output columns (of both W1 and W3
+//     in the fused kernel); a wavefront owns two n-tiles (16 columns each) for all 128 rows, so a
+//     fragment of activations read from LDS feeds four MFMAs and a tile of weights unpacked once in
+//     registers (unpack.h) feeds eight row tiles;
+//   - the packed weights never touch LDS: each wavefront streams its tiles HBM -> registers through
+//     a two-slot ring of buffer loads (a load past the end of the resource returns zeros, so the
+//     refills are unconditional and the waits static);
+//   - the activations of one k-step (128 rows x 256 columns, 64 KB, MFMA operand order) are
+//     double-buffered in LDS: the copy of the next k-step goes from global memory straight to LDS
+//     (no registers) while the current one is multiplied; one barrier per k-step;
+//   - the rank-r term rides the same stream as extra steps: the B factor's 32-wide units take the
+//     place of the codes in a ring slot and meet (in A), which a small kernel of the same shape
+//     (xa_tile_kernel: fp16 factor tiles instead of packed codes) has left in global memory.
+// Experts with few rows (decode) take the other flavour, ffn_decode.hip.
 #include <algorithm>
+#include <type_traits>
 
 #include "ffn_common.h"
 
@@ -21,362 +30,554 @@ namespace {
 
 using namespace ffn;
 
+constexpr int kTileWaves = 8;             // wavefronts per block
+constexpr int kBM = 128;                  // rows of an expert per block
+constexpr int kTMT = kBM / 16;            // row tiles
+constexpr int kStepUnits = kTMT * 8 * 64; // 16-byte units of one k-step of activations (64 KB)
+#ifndef LRC_TILE_PF
+#define LRC_TILE_PF(bits) 1
+#endif
 
-// One pass over all k-steps for up to MAXMT row tiles (16 rows each) starting at expert-local row `r`.
-//   - activations: staged chunk by chunk (kc k-steps) into LDS in MFMA B-operand order; two
-//     barriers per chunk, none inside it;
-//   - weights: each wavefront streams its own tiles HBM -> registers through a two-slot ring
-//     (the tile of its next-but-one k-step is in flight while it unpacks the current one).
-template <int BITS, bool DUAL, int MAXMT>
-__device__ inline void ffn_pass(const KArgs& a, const ExpertDesc& d, uint4* xs, int r0, int cnt, int r,
-                                int nt, int kw, bool wave_ok) {
+// LDS read of one 16-byte unit per lane whose result is awaited by lds_wait, not by the compiler
+// (which would move each read down to its use).
+template <int OFF> __device__ inline half8_t lds_read16(uint32_t addr) {
+  half8_t v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+  return v;
+}
+// Waits until at most N LDS operations issued after the wanted one are outstanding (LDS returns in
+// order), and ties the wanted register to the wait so that its uses stay behind it.
+template <int N> __device__ inline void lds_wait(half8_t& a) { asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a) : "n"(N)); }
+
+template <class T> __device__ inline const T* uniform_ptr(const T* p) {
+  const uint64_t v = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane(uint32_t(v)), hi = __builtin_amdgcn_readfirstlane(uint32_t(v >> 32));
+  return reinterpret_cast<const T*>((uint64_t(hi) << 32) | lo);
+}
+
+// Work item `item` of a launch -> (expert, first row of its 128-row chunk).  Routed experts: the
+// items enumerate the chunks of the experts in order (an expert with cnt rows has ceil(cnt / 128));
+// shared experts: every expert has the same T rows.
+struct Chunk { int e, r0, cnt, r; };
+__device__ inline bool find_chunk(const KArgs& a, int item, Chunk& c) {
+  if (!a.offsets) {
+    const int per = (a.T + kBM - 1) / kBM;
+    c.e = item / per; c.r = (item - c.e * per) * kBM; c.r0 = c.e * a.T; c.cnt = a.T;
+    return c.e < a.n_exp;
+  }
+  // 64 experts at a time: every lane counts the chunks of one expert, a prefix sum over the
+  // wavefront finds the one that holds the item (every wavefront of the block does the same)
+  const int lane = threadIdx.x & 63;
+  int base = 0;
+  for (int e0 = 0; e0 < a.n_exp; e0 += 64) {
+    const int e = e0 + lane;
+    int r0 = 0, cnt = 0;
+    if (e < a.n_exp) { r0 = a.offsets[e]; cnt = a.offsets[e + 1] - r0; }
+    const int n = (cnt + kBM - 1) / kBM;
+    int incl = n;
+#pragma unroll
+    for (int dlt = 1; dlt < 64; dlt *= 2) {
+      const int t = __shfl_up(incl, dlt);
+      if (lane >= dlt) incl += t;
+    }
+    const int total = __shfl(incl, 63);
+    if (item < base + total) {
+      const unsigned long long hit = __ballot(base + incl > item);
+      const int first = __ffsll(hit) - 1;
+      c.e = e0 + first;
+      c.r0 = __shfl(r0, first); c.cnt = __shfl(cnt, first);
+      c.r = (item - base - __shfl(incl - n, first)) * kBM;
+      return true;
+    }
+    base += total;
+  }
+  return false;
+}
+
+// Copy of the activations of k-step ks for the 128 rows from input row `rin` on into `buf`, as 64
+// fragments (row tile mt, sub-step s) of 64 units: wavefront w copies the eight fragments with
+// s = w, each lane its own 16 bytes from global memory straight to LDS.  Always eight copies per
+// wavefront (the waits count on that): a row or column past the end is clamped to a valid unit
+// (such rows are never stored; the padded weights of such columns are exact zeros).
+__device__ inline void stage_step(const KArgs& a, uint4* buf, int ks, int rin, int wave, int lane) {
+  const uint4* in_units = reinterpret_cast<const uint4*>(a.in);
+  const int q = lane >> 4, rowl = lane & 15, s = wave;
+  const int k8 = min(ks * 32 + q * 8 + s, a.K / 8 - 1);
+#pragma unroll
+  for (int mt = 0; mt < kTMT; ++mt) {
+    const int R = min(rin + 16 * mt + rowl, a.in_rt - 1);
+    __builtin_amdgcn_global_load_lds(
+        reinterpret_cast<const __attribute__((address_space(1))) void*>(reinterpret_cast<uintptr_t>(in_units + act_unit(k8, R, a.in_rt))),
+        reinterpret_cast<__attribute__((address_space(3))) void*>(reinterpret_cast<uintptr_t>(buf + (mt * 8 + s) * 64)), 16, 0, 0);
+  }
+}
+
+// Codes and metadata of one k-step of a wavefront's two n-tiles.
+template <int BITS, int NM, int NTW> struct Slot2 { Slot<BITS, NM> t[NTW]; };
+
+template <int BITS, bool DUAL, int NTW>
+__global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a) {
+  extern __shared__ uint4 xs[];           // two k-steps of activations; afterwards the (in A) fragments
   constexpr int NM = DUAL ? 2 : 1;
+  constexpr int kNTW = NTW;                              // n-tiles per wavefront
   constexpr int DW = 2 * BITS;
   constexpr int NC = Extract<BITS>::kClasses;
-  constexpr int kRing = ring_depth(BITS, DUAL);
-  const int lane = threadIdx.x & 63, th = threadIdx.x;
+  constexpr int LPS = BITS == 2 ? 2 : 3;                 // loads per tile and projection
+  constexpr int kSlotOps = kNTW * NM * LPS;              // loads of one ring slot
+  Chunk ch;
+  if (!find_chunk(a, blockIdx.y, ch)) return;
+  const int e = ch.e, r0 = ch.r0, cnt = ch.cnt, r = ch.r;
+  const ExpertDesc& d = a.desc[e];
+  const int th = threadIdx.x, lane = th & 63;
   const int wave = __builtin_amdgcn_readfirstlane(th >> 6);
-  const int tdw = kWave * DW;
   const int q = lane >> 4, c = lane & 15;
-  const int mt_n = min(MAXMT, (cnt - r + 15) >> 4);
-  // k-steps per chunk: as many as fit the LDS buffer for this many row tiles (a power of two)
-  const int kc = max(1, (kLdsUnits / 512) >> (mt_n == 1 ? 0 : (mt_n == 2 ? 1 : (mt_n <= 4 ? 2 : 3))));
+  const int tdw = kWave * DW;
+  const int mt_n = min(kTMT, (cnt - r + 15) >> 4);       // row tiles that hold rows of this expert
+  const int tile0 = (blockIdx.x * kTileWaves + wave) * kNTW;
 
-  // Buffer resources over this wavefront's tile stream and metadata of each projection: a load
-  // past the end (a k-step beyond the last, or a wavefront without an n-tile) returns zeros and
-  // touches no memory, so every step can issue its refill unconditionally and the count of loads
-  // in flight is known statically.
-  __amdgpu_buffer_rsrc_t code_rs[NM], meta_rs[NM];
+  const int code_bytes = a.KS * a.NT * tdw * 4, meta_bytes = a.G * a.NT * kTileN * 4;
+  const bool lowrank = a.rank > 0 && __builtin_amdgcn_readfirstlane(d.has_factors) != 0 && a.row_pair != nullptr;
+  const int LS = lowrank ? a.ls : 0;
+  const int bf_bytes = a.NT * a.ls * 1024;
+  __amdgpu_buffer_rsrc_t code_rs[NM], meta_rs[NM], bf_rs[NM];
+  float lam[NM];
 #pragma unroll
   for (int m = 0; m < NM; ++m) {
     const int mat = DUAL ? m : 2;
-    code_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(d.codes[mat]), 0,
-                                                   wave_ok ? a.KS * a.NT * tdw * 4 : 0, 0x00020000);
-    meta_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(d.meta[mat]), 0,
-                                                   wave_ok ? a.G * a.NT * kTileN * 4 : 0, 0x00020000);
+    code_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(uniform_ptr(d.codes[mat])), 0, code_bytes, 0x00020000);
+    meta_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(uniform_ptr(d.meta[mat])), 0, meta_bytes, 0x00020000);
+    bf_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<_Float16*>(uniform_ptr(d.bf[mat])), 0, lowrank ? bf_bytes : 0, 0x00020000);
+    lam[m] = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(d.inv_lambda[mat])));
   }
-  const int groups_per_step = kTileK >> a.group_shift;      // 4, 2 or 1
-  auto fetch = [&](int ks, Slot<BITS, NM>& sl) {
-    // wave-uniform byte offsets of tile (ks, nt) and of its first metadata row; a k-step past the
-    // end lands beyond the resource (k-step-major order), so the loads return zeros
-    // (offsets go into the per-lane offset operand: that is the one the hardware range-checks)
-    const bool ok = ks < a.KS;
-    const int tile_off = (ok ? (ks * a.NT + nt) * (tdw * 4) : a.KS * a.NT * tdw * 4) + lane * 16;
-    const int tile_off2 = (ok ? (ks * a.NT + nt) * (tdw * 4) : a.KS * a.NT * tdw * 4) + 1024 + lane * (BITS == 3 ? 8 : 16);
-    const int meta_off = (ok ? (ks * groups_per_step * a.NT + nt) * (kTileN * 4) : a.G * a.NT * kTileN * 4) +
-                         ((q * kLaneK) >> a.group_shift) * (a.NT * kTileN * 4) + c * 4;
-#pragma unroll
-    for (int m = 0; m < NM; ++m) {
-      const u32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(code_rs[m], tile_off, 0, 0);
-      sl.cw[m][0] = v0[0]; sl.cw[m][1] = v0[1]; sl.cw[m][2] = v0[2]; sl.cw[m][3] = v0[3];
-      if constexpr (BITS == 3) {
-        const u32x2 v1 = __builtin_amdgcn_raw_buffer_load_b64(code_rs[m], tile_off2, 0, 0);
-        sl.cw[m][4] = v1[0]; sl.cw[m][5] = v1[1];
-      } else if constexpr (BITS == 4) {
-        const u32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(code_rs[m], tile_off2, 0, 0);
-        sl.cw[m][4] = v1[0]; sl.cw[m][5] = v1[1]; sl.cw[m][6] = v1[2]; sl.cw[m][7] = v1[3];
-      }
-      sl.mw[m] = __builtin_amdgcn_raw_buffer_load_b32(meta_rs[m], meta_off, 0, 0);
-    }
-  };
+  const int gps = kTileK >> a.group_shift;               // groups per k-step
+  const int meta_lane = ((q * kLaneK) >> a.group_shift) * (a.NT * kTileN * 4) + c * 4;
 
-  // staging: the chunk is mt_n * nk * 512 units of 16 bytes (8 activations of one row); unit u is
-  // row u%16 of row tile (u/512)/nk, 8-element column (u/16)%32 of k-step (u/512)%nk.  The input
-  // is in operand order (act_unit): rows are contiguous, so 16 lanes read one 256-byte run.  Rows
-  // past the expert's last one read whatever follows (their output columns are never stored);
-  // columns past K read as zero.
-  constexpr int kThreads = 64 * block_waves(MAXMT);
-  const int rowl = th & 15;
-  const int rin = ((DUAL && !a.offsets) ? 0 : r0) + r;
-  const uint4* in_units = reinterpret_cast<const uint4*>(a.in);
-  auto stage = [&](int ks0, int nk) {
-    const int total = mt_n * nk * 512;
-    constexpr int kMaxUnits = (kLdsUnits + kThreads - 1) / kThreads;    // per thread
+  // step < KS: the packed tiles of k-step `step`; KS <= step < KS + LS: the B-factor units of rank
+  // step (step - KS); anything else (and an n-tile past the last) reads zeros past the resources
+  auto fetch = [&](int step, Slot2<BITS, NM, kNTW>& sl) {
 #pragma unroll
-    for (int b = 0; b < kMaxUnits; b += 4) {
-      if (th + b * kThreads >= total) break;
-      uint4 reg[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int u = th + (b + i) * kThreads;
-        reg[i] = make_uint4(0, 0, 0, 0);
-        if (u < total) {
-          const int k8l = (u >> 4) & 31, mk = u >> 9, mt = mk / nk, kl = mk - mt * nk;
-          const int k8 = (ks0 + kl) * 32 + k8l;
-          if (k8 * 8 < a.K) reg[i] = in_units[act_unit(k8, rin + 16 * mt + rowl, a.in_rt)];
-        }
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int u = th + (b + i) * kThreads;
-        if (u < total) {
-          const int k8l = (u >> 4) & 31, mk = u >> 9, mt = mk / nk, kl = mk - mt * nk;
-          xs[((mt * kc + kl) * 8 + (k8l & 7)) * 64 + (k8l >> 3) * 16 + rowl] = reg[i];
-        }
-      }
-    }
-  };
-
-  float4_t acc[MAXMT][NM];
-#pragma unroll
-  for (int mt = 0; mt < MAXMT; ++mt)
-#pragma unroll
-    for (int m = 0; m < NM; ++m) acc[mt][m] = float4_t{0.f, 0.f, 0.f, 0.f};
-
-  auto compute = [&](const Slot<BITS, NM>& cur, int kl) {
-    const uint4* xk = xs + size_t(kl) * 8 * 64 + lane;
-    uint32_t s2[NM][NC], c2[NM];
-#pragma unroll
-    for (int m = 0; m < NM; ++m) {
-      s2[m][0] = (cur.mw[m] & 0xffffu) | (cur.mw[m] << 16);
-      c2[m] = (cur.mw[m] >> 16) | (cur.mw[m] & 0xffff0000u);
-      constexpr uint32_t step = Extract<BITS>::kStepBits == 2 ? 0x44004400u : 0x48004800u;   // 4.0 or 8.0
-#pragma unroll
-      for (int p = 1; p < NC; ++p) s2[m][p] = pk_mul(s2[m][p - 1], step);
-    }
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      half8_t wf[NM];
+    for (int t = 0; t < kNTW; ++t) {
+      const int tile = tile0 + t;
+      const bool ok = step < a.KS && tile < a.NT;
+      const bool lr = step >= a.KS && step < a.KS + LS && tile < a.NT;
+      const int tile_off = (ok ? (step * a.NT + tile) * (tdw * 4) : lr ? (tile * a.ls + (step - a.KS)) * 1024 : max(code_bytes, bf_bytes)) + lane * 16;
+      const int tile_off2 = (ok ? (step * a.NT + tile) * (tdw * 4) : code_bytes) + 1024 + lane * (BITS == 3 ? 8 : 16);
+      const int meta_off = (ok ? (step * gps * a.NT + tile) * (kTileN * 4) : meta_bytes) + meta_lane;
 #pragma unroll
       for (int m = 0; m < NM; ++m) {
-        uint32_t v[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          v[j] = pk_fma(Extract<BITS>::field(cur.cw[m], 4 * s + j), s2[m][Extract<BITS>::cls(4 * s + j)], c2[m]);
-        wf[m] = __builtin_bit_cast(half8_t, make_uint4(v[0], v[1], v[2], v[3]));
+        Slot<BITS, NM>& s1 = sl.t[t];
+        const u32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(lr ? bf_rs[m] : code_rs[m], tile_off, 0, 0);
+        s1.cw[m][0] = v0[0]; s1.cw[m][1] = v0[1]; s1.cw[m][2] = v0[2]; s1.cw[m][3] = v0[3];
+        if constexpr (BITS == 3) {
+          const u32x2 v1 = __builtin_amdgcn_raw_buffer_load_b64(code_rs[m], tile_off2, 0, 0);
+          s1.cw[m][4] = v1[0]; s1.cw[m][5] = v1[1];
+        } else if constexpr (BITS == 4) {
+          const u32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(code_rs[m], tile_off2, 0, 0);
+          s1.cw[m][4] = v1[0]; s1.cw[m][5] = v1[1]; s1.cw[m][6] = v1[2]; s1.cw[m][7] = v1[3];
+        }
+        s1.mw[m] = __builtin_amdgcn_raw_buffer_load_b32(meta_rs[m], meta_off, 0, 0);
       }
+    }
+  };
+
+  // first input row of this chunk (shared experts all read the token rows 0..T-1)
+  const int rin = ((DUAL && !a.offsets) ? 0 : r0) + r;
+
+  float4_t acc[kNTW][kTMT][NM];
 #pragma unroll
-      for (int mt = 0; mt < MAXMT; ++mt)
-        if (mt < mt_n) {
-          const half8_t xf = __builtin_bit_cast(half8_t, xk[(size_t(mt) * kc * 8 + s) * 64]);
+  for (int t = 0; t < kNTW; ++t)
+#pragma unroll
+    for (int mt = 0; mt < kTMT; ++mt)
+#pragma unroll
+      for (int m = 0; m < NM; ++m) acc[t][mt][m] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+  // A fragment read from LDS meets the operands of all (tile, projection) pairs of the wavefront.
+  // The read of the next row tile's fragment is issued before the MFMAs of the current one.
+  constexpr int PF = LRC_TILE_PF(BITS);   // fragments requested ahead of the one being multiplied
+  auto mfma_rows = [&](const half8_t (&wf)[kNTW][NM], uint32_t base) {   // base: LDS byte address of (row tile 0, this lane)
+    half8_t xf[PF + 1];
+    if (mt_n == kTMT) {                   // a full chunk: straight-line, PF reads in flight
+      auto rd = [&](auto MT) {
+        constexpr int mt = decltype(MT)::value;
+        xf[mt % (PF + 1)] = lds_read16<mt * 8 * 1024>(base);
+      };
+      auto row_tile = [&](auto MT) {
+        constexpr int mt = decltype(MT)::value;
+#ifdef LRC_EXP_T_NOLDS
+        if constexpr (mt == 0) lds_wait<0>(xf[0]);
+#else
+        if constexpr (mt + PF < kTMT) rd(std::integral_constant<int, (mt + PF < kTMT ? mt + PF : 0)>{});
+        lds_wait<(kTMT - 1 - mt < PF ? kTMT - 1 - mt : PF)>(xf[mt % (PF + 1)]);
+#endif
+#pragma unroll
+        for (int t = 0; t < kNTW; ++t)
 #pragma unroll
           for (int m = 0; m < NM; ++m)
-            acc[mt][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[m], xf, acc[mt][m], 0, 0, 0);
-        }
-      // keep the sub-steps in order: hoisting later unpacks above these MFMAs only costs registers,
-      // the other wavefronts of the SIMD hide the latency
-      if (MAXMT <= 2 && (s & 1)) __builtin_amdgcn_sched_barrier(0);
+#ifdef LRC_EXP_T_NOLDS
+            acc[t][mt][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[t][m], xf[0], acc[t][mt][m], 0, 0, 0);
+#else
+            acc[t][mt][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[t][m], xf[mt % (PF + 1)], acc[t][mt][m], 0, 0, 0);
+#endif
+      };
+      rd(std::integral_constant<int, 0>{});
+      if constexpr (PF > 1) rd(std::integral_constant<int, 1>{});
+      if constexpr (PF > 2) rd(std::integral_constant<int, 2>{});
+      row_tile(std::integral_constant<int, 0>{}); row_tile(std::integral_constant<int, 1>{});
+      row_tile(std::integral_constant<int, 2>{}); row_tile(std::integral_constant<int, 3>{});
+      row_tile(std::integral_constant<int, 4>{}); row_tile(std::integral_constant<int, 5>{});
+      row_tile(std::integral_constant<int, 6>{}); row_tile(std::integral_constant<int, 7>{});
+      return;
     }
+    // a partly filled chunk: only the row tiles that hold rows, one read ahead
+    xf[0] = lds_read16<0>(base);
+    auto row_tile = [&](auto MT) {
+      constexpr int mt = decltype(MT)::value;
+      if (mt >= mt_n) return;
+      if constexpr (mt + 1 < kTMT) {
+        if (mt + 1 < mt_n) {
+          xf[(mt + 1) & 1] = lds_read16<(mt + 1) * 8 * 1024>(base);
+          lds_wait<1>(xf[mt & 1]);
+        } else {
+          lds_wait<0>(xf[mt & 1]);
+        }
+      } else {
+        lds_wait<0>(xf[mt & 1]);
+      }
+#pragma unroll
+      for (int t = 0; t < kNTW; ++t)
+#pragma unroll
+        for (int m = 0; m < NM; ++m)
+          acc[t][mt][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[t][m], xf[mt & 1], acc[t][mt][m], 0, 0, 0);
+    };
+    row_tile(std::integral_constant<int, 0>{}); row_tile(std::integral_constant<int, 1>{});
+    row_tile(std::integral_constant<int, 2>{}); row_tile(std::integral_constant<int, 3>{});
+    row_tile(std::integral_constant<int, 4>{}); row_tile(std::integral_constant<int, 5>{});
+    row_tile(std::integral_constant<int, 6>{}); row_tile(std::integral_constant<int, 7>{});
   };
 
-  // Ring of kRing slots, walked by a loop unrolled kRing times so that every slot index is static:
-  // slot i holds this wavefront's own k-steps i, i + kRing, ...  A slot is refilled right after it
-  // has been consumed, so kRing - 1 tiles stay in flight during an unpack.  All wavefronts of the
-  // block take the same number of steps (the k-steps of one step lie in the same chunk because
-  // the chunk length is a multiple of kw), so the barriers around the staging are uniform.
-  Slot<BITS, NM> ring[kRing];
+  // one k-step: unpack 32 rows of the four weight tiles per sub-step, multiply with all row tiles
+  auto compute = [&](const Slot2<BITS, NM, kNTW>& cur, const uint4* buf) {
+    uint32_t s2[kNTW][NM][NC], c2[kNTW][NM];
 #pragma unroll
-  for (int i = 0; i < kRing; ++i) fetch(kw + i * a.kw, ring[i]);
-  const int n_steps = (a.KS + a.kw - 1) / a.kw;
-  for (int j0 = 0; j0 < n_steps; j0 += kRing) {
-#pragma unroll
-    for (int i = 0; i < kRing; ++i) {
-      const int ksb = (j0 + i) * a.kw;     // first k-step of this step, block-uniform
-      if (ksb < a.KS) {
-        if (ksb % kc == 0) {
-          __syncthreads();                 // everyone is done with the previous chunk
-          stage(ksb, min(kc, a.KS - ksb));
-          __syncthreads();
-        }
-#ifndef LRC_EXP_NOCOMPUTE
-        if (wave_ok && ksb + kw < a.KS) compute(ring[i], (ksb + kw) % kc);
-#else
-        if (wave_ok && ksb + kw < a.KS) { acc[0][0][0] += __uint_as_float(ring[i].cw[0][0] ^ ring[i].cw[NM-1][3] ^ ring[i].mw[0]); }
-#endif
-      }
-#ifndef LRC_EXP_NOFETCH
-      fetch(ksb + kw + kRing * a.kw, ring[i]);
-#endif
-    }
-  }
-
-  // ---- wavefronts that shared an n-tile add up their partial sums through LDS ----
-  if (a.kw > 1) {
-    float4_t* red = reinterpret_cast<float4_t*>(xs);
-    __syncthreads();
-    if (kw != 0) {
-#pragma unroll
-      for (int mt = 0; mt < MAXMT; ++mt)
-        if (mt < mt_n)
-#pragma unroll
-          for (int m = 0; m < NM; ++m) red[((wave * MAXMT + mt) * NM + m) * 64 + lane] = acc[mt][m];
-    }
-    __syncthreads();
-    if (kw == 0) {
-      for (int j = 1; j < a.kw; ++j)
-#pragma unroll
-        for (int mt = 0; mt < MAXMT; ++mt)
-          if (mt < mt_n)
-#pragma unroll
-            for (int m = 0; m < NM; ++m) acc[mt][m] += red[(((wave + j) * MAXMT + mt) * NM + m) * 64 + lane];
-    }
-  }
-  if (kw != 0 || !wave_ok) return;
-
-  // ---- rank-r term: r/16 more MFMA steps, weights = packed B factor, activations = (in A) ----
-  const int PW = DUAL ? 2 * a.rpad : a.rpad;
-#pragma unroll
-  for (int mt = 0; mt < MAXMT; ++mt) {
-    if (mt >= mt_n) continue;
-    const int row = r + 16 * mt + c;   // this lane's token column of the tile
-    bool flagged = false;
-    if (a.rank > 0 && d.has_factors && a.row_pair != nullptr && row < cnt)
-      flagged = (a.row_pair[r0 + row] % a.top_k) < a.top_n;
-    if (__ballot(flagged) != 0ull) {
-      const int rs = a.rpad / 16;
+    for (int t = 0; t < kNTW; ++t)
 #pragma unroll
       for (int m = 0; m < NM; ++m) {
-        const int mat = DUAL ? m : 2;
-        const float lam = d.lambda[mat];
-        for (int st = 0; st < rs; ++st) {
-          float4_t pv = float4_t{0.f, 0.f, 0.f, 0.f};
-          if (flagged) {
-            const float* pp = a.p + size_t(r0 + row) * PW + m * a.rpad + 16 * st + 4 * q;
-            for (int sp = 0; sp < a.ksplit; ++sp)
-              pv += *reinterpret_cast<const float4_t*>(pp + size_t(sp) * a.total_rows * PW);
+        const uint32_t mw = cur.t[t].mw[m];
+        s2[t][m][0] = (mw & 0xffffu) | (mw << 16);
+        c2[t][m] = (mw >> 16) | (mw & 0xffff0000u);
+        constexpr uint32_t step = Extract<BITS>::kStepBits == 2 ? 0x44004400u : 0x48004800u;   // 4.0 or 8.0
+#pragma unroll
+        for (int p = 1; p < NC; ++p) s2[t][m][p] = pk_mul(s2[t][m][p - 1], step);
+      }
+    const uint32_t base = uint32_t(reinterpret_cast<uintptr_t>(buf + lane));
+    auto substep = [&](auto S) {
+      constexpr int s = decltype(S)::value;
+      half8_t wf[kNTW][NM];
+#pragma unroll
+      for (int t = 0; t < kNTW; ++t)
+#pragma unroll
+        for (int m = 0; m < NM; ++m) {
+          uint32_t v[4];
+#ifdef LRC_EXP_T_NOVALU
+#pragma unroll
+          for (int j = 0; j < 4; ++j) v[j] = cur.t[t].cw[m][(4 * s + j) % DW] ^ c2[t][m];
+          if (false)
+#endif
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            v[j] = pk_fma(Extract<BITS>::field(cur.t[t].cw[m], 4 * s + j), s2[t][m][Extract<BITS>::cls(4 * s + j)], c2[t][m]);
+          wf[t][m] = __builtin_bit_cast(half8_t, make_uint4(v[0], v[1], v[2], v[3]));
+        }
+      mfma_rows(wf, base + s * 1024);
+    };
+    substep(std::integral_constant<int, 0>{}); substep(std::integral_constant<int, 1>{});
+    substep(std::integral_constant<int, 2>{}); substep(std::integral_constant<int, 3>{});
+    substep(std::integral_constant<int, 4>{}); substep(std::integral_constant<int, 5>{});
+    substep(std::integral_constant<int, 6>{}); substep(std::integral_constant<int, 7>{});
+  };
+
+  // ---- prologue: the first k-step of activations and the first two ring slots
+  Slot2<BITS, NM, kNTW> ring[2];
+  stage_step(a, xs, 0, rin, wave, lane);
+  __builtin_amdgcn_sched_barrier(0);
+  fetch(0, ring[0]);
+  fetch(1, ring[1]);
+  // only the packed tiles are still in flight when the barrier is passed (written out: a
+  // __syncthreads() would first wait for every load in flight)
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(2 * kSlotOps) : "memory");
+
+  // ---- the k-steps, two per trip so that the ring slots are indexed statically.  In a step: the
+  //      copy of the next step's activations is issued into the other half of LDS (free since the
+  //      barrier that ended the previous step), the current step is multiplied, its slot refilled;
+  //      then only that refill may still be in flight (the copy has landed) and the barrier ends
+  //      the step.
+  const int steps = a.KS;
+  for (int s0 = 0; s0 < steps; s0 += 2) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int step = s0 + i;
+      if (step < steps) {
+        stage_step(a, xs + ((step + 1) & 1) * kStepUnits, step + 1, rin, wave, lane);
+        __builtin_amdgcn_sched_barrier(0);     // (the wait below counts the refill as the only later loads)
+        compute(ring[i], xs + (step & 1) * kStepUnits);
+        fetch(step + 2, ring[i]);
+        asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(kSlotOps) : "memory");
+      }
+    }
+  }
+
+  // ---- rank steps.  (in A) of the chunk's rows, fp16 row-major in global memory (xa_tile_kernel
+  //      has scaled it and zeroed the rows without the term), is copied into LDS as MFMA fragments:
+  //      unit ((m * LS + st) * 8 + mt) * 64 + lane = columns 32 st + 8 q .. + 7 of row 16 mt + lane % 16.
+  if (LS > 0) {
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");   // (the last copy issued serves no step)
+    const _Float16* P = reinterpret_cast<const _Float16*>(a.p);
+    const int pitch = NM * a.ls * 32;                                // halves per row
+    for (int f = wave; f < NM * LS * kTMT; f += kTileWaves) {
+      const int mt = f % kTMT, g = f / kTMT, st = g % LS, m = g / LS;
+      const int row = min(r0 + r + 16 * mt + c, a.total_rows - 1);
+      const _Float16* src = P + size_t(row) * pitch + m * a.ls * 32 + 32 * st + 8 * q;
+      __builtin_amdgcn_global_load_lds(
+          reinterpret_cast<const __attribute__((address_space(1))) void*>(reinterpret_cast<uintptr_t>(src)),
+          reinterpret_cast<__attribute__((address_space(3))) void*>(reinterpret_cast<uintptr_t>(xs + (size_t(g) * kTMT + mt) * 64)), 16, 0, 0);
+    }
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    auto rank_step = [&](const Slot2<BITS, NM, kNTW>& cur, int st) {
+#pragma unroll
+      for (int m = 0; m < NM; ++m) {
+        half8_t bfrag[kNTW];
+#pragma unroll
+        for (int t = 0; t < kNTW; ++t)
+          bfrag[t] = __builtin_bit_cast(half8_t, make_uint4(cur.t[t].cw[m][0], cur.t[t].cw[m][1], cur.t[t].cw[m][2], cur.t[t].cw[m][3]));
+#pragma unroll
+        for (int mt = 0; mt < kTMT; ++mt)
+          if (mt < mt_n) {
+            const half8_t pf = __builtin_bit_cast(half8_t, xs[((size_t(m) * LS + st) * kTMT + mt) * 64 + lane]);
+#pragma unroll
+            for (int t = 0; t < kNTW; ++t)
+              acc[t][mt][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(bfrag[t], pf, acc[t][mt][m], 0, 0, 0);
           }
-          const half4_t pf = half4_t{(_Float16)(pv[0] * lam), (_Float16)(pv[1] * lam),
-                                     (_Float16)(pv[2] * lam), (_Float16)(pv[3] * lam)};
-          // B factor: [N/16][ceil(rank/32)][lane][8], 32 rank indices per unit row; this step's 16
-          const int ls = (a.rank + 31) / 32;
-          const half4_t bfr = *reinterpret_cast<const half4_t*>(
-              d.bf[mat] + ((size_t(nt) * ls + (st >> 1)) * kWave + (2 * (st & 1) + (q >> 1)) * 16 + c) * 8 + 4 * (q & 1));
-          acc[mt][m] = __builtin_amdgcn_mfma_f32_16x16x16f16(bfr, pf, acc[mt][m], 0, 0, 0);
+      }
+    };
+    // the slot of step KS + st is ring[(KS + st) % 2]
+    for (int st0 = 0; st0 < LS + 1; st0 += 2) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        // trip element i handles the step whose slot is ring[i]
+        const int step = ((steps + st0) & ~1) + i;
+        if (step >= steps && step < steps + LS) {
+          rank_step(ring[i], step - steps);
+          fetch(step + 2, ring[i]);
         }
       }
     }
   }
 
-  // ---- epilogue: lane holds output columns 16*nt + 4*q .. +3 of token column c ----
+  // ---- epilogue: lane holds output columns 16*tile + 4*q .. +3 of token column c ----
 #pragma unroll
-  for (int mt = 0; mt < MAXMT; ++mt) {
-    const int row = r + 16 * mt + c;
-    if (mt >= mt_n || row >= cnt) continue;
-    const size_t o = size_t(r0 + row) * a.N + nt * kTileN + 4 * q;
-    if constexpr (DUAL) {
-      const float i1 = d.inv_lambda[0], i3 = d.inv_lambda[1];
-      half4_t hv;
+  for (int t = 0; t < kNTW; ++t) {
+    const int tile = tile0 + t;
+    if (tile >= a.NT) continue;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float g = acc[mt][0][i] * i1, u = acc[mt][1][i] * i3;
-        hv[i] = (_Float16)(g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u);
+    for (int mt = 0; mt < kTMT; ++mt) {
+      const int row = r + 16 * mt + c;
+      if (mt >= mt_n || row >= cnt) continue;
+      const size_t o = size_t(r0 + row) * a.N + tile * kTileN + 4 * q;
+      if constexpr (DUAL) {
+        half4_t hv;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float g = acc[t][mt][0][i] * lam[0], u = acc[t][mt][1][i] * lam[NM - 1];
+          hv[i] = (_Float16)(g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u);
+        }
+        // h in operand order for the W2 kernel: columns f .. f+3 are half of one 16-byte unit
+        const int f = tile * kTileN + 4 * q;
+        *reinterpret_cast<half4_t*>(reinterpret_cast<_Float16*>(a.out) + act_unit(f >> 3, r0 + row, a.out_rt) * 8 + (f & 7)) = hv;
+      } else {
+        uint2 yv;
+        yv.x = f32x2_to_bf16x2(acc[t][mt][0][0] * lam[0], acc[t][mt][0][1] * lam[0]);
+        yv.y = f32x2_to_bf16x2(acc[t][mt][0][2] * lam[0], acc[t][mt][0][3] * lam[0]);
+        *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + o) = yv;
       }
-      const int f = nt * kTileN + 4 * q;      // h in operand order for the W2 kernel
-      *reinterpret_cast<half4_t*>(reinterpret_cast<_Float16*>(a.out) + act_unit(f >> 3, r0 + row, a.out_rt) * 8 + (f & 7)) = hv;
-    } else {
-      const float i2 = d.inv_lambda[2];
-      uint2 yv;
-      yv.x = f32x2_to_bf16x2(acc[mt][0][0] * i2, acc[mt][0][1] * i2);
-      yv.y = f32x2_to_bf16x2(acc[mt][0][2] * i2, acc[mt][0][3] * i2);
-      *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + o) = yv;
     }
   }
 }
 
-// grid = (ceil(NT * kw / waves), experts); a block of `waves` wavefronts covers waves / kw n-tiles.
-// MAXMT = 2: decode flavour, 128 registers, 16 wavefronts per CU.  MAXMT = 8: many rows per expert,
-// one unpack serves up to 128 rows, 256 registers.
-template <int BITS, bool DUAL, int MAXMT>
-__global__ __launch_bounds__(64 * block_waves(MAXMT), MAXMT <= 2 ? LRC_DECODE_MINW : 2) void qgemm_kernel(KArgs a) {
-  __shared__ uint4 xs[kLdsUnits];
-  const int e = blockIdx.y;
-  const int r0 = a.offsets ? a.offsets[e] : e * a.T;
-  const int cnt = a.offsets ? a.offsets[e + 1] - r0 : a.T;
-  if (cnt == 0) return;
-  const ExpertDesc& d = a.desc[e];
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int kw = wave % a.kw;
-  const int nt = blockIdx.x * (block_waves(MAXMT) / a.kw) + wave / a.kw;
-  const bool wave_ok = nt < a.NT;
-  for (int r = 0; r < cnt; r += 16 * MAXMT) ffn_pass<BITS, DUAL, MAXMT>(a, d, xs, r0, cnt, r, nt, kw, wave_ok);
-}
-
-// p[sp][row][rho] = sum over k-slice sp of in[row][k] * A[k][rho], for rows that take the rank-r
-// term.  grid = (ksplit, experts); wavefronts loop over 16-column tiles of the factor(s).
+// (in A)[row][rho] for the 128-row chunks of every expert, in two launches.
+// xa_tile_kernel: K-block partial sums in fp32, [K-block][row][NM * ls * 32 columns] ([A1 | A3] in
+// the fused case, each padded to a multiple of 32), already multiplied by the projection's
+// power-of-two pre-scale.  Same shape as the kernel above (activations through double-buffered LDS,
+// eight row tiles per fragment of weights), with the fp16 factor tiles [K/32][rpad/16][lane][8] as
+// the weight operand: wavefront w owns the 16-column factor tiles w, w + 8, ... (at most four);
+// grid.x splits K so that the launch fills the chip.
+// xa_finish_kernel: adds the K-blocks in order, zeroes the rows without the rank-r term and the
+// padding columns, writes fp16 row-major.
 template <bool DUAL>
-__global__ __launch_bounds__(256) void xa_kernel(KArgs a) {
-  const int e = blockIdx.y, sp = blockIdx.x;
-  const int r0 = a.offsets[e], cnt = a.offsets[e + 1] - r0;
+__global__ __launch_bounds__(64 * kTileWaves, 2) void xa_tile_kernel(KArgs a) {
+  extern __shared__ uint4 xs[];
+  constexpr int NM = DUAL ? 2 : 1;
+  constexpr int kMaxT = 4;                               // factor tiles per wavefront: rank <= 256
+  Chunk ch;
+  if (!find_chunk(a, blockIdx.y, ch)) return;
+  const int e = ch.e, r0 = ch.r0, cnt = ch.cnt, r = ch.r;
   const ExpertDesc& d = a.desc[e];
-  if (cnt == 0 || !d.has_factors) return;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, c = lane & 15, q = lane >> 4;
-  const int rt = a.rpad / 16, tiles = DUAL ? 2 * rt : rt, PW = tiles * 16;
-  const int k32 = a.K / 32, per = (k32 + a.ksplit - 1) / a.ksplit;
-  const int kk0 = sp * per, kk1 = min(k32, kk0 + per);
-  for (int r = 0; r < cnt; r += 16) {
-    const int row = r + c;
-    bool flagged = false;
-    if (row < cnt) flagged = (a.row_pair[r0 + row] % a.top_k) < a.top_n;
-    if (__ballot(flagged) == 0ull) continue;
-    const half8_t* src = reinterpret_cast<const half8_t*>(a.in);   // operand order: unit (k8, row)
-    for (int tile = wave; tile < tiles; tile += 4) {
-      const int mat = DUAL ? (tile >= rt ? 1 : 0) : 2;
-      const int tl = DUAL && tile >= rt ? tile - rt : tile;
-      const _Float16* af = d.af[mat];
-      float4_t acc = float4_t{0.f, 0.f, 0.f, 0.f};
-      for (int kk = kk0; kk < kk1; ++kk) {
-        const half8_t wf = *reinterpret_cast<const half8_t*>(af + ((size_t(kk) * rt + tl) * kWave + lane) * 8);
-        half8_t xf = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
-        if (flagged) xf = src[act_unit(4 * kk + q, r0 + row, a.in_rt)];
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf, xf, acc, 0, 0, 0);
+  if (!d.has_factors) return;
+  const int th = threadIdx.x, lane = th & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(th >> 6);
+  const int q = lane >> 4, c = lane & 15;
+  const int mt_n = min(kTMT, (cnt - r + 15) >> 4);
+  const int rt = a.rpad / 16, tiles = NM * rt;           // 16-column factor tiles in all
+  const int pitch = NM * a.ls * 32;
+  const int rin = r0 + r;
+
+  float4_t acc[kMaxT][kTMT];
+#pragma unroll
+  for (int t = 0; t < kMaxT; ++t)
+#pragma unroll
+    for (int mt = 0; mt < kTMT; ++mt) acc[t][mt] = float4_t{0.f, 0.f, 0.f, 0.f};
+  // A fragment of activations (k-step ks, sub-step s) holds, in lane (q, row), the columns
+  // 256 ks + 64 q + 8 s + j: the factor unit that meets it is the one with those K rows, unit
+  // (8 ks + 2 q + s / 4, tile) of the packed factor, lane (s % 4, c) of it.
+  const half8_t* af[kMaxT];
+  int nmine = 0;
+#pragma unroll
+  for (int t = 0; t < kMaxT; ++t) {
+    const int tile = wave + t * kTileWaves;
+    af[t] = nullptr;
+    if (tile < tiles) {
+      const int m = tile / rt, tl = tile - m * rt;
+      af[t] = reinterpret_cast<const half8_t*>(uniform_ptr(d.af[DUAL ? m : 2])) + size_t(tl) * kWave + c;
+      nmine = t + 1;
+    }
+  }
+
+  const int all_steps = (a.K + kTileK - 1) / kTileK, per_kb = (all_steps + gridDim.x - 1) / gridDim.x;
+  const int step_lo = blockIdx.x * per_kb, steps = min(all_steps, step_lo + per_kb);
+  if (step_lo >= steps) return;              // (the finish kernel reads only K-blocks that exist)
+  stage_step(a, xs + (step_lo & 1) * kStepUnits, step_lo, rin, wave, lane);
+  asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+  for (int step = step_lo; step < steps; ++step) {
+    stage_step(a, xs + ((step + 1) & 1) * kStepUnits, step + 1, rin, wave, lane);
+    const uint4* buf = xs + (step & 1) * kStepUnits;
+    for (int s = 0; s < 8; ++s) {
+      const int kk = step * 8 + 2 * q + (s >> 2);        // this lane's 32-row unit of the factor
+      half8_t wf[kMaxT];
+#pragma unroll
+      for (int t = 0; t < kMaxT; ++t) {
+        wf[t] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
+        if (t < nmine && kk * 32 < a.K) wf[t] = af[t][size_t(kk) * rt * kWave + (s & 3) * 16];
       }
-      if (flagged)
-        *reinterpret_cast<float4_t*>(const_cast<float*>(a.p) + (size_t(sp) * a.total_rows + r0 + row) * PW +
-                                     16 * tile + 4 * q) = acc;
+#pragma unroll
+      for (int mt = 0; mt < kTMT; ++mt)
+        if (mt < mt_n) {
+          const half8_t xf = __builtin_bit_cast(half8_t, buf[(mt * 8 + s) * 64 + lane]);
+#pragma unroll
+          for (int t = 0; t < kMaxT; ++t)
+            if (t < nmine) acc[t][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[t], xf, acc[t][mt], 0, 0, 0);
+        }
+    }
+    // the copy of the next step has landed; everyone is done with this step's half of LDS
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  }
+
+  // lane holds columns 16*tile + 4*q .. +3 of row 16 mt + c
+  float* part = a.partial + size_t(blockIdx.x) * a.total_rows * pitch;
+#pragma unroll
+  for (int t = 0; t < kMaxT; ++t) {
+    const int tile = wave + t * kTileWaves;
+    if (tile >= tiles) continue;
+    const int m = tile / rt, tl = tile - m * rt;
+    const float lam = d.lambda[DUAL ? m : 2];
+#pragma unroll
+    for (int mt = 0; mt < kTMT; ++mt) {
+      const int row = r + 16 * mt + c;
+      if (mt >= mt_n || row >= cnt) continue;
+      *reinterpret_cast<float4_t*>(part + size_t(r0 + row) * pitch + m * a.ls * 32 + 16 * tl + 4 * q) = acc[t][mt] * lam;
     }
   }
 }
 
-// Wavefronts per n-tile: enough split-K that the launch fills the chip (~16 wavefronts per CU)
-// even when few experts are active.
-int pick_kw(int tasks, int waves, int cap) {
-  int best = 1;
-  for (int kw = 1; kw <= cap; kw *= 2)
-    if (waves % kw == 0) {
-      best = kw;
-      if (tasks * kw >= 3072) break;
-    }
-  return best;
+// P[row][col] = fp16(sum over K-blocks of part[kb][row][col]) for rows that take the rank-r term and
+// columns below the rank rounded up to 16; zero elsewhere.  One thread per four columns.
+__global__ __launch_bounds__(256) void xa_finish_kernel(const float* __restrict__ part, int kblocks, int rows, int pitch,
+                                                        int ls32, int rpad, const int32_t* __restrict__ row_pair,
+                                                        int top_k, int top_n, _Float16* __restrict__ P) {
+  const size_t i = size_t(blockIdx.x) * 256 + threadIdx.x;       // index of a group of four columns
+  const int per_row = pitch / 4;
+  if (i >= size_t(rows) * per_row) return;
+  const int row = int(i / per_row), col = int(i - size_t(row) * per_row) * 4;
+  half4_t v = half4_t{0, 0, 0, 0};
+  if ((row_pair[row] % top_k) < top_n && (col % ls32) < rpad) {
+    float4_t sum = *reinterpret_cast<const float4_t*>(part + size_t(row) * pitch + col);
+    for (int kb = 1; kb < kblocks; ++kb)
+      sum += *reinterpret_cast<const float4_t*>(part + (size_t(kb) * rows + row) * pitch + col);
+    v = half4_t{(_Float16)sum[0], (_Float16)sum[1], (_Float16)sum[2], (_Float16)sum[3]};
+  }
+  *reinterpret_cast<half4_t*>(P + size_t(row) * pitch + col) = v;
 }
 
-template <int BITS, int MAXMT>
+template <int BITS>
 hipError_t launch_bits(const FfnArgs& f, hipStream_t s) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    const void* fns[5] = {reinterpret_cast<const void*>(&qgemm_tile_kernel<BITS, true, 2>),
+                          reinterpret_cast<const void*>(&qgemm_tile_kernel<BITS, false, 4>),
+                          reinterpret_cast<const void*>(&qgemm_tile_kernel<BITS, false, 2>),
+                          reinterpret_cast<const void*>(&xa_tile_kernel<true>),
+                          reinterpret_cast<const void*>(&xa_tile_kernel<false>)};
+    for (const void* fn : fns) {
+      hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStepUnits * 16);
+      if (e != hipSuccess) return e;
+    }
+    attr_set = true;
+  }
   int gs = 0;
   while ((1 << gs) < f.group) ++gs;
   KArgs a{};
-  a.desc = f.desc; a.offsets = f.offsets; a.row_pair = f.row_pair;
+  a.desc = f.desc; a.offsets = f.offsets; a.row_pair = f.row_pair; a.n_exp = f.n_exp;
   a.group_shift = gs; a.top_k = f.top_k; a.top_n = f.top_n; a.T = f.T;
-  a.rank = f.rank; a.rpad = f.rpad; a.total_rows = f.total_rows;
+  a.rank = f.rank; a.rpad = f.rpad; a.ls = (f.rank + 31) / 32; a.total_rows = f.total_rows;
   const bool comp = f.rank > 0 && f.top_n > 0 && f.row_pair != nullptr;
-  // experts that can be active at all: at most one per routed pair
-  const int max_active = f.offsets ? std::min(f.n_exp, f.T * f.top_k) : f.n_exp;
-  // an expert can hold up to T rows; with more than 16 a chunk holds fewer k-steps than 8, and the
-  // split-K partial sums of a block must fit its 64 KB of LDS
-  const int kc_max = kLdsUnits / 512;
-  const int kw_cap = f.T <= 16 ? kc_max : (f.T <= 32 ? kc_max / 2 : (MAXMT <= 2 ? std::max(1, kc_max / 4) : 1));
-  constexpr int kWaves = block_waves(MAXMT);   // kw must divide both this and the chunk length
+  // 128-row chunks: at most one partly filled chunk per expert
+  const int items = f.offsets ? f.total_rows / kBM + f.n_exp : f.n_exp * ((f.T + kBM - 1) / kBM);
+  const size_t lds = size_t(2) * kStepUnits * 16;
 
   // W1 | W3 with the SwiGLU epilogue
   a.in = f.xh; a.out = f.h; a.K = f.H; a.N = f.F; a.NT = f.F / kTileN;
   a.in_rt = f.x_rt; a.out_rt = f.h_rt;
   a.KS = padded_k(f.H) / kTileK; a.G = padded_k(f.H) / f.group;
-  a.p = f.p13; a.ksplit = f.ksplit13;
-  a.kw = pick_kw(max_active * a.NT, kWaves, std::min(kw_cap, a.KS));
-  if (comp) hipLaunchKernelGGL(xa_kernel<true>, dim3(a.ksplit, f.n_exp), dim3(256), 0, s, a);
+  // (in A): fp16 result at the start of the buffer, the K-block partial sums behind it
+  auto xa = [&](auto kernel, float* buf, int nm, int ksplit) {
+    const int pitch = nm * a.ls * 32, steps = (a.K + kTileK - 1) / kTileK;
+    const int per_kb = (steps + std::max(1, ksplit) - 1) / std::max(1, ksplit);
+    const int kblocks = (steps + per_kb - 1) / per_kb;      // no K-block without a k-step
+    a.p = buf;
+    a.partial = buf + (size_t(f.total_rows) * pitch / 2 + 63) / 64 * 64;
+    hipLaunchKernelGGL(kernel, dim3(kblocks, items), dim3(64 * kTileWaves), lds, s, a);
+    const size_t groups = size_t(f.total_rows) * pitch / 4;
+    hipLaunchKernelGGL(xa_finish_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, s, a.partial, kblocks,
+                       f.total_rows, pitch, a.ls * 32, a.rpad, f.row_pair, f.top_k, f.top_n, reinterpret_cast<_Float16*>(buf));
+    a.partial = nullptr;
+  };
+  if (comp) xa(xa_tile_kernel<true>, f.p13, 2, f.ksplit13);
   if (f.marks) (void)hipEventRecord(f.marks[0], s);
-  hipLaunchKernelGGL((qgemm_kernel<BITS, true, MAXMT>), dim3((a.NT * a.kw + kWaves - 1) / kWaves, f.n_exp),
-                     dim3(64 * kWaves), 0, s, a);
+  hipLaunchKernelGGL((qgemm_tile_kernel<BITS, true, 2>), dim3((a.NT + 15) / 16, items), dim3(64 * kTileWaves), lds, s, a);
   if (f.marks) (void)hipEventRecord(f.marks[1], s);
   // W2
   a.in = f.h; a.out = f.y_rows; a.K = f.F; a.N = f.H; a.NT = f.H / kTileN;
   a.in_rt = f.h_rt; a.out_rt = 0;
   a.KS = padded_k(f.F) / kTileK; a.G = padded_k(f.F) / f.group;
-  a.p = f.p2; a.ksplit = f.ksplit2;
-  a.kw = pick_kw(max_active * a.NT, kWaves, std::min(kw_cap, a.KS));
-  if (comp) hipLaunchKernelGGL(xa_kernel<false>, dim3(a.ksplit, f.n_exp), dim3(256), 0, s, a);
+  if (comp) xa(xa_tile_kernel<false>, f.p2, 1, f.ksplit2);
   if (f.marks) (void)hipEventRecord(f.marks[2], s);
-  hipLaunchKernelGGL((qgemm_kernel<BITS, false, MAXMT>), dim3((a.NT * a.kw + kWaves - 1) / kWaves, f.n_exp),
-                     dim3(64 * kWaves), 0, s, a);
+  // four n-tiles per wavefront use a fragment of activations twice as often as two, but make
+  // blocks twice as large: take the one with fewer (weighted) rounds of blocks over the 256 CUs
+  // (expected number of chunks: about half of the experts end with a partly filled one)
+  const int chunks = std::max(1, f.offsets ? f.total_rows / kBM + (f.n_exp + 1) / 2 : f.n_exp * ((f.T + kBM - 1) / kBM));
+  auto rounds = [&](int ntw) { return (chunks * ((a.NT + 8 * ntw - 1) / (8 * ntw)) + 255) / 256 * ntw; };
+  if (rounds(4) * 100 <= rounds(2) * 108)
+    hipLaunchKernelGGL((qgemm_tile_kernel<BITS, false, 4>), dim3((a.NT + 31) / 32, items), dim3(64 * kTileWaves), lds, s, a);
+  else
+    hipLaunchKernelGGL((qgemm_tile_kernel<BITS, false, 2>), dim3((a.NT + 15) / 16, items), dim3(64 * kTileWaves), lds, s, a);
   if (f.marks) (void)hipEventRecord(f.marks[3], s);
   return hipGetLastError();
 }
@@ -388,9 +589,9 @@ hipError_t launch_expert_ffn(const FfnArgs& f, hipStream_t s) {
   const int rows = f.offsets ? (f.T * f.top_k + f.n_exp - 1) / f.n_exp : f.T;
   if (rows <= 24) return launch_decode_ffn(f, s);
   switch (f.bits) {
-    case 2: return launch_bits<2, 8>(f, s);
-    case 3: return launch_bits<3, 8>(f, s);
-    case 4: return launch_bits<4, 8>(f, s);
+    case 2: return launch_bits<2>(f, s);
+    case 3: return launch_bits<3>(f, s);
+    case 4: return launch_bits<4>(f, s);
   }
   return hipErrorInvalidValue;
 }

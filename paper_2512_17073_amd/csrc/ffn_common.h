@@ -60,6 +60,7 @@ struct KArgs {
   const float* p;            // split-K partials of (in A): [ksplit][total_rows][PW]
   int K, N, KS, G, NT, group_shift, top_k, top_n, T, rank, rpad, ksplit, total_rows;
   int ls;                    // rank steps of 32 of the B factor: ceil(rank / 32)
+  int n_exp;                 // experts of this launch (many-rows flavour: the grid enumerates row chunks)
   int kw;                    // wavefronts that share one n-tile, each taking every kw-th k-step
   int kb_steps;              // decode flavour: k-steps per K-block (grid.z blocks split K; KS if one)
   float* partial;            // decode flavour, more than one K-block: fp32 partial outputs [kb][rows][N]

@@ -256,6 +256,7 @@ __device__ LRC_BODY_INLINE void decode_body(const KArgs& a, uint4* xs, const int
     }
     const int nk0 = min(KP, KSl);
     stage_issue(0, nk0);                      // (no registers)
+    __builtin_amdgcn_sched_barrier(0);        // (the wait below counts the packed tiles as the only later loads)
     Slot<BITS, NM> ring[RING];
 #pragma unroll
     for (int i = 0; i < RING; ++i) fetch(i, ring[i]);
