@@ -84,7 +84,8 @@ Workspace plan_workspace(const moe_lrc_layer* L, int T) {
   // them, both with the columns padded to a multiple of 32
   w.p13 = take(size_t(L->ksplit13 + 1) * P * 2 * (rpad + 16) * 4 + 256);
   w.p2 = take(size_t(L->ksplit2 + 1) * P * (rpad + 16) * 4 + 256);
-  w.y_part = take(size_t(kMaxKBlocks) * std::max<size_t>(P, size_t(c.n_shared) * T) * c.hidden * 4);
+  w.y_part = take(size_t(kMaxKBlocks) * P * c.hidden * 4);
+  w.sh_y_part = take(size_t(kMaxKBlocks) * c.n_shared * T * c.hidden * 4);   // (shared experts run beside the routed ones)
   w.sh_h = take(c.n_shared ? (size_t(c.n_shared) * T + kActPadRows) * Fp * 2 : 0);
   w.sh_y = take(size_t(c.n_shared) * T * c.hidden * 2);
   w.total = o;
@@ -124,10 +125,15 @@ static void fill_algorithmic_stats(moe_lrc_layer* L, const int32_t* stat) {
   const moe_lrc_config& c = L->cfg;
   const uint64_t P = 3ull * c.hidden * c.ffn;
   moe_lrc_stats& s = L->stats;
-  s.active_experts = stat[0];
-  s.comp_experts = (c.rank > 0 && c.top_n > 0) ? stat[1] : 0;
-  s.bytes_codes = uint64_t(stat[0]) * (P * c.bits / 8) + uint64_t(c.n_shared) * (P * c.shared_bits / 8);
-  s.bytes_meta = uint64_t(stat[0] + c.n_shared) * (P / c.group * 4);
+  int active = 0, comp = 0;
+  for (int e = 0; e < c.n_experts; ++e) {
+    active += stat[2 + e] > 0;
+    comp += stat[2 + c.n_experts + e] > 0;
+  }
+  s.active_experts = active;
+  s.comp_experts = (c.rank > 0 && c.top_n > 0) ? comp : 0;
+  s.bytes_codes = uint64_t(active) * (P * c.bits / 8) + uint64_t(c.n_shared) * (P * c.shared_bits / 8);
+  s.bytes_meta = uint64_t(active + c.n_shared) * (P / c.group * 4);
   s.bytes_factors = uint64_t(s.comp_experts) * 3ull * c.rank * (c.hidden + c.ffn) * 2;
   L->stats_valid = true;
 }
@@ -196,7 +202,7 @@ static int run_shared(moe_lrc_layer* L, const void* x, int T, uint8_t* ws, hipSt
   a.offsets = nullptr; a.row_pair = nullptr; a.xh = xh;
   a.h = reinterpret_cast<_Float16*>(ws + w.sh_h);
   a.x_rt = T + kActPadRows; a.h_rt = c.n_shared * T + kActPadRows;
-  a.y_part = reinterpret_cast<float*>(ws + w.y_part);
+  a.y_part = reinterpret_cast<float*>(ws + w.sh_y_part);
   a.y_rows = ws + w.sh_y; a.ksplit13 = 1; a.ksplit2 = 1; a.total_rows = T * c.n_shared;
   LRC_HIP(launch_expert_ffn(a, stream));
   return MOE_LRC_OK;
@@ -242,9 +248,13 @@ int moe_lrc_layer_create(const moe_lrc_config* cfg, moe_lrc_layer** out) {
   if (cfg->residency == MOE_LRC_STAGED) {
     LRC_TRY(hipHostMalloc((void**)&L->h_w, std::max<size_t>(w, 256), hipHostMallocDefault));
     LRC_TRY(hipHostMalloc((void**)&L->h_f, std::max<size_t>(f, 256), hipHostMallocDefault));
-    LRC_TRY(hipStreamCreateWithFlags(&L->side, hipStreamNonBlocking));
     LRC_TRY(hipEventCreate(&L->ev_t0));
     LRC_TRY(hipEventCreate(&L->ev_t1));
+  }
+  if (cfg->residency == MOE_LRC_STAGED || cfg->n_shared > 0) {   // side stream: copies, or the shared experts
+    LRC_TRY(hipStreamCreateWithFlags(&L->side, hipStreamNonBlocking));
+    LRC_TRY(hipEventCreateWithFlags(&L->ev_fork, hipEventDisableTiming));
+    LRC_TRY(hipEventCreateWithFlags(&L->ev_join, hipEventDisableTiming));
   }
   LRC_TRY(hipMalloc((void**)&L->d_desc, sizeof(ExpertDesc) * L->n_total));
   LRC_TRY(hipMalloc((void**)&L->d_wg, size_t(cfg->n_experts) * cfg->hidden * 2));
@@ -289,6 +299,8 @@ int moe_lrc_layer_destroy(moe_lrc_layer* L) {
   if (L->side) (void)hipStreamDestroy(L->side);
   if (L->ev_t0) (void)hipEventDestroy(L->ev_t0);
   if (L->ev_t1) (void)hipEventDestroy(L->ev_t1);
+  if (L->ev_fork) (void)hipEventDestroy(L->ev_fork);
+  if (L->ev_join) (void)hipEventDestroy(L->ev_join);
   for (auto ev : L->marks)
     if (ev) (void)hipEventDestroy(ev);
   delete L;
@@ -429,12 +441,20 @@ int moe_lrc_forward(moe_lrc_layer* L, const void* x, int T, void* out, void* ws,
   LRC_HIP(launch_permute(L, idx, T, (int32_t*)(b + w.counts), offsets, row_pair, pair_row,
                          (int32_t*)(b + w.comp_counts), s));
   if (mk) LRC_HIP(hipEventRecord(L->marks[MOE_LRC_STAGE_PREP], s));
-  if ((rc = run_expert_ffn(L, x, T, offsets, row_pair, b + w.y_rows, b, s, mk))) return rc;
-  const void* y_shared = nullptr;
-  if (L->cfg.n_shared > 0) {
-    if ((rc = run_shared(L, x, T, b, s))) return rc;
-    y_shared = b + w.sh_y;
+  // Shared experts need nothing from the router: with resident weights they run on the layer's side
+  // stream beside the routed experts (forked here, joined before the combine).  In staged mode the
+  // side stream carries the copies and the shared experts follow the routed ones.
+  const bool fork = L->cfg.n_shared > 0 && L->cfg.residency == MOE_LRC_RESIDENT;
+  const void* y_shared = L->cfg.n_shared > 0 ? b + w.sh_y : nullptr;
+  if (fork) {
+    LRC_HIP(hipEventRecord(L->ev_fork, s));
+    LRC_HIP(hipStreamWaitEvent(L->side, L->ev_fork, 0));
+    if ((rc = run_shared(L, x, T, b, L->side))) return rc;
+    LRC_HIP(hipEventRecord(L->ev_join, L->side));
   }
+  if ((rc = run_expert_ffn(L, x, T, offsets, row_pair, b + w.y_rows, b, s, mk))) return rc;
+  if (fork) LRC_HIP(hipStreamWaitEvent(s, L->ev_join, 0));
+  else if (L->cfg.n_shared > 0 && (rc = run_shared(L, x, T, b, s))) return rc;
   if (mk) LRC_HIP(hipEventRecord(L->marks[MOE_LRC_STAGE_COMBINE], s));
   LRC_HIP(launch_combine(L, b + w.y_rows, tw, pair_row, y_shared, T, out, s));
   if (mk) {

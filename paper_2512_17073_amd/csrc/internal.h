@@ -32,7 +32,7 @@ struct BlobLayout {
 
 struct Workspace {       // carved out of the caller's buffer; all offsets 256-byte aligned
   size_t topk_idx, topk_w, counts, offsets, comp_counts, row_pair, pair_row;
-  size_t y_rows, xh, xh_sh, h, p13, p2, y_part, sh_h, sh_y, total;
+  size_t y_rows, xh, xh_sh, h, p13, p2, y_part, sh_y_part, sh_h, sh_y, total;
 };
 
 }  // namespace lrc
@@ -57,6 +57,7 @@ struct moe_lrc_layer {
   int32_t* h_stat = nullptr;           // pinned mirror
   hipStream_t side = nullptr;
   hipEvent_t ev_t0 = nullptr, ev_t1 = nullptr;   // bracket the staged copies on the side stream
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;   // shared experts on the side stream (resident mode)
   moe_lrc_stats stats{};
   bool stats_valid = false;
   int ksplit13 = 1, ksplit2 = 1;

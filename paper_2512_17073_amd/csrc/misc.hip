@@ -1,5 +1,7 @@
 // Weighted combine (Section 2.1: y = sum_{i in TopK} w_i E_i(x)), the fp16 activation copy with the
 // per-call expert statistics, and the unpack hook that reads the private packed layout back.
+#include <algorithm>
+
 #include "internal.h"
 #include "unpack.h"
 
@@ -52,37 +54,36 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict
   }
 }
 
-// Blocks 0..rows-1 write the fp16 copy of their row's token in operand order (the layout the FFN
-// kernels stage from, see act_unit in ffn_common.h): row R of the routed rows is the token of pair
-// row_pair[R]; without row_pair, row R is token R.  One extra block counts, per expert, the routed
-// rows and the rows that take the rank-r term (what the router-guided transfer must bring in).
-// stat = [active experts, comp-active experts, rows[E], comp rows[E]].
+// Blocks 0..ceil(rows/16)-1 write the fp16 copy of sixteen rows' tokens in operand order (the layout
+// the FFN kernels stage from, see act_unit in ffn_common.h): row R of the routed rows is the token
+// of pair row_pair[R]; without row_pair, row R is token R.  Thread (row r = t % 16, column lane
+// t / 16) converts the 16-byte units t / 16, t / 16 + 16, ... of its row: a wavefront reads 64
+// contiguous bytes of each of its rows and writes runs of 256 bytes (sixteen rows of one unit).
+// The blocks after those count, one wavefront per expert, the routed rows and the rows that take
+// the rank-r term (what the router-guided transfer must bring in): stat = [-, -, rows[E], comp rows[E]].
 __global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ x, int rows, int H,
                                                    uint4* __restrict__ xg, int rt,
                                                    const int32_t* __restrict__ offsets,
                                                    const int32_t* __restrict__ row_pair, int E, int top_k,
                                                    int top_n, int32_t* __restrict__ stat) {
-  if ((int)blockIdx.x == rows) {
-    __shared__ int n_active, n_comp;
-    if (threadIdx.x == 0) { n_active = 0; n_comp = 0; }
-    __syncthreads();
-    for (int e = threadIdx.x; e < E; e += 256) {
-      const int b = offsets[e], n = offsets[e + 1] - b;
-      int comp = 0;
-      for (int r = 0; r < n; ++r) comp += (row_pair[b + r] % top_k) < top_n;
-      stat[2 + e] = n;
-      stat[2 + E + e] = comp;
-      if (n > 0) atomicAdd(&n_active, 1);
-      if (comp > 0) atomicAdd(&n_comp, 1);
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) { stat[0] = n_active; stat[1] = n_comp; }
+  const int row_blocks = (rows + 15) / 16;
+  if ((int)blockIdx.x >= row_blocks) {
+    const int e = ((int)blockIdx.x - row_blocks) * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (e >= E || blockIdx.y != 0) return;
+    const int b = offsets[e], n = offsets[e + 1] - b;
+    int comp = 0;
+    for (int r = lane; r < n; r += 64) comp += (row_pair[b + r] % top_k) < top_n;
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) comp += __shfl_xor(comp, d);
+    if (lane == 0) { stat[2 + e] = n; stat[2 + E + e] = comp; }
     return;
   }
-  const int R = blockIdx.x;
+  const int R = blockIdx.x * 16 + (threadIdx.x & 15);
+  if (R >= rows) return;
   const int t = row_pair ? row_pair[R] / top_k : R;
   const uint4* xrow = reinterpret_cast<const uint4*>(x + size_t(t) * H);
-  for (int k8 = threadIdx.x; k8 < H / 8; k8 += 256) {
+  // (grid.y splits the columns when there are few rows, so that the launch still fills the chip)
+  for (int k8 = blockIdx.y * 16 + (threadIdx.x >> 4); k8 < H / 8; k8 += 16 * gridDim.y) {
     const uint4 v = xrow[k8];
     const uint32_t in[4] = {v.x, v.y, v.z, v.w};
     uint32_t o[4];
@@ -131,9 +132,11 @@ hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _
                             hipStream_t s) {
   const moe_lrc_config& c = L->cfg;
   const int rows = row_pair ? T * c.top_k : T;
-  hipLaunchKernelGGL(prep_kernel, dim3(rows + (stat ? 1 : 0)), dim3(256), 0, s, (const uint16_t*)x_bf16, rows,
-                     c.hidden, reinterpret_cast<uint4*>(xg), rt, offsets, row_pair, c.n_experts, c.top_k, c.top_n,
-                     stat);
+  const int row_blocks = (rows + 15) / 16;
+  const int ky = std::max(1, std::min(c.hidden / 128, 256 / std::max(1, row_blocks)));
+  hipLaunchKernelGGL(prep_kernel, dim3(row_blocks + (stat ? (c.n_experts + 3) / 4 : 0), ky), dim3(256), 0, s,
+                     (const uint16_t*)x_bf16, rows, c.hidden, reinterpret_cast<uint4*>(xg), rt, offsets, row_pair,
+                     c.n_experts, c.top_k, c.top_n, stat);
   return hipGetLastError();
 }
 
