@@ -29,7 +29,7 @@ MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16/bf16 MFMA, published
 # scaled by what the same counter reads for an elementwise kernel of known size; two separate
 # profiler runs of this script, summarised in profiles/).  Counters cannot be read from inside a
 # timed run, so the figure is carried here per workload; workloads not profiled report null.
-MEASURED_TRAFFIC_BYTES = {"mixtral_decode_T64_b2": 343.8e6}
+MEASURED_TRAFFIC_BYTES = {"mixtral_decode_T64_b2": 325.4e6}
 
 
 def algorithmic_bytes(cfg, T, active, comp):
@@ -84,6 +84,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true", help="replay one captured HIP graph per layer instance instead of launching eagerly")
     ap.add_argument("--cpu-tokens", type=int, default=64, help="tokens whose expert FFN the CPU oracle evaluates")
+    ap.add_argument("--staged", action="store_true",
+                    help="also time one layer in staged residency (packed experts and factors copied from the "
+                         "pinned pool per call, chosen by the router) and report it under 'staging'; "
+                         "never part of 'value'")
     ap.add_argument("--calib-copy", action="store_true",
                     help="after the timed region run an elementwise kernel that reads and writes 256 MiB, "
                          "so that a counter run can scale FETCH_SIZE / WRITE_SIZE by a known transfer")
@@ -189,11 +193,21 @@ def main():
     ab = algorithmic_bytes(cfg, T, st["active_experts"], st["comp_experts"])
     flops = algorithmic_flops(cfg, T)
     dom = "w13"
-    achieved = ab[dom] / (stage_avg[dom] * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "packed W1|W3 product + SwiGLU (qgemm_decode_kernel<bits,true> at decode sizes)",
-                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
-                "bytes_per_launch": int(ab[dom]), "avg_ms": round(stage_avg[dom], 5)}
+    rows_per_expert = T * cfg.top_k / cfg.n_experts
+    if rows_per_expert > 24:
+        # many rows per expert: the fused W1|W3 launch is a grouped GEMM, bound by the matrix cores
+        w13_flops = T * cfg.top_k * 2 * 2 * cfg.hidden * cfg.ffn + T * cfg.top_n * 2 * 2 * cfg.rank * cfg.ffn
+        achieved = w13_flops / (stage_avg[dom] * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": "packed W1|W3 product + SwiGLU (qgemm_tile_kernel<bits,true,2>: 128-row chunks)",
+                    "achieved": round(achieved, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(achieved / MFMA_F16_PEAK_TFLOPS, 4), "traffic": None,
+                    "flops_per_launch": int(w13_flops), "avg_ms": round(stage_avg[dom], 5)}
+    else:
+        achieved = ab[dom] / (stage_avg[dom] * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "packed W1|W3 product + SwiGLU (qgemm_decode_kernel<bits,true> at decode sizes)",
+                    "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
+                    "bytes_per_launch": int(ab[dom]), "avg_ms": round(stage_avg[dom], 5)}
     path_kernel_ms = sum(stage_avg.values())
     result = {
         "metric": "MoE-layer tokens/s (one layer forward, weights resident in HBM)",
@@ -214,6 +228,33 @@ def main():
                        "mfma_frac": round(flops / (ms_per_step * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4),
                        "stage_ms": {k: round(v, 5) for k, v in stage_avg.items()}},
     }
+    staging = None
+    if args.staged:
+        print("[bench] staged residency: one layer, packed experts copied from the pinned pool per call", file=sys.stderr, flush=True)
+        Ls = amd.Layer.from_config(cfg, residency=amd.STAGED)
+        Ls.set_gate(wg, bias)
+        for e in range(n_all):
+            for m in (0, 1, 2):
+                a = experts[e][m]
+                Ls.set_expert(e, m, a["codes"], a["scale"], a["zero"], a["A"], a["B"])
+        for _ in range(3):
+            Ls.forward_raw(x.data_ptr(), T, out.data_ptr(), ws.data_ptr(), ws_bytes, stream)
+        torch.cuda.synchronize()
+        reps_s = 20
+        copy_ms = []
+        t0s = time.perf_counter()
+        for _ in range(reps_s):
+            Ls.forward_raw(x.data_ptr(), T, out.data_ptr(), ws.data_ptr(), ws_bytes, stream)
+            torch.cuda.synchronize()
+            copy_ms.append(Ls.stats()["stage_ms"])
+        dts = (time.perf_counter() - t0s) / reps_s * 1e3
+        sst = Ls.stats()
+        moved = sst["bytes_codes"] + sst["bytes_meta"] + sst["bytes_factors"]
+        staging = {"ms_per_step_incl_copies": round(dts, 4), "copy_ms": round(float(np.mean(copy_ms)), 4),
+                   "bytes_per_step": int(moved), "copy_gbs": round(moved / (float(np.mean(copy_ms)) * 1e-3) / 1e9, 1),
+                   "tokens_per_s_incl_copies": round(T / (dts * 1e-3), 1),
+                   "experts_copied": int(sst["active_experts"]), "factor_sets_copied": int(sst["comp_experts"])}
+        Ls.close()
     if args.calib_copy:
         src = torch.zeros(64 << 20, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
@@ -221,6 +262,8 @@ def main():
             torch.add(src, 1.0, out=dst)        # reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
         del src, dst
+    if staging is not None:
+        result["staging"] = staging
     if not args.no_cpu_baseline:
         print("[bench] timing the CPU oracle on a bounded sample", file=sys.stderr, flush=True)
         result["cpu_baseline"] = cpu_baseline(cfg, layer, x_bits, args.cpu_tokens)
