@@ -50,7 +50,7 @@ extern "C" {
                              /* per call through a device slot pool on a side stream      */
 
 typedef struct {
-  int32_t hidden;       /* H, multiple of 64                                              */
+  int32_t hidden;       /* H, multiple of 64, at most 16384                               */
   int32_t ffn;          /* F, multiple of 64                                              */
   int32_t n_experts;    /* E routed experts, 1..256                                       */
   int32_t n_shared;     /* S always-on shared experts (Table 1 note), 0..8                */

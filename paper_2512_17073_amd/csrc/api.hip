@@ -48,6 +48,7 @@ static int check_config(const moe_lrc_config& c) {
   auto bad = [](const char* what) { return set_error(MOE_LRC_EINVAL, std::string("config: ") + what); };
   auto shape = [](const char* what) { return set_error(MOE_LRC_ESHAPE, std::string("config: ") + what); };
   if (c.hidden <= 0 || c.ffn <= 0) return bad("hidden and ffn must be positive");
+  if (c.hidden > 16384 || c.ffn > 65536) return shape("hidden above 16384 or ffn above 65536");
   if (c.n_experts < 1 || c.n_experts > 256) return bad("n_experts must be in 1..256");
   if (c.n_shared < 0 || c.n_shared > 8) return bad("n_shared must be in 0..8");
   if (c.top_k < 1 || c.top_k > 16 || c.top_k > c.n_experts) return bad("top_k must be in 1..min(n_experts,16)");
@@ -180,6 +181,7 @@ static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t*
   a.rank = c.rank; a.rpad = L->routed.mat[0].rpad;
   a.H = c.hidden; a.F = c.ffn; a.top_k = c.top_k; a.top_n = c.top_n; a.T = T;
   a.offsets = offsets; a.row_pair = row_pair; a.xh = xh;
+  a.comp_rows = L->d_stat + 2 + c.n_experts;
   a.h = reinterpret_cast<_Float16*>(ws + w.h);
   a.x_rt = P + kActPadRows; a.h_rt = P + kActPadRows;
   a.p13 = reinterpret_cast<float*>(ws + w.p13); a.p2 = reinterpret_cast<float*>(ws + w.p2);

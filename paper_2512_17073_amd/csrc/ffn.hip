@@ -136,7 +136,8 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
   const int tile0 = (blockIdx.x * kTileWaves + wave) * kNTW;
 
   const int code_bytes = a.KS * a.NT * tdw * 4, meta_bytes = a.G * a.NT * kTileN * 4;
-  const bool lowrank = a.rank > 0 && __builtin_amdgcn_readfirstlane(d.has_factors) != 0 && a.row_pair != nullptr;
+  const bool lowrank = a.rank > 0 && __builtin_amdgcn_readfirstlane(d.has_factors) != 0 && a.row_pair != nullptr &&
+                       __builtin_amdgcn_readfirstlane(a.comp_rows[e]) > 0;
   const int LS = lowrank ? a.ls : 0;
   const int bf_bytes = a.NT * a.ls * 1024;
   __amdgpu_buffer_rsrc_t code_rs[NM], meta_rs[NM], bf_rs[NM];
@@ -421,7 +422,7 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void xa_tile_kernel(KArgs a) {
   if (!find_chunk(a, blockIdx.y, ch)) return;
   const int e = ch.e, r0 = ch.r0, cnt = ch.cnt, r = ch.r;
   const ExpertDesc& d = a.desc[e];
-  if (!d.has_factors) return;
+  if (!d.has_factors || a.comp_rows[e] == 0) return;
   const int th = threadIdx.x, lane = th & 63;
   const int wave = __builtin_amdgcn_readfirstlane(th >> 6);
   const int q = lane >> 4, c = lane & 15;
@@ -534,7 +535,7 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s) {
   int gs = 0;
   while ((1 << gs) < f.group) ++gs;
   KArgs a{};
-  a.desc = f.desc; a.offsets = f.offsets; a.row_pair = f.row_pair; a.n_exp = f.n_exp;
+  a.desc = f.desc; a.offsets = f.offsets; a.row_pair = f.row_pair; a.comp_rows = f.comp_rows; a.n_exp = f.n_exp;
   a.group_shift = gs; a.top_k = f.top_k; a.top_n = f.top_n; a.T = f.T;
   a.rank = f.rank; a.rpad = f.rpad; a.ls = (f.rank + 31) / 32; a.total_rows = f.total_rows;
   const bool comp = f.rank > 0 && f.top_n > 0 && f.row_pair != nullptr;

@@ -54,6 +54,8 @@ struct KArgs {
   const ExpertDesc* desc;
   const int32_t* offsets;    // null: shared experts, expert e owns rows e*T .. e*T+T-1
   const int32_t* row_pair;   // null: rows are tokens
+  const int32_t* comp_rows;  // per expert: rows that take the rank-r term (an expert with none skips it:
+                             // in staged residency its factors were not brought in)
   const _Float16* in;        // activations in operand order (act_unit), in_rt rows: gathered x, or h
   void* out;                 // DUAL: h in operand order (out_rt rows); else y_rows [rows][N] bf16
   int in_rt, out_rt;         // row counts (incl. padding) of the operand-order buffers

@@ -127,7 +127,8 @@ __device__ LRC_BODY_INLINE void decode_body(const KArgs& a, uint4* xs, const int
 #ifdef LRC_EXP_NOLOWRANK
   const bool lowrank = false;
 #else
-  const bool lowrank = a.rank > 0 && has_factors && a.row_pair != nullptr && blockIdx.z == 0;
+  const bool lowrank = a.rank > 0 && has_factors && a.row_pair != nullptr && blockIdx.z == 0 &&
+                       __builtin_amdgcn_readfirstlane(a.comp_rows[e]) > 0;
 #endif
   const int LS = lowrank ? a.ls : 0;
   float lam[NM];
@@ -563,7 +564,7 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s) {
   int gs = 0;
   while ((1 << gs) < f.group) ++gs;
   KArgs a{};
-  a.desc = f.desc; a.offsets = f.offsets; a.row_pair = f.row_pair;
+  a.desc = f.desc; a.offsets = f.offsets; a.row_pair = f.row_pair; a.comp_rows = f.comp_rows;
   a.group_shift = gs; a.top_k = f.top_k; a.top_n = f.top_n; a.T = f.T;
   a.rank = f.rank; a.rpad = f.rpad; a.ls = (f.rank + 31) / 32; a.total_rows = f.total_rows; a.kw = 1; a.ksplit = 1;
   const bool comp = f.rank > 0 && f.top_n > 0 && f.row_pair != nullptr;

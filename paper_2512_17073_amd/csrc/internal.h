@@ -91,6 +91,7 @@ struct FfnArgs {
   int H, F, top_k, top_n, T;
   const int32_t* offsets;     // [n_exp+1] or null: shared experts, rows e*T .. e*T+T-1
   const int32_t* row_pair;    // null for shared experts (row -> token = row % T)
+  const int32_t* comp_rows;   // [n_exp] rows that take the rank-r term (written by the prep kernel), or null
   const _Float16* xh;         // gathered activations in operand order, x_rt rows (routed: one per pair)
   _Float16* h;                // SwiGLU output in operand order, h_rt rows
   int x_rt, h_rt;

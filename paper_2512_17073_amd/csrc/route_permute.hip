@@ -20,10 +20,13 @@ __device__ inline double wave_sum(double v) {
 // of experts w, w+4, ...: every bf16 x bf16 product is exact in fp64, so the logits differ from the
 // exact ones by ~1e-13 and the selection equals the exact selection.  The same instruction
 // sequence runs for every expert row, so duplicated gate rows give bit-identical logits.
-// Wavefront 0 then takes the Top-k with a shuffle arg-max (ties to the lower index) and the
-// softmax weights of the selected experts.
+// A lane keeps its 16-byte chunks of the token (chunks lane, lane + 64, ...: CH of them) in
+// registers for all experts, and the chunks of the next expert's gate row are in flight while the
+// current one is multiplied.  Wavefront 0 then takes the Top-k with a shuffle arg-max (ties to the
+// lower index) and the softmax weights of the selected experts.
 constexpr int kMaxExperts = 256;
 
+template <int CH>
 __global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__ x,
                                                     const uint16_t* __restrict__ wg,
                                                     const float* __restrict__ bias, int T, int H, int E,
@@ -49,30 +52,38 @@ __global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__
     }
   }
 
+  uint4 xv[CH];
+#pragma unroll
+  for (int j = 0; j < CH; ++j) {
+    const int c = lane + 64 * j;
+    xv[j] = c < chunks ? xrow[c] : make_uint4(0, 0, 0, 0);
+  }
+  auto load_row = [&](int e, uint4 (&wv)[CH]) {
+    const uint4* wrow = reinterpret_cast<const uint4*>(wg + size_t(min(e, E - 1)) * H);
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+      const int c = lane + 64 * j;
+      wv[j] = c < chunks ? wrow[c] : make_uint4(0, 0, 0, 0);
+    }
+  };
+  uint4 wcur[CH], wnext[CH];
+  load_row(wave, wcur);
   for (int e = wave; e < E; e += 4) {
-    const uint4* wrow = reinterpret_cast<const uint4*>(wg + size_t(e) * H);
+    load_row(e + 4, wnext);                               // (clamped past the last row; unused then)
     double acc = 0.0;
-    for (int c0 = lane; c0 < chunks; c0 += 64 * 8) {      // eight chunks of both rows in flight
-      uint4 xv[8], wv[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int c = c0 + 64 * u;
-        xv[u] = make_uint4(0, 0, 0, 0);
-        wv[u] = make_uint4(0, 0, 0, 0);
-        if (c < chunks) { xv[u] = xrow[c]; wv[u] = wrow[c]; }
-      }
+    for (int j = 0; j < CH; ++j) {                        // chunks in increasing order, as a plain loop would
+      const uint32_t xa[4] = {xv[j].x, xv[j].y, xv[j].z, xv[j].w}, wa[4] = {wcur[j].x, wcur[j].y, wcur[j].z, wcur[j].w};
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {                       // same accumulation order as a plain loop
-        const uint32_t xa[4] = {xv[u].x, xv[u].y, xv[u].z, xv[u].w}, wa[4] = {wv[u].x, wv[u].y, wv[u].z, wv[u].w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          acc = fma(bf16_to_double(xa[i] & 0xffffu), bf16_to_double(wa[i] & 0xffffu), acc);
-          acc = fma(bf16_to_double(xa[i] >> 16), bf16_to_double(wa[i] >> 16), acc);
-        }
+      for (int i = 0; i < 4; ++i) {
+        acc = fma(bf16_to_double(xa[i] & 0xffffu), bf16_to_double(wa[i] & 0xffffu), acc);
+        acc = fma(bf16_to_double(xa[i] >> 16), bf16_to_double(wa[i] >> 16), acc);
       }
     }
     acc = wave_sum(acc);
     if (lane == 0) logit[e] = acc + (bias ? (double)bias[e] : 0.0);
+#pragma unroll
+    for (int j = 0; j < CH; ++j) wcur[j] = wnext[j];
   }
   __syncthreads();
   if (wave != 0) return;
@@ -201,9 +212,19 @@ __global__ __launch_bounds__(1024) void permute_kernel(const int32_t* __restrict
 hipError_t launch_route(const moe_lrc_layer* L, const void* x, int T, int32_t* idx, float* w,
                         _Float16* xh, hipStream_t s) {
   const moe_lrc_config& c = L->cfg;
-  hipLaunchKernelGGL(route_kernel, dim3(T), dim3(256), 0, s, (const uint16_t*)x, L->d_wg,
-                     L->has_bias ? L->d_bias : nullptr, T, c.hidden, c.n_experts, c.top_k,
-                     c.renormalize, idx, w, xh);
+  const int ch = (c.hidden / 8 + 63) / 64;      // 16-byte chunks of a row per lane
+  auto go = [&](auto kernel) {
+    hipLaunchKernelGGL(kernel, dim3(T), dim3(256), 0, s, (const uint16_t*)x, L->d_wg,
+                       L->has_bias ? L->d_bias : nullptr, T, c.hidden, c.n_experts, c.top_k,
+                       c.renormalize, idx, w, xh);
+  };
+  if (ch <= 1) go(route_kernel<1>);
+  else if (ch <= 2) go(route_kernel<2>);
+  else if (ch <= 4) go(route_kernel<4>);
+  else if (ch <= 8) go(route_kernel<8>);
+  else if (ch <= 16) go(route_kernel<16>);
+  else if (ch <= 32) go(route_kernel<32>);
+  else return hipErrorInvalidValue;             // hidden > 16384 (layer_create rejects it)
   return hipGetLastError();
 }
 

@@ -44,6 +44,12 @@ SMALL = {
     "tiny_b4_n2": configs.TINY.with_(bits=4, top_n=2, rank=16, name="tiny_b4_n2"),
     # > 32 rows per expert: exercises two row tiles and the row-chunk loop, ragged tails
     "tiny_T200": configs.TINY.with_(tokens=200, name="tiny_T200"),
+    # several 128-row chunks per expert with a ragged last one; a rank that is no multiple of 16 or 32
+    # (padding columns of the factors) at 4 bit
+    "tiny_T700_r40": configs.TINY.with_(tokens=700, rank=40, bits=4, name="tiny_T700_r40"),
+    # heavily skewed routing at decode size: some experts get more than 32 rows (several passes of
+    # the decode kernel), others none
+    "tiny_skew": configs.TINY.with_(tokens=44, gate_kind="unit", gate_std=1.0, zipf_s=3.0, name="tiny_skew"),
     "tiny_T1": configs.TINY.with_(tokens=1, name="tiny_T1"),
     "tiny_renorm": configs.TINY.with_(renormalize=1, tokens=33, name="tiny_renorm"),
     # DeepSeek-shaped: shared experts at 4 bit, FFN 1408 (not a multiple of the 256-row k-step), k=6
@@ -193,8 +199,21 @@ def test_staged_mode_matches_resident(amd):
     import torch
     cfg = configs.TINY.with_(tokens=5, name="staged")     # few tokens: some experts stay on the host
     layer = fixtures.build_layer(cfg)
-    Lr = amd.Layer.from_config(cfg, max_tokens=16)
+    # The device slots of a staged layer start out with whatever the allocation held.  Make that
+    # NaN factors (a resident layer with poisoned factors, destroyed right before): an expert whose
+    # factors are not brought in must not touch its factor slot.
+    import copy
+    poison = copy.deepcopy(layer)
+    for ex in poison["experts"]:
+        for a in ex.values():
+            if a.get("A") is not None and np.size(a["A"]):
+                a["A"] = np.full_like(a["A"], 0x7FC0)
+                a["B"] = np.full_like(a["B"], 0x7FC0)
+    Lp = amd.Layer.from_config(cfg, max_tokens=16)
+    Lp.load(poison)
+    Lp.close()
     Ls = amd.Layer.from_config(cfg, max_tokens=16, residency=amd.STAGED)
+    Lr = amd.Layer.from_config(cfg, max_tokens=16)
     Lr.load(layer); Ls.load(layer)
     x_bits = synth.make_tokens(cfg)
     x = amd.bf16_tensor(x_bits)
