@@ -518,7 +518,7 @@ __global__ __launch_bounds__(256) void xa_finish_kernel(const float* __restrict_
 }
 
 template <int BITS>
-hipError_t launch_bits(const FfnArgs& f, hipStream_t s) {
+hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
   static bool attr_set = false;
   if (!attr_set) {
     const void* fns[5] = {reinterpret_cast<const void*>(&qgemm_tile_kernel<BITS, true, 2>),
@@ -543,10 +543,6 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s) {
   const int items = f.offsets ? f.total_rows / kBM + f.n_exp : f.n_exp * ((f.T + kBM - 1) / kBM);
   const size_t lds = size_t(2) * kStepUnits * 16;
 
-  // W1 | W3 with the SwiGLU epilogue
-  a.in = f.xh; a.out = f.h; a.K = f.H; a.N = f.F; a.NT = f.F / kTileN;
-  a.in_rt = f.x_rt; a.out_rt = f.h_rt;
-  a.KS = padded_k(f.H) / kTileK; a.G = padded_k(f.H) / f.group;
   // (in A): fp16 result at the start of the buffer, the K-block partial sums behind it
   auto xa = [&](auto kernel, float* buf, int nm, int ksplit) {
     const int pitch = nm * a.ls * 32, steps = (a.K + kTileK - 1) / kTileK;
@@ -560,10 +556,17 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s) {
                        f.total_rows, pitch, a.ls * 32, a.rpad, f.row_pair, f.top_k, f.top_n, reinterpret_cast<_Float16*>(buf));
     a.partial = nullptr;
   };
+  if (which & 1) {
+  // W1 | W3 with the SwiGLU epilogue
+  a.in = f.xh; a.out = f.h; a.K = f.H; a.N = f.F; a.NT = f.F / kTileN;
+  a.in_rt = f.x_rt; a.out_rt = f.h_rt;
+  a.KS = padded_k(f.H) / kTileK; a.G = padded_k(f.H) / f.group;
   if (comp) xa(xa_tile_kernel<true>, f.p13, 2, f.ksplit13);
   if (f.marks) (void)hipEventRecord(f.marks[0], s);
   hipLaunchKernelGGL((qgemm_tile_kernel<BITS, true, 2>), dim3((a.NT + 15) / 16, items), dim3(64 * kTileWaves), lds, s, a);
   if (f.marks) (void)hipEventRecord(f.marks[1], s);
+  }
+  if (which & 2) {
   // W2
   a.in = f.h; a.out = f.y_rows; a.K = f.F; a.N = f.H; a.NT = f.H / kTileN;
   a.in_rt = f.h_rt; a.out_rt = 0;
@@ -580,21 +583,37 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s) {
   else
     hipLaunchKernelGGL((qgemm_tile_kernel<BITS, false, 2>), dim3((a.NT + 15) / 16, items), dim3(64 * kTileWaves), lds, s, a);
   if (f.marks) (void)hipEventRecord(f.marks[3], s);
+  }
   return hipGetLastError();
 }
 
 }  // namespace
 
+// Which flavour a projection takes (measured on Mixtral, DeepSeek and Qwen3 shapes): the decode
+// flavour up to 24 rows per expert; beyond that the grouped GEMM as soon as it is efficient: the
+// fused W1|W3 from about 40 rows per expert on, W2 (whose grid has few column blocks) once its grid
+// of (128-row chunk, 256 columns) blocks covers the 256 CUs.
+#ifndef LRC_DECODE_MAX_ROWS13
+#define LRC_DECODE_MAX_ROWS13 40
+#endif
+
 hipError_t launch_expert_ffn(const FfnArgs& f, hipStream_t s) {
-  // expected rows per expert under uniform routing decides the flavour
+  // expected rows per expert under uniform routing decides the flavour of each projection
   const int rows = f.offsets ? (f.T * f.top_k + f.n_exp - 1) / f.n_exp : f.T;
-  if (rows <= 24) return launch_decode_ffn(f, s);
-  switch (f.bits) {
-    case 2: return launch_bits<2>(f, s);
-    case 3: return launch_bits<3>(f, s);
-    case 4: return launch_bits<4>(f, s);
-  }
-  return hipErrorInvalidValue;
+  auto tile = [&](int which) {
+    switch (f.bits) {
+      case 2: return launch_bits<2>(f, s, which);
+      case 3: return launch_bits<3>(f, s, which);
+      case 4: return launch_bits<4>(f, s, which);
+    }
+    return hipErrorInvalidValue;
+  };
+  const int chunks = f.offsets ? f.total_rows / kBM + (f.n_exp + 1) / 2 : f.n_exp * ((f.T + kBM - 1) / kBM);
+  const bool w2_grid_full = chunks * ((f.H / kTileN + 15) / 16) >= 256;
+  hipError_t e = rows <= LRC_DECODE_MAX_ROWS13 ? launch_decode_ffn(f, s, 1) : tile(1);
+  if (e != hipSuccess) return e;
+  // (beyond 128 rows per expert the decode flavour would stream the weights five times or more)
+  return rows <= 24 || (!w2_grid_full && rows <= 128) ? launch_decode_ffn(f, s, 2) : tile(2);
 }
 
 }  // namespace lrc

@@ -96,7 +96,8 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 }  // namespace ffn
 
-// decode flavour (ffn_decode.hip): few rows per expert, one 16-wavefront block per CU
-hipError_t launch_decode_ffn(const FfnArgs& f, hipStream_t s);
+// decode flavour (ffn_decode.hip): few rows per expert, one 16-wavefront block per CU.
+// which: bit 0 = the fused W1|W3 projection (with its (x A) kernel), bit 1 = W2 (with its (h A) kernel)
+hipError_t launch_decode_ffn(const FfnArgs& f, hipStream_t s, int which);
 
 }  // namespace lrc

@@ -549,7 +549,7 @@ __global__ __launch_bounds__(256) void reduce_kernel(const float* __restrict__ p
 }
 
 template <int BITS>
-hipError_t launch_bits(const FfnArgs& f, hipStream_t s) {
+hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
   static bool attr_set = false;
   if (!attr_set) {
     // 128 KB of activations + up to 32 KB of (in A) for 32 rows at rank 256 = all 160 KB of a CU
@@ -580,6 +580,7 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s) {
   auto lds_bytes = [&](int nm) { return size_t(kDecodeLdsUnits) * 16 + (comp ? size_t(nm) * a.ls * 2 * 1024 : 0); };
   auto xa_blocks = [](int K) { return std::max(1, std::min(8, K / 1024)); };   // K-blocks of the (in A) kernels
 
+  if (which & 1) {
   // W1 | W3 with the SwiGLU epilogue
   a.in = f.xh; a.out = f.h; a.K = f.H; a.N = f.F; a.NT = f.F / kTileN;
   a.in_rt = f.x_rt; a.out_rt = f.h_rt;
@@ -591,6 +592,8 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s) {
   hipLaunchKernelGGL((qgemm_decode_kernel<BITS, true>), dim3(blocks_per_expert(a.NT, 1), f.n_exp, 1),
                      dim3(64 * kDecodeWaves), lds_bytes(2), s, a);
   if (f.marks) (void)hipEventRecord(f.marks[1], s);
+  }
+  if (which & 2) {
   // W2
   a.in = f.h; a.out = f.y_rows; a.K = f.F; a.N = f.H; a.NT = f.H / kTileN;
   a.in_rt = f.h_rt; a.out_rt = 0;
@@ -611,6 +614,7 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s) {
                        size_t(f.total_rows) * f.H, units, reinterpret_cast<uint2*>(f.y_rows));
   }
   if (f.marks) (void)hipEventRecord(f.marks[3], s);
+  }
   return hipGetLastError();
 }
 
@@ -622,11 +626,11 @@ extern "C" int moe_lrc_debug_timeline(long long* host_out) {
 }
 #endif
 
-hipError_t launch_decode_ffn(const FfnArgs& f, hipStream_t s) {
+hipError_t launch_decode_ffn(const FfnArgs& f, hipStream_t s, int which) {
   switch (f.bits) {
-    case 2: return launch_bits<2>(f, s);
-    case 3: return launch_bits<3>(f, s);
-    case 4: return launch_bits<4>(f, s);
+    case 2: return launch_bits<2>(f, s, which);
+    case 3: return launch_bits<3>(f, s, which);
+    case 4: return launch_bits<4>(f, s, which);
   }
   return hipErrorInvalidValue;
 }
