@@ -194,7 +194,7 @@ def main():
     flops = algorithmic_flops(cfg, T)
     dom = "w13"
     rows_per_expert = T * cfg.top_k / cfg.n_experts
-    if rows_per_expert > 24:
+    if rows_per_expert > 40:     # (the library takes the grouped-GEMM flavour for W1|W3 from there on)
         # many rows per expert: the fused W1|W3 launch is a grouped GEMM, bound by the matrix cores
         w13_flops = T * cfg.top_k * 2 * 2 * cfg.hidden * cfg.ffn + T * cfg.top_n * 2 * 2 * cfg.rank * cfg.ffn
         achieved = w13_flops / (stage_avg[dom] * 1e-3) / 1e12
