@@ -259,3 +259,40 @@ def test_hot_path_argument_errors(amd):
                      np.zeros((4, 512), np.uint16), np.zeros((256, 8), np.uint16), np.zeros((8, 512), np.uint16))
     assert ei.value.code == -1                    # code out of range for 3 bits
     L.close()
+
+
+@pytest.mark.parametrize("name", ["tiny", "deepseek_small"])
+def test_forward_under_graph_capture_replays_like_eager(amd, name):
+    """moe_lrc_forward allocates nothing, never synchronises in resident mode and clears nothing with
+    a memset, so it can be captured into a HIP graph (with shared experts the capture forks to the
+    layer's side stream and joins again).  Every replay, with the program's own eager work and
+    synchronisations in between, must give the bits of the eager call on the same tokens."""
+    import torch
+    cfg = SMALL[name]
+    layer = fixtures.build_layer(cfg)
+    L = amd.Layer.from_config(cfg)
+    L.load(layer)
+    T = cfg.tokens
+    xs = [amd.bf16_tensor(synth.make_tokens(cfg.with_(seed=cfg.seed + 17 * i))) for i in range(3)]
+    eager = [L.forward(x).clone() for x in xs]           # (also the warm-up: function attributes are set)
+    torch.cuda.synchronize()
+    x_static = xs[0].clone()
+    out = torch.empty((T, cfg.hidden), dtype=torch.bfloat16, device="cuda")
+    ws = L.workspace(T)
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            L.forward_raw(x_static.data_ptr(), T, out.data_ptr(), ws.data_ptr(), ws.numel(),
+                          torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    for rep in range(2):
+        for i, x in enumerate(xs):
+            x_static.copy_(x)
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out.view(torch.int16), eager[i].view(torch.int16)), (rep, i)
+            again = L.forward(x)                          # eager work between the replays
+            torch.cuda.synchronize()
+            assert torch.equal(again.view(torch.int16), eager[i].view(torch.int16))
+    L.close()
