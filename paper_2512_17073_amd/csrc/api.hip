@@ -89,6 +89,7 @@ Workspace plan_workspace(const moe_lrc_layer* L, int T) {
   w.sh_y_part = take(size_t(kMaxKBlocks) * c.n_shared * T * c.hidden * 4);   // (shared experts run beside the routed ones)
   w.sh_h = take(c.n_shared ? (size_t(c.n_shared) * T + kActPadRows) * Fp * 2 : 0);
   w.sh_y = take(size_t(c.n_shared) * T * c.hidden * 2);
+  w.plan = take(size_t(plan_blocks(c.n_experts, int(P), c.ffn / 16) + plan_blocks(c.n_experts, int(P), c.hidden / 16)) * 16);
   w.total = o;
   return w;
 }
@@ -186,6 +187,7 @@ static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t*
   a.x_rt = P + kActPadRows; a.h_rt = P + kActPadRows;
   a.p13 = reinterpret_cast<float*>(ws + w.p13); a.p2 = reinterpret_cast<float*>(ws + w.p2);
   a.y_part = reinterpret_cast<float*>(ws + w.y_part);
+  a.plan = reinterpret_cast<int32_t*>(ws + w.plan);
   a.y_rows = y_rows; a.ksplit13 = L->ksplit13; a.ksplit2 = L->ksplit2; a.total_rows = T * c.top_k;
   a.marks = mark ? &L->marks[MOE_LRC_STAGE_W13] : nullptr;
   LRC_HIP(launch_expert_ffn(a, stream));

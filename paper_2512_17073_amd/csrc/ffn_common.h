@@ -66,6 +66,8 @@ struct KArgs {
   int kw;                    // wavefronts that share one n-tile, each taking every kw-th k-step
   int kb_steps;              // decode flavour: k-steps per K-block (grid.z blocks split K; KS if one)
   float* partial;            // decode flavour, more than one K-block: fp32 partial outputs [kb][rows][N]
+  const int32_t* plan;       // decode flavour: null (grid = blocks per expert x experts), or for block
+                             // blockIdx.x the ints (expert or -1, block of the expert, blocks of the expert, -)
 };
 
 __device__ inline uint32_t f32x2_to_bf16x2(float a, float b) {

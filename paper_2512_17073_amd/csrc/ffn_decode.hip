@@ -85,7 +85,8 @@ template <class T> __device__ inline const T* uniform_ptr(const T* p) {
 }
 
 template <int BITS, bool DUAL, int MT>
-__device__ LRC_BODY_INLINE void decode_body(const KArgs& a, uint4* xs, const int e, const int r0, const int cnt) {
+__device__ LRC_BODY_INLINE void decode_body(const KArgs& a, uint4* xs, const int e, const int r0, const int cnt,
+                                            const int b, const int G) {
   constexpr int NM = DUAL ? 2 : 1;
   constexpr int DW = 2 * BITS;
   constexpr int NC = Extract<BITS>::kClasses;
@@ -98,8 +99,7 @@ __device__ LRC_BODY_INLINE void decode_body(const KArgs& a, uint4* xs, const int
   const int tdw = kWave * DW;
   LRC_STAMP(0);
 
-  // this block's n-tiles, and how they are dealt to the 16 wavefronts
-  const int G = gridDim.x, b = blockIdx.x;
+  // this block's n-tiles (block b of the G that share the expert), and how they are dealt to the 16 wavefronts
   const int t0 = (int)((long long)b * a.NT / G), t1 = (int)((long long)(b + 1) * a.NT / G);
   const int nt_b = t1 - t0;
   if (nt_b == 0) return;
@@ -470,16 +470,68 @@ __device__ LRC_BODY_INLINE void decode_body(const KArgs& a, uint4* xs, const int
 template <int BITS, bool DUAL>
 __global__ __launch_bounds__(64 * kDecodeWaves, 4) void qgemm_decode_kernel(KArgs a) {
   extern __shared__ uint4 xs[];
-  const int e = blockIdx.y;
+  int e = blockIdx.y, b = blockIdx.x, G = gridDim.x;
+  if (a.plan != nullptr) {                   // shares by table (plan_kernel)
+    const int4 pe = reinterpret_cast<const int4*>(a.plan)[blockIdx.x];
+    e = __builtin_amdgcn_readfirstlane(pe.x); b = __builtin_amdgcn_readfirstlane(pe.y); G = __builtin_amdgcn_readfirstlane(pe.z);
+    if (e < 0) return;
+  }
   const int r0 = a.offsets ? a.offsets[e] : e * a.T;
   const int cnt = a.offsets ? a.offsets[e + 1] - r0 : a.T;
   if (cnt == 0) return;
 #if defined(LRC_FORCE_MT)
-  decode_body<BITS, DUAL, LRC_FORCE_MT>(a, xs, e, r0, cnt);
+  decode_body<BITS, DUAL, LRC_FORCE_MT>(a, xs, e, r0, cnt, b, G);
 #else
-  if (cnt <= 16) decode_body<BITS, DUAL, 1>(a, xs, e, r0, cnt);
-  else decode_body<BITS, DUAL, 2>(a, xs, e, r0, cnt);
+  if (cnt <= 16) decode_body<BITS, DUAL, 1>(a, xs, e, r0, cnt, b, G);
+  else decode_body<BITS, DUAL, 2>(a, xs, e, r0, cnt, b, G);
 #endif
+}
+
+// With many experts and skewed routing most experts have no rows and some have several 32-row
+// passes' worth: a fixed number of blocks per expert leaves most of the chip idle.  One wavefront
+// shares the B blocks of a launch out among the experts that have rows: each gets `base` blocks
+// (enough for 32 n-tiles per block), the rest of `target` blocks go by weight (5 for up to 16 rows, 8 per 32 rows
+// beyond: what a pass costs), dealt by the running sum of the weights.  Entry i of the table: expert
+// (or -1), index of the block within the expert, blocks of the expert.
+__global__ __launch_bounds__(64) void plan_kernel(const int32_t* __restrict__ offsets, int E, int B, int base,
+                                                  int target, int32_t* __restrict__ plan) {
+  const int lane = threadIdx.x;
+  auto weight = [](int cnt) { return cnt == 0 ? 0 : cnt <= 16 ? 5 : 8 * ((cnt + 31) / 32); };
+  auto scan = [&](int v) {
+#pragma unroll
+    for (int dlt = 1; dlt < 64; dlt *= 2) {
+      const int t = __shfl_up(v, dlt);
+      if (lane >= dlt) v += t;
+    }
+    return v;
+  };
+  int n_active = 0, wsum = 0;
+  for (int e0 = 0; e0 < E; e0 += 64) {
+    const int e = e0 + lane;
+    const int cnt = e < E ? offsets[e + 1] - offsets[e] : 0;
+    n_active += __popcll(__ballot(cnt > 0));
+    wsum += __shfl(scan(weight(cnt)), 63);
+  }
+  // as many blocks as fill the chip (`target`), more only if the experts with rows need them; the
+  // rest of the grid exits at once
+  const int total = min(B, max(target, n_active * base));
+  const long long extra = total - n_active * base;
+  int act_before = 0, w_before = 0, used = 0;
+  for (int e0 = 0; e0 < E; e0 += 64) {
+    const int e = e0 + lane;
+    const int cnt = e < E ? offsets[e + 1] - offsets[e] : 0;
+    const int act = cnt > 0 ? 1 : 0, w = weight(cnt), wi = scan(w), ai = scan(act);
+    if (act) {
+      const int lo = (act_before + ai - 1) * base + int(extra * (w_before + wi - w) / wsum);
+      const int hi = (act_before + ai) * base + int(extra * (w_before + wi) / wsum);
+      for (int i = lo; i < hi && i < B; ++i) {
+        plan[4 * i] = e; plan[4 * i + 1] = i - lo; plan[4 * i + 2] = hi - lo; plan[4 * i + 3] = 0;
+      }
+    }
+    act_before += __shfl(ai, 63); w_before += __shfl(wi, 63);
+  }
+  used = n_active > 0 ? n_active * base + int(extra) : 0;
+  for (int i = used + lane; i < B; i += 64) { plan[4 * i] = -1; plan[4 * i + 1] = 0; plan[4 * i + 2] = 1; plan[4 * i + 3] = 0; }
 }
 
 // Partial (in A): pk[kb2][row][rho] = sum over K-block kb2 of in[row][k] * A[k][rho] in fp32, for the
@@ -579,6 +631,8 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
   // activations + the (in A) fragments: [projections][rank steps][2 row tiles] KB
   auto lds_bytes = [&](int nm) { return size_t(kDecodeLdsUnits) * 16 + (comp ? size_t(nm) * a.ls * 2 * 1024 : 0); };
   auto xa_blocks = [](int K) { return std::max(1, std::min(8, K / 1024)); };   // K-blocks of the (in A) kernels
+  // many experts: the blocks are shared out on the device among the experts that have rows
+  const bool by_table = f.offsets != nullptr && f.plan != nullptr && f.n_exp >= 32;
 
   if (which & 1) {
   // W1 | W3 with the SwiGLU epilogue
@@ -589,8 +643,16 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
   if (comp) hipLaunchKernelGGL(xa_split_kernel<true>, dim3(2 * f.rpad / 16, f.n_exp, a.ksplit), dim3(512), 0, s, a);
   if (f.marks) (void)hipEventRecord(f.marks[0], s);
   a.kb_steps = a.KS; a.partial = nullptr;
-  hipLaunchKernelGGL((qgemm_decode_kernel<BITS, true>), dim3(blocks_per_expert(a.NT, 1), f.n_exp, 1),
-                     dim3(64 * kDecodeWaves), lds_bytes(2), s, a);
+  if (by_table) {
+    const int B = plan_blocks(f.n_exp, f.T * f.top_k, a.NT);
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(64), 0, s, f.offsets, f.n_exp, B, (a.NT + 31) / 32, 256, f.plan);
+    a.plan = f.plan;
+    hipLaunchKernelGGL((qgemm_decode_kernel<BITS, true>), dim3(B, 1, 1), dim3(64 * kDecodeWaves), lds_bytes(2), s, a);
+    a.plan = nullptr;
+  } else {
+    hipLaunchKernelGGL((qgemm_decode_kernel<BITS, true>), dim3(blocks_per_expert(a.NT, 1), f.n_exp, 1),
+                       dim3(64 * kDecodeWaves), lds_bytes(2), s, a);
+  }
   if (f.marks) (void)hipEventRecord(f.marks[1], s);
   }
   if (which & 2) {
@@ -606,8 +668,19 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
   const int kblocks = f.y_part ? std::min(kMaxKBlocks, (a.KS + 15) / 16) : 1;
   a.kb_steps = (a.KS + kblocks - 1) / kblocks;
   a.partial = kblocks > 1 ? f.y_part : nullptr;
-  hipLaunchKernelGGL((qgemm_decode_kernel<BITS, false>), dim3(blocks_per_expert(a.NT, kblocks), f.n_exp, kblocks),
-                     dim3(64 * kDecodeWaves), lds_bytes(1), s, a);
+  if (by_table) {
+    // (second table behind the first; every K-block uses the same shares)
+    int32_t* plan2 = f.plan + 4 * plan_blocks(f.n_exp, f.T * f.top_k, f.F / kTileN);
+    const int B = plan_blocks(f.n_exp, f.T * f.top_k, a.NT);
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(64), 0, s, f.offsets, f.n_exp, B, (a.NT + 31) / 32,
+                       (256 + kblocks - 1) / kblocks, plan2);
+    a.plan = plan2;
+    hipLaunchKernelGGL((qgemm_decode_kernel<BITS, false>), dim3(B, 1, kblocks), dim3(64 * kDecodeWaves), lds_bytes(1), s, a);
+    a.plan = nullptr;
+  } else {
+    hipLaunchKernelGGL((qgemm_decode_kernel<BITS, false>), dim3(blocks_per_expert(a.NT, kblocks), f.n_exp, kblocks),
+                       dim3(64 * kDecodeWaves), lds_bytes(1), s, a);
+  }
   if (kblocks > 1) {
     const size_t units = size_t(f.total_rows) * f.H / 4;
     hipLaunchKernelGGL(reduce_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, s, f.y_part, kblocks,

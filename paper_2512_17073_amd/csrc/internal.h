@@ -32,7 +32,7 @@ struct BlobLayout {
 
 struct Workspace {       // carved out of the caller's buffer; all offsets 256-byte aligned
   size_t topk_idx, topk_w, counts, offsets, comp_counts, row_pair, pair_row;
-  size_t y_rows, xh, xh_sh, h, p13, p2, y_part, sh_y_part, sh_h, sh_y, total;
+  size_t y_rows, xh, xh_sh, h, p13, p2, y_part, sh_y_part, sh_h, sh_y, plan, total;
 };
 
 }  // namespace lrc
@@ -82,6 +82,12 @@ hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _
                             const int32_t* offsets, const int32_t* row_pair, int32_t* stat,
                             hipStream_t s);
 constexpr int kMaxKBlocks = 8;    // most K-blocks the decode W2 kernel splits into
+// blocks (per K-block) of a decode launch that shares its blocks out by a table: the 256 CUs, or
+// enough for ceil(NT / 32) blocks per expert that can be active
+inline int plan_blocks(int n_exp, int pairs, int NT) {
+  const int active = n_exp < pairs ? n_exp : pairs, base = (NT + 31) / 32;
+  return active * base > 256 ? active * base : 256;
+}
 constexpr int kActPadRows = 32;   // rows past the last one that a 32-row staging pass may read
 
 struct FfnArgs {
@@ -99,6 +105,8 @@ struct FfnArgs {
   float* p2;                  // [ksplit2][rows][rpad]
   void* y_rows;               // [rows][H] bf16
   float* y_part;              // fp32 partial outputs of the W2 K-blocks (decode flavour), or null
+  int32_t* plan;              // decode flavour, many experts: block -> (expert, block of the expert, blocks of
+                              // the expert) tables of the two projections, kPlanBlocks(...) entries of 4 ints each
   int ksplit13, ksplit2, total_rows;
   hipEvent_t* marks;          // null, or 4 events recorded after xa13, w13, xa2, w2
 };
