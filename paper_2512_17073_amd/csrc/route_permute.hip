@@ -16,8 +16,8 @@ __device__ inline double wave_sum(double v) {
   return v;
 }
 
-// One workgroup (4 wavefronts) per token.  Wavefront w accumulates, in fp64, the gate dot products
-// of experts w, w+4, ...: every bf16 x bf16 product is exact in fp64, so the logits differ from the
+// One workgroup (NW wavefronts: 4, or 16 when there are many experts) per token.  Wavefront w
+// accumulates, in fp64, the gate dot products of experts w, w+NW, ...: every bf16 x bf16 product is exact in fp64, so the logits differ from the
 // exact ones by ~1e-13 and the selection equals the exact selection.  The same instruction
 // sequence runs for every expert row, so duplicated gate rows give bit-identical logits.
 // A lane keeps its 16-byte chunks of the token (chunks lane, lane + 64, ...: CH of them) in
@@ -26,8 +26,8 @@ __device__ inline double wave_sum(double v) {
 // lower index) and the softmax weights of the selected experts.
 constexpr int kMaxExperts = 256;
 
-template <int CH>
-__global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__ x,
+template <int CH, int NW>
+__global__ __launch_bounds__(64 * NW) void route_kernel(const uint16_t* __restrict__ x,
                                                     const uint16_t* __restrict__ wg,
                                                     const float* __restrict__ bias, int T, int H, int E,
                                                     int top_k, int renorm, int32_t* __restrict__ idx,
@@ -38,7 +38,7 @@ __global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__
   const int chunks = H / 8;
 
   if (xh != nullptr) {     // fp16 copy of the token for the expert kernels (exact for |x| < 65504)
-    for (int c = threadIdx.x; c < chunks; c += 256) {
+    for (int c = threadIdx.x; c < chunks; c += 64 * NW) {
       const uint4 v = xrow[c];
       const uint32_t in[4] = {v.x, v.y, v.z, v.w};
       uint32_t o[4];
@@ -68,8 +68,8 @@ __global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__
   };
   uint4 wcur[CH], wnext[CH];
   load_row(wave, wcur);
-  for (int e = wave; e < E; e += 4) {
-    load_row(e + 4, wnext);                               // (clamped past the last row; unused then)
+  for (int e = wave; e < E; e += NW) {
+    load_row(e + NW, wnext);                               // (clamped past the last row; unused then)
     double acc = 0.0;
 #pragma unroll
     for (int j = 0; j < CH; ++j) {                        // chunks in increasing order, as a plain loop would
@@ -213,17 +213,21 @@ hipError_t launch_route(const moe_lrc_layer* L, const void* x, int T, int32_t* i
                         _Float16* xh, hipStream_t s) {
   const moe_lrc_config& c = L->cfg;
   const int ch = (c.hidden / 8 + 63) / 64;      // 16-byte chunks of a row per lane
-  auto go = [&](auto kernel) {
-    hipLaunchKernelGGL(kernel, dim3(T), dim3(256), 0, s, (const uint16_t*)x, L->d_wg,
+  auto go = [&](auto kernel, int nw) {
+    hipLaunchKernelGGL(kernel, dim3(T), dim3(64 * nw), 0, s, (const uint16_t*)x, L->d_wg,
                        L->has_bias ? L->d_bias : nullptr, T, c.hidden, c.n_experts, c.top_k,
                        c.renormalize, idx, w, xh);
   };
-  if (ch <= 1) go(route_kernel<1>);
-  else if (ch <= 2) go(route_kernel<2>);
-  else if (ch <= 4) go(route_kernel<4>);
-  else if (ch <= 8) go(route_kernel<8>);
-  else if (ch <= 16) go(route_kernel<16>);
-  else if (ch <= 32) go(route_kernel<32>);
+  // 16 wavefronts per token when every wavefront would otherwise walk 16 or more gate rows one
+  // after the other, the chunks of a row fit the smaller register budget, and the launch is bound
+  // by that latency rather than by throughput (few tokens)
+  const bool wide = c.n_experts >= 64 && ch <= 8 && T <= 128;
+  if (ch <= 1) wide ? go(route_kernel<1, 16>, 16) : go(route_kernel<1, 4>, 4);
+  else if (ch <= 2) wide ? go(route_kernel<2, 16>, 16) : go(route_kernel<2, 4>, 4);
+  else if (ch <= 4) wide ? go(route_kernel<4, 16>, 16) : go(route_kernel<4, 4>, 4);
+  else if (ch <= 8) wide ? go(route_kernel<8, 16>, 16) : go(route_kernel<8, 4>, 4);
+  else if (ch <= 16) go(route_kernel<16, 4>, 4);
+  else if (ch <= 32) go(route_kernel<32, 4>, 4);
   else return hipErrorInvalidValue;             // hidden > 16384 (layer_create rejects it)
   return hipGetLastError();
 }
