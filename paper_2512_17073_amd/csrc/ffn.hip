@@ -413,11 +413,12 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
 // grid.x splits K so that the launch fills the chip.
 // xa_finish_kernel: adds the K-blocks in order, zeroes the rows without the rank-r term and the
 // padding columns, writes fp16 row-major.
-template <bool DUAL>
+template <bool DUAL, int NT>
 __global__ __launch_bounds__(64 * kTileWaves, 2) void xa_tile_kernel(KArgs a) {
   extern __shared__ uint4 xs[];
   constexpr int NM = DUAL ? 2 : 1;
-  constexpr int kMaxT = 4;                               // factor tiles per wavefront: rank <= 256
+  constexpr int kMaxT = NT;                              // factor tiles per wavefront (2 or 4: rank <= 256)
+  constexpr bool kAhead = NT <= 2;                       // registers for the factor units of a whole k-step ahead
   Chunk ch;
   if (!find_chunk(a, blockIdx.y, ch)) return;
   const int e = ch.e, r0 = ch.r0, cnt = ch.cnt, r = ch.r;
@@ -455,18 +456,43 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void xa_tile_kernel(KArgs a) {
   const int all_steps = (a.K + kTileK - 1) / kTileK, per_kb = (all_steps + gridDim.x - 1) / gridDim.x;
   const int step_lo = blockIdx.x * per_kb, steps = min(all_steps, step_lo + per_kb);
   if (step_lo >= steps) return;              // (the finish kernel reads only K-blocks that exist)
+  // the factor units of sub-step s of k-step `step` for this lane (zero past K)
+  auto load_unit = [&](int step, int s, int t) {
+    const int kk = step * 8 + 2 * q + (s >> 2);          // this lane's 32-row unit of the factor
+    half8_t v = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
+    if (t < nmine && kk * 32 < a.K) v = af[t][size_t(kk) * rt * kWave + (s & 3) * 16];
+    return v;
+  };
+  half8_t wnext[kAhead ? 8 : 1][kMaxT];
+  if constexpr (kAhead) {
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+#pragma unroll
+      for (int t = 0; t < kMaxT; ++t) wnext[s][t] = load_unit(step_lo, s, t);
+  }
   stage_step(a, xs + (step_lo & 1) * kStepUnits, step_lo, rin, wave, lane);
   asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
   for (int step = step_lo; step < steps; ++step) {
     stage_step(a, xs + ((step + 1) & 1) * kStepUnits, step + 1, rin, wave, lane);
     const uint4* buf = xs + (step & 1) * kStepUnits;
+    half8_t wcur[kAhead ? 8 : 1][kMaxT];
+    if constexpr (kAhead) {                  // this step's units have arrived; ask for the next step's
+#pragma unroll
+      for (int s = 0; s < 8; ++s)
+#pragma unroll
+        for (int t = 0; t < kMaxT; ++t) wcur[s][t] = wnext[s][t];
+#pragma unroll
+      for (int s = 0; s < 8; ++s)
+#pragma unroll
+        for (int t = 0; t < kMaxT; ++t) wnext[s][t] = load_unit(step + 1, s, t);
+    }
+#pragma unroll
     for (int s = 0; s < 8; ++s) {
-      const int kk = step * 8 + 2 * q + (s >> 2);        // this lane's 32-row unit of the factor
       half8_t wf[kMaxT];
 #pragma unroll
       for (int t = 0; t < kMaxT; ++t) {
-        wf[t] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
-        if (t < nmine && kk * 32 < a.K) wf[t] = af[t][size_t(kk) * rt * kWave + (s & 3) * 16];
+        if constexpr (kAhead) wf[t] = wcur[s][t];
+        else wf[t] = load_unit(step, s, t);
       }
 #pragma unroll
       for (int mt = 0; mt < kTMT; ++mt)
@@ -521,11 +547,13 @@ template <int BITS>
 hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
   static bool attr_set = false;
   if (!attr_set) {
-    const void* fns[5] = {reinterpret_cast<const void*>(&qgemm_tile_kernel<BITS, true, 2>),
+    const void* fns[7] = {reinterpret_cast<const void*>(&qgemm_tile_kernel<BITS, true, 2>),
                           reinterpret_cast<const void*>(&qgemm_tile_kernel<BITS, false, 4>),
                           reinterpret_cast<const void*>(&qgemm_tile_kernel<BITS, false, 2>),
-                          reinterpret_cast<const void*>(&xa_tile_kernel<true>),
-                          reinterpret_cast<const void*>(&xa_tile_kernel<false>)};
+                          reinterpret_cast<const void*>(&xa_tile_kernel<true, 2>),
+                          reinterpret_cast<const void*>(&xa_tile_kernel<false, 2>),
+                          reinterpret_cast<const void*>(&xa_tile_kernel<true, 4>),
+                          reinterpret_cast<const void*>(&xa_tile_kernel<false, 4>)};
     for (const void* fn : fns) {
       hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStepUnits * 16);
       if (e != hipSuccess) return e;
@@ -544,13 +572,15 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
   const size_t lds = size_t(2) * kStepUnits * 16;
 
   // (in A): fp16 result at the start of the buffer, the K-block partial sums behind it
-  auto xa = [&](auto kernel, float* buf, int nm, int ksplit) {
+  auto xa = [&](auto k2, auto k4, float* buf, int nm, int ksplit) {
+    const int per_wave = (nm * f.rpad / 16 + kTileWaves - 1) / kTileWaves;   // factor tiles per wavefront
     const int pitch = nm * a.ls * 32, steps = (a.K + kTileK - 1) / kTileK;
     const int per_kb = (steps + std::max(1, ksplit) - 1) / std::max(1, ksplit);
     const int kblocks = (steps + per_kb - 1) / per_kb;      // no K-block without a k-step
     a.p = buf;
     a.partial = buf + (size_t(f.total_rows) * pitch / 2 + 63) / 64 * 64;
-    hipLaunchKernelGGL(kernel, dim3(kblocks, items), dim3(64 * kTileWaves), lds, s, a);
+    if (per_wave <= 2) hipLaunchKernelGGL(k2, dim3(kblocks, items), dim3(64 * kTileWaves), lds, s, a);
+    else hipLaunchKernelGGL(k4, dim3(kblocks, items), dim3(64 * kTileWaves), lds, s, a);
     const size_t groups = size_t(f.total_rows) * pitch / 4;
     hipLaunchKernelGGL(xa_finish_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, s, a.partial, kblocks,
                        f.total_rows, pitch, a.ls * 32, a.rpad, f.row_pair, f.top_k, f.top_n, reinterpret_cast<_Float16*>(buf));
@@ -561,7 +591,7 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
   a.in = f.xh; a.out = f.h; a.K = f.H; a.N = f.F; a.NT = f.F / kTileN;
   a.in_rt = f.x_rt; a.out_rt = f.h_rt;
   a.KS = padded_k(f.H) / kTileK; a.G = padded_k(f.H) / f.group;
-  if (comp) xa(xa_tile_kernel<true>, f.p13, 2, f.ksplit13);
+  if (comp) xa(xa_tile_kernel<true, 2>, xa_tile_kernel<true, 4>, f.p13, 2, f.ksplit13);
   if (f.marks) (void)hipEventRecord(f.marks[0], s);
   hipLaunchKernelGGL((qgemm_tile_kernel<BITS, true, 2>), dim3((a.NT + 15) / 16, items), dim3(64 * kTileWaves), lds, s, a);
   if (f.marks) (void)hipEventRecord(f.marks[1], s);
@@ -571,7 +601,7 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
   a.in = f.h; a.out = f.y_rows; a.K = f.F; a.N = f.H; a.NT = f.H / kTileN;
   a.in_rt = f.h_rt; a.out_rt = 0;
   a.KS = padded_k(f.F) / kTileK; a.G = padded_k(f.F) / f.group;
-  if (comp) xa(xa_tile_kernel<false>, f.p2, 1, f.ksplit2);
+  if (comp) xa(xa_tile_kernel<false, 2>, xa_tile_kernel<false, 4>, f.p2, 1, f.ksplit2);
   if (f.marks) (void)hipEventRecord(f.marks[2], s);
   // four n-tiles per wavefront use a fragment of activations twice as often as two, but make
   // blocks twice as large: take the one with fewer (weighted) rounds of blocks over the 256 CUs
