@@ -23,6 +23,11 @@
  *     moe_lrc_expert_ffn / moe_lrc_forward to decide which experts to copy, and therefore
  *     synchronises `stream` once per call.
  *   - argument errors are reported before any device work is issued.
+ *   - a layer serves one hot-path call at a time: calls on the same layer must be ordered on one
+ *     stream (they share the layer's counters and, with shared experts or staged residency, its
+ *     side stream).  moe_lrc_forward on a layer with shared experts forks to that side stream and
+ *     joins it before the combine, so everything it does is ordered before later work on `stream`;
+ *     it can be captured into a HIP graph (resident layers only: staged ones synchronise).
  *   - matrices are input-dim-major: W[K_in][N_out], y = x W.  mat 0 = W1 (gate projection,
  *     [H][F]), 1 = W3 (up projection, [H][F]), 2 = W2 (down projection, [F][H]);
  *     E_i(x) = (silu(x W1) * (x W3)) W2.
@@ -51,7 +56,7 @@ extern "C" {
 
 typedef struct {
   int32_t hidden;       /* H, multiple of 64, at most 16384                               */
-  int32_t ffn;          /* F, multiple of 64                                              */
+  int32_t ffn;          /* F, multiple of 64, at most 65536                               */
   int32_t n_experts;    /* E routed experts, 1..256                                       */
   int32_t n_shared;     /* S always-on shared experts (Table 1 note), 0..8                */
   int32_t top_k;        /* k, 1..min(E,16)                                                */
