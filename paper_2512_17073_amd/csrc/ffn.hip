@@ -204,21 +204,13 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
       };
       auto row_tile = [&](auto MT) {
         constexpr int mt = decltype(MT)::value;
-#ifdef LRC_EXP_T_NOLDS
-        if constexpr (mt == 0) lds_wait<0>(xf[0]);
-#else
         if constexpr (mt + PF < kTMT) rd(std::integral_constant<int, (mt + PF < kTMT ? mt + PF : 0)>{});
         lds_wait<(kTMT - 1 - mt < PF ? kTMT - 1 - mt : PF)>(xf[mt % (PF + 1)]);
-#endif
 #pragma unroll
         for (int t = 0; t < kNTW; ++t)
 #pragma unroll
           for (int m = 0; m < NM; ++m)
-#ifdef LRC_EXP_T_NOLDS
-            acc[t][mt][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[t][m], xf[0], acc[t][mt][m], 0, 0, 0);
-#else
             acc[t][mt][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[t][m], xf[mt % (PF + 1)], acc[t][mt][m], 0, 0, 0);
-#endif
       };
       rd(std::integral_constant<int, 0>{});
       if constexpr (PF > 1) rd(std::integral_constant<int, 1>{});
@@ -279,11 +271,6 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
 #pragma unroll
         for (int m = 0; m < NM; ++m) {
           uint32_t v[4];
-#ifdef LRC_EXP_T_NOVALU
-#pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] = cur.t[t].cw[m][(4 * s + j) % DW] ^ c2[t][m];
-          if (false)
-#endif
 #pragma unroll
           for (int j = 0; j < 4; ++j)
             v[j] = pk_fma(Extract<BITS>::field(cur.t[t].cw[m], 4 * s + j), s2[t][m][Extract<BITS>::cls(4 * s + j)], c2[t][m]);

@@ -14,31 +14,6 @@ typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 
-// Tunables of the decode flavour (overridable at build time for sweeps).
-#ifndef LRC_LDS_UNITS
-#define LRC_LDS_UNITS 4096
-#endif
-#ifndef LRC_DECODE_WAVES
-#define LRC_DECODE_WAVES 6
-#endif
-#ifndef LRC_DECODE_MINW
-#define LRC_DECODE_MINW 3
-#endif
-#ifndef LRC_RING
-#define LRC_RING 4
-#endif
-#ifndef LRC_RING_WIDE
-#define LRC_RING_WIDE 3
-#endif
-constexpr int kLdsUnits = LRC_LDS_UNITS;   // LDS for activations in 16-byte units (4096 = 64 KB)
-// k-steps of packed tiles a wavefront keeps in registers (one being unpacked, the rest in flight);
-// 3- and 4-bit tiles of two projections are larger, three of them fill the register budget
-__host__ __device__ constexpr int ring_depth(int bits, bool dual) { return dual && bits > 2 ? LRC_RING_WIDE : LRC_RING; }
-
-// wavefronts per block: 6 (two blocks = 12 wavefronts per CU at <= 168 registers) for the decode
-// flavour, 8 (one block per CU at <= 256 registers) when many rows share one unpack
-__host__ __device__ constexpr int block_waves(int maxmt) { return maxmt <= 2 ? LRC_DECODE_WAVES : 8; }
-
 __device__ inline uint32_t pk_fma(uint32_t q, uint32_t s, uint32_t c) {
   const half2_t r = __builtin_elementwise_fma(__builtin_bit_cast(half2_t, q),
                                               __builtin_bit_cast(half2_t, s),

@@ -124,12 +124,8 @@ __device__ LRC_BODY_INLINE void decode_body(const KArgs& a, uint4* xs, const int
   // ring slot and go into the MFMA as they are, against (in A) instead of the activations.  A
   // resource of size zero (no factors, or not this K-block's job) makes those steps read zeros.
   const bool has_factors = __builtin_amdgcn_readfirstlane(d.has_factors) != 0;
-#ifdef LRC_EXP_NOLOWRANK
-  const bool lowrank = false;
-#else
   const bool lowrank = a.rank > 0 && has_factors && a.row_pair != nullptr && blockIdx.z == 0 &&
                        __builtin_amdgcn_readfirstlane(a.comp_rows[e]) > 0;
-#endif
   const int LS = lowrank ? a.ls : 0;
   float lam[NM];
 #pragma unroll
@@ -291,19 +287,6 @@ __device__ LRC_BODY_INLINE void decode_body(const KArgs& a, uint4* xs, const int
     };
     // a k-step of packed codes of one n-tile
     auto compute = [&](const Slot<BITS, NM>& cur, int kl, float4_t (&ac)[kDMT][NM]) {
-#ifdef LRC_EXP_NOCOMPUTE
-      {
-        uint32_t t = 0;
-#pragma unroll
-        for (int m = 0; m < NM; ++m) {
-          t ^= cur.mw[m];
-#pragma unroll
-          for (int j = 0; j < DW; ++j) t ^= cur.cw[m][j];
-        }
-        ac[0][0][0] += __uint_as_float(t & 0x3f800000u);
-        return;
-      }
-#endif
       const uint4* xk = xs + size_t(kl) * 8 * 64 + lane;
       uint32_t s2[NM][NC], c2[NM];
 #pragma unroll
@@ -342,11 +325,6 @@ __device__ LRC_BODY_INLINE void decode_body(const KArgs& a, uint4* xs, const int
 #pragma unroll
         for (int m = 0; m < NM; ++m) {
           uint32_t v[4];
-#ifdef LRC_EXP_NOVALU
-#pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] = cur.cw[m][(4 * s + j) % DW] ^ c2[m];
-          if (false)
-#endif
 #pragma unroll
           for (int j = 0; j < 4; ++j)
             v[j] = pk_fma(Extract<BITS>::field(cur.cw[m], 4 * s + j), s2[m][Extract<BITS>::cls(4 * s + j)], c2[m]);
@@ -357,16 +335,11 @@ __device__ LRC_BODY_INLINE void decode_body(const KArgs& a, uint4* xs, const int
           if constexpr (kDMT == 1) lds_wait<(s < 7 ? 1 : 0)>(xf[s & 1][0]);
           else lds_wait<(s < 7 ? 2 : 0)>(xf[s & 1][0], xf[s & 1][kDMT - 1]);
         }
-#ifdef LRC_EXP_NOMFMA
-#pragma unroll
-        for (int m = 0; m < NM; ++m) { ac[0][m][0] += (float)wf[m][0]; ac[0][m][1] += (float)wf[m][2]; ac[0][m][2] += (float)wf[m][4]; ac[0][m][3] += (float)wf[m][6]; }
-#else
 #pragma unroll
         for (int mt = 0; mt < kDMT; ++mt)
 #pragma unroll
           for (int m = 0; m < NM; ++m)
             ac[mt][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[m], xf[XB == 2 ? (s & 1) : 0][mt], ac[mt][m], 0, 0, 0);
-#endif
       };
       substep(std::integral_constant<int, 0>{}); substep(std::integral_constant<int, 1>{});
       substep(std::integral_constant<int, 2>{}); substep(std::integral_constant<int, 3>{});
@@ -479,12 +452,8 @@ __global__ __launch_bounds__(64 * kDecodeWaves, 4) void qgemm_decode_kernel(KArg
   const int r0 = a.offsets ? a.offsets[e] : e * a.T;
   const int cnt = a.offsets ? a.offsets[e + 1] - r0 : a.T;
   if (cnt == 0) return;
-#if defined(LRC_FORCE_MT)
-  decode_body<BITS, DUAL, LRC_FORCE_MT>(a, xs, e, r0, cnt, b, G);
-#else
   if (cnt <= 16) decode_body<BITS, DUAL, 1>(a, xs, e, r0, cnt, b, G);
   else decode_body<BITS, DUAL, 2>(a, xs, e, r0, cnt, b, G);
-#endif
 }
 
 // With many experts and skewed routing most experts have no rows and some have several 32-row
