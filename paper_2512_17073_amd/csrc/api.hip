@@ -263,6 +263,8 @@ int moe_lrc_layer_create(const moe_lrc_config* cfg, moe_lrc_layer** out) {
   LRC_TRY(hipMalloc((void**)&L->d_desc, sizeof(ExpertDesc) * L->n_total));
   LRC_TRY(hipMalloc((void**)&L->d_wg, size_t(cfg->n_experts) * cfg->hidden * 2));
   LRC_TRY(hipMalloc((void**)&L->d_bias, size_t(cfg->n_experts) * 4));
+  if (cfg->max_tokens >= 1024 && cfg->n_experts >= 128)
+    LRC_TRY(hipMalloc((void**)&L->d_logits, size_t(cfg->max_tokens) * cfg->n_experts * 8));
   LRC_TRY(hipMalloc((void**)&L->d_stat, (2 + 2 * cfg->n_experts) * 4));
   LRC_TRY(hipMemset(L->d_stat, 0, (2 + 2 * cfg->n_experts) * 4));
   LRC_TRY(hipHostMalloc((void**)&L->h_stat, (2 + 2 * cfg->n_experts) * 4, hipHostMallocDefault));
@@ -299,6 +301,7 @@ int moe_lrc_layer_destroy(moe_lrc_layer* L) {
   if (L->d_wg) (void)hipFree(L->d_wg);
   if (L->d_bias) (void)hipFree(L->d_bias);
   if (L->d_stat) (void)hipFree(L->d_stat);
+  if (L->d_logits) (void)hipFree(L->d_logits);
   if (L->h_stat) (void)hipHostFree(L->h_stat);
   if (L->side) (void)hipStreamDestroy(L->side);
   if (L->ev_t0) (void)hipEventDestroy(L->ev_t0);

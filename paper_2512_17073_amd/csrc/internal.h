@@ -51,6 +51,7 @@ struct moe_lrc_layer {
   std::vector<lrc::ExpertDesc> h_desc;
   uint16_t* d_wg = nullptr;
   float* d_bias = nullptr;
+  double* d_logits = nullptr;          // [max_tokens][E] gate logits of the tiled routing path (many tokens and experts)
   bool gate_set = false, has_bias = false;
   std::vector<uint8_t> mat_set;        // [n_total*3]
   int32_t* d_stat = nullptr;           // [2 + 2E]: active, comp-active, counts, comp counts

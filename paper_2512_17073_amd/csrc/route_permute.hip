@@ -16,6 +16,49 @@ __device__ inline double wave_sum(double v) {
   return v;
 }
 
+// Top-k of one token's logits by a shuffle arg-max (value descending, ties to the lower index), and
+// the softmax weights of the selected experts (Section 2.1), by one wavefront: lane holds the
+// logits of experts lane, lane + 64, lane + 128, lane + 192.
+__device__ inline void select_topk(const double (&v)[4], int lane, int E, int top_k, int renorm,
+                                   int32_t* __restrict__ idx_t, float* __restrict__ w_t) {
+  uint32_t taken = 0;
+#pragma unroll
+  for (int m = 0; m < 4; ++m)
+    if (lane + 64 * m >= E) taken |= 1u << m;
+  double vmax = 0.0, den = 0.0, sel_sum = 0.0, my_w = 0.0;
+  int my_idx = 0;
+  for (int j = 0; j < top_k; ++j) {
+    double bv = 0.0;
+    int bi = 0x7fffffff;
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+      if (!(taken & (1u << m)) && (bi == 0x7fffffff || v[m] > bv)) { bv = v[m]; bi = lane + 64 * m; }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      const double ov = __shfl_xor(bv, off);
+      const int oi = __shfl_xor(bi, off);
+      const bool take = oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi));
+      if (take) { bv = ov; bi = oi; }
+    }
+    if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
+    if (j == 0) {
+      vmax = bv;
+      double part = 0.0;
+#pragma unroll
+      for (int m = 0; m < 4; ++m)
+        if (lane + 64 * m < E) part += exp(v[m] - vmax);
+      den = wave_sum(part);
+    }
+    const double score = exp(bv - vmax) / den;
+    sel_sum += score;
+    if (lane == j) { my_w = score; my_idx = bi; }
+  }
+  if (lane < top_k) {
+    idx_t[lane] = my_idx;
+    w_t[lane] = (float)(renorm ? my_w / sel_sum : my_w);
+  }
+}
+
 // One workgroup (NW wavefronts: 4, or 16 when there are many experts) per token.  Wavefront w
 // accumulates, in fp64, the gate dot products of experts w, w+NW, ...: every bf16 x bf16 product is exact in fp64, so the logits differ from the
 // exact ones by ~1e-13 and the selection equals the exact selection.  The same instruction
@@ -90,45 +133,75 @@ __global__ __launch_bounds__(64 * NW) void route_kernel(const uint16_t* __restri
 
   // lane holds experts lane, lane+64, lane+128, lane+192
   double v[4];
-  uint32_t taken = 0;
 #pragma unroll
   for (int m = 0; m < 4; ++m) {
     const int e = lane + 64 * m;
     v[m] = e < E ? logit[e] : 0.0;
-    if (e >= E) taken |= 1u << m;
   }
-  double vmax = 0.0, den = 0.0, sel_sum = 0.0, my_w = 0.0;
-  int my_idx = 0;
-  for (int j = 0; j < top_k; ++j) {
-    double bv = 0.0;
-    int bi = 0x7fffffff;
+  select_topk(v, lane, E, top_k, renorm, idx + size_t(t) * top_k, w + size_t(t) * top_k);
+}
+
+// Many tokens: the logits of a 16-token x 16-expert tile on the fp64 matrix cores (every wavefront
+// of the other kernel re-reads the whole gate for one token; here a gate row serves 16 tokens).
+// v_mfma_f64_16x16x4: experts are the rows, tokens the columns; lane (i = lane % 16, kq = lane / 16)
+// supplies gate row i and token i at the k index of the step; it walks quarter kq of the hidden
+// dimension in order, eight elements per 16-byte load.  Products of bf16 values are exact in fp64
+// and every (expert, token) pair sees the same sequence of operations, so duplicated gate rows
+// give bit-identical logits.  Grid: (token tiles, groups of four expert tiles); logits [T][E].
+typedef double double4_t __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void gate_logits_kernel(const uint16_t* __restrict__ x,
+                                                          const uint16_t* __restrict__ wg, int T, int H, int E,
+                                                          double* __restrict__ logits) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int et = blockIdx.y * 4 + wave;
+  if (et * 16 >= E) return;
+  const int i = lane & 15, kq = lane >> 4, Hq = H / 4;
+  const int token = min((int)blockIdx.x * 16 + i, T - 1), expert = min(et * 16 + i, E - 1);
+  const uint4* xp = reinterpret_cast<const uint4*>(x + size_t(token) * H + kq * Hq);
+  const uint4* wp = reinterpret_cast<const uint4*>(wg + size_t(expert) * H + kq * Hq);
+  double4_t acc = double4_t{0.0, 0.0, 0.0, 0.0};
+  const int chunks = Hq / 8;
+  for (int c0 = 0; c0 < chunks; c0 += 4) {                  // four loads of each operand in flight
+    uint4 xv[4], wv[4];
 #pragma unroll
-    for (int m = 0; m < 4; ++m)
-      if (!(taken & (1u << m)) && (bi == 0x7fffffff || v[m] > bv)) { bv = v[m]; bi = lane + 64 * m; }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-      const double ov = __shfl_xor(bv, off);
-      const int oi = __shfl_xor(bi, off);
-      const bool take = oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi));
-      if (take) { bv = ov; bi = oi; }
+    for (int u = 0; u < 4; ++u) {
+      xv[u] = make_uint4(0, 0, 0, 0); wv[u] = make_uint4(0, 0, 0, 0);
+      if (c0 + u < chunks) { xv[u] = xp[c0 + u]; wv[u] = wp[c0 + u]; }
     }
-    if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
-    if (j == 0) {
-      vmax = bv;
-      double part = 0.0;
 #pragma unroll
-      for (int m = 0; m < 4; ++m)
-        if (lane + 64 * m < E) part += exp(v[m] - vmax);
-      den = wave_sum(part);
+    for (int u = 0; u < 4; ++u) {
+      const uint32_t xa[4] = {xv[u].x, xv[u].y, xv[u].z, xv[u].w}, wa[4] = {wv[u].x, wv[u].y, wv[u].z, wv[u].w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(bf16_to_double(wa[j] & 0xffffu), bf16_to_double(xa[j] & 0xffffu), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(bf16_to_double(wa[j] >> 16), bf16_to_double(xa[j] >> 16), acc, 0, 0, 0);
+      }
     }
-    const double score = exp(bv - vmax) / den;
-    sel_sum += score;
-    if (lane == j) { my_w = score; my_idx = bi; }
   }
-  if (lane < top_k) {
-    idx[size_t(t) * top_k + lane] = my_idx;
-    w[size_t(t) * top_k + lane] = (float)(renorm ? my_w / sel_sum : my_w);
+  // register r of lane (i, kq) holds row kq + 4 r of the tile (the fp64 variant interleaves the
+  // rows by four), i.e. expert 16 et + kq + 4 r, of token 16 tile + i
+  const int t = blockIdx.x * 16 + i;
+  if (t < T)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int e = et * 16 + kq + 4 * r;
+      if (e < E) logits[size_t(t) * E + e] = acc[r];
+    }
+}
+
+// Top-k and softmax weights from stored logits: one wavefront per token.
+__global__ __launch_bounds__(256) void topk_kernel(const double* __restrict__ logits, const float* __restrict__ bias,
+                                                   int T, int E, int top_k, int renorm, int32_t* __restrict__ idx,
+                                                   float* __restrict__ w) {
+  const int lane = threadIdx.x & 63, t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;
+  double v[4];
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    const int e = lane + 64 * m;
+    v[m] = e < E ? logits[size_t(t) * E + e] + (bias ? (double)bias[e] : 0.0) : 0.0;
   }
+  select_topk(v, lane, E, top_k, renorm, idx + size_t(t) * top_k, w + size_t(t) * top_k);
 }
 
 // Grouping: one workgroup of 16 wavefronts.  Wavefront w owns a contiguous run of pair ids, so
@@ -212,6 +285,16 @@ __global__ __launch_bounds__(1024) void permute_kernel(const int32_t* __restrict
 hipError_t launch_route(const moe_lrc_layer* L, const void* x, int T, int32_t* idx, float* w,
                         _Float16* xh, hipStream_t s) {
   const moe_lrc_config& c = L->cfg;
+  // Many tokens and many experts: tiled on the fp64 matrix cores.  (With few expert tiles a tile's
+  // chain of H / 4 dependent 64-cycle MFMAs is longer than the per-token kernel takes: measured
+  // slower for 8 and 64 experts up to T = 2048.)
+  if (T >= 1024 && c.n_experts >= 128 && xh == nullptr && L->d_logits != nullptr) {
+    hipLaunchKernelGGL(gate_logits_kernel, dim3((T + 15) / 16, (c.n_experts + 63) / 64), dim3(256), 0, s,
+                       (const uint16_t*)x, L->d_wg, T, c.hidden, c.n_experts, L->d_logits);
+    hipLaunchKernelGGL(topk_kernel, dim3((T + 3) / 4), dim3(256), 0, s, L->d_logits,
+                       L->has_bias ? L->d_bias : nullptr, T, c.n_experts, c.top_k, c.renormalize, idx, w);
+    return hipGetLastError();
+  }
   const int ch = (c.hidden / 8 + 63) / 64;      // 16-byte chunks of a row per lane
   auto go = [&](auto kernel, int nw) {
     hipLaunchKernelGGL(kernel, dim3(T), dim3(64 * nw), 0, s, (const uint16_t*)x, L->d_wg,

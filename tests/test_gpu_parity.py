@@ -296,3 +296,22 @@ def test_forward_under_graph_capture_replays_like_eager(amd, name):
             torch.cuda.synchronize()
             assert torch.equal(again.view(torch.int16), eager[i].view(torch.int16))
     L.close()
+
+
+def test_route_tiled_path_many_tokens_and_experts(amd):
+    """With >= 1024 tokens and >= 128 experts the logits come from the tiled fp64-matrix-core kernel
+    (ragged token and expert tiles here: T = 1100, E = 136): indices bit-exact, ties included."""
+    cfg = configs.QWEN3.with_(hidden=320, ffn=256, group=64, n_experts=136, tokens=1100, rank=0, top_n=0, name="route_tiled")
+    wg, bias = synth.make_gate(cfg)
+    wg = wg.copy()
+    wg[5] = wg[77]                      # a duplicated gate row: equal logits, the lower index wins
+    if bias is not None:
+        bias = bias.copy(); bias[5] = bias[77]
+    x_bits = synth.make_tokens(cfg)
+    ref = orc.route(x_bits, wg, cfg.top_k, cfg.renormalize, bias)
+    L = amd.Layer.from_config(cfg)
+    L.set_gate(wg, bias)
+    idx, w = L.route(amd.bf16_tensor(x_bits))
+    np.testing.assert_array_equal(_to_np(idx), ref["idx"])
+    np.testing.assert_allclose(_to_np(w), ref["w"], rtol=2e-6, atol=1e-30)
+    L.close()
