@@ -17,8 +17,8 @@ from . import moe_lrc_oracle as orc
 
 
 def _compress_one(args):
-    cfg, e, mat, method, keep_weights, keep_fp64_factors = args
-    return _compress_job(cfg, e, mat, method, keep_weights, keep_fp64_factors)
+    cfg, e, mat, method, keep_weights, keep_fp64_factors, rank = args
+    return _compress_job(cfg, e, mat, method, keep_weights, keep_fp64_factors, rank)
 
 
 def _compress_one_single_thread(args):
@@ -31,21 +31,34 @@ def _compress_one_single_thread(args):
         return _compress_one(args)
 
 
-def _compress_job(cfg, e, mat, method, keep_weights, keep_fp64_factors):
+def _compress_job(cfg, e, mat, method, keep_weights, keep_fp64_factors, rank=None):
     shared = e >= cfg.n_experts
     W = synth.make_expert_weight(cfg, e, mat)
-    art = compress.compress_matrix(W, synth.expert_bits(cfg, e), cfg.group, 0 if shared else cfg.rank,
+    r = 0 if shared else (cfg.rank if rank is None else int(rank))
+    art = compress.compress_matrix(W, synth.expert_bits(cfg, e), cfg.group, r,
                                    method=method, seed=cfg.seed + 31 * e + mat,
                                    keep_fp64_factors=keep_fp64_factors)
     art.pop("sigma", None)
+    if rank is not None and not shared:
+        art["rank"] = r            # this projection's own rank (Section 3.1)
     if keep_weights:
         art["W"] = W
     return e, mat, art
 
 
+def kurtosis_ranks(cfg: LayerConfig, r_avg: int, buckets) -> np.ndarray:
+    """Ranks [n_experts][3] of the routed experts' projections by the kurtosis-guided greedy
+    allocation of Section 3.1 (step 1) on the seeded raw weights."""
+    kappas = [compress.kurtosis(synth.make_expert_weight(cfg, e, mat))
+              for e in range(cfg.n_experts) for mat in (synth.MAT_W1, synth.MAT_W3, synth.MAT_W2)]
+    return compress.allocate_ranks(kappas, r_avg, buckets).reshape(cfg.n_experts, 3)
+
+
 def build_layer(cfg: LayerConfig, method: str = "exact", keep_weights: bool = False,
-                keep_fp64_factors: bool = False, progress: bool = False, workers: int = 0) -> dict:
-    """Quantize-then-compensate every expert of `cfg` (Section 3.1 step 2, uniform rank).
+                keep_fp64_factors: bool = False, progress: bool = False, workers: int = 0,
+                ranks=None) -> dict:
+    """Quantize-then-compensate every expert of `cfg` (Section 3.1 step 2).  Uniform rank cfg.rank,
+    or `ranks` [n_experts][3] (columns in the order W1, W3, W2) for a rank per projection.
 
     Returns {"wg", "bias", "experts": [ {mat: artefacts} ... routed then shared ]}.
     Shared experts use cfg.shared_bits and carry no factors.  `workers` > 1 compresses the
@@ -53,8 +66,10 @@ def build_layer(cfg: LayerConfig, method: str = "exact", keep_weights: bool = Fa
     """
     wg, bias = synth.make_gate(cfg)
     n_all = cfg.n_experts + cfg.n_shared
-    jobs = [(cfg, e, mat, method, keep_weights, keep_fp64_factors)
-            for e in range(n_all) for mat in (synth.MAT_W1, synth.MAT_W3, synth.MAT_W2)]
+    order = (synth.MAT_W1, synth.MAT_W3, synth.MAT_W2)
+    jobs = [(cfg, e, mat, method, keep_weights, keep_fp64_factors,
+             None if ranks is None or e >= cfg.n_experts else int(ranks[e][order.index(mat)]))
+            for e in range(n_all) for mat in order]
     experts = [dict() for _ in range(n_all)]
     t0 = time.time()
     done = 0

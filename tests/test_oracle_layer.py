@@ -159,3 +159,34 @@ def test_compensation_reduces_layer_error():
     fp = dense_moe_torch(x, layer["wg"], [tuple(ex[m]["W"] for m in (0, 1, 2)) for ex in layer["experts"]], cfg.top_k)
     errs = [orc.rel_frobenius(fixtures.oracle_forward(cfg.with_(top_n=n), layer, x)["out"], fp) for n in (0, 1, 2)]
     assert errs[0] > errs[1] > errs[2]
+
+
+def test_rank_per_projection_from_kurtosis():
+    # Section 3.1: the rank budget goes to the matrices in descending kurtosis order, so every
+    # projection has a rank of its own (0 included).  The layer with such factors equals the
+    # materialised form built from each projection's own factor pair.
+    cfg = configs.TINY.with_(rank=32, top_n=2)
+    ranks = fixtures.kurtosis_ranks(cfg, 10, (0, 8, 16, 32))
+    assert ranks.shape == (cfg.n_experts, 3) and ranks.sum() <= cfg.n_experts * 3 * 10
+    assert len(set(ranks.ravel().tolist())) >= 3 and (ranks[:, 0] != ranks[:, 1]).any()
+    layer = fixtures.build_layer(cfg, ranks=ranks)
+    for e, ex in enumerate(layer["experts"]):
+        for j, m in enumerate((0, 1, 2)):
+            r = int(ranks[e][j])
+            assert ex[m]["rank"] == r
+            assert (ex[m]["A"] is None) == (r == 0)
+            if r:
+                assert ex[m]["A"].shape[1] == r and ex[m]["B"].shape[0] == r
+    x = synth.make_tokens(cfg)
+    got = fixtures.oracle_forward(cfg, layer, x)["out"]
+    W_hat = []
+    for ex in layer["experts"]:
+        mats = []
+        for m in (0, 1, 2):
+            Wm = orc.dequant(ex[m]["codes"], ex[m]["scale"], ex[m]["zero"], cfg.group)
+            if ex[m]["A"] is not None:
+                Wm = Wm + orc.bf16_to_f64(ex[m]["A"]) @ orc.bf16_to_f64(ex[m]["B"])
+            mats.append(Wm)
+        W_hat.append(tuple(mats))
+    ref = dense_moe_torch(x, layer["wg"], W_hat, cfg.top_k)
+    np.testing.assert_allclose(got, ref, rtol=1e-10, atol=1e-12)
