@@ -41,6 +41,7 @@ def _cfg(**kw):
     (dict(max_tokens=0), -1), (dict(residency=2), -1), (dict(renormalize=2), -1), (dict(n_shared=9), -1),
     (dict(n_shared=1, shared_bits=7), -1),
     (dict(group=32), -2), (dict(hidden=200), -2), (dict(ffn=500), -2), (dict(group=128, hidden=320), -2),
+    (dict(hidden=16448), -2), (dict(ffn=65600), -2),
 ])
 def test_config_errors_before_any_device_work(lib, kw, code):
     h = C.c_void_p()
