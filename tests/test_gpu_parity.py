@@ -50,6 +50,10 @@ SMALL = {
     # heavily skewed routing at decode size: some experts get more than 32 rows (several passes of
     # the decode kernel), others none
     "tiny_skew": configs.TINY.with_(tokens=44, gate_kind="unit", gate_std=1.0, zipf_s=3.0, name="tiny_skew"),
+    # the largest quantization group (one scale/zero per 256 inputs = one per k-step of a lane row)
+    "tiny_g256": configs.TINY.with_(group=256, bits=2, tokens=20, name="tiny_g256"),
+    # a single expert: every token routes to it with weight 1, k = n = 1
+    "tiny_e1": configs.TINY.with_(n_experts=1, top_k=1, top_n=1, tokens=40, name="tiny_e1"),
     "tiny_T1": configs.TINY.with_(tokens=1, name="tiny_T1"),
     "tiny_renorm": configs.TINY.with_(renormalize=1, tokens=33, name="tiny_renorm"),
     # DeepSeek-shaped: shared experts at 4 bit, FFN 1408 (not a multiple of the 256-row k-step), k=6
