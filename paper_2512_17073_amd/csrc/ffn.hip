@@ -627,10 +627,13 @@ hipError_t launch_expert_ffn(const FfnArgs& f, hipStream_t s) {
   };
   const int chunks = f.offsets ? f.total_rows / kBM + (f.n_exp + 1) / 2 : f.n_exp * ((f.T + kBM - 1) / kBM);
   const bool w2_grid_full = chunks * ((f.H / kTileN + 15) / 16) >= 256;
-  hipError_t e = rows <= LRC_DECODE_MAX_ROWS13 ? launch_decode_ffn(f, s, 1) : tile(1);
-  if (e != hipSuccess) return e;
+  const bool d13 = rows <= LRC_DECODE_MAX_ROWS13;
   // (beyond 128 rows per expert the decode flavour would stream the weights five times or more)
-  return rows <= 24 || (!w2_grid_full && rows <= 128) ? launch_decode_ffn(f, s, 2) : tile(2);
+  const bool d2 = rows <= 24 || (!w2_grid_full && rows <= 128);
+  if (d13 && d2) return launch_decode_ffn(f, s, 3);
+  hipError_t e = d13 ? launch_decode_ffn(f, s, 1) : tile(1);
+  if (e != hipSuccess) return e;
+  return d2 ? launch_decode_ffn(f, s, 2) : tile(2);
 }
 
 }  // namespace lrc

@@ -462,9 +462,14 @@ __global__ __launch_bounds__(64 * kDecodeWaves, 4) void qgemm_decode_kernel(KArg
 // (enough for 32 n-tiles per block), the rest of `target` blocks go by weight (5 for up to 16 rows, 8 per 32 rows
 // beyond: what a pass costs), dealt by the running sum of the weights.  Entry i of the table: expert
 // (or -1), index of the block within the expert, blocks of the expert.
-__global__ __launch_bounds__(64) void plan_kernel(const int32_t* __restrict__ offsets, int E, int B, int base,
-                                                  int target, int32_t* __restrict__ plan) {
-  const int lane = threadIdx.x;
+struct PlanSpec { int B, base, target; int32_t* plan; };
+__global__ __launch_bounds__(128) void plan_kernel(const int32_t* __restrict__ offsets, int E, PlanSpec s0, PlanSpec s1) {
+  // wavefront 0 makes the first table, wavefront 1 the second (if any)
+  const PlanSpec sp = threadIdx.x < 64 ? s0 : s1;
+  if (sp.plan == nullptr) return;
+  const int B = sp.B, base = sp.base, target = sp.target;
+  int32_t* __restrict__ plan = sp.plan;
+  const int lane = threadIdx.x & 63;
   auto weight = [](int cnt) { return cnt == 0 ? 0 : cnt <= 16 ? 5 : 8 * ((cnt + 31) / 32); };
   auto scan = [&](int v) {
 #pragma unroll
@@ -614,7 +619,14 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
   a.kb_steps = a.KS; a.partial = nullptr;
   if (by_table) {
     const int B = plan_blocks(f.n_exp, f.T * f.top_k, a.NT);
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(64), 0, s, f.offsets, f.n_exp, B, (a.NT + 31) / 32, 256, f.plan);
+    const PlanSpec p13{B, (a.NT + 31) / 32, 256, f.plan};
+    PlanSpec p2{0, 0, 0, nullptr};
+    if (which & 2) {                         // the table of W2 in the same launch
+      const int NT2 = f.H / kTileN, KS2 = padded_k(f.F) / kTileK;
+      const int kb2 = f.y_part ? std::min(kMaxKBlocks, (KS2 + 15) / 16) : 1;
+      p2 = PlanSpec{plan_blocks(f.n_exp, f.T * f.top_k, NT2), (NT2 + 31) / 32, (256 + kb2 - 1) / kb2, f.plan + 4 * B};
+    }
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(128), 0, s, f.offsets, f.n_exp, p13, p2);
     a.plan = f.plan;
     hipLaunchKernelGGL((qgemm_decode_kernel<BITS, true>), dim3(B, 1, 1), dim3(64 * kDecodeWaves), lds_bytes(2), s, a);
     a.plan = nullptr;
@@ -641,8 +653,9 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
     // (second table behind the first; every K-block uses the same shares)
     int32_t* plan2 = f.plan + 4 * plan_blocks(f.n_exp, f.T * f.top_k, f.F / kTileN);
     const int B = plan_blocks(f.n_exp, f.T * f.top_k, a.NT);
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(64), 0, s, f.offsets, f.n_exp, B, (a.NT + 31) / 32,
-                       (256 + kblocks - 1) / kblocks, plan2);
+    if (!(which & 1))                        // (otherwise made together with the table of W1|W3)
+      hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(128), 0, s, f.offsets, f.n_exp,
+                         PlanSpec{B, (a.NT + 31) / 32, (256 + kblocks - 1) / kblocks, plan2}, PlanSpec{0, 0, 0, nullptr});
     a.plan = plan2;
     hipLaunchKernelGGL((qgemm_decode_kernel<BITS, false>), dim3(B, 1, kblocks), dim3(64 * kDecodeWaves), lds_bytes(1), s, a);
     a.plan = nullptr;
