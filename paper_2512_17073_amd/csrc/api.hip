@@ -6,6 +6,7 @@
 #include <new>
 
 #include "internal.h"
+#include "plan.h"
 #include "pack.h"
 
 using namespace lrc;
@@ -169,14 +170,6 @@ static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t*
   const Workspace w = plan_workspace(L, T);
   _Float16* xh = reinterpret_cast<_Float16*>(ws + w.xh);
   const int P = T * c.top_k;
-  LRC_HIP(launch_convert_x(L, x, T, xh, P + kActPadRows, offsets, row_pair, L->d_stat, stream));
-  L->stats_valid = false;
-  L->stats.stage_ms = 0.f;
-  if (c.residency == MOE_LRC_STAGED) {
-    const int rc = stage_selected(L, stream);
-    if (rc) return rc;
-  }
-  if (mark) LRC_HIP(hipEventRecord(L->marks[MOE_LRC_STAGE_XA13], stream));
   FfnArgs a{};
   a.desc = L->d_desc; a.n_exp = c.n_experts; a.bits = c.bits; a.group = c.group;
   a.rank = c.rank; a.rpad = L->routed.mat[0].rpad;
@@ -189,6 +182,17 @@ static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t*
   a.y_part = reinterpret_cast<float*>(ws + w.y_part);
   a.plan = reinterpret_cast<int32_t*>(ws + w.plan);
   a.y_rows = y_rows; a.ksplit13 = L->ksplit13; a.ksplit2 = L->ksplit2; a.total_rows = T * c.top_k;
+  // the launch that converts the activations also makes the block tables of the decode launches
+  PlanSpec plans[2];
+  expert_ffn_plan_specs(a, plans[0], plans[1]);
+  LRC_HIP(launch_convert_x(L, x, T, xh, P + kActPadRows, offsets, row_pair, L->d_stat, plans, stream));
+  L->stats_valid = false;
+  L->stats.stage_ms = 0.f;
+  if (c.residency == MOE_LRC_STAGED) {
+    const int rc = stage_selected(L, stream);
+    if (rc) return rc;
+  }
+  if (mark) LRC_HIP(hipEventRecord(L->marks[MOE_LRC_STAGE_XA13], stream));
   a.marks = mark ? &L->marks[MOE_LRC_STAGE_W13] : nullptr;
   LRC_HIP(launch_expert_ffn(a, stream));
   L->stats.path = 0;
@@ -199,7 +203,7 @@ static int run_shared(moe_lrc_layer* L, const void* x, int T, uint8_t* ws, hipSt
   const moe_lrc_config& c = L->cfg;
   const Workspace w = plan_workspace(L, T);
   _Float16* xh = reinterpret_cast<_Float16*>(ws + w.xh_sh);
-  LRC_HIP(launch_convert_x(L, x, T, xh, T + kActPadRows, nullptr, nullptr, nullptr, stream));
+  LRC_HIP(launch_convert_x(L, x, T, xh, T + kActPadRows, nullptr, nullptr, nullptr, nullptr, stream));
   FfnArgs a{};
   a.desc = L->d_desc + c.n_experts; a.n_exp = c.n_shared; a.bits = c.shared_bits; a.group = c.group;
   a.rank = 0; a.rpad = 0; a.H = c.hidden; a.F = c.ffn; a.top_k = c.top_k; a.top_n = 0; a.T = T;

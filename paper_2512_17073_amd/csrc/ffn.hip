@@ -23,6 +23,7 @@
 #include <type_traits>
 
 #include "ffn_common.h"
+#include "plan.h"
 
 namespace lrc {
 
@@ -614,9 +615,21 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
 #define LRC_DECODE_MAX_ROWS13 40
 #endif
 
-hipError_t launch_expert_ffn(const FfnArgs& f, hipStream_t s) {
+// bit 0: W1|W3 takes the decode flavour, bit 1: W2 does
+static int decode_parts(const FfnArgs& f) {
   // expected rows per expert under uniform routing decides the flavour of each projection
   const int rows = f.offsets ? (f.T * f.top_k + f.n_exp - 1) / f.n_exp : f.T;
+  const int chunks = f.offsets ? f.total_rows / kBM + (f.n_exp + 1) / 2 : f.n_exp * ((f.T + kBM - 1) / kBM);
+  const bool w2_grid_full = chunks * ((f.H / kTileN + 15) / 16) >= 256;
+  const bool d13 = rows <= LRC_DECODE_MAX_ROWS13;
+  // (beyond 128 rows per expert the decode flavour would stream the weights five times or more)
+  const bool d2 = rows <= 24 || (!w2_grid_full && rows <= 128);
+  return (d13 ? 1 : 0) | (d2 ? 2 : 0);
+}
+
+void expert_ffn_plan_specs(const FfnArgs& f, PlanSpec& p13, PlanSpec& p2) { decode_plan_specs(f, decode_parts(f), p13, p2); }
+
+hipError_t launch_expert_ffn(const FfnArgs& f, hipStream_t s) {
   auto tile = [&](int which) {
     switch (f.bits) {
       case 2: return launch_bits<2>(f, s, which);
@@ -625,15 +638,11 @@ hipError_t launch_expert_ffn(const FfnArgs& f, hipStream_t s) {
     }
     return hipErrorInvalidValue;
   };
-  const int chunks = f.offsets ? f.total_rows / kBM + (f.n_exp + 1) / 2 : f.n_exp * ((f.T + kBM - 1) / kBM);
-  const bool w2_grid_full = chunks * ((f.H / kTileN + 15) / 16) >= 256;
-  const bool d13 = rows <= LRC_DECODE_MAX_ROWS13;
-  // (beyond 128 rows per expert the decode flavour would stream the weights five times or more)
-  const bool d2 = rows <= 24 || (!w2_grid_full && rows <= 128);
-  if (d13 && d2) return launch_decode_ffn(f, s, 3);
-  hipError_t e = d13 ? launch_decode_ffn(f, s, 1) : tile(1);
+  const int dp = decode_parts(f);
+  if (dp == 3) return launch_decode_ffn(f, s, 3);
+  hipError_t e = (dp & 1) ? launch_decode_ffn(f, s, 1) : tile(1);
   if (e != hipSuccess) return e;
-  return d2 ? launch_decode_ffn(f, s, 2) : tile(2);
+  return (dp & 2) ? launch_decode_ffn(f, s, 2) : tile(2);
 }
 
 }  // namespace lrc

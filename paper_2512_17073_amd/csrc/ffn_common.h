@@ -76,5 +76,7 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 // decode flavour (ffn_decode.hip): few rows per expert, one 16-wavefront block per CU.
 // which: bit 0 = the fused W1|W3 projection (with its (x A) kernel), bit 1 = W2 (with its (h A) kernel)
 hipError_t launch_decode_ffn(const FfnArgs& f, hipStream_t s, int which);
+// the block tables (plan.h) a decode launch of the projections in `which` reads
+void decode_plan_specs(const FfnArgs& f, int which, PlanSpec& p13, PlanSpec& p2);
 
 }  // namespace lrc

@@ -18,6 +18,7 @@
 #include <type_traits>
 
 #include "ffn_common.h"
+#include "plan.h"
 
 namespace lrc {
 
@@ -456,58 +457,6 @@ __global__ __launch_bounds__(64 * kDecodeWaves, 4) void qgemm_decode_kernel(KArg
   else decode_body<BITS, DUAL, 2>(a, xs, e, r0, cnt, b, G);
 }
 
-// With many experts and skewed routing most experts have no rows and some have several 32-row
-// passes' worth: a fixed number of blocks per expert leaves most of the chip idle.  One wavefront
-// shares the B blocks of a launch out among the experts that have rows: each gets `base` blocks
-// (enough for 32 n-tiles per block), the rest of `target` blocks go by weight (5 for up to 16 rows, 8 per 32 rows
-// beyond: what a pass costs), dealt by the running sum of the weights.  Entry i of the table: expert
-// (or -1), index of the block within the expert, blocks of the expert.
-struct PlanSpec { int B, base, target; int32_t* plan; };
-__global__ __launch_bounds__(128) void plan_kernel(const int32_t* __restrict__ offsets, int E, PlanSpec s0, PlanSpec s1) {
-  // wavefront 0 makes the first table, wavefront 1 the second (if any)
-  const PlanSpec sp = threadIdx.x < 64 ? s0 : s1;
-  if (sp.plan == nullptr) return;
-  const int B = sp.B, base = sp.base, target = sp.target;
-  int32_t* __restrict__ plan = sp.plan;
-  const int lane = threadIdx.x & 63;
-  auto weight = [](int cnt) { return cnt == 0 ? 0 : cnt <= 16 ? 5 : 8 * ((cnt + 31) / 32); };
-  auto scan = [&](int v) {
-#pragma unroll
-    for (int dlt = 1; dlt < 64; dlt *= 2) {
-      const int t = __shfl_up(v, dlt);
-      if (lane >= dlt) v += t;
-    }
-    return v;
-  };
-  int n_active = 0, wsum = 0;
-  for (int e0 = 0; e0 < E; e0 += 64) {
-    const int e = e0 + lane;
-    const int cnt = e < E ? offsets[e + 1] - offsets[e] : 0;
-    n_active += __popcll(__ballot(cnt > 0));
-    wsum += __shfl(scan(weight(cnt)), 63);
-  }
-  // as many blocks as fill the chip (`target`), more only if the experts with rows need them; the
-  // rest of the grid exits at once
-  const int total = min(B, max(target, n_active * base));
-  const long long extra = total - n_active * base;
-  int act_before = 0, w_before = 0, used = 0;
-  for (int e0 = 0; e0 < E; e0 += 64) {
-    const int e = e0 + lane;
-    const int cnt = e < E ? offsets[e + 1] - offsets[e] : 0;
-    const int act = cnt > 0 ? 1 : 0, w = weight(cnt), wi = scan(w), ai = scan(act);
-    if (act) {
-      const int lo = (act_before + ai - 1) * base + int(extra * (w_before + wi - w) / wsum);
-      const int hi = (act_before + ai) * base + int(extra * (w_before + wi) / wsum);
-      for (int i = lo; i < hi && i < B; ++i) {
-        plan[4 * i] = e; plan[4 * i + 1] = i - lo; plan[4 * i + 2] = hi - lo; plan[4 * i + 3] = 0;
-      }
-    }
-    act_before += __shfl(ai, 63); w_before += __shfl(wi, 63);
-  }
-  used = n_active > 0 ? n_active * base + int(extra) : 0;
-  for (int i = used + lane; i < B; i += 64) { plan[4 * i] = -1; plan[4 * i + 1] = 0; plan[4 * i + 2] = 1; plan[4 * i + 3] = 0; }
-}
-
 // Partial (in A): pk[kb2][row][rho] = sum over K-block kb2 of in[row][k] * A[k][rho] in fp32, for the
 // rows that take the rank-r term.  grid = (16-column tiles of the factor(s), experts, K-blocks); the
 // 8 wavefronts of a block split their K-block and add their parts through LDS in a fixed order.
@@ -574,6 +523,13 @@ __global__ __launch_bounds__(256) void reduce_kernel(const float* __restrict__ p
   y[u] = v;
 }
 
+// Block tables pay when experts are likely to be without rows or to differ much in rows: many
+// experts, or few pairs per expert.  Otherwise (e.g. 8 experts, 64 tokens) every expert gets the
+// same share of a (blocks per expert x experts) grid.
+static bool use_plan(const FfnArgs& f) {
+  return f.offsets != nullptr && f.plan != nullptr && (f.n_exp >= 32 || f.T * f.top_k < 4 * f.n_exp);
+}
+
 template <int BITS>
 hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
   static bool attr_set = false;
@@ -605,8 +561,9 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
   // activations + the (in A) fragments: [projections][rank steps][2 row tiles] KB
   auto lds_bytes = [&](int nm) { return size_t(kDecodeLdsUnits) * 16 + (comp ? size_t(nm) * a.ls * 2 * 1024 : 0); };
   auto xa_blocks = [](int K) { return std::max(1, std::min(8, K / 1024)); };   // K-blocks of the (in A) kernels
-  // many experts: the blocks are shared out on the device among the experts that have rows
-  const bool by_table = f.offsets != nullptr && f.plan != nullptr && f.n_exp >= 32;
+  // the blocks are shared out among the experts that have rows by the tables the launch that
+  // prepared the activations has left (plan.h)
+  const bool by_table = use_plan(f);
 
   if (which & 1) {
   // W1 | W3 with the SwiGLU epilogue
@@ -619,14 +576,6 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
   a.kb_steps = a.KS; a.partial = nullptr;
   if (by_table) {
     const int B = plan_blocks(f.n_exp, f.T * f.top_k, a.NT);
-    const PlanSpec p13{B, (a.NT + 31) / 32, 256, f.plan};
-    PlanSpec p2{0, 0, 0, nullptr};
-    if (which & 2) {                         // the table of W2 in the same launch
-      const int NT2 = f.H / kTileN, KS2 = padded_k(f.F) / kTileK;
-      const int kb2 = f.y_part ? std::min(kMaxKBlocks, (KS2 + 15) / 16) : 1;
-      p2 = PlanSpec{plan_blocks(f.n_exp, f.T * f.top_k, NT2), (NT2 + 31) / 32, (256 + kb2 - 1) / kb2, f.plan + 4 * B};
-    }
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(128), 0, s, f.offsets, f.n_exp, p13, p2);
     a.plan = f.plan;
     hipLaunchKernelGGL((qgemm_decode_kernel<BITS, true>), dim3(B, 1, 1), dim3(64 * kDecodeWaves), lds_bytes(2), s, a);
     a.plan = nullptr;
@@ -652,10 +601,7 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
   if (by_table) {
     // (second table behind the first; every K-block uses the same shares)
     int32_t* plan2 = f.plan + 4 * plan_blocks(f.n_exp, f.T * f.top_k, f.F / kTileN);
-    const int B = plan_blocks(f.n_exp, f.T * f.top_k, a.NT);
-    if (!(which & 1))                        // (otherwise made together with the table of W1|W3)
-      hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(128), 0, s, f.offsets, f.n_exp,
-                         PlanSpec{B, (a.NT + 31) / 32, (256 + kblocks - 1) / kblocks, plan2}, PlanSpec{0, 0, 0, nullptr});
+    const int B = plan_blocks(f.n_exp, f.T * f.top_k, a.NT, (256 + kblocks - 1) / kblocks);
     a.plan = plan2;
     hipLaunchKernelGGL((qgemm_decode_kernel<BITS, false>), dim3(B, 1, kblocks), dim3(64 * kDecodeWaves), lds_bytes(1), s, a);
     a.plan = nullptr;
@@ -680,6 +626,20 @@ extern "C" int moe_lrc_debug_timeline(long long* host_out) {
   return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_timeline), sizeof(long long) * 2 * 4096 * 16);
 }
 #endif
+
+void decode_plan_specs(const FfnArgs& f, int which, PlanSpec& p13, PlanSpec& p2) {
+  p13 = PlanSpec{0, 0, 0, nullptr};
+  p2 = PlanSpec{0, 0, 0, nullptr};
+  if (!use_plan(f)) return;
+  const int pairs = f.T * f.top_k, NT13 = f.F / kTileN, NT2 = f.H / kTileN;
+  const int B13 = plan_blocks(f.n_exp, pairs, NT13);
+  if (which & 1) p13 = PlanSpec{B13, (NT13 + 31) / 32, 256, f.plan};
+  if (which & 2) {
+    const int KS2 = padded_k(f.F) / kTileK, kb2 = f.y_part ? std::min(kMaxKBlocks, (KS2 + 15) / 16) : 1;
+    const int target2 = (256 + kb2 - 1) / kb2;
+    p2 = PlanSpec{plan_blocks(f.n_exp, pairs, NT2, target2), (NT2 + 31) / 32, target2, f.plan + 4 * B13};
+  }
+}
 
 hipError_t launch_decode_ffn(const FfnArgs& f, hipStream_t s, int which) {
   switch (f.bits) {

@@ -77,18 +77,20 @@ hipError_t launch_route(const moe_lrc_layer* L, const void* x, int T, int32_t* i
 hipError_t launch_permute(const moe_lrc_layer* L, const int32_t* idx, int T, int32_t* counts,
                           int32_t* offsets, int32_t* row_pair, int32_t* pair_row,
                           int32_t* comp_counts, hipStream_t s);
+struct PlanSpec;   // plan.h
 // fp16 copy of the activations in operand order: one row per routed pair (row_pair given) or one
 // per token (row_pair null); with `stat`, one more block counts the per-expert rows
 hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _Float16* xg, int rt,
                             const int32_t* offsets, const int32_t* row_pair, int32_t* stat,
-                            hipStream_t s);
+                            const PlanSpec* plans /* two, or null */, hipStream_t s);
 constexpr int kMaxKBlocks = 8;    // most K-blocks the decode W2 kernel splits into
-// blocks (per K-block) of a decode launch that shares its blocks out by a table: the 256 CUs, or
-// enough for ceil(NT / 32) blocks per expert that can be active
-inline int plan_blocks(int n_exp, int pairs, int NT) {
+// blocks (per K-block) of a decode launch that shares its blocks out by a table: `target` (the 256
+// CUs over the K-blocks), or enough for ceil(NT / 32) blocks per expert that can be active
+inline int plan_blocks(int n_exp, int pairs, int NT, int target = 256) {
   const int active = n_exp < pairs ? n_exp : pairs, base = (NT + 31) / 32;
-  return active * base > 256 ? active * base : 256;
+  return active * base > target ? active * base : target;
 }
+
 constexpr int kActPadRows = 32;   // rows past the last one that a 32-row staging pass may read
 
 struct FfnArgs {
@@ -112,6 +114,8 @@ struct FfnArgs {
   hipEvent_t* marks;          // null, or 4 events recorded after xa13, w13, xa2, w2
 };
 hipError_t launch_expert_ffn(const FfnArgs& a, hipStream_t s);
+// the block tables (plan.h) that launch_expert_ffn(a) will read: to be made by launch_convert_x
+void expert_ffn_plan_specs(const FfnArgs& a, PlanSpec& p13, PlanSpec& p2);
 hipError_t launch_combine(const moe_lrc_layer* L, const void* y_rows, const float* w,
                           const int32_t* pair_row, const void* y_shared, int T, void* out,
                           hipStream_t s);

@@ -3,6 +3,7 @@
 #include <algorithm>
 
 #include "internal.h"
+#include "plan.h"
 #include "unpack.h"
 
 namespace lrc {
@@ -65,8 +66,13 @@ __global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ 
                                                    uint4* __restrict__ xg, int rt,
                                                    const int32_t* __restrict__ offsets,
                                                    const int32_t* __restrict__ row_pair, int E, int top_k,
-                                                   int top_n, int32_t* __restrict__ stat) {
+                                                   int top_n, int32_t* __restrict__ stat, PlanSpec plan0,
+                                                   PlanSpec plan1) {
   const int row_blocks = (rows + 15) / 16;
+  if ((int)blockIdx.x == (int)gridDim.x - 1 && plan0.B + plan1.B > 0) {   // last block: the block tables (plan.h)
+    if (blockIdx.y == 0 && threadIdx.x < 128) make_plan(offsets, E, threadIdx.x < 64 ? plan0 : plan1, threadIdx.x & 63);
+    return;
+  }
   if ((int)blockIdx.x >= row_blocks) {
     const int e = ((int)blockIdx.x - row_blocks) * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
     if (e >= E || blockIdx.y != 0) return;
@@ -129,14 +135,17 @@ hipError_t launch_combine(const moe_lrc_layer* L, const void* y_rows, const floa
 
 hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _Float16* xg, int rt,
                             const int32_t* offsets, const int32_t* row_pair, int32_t* stat,
-                            hipStream_t s) {
+                            const PlanSpec* plans, hipStream_t s) {
   const moe_lrc_config& c = L->cfg;
   const int rows = row_pair ? T * c.top_k : T;
   const int row_blocks = (rows + 15) / 16;
   const int ky = std::max(1, std::min(c.hidden / 128, 256 / std::max(1, row_blocks)));
-  hipLaunchKernelGGL(prep_kernel, dim3(row_blocks + (stat ? (c.n_experts + 3) / 4 : 0), ky), dim3(256), 0, s,
+  const PlanSpec none{0, 0, 0, nullptr};
+  const PlanSpec p0 = plans ? plans[0] : none, p1 = plans ? plans[1] : none;
+  const int plan_block = p0.B + p1.B > 0 ? 1 : 0;
+  hipLaunchKernelGGL(prep_kernel, dim3(row_blocks + (stat ? (c.n_experts + 3) / 4 : 0) + plan_block, ky), dim3(256), 0, s,
                      (const uint16_t*)x_bf16, rows, c.hidden, reinterpret_cast<uint4*>(xg), rt, offsets, row_pair,
-                     c.n_experts, c.top_k, c.top_n, stat);
+                     c.n_experts, c.top_k, c.top_n, stat, p0, p1);
   return hipGetLastError();
 }
 

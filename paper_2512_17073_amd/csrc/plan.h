@@ -1,0 +1,74 @@
+// Sharing a decode launch's blocks out among the experts that have rows.
+//
+// With a fixed number of blocks per expert, experts without rows leave CUs idle and experts with
+// several 32-row passes finish last.  One wavefront (part of the launch that prepares the
+// activations) writes, for every block of the later launch, which expert it serves: each expert with
+// rows gets `base` blocks (enough for 32 n-tiles per block), the rest of `target` blocks go by
+// weight (5 for up to 16 rows, 8 per 32-row pass beyond: what they cost), dealt by the running
+// sum of the weights.  Entry i of the table: expert (or -1: the block exits), index of the block within
+// the expert, blocks of the expert, unused.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lrc {
+
+struct PlanSpec { int B, base, target; int32_t* plan; };   // B entries; plan == null: no table wanted
+
+__device__ inline void make_plan(const int32_t* __restrict__ offsets, int E, const PlanSpec sp, int lane) {
+  if (sp.plan == nullptr) return;
+  const int B = sp.B, base = sp.base, target = sp.target;
+  int32_t* __restrict__ plan = sp.plan;
+  auto weight = [](int cnt) { return cnt == 0 ? 0 : cnt <= 16 ? 5 : 8 * ((cnt + 31) / 32); };
+  auto scan = [&](int v) {
+#pragma unroll
+    for (int dlt = 1; dlt < 64; dlt *= 2) {
+      const int t = __shfl_up(v, dlt);
+      if (lane >= dlt) v += t;
+    }
+    return v;
+  };
+  int n_active = 0, wsum = 0;
+  for (int e0 = 0; e0 < E; e0 += 64) {
+    const int e = e0 + lane;
+    const int cnt = e < E ? offsets[e + 1] - offsets[e] : 0;
+    n_active += __popcll(__ballot(cnt > 0));
+    wsum += __shfl(scan(weight(cnt)), 63);
+  }
+  // as many blocks as fill the chip (`target`), more only if the experts with rows need them; the
+  // rest of the grid exits at once
+  const int total = min(B, max(target, n_active * base));
+  const long long extra = total - n_active * base;
+  int act_before = 0, w_before = 0;
+  for (int e0 = 0; e0 < E; e0 += 64) {
+    const int e = e0 + lane;
+    const int cnt = e < E ? offsets[e + 1] - offsets[e] : 0;
+    const int act = cnt > 0 ? 1 : 0, w = weight(cnt), wi = scan(w), ai = scan(act);
+    int lo = 0, hi = 0;
+    if (act) {
+      lo = (act_before + ai - 1) * base + int(extra * (w_before + wi - w) / wsum);
+      hi = (act_before + ai) * base + int(extra * (w_before + wi) / wsum);
+    }
+    const unsigned long long with_rows = __ballot(act != 0);
+    if (__popcll(with_rows) <= 8) {
+      // few experts with many blocks each: the whole wavefront writes one expert's entries after the other's
+      for (unsigned long long todo = with_rows; todo; todo &= todo - 1) {
+        const int j = __ffsll(todo) - 1;
+        const int lo_j = __shfl(lo, j), G_j = __shfl(hi, j) - lo_j, hi_j = min(lo_j + G_j, B);
+        for (int i = lo_j + lane; i < hi_j; i += 64) {
+          plan[4 * i] = e0 + j; plan[4 * i + 1] = i - lo_j; plan[4 * i + 2] = G_j; plan[4 * i + 3] = 0;
+        }
+      }
+    } else if (act) {
+      // many experts with few blocks each: every lane writes its own expert's entries
+      for (int i = lo; i < hi && i < B; ++i) {
+        plan[4 * i] = e; plan[4 * i + 1] = i - lo; plan[4 * i + 2] = hi - lo; plan[4 * i + 3] = 0;
+      }
+    }
+    act_before += __shfl(ai, 63); w_before += __shfl(wi, 63);
+  }
+  const int used = n_active > 0 ? n_active * base + int(extra) : 0;
+  for (int i = used + lane; i < B; i += 64) { plan[4 * i] = -1; plan[4 * i + 1] = 0; plan[4 * i + 2] = 1; plan[4 * i + 3] = 0; }
+}
+
+}  // namespace lrc
