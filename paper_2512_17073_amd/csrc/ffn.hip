@@ -162,7 +162,7 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
       const int tile = tile0 + t;
       const bool ok = step < a.KS && tile < a.NT;
       const bool lr = step >= a.KS && step < a.KS + LS && tile < a.NT;
-      const int tile_off = (ok ? (step * a.NT + tile) * (tdw * 4) : lr ? (tile * a.ls + (step - a.KS)) * 1024 : max(code_bytes, bf_bytes)) + lane * 16;
+      const int tile_off = (ok ? (step * a.NT + tile) * (tdw * 4) : lr ? ((step - a.KS) * a.NT + tile) * 1024 : max(code_bytes, bf_bytes)) + lane * 16;
       const int tile_off2 = (ok ? (step * a.NT + tile) * (tdw * 4) : code_bytes) + 1024 + lane * (BITS == 3 ? 8 : 16);
       const int meta_off = (ok ? (step * gps * a.NT + tile) * (kTileN * 4) : meta_bytes) + meta_lane;
 #pragma unroll
@@ -396,7 +396,7 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
 // xa_tile_kernel: K-block partial sums in fp32, [K-block][row][NM * ls * 32 columns] ([A1 | A3] in
 // the fused case, each padded to a multiple of 32), already multiplied by the projection's
 // power-of-two pre-scale.  Same shape as the kernel above (activations through double-buffered LDS,
-// eight row tiles per fragment of weights), with the fp16 factor tiles [K/32][rpad/16][lane][8] as
+// eight row tiles per fragment of weights), with the fp16 factor tiles [rpad/16][K/32][lane][8] as
 // the weight operand: wavefront w owns the 16-column factor tiles w, w + 8, ... (at most four);
 // grid.x splits K so that the launch fills the chip.
 // xa_finish_kernel: adds the K-blocks in order, zeroes the rows without the rank-r term and the
@@ -436,7 +436,7 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void xa_tile_kernel(KArgs a) {
     af[t] = nullptr;
     if (tile < tiles) {
       const int m = tile / rt, tl = tile - m * rt;
-      af[t] = reinterpret_cast<const half8_t*>(uniform_ptr(d.af[DUAL ? m : 2])) + size_t(tl) * kWave + c;
+      af[t] = reinterpret_cast<const half8_t*>(uniform_ptr(d.af[DUAL ? m : 2])) + size_t(tl) * (a.K / 32) * kWave + c;
       nmine = t + 1;
     }
   }
@@ -448,7 +448,7 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void xa_tile_kernel(KArgs a) {
   auto load_unit = [&](int step, int s, int t) {
     const int kk = step * 8 + 2 * q + (s >> 2);          // this lane's 32-row unit of the factor
     half8_t v = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
-    if (t < nmine && kk * 32 < a.K) v = af[t][size_t(kk) * rt * kWave + (s & 3) * 16];
+    if (t < nmine && kk * 32 < a.K) v = af[t][size_t(kk) * kWave + (s & 3) * 16];
     return v;
   };
   half8_t wnext[kAhead ? 8 : 1][kMaxT];

@@ -167,7 +167,7 @@ __device__ LRC_BODY_INLINE void decode_body(const KArgs& a, uint4* xs, const int
       const bool lr = !reg && l < LSP && tile < t1 && st < LS;               // a rank step of the B factor
       const int ks = ks_lo + ph * KP + kl;
       // the offsets go into the per-lane offset operand: that is the one the hardware range-checks
-      const int tile_off = (ok ? (ks * a.NT + tile) * (tdw * 4) : lr ? (tile * a.ls + st) * 1024 : max(code_bytes, bf_bytes)) + lane * 16;
+      const int tile_off = (ok ? (ks * a.NT + tile) * (tdw * 4) : lr ? (st * a.NT + tile) * 1024 : max(code_bytes, bf_bytes)) + lane * 16;
       const int tile_off2 = (ok ? (ks * a.NT + tile) * (tdw * 4) : code_bytes) + 1024 + lane * (BITS == 3 ? 8 : 16);
       const int meta_off = (ok ? (ks * gps * a.NT + tile) * (kTileN * 4) : meta_bytes) + meta_lane;
 #pragma unroll
@@ -491,7 +491,7 @@ __global__ __launch_bounds__(512) void xa_split_kernel(KArgs a) {
         wf[u] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
         xf[u] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
         if (kk + u < kk1) {
-          wf[u] = af[(size_t(kk + u) * rt + tl) * kWave + lane];
+          wf[u] = af[(size_t(tl) * k32 + kk + u) * kWave + lane];
           if (flagged) xf[u] = src[act_unit(4 * (kk + u) + q, r0 + row, a.in_rt)];
         }
       }

@@ -125,30 +125,32 @@ float pack_meta(const MatLayout& m, const uint16_t* scale_f16, const uint16_t* z
   return (float)lambda;
 }
 
+// Both factors are stored rank-major, so that a smaller rank is a prefix of the same layout: the
+// 16-column tiles of A one after the other, the 32-wide rank steps of B one after the other.
 void pack_factor_a(const MatLayout& m, int rank, const uint16_t* A_bf16, uint16_t* out) {
-  // [K/32][rpad/16][lane][8]: lane (c, q) holds A[32*kk + 8*q + j][16*tile + c], j = 0..7
-  const int rt = m.rpad / 16;
+  // [rpad/16][K/32][lane][8]: lane (c, q) holds A[32*kk + 8*q + j][16*tile + c], j = 0..7
+  const int rt = m.rpad / 16, k32 = m.K / 32;
   std::memset(out, 0, m.af_bytes);
-  for (int kk = 0; kk < m.K / 32; ++kk)
-    for (int tile = 0; tile < rt; ++tile)
+  for (int tile = 0; tile < rt; ++tile)
+    for (int kk = 0; kk < k32; ++kk)
       for (int lane = 0; lane < kWave; ++lane) {
         const int c = lane & 15, q = lane >> 4, rho = 16 * tile + c;
         if (rho >= rank) continue;
-        uint16_t* dst = out + ((size_t(kk) * rt + tile) * kWave + lane) * 8;
+        uint16_t* dst = out + ((size_t(tile) * k32 + kk) * kWave + lane) * 8;
         for (int j = 0; j < 8; ++j)
           dst[j] = float_to_f16_bits(bf16_bits_to_float(A_bf16[size_t(32 * kk + 8 * q + j) * rank + rho]));
       }
 }
 
 void pack_factor_b(const MatLayout& m, int rank, const uint16_t* B_bf16, uint16_t* out) {
-  // [N/16][ceil(rank/32)][lane][8]: lane (c, q) holds B[32*st + 8*q + j][16*nt + c], j = 0..7 (zero past
+  // [ceil(rank/32)][N/16][lane][8]: lane (c, q) holds B[32*st + 8*q + j][16*nt + c], j = 0..7 (zero past
   // the rank): one 16-byte unit per lane, the A operand of a 16x16x32 MFMA step over 32 rank indices
   std::memset(out, 0, m.bf_bytes);
-  for (int nt = 0; nt < m.NT; ++nt)
-    for (int st = 0; st < m.ls; ++st)
+  for (int st = 0; st < m.ls; ++st)
+    for (int nt = 0; nt < m.NT; ++nt)
       for (int lane = 0; lane < kWave; ++lane) {
         const int c = lane & 15, q = lane >> 4;
-        uint16_t* dst = out + ((size_t(nt) * m.ls + st) * kWave + lane) * 8;
+        uint16_t* dst = out + ((size_t(st) * m.NT + nt) * kWave + lane) * 8;
         for (int j = 0; j < 8; ++j) {
           const int rho = 32 * st + 8 * q + j;
           if (rho < rank)
