@@ -64,7 +64,8 @@ typedef struct {
   int32_t bits;         /* code width of routed experts: 2, 3 or 4                        */
   int32_t shared_bits;  /* code width of shared experts: 2, 3 or 4 (ignored if S == 0)    */
   int32_t group;        /* quantization group along the input dim: 64, 128 or 256         */
-  int32_t rank;         /* compensator rank r >= 0, multiple of 8, <= 256                 */
+  int32_t rank;         /* compensator rank r >= 0, multiple of 8, <= 256: the rank of
+                           moe_lrc_set_expert, the largest moe_lrc_set_expert_ranked takes  */
   int32_t renormalize;  /* 0: routing weights are the softmax-over-all scores (Section 2.1)
                            1: divided by their sum over the k selected                    */
   int32_t max_tokens;   /* largest T any call will pass                                   */
@@ -95,6 +96,16 @@ int moe_lrc_set_gate(moe_lrc_layer* layer, const uint16_t* wg_bf16, const float*
 int moe_lrc_set_expert(moe_lrc_layer* layer, int expert, int mat, const uint8_t* codes,
                        const uint16_t* scale_f16, const uint16_t* zero_f16,
                        const uint16_t* A_bf16, const uint16_t* B_bf16);
+
+/* The same with a rank of its own for this projection (Section 3.1: the rank budget is spread over
+ * the expert matrices by their kurtosis, so ranks differ from matrix to matrix and may be 0).
+ * rank: multiple of 8, 0..cfg.rank; A_bf16 [K][rank], B_bf16 [rank][N], both NULL when rank == 0.
+ * Only `rank` columns/rows are stored in the pinned pool and moved by the staged mode (the byte
+ * counters of moe_lrc_get_stats follow); the kernels run cfg.rank steps on zero padding.
+ * moe_lrc_set_expert is this call with rank = cfg.rank (0 for shared experts). */
+int moe_lrc_set_expert_ranked(moe_lrc_layer* layer, int expert, int mat, const uint8_t* codes,
+                              const uint16_t* scale_f16, const uint16_t* zero_f16,
+                              const uint16_t* A_bf16, const uint16_t* B_bf16, int rank);
 
 /* Bytes of device workspace the hot-path calls need for T tokens (the largest over all calls). */
 size_t moe_lrc_workspace_bytes(const moe_lrc_layer* layer, int T);

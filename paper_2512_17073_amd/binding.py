@@ -20,7 +20,7 @@ RESIDENT, STAGED = 0, 1
 # every symbol include/moe_lrc.h declares
 EXPORTS = [
     "moe_lrc_last_error", "moe_lrc_layer_create", "moe_lrc_layer_destroy", "moe_lrc_set_gate",
-    "moe_lrc_set_expert", "moe_lrc_workspace_bytes", "moe_lrc_route", "moe_lrc_permute",
+    "moe_lrc_set_expert", "moe_lrc_set_expert_ranked", "moe_lrc_workspace_bytes", "moe_lrc_route", "moe_lrc_permute",
     "moe_lrc_expert_ffn", "moe_lrc_combine", "moe_lrc_forward", "moe_lrc_debug_unpack",
     "moe_lrc_packed_bytes", "moe_lrc_pack_codes", "moe_lrc_unpack_codes", "moe_lrc_get_stats",
     "moe_lrc_profile_enable", "moe_lrc_profile_read",
@@ -66,6 +66,7 @@ def lib() -> C.CDLL:
         L.moe_lrc_layer_destroy.argtypes = [vp]
         L.moe_lrc_set_gate.argtypes = [vp, vp, vp]
         L.moe_lrc_set_expert.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp]
+        L.moe_lrc_set_expert_ranked.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, i32]
         L.moe_lrc_workspace_bytes.argtypes = [vp, i32]
         L.moe_lrc_workspace_bytes.restype = sz
         L.moe_lrc_route.argtypes = [vp, vp, i32, vp, vp, vp]
@@ -164,10 +165,16 @@ class Layer:
         b = _host(bias, np.float32)
         _check(lib().moe_lrc_set_gate(self._h, _hp(wg), _hp(b)))
 
-    def set_expert(self, expert: int, mat: int, codes, scale_f16, zero_f16, A_bf16=None, B_bf16=None) -> None:
+    def set_expert(self, expert: int, mat: int, codes, scale_f16, zero_f16, A_bf16=None, B_bf16=None,
+                   rank: Optional[int] = None) -> None:
+        """rank None: the layer's rank (moe_lrc_set_expert); an int: this projection's own rank
+        (moe_lrc_set_expert_ranked), with A [K][rank] and B [rank][N], both None for rank 0."""
         arrs = [_host(codes, np.uint8), _host(scale_f16, np.uint16), _host(zero_f16, np.uint16),
                 _host(A_bf16, np.uint16), _host(B_bf16, np.uint16)]
-        _check(lib().moe_lrc_set_expert(self._h, expert, mat, *[_hp(a) for a in arrs]))
+        if rank is None:
+            _check(lib().moe_lrc_set_expert(self._h, expert, mat, *[_hp(a) for a in arrs]))
+        else:
+            _check(lib().moe_lrc_set_expert_ranked(self._h, expert, mat, *[_hp(a) for a in arrs], int(rank)))
 
     def load(self, layer: dict) -> None:
         """layer = {"wg", "bias", "experts": [{mat: {"codes","scale","zero","A","B"}}]}."""
@@ -175,7 +182,7 @@ class Layer:
         for e, ex in enumerate(layer["experts"]):
             for mat in (0, 1, 2):
                 a = ex[mat]
-                self.set_expert(e, mat, a["codes"], a["scale"], a["zero"], a.get("A"), a.get("B"))
+                self.set_expert(e, mat, a["codes"], a["scale"], a["zero"], a.get("A"), a.get("B"), a.get("rank"))
 
     # ---- workspace ----
     def workspace_bytes(self, T: int) -> int:

@@ -137,7 +137,12 @@ static void fill_algorithmic_stats(moe_lrc_layer* L, const int32_t* stat) {
   s.comp_experts = (c.rank > 0 && c.top_n > 0) ? comp : 0;
   s.bytes_codes = uint64_t(active) * (P * c.bits / 8) + uint64_t(c.n_shared) * (P * c.shared_bits / 8);
   s.bytes_meta = uint64_t(active + c.n_shared) * (P / c.group * 4);
-  s.bytes_factors = uint64_t(s.comp_experts) * 3ull * c.rank * (c.hidden + c.ffn) * 2;
+  s.bytes_factors = 0;
+  if (c.rank > 0 && c.top_n > 0)
+    for (int e = 0; e < c.n_experts; ++e)
+      if (stat[2 + c.n_experts + e] > 0)
+        for (int mat = 0; mat < 3; ++mat)      // A [K][r] and B [r][N] as bf16: r (K + N) values
+          s.bytes_factors += uint64_t(L->mat_rank[e * 3 + mat]) * (c.hidden + c.ffn) * 2;
   L->stats_valid = true;
 }
 
@@ -156,7 +161,14 @@ static int stage_selected(moe_lrc_layer* L, hipStream_t stream) {
     if (shared || L->h_stat[2 + e] > 0)
       LRC_HIP(hipMemcpyAsync(L->d_w + L->w_off[e], L->h_w + L->w_off[e], b.w_bytes, hipMemcpyHostToDevice, L->side));
     if (!shared && b.f_bytes && c.top_n > 0 && L->h_stat[2 + E + e] > 0)
-      LRC_HIP(hipMemcpyAsync(L->d_f + L->f_off[e], L->h_f + L->f_off[e], b.f_bytes, hipMemcpyHostToDevice, L->side));
+      for (int mat = 0; mat < 3; ++mat) {
+        const int r = L->mat_rank[e * 3 + mat];
+        if (r == 0) continue;
+        const MatLayout fm = make_layout(b.mat[mat].K, b.mat[mat].N, b.mat[mat].bits, b.mat[mat].group, r);
+        const size_t aoff = L->f_off[e] + b.off_af[mat], boff = L->f_off[e] + b.off_bf[mat];
+        LRC_HIP(hipMemcpyAsync(L->d_f + aoff, L->h_f + aoff, fm.af_bytes, hipMemcpyHostToDevice, L->side));
+        LRC_HIP(hipMemcpyAsync(L->d_f + boff, L->h_f + boff, fm.bf_bytes, hipMemcpyHostToDevice, L->side));
+      }
   }
   LRC_HIP(hipEventRecord(L->ev_t1, L->side));
   LRC_HIP(hipStreamWaitEvent(stream, L->ev_t1, 0));
@@ -238,6 +250,7 @@ int moe_lrc_layer_create(const moe_lrc_config* cfg, moe_lrc_layer** out) {
   L->ksplit13 = std::max(1, std::min(8, cfg->hidden / 512));
   L->ksplit2 = std::max(1, std::min(16, cfg->ffn / 512));
   L->mat_set.assign(size_t(L->n_total) * 3, 0);
+  L->mat_rank.assign(size_t(L->n_total) * 3, 0);
   size_t w = 0, f = 0;
   for (int e = 0; e < L->n_total; ++e) {
     L->w_off.push_back(w); L->f_off.push_back(f);
@@ -253,6 +266,8 @@ int moe_lrc_layer_create(const moe_lrc_config* cfg, moe_lrc_layer** out) {
   } while (0)
   LRC_TRY(hipMalloc((void**)&L->d_w, std::max<size_t>(w, 256)));
   LRC_TRY(hipMalloc((void**)&L->d_f, std::max<size_t>(f, 256)));
+  // (a projection uploaded with a smaller rank fills a prefix of its sections: the rest stays zero)
+  LRC_TRY(hipMemset(L->d_f, 0, std::max<size_t>(f, 256)));
   if (cfg->residency == MOE_LRC_STAGED) {
     LRC_TRY(hipHostMalloc((void**)&L->h_w, std::max<size_t>(w, 256), hipHostMallocDefault));
     LRC_TRY(hipHostMalloc((void**)&L->h_f, std::max<size_t>(f, 256), hipHostMallocDefault));
@@ -328,15 +343,19 @@ int moe_lrc_set_gate(moe_lrc_layer* L, const uint16_t* wg, const float* bias) {
   return MOE_LRC_OK;
 }
 
-int moe_lrc_set_expert(moe_lrc_layer* L, int expert, int mat, const uint8_t* codes,
-                       const uint16_t* scale, const uint16_t* zero, const uint16_t* A, const uint16_t* B) {
+int moe_lrc_set_expert_ranked(moe_lrc_layer* L, int expert, int mat, const uint8_t* codes,
+                              const uint16_t* scale, const uint16_t* zero, const uint16_t* A, const uint16_t* B,
+                              int rank) {
   if (!L || !codes || !scale || !zero) return set_error(MOE_LRC_EINVAL, "set_expert: null argument");
   if (expert < 0 || expert >= L->n_total) return set_error(MOE_LRC_EINVAL, "set_expert: expert out of range");
   if (mat < 0 || mat > 2) return set_error(MOE_LRC_EINVAL, "set_expert: mat must be 0, 1 or 2");
   const moe_lrc_config& c = L->cfg;
   const BlobLayout& b = blob_of(L, expert);
   const MatLayout& m = b.mat[mat];
-  const bool wants = b.f_bytes > 0;
+  const int max_rank = b.f_bytes > 0 ? c.rank : 0;
+  if (rank < 0 || rank > max_rank || rank % 8)
+    return set_error(MOE_LRC_EINVAL, "set_expert: rank must be a multiple of 8 in 0..layer rank (0 for shared experts)");
+  const bool wants = rank > 0;
   if (wants && (!A || !B)) return set_error(MOE_LRC_EINVAL, "set_expert: factors required when rank > 0");
   if (!wants && (A || B)) return set_error(MOE_LRC_EINVAL, "set_expert: factors given for rank 0 or a shared expert");
   const uint32_t limit = 1u << m.bits;
@@ -348,26 +367,43 @@ int moe_lrc_set_expert(moe_lrc_layer* L, int expert, int mat, const uint8_t* cod
   const float lambda = pack_meta(m, scale, zero, reinterpret_cast<uint32_t*>(wbuf.data() + m.codes_bytes));
   // codes and meta sections of one projection are adjacent in the blob
   const size_t woff = L->w_off[expert] + b.off_codes[mat];
-  std::vector<uint8_t> fbuf;
-  size_t foff = 0;
-  if (wants) {
-    fbuf.resize(m.af_bytes + m.bf_bytes);
-    pack_factor_a(m, c.rank, A, reinterpret_cast<uint16_t*>(fbuf.data()));
-    pack_factor_b(m, c.rank, B, reinterpret_cast<uint16_t*>(fbuf.data() + m.af_bytes));
-    foff = L->f_off[expert] + b.off_af[mat];
+  if (c.residency == MOE_LRC_STAGED) std::memcpy(L->h_w + woff, wbuf.data(), wbuf.size());
+  else LRC_HIP(hipMemcpy(L->d_w + woff, wbuf.data(), wbuf.size(), hipMemcpyHostToDevice));
+
+  // Factors: the layouts are rank-major, so the pair of rank `rank` is a prefix of the projection's A
+  // section and a prefix of its B section; the rest of both sections is kept zero in the device slot
+  // (the kernels run the layer's rank on every expert), and only the prefixes are staged.
+  if (b.f_bytes > 0) {
+    const MatLayout fm = make_layout(m.K, m.N, m.bits, m.group, rank);     // sizes of the prefixes
+    const size_t aoff = L->f_off[expert] + b.off_af[mat], boff = L->f_off[expert] + b.off_bf[mat];
+    std::vector<uint8_t> abuf(fm.af_bytes), bbuf(fm.bf_bytes);
+    if (wants) {
+      pack_factor_a(fm, rank, A, reinterpret_cast<uint16_t*>(abuf.data()));
+      pack_factor_b(fm, rank, B, reinterpret_cast<uint16_t*>(bbuf.data()));
+    }
+    if (c.residency == MOE_LRC_STAGED) {
+      if (wants) { std::memcpy(L->h_f + aoff, abuf.data(), abuf.size()); std::memcpy(L->h_f + boff, bbuf.data(), bbuf.size()); }
+    } else if (wants) {
+      LRC_HIP(hipMemcpy(L->d_f + aoff, abuf.data(), abuf.size(), hipMemcpyHostToDevice));
+      LRC_HIP(hipMemcpy(L->d_f + boff, bbuf.data(), bbuf.size(), hipMemcpyHostToDevice));
+    }
+    // what an earlier upload with a larger rank may have left behind the prefixes
+    if (m.af_bytes > fm.af_bytes) LRC_HIP(hipMemset(L->d_f + aoff + fm.af_bytes, 0, m.af_bytes - fm.af_bytes));
+    if (m.bf_bytes > fm.bf_bytes) LRC_HIP(hipMemset(L->d_f + boff + fm.bf_bytes, 0, m.bf_bytes - fm.bf_bytes));
   }
-  if (c.residency == MOE_LRC_STAGED) {
-    std::memcpy(L->h_w + woff, wbuf.data(), wbuf.size());
-    if (wants) std::memcpy(L->h_f + foff, fbuf.data(), fbuf.size());
-  } else {
-    LRC_HIP(hipMemcpy(L->d_w + woff, wbuf.data(), wbuf.size(), hipMemcpyHostToDevice));
-    if (wants) LRC_HIP(hipMemcpy(L->d_f + foff, fbuf.data(), fbuf.size(), hipMemcpyHostToDevice));
-  }
+  L->mat_rank[expert * 3 + mat] = rank;
   L->h_desc[expert].lambda[mat] = lambda;
   L->h_desc[expert].inv_lambda[mat] = 1.0f / lambda;
   LRC_HIP(hipMemcpy(L->d_desc + expert, &L->h_desc[expert], sizeof(ExpertDesc), hipMemcpyHostToDevice));
   L->mat_set[expert * 3 + mat] = 1;
   return MOE_LRC_OK;
+}
+
+int moe_lrc_set_expert(moe_lrc_layer* L, int expert, int mat, const uint8_t* codes,
+                       const uint16_t* scale, const uint16_t* zero, const uint16_t* A, const uint16_t* B) {
+  if (!L) return set_error(MOE_LRC_EINVAL, "set_expert: null argument");
+  const bool routed = expert >= 0 && expert < L->cfg.n_experts;
+  return moe_lrc_set_expert_ranked(L, expert, mat, codes, scale, zero, A, B, routed ? L->cfg.rank : 0);
 }
 
 size_t moe_lrc_workspace_bytes(const moe_lrc_layer* L, int T) {

@@ -54,6 +54,7 @@ struct moe_lrc_layer {
   double* d_logits = nullptr;          // [max_tokens][E] gate logits of the tiled routing path (many tokens and experts)
   bool gate_set = false, has_bias = false;
   std::vector<uint8_t> mat_set;        // [n_total*3]
+  std::vector<int> mat_rank;           // [n_total*3] rank of each projection's factor pair (Section 3.1: may differ)
   int32_t* d_stat = nullptr;           // [2 + 2E]: active, comp-active, counts, comp counts
   int32_t* h_stat = nullptr;           // pinned mirror
   hipStream_t side = nullptr;

@@ -319,3 +319,42 @@ def test_route_tiled_path_many_tokens_and_experts(amd):
     np.testing.assert_array_equal(_to_np(idx), ref["idx"])
     np.testing.assert_allclose(_to_np(w), ref["w"], rtol=2e-6, atol=1e-30)
     L.close()
+
+
+@pytest.mark.parametrize("tokens", [16, 300])
+def test_rank_per_projection_from_kurtosis(amd, tokens):
+    """Section 3.1 step 1: the rank budget is spread over the expert matrices by their kurtosis, so
+    every projection has a rank of its own (0 included, W1 and W3 of one expert may differ).
+    Decode flavour (16 tokens) and grouped-GEMM flavour (300 tokens), resident and staged; the
+    staged mode moves only the ranks uploaded."""
+    import torch
+    cfg = configs.TINY.with_(rank=32, tokens=tokens, name=f"ranks_T{tokens}")
+    ranks = fixtures.kurtosis_ranks(cfg, 10, (0, 8, 16, 32))
+    assert len(set(ranks.ravel().tolist())) >= 3 and (ranks[:, 0] != ranks[:, 1]).any()
+    layer = fixtures.build_layer(cfg, ranks=ranks)
+    x_bits = synth.make_tokens(cfg)
+    x = amd.bf16_tensor(x_bits)
+    ref = fixtures.oracle_forward(cfg, layer, x_bits)
+    Lr = amd.Layer.from_config(cfg)
+    Ls = amd.Layer.from_config(cfg, residency=amd.STAGED)
+    Lr.load(layer); Ls.load(layer)
+    out_r = Lr.forward(x).clone()
+    torch.cuda.synchronize()
+    out_s = Ls.forward(x).clone()
+    torch.cuda.synchronize()
+    err = orc.rel_frobenius(_to_np(out_r), ref["out"])
+    print(f"\n[ranks_T{tokens}] ranks {ranks.tolist()} out rel err {err:.2e}", flush=True)
+    assert err <= TOL
+    assert torch.equal(out_r.view(torch.int16), out_s.view(torch.int16))
+    st = Ls.stats()
+    comp = np.asarray(ref["perm"]["comp_counts"]) > 0
+    assert st["bytes_factors"] == int((ranks[comp].sum(axis=1) * (cfg.hidden + cfg.ffn) * 2).sum())
+    # re-uploading a projection with a smaller rank leaves no trace of the larger one
+    e = int(np.argmax(ranks[:, 0] == 32))
+    a = dict(layer["experts"][e][0])
+    Lr.set_expert(e, 0, a["codes"], a["scale"], a["zero"], None, None, rank=0)
+    layer2 = {"wg": layer["wg"], "bias": layer["bias"], "experts": [dict(ex) for ex in layer["experts"]]}
+    layer2["experts"][e][0] = dict(a, A=None, B=None, rank=0)
+    ref2 = fixtures.oracle_forward(cfg, layer2, x_bits)
+    assert orc.rel_frobenius(_to_np(Lr.forward(x)), ref2["out"]) <= TOL
+    Lr.close(); Ls.close()
