@@ -160,15 +160,20 @@ static int stage_selected(moe_lrc_layer* L, hipStream_t stream) {
     const BlobLayout& b = blob_of(L, e);
     if (shared || L->h_stat[2 + e] > 0)
       LRC_HIP(hipMemcpyAsync(L->d_w + L->w_off[e], L->h_w + L->w_off[e], b.w_bytes, hipMemcpyHostToDevice, L->side));
-    if (!shared && b.f_bytes && c.top_n > 0 && L->h_stat[2 + E + e] > 0)
-      for (int mat = 0; mat < 3; ++mat) {
-        const int r = L->mat_rank[e * 3 + mat];
-        if (r == 0) continue;
-        const MatLayout fm = make_layout(b.mat[mat].K, b.mat[mat].N, b.mat[mat].bits, b.mat[mat].group, r);
-        const size_t aoff = L->f_off[e] + b.off_af[mat], boff = L->f_off[e] + b.off_bf[mat];
-        LRC_HIP(hipMemcpyAsync(L->d_f + aoff, L->h_f + aoff, fm.af_bytes, hipMemcpyHostToDevice, L->side));
-        LRC_HIP(hipMemcpyAsync(L->d_f + boff, L->h_f + boff, fm.bf_bytes, hipMemcpyHostToDevice, L->side));
+    if (!shared && b.f_bytes && c.top_n > 0 && L->h_stat[2 + E + e] > 0) {
+      const int* r = &L->mat_rank[e * 3];
+      if (r[0] == c.rank && r[1] == c.rank && r[2] == c.rank) {      // the whole factor blob in one piece
+        LRC_HIP(hipMemcpyAsync(L->d_f + L->f_off[e], L->h_f + L->f_off[e], b.f_bytes, hipMemcpyHostToDevice, L->side));
+      } else {
+        for (int mat = 0; mat < 3; ++mat) {                           // the prefixes the projection's rank fills
+          if (r[mat] == 0) continue;
+          const MatLayout fm = make_layout(b.mat[mat].K, b.mat[mat].N, b.mat[mat].bits, b.mat[mat].group, r[mat]);
+          const size_t aoff = L->f_off[e] + b.off_af[mat], boff = L->f_off[e] + b.off_bf[mat];
+          LRC_HIP(hipMemcpyAsync(L->d_f + aoff, L->h_f + aoff, fm.af_bytes, hipMemcpyHostToDevice, L->side));
+          LRC_HIP(hipMemcpyAsync(L->d_f + boff, L->h_f + boff, fm.bf_bytes, hipMemcpyHostToDevice, L->side));
+        }
       }
+    }
   }
   LRC_HIP(hipEventRecord(L->ev_t1, L->side));
   LRC_HIP(hipStreamWaitEvent(stream, L->ev_t1, 0));
