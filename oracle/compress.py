@@ -103,16 +103,31 @@ def residual_factors(E: np.ndarray, r: int, method: str = "exact", seed: int = 0
     return U * root[None, :], root[:, None] * Vt, S
 
 
+FACTOR_BITS, FACTOR_GROUP = 3, 64
+
+
+def quantize_factors(A: np.ndarray, B: np.ndarray) -> tuple:
+    """(Aq, Bq): the factor pair at FACTOR_BITS bits (Section 3.1 step 2 stores the factors at INT3).
+    The paper gives no group format; here both factors are quantized like the weights (asymmetric,
+    fp16 scale/zero) in groups of FACTOR_GROUP along their long dimension, one rank index per
+    column: A [K][r] along K, B as its transpose [N][r] along N."""
+    return (quantize_groupwise(np.asarray(A, np.float64), FACTOR_BITS, FACTOR_GROUP),
+            quantize_groupwise(np.asarray(B, np.float64).T.copy(), FACTOR_BITS, FACTOR_GROUP))
+
+
 def compress_matrix(W: np.ndarray, bits: int, group: int, rank: int, method: str = "exact",
-                    seed: int = 0, keep_fp64_factors: bool = False) -> dict:
-    """Quantize-then-compensate for one matrix: stored artefacts in the layout the C ABI takes."""
+                    seed: int = 0, keep_fp64_factors: bool = False, int3_factors: bool = False) -> dict:
+    """Quantize-then-compensate for one matrix: stored artefacts in the layout the C ABI takes.
+    int3_factors: the factor pair is stored quantized ("Aq", "Bq") instead of as bf16 ("A", "B")."""
     q = quantize_groupwise(W, bits, group)
     art = {"codes": q["codes"], "scale": q["scale"], "zero": q["zero"], "A": None, "B": None}
     if rank > 0:
         E = np.asarray(W, dtype=np.float64) - dequantize(q, group)
         A, B, S = residual_factors(E, rank, method, seed)
         art["sigma"] = S
-        if keep_fp64_factors:
+        if int3_factors:
+            art["Aq"], art["Bq"] = quantize_factors(A, B)
+        elif keep_fp64_factors:
             art["A"], art["B"] = A, B
         else:
             art["A"], art["B"] = round_to_bf16_bits(A), round_to_bf16_bits(B)
@@ -151,6 +166,12 @@ def expert_code_bytes(hidden: int, ffn: int, bits: int) -> int:
 def expert_meta_bytes(hidden: int, ffn: int, group: int) -> int:
     """fp16 scale + fp16 zero per group of one expert's three projections."""
     return 3 * hidden * ffn // group * 4
+
+
+def factor_meta_bytes(hidden: int, ffn: int, rank: int) -> int:
+    """fp16 scale + fp16 zero per group of FACTOR_GROUP of one expert's three quantized factor pairs:
+    every pair has r (K + N) values."""
+    return 3 * rank * (hidden + ffn) // FACTOR_GROUP * 4
 
 
 def compensator_bytes(hidden: int, ffn: int, rank: int, factor_bits: int) -> int:

@@ -17,8 +17,8 @@ from . import moe_lrc_oracle as orc
 
 
 def _compress_one(args):
-    cfg, e, mat, method, keep_weights, keep_fp64_factors, rank = args
-    return _compress_job(cfg, e, mat, method, keep_weights, keep_fp64_factors, rank)
+    cfg, e, mat, method, keep_weights, keep_fp64_factors, rank, int3 = args
+    return _compress_job(cfg, e, mat, method, keep_weights, keep_fp64_factors, rank, int3)
 
 
 def _compress_one_single_thread(args):
@@ -31,13 +31,13 @@ def _compress_one_single_thread(args):
         return _compress_one(args)
 
 
-def _compress_job(cfg, e, mat, method, keep_weights, keep_fp64_factors, rank=None):
+def _compress_job(cfg, e, mat, method, keep_weights, keep_fp64_factors, rank=None, int3=False):
     shared = e >= cfg.n_experts
     W = synth.make_expert_weight(cfg, e, mat)
     r = 0 if shared else (cfg.rank if rank is None else int(rank))
     art = compress.compress_matrix(W, synth.expert_bits(cfg, e), cfg.group, r,
                                    method=method, seed=cfg.seed + 31 * e + mat,
-                                   keep_fp64_factors=keep_fp64_factors)
+                                   keep_fp64_factors=keep_fp64_factors, int3_factors=int3)
     art.pop("sigma", None)
     if rank is not None and not shared:
         art["rank"] = r            # this projection's own rank (Section 3.1)
@@ -56,9 +56,10 @@ def kurtosis_ranks(cfg: LayerConfig, r_avg: int, buckets) -> np.ndarray:
 
 def build_layer(cfg: LayerConfig, method: str = "exact", keep_weights: bool = False,
                 keep_fp64_factors: bool = False, progress: bool = False, workers: int = 0,
-                ranks=None) -> dict:
+                ranks=None, int3_factors: bool = False) -> dict:
     """Quantize-then-compensate every expert of `cfg` (Section 3.1 step 2).  Uniform rank cfg.rank,
     or `ranks` [n_experts][3] (columns in the order W1, W3, W2) for a rank per projection.
+    int3_factors: the factor pairs are stored at 3 bits ("Aq", "Bq") instead of bf16.
 
     Returns {"wg", "bias", "experts": [ {mat: artefacts} ... routed then shared ]}.
     Shared experts use cfg.shared_bits and carry no factors.  `workers` > 1 compresses the
@@ -68,7 +69,7 @@ def build_layer(cfg: LayerConfig, method: str = "exact", keep_weights: bool = Fa
     n_all = cfg.n_experts + cfg.n_shared
     order = (synth.MAT_W1, synth.MAT_W3, synth.MAT_W2)
     jobs = [(cfg, e, mat, method, keep_weights, keep_fp64_factors,
-             None if ranks is None or e >= cfg.n_experts else int(ranks[e][order.index(mat)]))
+             None if ranks is None or e >= cfg.n_experts else int(ranks[e][order.index(mat)]), int3_factors)
             for e in range(n_all) for mat in order]
     experts = [dict() for _ in range(n_all)]
     t0 = time.time()

@@ -109,6 +109,9 @@ def permute(topk_idx: np.ndarray, n_experts: int, top_n: int) -> dict:
 
 
 # ----------------------------------------------------------------------------- experts
+FACTOR_GROUP = 64     # group size of the quantized factors along their long dimension (our choice: the paper gives none)
+
+
 def dequant(codes: np.ndarray, scale_bits: np.ndarray, zero_bits: np.ndarray, group: int) -> np.ndarray:
     """Qinv(Q(W)) of Section 2.3: D[k][o] = (code[k][o] - zero[k/group][o]) * scale[k/group][o]."""
     K, N = codes.shape
@@ -124,7 +127,13 @@ def silu(g: np.ndarray) -> np.ndarray:
 def _project(X: np.ndarray, flags: np.ndarray, art: dict, group: int) -> np.ndarray:
     """X @ W_hat row by row: D for every row, plus (X A) B for rows whose flag is set (Section 3.2)."""
     out = X @ dequant(art["codes"], art["scale"], art["zero"], group)
-    if art.get("A") is not None and flags.any():
+    if art.get("Aq") is not None and flags.any():
+        # INT3-quantized factors (Section 3.1 stores the factors at 3 bits): A [K][r] in groups of
+        # FACTOR_GROUP along K, B kept transposed [N][r] in groups of FACTOR_GROUP along N
+        A = dequant(art["Aq"]["codes"], art["Aq"]["scale"], art["Aq"]["zero"], FACTOR_GROUP)
+        B = dequant(art["Bq"]["codes"], art["Bq"]["scale"], art["Bq"]["zero"], FACTOR_GROUP).T
+        out[flags] += (X[flags] @ A) @ B
+    elif art.get("A") is not None and flags.any():
         A = art["A"] if art["A"].dtype == np.float64 else bf16_to_f64(art["A"])
         B = art["B"] if art["B"].dtype == np.float64 else bf16_to_f64(art["B"])
         out[flags] += (X[flags] @ A) @ B

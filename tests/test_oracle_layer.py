@@ -190,3 +190,40 @@ def test_rank_per_projection_from_kurtosis():
         W_hat.append(tuple(mats))
     ref = dense_moe_torch(x, layer["wg"], W_hat, cfg.top_k)
     np.testing.assert_allclose(got, ref, rtol=1e-10, atol=1e-12)
+
+
+def test_int3_factors_layer_equals_materialised_form_and_still_compensates():
+    # Section 3.1 step 2 stores the factors at INT3.  The layer with quantized factors equals the
+    # materialised form D + Qinv(Aq) Qinv(Bq)^T, and the quantized compensator still removes most of
+    # what the bf16 one removes of the quantization error.
+    cfg = configs.TINY.with_(top_n=2, rank=16, bits=2)
+    x = synth.make_tokens(cfg)
+    layer_q = fixtures.build_layer(cfg, int3_factors=True, keep_weights=True)
+    got = fixtures.oracle_forward(cfg, layer_q, x)["out"]
+    W_hat = []
+    for ex in layer_q["experts"]:
+        mats = []
+        for m in (0, 1, 2):
+            a = ex[m]
+            assert a["A"] is None and a["Aq"]["codes"].max() <= 7 and a["Bq"]["codes"].shape == (a["codes"].shape[1], cfg.rank)
+            A = orc.dequant(a["Aq"]["codes"], a["Aq"]["scale"], a["Aq"]["zero"], orc.FACTOR_GROUP)
+            B = orc.dequant(a["Bq"]["codes"], a["Bq"]["scale"], a["Bq"]["zero"], orc.FACTOR_GROUP).T
+            mats.append(orc.dequant(a["codes"], a["scale"], a["zero"], cfg.group) + A @ B)
+        W_hat.append(tuple(mats))
+    np.testing.assert_allclose(got, dense_moe_torch(x, layer_q["wg"], W_hat, cfg.top_k), rtol=1e-10, atol=1e-12)
+    dense = dense_moe_torch(x, layer_q["wg"], [tuple(ex[m]["W"] for m in (0, 1, 2)) for ex in layer_q["experts"]], cfg.top_k)
+    layer_b = fixtures.build_layer(cfg)
+    e_none = orc.rel_frobenius(fixtures.oracle_forward(cfg.with_(top_n=0), layer_b, x)["out"], dense)
+    e_bf16 = orc.rel_frobenius(fixtures.oracle_forward(cfg, layer_b, x)["out"], dense)
+    e_int3 = orc.rel_frobenius(got, dense)
+    assert e_bf16 < e_int3 < e_none
+    assert (e_none - e_int3) > 0.5 * (e_none - e_bf16)
+
+
+def test_factor_byte_accounting_at_int3():
+    from oracle import compress
+    # one expert's factor pairs at rank 32 of a Mixtral-sized layer: 3 bits per value + scale/zero per 64
+    H, F, r = 4096, 14336, 32
+    vals = 3 * r * (H + F)
+    assert compress.compensator_bytes(H, F, r, 3) == vals * 3 // 8
+    assert compress.factor_meta_bytes(H, F, r) == vals // 64 * 4
