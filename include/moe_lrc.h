@@ -107,6 +107,20 @@ int moe_lrc_set_expert_ranked(moe_lrc_layer* layer, int expert, int mat, const u
                               const uint16_t* scale_f16, const uint16_t* zero_f16,
                               const uint16_t* A_bf16, const uint16_t* B_bf16, int rank);
 
+/* Factor pair of one routed projection at 3 bits (Section 3.1 step 2 stores the factors at INT3; the
+ * paper gives no group format, this is ours): A [K][rank] quantized in groups of 64 along K, B kept
+ * transposed [N][rank] and quantized in groups of 64 along N, both like the weights
+ * (value = (code - zero) * scale).  All host memory:
+ *   a_codes [K][rank], b_codes [N][rank]   one code per byte, each < 8
+ *   a_scale, a_zero  fp16 [K/64][rank];  b_scale, b_zero  fp16 [N/64][rank]
+ * rank: multiple of 8 in 8..cfg.rank.  Call after moe_lrc_set_expert(_ranked) of the same projection
+ * (with A = B = NULL, rank 0), which uploads the codes of the weights.  The pair is kept at 3 bits in
+ * the pinned pool of a staged layer and expanded to fp16 on the device when it arrives (a resident
+ * layer expands it once, here); the staged byte counters count 3 bits + scale/zero per value. */
+int moe_lrc_set_expert_factors_quantized(moe_lrc_layer* layer, int expert, int mat, int rank,
+                                  const uint8_t* a_codes, const uint16_t* a_scale_f16, const uint16_t* a_zero_f16,
+                                  const uint8_t* b_codes, const uint16_t* b_scale_f16, const uint16_t* b_zero_f16);
+
 /* Bytes of device workspace the hot-path calls need for T tokens (the largest over all calls). */
 size_t moe_lrc_workspace_bytes(const moe_lrc_layer* layer, int T);
 

@@ -20,7 +20,7 @@ RESIDENT, STAGED = 0, 1
 # every symbol include/moe_lrc.h declares
 EXPORTS = [
     "moe_lrc_last_error", "moe_lrc_layer_create", "moe_lrc_layer_destroy", "moe_lrc_set_gate",
-    "moe_lrc_set_expert", "moe_lrc_set_expert_ranked", "moe_lrc_workspace_bytes", "moe_lrc_route", "moe_lrc_permute",
+    "moe_lrc_set_expert", "moe_lrc_set_expert_ranked", "moe_lrc_set_expert_factors_quantized", "moe_lrc_workspace_bytes", "moe_lrc_route", "moe_lrc_permute",
     "moe_lrc_expert_ffn", "moe_lrc_combine", "moe_lrc_forward", "moe_lrc_debug_unpack",
     "moe_lrc_packed_bytes", "moe_lrc_pack_codes", "moe_lrc_unpack_codes", "moe_lrc_get_stats",
     "moe_lrc_profile_enable", "moe_lrc_profile_read",
@@ -67,6 +67,7 @@ def lib() -> C.CDLL:
         L.moe_lrc_set_gate.argtypes = [vp, vp, vp]
         L.moe_lrc_set_expert.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp]
         L.moe_lrc_set_expert_ranked.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, i32]
+        L.moe_lrc_set_expert_factors_quantized.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp]
         L.moe_lrc_workspace_bytes.argtypes = [vp, i32]
         L.moe_lrc_workspace_bytes.restype = sz
         L.moe_lrc_route.argtypes = [vp, vp, i32, vp, vp, vp]
@@ -176,13 +177,23 @@ class Layer:
         else:
             _check(lib().moe_lrc_set_expert_ranked(self._h, expert, mat, *[_hp(a) for a in arrs], int(rank)))
 
+    def set_expert_factors_quantized(self, expert: int, mat: int, rank: int, Aq: dict, Bq: dict) -> None:
+        """Aq / Bq: {"codes", "scale", "zero"} of A [K][rank] and of B transposed [N][rank] at 3 bits."""
+        arrs = [_host(Aq["codes"], np.uint8), _host(Aq["scale"], np.uint16), _host(Aq["zero"], np.uint16),
+                _host(Bq["codes"], np.uint8), _host(Bq["scale"], np.uint16), _host(Bq["zero"], np.uint16)]
+        _check(lib().moe_lrc_set_expert_factors_quantized(self._h, expert, mat, int(rank), *[_hp(a) for a in arrs]))
+
     def load(self, layer: dict) -> None:
         """layer = {"wg", "bias", "experts": [{mat: {"codes","scale","zero","A","B"}}]}."""
         self.set_gate(layer["wg"], layer.get("bias"))
         for e, ex in enumerate(layer["experts"]):
             for mat in (0, 1, 2):
                 a = ex[mat]
-                self.set_expert(e, mat, a["codes"], a["scale"], a["zero"], a.get("A"), a.get("B"), a.get("rank"))
+                if a.get("Aq") is not None:          # factor pair at 3 bits
+                    self.set_expert(e, mat, a["codes"], a["scale"], a["zero"], None, None, 0)
+                    self.set_expert_factors_quantized(e, mat, a["Aq"]["codes"].shape[1], a["Aq"], a["Bq"])
+                else:
+                    self.set_expert(e, mat, a["codes"], a["scale"], a["zero"], a.get("A"), a.get("B"), a.get("rank"))
 
     # ---- workspace ----
     def workspace_bytes(self, T: int) -> int:

@@ -142,7 +142,10 @@ static void fill_algorithmic_stats(moe_lrc_layer* L, const int32_t* stat) {
     for (int e = 0; e < c.n_experts; ++e)
       if (stat[2 + c.n_experts + e] > 0)
         for (int mat = 0; mat < 3; ++mat)      // A [K][r] and B [r][N] as bf16: r (K + N) values
-          s.bytes_factors += uint64_t(L->mat_rank[e * 3 + mat]) * (c.hidden + c.ffn) * 2;
+          s.bytes_factors += L->mat_q3[e * 3 + mat]
+                                 ? uint64_t(L->mat_rank[e * 3 + mat]) * (c.hidden + c.ffn) * 3 / 8 +      // 3-bit codes
+                                       uint64_t(L->mat_rank[e * 3 + mat]) * (c.hidden + c.ffn) / 64 * 4     // fp16 scale + zero
+                                 : uint64_t(L->mat_rank[e * 3 + mat]) * (c.hidden + c.ffn) * 2;
   L->stats_valid = true;
 }
 
@@ -162,7 +165,23 @@ static int stage_selected(moe_lrc_layer* L, hipStream_t stream) {
       LRC_HIP(hipMemcpyAsync(L->d_w + L->w_off[e], L->h_w + L->w_off[e], b.w_bytes, hipMemcpyHostToDevice, L->side));
     if (!shared && b.f_bytes && c.top_n > 0 && L->h_stat[2 + E + e] > 0) {
       const int* r = &L->mat_rank[e * 3];
-      if (r[0] == c.rank && r[1] == c.rank && r[2] == c.rank) {      // the whole factor blob in one piece
+      const uint8_t* q3 = &L->mat_q3[e * 3];
+      if (q3[0] | q3[1] | q3[2]) {
+        for (int mat = 0; mat < 3; ++mat) {
+          if (r[mat] == 0) continue;
+          const MatLayout& m = b.mat[mat];
+          const size_t aoff = L->f_off[e] + b.off_af[mat], boff = L->f_off[e] + b.off_bf[mat];
+          if (q3[mat]) {                                              // 3-bit blob, expanded to fp16 on arrival
+            LRC_HIP(hipMemcpyAsync(L->d_fq + aoff, L->h_f + aoff, q3_blob_bytes(m.K, m.N, r[mat]), hipMemcpyHostToDevice, L->side));
+            LRC_HIP(launch_expand_q3(L->d_fq + aoff, m.K, m.N, r[mat], reinterpret_cast<_Float16*>(L->d_f + aoff),
+                                     reinterpret_cast<_Float16*>(L->d_f + boff), L->side));
+          } else {
+            const MatLayout fm = make_layout(m.K, m.N, m.bits, m.group, r[mat]);
+            LRC_HIP(hipMemcpyAsync(L->d_f + aoff, L->h_f + aoff, fm.af_bytes, hipMemcpyHostToDevice, L->side));
+            LRC_HIP(hipMemcpyAsync(L->d_f + boff, L->h_f + boff, fm.bf_bytes, hipMemcpyHostToDevice, L->side));
+          }
+        }
+      } else if (r[0] == c.rank && r[1] == c.rank && r[2] == c.rank) {      // the whole factor blob in one piece
         LRC_HIP(hipMemcpyAsync(L->d_f + L->f_off[e], L->h_f + L->f_off[e], b.f_bytes, hipMemcpyHostToDevice, L->side));
       } else {
         for (int mat = 0; mat < 3; ++mat) {                           // the prefixes the projection's rank fills
@@ -256,6 +275,7 @@ int moe_lrc_layer_create(const moe_lrc_config* cfg, moe_lrc_layer** out) {
   L->ksplit2 = std::max(1, std::min(16, cfg->ffn / 512));
   L->mat_set.assign(size_t(L->n_total) * 3, 0);
   L->mat_rank.assign(size_t(L->n_total) * 3, 0);
+  L->mat_q3.assign(size_t(L->n_total) * 3, 0);
   size_t w = 0, f = 0;
   for (int e = 0; e < L->n_total; ++e) {
     L->w_off.push_back(w); L->f_off.push_back(f);
@@ -270,6 +290,7 @@ int moe_lrc_layer_create(const moe_lrc_config* cfg, moe_lrc_layer** out) {
                             std::string(#expr) + ": " + hipGetErrorString(e_)));                  \
   } while (0)
   LRC_TRY(hipMalloc((void**)&L->d_w, std::max<size_t>(w, 256)));
+  L->f_total = std::max<size_t>(f, 256);
   LRC_TRY(hipMalloc((void**)&L->d_f, std::max<size_t>(f, 256)));
   // (a projection uploaded with a smaller rank fills a prefix of its sections: the rest stays zero)
   LRC_TRY(hipMemset(L->d_f, 0, std::max<size_t>(f, 256)));
@@ -319,6 +340,7 @@ int moe_lrc_layer_destroy(moe_lrc_layer* L) {
   (void)hipDeviceSynchronize();
   if (L->d_w) (void)hipFree(L->d_w);
   if (L->d_f) (void)hipFree(L->d_f);
+  if (L->d_fq) (void)hipFree(L->d_fq);
   if (L->h_w) (void)hipHostFree(L->h_w);
   if (L->h_f) (void)hipHostFree(L->h_f);
   if (L->d_desc) (void)hipFree(L->d_desc);
@@ -397,6 +419,7 @@ int moe_lrc_set_expert_ranked(moe_lrc_layer* L, int expert, int mat, const uint8
     if (m.bf_bytes > fm.bf_bytes) LRC_HIP(hipMemset(L->d_f + boff + fm.bf_bytes, 0, m.bf_bytes - fm.bf_bytes));
   }
   L->mat_rank[expert * 3 + mat] = rank;
+  L->mat_q3[expert * 3 + mat] = 0;
   L->h_desc[expert].lambda[mat] = lambda;
   L->h_desc[expert].inv_lambda[mat] = 1.0f / lambda;
   LRC_HIP(hipMemcpy(L->d_desc + expert, &L->h_desc[expert], sizeof(ExpertDesc), hipMemcpyHostToDevice));
@@ -409,6 +432,48 @@ int moe_lrc_set_expert(moe_lrc_layer* L, int expert, int mat, const uint8_t* cod
   if (!L) return set_error(MOE_LRC_EINVAL, "set_expert: null argument");
   const bool routed = expert >= 0 && expert < L->cfg.n_experts;
   return moe_lrc_set_expert_ranked(L, expert, mat, codes, scale, zero, A, B, routed ? L->cfg.rank : 0);
+}
+
+int moe_lrc_set_expert_factors_quantized(moe_lrc_layer* L, int expert, int mat, int rank,
+                                  const uint8_t* a_codes, const uint16_t* a_scale, const uint16_t* a_zero,
+                                  const uint8_t* b_codes, const uint16_t* b_scale, const uint16_t* b_zero) {
+  if (!L || !a_codes || !a_scale || !a_zero || !b_codes || !b_scale || !b_zero)
+    return set_error(MOE_LRC_EINVAL, "set_expert_factors_quantized: null argument");
+  const moe_lrc_config& c = L->cfg;
+  if (expert < 0 || expert >= c.n_experts) return set_error(MOE_LRC_EINVAL, "set_expert_factors_quantized: not a routed expert");
+  if (mat < 0 || mat > 2) return set_error(MOE_LRC_EINVAL, "set_expert_factors_quantized: mat must be 0, 1 or 2");
+  if (rank <= 0 || rank > c.rank || rank % 8)
+    return set_error(MOE_LRC_EINVAL, "set_expert_factors_quantized: rank must be a multiple of 8 in 8..layer rank");
+  if (!L->mat_set[expert * 3 + mat])
+    return set_error(MOE_LRC_ESTATE, "set_expert_factors_quantized: upload the projection's codes with set_expert first");
+  const BlobLayout& b = L->routed;
+  const MatLayout& m = b.mat[mat];
+  size_t off[6];
+  q3_offsets(m.K, m.N, rank, off);
+  std::vector<uint8_t> blob(off[5]);
+  if (!pack_q3_blob(m.K, m.N, rank, a_codes, a_scale, a_zero, b_codes, b_scale, b_zero, blob.data()))
+    return set_error(MOE_LRC_EINVAL, "set_expert_factors_quantized: code out of range (3 bits)");
+  if (!L->d_fq) {                          // landing area of the blobs, laid out like the fp16 sections (first use)
+    hipError_t e = hipMalloc((void**)&L->d_fq, L->f_total);
+    if (e != hipSuccess) return set_error(MOE_LRC_ENOMEM, std::string("set_expert_factors_quantized: ") + hipGetErrorString(e));
+  }
+  // the blob (0.44 bytes per value) takes the start of the projection's A section (2 bytes per value)
+  const size_t aoff = L->f_off[expert] + b.off_af[mat], boff = L->f_off[expert] + b.off_bf[mat];
+  const MatLayout fm = make_layout(m.K, m.N, m.bits, m.group, rank);
+  _Float16* af = reinterpret_cast<_Float16*>(L->d_f + aoff);
+  _Float16* bf = reinterpret_cast<_Float16*>(L->d_f + boff);
+  if (c.residency == MOE_LRC_STAGED) {
+    std::memcpy(L->h_f + aoff, blob.data(), blob.size());
+  } else {                                 // resident: expanded to fp16 once, here
+    LRC_HIP(hipMemcpy(L->d_fq + aoff, blob.data(), blob.size(), hipMemcpyHostToDevice));
+    LRC_HIP(launch_expand_q3(L->d_fq + aoff, m.K, m.N, rank, af, bf, nullptr));
+    LRC_HIP(hipDeviceSynchronize());
+  }
+  if (m.af_bytes > fm.af_bytes) LRC_HIP(hipMemset(L->d_f + aoff + fm.af_bytes, 0, m.af_bytes - fm.af_bytes));
+  if (m.bf_bytes > fm.bf_bytes) LRC_HIP(hipMemset(L->d_f + boff + fm.bf_bytes, 0, m.bf_bytes - fm.bf_bytes));
+  L->mat_rank[expert * 3 + mat] = rank;
+  L->mat_q3[expert * 3 + mat] = 1;
+  return MOE_LRC_OK;
 }
 
 size_t moe_lrc_workspace_bytes(const moe_lrc_layer* L, int T) {

@@ -55,6 +55,9 @@ struct moe_lrc_layer {
   bool gate_set = false, has_bias = false;
   std::vector<uint8_t> mat_set;        // [n_total*3]
   std::vector<int> mat_rank;           // [n_total*3] rank of each projection's factor pair (Section 3.1: may differ)
+  std::vector<uint8_t> mat_q3;         // [n_total*3] 1: the pair is held at 3 bits (pinned pool / d_fq) and expanded to fp16
+  uint8_t* d_fq = nullptr;             // device: landing area of the 3-bit factor blobs, laid out like d_f (allocated on first use)
+  size_t f_total = 0;                  // bytes of d_f (and of d_fq, h_f)
   int32_t* d_stat = nullptr;           // [2 + 2E]: active, comp-active, counts, comp counts
   int32_t* h_stat = nullptr;           // pinned mirror
   hipStream_t side = nullptr;
@@ -122,5 +125,8 @@ hipError_t launch_combine(const moe_lrc_layer* L, const void* y_rows, const floa
                           hipStream_t s);
 hipError_t launch_debug_unpack(const uint32_t* packed, const MatLayout& m, uint8_t* codes_dev,
                                hipStream_t s);
+// 3-bit factor blob (q3_blob_bytes) -> the fp16 factor sections of one projection (rank-major layouts)
+size_t q3_blob_bytes(int K, int N, int rank);
+hipError_t launch_expand_q3(const uint8_t* blob_dev, int K, int N, int rank, _Float16* af, _Float16* bf, hipStream_t s);
 
 }  // namespace lrc

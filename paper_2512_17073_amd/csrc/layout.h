@@ -102,4 +102,16 @@ inline MatLayout make_layout(int K, int N, int bits, int group, int rank) {
   return m;
 }
 
+// Blob of one projection's factor pair held at 3 bits: A codes (dense 3-bit stream of [K][r], one
+// spare byte), A scale, A zero (fp16 [K/64][r]), then the same for B transposed ([N][r], groups of 64
+// along N); every section starts at a multiple of 16 bytes.  off = {A scale, A zero, B codes,
+// B scale, B zero, end}.
+inline void q3_offsets(int K, int N, int rank, size_t (&off)[6]) {
+  auto r16 = [](size_t x) { return (x + 15) & ~size_t(15); };
+  const size_t a_codes = r16(size_t(K) * rank * 3 / 8 + 1), a_meta = r16(size_t(K / 64) * rank * 2);
+  const size_t b_codes = r16(size_t(N) * rank * 3 / 8 + 1), b_meta = r16(size_t(N / 64) * rank * 2);
+  off[0] = a_codes; off[1] = off[0] + a_meta; off[2] = off[1] + a_meta;
+  off[3] = off[2] + b_codes; off[4] = off[3] + b_meta; off[5] = off[4] + b_meta;
+}
+
 }  // namespace lrc

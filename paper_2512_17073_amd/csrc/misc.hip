@@ -122,7 +122,80 @@ __global__ __launch_bounds__(64) void unpack_kernel(const uint32_t* __restrict__
   }
 }
 
+// Factor pairs stored at 3 bits (Section 3.1 step 2) are expanded to the fp16 MFMA units the FFN
+// kernels read.  Blob of one projection: A codes (dense 3-bit stream, code i of [K][r] at bit 3 i),
+// A scale, A zero (fp16 [K/64][r] each), then the same for B transposed ([N][r], groups of 64 along
+// N); sections start at multiples of 16 bytes.  One thread per 16-byte unit of the rank-major
+// layouts: A unit (tile, kk, lane (q, c)) = A[32 kk + 8 q + j][16 tile + c], B unit (st, nt, lane)
+// = B[32 st + 8 q + j][16 nt + c], j = 0..7; value = (code - zero) * scale, zero past the rank.
+__device__ inline uint32_t q3_code(const uint8_t* __restrict__ stream, size_t i) {
+  const size_t bit = 3 * i;
+  const uint32_t two = uint32_t(stream[bit >> 3]) | (uint32_t(stream[(bit >> 3) + 1]) << 8);   // (one spare byte follows)
+  return (two >> (bit & 7)) & 7u;
+}
+__device__ inline float f16_bits_to_f32(uint16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
+
+__global__ __launch_bounds__(256) void expand_q3_kernel(const uint8_t* __restrict__ blob, int K, int N, int rank,
+                                                        size_t a_scale_off, size_t a_zero_off, size_t b_codes_off,
+                                                        size_t b_scale_off, size_t b_zero_off,
+                                                        _Float16* __restrict__ af, _Float16* __restrict__ bf) {
+  const int rt = (rank + 15) / 16, ls = (rank + 31) / 32, k32 = K / 32, NT = N / 16;
+  const size_t a_units = size_t(rt) * k32 * 64, b_units = size_t(ls) * NT * 64;
+  const size_t u = size_t(blockIdx.x) * 256 + threadIdx.x;
+  if (u >= a_units + b_units) return;
+  _Float16 v[8];
+  if (u < a_units) {
+    const int lane = u & 63, c = lane & 15, q = lane >> 4;
+    const int kk = int((u >> 6) % k32), tile = int((u >> 6) / k32), rho = 16 * tile + c;
+    const uint16_t* sc = reinterpret_cast<const uint16_t*>(blob + a_scale_off);
+    const uint16_t* zr = reinterpret_cast<const uint16_t*>(blob + a_zero_off);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int k = 32 * kk + 8 * q + j;
+      float val = 0.f;
+      if (rho < rank) {
+        const size_t g = size_t(k >> 6) * rank + rho;
+        val = (float(q3_code(blob, size_t(k) * rank + rho)) - f16_bits_to_f32(zr[g])) * f16_bits_to_f32(sc[g]);
+      }
+      v[j] = (_Float16)val;
+    }
+    *reinterpret_cast<uint4*>(af + u * 8) = *reinterpret_cast<const uint4*>(v);
+  } else {
+    const size_t ub = u - a_units;
+    const int lane = ub & 63, c = lane & 15, q = lane >> 4;
+    const int nt = int((ub >> 6) % NT), st = int((ub >> 6) / NT), n = 16 * nt + c;
+    const uint16_t* sc = reinterpret_cast<const uint16_t*>(blob + b_scale_off);
+    const uint16_t* zr = reinterpret_cast<const uint16_t*>(blob + b_zero_off);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int rho = 32 * st + 8 * q + j;
+      float val = 0.f;
+      if (rho < rank) {
+        const size_t g = size_t(n >> 6) * rank + rho;
+        val = (float(q3_code(blob + b_codes_off, size_t(n) * rank + rho)) - f16_bits_to_f32(zr[g])) * f16_bits_to_f32(sc[g]);
+      }
+      v[j] = (_Float16)val;
+    }
+    *reinterpret_cast<uint4*>(bf + ub * 8) = *reinterpret_cast<const uint4*>(v);
+  }
+}
+
 }  // namespace
+
+size_t q3_blob_bytes(int K, int N, int rank) {
+  size_t off[6];
+  q3_offsets(K, N, rank, off);
+  return off[5];
+}
+
+hipError_t launch_expand_q3(const uint8_t* blob_dev, int K, int N, int rank, _Float16* af, _Float16* bf, hipStream_t s) {
+  size_t off[6];
+  q3_offsets(K, N, rank, off);
+  const size_t units = (size_t((rank + 15) / 16) * (K / 32) + size_t((rank + 31) / 32) * (N / 16)) * 64;
+  hipLaunchKernelGGL(expand_q3_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, s, blob_dev, K, N, rank,
+                     off[0], off[1], off[2], off[3], off[4], af, bf);
+  return hipGetLastError();
+}
 
 hipError_t launch_combine(const moe_lrc_layer* L, const void* y_rows, const float* w,
                           const int32_t* pair_row, const void* y_shared, int T, void* out,

@@ -159,4 +159,27 @@ void pack_factor_b(const MatLayout& m, int rank, const uint16_t* B_bf16, uint16_
       }
 }
 
+bool pack_q3_blob(int K, int N, int rank, const uint8_t* a_codes, const uint16_t* a_scale, const uint16_t* a_zero,
+                  const uint8_t* b_codes, const uint16_t* b_scale, const uint16_t* b_zero, uint8_t* out) {
+  size_t off[6];
+  q3_offsets(K, N, rank, off);
+  std::memset(out, 0, off[5]);
+  auto stream = [](const uint8_t* codes, size_t n, uint8_t* dst) {
+    for (size_t i = 0; i < n; ++i) {
+      if (codes[i] > 7) return false;
+      const size_t bit = 3 * i;
+      const uint32_t v = uint32_t(codes[i]) << (bit & 7);
+      dst[bit >> 3] |= uint8_t(v);
+      dst[(bit >> 3) + 1] |= uint8_t(v >> 8);
+    }
+    return true;
+  };
+  if (!stream(a_codes, size_t(K) * rank, out) || !stream(b_codes, size_t(N) * rank, out + off[2])) return false;
+  std::memcpy(out + off[0], a_scale, size_t(K / 64) * rank * 2);
+  std::memcpy(out + off[1], a_zero, size_t(K / 64) * rank * 2);
+  std::memcpy(out + off[3], b_scale, size_t(N / 64) * rank * 2);
+  std::memcpy(out + off[4], b_zero, size_t(N / 64) * rank * 2);
+  return true;
+}
+
 }  // namespace lrc

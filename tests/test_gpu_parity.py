@@ -358,3 +358,34 @@ def test_rank_per_projection_from_kurtosis(amd, tokens):
     ref2 = fixtures.oracle_forward(cfg, layer2, x_bits)
     assert orc.rel_frobenius(_to_np(Lr.forward(x)), ref2["out"]) <= TOL
     Lr.close(); Ls.close()
+
+
+@pytest.mark.parametrize("tokens,rank", [(16, 16), (300, 32), (40, 24)])
+def test_int3_factors(amd, tokens, rank):
+    """Section 3.1 step 2 stores the factor pairs at INT3: uploaded as 3-bit codes + fp16 scale/zero
+    per group of 64, kept at 3 bits in the pinned pool, expanded to fp16 units on the device.
+    Resident and staged layers agree bit for bit and match the oracle on the quantized factors; the
+    staged byte counter counts 3 bits + scale/zero per value."""
+    import torch
+    cfg = configs.TINY.with_(rank=rank, tokens=tokens, bits=2, name=f"int3_T{tokens}_r{rank}")
+    layer = fixtures.build_layer(cfg, int3_factors=True)
+    x_bits = synth.make_tokens(cfg)
+    x = amd.bf16_tensor(x_bits)
+    ref = fixtures.oracle_forward(cfg, layer, x_bits)
+    Lr = amd.Layer.from_config(cfg)
+    Ls = amd.Layer.from_config(cfg, residency=amd.STAGED)
+    Lr.load(layer); Ls.load(layer)
+    out_r = Lr.forward(x).clone()
+    torch.cuda.synchronize()
+    out_s = Ls.forward(x).clone()
+    torch.cuda.synchronize()
+    err = orc.rel_frobenius(_to_np(out_r), ref["out"])
+    print(f"\n[{cfg.name}] out rel err {err:.2e}", flush=True)
+    assert err <= TOL
+    assert torch.equal(out_r.view(torch.int16), out_s.view(torch.int16))
+    n_comp = int((np.asarray(ref["perm"]["comp_counts"]) > 0).sum())
+    vals = 3 * rank * (cfg.hidden + cfg.ffn)
+    assert Ls.stats()["bytes_factors"] == n_comp * (vals * 3 // 8 + vals // 64 * 4)
+    # the compensation is really there: without it the output differs by far more than the tolerance
+    assert orc.rel_frobenius(_to_np(out_r), fixtures.oracle_forward(cfg.with_(top_n=0), layer, x_bits)["out"]) > 5 * TOL
+    Lr.close(); Ls.close()
