@@ -106,3 +106,11 @@ def test_pack_rejects_out_of_range_codes(lib):
     assert ei.value.code == -1
     with pytest.raises(binding.MoeLrcError):
         binding.pack_codes(2, np.zeros((256, 10), np.uint8))     # N not a multiple of 16
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # this build runs on one GPU: bench.py says so and exits before touching a device
+    import subprocess, sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
