@@ -88,6 +88,8 @@ def main():
                     help="also time one layer in staged residency (packed experts and factors copied from the "
                          "pinned pool per call, chosen by the router) and report it under 'staging'; "
                          "never part of 'value'")
+    ap.add_argument("--staged-int3", action="store_true",
+                    help="with --staged: the factor pairs are held at 3 bits in the pinned pool and expanded on the device")
     ap.add_argument("--calib-copy", action="store_true",
                     help="after the timed region run an elementwise kernel that reads and writes 256 MiB, "
                          "so that a counter run can scale FETCH_SIZE / WRITE_SIZE by a known transfer")
@@ -236,7 +238,11 @@ def main():
         for e in range(n_all):
             for m in (0, 1, 2):
                 a = experts[e][m]
-                Ls.set_expert(e, m, a["codes"], a["scale"], a["zero"], a["A"], a["B"])
+                if args.staged_int3 and e < cfg.n_experts and cfg.rank > 0:
+                    Ls.set_expert(e, m, a["codes"], a["scale"], a["zero"], None, None, 0)
+                    Ls.set_expert_factors_quantized(e, m, cfg.rank, *synth.sample_factor_codes(cfg, e, m))
+                else:
+                    Ls.set_expert(e, m, a["codes"], a["scale"], a["zero"], a["A"], a["B"])
         for _ in range(3):
             Ls.forward_raw(x.data_ptr(), T, out.data_ptr(), ws.data_ptr(), ws_bytes, stream)
         torch.cuda.synchronize()
@@ -253,7 +259,8 @@ def main():
         staging = {"ms_per_step_incl_copies": round(dts, 4), "copy_ms": round(float(np.mean(copy_ms)), 4),
                    "bytes_per_step": int(moved), "copy_gbs": round(moved / (float(np.mean(copy_ms)) * 1e-3) / 1e9, 1),
                    "tokens_per_s_incl_copies": round(T / (dts * 1e-3), 1),
-                   "experts_copied": int(sst["active_experts"]), "factor_sets_copied": int(sst["comp_experts"])}
+                   "experts_copied": int(sst["active_experts"]), "factor_sets_copied": int(sst["comp_experts"]),
+                   "bytes_factors": int(sst["bytes_factors"]), "factors": "int3" if args.staged_int3 else "bf16"}
         Ls.close()
     if args.calib_copy:
         src = torch.zeros(64 << 20, dtype=torch.float32, device="cuda")

@@ -122,3 +122,19 @@ def sample_artifacts(cfg: LayerConfig, expert: int, mat: int, with_factors: bool
         out["A"] = f32_to_bf16_bits(amp / np.float32(np.sqrt(K)) * rng.standard_normal((K, r), dtype=np.float32))
         out["B"] = f32_to_bf16_bits(amp / np.float32(np.sqrt(N)) * rng.standard_normal((r, N), dtype=np.float32))
     return out
+
+
+def sample_factor_codes(cfg: LayerConfig, expert: int, mat: int) -> tuple:
+    """A factor pair held at 3 bits, drawn directly (for timing runs only): uniform codes, scale and
+    zero of the magnitude a min/max quantizer gives on the factors of sample_artifacts.
+    Returns (Aq, Bq): {"codes" uint8 [K][r] / [N][r], "scale", "zero" fp16 bits [K/64][r] / [N/64][r]}."""
+    K, N = mat_shape(cfg, mat)
+    r = cfg.rank
+    rng = np.random.default_rng([cfg.seed, _TAG_ART, expert, mat, 3])
+    out = []
+    for rows in (K, N):
+        codes = rng.integers(0, 8, size=(rows, r), dtype=np.uint8)
+        scale = 0.004 * np.exp(0.15 * rng.standard_normal((rows // 64, r), dtype=np.float32))
+        zero = 3.5 + 0.15 * rng.standard_normal((rows // 64, r), dtype=np.float32)
+        out.append({"codes": codes, "scale": f16_bits(scale), "zero": f16_bits(zero)})
+    return out[0], out[1]
