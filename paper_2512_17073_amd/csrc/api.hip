@@ -167,19 +167,29 @@ static int stage_selected(moe_lrc_layer* L, hipStream_t stream) {
       const int* r = &L->mat_rank[e * 3];
       const uint8_t* q3 = &L->mat_q3[e * 3];
       if (q3[0] | q3[1] | q3[2]) {
+        // 3-bit blobs: one copy from the first to the last byte of the expert's blobs, one launch
+        // that expands them to fp16; projections uploaded as fp16 pairs copy their prefixes
+        size_t lo = ~size_t(0), hi = 0;
+        Q3Expand jobs[3];
         for (int mat = 0; mat < 3; ++mat) {
-          if (r[mat] == 0) continue;
           const MatLayout& m = b.mat[mat];
           const size_t aoff = L->f_off[e] + b.off_af[mat], boff = L->f_off[e] + b.off_bf[mat];
-          if (q3[mat]) {                                              // 3-bit blob, expanded to fp16 on arrival
-            LRC_HIP(hipMemcpyAsync(L->d_fq + aoff, L->h_f + aoff, q3_blob_bytes(m.K, m.N, r[mat]), hipMemcpyHostToDevice, L->side));
-            LRC_HIP(launch_expand_q3(L->d_fq + aoff, m.K, m.N, r[mat], reinterpret_cast<_Float16*>(L->d_f + aoff),
-                                     reinterpret_cast<_Float16*>(L->d_f + boff), L->side));
+          jobs[mat] = Q3Expand{nullptr, m.K, m.N, 0, nullptr, nullptr};
+          if (r[mat] == 0) continue;
+          if (q3[mat]) {
+            const size_t qoff = L->f_off[e] + q3_slot(b, c.rank, mat);
+            lo = std::min(lo, qoff); hi = std::max(hi, qoff + q3_blob_bytes(m.K, m.N, r[mat]));
+            jobs[mat] = Q3Expand{L->d_fq + qoff, m.K, m.N, r[mat], reinterpret_cast<_Float16*>(L->d_f + aoff),
+                                 reinterpret_cast<_Float16*>(L->d_f + boff)};
           } else {
             const MatLayout fm = make_layout(m.K, m.N, m.bits, m.group, r[mat]);
             LRC_HIP(hipMemcpyAsync(L->d_f + aoff, L->h_f + aoff, fm.af_bytes, hipMemcpyHostToDevice, L->side));
             LRC_HIP(hipMemcpyAsync(L->d_f + boff, L->h_f + boff, fm.bf_bytes, hipMemcpyHostToDevice, L->side));
           }
+        }
+        if (hi > lo) {
+          LRC_HIP(hipMemcpyAsync(L->d_fq + lo, L->h_f + lo, hi - lo, hipMemcpyHostToDevice, L->side));
+          LRC_HIP(launch_expand_q3(3, jobs, L->side));
         }
       } else if (r[0] == c.rank && r[1] == c.rank && r[2] == c.rank) {      // the whole factor blob in one piece
         LRC_HIP(hipMemcpyAsync(L->d_f + L->f_off[e], L->h_f + L->f_off[e], b.f_bytes, hipMemcpyHostToDevice, L->side));
@@ -434,6 +444,13 @@ int moe_lrc_set_expert(moe_lrc_layer* L, int expert, int mat, const uint8_t* cod
   return moe_lrc_set_expert_ranked(L, expert, mat, codes, scale, zero, A, B, routed ? L->cfg.rank : 0);
 }
 
+// offset of projection `mat`'s 3-bit blob inside an expert's factor region (room for rank `max_rank` each)
+static size_t q3_slot(const BlobLayout& b, int max_rank, int mat) {
+  size_t o = 0;
+  for (int j = 0; j < mat; ++j) o += (q3_blob_bytes(b.mat[j].K, b.mat[j].N, max_rank) + 255) & ~size_t(255);
+  return o;
+}
+
 int moe_lrc_set_expert_factors_quantized(moe_lrc_layer* L, int expert, int mat, int rank,
                                   const uint8_t* a_codes, const uint16_t* a_scale, const uint16_t* a_zero,
                                   const uint8_t* b_codes, const uint16_t* b_scale, const uint16_t* b_zero) {
@@ -457,16 +474,18 @@ int moe_lrc_set_expert_factors_quantized(moe_lrc_layer* L, int expert, int mat, 
     hipError_t e = hipMalloc((void**)&L->d_fq, L->f_total);
     if (e != hipSuccess) return set_error(MOE_LRC_ENOMEM, std::string("set_expert_factors_quantized: ") + hipGetErrorString(e));
   }
-  // the blob (0.44 bytes per value) takes the start of the projection's A section (2 bytes per value)
+  // the blobs of an expert's three projections (0.44 bytes per value) lie back to back at the start
+  // of its factor region in the pinned pool and in the landing area, each with room for the layer's rank
+  const size_t qoff = L->f_off[expert] + q3_slot(b, c.rank, mat);
   const size_t aoff = L->f_off[expert] + b.off_af[mat], boff = L->f_off[expert] + b.off_bf[mat];
   const MatLayout fm = make_layout(m.K, m.N, m.bits, m.group, rank);
-  _Float16* af = reinterpret_cast<_Float16*>(L->d_f + aoff);
-  _Float16* bf = reinterpret_cast<_Float16*>(L->d_f + boff);
   if (c.residency == MOE_LRC_STAGED) {
-    std::memcpy(L->h_f + aoff, blob.data(), blob.size());
+    std::memcpy(L->h_f + qoff, blob.data(), blob.size());
   } else {                                 // resident: expanded to fp16 once, here
-    LRC_HIP(hipMemcpy(L->d_fq + aoff, blob.data(), blob.size(), hipMemcpyHostToDevice));
-    LRC_HIP(launch_expand_q3(L->d_fq + aoff, m.K, m.N, rank, af, bf, nullptr));
+    LRC_HIP(hipMemcpy(L->d_fq + qoff, blob.data(), blob.size(), hipMemcpyHostToDevice));
+    const Q3Expand job{L->d_fq + qoff, m.K, m.N, rank, reinterpret_cast<_Float16*>(L->d_f + aoff),
+                       reinterpret_cast<_Float16*>(L->d_f + boff)};
+    LRC_HIP(launch_expand_q3(1, &job, nullptr));
     LRC_HIP(hipDeviceSynchronize());
   }
   if (m.af_bytes > fm.af_bytes) LRC_HIP(hipMemset(L->d_f + aoff + fm.af_bytes, 0, m.af_bytes - fm.af_bytes));

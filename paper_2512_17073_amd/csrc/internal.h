@@ -127,6 +127,8 @@ hipError_t launch_debug_unpack(const uint32_t* packed, const MatLayout& m, uint8
                                hipStream_t s);
 // 3-bit factor blob (q3_blob_bytes) -> the fp16 factor sections of one projection (rank-major layouts)
 size_t q3_blob_bytes(int K, int N, int rank);
-hipError_t launch_expand_q3(const uint8_t* blob_dev, int K, int N, int rank, _Float16* af, _Float16* bf, hipStream_t s);
+struct Q3Expand { const uint8_t* blob; int K, N, rank; _Float16* af; _Float16* bf; };   // blob on the device; rank 0: skip
+// one launch for up to three projections
+hipError_t launch_expand_q3(int n, const Q3Expand* jobs, hipStream_t s);
 
 }  // namespace lrc
