@@ -134,3 +134,47 @@ def covering_token_mask(cfg: LayerConfig, route_idx: np.ndarray, min_tokens: int
             break
         mask[t] = True
     return mask
+
+
+def stratified_rows(cnt: int) -> list:
+    """Positions (0-based, within one expert's `cnt` grouped rows) that a full-size check must look
+    at: the first and last row of the first and of the last 16-row tile of the first, a middle and
+    the last (ragged) 128-row chunk; the same for the second 32-row pass when there is one (rows 32,
+    47, 48, 63); and row 16 (the first row of a second row tile) whenever the expert has one."""
+    pos = set()
+    if cnt <= 0:
+        return []
+    chunks = (cnt + 127) // 128
+    for c in sorted({0, chunks // 2, chunks - 1}):
+        base = 128 * c
+        n = min(128, cnt - base)
+        last_tile = base + 16 * ((n - 1) // 16)
+        for r in (base, min(base + 15, base + n - 1), last_tile, base + n - 1):
+            pos.add(r)
+    for r in (16, 31, 32, 47, 48, 63):
+        if r < cnt:
+            pos.add(r)
+    return sorted(pos)
+
+
+def stratified_token_mask(cfg: LayerConfig, route_idx: np.ndarray, perm: dict, min_tokens: int = 64) -> np.ndarray:
+    """Tokens for a full-size output check: for every expert the tokens that hold its rows at
+    stratified_rows(count), plus covering_token_mask (both flag classes of every active expert),
+    padded to `min_tokens` with tokens spread evenly over the batch."""
+    T, k = route_idx.shape
+    mask = covering_token_mask(cfg, route_idx, min_tokens=0)
+    off = perm["offsets"]
+    for e in range(len(off) - 1):
+        for r in stratified_rows(int(off[e + 1] - off[e])):
+            mask[perm["row_pair"][off[e] + r] // k] = True
+    want = min(min_tokens, T)
+    if mask.sum() < want:
+        for t in np.linspace(0, T - 1, num=T, dtype=np.int64)[:: max(1, T // want)]:
+            if mask.sum() >= want:
+                break
+            mask[t] = True
+        for t in range(T):
+            if mask.sum() >= want:
+                break
+            mask[t] = True
+    return mask

@@ -2,13 +2,20 @@
 Qwen3-MoE-shaped layers), in the launch configuration bench.py times.
 
 Routing, counts and permutation are compared for every token (bit-exact).  The expert FFN is
-O(T * 3HF) in fp64 on the CPU, so the layer output is compared on a deterministic token subset that
-touches every active expert in both flag classes (compensated / not), as a relative Frobenius
-error over that subset (bar: 5e-3).  Unpacked codes are compared for a sample of projections.
+O(T * 3HF) in fp64 on the CPU, so the layer output is compared on a deterministic token subset, as
+a relative Frobenius error over that subset (bar: 5e-3) and per token.  The subset is stratified by
+where a token's rows fall inside their experts (oracle.fixtures.stratified_token_mask): the first
+and last row of the first and last 16-row tile of the first, a middle and the last (ragged) 128-row
+chunk, the second 32-row pass, row 16 and up of every expert that has one, and both flag classes
+(compensated / not) of every active expert; at least 64 tokens.  Every (row tile, chunk, pass)
+class the kernels distinguish therefore meets the oracle at the full K.  The measured errors are
+appended to gpurun_out/parity_errors.jsonl.  Unpacked codes are compared for a sample of projections.
 Fixtures are the real recipe (N(0,0.02) weights with outliers, group-wise quantizer, residual
 factors); at these sizes the factors come from the randomized truncated SVD of the oracle's
 compressor, which the forward pass does not care about (it is checked on whatever is stored).
 """
+import json
+import os
 import sys
 import time
 
@@ -25,6 +32,19 @@ TOL = 5e-3
 
 def _say(msg):
     print(f"[full-size] {msg}", flush=True, file=sys.stderr)
+
+
+def _record(entry):
+    """Appends one measured-error record to gpurun_out/parity_errors.jsonl (the figures tabled in
+    the design notes come from this file)."""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = os.path.join(root, "gpurun_out")
+    try:
+        os.makedirs(out, exist_ok=True)
+        with open(os.path.join(out, "parity_errors.jsonl"), "a") as f:
+            f.write(json.dumps(entry) + "\n")
+    except OSError:
+        pass
 
 
 @pytest.fixture(scope="module")
@@ -79,8 +99,10 @@ def _check(amd, cfg, layer, L, sample_mats=((0, 0), (1, 2))):
         np.testing.assert_array_equal(_to_np(got), p[key], err_msg=key)
     for e, mat in sample_mats:
         np.testing.assert_array_equal(_to_np(L.debug_unpack(e, mat)), layer["experts"][e][mat]["codes"])
-    mask = fixtures.covering_token_mask(cfg, r["idx"], min_tokens=min(T, 24))
-    _say(f"{cfg.name}: T={T} oracle FFN on {int(mask.sum())} tokens")
+    mask = fixtures.stratified_token_mask(cfg, r["idx"], p, min_tokens=64)
+    rows_checked = max((int(np.flatnonzero(mask[p["row_pair"][p["offsets"][e]:p["offsets"][e + 1]] // cfg.top_k]).max(initial=-1))
+                        for e in range(cfg.n_experts)), default=-1)
+    _say(f"{cfg.name}: T={T} oracle FFN on {int(mask.sum())} tokens (highest row within an expert: {rows_checked})")
     t0 = time.time()
     ref = fixtures.oracle_forward(cfg, layer, x_bits, token_mask=mask)
     _say(f"{cfg.name}: oracle done in {time.time() - t0:.0f}s; GPU forward")
@@ -91,8 +113,11 @@ def _check(amd, cfg, layer, L, sample_mats=((0, 0), (1, 2))):
     got = _to_np(out)
     assert np.isfinite(got).all()
     err = orc.rel_frobenius(got, ref["out"])
-    _say(f"{cfg.name}: T={T} output rel. Frobenius error {err:.2e} on {int(mask.sum())} tokens")
-    assert err <= TOL
+    per_tok = np.linalg.norm(got[mask] - ref["out"][mask], axis=1) / np.linalg.norm(ref["out"][mask], axis=1)
+    _say(f"{cfg.name}: T={T} output rel. Frobenius error {err:.2e} on {int(mask.sum())} tokens, worst token {per_tok.max():.2e}")
+    _record({"config": cfg.name, "T": T, "bits": cfg.bits, "rank": cfg.rank, "tokens_checked": int(mask.sum()),
+             "highest_row_in_expert": rows_checked, "rel_frobenius": err, "worst_token": float(per_tok.max())})
+    assert err <= TOL and per_tok.max() <= 2 * TOL
     st = L.stats()
     want = compress.staged_bytes(p["counts"], p["comp_counts"], cfg.hidden, cfg.ffn, cfg.bits, cfg.group, cfg.rank)
     P = 3 * cfg.hidden * cfg.ffn
@@ -120,7 +145,7 @@ def test_mixtral_3bit_decode_and_prefill(amd):
     layer32 = _with_rank(layer64, 32)
     L32 = amd.Layer.from_config(dec, max_tokens=64)
     L32.load(layer32)
-    for T in (1, 64):
+    for T in (1, 8, 32, 64):
         _check(amd, dec.with_(tokens=T, name=f"mixtral_decode_T{T}_b3"), layer32, L32)
     L32.close()
 
