@@ -13,7 +13,7 @@ from typing import Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("MOE_LRC_LIB") or os.path.join(_HERE, "libmoe_lrc.so")   # override: kernel-variant sweeps
+LIB_PATH = os.path.join(_HERE, "libmoe_lrc.so")
 
 RESIDENT, STAGED = 0, 1
 

@@ -3,6 +3,7 @@
 // factors from the pinned pool (Sections 3.2 and 4.3 case 1), and the launch sequence.
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "internal.h"
@@ -90,7 +91,7 @@ Workspace plan_workspace(const moe_lrc_layer* L, int T) {
   w.sh_y_part = take(size_t(kMaxKBlocks) * c.n_shared * T * c.hidden * 4);   // (shared experts run beside the routed ones)
   w.sh_h = take(c.n_shared ? (size_t(c.n_shared) * T + kActPadRows) * Fp * 2 : 0);
   w.sh_y = take(size_t(c.n_shared) * T * c.hidden * 2);
-  w.plan = take(size_t(plan_blocks(c.n_experts, int(P), c.ffn / 16) + plan_blocks(c.n_experts, int(P), c.hidden / 16)) * 16);
+  w.plan = take(size_t(plan_blocks(c.n_experts, int(P), c.ffn / 16, L->n_cu) + plan_blocks(c.n_experts, int(P), c.hidden / 16, L->n_cu)) * 16);
   w.total = o;
   return w;
 }
@@ -149,6 +150,13 @@ static void fill_algorithmic_stats(moe_lrc_layer* L, const int32_t* stat) {
   L->stats_valid = true;
 }
 
+// offset of projection `mat`'s 3-bit blob inside an expert's factor region (room for rank `max_rank` each)
+static size_t q3_slot(const BlobLayout& b, int max_rank, int mat) {
+  size_t o = 0;
+  for (int j = 0; j < mat; ++j) o += (q3_blob_bytes(b.mat[j].K, b.mat[j].N, max_rank) + 255) & ~size_t(255);
+  return o;
+}
+
 // Copies the packed blobs of every expert that received a row, and the factor blobs of every expert
 // that received a Top-n row, from the pinned pool into the device slots on the side stream.
 static int stage_selected(moe_lrc_layer* L, hipStream_t stream) {
@@ -158,12 +166,11 @@ static int stage_selected(moe_lrc_layer* L, hipStream_t stream) {
   LRC_HIP(hipStreamSynchronize(stream));       // the one host read-back: which experts are needed
   fill_algorithmic_stats(L, L->h_stat);
   LRC_HIP(hipEventRecord(L->ev_t0, L->side));
-  for (int e = 0; e < L->n_total; ++e) {
-    const bool shared = e >= E;
+  for (int e = 0; e < E; ++e) {
     const BlobLayout& b = blob_of(L, e);
-    if (shared || L->h_stat[2 + e] > 0)
+    if (L->h_stat[2 + e] > 0)
       LRC_HIP(hipMemcpyAsync(L->d_w + L->w_off[e], L->h_w + L->w_off[e], b.w_bytes, hipMemcpyHostToDevice, L->side));
-    if (!shared && b.f_bytes && c.top_n > 0 && L->h_stat[2 + E + e] > 0) {
+    if (b.f_bytes && c.top_n > 0 && L->h_stat[2 + E + e] > 0) {
       const int* r = &L->mat_rank[e * 3];
       const uint8_t* q3 = &L->mat_q3[e * 3];
       if (q3[0] | q3[1] | q3[2]) {
@@ -188,7 +195,7 @@ static int stage_selected(moe_lrc_layer* L, hipStream_t stream) {
           }
         }
         if (hi > lo) {
-          LRC_HIP(hipMemcpyAsync(L->d_fq + lo, L->h_f + lo, hi - lo, hipMemcpyHostToDevice, L->side));
+          LRC_HIP(hipMemcpyAsync(L->d_fq + lo, L->h_fq + lo, hi - lo, hipMemcpyHostToDevice, L->side));
           LRC_HIP(launch_expand_q3(3, jobs, L->side));
         }
       } else if (r[0] == c.rank && r[1] == c.rank && r[2] == c.rank) {      // the whole factor blob in one piece
@@ -228,6 +235,7 @@ static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t*
   a.y_part = reinterpret_cast<float*>(ws + w.y_part);
   a.plan = reinterpret_cast<int32_t*>(ws + w.plan);
   a.y_rows = y_rows; a.ksplit13 = L->ksplit13; a.ksplit2 = L->ksplit2; a.total_rows = T * c.top_k;
+  a.n_cu = L->n_cu;
   // the launch that converts the activations also makes the block tables of the decode launches
   PlanSpec plans[2];
   expert_ffn_plan_specs(a, plans[0], plans[1]);
@@ -241,7 +249,7 @@ static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t*
   if (mark) LRC_HIP(hipEventRecord(L->marks[MOE_LRC_STAGE_XA13], stream));
   a.marks = mark ? &L->marks[MOE_LRC_STAGE_W13] : nullptr;
   LRC_HIP(launch_expert_ffn(a, stream));
-  L->stats.path = 0;
+  L->stats.path = expert_ffn_path(a);
   return MOE_LRC_OK;
 }
 
@@ -258,6 +266,7 @@ static int run_shared(moe_lrc_layer* L, const void* x, int T, uint8_t* ws, hipSt
   a.x_rt = T + kActPadRows; a.h_rt = c.n_shared * T + kActPadRows;
   a.y_part = reinterpret_cast<float*>(ws + w.sh_y_part);
   a.y_rows = ws + w.sh_y; a.ksplit13 = 1; a.ksplit2 = 1; a.total_rows = T * c.n_shared;
+  a.n_cu = L->n_cu;
   LRC_HIP(launch_expert_ffn(a, stream));
   return MOE_LRC_OK;
 }
@@ -278,6 +287,24 @@ int moe_lrc_layer_create(const moe_lrc_config* cfg, moe_lrc_layer** out) {
   if (!L) return set_error(MOE_LRC_ENOMEM, "layer_create: out of host memory");
   L->cfg = *cfg;
   L->device = dev;
+  {
+    // once per device: the FFN kernels are allowed the whole LDS of a CU
+    static std::mutex mu;
+    static bool ready[64] = {};
+    std::lock_guard<std::mutex> lock(mu);
+    if (dev >= 0 && dev < 64 && !ready[dev]) {
+      hipError_t e = ffn_init_device();
+      if (e != hipSuccess) {
+        delete L;
+        return set_error(MOE_LRC_EHIP, std::string("layer_create: kernel attributes: ") + hipGetErrorString(e));
+      }
+      ready[dev] = true;
+    }
+  }
+  if (hipDeviceGetAttribute(&L->n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || L->n_cu <= 0) {
+    delete L;
+    return set_error(MOE_LRC_EHIP, "layer_create: cannot read the device's compute unit count");
+  }
   L->n_total = cfg->n_experts + cfg->n_shared;
   L->routed = make_blob(*cfg, cfg->bits, cfg->rank);
   L->shared = make_blob(*cfg, cfg->n_shared ? cfg->shared_bits : cfg->bits, 0);
@@ -353,6 +380,7 @@ int moe_lrc_layer_destroy(moe_lrc_layer* L) {
   if (L->d_fq) (void)hipFree(L->d_fq);
   if (L->h_w) (void)hipHostFree(L->h_w);
   if (L->h_f) (void)hipHostFree(L->h_f);
+  if (L->h_fq) (void)hipHostFree(L->h_fq);
   if (L->d_desc) (void)hipFree(L->d_desc);
   if (L->d_wg) (void)hipFree(L->d_wg);
   if (L->d_bias) (void)hipFree(L->d_bias);
@@ -403,8 +431,10 @@ int moe_lrc_set_expert_ranked(moe_lrc_layer* L, int expert, int mat, const uint8
   pack_codes(m, codes, reinterpret_cast<uint32_t*>(wbuf.data()));
   const float lambda = pack_meta(m, scale, zero, reinterpret_cast<uint32_t*>(wbuf.data() + m.codes_bytes));
   // codes and meta sections of one projection are adjacent in the blob
+  // (shared experts serve every token of every call: their slots are filled here, once, also in
+  // staged residency; only routed experts live in the pinned pool)
   const size_t woff = L->w_off[expert] + b.off_codes[mat];
-  if (c.residency == MOE_LRC_STAGED) std::memcpy(L->h_w + woff, wbuf.data(), wbuf.size());
+  if (c.residency == MOE_LRC_STAGED && expert < c.n_experts) std::memcpy(L->h_w + woff, wbuf.data(), wbuf.size());
   else LRC_HIP(hipMemcpy(L->d_w + woff, wbuf.data(), wbuf.size(), hipMemcpyHostToDevice));
 
   // Factors: the layouts are rank-major, so the pair of rank `rank` is a prefix of the projection's A
@@ -444,13 +474,6 @@ int moe_lrc_set_expert(moe_lrc_layer* L, int expert, int mat, const uint8_t* cod
   return moe_lrc_set_expert_ranked(L, expert, mat, codes, scale, zero, A, B, routed ? L->cfg.rank : 0);
 }
 
-// offset of projection `mat`'s 3-bit blob inside an expert's factor region (room for rank `max_rank` each)
-static size_t q3_slot(const BlobLayout& b, int max_rank, int mat) {
-  size_t o = 0;
-  for (int j = 0; j < mat; ++j) o += (q3_blob_bytes(b.mat[j].K, b.mat[j].N, max_rank) + 255) & ~size_t(255);
-  return o;
-}
-
 int moe_lrc_set_expert_factors_quantized(moe_lrc_layer* L, int expert, int mat, int rank,
                                   const uint8_t* a_codes, const uint16_t* a_scale, const uint16_t* a_zero,
                                   const uint8_t* b_codes, const uint16_t* b_scale, const uint16_t* b_zero) {
@@ -474,13 +497,18 @@ int moe_lrc_set_expert_factors_quantized(moe_lrc_layer* L, int expert, int mat, 
     hipError_t e = hipMalloc((void**)&L->d_fq, L->f_total);
     if (e != hipSuccess) return set_error(MOE_LRC_ENOMEM, std::string("set_expert_factors_quantized: ") + hipGetErrorString(e));
   }
+  if (c.residency == MOE_LRC_STAGED && !L->h_fq) {   // pinned home of the 3-bit blobs: a region of its own, so that a
+    // projection held at 3 bits and one held as an fp16 pair can share an expert
+    hipError_t e = hipHostMalloc((void**)&L->h_fq, L->f_total, hipHostMallocDefault);
+    if (e != hipSuccess) return set_error(MOE_LRC_ENOMEM, std::string("set_expert_factors_quantized: ") + hipGetErrorString(e));
+  }
   // the blobs of an expert's three projections (0.44 bytes per value) lie back to back at the start
-  // of its factor region in the pinned pool and in the landing area, each with room for the layer's rank
+  // of the expert's range in that region and in the landing area, each with room for the layer's rank
   const size_t qoff = L->f_off[expert] + q3_slot(b, c.rank, mat);
   const size_t aoff = L->f_off[expert] + b.off_af[mat], boff = L->f_off[expert] + b.off_bf[mat];
   const MatLayout fm = make_layout(m.K, m.N, m.bits, m.group, rank);
   if (c.residency == MOE_LRC_STAGED) {
-    std::memcpy(L->h_f + qoff, blob.data(), blob.size());
+    std::memcpy(L->h_fq + qoff, blob.data(), blob.size());
   } else {                                 // resident: expanded to fp16 once, here
     LRC_HIP(hipMemcpy(L->d_fq + qoff, blob.data(), blob.size(), hipMemcpyHostToDevice));
     const Q3Expand job{L->d_fq + qoff, m.K, m.N, rank, reinterpret_cast<_Float16*>(L->d_f + aoff),

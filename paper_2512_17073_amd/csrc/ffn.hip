@@ -35,27 +35,6 @@ constexpr int kTileWaves = 8;             // wavefronts per block
 constexpr int kBM = 128;                  // rows of an expert per block
 constexpr int kTMT = kBM / 16;            // row tiles
 constexpr int kStepUnits = kTMT * 8 * 64; // 16-byte units of one k-step of activations (64 KB)
-#ifndef LRC_TILE_PF
-#define LRC_TILE_PF(bits) 1
-#endif
-
-// LDS read of one 16-byte unit per lane whose result is awaited by lds_wait, not by the compiler
-// (which would move each read down to its use).
-template <int OFF> __device__ inline half8_t lds_read16(uint32_t addr) {
-  half8_t v;
-  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
-  return v;
-}
-// Waits until at most N LDS operations issued after the wanted one are outstanding (LDS returns in
-// order), and ties the wanted register to the wait so that its uses stay behind it.
-template <int N> __device__ inline void lds_wait(half8_t& a) { asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a) : "n"(N)); }
-
-template <class T> __device__ inline const T* uniform_ptr(const T* p) {
-  const uint64_t v = reinterpret_cast<uint64_t>(p);
-  const uint32_t lo = __builtin_amdgcn_readfirstlane(uint32_t(v)), hi = __builtin_amdgcn_readfirstlane(uint32_t(v >> 32));
-  return reinterpret_cast<const T*>((uint64_t(hi) << 32) | lo);
-}
-
 // Work item `item` of a launch -> (expert, first row of its 128-row chunk).  Routed experts: the
 // items enumerate the chunks of the experts in order (an expert with cnt rows has ceil(cnt / 128));
 // shared experts: every expert has the same T rows.
@@ -195,7 +174,7 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
 
   // A fragment read from LDS meets the operands of all (tile, projection) pairs of the wavefront.
   // The read of the next row tile's fragment is issued before the MFMAs of the current one.
-  constexpr int PF = LRC_TILE_PF(BITS);   // fragments requested ahead of the one being multiplied
+  constexpr int PF = 1;                   // fragments requested ahead of the one being multiplied
   auto mfma_rows = [&](const half8_t (&wf)[kNTW][NM], uint32_t base) {   // base: LDS byte address of (row tile 0, this lane)
     half8_t xf[PF + 1];
     if (mt_n == kTMT) {                   // a full chunk: straight-line, PF reads in flight
@@ -533,21 +512,6 @@ __global__ __launch_bounds__(256) void xa_finish_kernel(const float* __restrict_
 
 template <int BITS>
 hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    const void* fns[7] = {reinterpret_cast<const void*>(&qgemm_tile_kernel<BITS, true, 2>),
-                          reinterpret_cast<const void*>(&qgemm_tile_kernel<BITS, false, 4>),
-                          reinterpret_cast<const void*>(&qgemm_tile_kernel<BITS, false, 2>),
-                          reinterpret_cast<const void*>(&xa_tile_kernel<true, 2>),
-                          reinterpret_cast<const void*>(&xa_tile_kernel<false, 2>),
-                          reinterpret_cast<const void*>(&xa_tile_kernel<true, 4>),
-                          reinterpret_cast<const void*>(&xa_tile_kernel<false, 4>)};
-    for (const void* fn : fns) {
-      hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStepUnits * 16);
-      if (e != hipSuccess) return e;
-    }
-    attr_set = true;
-  }
   int gs = 0;
   while ((1 << gs) < f.group) ++gs;
   KArgs a{};
@@ -595,7 +559,7 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
   // blocks twice as large: take the one with fewer (weighted) rounds of blocks over the 256 CUs
   // (expected number of chunks: about half of the experts end with a partly filled one)
   const int chunks = std::max(1, f.offsets ? f.total_rows / kBM + (f.n_exp + 1) / 2 : f.n_exp * ((f.T + kBM - 1) / kBM));
-  auto rounds = [&](int ntw) { return (chunks * ((a.NT + 8 * ntw - 1) / (8 * ntw)) + 255) / 256 * ntw; };
+  auto rounds = [&](int ntw) { return (chunks * ((a.NT + 8 * ntw - 1) / (8 * ntw)) + f.n_cu - 1) / f.n_cu * ntw; };
   if (rounds(4) * 100 <= rounds(2) * 108)
     hipLaunchKernelGGL((qgemm_tile_kernel<BITS, false, 4>), dim3((a.NT + 31) / 32, items), dim3(64 * kTileWaves), lds, s, a);
   else
@@ -611,21 +575,46 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
 // flavour up to 24 rows per expert; beyond that the grouped GEMM as soon as it is efficient: the
 // fused W1|W3 from about 40 rows per expert on, W2 (whose grid has few column blocks) once its grid
 // of (128-row chunk, 256 columns) blocks covers the 256 CUs.
-#ifndef LRC_DECODE_MAX_ROWS13
-#define LRC_DECODE_MAX_ROWS13 40
-#endif
+constexpr int kDecodeMaxRows13 = 40;
 
 // bit 0: W1|W3 takes the decode flavour, bit 1: W2 does
 static int decode_parts(const FfnArgs& f) {
   // expected rows per expert under uniform routing decides the flavour of each projection
   const int rows = f.offsets ? (f.T * f.top_k + f.n_exp - 1) / f.n_exp : f.T;
   const int chunks = f.offsets ? f.total_rows / kBM + (f.n_exp + 1) / 2 : f.n_exp * ((f.T + kBM - 1) / kBM);
-  const bool w2_grid_full = chunks * ((f.H / kTileN + 15) / 16) >= 256;
-  const bool d13 = rows <= LRC_DECODE_MAX_ROWS13;
+  const bool w2_grid_full = chunks * ((f.H / kTileN + 15) / 16) >= f.n_cu;
+  const bool d13 = rows <= kDecodeMaxRows13;
   // (beyond 128 rows per expert the decode flavour would stream the weights five times or more)
   const bool d2 = rows <= 24 || (!w2_grid_full && rows <= 128);
   return (d13 ? 1 : 0) | (d2 ? 2 : 0);
 }
+
+template <int BITS> static hipError_t tile_init_bits() {
+  const void* fns[3] = {reinterpret_cast<const void*>(&qgemm_tile_kernel<BITS, true, 2>),
+                        reinterpret_cast<const void*>(&qgemm_tile_kernel<BITS, false, 4>),
+                        reinterpret_cast<const void*>(&qgemm_tile_kernel<BITS, false, 2>)};
+  for (const void* fn : fns) {
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStepUnits * 16);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+hipError_t ffn_init_device() {
+  const void* fns[4] = {reinterpret_cast<const void*>(&xa_tile_kernel<true, 2>), reinterpret_cast<const void*>(&xa_tile_kernel<false, 2>),
+                        reinterpret_cast<const void*>(&xa_tile_kernel<true, 4>), reinterpret_cast<const void*>(&xa_tile_kernel<false, 4>)};
+  for (const void* fn : fns) {
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStepUnits * 16);
+    if (e != hipSuccess) return e;
+  }
+  hipError_t e = tile_init_bits<2>();
+  if (e == hipSuccess) e = tile_init_bits<3>();
+  if (e == hipSuccess) e = tile_init_bits<4>();
+  if (e == hipSuccess) e = decode_init_device();
+  return e;
+}
+
+int expert_ffn_path(const FfnArgs& f) { return 3 & ~decode_parts(f); }
 
 void expert_ffn_plan_specs(const FfnArgs& f, PlanSpec& p13, PlanSpec& p2) { decode_plan_specs(f, decode_parts(f), p13, p2); }
 

@@ -62,6 +62,27 @@ __device__ inline size_t act_unit(int k8, int R, int rt) {
   return size_t((ks * 8 + s) * 4 + q) * rt + R;
 }
 
+// LDS read of one 16-byte unit per lane whose result is awaited by lds_wait, not by the compiler
+// (which would move each read down to its use).
+template <int OFF> __device__ inline half8_t lds_read16(uint32_t addr) {
+  half8_t v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+  return v;
+}
+// Waits until at most N LDS operations issued after the wanted ones are outstanding (LDS returns in
+// order), and ties the wanted registers to the wait so that their uses stay behind it.
+template <int N> __device__ inline void lds_wait(half8_t& a) { asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a) : "n"(N)); }
+template <int N> __device__ inline void lds_wait(half8_t& a, half8_t& b) {
+  asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
+}
+
+// A pointer read from memory, moved into scalar registers (a buffer resource must be wave-uniform).
+template <class T> __device__ inline const T* uniform_ptr(const T* p) {
+  const uint64_t v = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane(uint32_t(v)), hi = __builtin_amdgcn_readfirstlane(uint32_t(v >> 32));
+  return reinterpret_cast<const T*>((uint64_t(hi) << 32) | lo);
+}
+
 // Codes and metadata of one k-step of one wavefront (both projections when DUAL), in registers.
 template <int BITS, int NM> struct Slot {
   uint32_t cw[NM][2 * BITS];

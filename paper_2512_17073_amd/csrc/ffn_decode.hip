@@ -29,76 +29,26 @@ using namespace ffn;
 constexpr int kDecodeWaves = 16;
 constexpr int kDecodeLdsUnits = 8192;     // 128 KB in 16-byte units
 constexpr int kTPW = 2;                   // n-tiles per wavefront (at most)
-// packed tiles a wavefront holds in registers (one being unpacked, the others in flight), chosen
-// per kernel so that it stays within 128 registers at 16 wavefronts per CU.  Blocks with more in
-// flight take a larger share of a saturated memory system, so the depths are the same for one
-// and two row tiles per pass (measured: deeper rings for one row tile slow the whole kernel down)
-#ifndef LRC_RING_D1
-#define LRC_RING_D1(bits) 2
-#endif
-#ifndef LRC_RING_D2
-#define LRC_RING_D2(bits) 2
-#endif
-#ifndef LRC_RING_S1
-#define LRC_RING_S1(bits) 4
-#endif
-#ifndef LRC_RING_S2
-#define LRC_RING_S2(bits) 4
-#endif
-__host__ __device__ constexpr int decode_ring(int bits, bool dual, int mt) {
-  return dual ? (mt == 1 ? LRC_RING_D1(bits) : LRC_RING_D2(bits)) : (mt == 1 ? LRC_RING_S1(bits) : LRC_RING_S2(bits));
-}
+// packed tiles a wavefront holds in registers (one being unpacked, the others in flight): two for
+// the fused W1|W3 kernel (two projections per slot), four for W2.  Blocks with more in flight take a
+// larger share of a saturated memory system, so the depths are the same for one and two row tiles
+// per pass (measured: deeper rings for one row tile slow the whole kernel down).
+__host__ __device__ constexpr int decode_ring(bool dual) { return dual ? 2 : 4; }
 
-#ifdef LRC_TIMELINE
-// development aid (variant builds only): per-block time stamps of the last decode kernels
-__device__ long long g_timeline[2][4096][16];
-#define LRC_STAMP(slot)                                                                         \
-  do {                                                                                          \
-    if (threadIdx.x == 0 && blockIdx.y * gridDim.x + blockIdx.x < 4096)                         \
-      g_timeline[DUAL ? 0 : 1][blockIdx.y * gridDim.x + blockIdx.x][slot] = wall_clock64();     \
-  } while (0)
-#else
-#define LRC_STAMP(slot) do {} while (0)
-#endif
-
-// One expert's share of a block: MT = row tiles per pass (1 when the expert has at most 16 rows: fewer
-// accumulators, so a deeper ring of packed tiles in flight).
-#ifndef LRC_BODY_INLINE
-#define LRC_BODY_INLINE __forceinline__
-#endif
-// LDS read of one 16-byte unit per lane whose result is awaited by lds_wait, not by the compiler.
-template <int OFF> __device__ inline half8_t lds_read16(uint32_t addr) {
-  half8_t v;
-  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
-  return v;
-}
-// Waits until at most N LDS operations issued after the wanted ones are outstanding (LDS returns in
-// order), and ties the wanted registers to the wait so that their uses stay behind it.
-template <int N> __device__ inline void lds_wait(half8_t& a) { asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a) : "n"(N)); }
-template <int N> __device__ inline void lds_wait(half8_t& a, half8_t& b) {
-  asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
-}
-
-template <class T> __device__ inline const T* uniform_ptr(const T* p) {
-  const uint64_t v = reinterpret_cast<uint64_t>(p);
-  const uint32_t lo = __builtin_amdgcn_readfirstlane(uint32_t(v)), hi = __builtin_amdgcn_readfirstlane(uint32_t(v >> 32));
-  return reinterpret_cast<const T*>((uint64_t(hi) << 32) | lo);
-}
-
+// One expert's share of a block: MT = row tiles per pass (1 when the expert has at most 16 rows).
 template <int BITS, bool DUAL, int MT>
-__device__ LRC_BODY_INLINE void decode_body(const KArgs& a, uint4* xs, const int e, const int r0, const int cnt,
+__device__ __forceinline__ void decode_body(const KArgs& a, uint4* xs, const int e, const int r0, const int cnt,
                                             const int b, const int G) {
   constexpr int NM = DUAL ? 2 : 1;
   constexpr int DW = 2 * BITS;
   constexpr int NC = Extract<BITS>::kClasses;
-  constexpr int RING = decode_ring(BITS, DUAL, MT);
+  constexpr int RING = decode_ring(DUAL);
   constexpr int kDMT = MT;
   const ExpertDesc& d = a.desc[e];
   const int th = threadIdx.x, lane = th & 63;
   const int wave = __builtin_amdgcn_readfirstlane(th >> 6);
   const int q = lane >> 4, c = lane & 15, rowl = th & 15;
   const int tdw = kWave * DW;
-  LRC_STAMP(0);
 
   // this block's n-tiles (block b of the G that share the expert), and how they are dealt to the 16 wavefronts
   const int t0 = (int)((long long)b * a.NT / G), t1 = (int)((long long)(b + 1) * a.NT / G);
@@ -213,7 +163,6 @@ __device__ LRC_BODY_INLINE void decode_body(const KArgs& a, uint4* xs, const int
     //      one round trip); then the activations of phase 0 (straight to LDS) and the first packed
     //      tiles are issued, and only the packed tiles are still in flight when the first barrier is
     //      passed.
-    LRC_STAMP(11);
     if (r > 0) __syncthreads();               // everyone is done with the previous pass's LDS
     // (in A) of this pass's rows, times the projection's power-of-two pre-scale, as fp16 in MFMA
     // operand order: unit ((m * LS + st) * MT + mt) * 64 + lane holds columns 32 st + 8 q .. + 7 of
@@ -258,12 +207,10 @@ __device__ LRC_BODY_INLINE void decode_body(const KArgs& a, uint4* xs, const int
     Slot<BITS, NM> ring[RING];
 #pragma unroll
     for (int i = 0; i < RING; ++i) fetch(i, ring[i]);
-    LRC_STAMP(12);
     // everything but the packed tiles issued last has arrived: the activations are in LDS
     // The barrier is written out: a __syncthreads() here would first wait for every load in flight,
     // the packed tiles included.  LDS writes of this wavefront are awaited by lgkmcnt(0).
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(RING * NM * (BITS == 2 ? 2 : 3)) : "memory");
-    LRC_STAMP(2);
 
     float4_t acc[kTPW][kDMT][NM];
 #pragma unroll
@@ -379,8 +326,6 @@ __device__ LRC_BODY_INLINE void decode_body(const KArgs& a, uint4* xs, const int
       }
       n += RING;
     }
-
-    LRC_STAMP(13);
     // ---- wavefronts that shared an n-tile add up their partial sums through LDS ----
     if (kw > 1) {
       float4_t* red = reinterpret_cast<float4_t*>(xs);
@@ -400,7 +345,6 @@ __device__ LRC_BODY_INLINE void decode_body(const KArgs& a, uint4* xs, const int
             for (int m = 0; m < NM; ++m) acc[0][mt][m] += red[(((wave + j) * kDMT + mt) * NM + m) * 64 + lane];
       }
     }
-    LRC_STAMP(14);
     if (kwi != 0) continue;                  // (the next pass starts with a barrier every wavefront reaches)
 
     // ---- epilogue: lane holds output columns 16*tile + 4*q .. +3 of token column c ----
@@ -437,7 +381,6 @@ __device__ LRC_BODY_INLINE void decode_body(const KArgs& a, uint4* xs, const int
         }
       }
     }
-    LRC_STAMP(15);
   }
 }
 
@@ -532,17 +475,6 @@ static bool use_plan(const FfnArgs& f) {
 
 template <int BITS>
 hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    // 128 KB of activations + up to 32 KB of (in A) for 32 rows at rank 256 = all 160 KB of a CU
-    hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(&qgemm_decode_kernel<BITS, true>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, kDecodeLdsUnits * 16 + 32768);
-    hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(&qgemm_decode_kernel<BITS, false>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, kDecodeLdsUnits * 16 + 32768);
-    if (e1 != hipSuccess) return e1;
-    if (e2 != hipSuccess) return e2;
-    attr_set = true;
-  }
   int gs = 0;
   while ((1 << gs) < f.group) ++gs;
   KArgs a{};
@@ -551,10 +483,10 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
   a.rank = f.rank; a.rpad = f.rpad; a.ls = (f.rank + 31) / 32; a.total_rows = f.total_rows; a.kw = 1; a.ksplit = 1;
   const bool comp = f.rank > 0 && f.top_n > 0 && f.row_pair != nullptr;
   // experts that can be active at all: at most one per routed pair; the blocks of the active
-  // experts alone should cover the 256 CUs, and a block takes at most 32 n-tiles
+  // experts alone should cover the CUs, and a block takes at most 32 n-tiles
   const int max_active = f.offsets ? std::min(f.n_exp, f.T * f.top_k) : f.n_exp;
   auto blocks_per_expert = [&](int NT, int kblocks) {
-    int g = (256 + max_active * kblocks - 1) / (max_active * kblocks);
+    int g = (f.n_cu + max_active * kblocks - 1) / (max_active * kblocks);
     g = std::max(g, (NT + 16 * kTPW - 1) / (16 * kTPW));
     return std::min(g, NT);
   };
@@ -575,7 +507,7 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
   if (f.marks) (void)hipEventRecord(f.marks[0], s);
   a.kb_steps = a.KS; a.partial = nullptr;
   if (by_table) {
-    const int B = plan_blocks(f.n_exp, f.T * f.top_k, a.NT);
+    const int B = plan_blocks(f.n_exp, f.T * f.top_k, a.NT, f.n_cu);
     a.plan = f.plan;
     hipLaunchKernelGGL((qgemm_decode_kernel<BITS, true>), dim3(B, 1, 1), dim3(64 * kDecodeWaves), lds_bytes(2), s, a);
     a.plan = nullptr;
@@ -600,8 +532,8 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
   a.partial = kblocks > 1 ? f.y_part : nullptr;
   if (by_table) {
     // (second table behind the first; every K-block uses the same shares)
-    int32_t* plan2 = f.plan + 4 * plan_blocks(f.n_exp, f.T * f.top_k, f.F / kTileN);
-    const int B = plan_blocks(f.n_exp, f.T * f.top_k, a.NT, (256 + kblocks - 1) / kblocks);
+    int32_t* plan2 = f.plan + 4 * plan_blocks(f.n_exp, f.T * f.top_k, f.F / kTileN, f.n_cu);
+    const int B = plan_blocks(f.n_exp, f.T * f.top_k, a.NT, (f.n_cu + kblocks - 1) / kblocks);
     a.plan = plan2;
     hipLaunchKernelGGL((qgemm_decode_kernel<BITS, false>), dim3(B, 1, kblocks), dim3(64 * kDecodeWaves), lds_bytes(1), s, a);
     a.plan = nullptr;
@@ -621,24 +553,30 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
 
 }  // namespace
 
-#ifdef LRC_TIMELINE
-extern "C" int moe_lrc_debug_timeline(long long* host_out) {
-  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_timeline), sizeof(long long) * 2 * 4096 * 16);
-}
-#endif
-
 void decode_plan_specs(const FfnArgs& f, int which, PlanSpec& p13, PlanSpec& p2) {
   p13 = PlanSpec{0, 0, 0, nullptr};
   p2 = PlanSpec{0, 0, 0, nullptr};
   if (!use_plan(f)) return;
   const int pairs = f.T * f.top_k, NT13 = f.F / kTileN, NT2 = f.H / kTileN;
-  const int B13 = plan_blocks(f.n_exp, pairs, NT13);
-  if (which & 1) p13 = PlanSpec{B13, (NT13 + 31) / 32, 256, f.plan};
+  const int B13 = plan_blocks(f.n_exp, pairs, NT13, f.n_cu);
+  if (which & 1) p13 = PlanSpec{B13, (NT13 + 31) / 32, f.n_cu, f.plan};
   if (which & 2) {
     const int KS2 = padded_k(f.F) / kTileK, kb2 = f.y_part ? std::min(kMaxKBlocks, (KS2 + 15) / 16) : 1;
-    const int target2 = (256 + kb2 - 1) / kb2;
+    const int target2 = (f.n_cu + kb2 - 1) / kb2;
     p2 = PlanSpec{plan_blocks(f.n_exp, pairs, NT2, target2), (NT2 + 31) / 32, target2, f.plan + 4 * B13};
   }
+}
+
+hipError_t decode_init_device() {
+  // 128 KB of activations + up to 32 KB of (in A) for 32 rows at rank 256 = all 160 KB of a CU
+  const void* fns[6] = {reinterpret_cast<const void*>(&qgemm_decode_kernel<2, true>), reinterpret_cast<const void*>(&qgemm_decode_kernel<2, false>),
+                        reinterpret_cast<const void*>(&qgemm_decode_kernel<3, true>), reinterpret_cast<const void*>(&qgemm_decode_kernel<3, false>),
+                        reinterpret_cast<const void*>(&qgemm_decode_kernel<4, true>), reinterpret_cast<const void*>(&qgemm_decode_kernel<4, false>)};
+  for (const void* fn : fns) {
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kDecodeLdsUnits * 16 + 32768);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 hipError_t launch_decode_ffn(const FfnArgs& f, hipStream_t s, int which) {

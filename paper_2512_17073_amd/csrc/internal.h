@@ -40,6 +40,7 @@ struct Workspace {       // carved out of the caller's buffer; all offsets 256-b
 struct moe_lrc_layer {
   moe_lrc_config cfg;
   int device;
+  int n_cu = 0;                        // compute units of `device`
   lrc::BlobLayout routed, shared;
   int n_total;                         // E + S
   uint8_t* d_w = nullptr;              // device: weight blobs (resident) or slot pool (staged)
@@ -57,6 +58,7 @@ struct moe_lrc_layer {
   std::vector<int> mat_rank;           // [n_total*3] rank of each projection's factor pair (Section 3.1: may differ)
   std::vector<uint8_t> mat_q3;         // [n_total*3] 1: the pair is held at 3 bits (pinned pool / d_fq) and expanded to fp16
   uint8_t* d_fq = nullptr;             // device: landing area of the 3-bit factor blobs, laid out like d_f (allocated on first use)
+  uint8_t* h_fq = nullptr;             // pinned home of the 3-bit factor blobs (staged only; allocated on first use)
   size_t f_total = 0;                  // bytes of d_f (and of d_fq, h_f)
   int32_t* d_stat = nullptr;           // [2 + 2E]: active, comp-active, counts, comp counts
   int32_t* h_stat = nullptr;           // pinned mirror
@@ -88,9 +90,9 @@ hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _
                             const int32_t* offsets, const int32_t* row_pair, int32_t* stat,
                             const PlanSpec* plans /* two, or null */, hipStream_t s);
 constexpr int kMaxKBlocks = 8;    // most K-blocks the decode W2 kernel splits into
-// blocks (per K-block) of a decode launch that shares its blocks out by a table: `target` (the 256
-// CUs over the K-blocks), or enough for ceil(NT / 32) blocks per expert that can be active
-inline int plan_blocks(int n_exp, int pairs, int NT, int target = 256) {
+// blocks (per K-block) of a decode launch that shares its blocks out by a table: `target` (the
+// device's CUs over the K-blocks), or enough for ceil(NT / 32) blocks per expert that can be active
+inline int plan_blocks(int n_exp, int pairs, int NT, int target) {
   const int active = n_exp < pairs ? n_exp : pairs, base = (NT + 31) / 32;
   return active * base > target ? active * base : target;
 }
@@ -115,9 +117,15 @@ struct FfnArgs {
   int32_t* plan;              // decode flavour, many experts: block -> (expert, block of the expert, blocks of
                               // the expert) tables of the two projections, kPlanBlocks(...) entries of 4 ints each
   int ksplit13, ksplit2, total_rows;
+  int n_cu;                   // compute units of the device (the launches size their grids to fill them)
   hipEvent_t* marks;          // null, or 4 events recorded after xa13, w13, xa2, w2
 };
 hipError_t launch_expert_ffn(const FfnArgs& a, hipStream_t s);
+// bit 0: the fused W1|W3 projection takes the grouped GEMM (else the decode flavour), bit 1: W2 does
+int expert_ffn_path(const FfnArgs& a);
+// once per device, before the first launch: lets the FFN kernels use the whole LDS of a CU
+hipError_t ffn_init_device();
+hipError_t decode_init_device();
 // the block tables (plan.h) that launch_expert_ffn(a) will read: to be made by launch_convert_x
 void expert_ffn_plan_specs(const FfnArgs& a, PlanSpec& p13, PlanSpec& p2);
 hipError_t launch_combine(const moe_lrc_layer* L, const void* y_rows, const float* w,

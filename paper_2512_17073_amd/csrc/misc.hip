@@ -224,7 +224,7 @@ hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _
   const moe_lrc_config& c = L->cfg;
   const int rows = row_pair ? T * c.top_k : T;
   const int row_blocks = (rows + 15) / 16;
-  const int ky = std::max(1, std::min(c.hidden / 128, 256 / std::max(1, row_blocks)));
+  const int ky = std::max(1, std::min(c.hidden / 128, L->n_cu / std::max(1, row_blocks)));
   const PlanSpec none{0, 0, 0, nullptr};
   const PlanSpec p0 = plans ? plans[0] : none, p1 = plans ? plans[1] : none;
   const int plan_block = p0.B + p1.B > 0 ? 1 : 0;
