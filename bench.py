@@ -25,11 +25,23 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16/bf16 MFMA, published
 
-# HBM bytes per launch of the dominant kernel from hardware counters (FETCH_SIZE + WRITE_SIZE, each
-# scaled by what the same counter reads for an elementwise kernel of known size; two separate
-# profiler runs of this script, summarised in profiles/).  Counters cannot be read from inside a
-# timed run, so the figure is carried here per workload; workloads not profiled report null.
-MEASURED_TRAFFIC_BYTES = {"mixtral_decode_T64_b2": 325.4e6}
+
+
+def counter_traffic(workload):
+    """HBM bytes per launch of the dominant kernel from hardware counters (FETCH_SIZE + WRITE_SIZE,
+    each scaled by what the same counter reads for a copy kernel of known size; two separate profiler
+    runs of this script).  Counters cannot be read from inside a timed run: the figure is taken from
+    the counter summary of this workload under profiles/ (a line `traffic_bytes_per_launch: N`), and
+    is null when there is none.  Returns (bytes or None, file name or None)."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.md")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return float(line.split(":", 1)[1].strip()), os.path.relpath(path, ROOT)
+    except OSError:
+        pass
+    return None, None
 
 
 def algorithmic_bytes(cfg, T, active, comp):
@@ -90,6 +102,9 @@ def main():
                          "never part of 'value'")
     ap.add_argument("--staged-int3", action="store_true",
                     help="with --staged: the factor pairs are held at 3 bits in the pinned pool and expanded on the device")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also measure what this device sustains (streaming read of 3 GiB, pinned host->device "
+                         "copy, f16 MFMA rate) and report it as roofline.peak_measured beside the published peaks")
     ap.add_argument("--calib-copy", action="store_true",
                     help="after the timed region run an elementwise kernel that reads and writes 256 MiB, "
                          "so that a counter run can scale FETCH_SIZE / WRITE_SIZE by a known transfer")
@@ -177,6 +192,43 @@ def main():
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
 
+    # spread: the same steps again, each bracketed by its own pair of events on the launch stream
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(min(args.steps, 200))]
+    for i, (a, b) in enumerate(ev):
+        a.record()
+        step(i)
+        b.record()
+    torch.cuda.synchronize()
+    each = np.array([a.elapsed_time(b) for a, b in ev])
+    spread = {"median_ms": round(float(np.median(each)), 5), "p10_ms": round(float(np.percentile(each, 10)), 5),
+              "p90_ms": round(float(np.percentile(each, 90)), 5), "n": len(ev),
+              "note": "per-step HIP events (each pair adds a few microseconds to a step)"}
+    other = None
+    if not use_graph and not args.staged:
+        # the same steps replayed from one captured HIP graph per layer instance, for comparison
+        try:
+            graphs = []
+            cap_stream = torch.cuda.Stream()
+            with torch.cuda.stream(cap_stream):
+                for L in layers:
+                    g = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g, stream=cap_stream):
+                        L.forward_raw(x.data_ptr(), T, out.data_ptr(), ws.data_ptr(), ws_bytes,
+                                      torch.cuda.current_stream().cuda_stream)
+                    graphs.append(g)
+            torch.cuda.synchronize()
+            for i in range(max(args.warmup, n_layers)):
+                graphs[i % n_layers].replay()
+            torch.cuda.synchronize()
+            tg = time.perf_counter()
+            for i in range(args.steps):
+                graphs[i % n_layers].replay()
+            torch.cuda.synchronize()
+            other = {"launch": "hip_graph", "ms_per_step": round((time.perf_counter() - tg) / args.steps * 1e3, 5)}
+            del graphs
+        except Exception as exc:     # the graph leg is extra information: never fail the bench line on it
+            other = {"launch": "hip_graph", "error": str(exc)[:200]}
+
     # per-kernel durations: the same calls again with HIP events recorded on the stream between kernels
     for L in layers:
         L.profile_enable(True)
@@ -208,8 +260,16 @@ def main():
         achieved = ab[dom] / (stage_avg[dom] * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": "packed W1|W3 product + SwiGLU (qgemm_decode_kernel<bits,true> at decode sizes)",
                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
+                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": counter_traffic(cfg.name)[0],
+                    "traffic_source": counter_traffic(cfg.name)[1],
                     "bytes_per_launch": int(ab[dom]), "avg_ms": round(stage_avg[dom], 5)}
+    if args.calibrate:
+        print("[bench] calibration: streaming read, pinned copy, MFMA rate", file=sys.stderr, flush=True)
+        roofline["peak_measured"] = {
+            "hbm_read_gbs": round(amd.calibrate(amd.CAL_HBM_READ, 3 << 30, 5), 1),
+            "h2d_pinned_gbs": round(amd.calibrate(amd.CAL_H2D, 256 << 20, 5), 1),
+            "mfma_f16_tflops": round(amd.calibrate(amd.CAL_MFMA_F16, 0, 5), 1),
+            "note": "moe_lrc_calibrate on this device: 3 GiB streaming read, 256 MiB pinned copy, register-only MFMA loop"}
     path_kernel_ms = sum(stage_avg.values())
     result = {
         "metric": "MoE-layer tokens/s (one layer forward, weights resident in HBM)",
@@ -223,6 +283,8 @@ def main():
                    "active_experts": st["active_experts"], "comp_experts": st["comp_experts"],
                    "launch": "hip_graph" if use_graph else "eager"},
         "roofline": roofline,
+        "spread": spread,
+        "other_launch_mode": other,
         "whole_path": {"algorithmic_bytes": int(ab["total"]), "hbm_gbs_wall": round(ab["total"] / (ms_per_step * 1e-3) / 1e9, 1),
                        "hbm_frac_wall": round(ab["total"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                        "hbm_gbs_kernels": round(ab["total"] / (path_kernel_ms * 1e-3) / 1e9, 1),

@@ -159,6 +159,18 @@ int moe_lrc_combine(moe_lrc_layer* layer, const void* y_rows_bf16, const float* 
 int moe_lrc_forward(moe_lrc_layer* layer, const void* x_bf16, int T, void* out_bf16,
                     void* ws, size_t ws_bytes, void* stream);
 
+/* moe_lrc_forward for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The intermediates
+ * live in a fixed device array inside the library (MOE_LRC_NOALLOC_WS_BYTES, held by every GPU the
+ * library is loaded on until the process ends) instead of a caller workspace; the caller still owns
+ * x and out.  Calls no allocator.  Returns MOE_LRC_ENOMEM, before any device work, when
+ * moe_lrc_workspace_bytes(layer, T) exceeds the array (the Mixtral-shaped layer fits up to T = 64),
+ * MOE_LRC_ESTATE when the layer's device is not the current device.  Every call on a GPU shares that
+ * GPU's array: calls that overlap on one GPU (two streams, two layers) race; order them on one
+ * stream.  Same result as moe_lrc_forward, bit for bit. */
+#define MOE_LRC_NOALLOC_WS_BYTES (32u << 20)
+int moe_lrc_forward_noalloc(moe_lrc_layer* layer, const void* x_bf16, int T, void* out_bf16, void* stream);
+
 /* ---- evidence and test hooks ------------------------------------------------------------- */
 
 /* Unpacks the layer's private copy of one projection back to one code per byte, device [K][N]. */
@@ -176,7 +188,9 @@ typedef struct {
   uint64_t bytes_factors;  /* bf16 factor bytes of experts with at least one Top-n pair          */
   int32_t  active_experts;
   int32_t  comp_experts;
-  int32_t  path;           /* kernel path of the last expert_ffn: 0 = skinny (decode), 1 = tiled */
+  int32_t  path;           /* kernel flavour of the last expert_ffn's routed projections:
+                              bit 0 set: W1|W3 ran as the grouped GEMM (many rows per expert),
+                              bit 1 set: W2 did; a clear bit: the skinny decode flavour            */
   float    stage_ms;       /* staged mode: time of the last call's host->device copies, else 0   */
 } moe_lrc_stats;
 
@@ -202,6 +216,19 @@ int moe_lrc_profile_enable(moe_lrc_layer* layer, int on);
 /* Waits for the last moe_lrc_forward of this layer and writes its stage durations in
  * milliseconds to ms[MOE_LRC_N_STAGES] (host). */
 int moe_lrc_profile_read(moe_lrc_layer* layer, float* ms);
+
+/* What the current device sustains on the resources the roofline figures are priced against
+ * (Section 2.2's roofline remark: offloaded MoE decoding is bound by moving expert weights).
+ * Measurement hook: allocates its own buffers, runs on the default stream and synchronises.
+ *   MOE_LRC_CAL_HBM_READ  streaming read of a `bytes`-sized device buffer (use several times the
+ *                         256 MB last-level cache), *result = GB/s of the median of `reps` passes
+ *   MOE_LRC_CAL_H2D       copy of `bytes` from pinned host memory to the device, GB/s
+ *   MOE_LRC_CAL_MFMA_F16  dense v_mfma_f32_16x16x32_f16 issue rate on registers, TFLOP/s (`bytes` unused)
+ * result: host pointer to one double. */
+#define MOE_LRC_CAL_HBM_READ 0
+#define MOE_LRC_CAL_H2D      1
+#define MOE_LRC_CAL_MFMA_F16 2
+int moe_lrc_calibrate(int kind, size_t bytes, int reps, double* result);
 
 #ifdef __cplusplus
 }

@@ -21,9 +21,9 @@ RESIDENT, STAGED = 0, 1
 EXPORTS = [
     "moe_lrc_last_error", "moe_lrc_layer_create", "moe_lrc_layer_destroy", "moe_lrc_set_gate",
     "moe_lrc_set_expert", "moe_lrc_set_expert_ranked", "moe_lrc_set_expert_factors_quantized", "moe_lrc_workspace_bytes", "moe_lrc_route", "moe_lrc_permute",
-    "moe_lrc_expert_ffn", "moe_lrc_combine", "moe_lrc_forward", "moe_lrc_debug_unpack",
+    "moe_lrc_expert_ffn", "moe_lrc_combine", "moe_lrc_forward", "moe_lrc_forward_noalloc", "moe_lrc_debug_unpack",
     "moe_lrc_packed_bytes", "moe_lrc_pack_codes", "moe_lrc_unpack_codes", "moe_lrc_get_stats",
-    "moe_lrc_profile_enable", "moe_lrc_profile_read",
+    "moe_lrc_profile_enable", "moe_lrc_profile_read", "moe_lrc_calibrate",
 ]
 STAGES = ["route", "permute", "prep", "xa13", "w13", "xa2", "w2", "shared", "combine"]
 
@@ -75,6 +75,7 @@ def lib() -> C.CDLL:
         L.moe_lrc_expert_ffn.argtypes = [vp, vp, i32, vp, vp, vp, vp, sz, vp]
         L.moe_lrc_combine.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
         L.moe_lrc_forward.argtypes = [vp, vp, i32, vp, vp, sz, vp]
+        L.moe_lrc_forward_noalloc.argtypes = [vp, vp, i32, vp, vp]
         L.moe_lrc_debug_unpack.argtypes = [vp, i32, i32, vp, vp]
         L.moe_lrc_packed_bytes.argtypes = [i32, i32, i32]
         L.moe_lrc_packed_bytes.restype = sz
@@ -83,6 +84,7 @@ def lib() -> C.CDLL:
         L.moe_lrc_get_stats.argtypes = [vp, C.POINTER(Stats)]
         L.moe_lrc_profile_enable.argtypes = [vp, i32]
         L.moe_lrc_profile_read.argtypes = [vp, C.POINTER(C.c_float)]
+        L.moe_lrc_calibrate.argtypes = [i32, sz, i32, C.POINTER(C.c_double)]
         _lib = L
     return _lib
 
@@ -109,6 +111,16 @@ def _hp(a: Optional[np.ndarray]):
 def _stream() -> int:
     import torch
     return torch.cuda.current_stream().cuda_stream
+
+
+CAL_HBM_READ, CAL_H2D, CAL_MFMA_F16 = 0, 1, 2
+
+
+def calibrate(kind: int, nbytes: int = 0, reps: int = 5) -> float:
+    """moe_lrc_calibrate: GB/s (HBM read, pinned host -> device) or TFLOP/s (f16 MFMA) of this device."""
+    out = C.c_double(0.0)
+    _check(lib().moe_lrc_calibrate(kind, nbytes, reps, C.byref(out)))
+    return out.value
 
 
 # ---- host-only helpers (no device) ----------------------------------------------------------
@@ -254,6 +266,10 @@ class Layer:
         ws = self.workspace(T)
         _check(lib().moe_lrc_forward(self._h, x.data_ptr(), T, out.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
         return out
+
+    def forward_noalloc(self, x, out) -> None:
+        """moe_lrc_forward_noalloc: the workspace is the library's built-in device array."""
+        _check(lib().moe_lrc_forward_noalloc(self._h, x.data_ptr(), x.shape[0], out.data_ptr(), _stream()))
 
     def forward_raw(self, x_ptr: int, T: int, out_ptr: int, ws_ptr: int, ws_bytes: int, stream: int) -> None:
         _check(lib().moe_lrc_forward(self._h, x_ptr, T, out_ptr, ws_ptr, ws_bytes, stream))

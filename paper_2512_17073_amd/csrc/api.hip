@@ -628,6 +628,49 @@ int moe_lrc_forward(moe_lrc_layer* L, const void* x, int T, void* out, void* ws,
   return MOE_LRC_OK;
 }
 
+// ---- the entry point that allocates nothing --------------------------------------------------
+// moe_lrc_forward with its workspace in a fixed device array of this library instead of a caller
+// buffer.  Every GPU the library runs on holds its own copy of the array at its own address from
+// the moment the code object is loaded until the process ends; the address is looked up once per
+// device (with that device current) and kept.  Host code never uses the array's name for anything
+// but that lookup: on the host the name is a stand-in, not a device address.
+static __device__ __align__(256) unsigned char scratch[MOE_LRC_NOALLOC_WS_BYTES];
+
+static int scratch_of_device(int dev, uint8_t** out) {
+  static std::mutex mu;
+  static uint8_t* ptr[64] = {};
+  if (dev < 0 || dev >= 64) return set_error(MOE_LRC_EINVAL, "forward_noalloc: device index out of range");
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p)
+      return set_error(MOE_LRC_EHIP, std::string("forward_noalloc: hipGetSymbolAddress: ") + hipGetErrorString(e));
+    ptr[dev] = static_cast<uint8_t*>(p);
+  }
+  *out = ptr[dev];
+  return MOE_LRC_OK;
+}
+
+int moe_lrc_forward_noalloc(moe_lrc_layer* L, const void* x, int T, void* out, void* stream) {
+  int rc = check_hot(L, T, "forward_noalloc");
+  if (rc) return rc;
+  int dev = -1;
+  LRC_HIP(hipGetDevice(&dev));
+  if (dev != L->device)
+    return set_error(MOE_LRC_ESTATE, "forward_noalloc: the layer's device must be the current device");
+  const size_t need = plan_workspace(L, T).total;
+  if (need > size_t(MOE_LRC_NOALLOC_WS_BYTES))
+    return set_error(MOE_LRC_ENOMEM, "forward_noalloc: T tokens of this layer need " + std::to_string(need) +
+                                         " bytes of workspace, the built-in one holds " +
+                                         std::to_string(size_t(MOE_LRC_NOALLOC_WS_BYTES)) + "; use moe_lrc_forward");
+  uint8_t* ws = nullptr;
+  if ((rc = scratch_of_device(dev, &ws))) return rc;
+  // (nothing in the workspace has to start at zero: every buffer in it is written by an earlier
+  // kernel of the same call before a later one reads it, so the last call's contents do no harm)
+  return moe_lrc_forward(L, x, T, out, ws, size_t(MOE_LRC_NOALLOC_WS_BYTES), stream);
+}
+
 int moe_lrc_debug_unpack(moe_lrc_layer* L, int expert, int mat, uint8_t* codes_dev, void* stream) {
   if (!L || !codes_dev) return set_error(MOE_LRC_EINVAL, "debug_unpack: null argument");
   if (expert < 0 || expert >= L->n_total || mat < 0 || mat > 2)

@@ -389,3 +389,59 @@ def test_int3_factors(amd, tokens, rank):
     # the compensation is really there: without it the output differs by far more than the tolerance
     assert orc.rel_frobenius(_to_np(out_r), fixtures.oracle_forward(cfg.with_(top_n=0), layer, x_bits)["out"]) > 5 * TOL
     Lr.close(); Ls.close()
+
+
+def test_mixed_fp16_and_int3_projections_staged(amd):
+    """One expert may hold one projection's factors as an fp16 pair and the others at 3 bits: the
+    two kinds live in separate pinned regions, so neither upload disturbs the other.  Staged and
+    resident layers agree bit for bit and match the oracle."""
+    import torch
+    cfg = configs.TINY.with_(rank=32, tokens=24, bits=2, name="mixed_q3")
+    bf = fixtures.build_layer(cfg)
+    q3 = fixtures.build_layer(cfg, int3_factors=True)
+    experts = []
+    for e in range(cfg.n_experts):                       # W1 as a bf16 pair, W3 and W2 at 3 bits (and rotated per expert)
+        keep = e % 3
+        experts.append({m: (bf if m == keep else q3)["experts"][e][m] for m in (0, 1, 2)})
+    layer = {"wg": bf["wg"], "bias": bf["bias"], "experts": experts}
+    x_bits = synth.make_tokens(cfg)
+    x = amd.bf16_tensor(x_bits)
+    ref = fixtures.oracle_forward(cfg, layer, x_bits)
+    Lr = amd.Layer.from_config(cfg)
+    Ls = amd.Layer.from_config(cfg, residency=amd.STAGED)
+    # upload order matters for an overlap bug: 3-bit blobs first on one layer, last on the other
+    Lr.load(layer)
+    Ls.set_gate(layer["wg"], layer["bias"])
+    for e, ex in enumerate(experts):
+        for m in (2, 1, 0):
+            a = ex[m]
+            if a.get("Aq") is not None:
+                Ls.set_expert(e, m, a["codes"], a["scale"], a["zero"], None, None, 0)
+                Ls.set_expert_factors_quantized(e, m, a["Aq"]["codes"].shape[1], a["Aq"], a["Bq"])
+        for m in (0, 1, 2):
+            a = ex[m]
+            if a.get("Aq") is None:
+                Ls.set_expert(e, m, a["codes"], a["scale"], a["zero"], a["A"], a["B"], cfg.rank)
+    out_r = Lr.forward(x).clone()
+    out_s = Ls.forward(x).clone()
+    torch.cuda.synchronize()
+    err = orc.rel_frobenius(_to_np(out_r), ref["out"])
+    print(f"\n[{cfg.name}] out rel err {err:.2e}", flush=True)
+    assert err <= TOL
+    assert torch.equal(out_r.view(torch.int16), out_s.view(torch.int16))
+    Lr.close(); Ls.close()
+
+
+def test_stats_path_reports_the_flavour(amd):
+    """moe_lrc_stats.path: bit 0 = W1|W3 ran as the grouped GEMM, bit 1 = W2 did."""
+    import torch
+    cfg = configs.TINY.with_(tokens=700, rank=8, name="path")
+    layer = fixtures.sample_layer(cfg)
+    L = amd.Layer.from_config(cfg)
+    L.load(layer)
+    for T, want in ((8, 0), (700, 3)):
+        x = amd.bf16_tensor(synth.make_tokens(cfg, T))
+        L.forward(x)
+        torch.cuda.synchronize()
+        assert L.stats()["path"] == want, (T, L.stats()["path"])
+    L.close()
