@@ -64,8 +64,9 @@ typedef struct {
   int32_t bits;         /* code width of routed experts: 2, 3 or 4                        */
   int32_t shared_bits;  /* code width of shared experts: 2, 3 or 4 (ignored if S == 0)    */
   int32_t group;        /* quantization group along the input dim: 64, 128 or 256         */
-  int32_t rank;         /* compensator rank r >= 0, multiple of 8, <= 256: the rank of
-                           moe_lrc_set_expert, the largest moe_lrc_set_expert_ranked takes  */
+  int32_t rank;         /* compensator rank r >= 0, multiple of 8, <= 1024 (the largest bucket of
+                           Section 3.1): the rank of moe_lrc_set_expert, the largest
+                           moe_lrc_set_expert_ranked takes                                   */
   int32_t renormalize;  /* 0: routing weights are the softmax-over-all scores (Section 2.1)
                            1: divided by their sum over the k selected                    */
   int32_t max_tokens;   /* largest T any call will pass                                   */
@@ -101,7 +102,8 @@ int moe_lrc_set_expert(moe_lrc_layer* layer, int expert, int mat, const uint8_t*
  * the expert matrices by their kurtosis, so ranks differ from matrix to matrix and may be 0).
  * rank: multiple of 8, 0..cfg.rank; A_bf16 [K][rank], B_bf16 [rank][N], both NULL when rank == 0.
  * Only `rank` columns/rows are stored in the pinned pool and moved by the staged mode (the byte
- * counters of moe_lrc_get_stats follow); the kernels run cfg.rank steps on zero padding.
+ * counters of moe_lrc_get_stats follow), and the expert kernels run only the rank steps of the
+ * projection's own rank and read only that many rows of B (a rank-0 projection costs nothing).
  * moe_lrc_set_expert is this call with rank = cfg.rank (0 for shared experts). */
 int moe_lrc_set_expert_ranked(moe_lrc_layer* layer, int expert, int mat, const uint8_t* codes,
                               const uint16_t* scale_f16, const uint16_t* zero_f16,
@@ -155,7 +157,9 @@ int moe_lrc_combine(moe_lrc_layer* layer, const void* y_rows_bf16, const float* 
                     void* out_bf16, void* ws, size_t ws_bytes, void* stream);
 
 /* The whole layer: route -> permute -> (stage) -> expert_ffn -> combine, intermediates in ws.
- * Indices equal those of the four separate calls; `out` equals theirs bit for bit. */
+ * Indices equal those of the four separate calls; `out` equals theirs up to rounding: when the
+ * skinny W2 kernel splits its long K into blocks, the combine adds the fp32 partial sums itself
+ * instead of reading expert rows that were rounded to bf16 first (one rounding fewer). */
 int moe_lrc_forward(moe_lrc_layer* layer, const void* x_bf16, int T, void* out_bf16,
                     void* ws, size_t ws_bytes, void* stream);
 
@@ -216,6 +220,19 @@ int moe_lrc_profile_enable(moe_lrc_layer* layer, int on);
 /* Waits for the last moe_lrc_forward of this layer and writes its stage durations in
  * milliseconds to ms[MOE_LRC_N_STAGES] (host). */
 int moe_lrc_profile_read(moe_lrc_layer* layer, float* ms);
+
+/* Host-only self-check of the index arithmetic of the skinny (decode) FFN kernels; needs no device.
+ * The kernels form every buffer offset and LDS address through a small set of integer functions;
+ * this call walks the same functions for every block, wavefront, lane and step of the two launches
+ * (fused W1|W3, then W2 in `kblocks_w2` K-blocks) that serve one expert with `rows` rows starting at
+ * `first_row` of `total_rows`, the expert's n-tiles shared by `blocks_w13` / `blocks_w2` blocks, and
+ * checks every offset against the size of what it addresses, and that every packed tile and every
+ * rank step of each projection (rank1, rank3, rank2 <= layer_rank <= 1024: Section 3.1 gives every
+ * expert matrix a rank of its own) is read exactly once.  Returns 0, or MOE_LRC_ESHAPE with the first
+ * violation in moe_lrc_last_error(). */
+int moe_lrc_selftest_decode_index(int hidden, int ffn, int bits, int group, int layer_rank, int rank1,
+                                  int rank3, int rank2, int first_row, int rows, int total_rows,
+                                  int blocks_w13, int blocks_w2, int kblocks_w2);
 
 /* What the current device sustains on the resources the roofline figures are priced against
  * (Section 2.2's roofline remark: offloaded MoE decoding is bound by moving expert weights).

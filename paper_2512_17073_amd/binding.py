@@ -24,6 +24,7 @@ EXPORTS = [
     "moe_lrc_expert_ffn", "moe_lrc_combine", "moe_lrc_forward", "moe_lrc_forward_noalloc", "moe_lrc_debug_unpack",
     "moe_lrc_packed_bytes", "moe_lrc_pack_codes", "moe_lrc_unpack_codes", "moe_lrc_get_stats",
     "moe_lrc_profile_enable", "moe_lrc_profile_read", "moe_lrc_calibrate",
+    "moe_lrc_selftest_decode_index",
 ]
 STAGES = ["route", "permute", "prep", "xa13", "w13", "xa2", "w2", "shared", "combine"]
 
@@ -85,6 +86,7 @@ def lib() -> C.CDLL:
         L.moe_lrc_profile_enable.argtypes = [vp, i32]
         L.moe_lrc_profile_read.argtypes = [vp, C.POINTER(C.c_float)]
         L.moe_lrc_calibrate.argtypes = [i32, sz, i32, C.POINTER(C.c_double)]
+        L.moe_lrc_selftest_decode_index.argtypes = [i32] * 14
         _lib = L
     return _lib
 
@@ -121,6 +123,13 @@ def calibrate(kind: int, nbytes: int = 0, reps: int = 5) -> float:
     out = C.c_double(0.0)
     _check(lib().moe_lrc_calibrate(kind, nbytes, reps, C.byref(out)))
     return out.value
+
+
+def selftest_decode_index(hidden, ffn, bits, group, layer_rank, ranks, first_row, rows, total_rows,
+                          blocks_w13, blocks_w2, kblocks_w2) -> None:
+    """moe_lrc_selftest_decode_index (host only): raises MoeLrcError with the first violation."""
+    _check(lib().moe_lrc_selftest_decode_index(hidden, ffn, bits, group, layer_rank, ranks[0], ranks[1], ranks[2],
+                                               first_row, rows, total_rows, blocks_w13, blocks_w2, kblocks_w2))
 
 
 # ---- host-only helpers (no device) ----------------------------------------------------------

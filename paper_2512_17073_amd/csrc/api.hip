@@ -57,7 +57,7 @@ static int check_config(const moe_lrc_config& c) {
   if (c.top_n < 0 || c.top_n > c.top_k) return bad("top_n must be in 0..top_k");
   if (c.bits < 2 || c.bits > 4) return bad("bits must be 2, 3 or 4");
   if (c.n_shared > 0 && (c.shared_bits < 2 || c.shared_bits > 4)) return bad("shared_bits must be 2, 3 or 4");
-  if (c.rank < 0 || c.rank > 256 || c.rank % 8) return bad("rank must be a multiple of 8 in 0..256");
+  if (c.rank < 0 || c.rank > 1024 || c.rank % 8) return bad("rank must be a multiple of 8 in 0..1024");
   if (c.renormalize != 0 && c.renormalize != 1) return bad("renormalize must be 0 or 1");
   if (c.max_tokens < 1 || (long long)c.max_tokens * c.top_k > (1 << 24)) return bad("max_tokens out of range");
   if (c.residency != MOE_LRC_RESIDENT && c.residency != MOE_LRC_STAGED) return bad("residency must be 0 or 1");
@@ -91,7 +91,7 @@ Workspace plan_workspace(const moe_lrc_layer* L, int T) {
   w.sh_y_part = take(size_t(kMaxKBlocks) * c.n_shared * T * c.hidden * 4);   // (shared experts run beside the routed ones)
   w.sh_h = take(c.n_shared ? (size_t(c.n_shared) * T + kActPadRows) * Fp * 2 : 0);
   w.sh_y = take(size_t(c.n_shared) * T * c.hidden * 2);
-  w.plan = take(size_t(plan_blocks(c.n_experts, int(P), c.ffn / 16, L->n_cu) + plan_blocks(c.n_experts, int(P), c.hidden / 16, L->n_cu)) * 16);
+  w.plan = take(size_t(plan_blocks(c.n_experts, int(P), c.ffn / 16, L->n_cu) + plan_blocks(c.n_experts, int(P), c.hidden / 16, L->n_cu)) * kPlanEntryInts * 4);
   w.total = o;
   return w;
 }
@@ -218,7 +218,7 @@ static int stage_selected(moe_lrc_layer* L, hipStream_t stream) {
 
 static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t* offsets,
                           const int32_t* row_pair, void* y_rows, uint8_t* ws, hipStream_t stream,
-                          bool mark = false) {
+                          bool mark = false, bool keep_partials = false, int* kblocks_out = nullptr) {
   const moe_lrc_config& c = L->cfg;
   const Workspace w = plan_workspace(L, T);
   _Float16* xh = reinterpret_cast<_Float16*>(ws + w.xh);
@@ -236,10 +236,16 @@ static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t*
   a.plan = reinterpret_cast<int32_t*>(ws + w.plan);
   a.y_rows = y_rows; a.ksplit13 = L->ksplit13; a.ksplit2 = L->ksplit2; a.total_rows = T * c.top_k;
   a.n_cu = L->n_cu;
+  const int path = expert_ffn_path(a);
+  // the combine can add the K-block partial sums of a decode-flavour W2 itself
+  const int kblocks = (path & 2) ? 1 : decode_w2_kblocks(a);
+  a.keep_partials = keep_partials && kblocks > 1;
+  if (kblocks_out) *kblocks_out = a.keep_partials ? kblocks : 1;
   // the launch that converts the activations also makes the block tables of the decode launches
+  // and, for the decode flavour of the fused projection, (x A1 | x A3)
   PlanSpec plans[2];
   expert_ffn_plan_specs(a, plans[0], plans[1]);
-  LRC_HIP(launch_convert_x(L, x, T, xh, P + kActPadRows, offsets, row_pair, L->d_stat, plans, stream));
+  LRC_HIP(launch_convert_x(L, x, T, xh, P + kActPadRows, offsets, row_pair, L->d_stat, plans, (path & 1) ? nullptr : &a, stream));
   L->stats_valid = false;
   L->stats.stage_ms = 0.f;
   if (c.residency == MOE_LRC_STAGED) {
@@ -249,7 +255,7 @@ static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t*
   if (mark) LRC_HIP(hipEventRecord(L->marks[MOE_LRC_STAGE_XA13], stream));
   a.marks = mark ? &L->marks[MOE_LRC_STAGE_W13] : nullptr;
   LRC_HIP(launch_expert_ffn(a, stream));
-  L->stats.path = expert_ffn_path(a);
+  L->stats.path = path;
   return MOE_LRC_OK;
 }
 
@@ -257,7 +263,7 @@ static int run_shared(moe_lrc_layer* L, const void* x, int T, uint8_t* ws, hipSt
   const moe_lrc_config& c = L->cfg;
   const Workspace w = plan_workspace(L, T);
   _Float16* xh = reinterpret_cast<_Float16*>(ws + w.xh_sh);
-  LRC_HIP(launch_convert_x(L, x, T, xh, T + kActPadRows, nullptr, nullptr, nullptr, nullptr, stream));
+  LRC_HIP(launch_convert_x(L, x, T, xh, T + kActPadRows, nullptr, nullptr, nullptr, nullptr, nullptr, stream));
   FfnArgs a{};
   a.desc = L->d_desc + c.n_experts; a.n_exp = c.n_shared; a.bits = c.shared_bits; a.group = c.group;
   a.rank = 0; a.rpad = 0; a.H = c.hidden; a.F = c.ffn; a.top_k = c.top_k; a.top_n = 0; a.T = T;
@@ -460,6 +466,7 @@ int moe_lrc_set_expert_ranked(moe_lrc_layer* L, int expert, int mat, const uint8
   }
   L->mat_rank[expert * 3 + mat] = rank;
   L->mat_q3[expert * 3 + mat] = 0;
+  L->h_desc[expert].rank[mat] = rank;
   L->h_desc[expert].lambda[mat] = lambda;
   L->h_desc[expert].inv_lambda[mat] = 1.0f / lambda;
   LRC_HIP(hipMemcpy(L->d_desc + expert, &L->h_desc[expert], sizeof(ExpertDesc), hipMemcpyHostToDevice));
@@ -520,6 +527,8 @@ int moe_lrc_set_expert_factors_quantized(moe_lrc_layer* L, int expert, int mat, 
   if (m.bf_bytes > fm.bf_bytes) LRC_HIP(hipMemset(L->d_f + boff + fm.bf_bytes, 0, m.bf_bytes - fm.bf_bytes));
   L->mat_rank[expert * 3 + mat] = rank;
   L->mat_q3[expert * 3 + mat] = 1;
+  L->h_desc[expert].rank[mat] = rank;
+  LRC_HIP(hipMemcpy(L->d_desc + expert, &L->h_desc[expert], sizeof(ExpertDesc), hipMemcpyHostToDevice));
   return MOE_LRC_OK;
 }
 
@@ -577,7 +586,7 @@ int moe_lrc_combine(moe_lrc_layer* L, const void* y_rows, const float* w, const 
     if ((rc = run_shared(L, x, T, (uint8_t*)ws, (hipStream_t)stream))) return rc;
     y_shared = (uint8_t*)ws + plan_workspace(L, T).sh_y;
   }
-  LRC_HIP(launch_combine(L, y_rows, w, pair_row, y_shared, T, out, (hipStream_t)stream));
+  LRC_HIP(launch_combine(L, y_rows, nullptr, 1, w, pair_row, y_shared, T, out, (hipStream_t)stream));
   return MOE_LRC_OK;
 }
 
@@ -616,11 +625,14 @@ int moe_lrc_forward(moe_lrc_layer* L, const void* x, int T, void* out, void* ws,
     if ((rc = run_shared(L, x, T, b, L->side))) return rc;
     LRC_HIP(hipEventRecord(L->ev_join, L->side));
   }
-  if ((rc = run_expert_ffn(L, x, T, offsets, row_pair, b + w.y_rows, b, s, mk))) return rc;
+  // (the K-block partial sums of a decode-flavour W2 go to the combine as they are: no pass that
+  // adds them into bf16 rows first)
+  int kblocks = 1;
+  if ((rc = run_expert_ffn(L, x, T, offsets, row_pair, b + w.y_rows, b, s, mk, true, &kblocks))) return rc;
   if (fork) LRC_HIP(hipStreamWaitEvent(s, L->ev_join, 0));
   else if (L->cfg.n_shared > 0 && (rc = run_shared(L, x, T, b, s))) return rc;
   if (mk) LRC_HIP(hipEventRecord(L->marks[MOE_LRC_STAGE_COMBINE], s));
-  LRC_HIP(launch_combine(L, b + w.y_rows, tw, pair_row, y_shared, T, out, s));
+  LRC_HIP(launch_combine(L, b + w.y_rows, kblocks > 1 ? (const float*)(b + w.y_part) : nullptr, kblocks, tw, pair_row, y_shared, T, out, s));
   if (mk) {
     LRC_HIP(hipEventRecord(L->marks[MOE_LRC_N_STAGES], s));
     L->profile_valid = true;

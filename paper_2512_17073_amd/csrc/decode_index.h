@@ -1,0 +1,117 @@
+// Index arithmetic of the decode-flavour FFN kernels (ffn_decode.hip), as plain integer functions
+// that compile for the device and for the host.  The kernels call them; moe_lrc_selftest_decode_index
+// (host only) sweeps shapes, ranks and block shares through the same functions and checks every
+// offset against the size of the buffer resource or LDS region it addresses.
+#pragma once
+#include <stdint.h>
+
+#include "layout.h"
+
+namespace lrc {
+namespace dec {
+
+constexpr int kWaves = 16;            // wavefronts of a block
+constexpr int kLdsUnits = 8192;       // 16-byte units of staged activations (128 KB)
+constexpr int kSpareUnits = 2048;     // 16-byte units behind them (32 KB): (in A) fragments of small ranks
+constexpr int kRing = 2;              // ring slots of a wavefront (each holds one k-step of two streams)
+constexpr int kStreams = 2;           // streams of a slot: (W1, W3) tiles of one n-tile, or two n-tiles of W2
+
+// A block's n-tiles: block b of the G that share an expert owns tiles [t0, t1).
+LRC_HD void block_tiles(int b, int G, int NT, int& t0, int& t1) {
+  t0 = (int)((long long)b * NT / G);
+  t1 = (int)((long long)(b + 1) * NT / G);
+}
+
+// Work units of a block: an n-tile of both projections (DUAL) or a pair of adjacent n-tiles (W2).
+LRC_HD int block_units(int nt_b, bool dual) { return dual ? nt_b : (nt_b + 1) / 2; }
+// unit slots a wavefront visits one after the other
+LRC_HD int unit_slots(bool dual) { return dual ? 2 : 1; }
+
+// Wavefronts that share one unit, each taking every kw-th k-step (power of two, 1..16).
+LRC_HD int waves_per_unit(int units) {
+  int kw = 1;
+  while (kw < kWaves && units * kw * 2 <= kWaves) kw *= 2;
+  return kw;
+}
+
+// n-tile of stream m of unit u (block-relative unit index): DUAL: tile t0 + u for both streams;
+// W2: tiles t0 + 2u and t0 + 2u + 1.
+LRC_HD int stream_tile(int t0, int u, int m, bool dual) { return dual ? t0 + u : t0 + 2 * u + m; }
+
+// Steps of a wavefront, in order: [phase][unit slot][own k-step] (each segment padded to a multiple
+// of the ring depth), then [own rank step][unit slot] (padded likewise).
+struct StepPlan {
+  int KP;        // k-steps per phase (16 with one row tile, 8 with two)
+  int n_ph;      // phases of this K-block
+  int SP;        // padded own k-steps per (unit slot, phase) segment
+  int n_reg;     // regular steps in all
+  int LSP;       // padded rank steps in all
+};
+LRC_HD StepPlan step_plan(int KSl, int mt, int kw, int LS, bool dual) {
+  StepPlan p;
+  p.KP = (kLdsUnits / 512) / mt;
+  p.n_ph = (KSl + p.KP - 1) / p.KP;
+  const int spw = (p.KP + kw - 1) / kw;
+  p.SP = (spw + kRing - 1) / kRing * kRing;
+  p.n_reg = p.n_ph * unit_slots(dual) * p.SP;
+  p.LSP = (unit_slots(dual) * ((LS + kw - 1) / kw) + kRing - 1) / kRing * kRing;
+  return p;
+}
+
+// What step n of a wavefront (group grp of `groups`, k-share kwi of kw) reads.
+struct StepRef {
+  bool reg;      // a k-step of packed codes (else a rank step, or nothing)
+  bool lr;       // a rank step of the B factor
+  int ts;        // unit slot
+  int unit;      // block-relative unit
+  int ks;        // absolute k-step (reg)
+  int kl;        // k-step within the phase (reg)
+  int st;        // rank step (lr)
+};
+LRC_HD StepRef step_ref(int n, const StepPlan& p, int grp, int groups, int kwi, int kw, int units, int ks_lo, int KSl,
+                        int LS, bool dual) {
+  StepRef r{};
+  const int TS = unit_slots(dual);
+  if (n < p.n_reg) {
+    const int seg = n / p.SP, si = n - seg * p.SP, ph = seg / TS;
+    r.ts = seg - ph * TS;
+    r.unit = grp + r.ts * groups;
+    r.kl = si * kw + kwi;
+    r.ks = ks_lo + ph * p.KP + r.kl;
+    r.reg = r.unit < units && r.kl < p.KP && ph * p.KP + r.kl < KSl;
+  } else {
+    const int l = n - p.n_reg;
+    r.ts = l % TS;
+    r.unit = grp + r.ts * groups;
+    r.st = (l / TS) * kw + kwi;
+    r.lr = l < p.LSP && r.unit < units && r.st < LS;
+  }
+  return r;
+}
+
+// Byte offsets of a lane's loads of one stream of a step (the hardware range-checks offset + size
+// against the resource; a step that reads nothing gets an offset at the end of every resource).
+struct LaneOffsets { uint32_t code0, code1, meta, bf; };
+LRC_HD LaneOffsets lane_offsets(const StepRef& r, int tile, bool tile_ok, int lane, int bits, int NT, int group_shift,
+                                uint32_t code_bytes, uint32_t meta_bytes, uint32_t bf_bytes_max) {
+  const uint32_t tdw = kWave * 2 * bits, q = lane >> 4, c = lane & 15;
+  const uint32_t gps = kTileK >> group_shift;
+  const uint32_t meta_lane = ((q * kLaneK) >> group_shift) * (uint32_t(NT) * kTileN * 4) + c * 4;
+  LaneOffsets o;
+  const bool ok = r.reg && tile_ok, lr = r.lr && tile_ok;
+  const uint32_t past = code_bytes > bf_bytes_max ? code_bytes : bf_bytes_max;
+  const uint32_t tile_base = (uint32_t(r.ks) * NT + tile) * (tdw * 4);
+  o.code0 = (ok ? tile_base : past) + lane * 16;
+  o.code1 = (ok ? tile_base : code_bytes) + 1024 + lane * (bits == 3 ? 8 : 16);
+  o.meta = (ok ? (uint32_t(r.ks) * gps * NT + tile) * (kTileN * 4) : meta_bytes) + meta_lane;
+  o.bf = (lr ? (uint32_t(r.st) * NT + tile) * 1024 : past) + lane * 16;
+  return o;
+}
+
+// LDS unit of staged activation fragment (row tile mt, k-step kl of the phase, sub-step s).
+LRC_HD int act_frag_unit(int mt, int kl, int s, int KP) { return ((mt * KP + kl) * 8 + s) * 64; }
+// LDS unit (relative to the fragment region) of (in A) fragment (stream m, rank step st, row tile mt).
+LRC_HD int p_frag_unit(int m, int st, int mt, int LS, int MT) { return ((m * LS + st) * MT + mt) * 64; }
+
+}  // namespace dec
+}  // namespace lrc

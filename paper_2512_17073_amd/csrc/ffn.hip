@@ -118,18 +118,22 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
   const int code_bytes = a.KS * a.NT * tdw * 4, meta_bytes = a.G * a.NT * kTileN * 4;
   const bool lowrank = a.rank > 0 && __builtin_amdgcn_readfirstlane(d.has_factors) != 0 && a.row_pair != nullptr &&
                        __builtin_amdgcn_readfirstlane(a.comp_rows[e]) > 0;
-  const int LS = lowrank ? a.ls : 0;
+  // every projection has the rank of its own factor pair (Section 3.1): the expert runs the rank
+  // steps of the larger one, a resource of the size its rank fills makes the other read zeros
+  int LSm[NM];
   const int bf_bytes = a.NT * a.ls * 1024;
   __amdgpu_buffer_rsrc_t code_rs[NM], meta_rs[NM], bf_rs[NM];
   float lam[NM];
 #pragma unroll
   for (int m = 0; m < NM; ++m) {
     const int mat = DUAL ? m : 2;
+    LSm[m] = lowrank ? (min(__builtin_amdgcn_readfirstlane(d.rank[mat]), a.rank) + 31) / 32 : 0;
     code_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(uniform_ptr(d.codes[mat])), 0, code_bytes, 0x00020000);
     meta_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(uniform_ptr(d.meta[mat])), 0, meta_bytes, 0x00020000);
-    bf_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<_Float16*>(uniform_ptr(d.bf[mat])), 0, lowrank ? bf_bytes : 0, 0x00020000);
+    bf_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<_Float16*>(uniform_ptr(d.bf[mat])), 0, a.NT * LSm[m] * 1024, 0x00020000);
     lam[m] = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(d.inv_lambda[mat])));
   }
+  const int LS = max(LSm[0], LSm[NM - 1]);
   const int gps = kTileK >> a.group_shift;               // groups per k-step
   const int meta_lane = ((q * kLaneK) >> a.group_shift) * (a.NT * kTileN * 4) + c * 4;
 
@@ -295,24 +299,30 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
   }
 
   // ---- rank steps.  (in A) of the chunk's rows, fp16 row-major in global memory (xa_tile_kernel
-  //      has scaled it and zeroed the rows without the term), is copied into LDS as MFMA fragments:
-  //      unit ((m * LS + st) * 8 + mt) * 64 + lane = columns 32 st + 8 q .. + 7 of row 16 mt + lane % 16.
-  if (LS > 0) {
-    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");   // (the last copy issued serves no step)
+  //      has scaled it and zeroed the rows without the term), is copied into LDS as MFMA fragments,
+  //      kRankChunk rank steps at a time (all of them for ranks up to 256): unit
+  //      ((m * kRankChunk + st - c0) * 8 + mt) * 64 + lane = columns 32 st + 8 q .. + 7 of row 16 mt + lane % 16.
+  constexpr int kRankChunk = 2 * kStepUnits / (NM * kTMT * 64);     // 8 (fused) or 16 rank steps fill the 128 KB
+  for (int c0 = 0; c0 < LS; c0 += kRankChunk) {
+    const int c1 = min(LS, c0 + kRankChunk);
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");   // (everyone is done with what LDS held)
     const _Float16* P = reinterpret_cast<const _Float16*>(a.p);
     const int pitch = NM * a.ls * 32;                                // halves per row
-    for (int f = wave; f < NM * LS * kTMT; f += kTileWaves) {
-      const int mt = f % kTMT, g = f / kTMT, st = g % LS, m = g / LS;
+    for (int f = wave; f < NM * (c1 - c0) * kTMT; f += kTileWaves) {
+      const int mt = f % kTMT, g = f / kTMT, sl = g % (c1 - c0), m = g / (c1 - c0);
       const int row = min(r0 + r + 16 * mt + c, a.total_rows - 1);
-      const _Float16* src = P + size_t(row) * pitch + m * a.ls * 32 + 32 * st + 8 * q;
+      const _Float16* src = P + size_t(row) * pitch + m * a.ls * 32 + 32 * (c0 + sl) + 8 * q;
       __builtin_amdgcn_global_load_lds(
           reinterpret_cast<const __attribute__((address_space(1))) void*>(reinterpret_cast<uintptr_t>(src)),
-          reinterpret_cast<__attribute__((address_space(3))) void*>(reinterpret_cast<uintptr_t>(xs + (size_t(g) * kTMT + mt) * 64)), 16, 0, 0);
+          reinterpret_cast<__attribute__((address_space(3))) void*>(reinterpret_cast<uintptr_t>(xs + ((size_t(m) * kRankChunk + sl) * kTMT + mt) * 64)), 16, 0, 0);
     }
+    // (the ring slots are refilled below, after this wait: only the copies just issued and the two
+    // slots requested before them are outstanding)
     asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
     auto rank_step = [&](const Slot2<BITS, NM, kNTW>& cur, int st) {
 #pragma unroll
       for (int m = 0; m < NM; ++m) {
+        if (st >= LSm[m]) continue;
         half8_t bfrag[kNTW];
 #pragma unroll
         for (int t = 0; t < kNTW; ++t)
@@ -320,20 +330,19 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
 #pragma unroll
         for (int mt = 0; mt < kTMT; ++mt)
           if (mt < mt_n) {
-            const half8_t pf = __builtin_bit_cast(half8_t, xs[((size_t(m) * LS + st) * kTMT + mt) * 64 + lane]);
+            const half8_t pf = __builtin_bit_cast(half8_t, xs[((size_t(m) * kRankChunk + st - c0) * kTMT + mt) * 64 + lane]);
 #pragma unroll
             for (int t = 0; t < kNTW; ++t)
               acc[t][mt][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(bfrag[t], pf, acc[t][mt][m], 0, 0, 0);
           }
       }
     };
-    // the slot of step KS + st is ring[(KS + st) % 2]
-    for (int st0 = 0; st0 < LS + 1; st0 += 2) {
+    // the slot of step KS + st is ring[(KS + st) % 2]: walk the chunk's steps in aligned pairs
+    for (int s0 = (steps + c0) & ~1; s0 < steps + c1; s0 += 2) {
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        // trip element i handles the step whose slot is ring[i]
-        const int step = ((steps + st0) & ~1) + i;
-        if (step >= steps && step < steps + LS) {
+        const int step = s0 + i;
+        if (step >= steps + c0 && step < steps + c1) {
           rank_step(ring[i], step - steps);
           fetch(step + 2, ring[i]);
         }
@@ -384,7 +393,7 @@ template <bool DUAL, int NT>
 __global__ __launch_bounds__(64 * kTileWaves, 2) void xa_tile_kernel(KArgs a) {
   extern __shared__ uint4 xs[];
   constexpr int NM = DUAL ? 2 : 1;
-  constexpr int kMaxT = NT;                              // factor tiles per wavefront (2 or 4: rank <= 256)
+  constexpr int kMaxT = NT;                              // factor tiles per wavefront (2 or 4); grid.z: groups of 8 * NT tiles
   constexpr bool kAhead = NT <= 2;                       // registers for the factor units of a whole k-step ahead
   Chunk ch;
   if (!find_chunk(a, blockIdx.y, ch)) return;
@@ -411,7 +420,7 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void xa_tile_kernel(KArgs a) {
   int nmine = 0;
 #pragma unroll
   for (int t = 0; t < kMaxT; ++t) {
-    const int tile = wave + t * kTileWaves;
+    const int tile = blockIdx.z * (kTileWaves * kMaxT) + wave + t * kTileWaves;
     af[t] = nullptr;
     if (tile < tiles) {
       const int m = tile / rt, tl = tile - m * rt;
@@ -478,7 +487,7 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void xa_tile_kernel(KArgs a) {
   float* part = a.partial + size_t(blockIdx.x) * a.total_rows * pitch;
 #pragma unroll
   for (int t = 0; t < kMaxT; ++t) {
-    const int tile = wave + t * kTileWaves;
+    const int tile = blockIdx.z * (kTileWaves * kMaxT) + wave + t * kTileWaves;
     if (tile >= tiles) continue;
     const int m = tile / rt, tl = tile - m * rt;
     const float lam = d.lambda[DUAL ? m : 2];
@@ -531,8 +540,9 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
     const int kblocks = (steps + per_kb - 1) / per_kb;      // no K-block without a k-step
     a.p = buf;
     a.partial = buf + (size_t(f.total_rows) * pitch / 2 + 63) / 64 * 64;
+    // (more than 32 factor tiles, i.e. ranks above 256: further groups of 32 tiles in grid.z)
     if (per_wave <= 2) hipLaunchKernelGGL(k2, dim3(kblocks, items), dim3(64 * kTileWaves), lds, s, a);
-    else hipLaunchKernelGGL(k4, dim3(kblocks, items), dim3(64 * kTileWaves), lds, s, a);
+    else hipLaunchKernelGGL(k4, dim3(kblocks, items, (per_wave + 3) / 4), dim3(64 * kTileWaves), lds, s, a);
     const size_t groups = size_t(f.total_rows) * pitch / 4;
     hipLaunchKernelGGL(xa_finish_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, s, a.partial, kblocks,
                        f.total_rows, pitch, a.ls * 32, a.rpad, f.row_pair, f.top_k, f.top_n, reinterpret_cast<_Float16*>(buf));

@@ -34,15 +34,15 @@ struct KArgs {
   const _Float16* in;        // activations in operand order (act_unit), in_rt rows: gathered x, or h
   void* out;                 // DUAL: h in operand order (out_rt rows); else y_rows [rows][N] bf16
   int in_rt, out_rt;         // row counts (incl. padding) of the operand-order buffers
-  const float* p;            // split-K partials of (in A): [ksplit][total_rows][PW]
-  int K, N, KS, G, NT, group_shift, top_k, top_n, T, rank, rpad, ksplit, total_rows;
+  const float* p;            // (in A): fp16 [total_rows][projections * ls * 32], scaled by the projections' pre-scales,
+                             // zero for rows without the rank-r term (written by the (in A) kernels)
+  int K, N, KS, G, NT, group_shift, top_k, top_n, T, rank, rpad, total_rows;
   int ls;                    // rank steps of 32 of the B factor: ceil(rank / 32)
   int n_exp;                 // experts of this launch (many-rows flavour: the grid enumerates row chunks)
-  int kw;                    // wavefronts that share one n-tile, each taking every kw-th k-step
   int kb_steps;              // decode flavour: k-steps per K-block (grid.z blocks split K; KS if one)
   float* partial;            // decode flavour, more than one K-block: fp32 partial outputs [kb][rows][N]
-  const int32_t* plan;       // decode flavour: null (grid = blocks per expert x experts), or for block
-                             // blockIdx.x the ints (expert or -1, block of the expert, blocks of the expert, -)
+  const int32_t* plan;       // decode flavour: null (grid = blocks per expert x experts), or the block table
+                             // (PlanEntry per block, plan.h)
 };
 
 __device__ inline uint32_t f32x2_to_bf16x2(float a, float b) {
@@ -57,7 +57,7 @@ __device__ inline uint32_t f32x2_to_bf16x2(float a, float b) {
 // unit at index ((ks*8 + s)*4 + q) * rt + R, where k8 = ks*32 + q*8 + s.  For a fixed (ks, s, q) the
 // rows are contiguous, so the 16 rows x 4 q of one MFMA B-operand fragment are four 256-byte runs
 // and staging a fragment into LDS is a lane-linear copy.
-__device__ inline size_t act_unit(int k8, int R, int rt) {
+__host__ __device__ inline size_t act_unit(int k8, int R, int rt) {
   const int ks = k8 >> 5, q = (k8 >> 3) & 3, s = k8 & 7;
   return size_t((ks * 8 + s) * 4 + q) * rt + R;
 }

@@ -19,8 +19,8 @@ struct ExpertDesc {
   const _Float16* bf[3];      // packed B factor
   float lambda[3];            // power-of-two pre-scale folded into the metadata
   float inv_lambda[3];
+  int32_t rank[3];            // rank of each projection's factor pair (0: none); a prefix of the factor sections
   int32_t has_factors;
-  int32_t pad_;
 };
 
 // Byte offsets of the sections of an expert's two blobs (weights: codes+meta; factors: A+B).
@@ -86,9 +86,12 @@ hipError_t launch_permute(const moe_lrc_layer* L, const int32_t* idx, int T, int
 struct PlanSpec;   // plan.h
 // fp16 copy of the activations in operand order: one row per routed pair (row_pair given) or one
 // per token (row_pair null); with `stat`, one more block counts the per-expert rows
+struct FfnArgs;
+// xa13: the arguments of the expert-FFN launches that follow, when their fused W1|W3 projection takes
+// the decode flavour and wants (x A1 | x A3) made by further blocks of this launch; else null
 hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _Float16* xg, int rt,
                             const int32_t* offsets, const int32_t* row_pair, int32_t* stat,
-                            const PlanSpec* plans /* two, or null */, hipStream_t s);
+                            const PlanSpec* plans /* two, or null */, const FfnArgs* xa13, hipStream_t s);
 constexpr int kMaxKBlocks = 8;    // most K-blocks the decode W2 kernel splits into
 // blocks (per K-block) of a decode launch that shares its blocks out by a table: `target` (the
 // device's CUs over the K-blocks), or enough for ceil(NT / 32) blocks per expert that can be active
@@ -114,13 +117,17 @@ struct FfnArgs {
   float* p2;                  // [ksplit2][rows][rpad]
   void* y_rows;               // [rows][H] bf16
   float* y_part;              // fp32 partial outputs of the W2 K-blocks (decode flavour), or null
-  int32_t* plan;              // decode flavour, many experts: block -> (expert, block of the expert, blocks of
-                              // the expert) tables of the two projections, kPlanBlocks(...) entries of 4 ints each
+  int32_t* plan;              // decode flavour, routed experts: the block tables (plan.h) of the two projections
+  int keep_partials;          // decode flavour, W2 split into K-blocks: leave the fp32 partial sums in y_part for
+                              // the combine instead of adding them into y_rows
   int ksplit13, ksplit2, total_rows;
   int n_cu;                   // compute units of the device (the launches size their grids to fill them)
   hipEvent_t* marks;          // null, or 4 events recorded after xa13, w13, xa2, w2
 };
 hipError_t launch_expert_ffn(const FfnArgs& a, hipStream_t s);
+// K-blocks the decode flavour splits W2 into (1: none); the W2 output of a launch is y_rows, or with
+// keep_partials that many fp32 partial sums [kb][rows][H] in y_part
+int decode_w2_kblocks(const FfnArgs& a);
 // bit 0: the fused W1|W3 projection takes the grouped GEMM (else the decode flavour), bit 1: W2 does
 int expert_ffn_path(const FfnArgs& a);
 // once per device, before the first launch: lets the FFN kernels use the whole LDS of a CU
@@ -128,7 +135,9 @@ hipError_t ffn_init_device();
 hipError_t decode_init_device();
 // the block tables (plan.h) that launch_expert_ffn(a) will read: to be made by launch_convert_x
 void expert_ffn_plan_specs(const FfnArgs& a, PlanSpec& p13, PlanSpec& p2);
-hipError_t launch_combine(const moe_lrc_layer* L, const void* y_rows, const float* w,
+// y_part != null: the expert outputs are the sums over `kblocks` fp32 partial sums [kb][T*k][H]
+// (the decode flavour's W2 K-blocks) instead of the bf16 rows y_rows
+hipError_t launch_combine(const moe_lrc_layer* L, const void* y_rows, const float* y_part, int kblocks, const float* w,
                           const int32_t* pair_row, const void* y_shared, int T, void* out,
                           hipStream_t s);
 hipError_t launch_debug_unpack(const uint32_t* packed, const MatLayout& m, uint8_t* codes_dev,

@@ -5,6 +5,7 @@
 #include "internal.h"
 #include "plan.h"
 #include "unpack.h"
+#include "xa_rows.h"
 
 namespace lrc {
 
@@ -20,8 +21,11 @@ __device__ inline uint32_t pack_bf16(float a, float b) {
 }
 
 // out[t] = sum_j w[t][j] * y_rows[pair_row[t*k+j]] + sum_s y_shared[s*T+t]; slots in order j = 0..k-1,
-// then the shared experts: a fixed order, so two runs give identical bits.
+// then the shared experts: a fixed order, so two runs give identical bits.  With y_part, row R's
+// output is the sum over the K-blocks kb = 0.. of y_part[kb][R] (fp32, in that order) instead of
+// the bf16 row y_rows[R].
 __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict__ y_rows,
+                                                      const float* __restrict__ y_part, int kblocks, size_t kb_stride,
                                                       const float* __restrict__ w,
                                                       const int32_t* __restrict__ pair_row,
                                                       const uint16_t* __restrict__ y_shared, int T, int H,
@@ -32,6 +36,19 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict
     for (int j = 0; j < top_k; ++j) {
       const int row = pair_row[t * top_k + j];
       const float wj = w[t * top_k + j];
+      if (y_part != nullptr) {
+        const float4* src = reinterpret_cast<const float4*>(y_part + size_t(row) * H) + 2 * ch;
+        float4 lo = src[0], hi = src[1];
+        for (int kb = 1; kb < kblocks; ++kb) {
+          const float4* s2 = reinterpret_cast<const float4*>(y_part + kb * kb_stride + size_t(row) * H) + 2 * ch;
+          const float4 a = s2[0], b = s2[1];
+          lo.x += a.x; lo.y += a.y; lo.z += a.z; lo.w += a.w;
+          hi.x += b.x; hi.y += b.y; hi.z += b.z; hi.w += b.w;
+        }
+        acc[0] = fmaf(wj, lo.x, acc[0]); acc[1] = fmaf(wj, lo.y, acc[1]); acc[2] = fmaf(wj, lo.z, acc[2]); acc[3] = fmaf(wj, lo.w, acc[3]);
+        acc[4] = fmaf(wj, hi.x, acc[4]); acc[5] = fmaf(wj, hi.y, acc[5]); acc[6] = fmaf(wj, hi.z, acc[6]); acc[7] = fmaf(wj, hi.w, acc[7]);
+        continue;
+      }
       const uint4 v = reinterpret_cast<const uint4*>(y_rows + size_t(row) * H)[ch];
       const uint32_t a[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -62,14 +79,24 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict
 // contiguous bytes of each of its rows and writes runs of 256 bytes (sixteen rows of one unit).
 // The blocks after those count, one wavefront per expert, the routed rows and the rows that take
 // the rank-r term (what the router-guided transfer must bring in): stat = [-, -, rows[E], comp rows[E]].
+// Then one block makes the block tables of the decode launches (plan.h), and xa_tiles * E further
+// blocks compute (x A1 | x A3) for the decode flavour of the fused projection from the bf16 tokens
+// (xa_rows.h), so that no launch of its own stands between this one and the W1|W3 kernel.
 __global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ x, int rows, int H,
                                                    uint4* __restrict__ xg, int rt,
                                                    const int32_t* __restrict__ offsets,
                                                    const int32_t* __restrict__ row_pair, int E, int top_k,
                                                    int top_n, int32_t* __restrict__ stat, PlanSpec plan0,
-                                                   PlanSpec plan1) {
+                                                   PlanSpec plan1, int xa_tiles, ffn::KArgs xa) {
+  __shared__ ffn::float4_t red[4][64];
   const int row_blocks = (rows + 15) / 16;
-  if ((int)blockIdx.x == (int)gridDim.x - 1 && plan0.B + plan1.B > 0) {   // last block: the block tables (plan.h)
+  const int stat_blocks = stat ? (E + 3) / 4 : 0, plan_block = plan0.B + plan1.B > 0 ? 1 : 0;
+  if ((int)blockIdx.x >= row_blocks + stat_blocks + plan_block) {          // (x A1 | x A3)
+    const int i = (int)blockIdx.x - (row_blocks + stat_blocks + plan_block);
+    if (blockIdx.y == 0) ffn::xa_rows_body<true, true, 4>(xa, x, i % xa_tiles, i / xa_tiles, red);
+    return;
+  }
+  if (plan_block && (int)blockIdx.x == row_blocks + stat_blocks) {         // the block tables (plan.h)
     if (blockIdx.y == 0 && threadIdx.x < 128) make_plan(offsets, E, threadIdx.x < 64 ? plan0 : plan1, threadIdx.x & 63);
     return;
   }
@@ -209,18 +236,19 @@ hipError_t launch_expand_q3(int n, const Q3Expand* jobs, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_combine(const moe_lrc_layer* L, const void* y_rows, const float* w,
+hipError_t launch_combine(const moe_lrc_layer* L, const void* y_rows, const float* y_part, int kblocks, const float* w,
                           const int32_t* pair_row, const void* y_shared, int T, void* out,
                           hipStream_t s) {
   const moe_lrc_config& c = L->cfg;
-  hipLaunchKernelGGL(combine_kernel, dim3(T), dim3(256), 0, s, (const uint16_t*)y_rows, w, pair_row,
+  hipLaunchKernelGGL(combine_kernel, dim3(T), dim3(256), 0, s, (const uint16_t*)y_rows, y_part, kblocks,
+                     size_t(T) * c.top_k * c.hidden, w, pair_row,
                      (const uint16_t*)y_shared, T, c.hidden, c.top_k, c.n_shared, (uint16_t*)out);
   return hipGetLastError();
 }
 
 hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _Float16* xg, int rt,
                             const int32_t* offsets, const int32_t* row_pair, int32_t* stat,
-                            const PlanSpec* plans, hipStream_t s) {
+                            const PlanSpec* plans, const FfnArgs* xa13, hipStream_t s) {
   const moe_lrc_config& c = L->cfg;
   const int rows = row_pair ? T * c.top_k : T;
   const int row_blocks = (rows + 15) / 16;
@@ -228,9 +256,18 @@ hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _
   const PlanSpec none{0, 0, 0, nullptr};
   const PlanSpec p0 = plans ? plans[0] : none, p1 = plans ? plans[1] : none;
   const int plan_block = p0.B + p1.B > 0 ? 1 : 0;
-  hipLaunchKernelGGL(prep_kernel, dim3(row_blocks + (stat ? (c.n_experts + 3) / 4 : 0) + plan_block, ky), dim3(256), 0, s,
-                     (const uint16_t*)x_bf16, rows, c.hidden, reinterpret_cast<uint4*>(xg), rt, offsets, row_pair,
-                     c.n_experts, c.top_k, c.top_n, stat, p0, p1);
+  // (x A1 | x A3) of the decode flavour: 16-column tiles of both factors, each padded to ls * 32 columns
+  ffn::KArgs xa{};
+  int xa_tiles = 0;
+  if (xa13 && xa13->rank > 0 && xa13->top_n > 0 && row_pair) {
+    const FfnArgs& f = *xa13;
+    xa.desc = f.desc; xa.offsets = f.offsets; xa.row_pair = f.row_pair; xa.top_k = f.top_k; xa.top_n = f.top_n;
+    xa.rank = f.rank; xa.ls = (f.rank + 31) / 32; xa.K = f.H; xa.p = f.p13; xa.total_rows = f.total_rows;
+    xa_tiles = 4 * xa.ls;
+  }
+  hipLaunchKernelGGL(prep_kernel, dim3(row_blocks + (stat ? (c.n_experts + 3) / 4 : 0) + plan_block + xa_tiles * c.n_experts, ky),
+                     dim3(256), 0, s, (const uint16_t*)x_bf16, rows, c.hidden, reinterpret_cast<uint4*>(xg), rt, offsets,
+                     row_pair, c.n_experts, c.top_k, c.top_n, stat, p0, p1, xa_tiles, xa);
   return hipGetLastError();
 }
 

@@ -5,8 +5,9 @@
 // activations) writes, for every block of the later launch, which expert it serves: each expert with
 // rows gets `base` blocks (enough for 32 n-tiles per block), the rest of `target` blocks go by
 // weight (5 for up to 16 rows, 8 per 32-row pass beyond: what they cost), dealt by the running
-// sum of the weights.  Entry i of the table: expert (or -1: the block exits), index of the block within
-// the expert, blocks of the expert, unused.
+// sum of the weights.  Entry i of the table (PlanEntry, 32 bytes, read by block i with one scalar
+// load): expert (or -1: the block exits), index of the block within the expert, blocks of the expert,
+// first row and number of rows of the expert.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -14,6 +15,8 @@
 namespace lrc {
 
 struct PlanSpec { int B, base, target; int32_t* plan; };   // B entries; plan == null: no table wanted
+struct PlanEntry { int32_t e, b, G, r0, cnt, pad0, pad1, pad2; };
+constexpr int kPlanEntryInts = 8;
 
 __device__ inline void make_plan(const int32_t* __restrict__ offsets, int E, const PlanSpec sp, int lane) {
   if (sp.plan == nullptr) return;
@@ -43,6 +46,7 @@ __device__ inline void make_plan(const int32_t* __restrict__ offsets, int E, con
   for (int e0 = 0; e0 < E; e0 += 64) {
     const int e = e0 + lane;
     const int cnt = e < E ? offsets[e + 1] - offsets[e] : 0;
+    const int r0 = e < E ? offsets[e] : 0;
     const int act = cnt > 0 ? 1 : 0, w = weight(cnt), wi = scan(w), ai = scan(act);
     int lo = 0, hi = 0;
     if (act) {
@@ -55,20 +59,18 @@ __device__ inline void make_plan(const int32_t* __restrict__ offsets, int E, con
       for (unsigned long long todo = with_rows; todo; todo &= todo - 1) {
         const int j = __ffsll(todo) - 1;
         const int lo_j = __shfl(lo, j), G_j = __shfl(hi, j) - lo_j, hi_j = min(lo_j + G_j, B);
-        for (int i = lo_j + lane; i < hi_j; i += 64) {
-          plan[4 * i] = e0 + j; plan[4 * i + 1] = i - lo_j; plan[4 * i + 2] = G_j; plan[4 * i + 3] = 0;
-        }
+        const int r0_j = __shfl(r0, j), cnt_j = __shfl(cnt, j);
+        for (int i = lo_j + lane; i < hi_j; i += 64)
+          reinterpret_cast<PlanEntry*>(plan)[i] = PlanEntry{e0 + j, i - lo_j, G_j, r0_j, cnt_j, 0, 0, 0};
       }
     } else if (act) {
       // many experts with few blocks each: every lane writes its own expert's entries
-      for (int i = lo; i < hi && i < B; ++i) {
-        plan[4 * i] = e; plan[4 * i + 1] = i - lo; plan[4 * i + 2] = hi - lo; plan[4 * i + 3] = 0;
-      }
+      for (int i = lo; i < hi && i < B; ++i) reinterpret_cast<PlanEntry*>(plan)[i] = PlanEntry{e, i - lo, hi - lo, r0, cnt, 0, 0, 0};
     }
     act_before += __shfl(ai, 63); w_before += __shfl(wi, 63);
   }
   const int used = n_active > 0 ? n_active * base + int(extra) : 0;
-  for (int i = used + lane; i < B; i += 64) { plan[4 * i] = -1; plan[4 * i + 1] = 0; plan[4 * i + 2] = 1; plan[4 * i + 3] = 0; }
+  for (int i = used + lane; i < B; i += 64) reinterpret_cast<PlanEntry*>(plan)[i] = PlanEntry{-1, 0, 1, 0, 0, 0, 0, 0};
 }
 
 }  // namespace lrc

@@ -136,8 +136,12 @@ def test_forward_matches_four_calls_and_is_deterministic(case):
     out_a = L.forward(x).clone()
     out_b = L.forward(x).clone()
     assert torch.equal(out_a.view(torch.int16), out_b.view(torch.int16)), "two runs differ"
-    assert torch.equal(out_a.view(torch.int16), out4.view(torch.int16)), "forward differs from the four calls"
-    assert orc.rel_frobenius(_to_np(out_a), ref["out"]) <= TOL
+    # the composite equals the four calls up to rounding: it may add the fp32 K-block partial sums of
+    # W2 in the combine instead of reading expert rows rounded to bf16 (one bf16 rounding, 2^-9, fewer)
+    assert orc.rel_frobenius(_to_np(out_a), _to_np(out4)) <= 2.5e-3, "forward differs from the four calls by more than a rounding"
+    e_fwd, e_four = orc.rel_frobenius(_to_np(out_a), ref["out"]), orc.rel_frobenius(_to_np(out4), ref["out"])
+    print(f"[{cfg.name}] forward {e_fwd:.2e}, four calls {e_four:.2e}")
+    assert e_fwd <= TOL and e_fwd <= e_four * 1.05 + 1e-4
 
 
 def test_constructed_ties(amd):
@@ -445,3 +449,40 @@ def test_stats_path_reports_the_flavour(amd):
         torch.cuda.synchronize()
         assert L.stats()["path"] == want, (T, L.stats()["path"])
     L.close()
+
+
+@pytest.mark.parametrize("tokens", [16, 100, 300, 700])
+def test_ranks_from_the_papers_bucket_up_to_1024(amd, tokens):
+    """Section 3.1 step 1 allocates every expert matrix a rank from the bucket {0, 16, 32, 128, 256,
+    512, 1024}.  A layer whose projections cycle through the whole bucket (W1, W3 and W2 of one expert
+    all different), at 16 tokens (skinny kernels, one row tile), 100 (two row tiles, several passes,
+    the (in A) fragments of the large ranks taking the place of the staged activations), 300 (fused
+    projection as grouped GEMM, W2 skinny) and 700 (both grouped GEMM, rank steps in chunks), against
+    the oracle on the same stored factors; resident and staged layers agree bit for bit."""
+    import torch
+    bucket = (0, 16, 32, 128, 256, 512, 1024)
+    cfg = configs.TINY.with_(rank=1024, tokens=tokens, bits=2, name=f"bucket_T{tokens}")
+    layer = fixtures.sample_layer(cfg)
+    for e, ex in enumerate(layer["experts"]):
+        for m in (0, 1, 2):
+            r = bucket[(3 * e + 2 * m) % len(bucket)]
+            a = ex[m]
+            a["rank"] = r
+            a["A"] = np.ascontiguousarray(a["A"][:, :r]) if r else None
+            a["B"] = np.ascontiguousarray(a["B"][:r]) if r else None
+    x_bits = synth.make_tokens(cfg)
+    x = amd.bf16_tensor(x_bits)
+    ref = fixtures.oracle_forward(cfg, layer, x_bits)
+    Lr = amd.Layer.from_config(cfg)
+    Ls = amd.Layer.from_config(cfg, residency=amd.STAGED)
+    Lr.load(layer); Ls.load(layer)
+    out_r = Lr.forward(x).clone()
+    torch.cuda.synchronize()
+    out_s = Ls.forward(x).clone()
+    torch.cuda.synchronize()
+    err = orc.rel_frobenius(_to_np(out_r), ref["out"])
+    none = orc.rel_frobenius(_to_np(out_r), fixtures.oracle_forward(cfg.with_(top_n=0), layer, x_bits)["out"])
+    print(f"\n[{cfg.name}] out rel err {err:.2e} (the rank terms move the output by {none:.2e})", flush=True)
+    assert err <= TOL and none > 10 * TOL
+    assert torch.equal(out_r.view(torch.int16), out_s.view(torch.int16))
+    Lr.close(); Ls.close()
