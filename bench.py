@@ -269,6 +269,7 @@ def main():
             "hbm_read_gbs": round(amd.calibrate(amd.CAL_HBM_READ, 3 << 30, 5), 1),
             "h2d_pinned_gbs": round(amd.calibrate(amd.CAL_H2D, 256 << 20, 5), 1),
             "mfma_f16_tflops": round(amd.calibrate(amd.CAL_MFMA_F16, 0, 5), 1),
+            "mfma_f16_32x32x16_tflops": round(amd.calibrate(amd.CAL_MFMA_F16_32, 0, 5), 1),
             "note": "moe_lrc_calibrate on this device: 3 GiB streaming read, 256 MiB pinned copy, register-only MFMA loop"}
     path_kernel_ms = sum(stage_avg.values())
     result = {

@@ -241,10 +241,12 @@ int moe_lrc_selftest_decode_index(int hidden, int ffn, int bits, int group, int 
  *                         256 MB last-level cache), *result = GB/s of the median of `reps` passes
  *   MOE_LRC_CAL_H2D       copy of `bytes` from pinned host memory to the device, GB/s
  *   MOE_LRC_CAL_MFMA_F16  dense v_mfma_f32_16x16x32_f16 issue rate on registers, TFLOP/s (`bytes` unused)
+ *   MOE_LRC_CAL_MFMA_F16_32  the same with v_mfma_f32_32x32x16_f16
  * result: host pointer to one double. */
 #define MOE_LRC_CAL_HBM_READ 0
 #define MOE_LRC_CAL_H2D      1
 #define MOE_LRC_CAL_MFMA_F16 2
+#define MOE_LRC_CAL_MFMA_F16_32 3
 int moe_lrc_calibrate(int kind, size_t bytes, int reps, double* result);
 
 #ifdef __cplusplus

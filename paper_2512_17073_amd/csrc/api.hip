@@ -86,7 +86,8 @@ Workspace plan_workspace(const moe_lrc_layer* L, int T) {
   // (in A): K-block partial sums in fp32 and, in the many-rows flavour, the fp16 result in front of
   // them, both with the columns padded to a multiple of 32
   w.p13 = take(size_t(L->ksplit13 + 1) * P * 2 * (rpad + 16) * 4 + 256);
-  w.p2 = take(size_t(L->ksplit2 + 1) * P * (rpad + 16) * 4 + 256);
+  // (the decode flavour keeps one fp16 (h A2) per W2 K-block)
+  w.p2 = take(std::max(size_t(L->ksplit2 + 1) * P * (rpad + 16) * 4, size_t(kMaxKBlocks) * P * (rpad + 16) * 2) + 256);
   w.y_part = take(size_t(kMaxKBlocks) * P * c.hidden * 4);
   w.sh_y_part = take(size_t(kMaxKBlocks) * c.n_shared * T * c.hidden * 4);   // (shared experts run beside the routed ones)
   w.sh_h = take(c.n_shared ? (size_t(c.n_shared) * T + kActPadRows) * Fp * 2 : 0);
@@ -245,7 +246,10 @@ static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t*
   // and, for the decode flavour of the fused projection, (x A1 | x A3)
   PlanSpec plans[2];
   expert_ffn_plan_specs(a, plans[0], plans[1]);
-  LRC_HIP(launch_convert_x(L, x, T, xh, P + kActPadRows, offsets, row_pair, L->d_stat, plans, (path & 1) ? nullptr : &a, stream));
+  a.xa13_here = c.residency == MOE_LRC_STAGED;
+  a.x_tokens = x;
+  LRC_HIP(launch_convert_x(L, x, T, xh, P + kActPadRows, offsets, row_pair, L->d_stat, plans,
+                           ((path & 1) || a.xa13_here) ? nullptr : &a, stream));
   L->stats_valid = false;
   L->stats.stage_ms = 0.f;
   if (c.residency == MOE_LRC_STAGED) {

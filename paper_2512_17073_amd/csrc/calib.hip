@@ -58,6 +58,27 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(int iters, float* __rest
   if (s == 12345.678f) sink[0] = s;
 }
 
+// The same with v_mfma_f32_32x32x16_f16 (four independent 32x32 accumulators per wavefront).
+typedef float float16_t __attribute__((ext_vector_type(16)));
+__global__ __launch_bounds__(256) void mfma_rate32_kernel(int iters, float* __restrict__ sink) {
+  half8_t a, b;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) { a[i] = (_Float16)(0.001f * float(threadIdx.x + i)); b[i] = (_Float16)(0.002f * float(i + 1)); }
+  float16_t acc[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[j], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) s += acc[j][0] + acc[j][5] + acc[j][10] + acc[j][15];
+  if (s == 12345.678f) sink[0] = s;
+}
+
 }  // namespace
 
 }  // namespace lrc
@@ -75,8 +96,8 @@ using namespace lrc;
 
 extern "C" int moe_lrc_calibrate(int kind, size_t bytes, int reps, double* result) {
   if (!result || reps < 1 || reps > 1000) return set_error(MOE_LRC_EINVAL, "calibrate: result is null or reps outside 1..1000");
-  if (kind < MOE_LRC_CAL_HBM_READ || kind > MOE_LRC_CAL_MFMA_F16) return set_error(MOE_LRC_EINVAL, "calibrate: unknown kind");
-  if (kind != MOE_LRC_CAL_MFMA_F16 && (bytes < (1u << 20) || bytes > (size_t(16) << 30)))
+  if (kind < MOE_LRC_CAL_HBM_READ || kind > MOE_LRC_CAL_MFMA_F16_32) return set_error(MOE_LRC_EINVAL, "calibrate: unknown kind");
+  if (kind < MOE_LRC_CAL_MFMA_F16 && (bytes < (1u << 20) || bytes > (size_t(16) << 30)))
     return set_error(MOE_LRC_EINVAL, "calibrate: bytes must be between 1 MiB and 16 GiB");
   int rc = MOE_LRC_OK, dev = 0, n_cu = 0;
   void *dbuf = nullptr, *hbuf = nullptr;
@@ -123,14 +144,15 @@ extern "C" int moe_lrc_calibrate(int kind, size_t bytes, int reps, double* resul
     const int iters = 4096, blocks = n_cu * 8;
     for (int i = 0; i < reps + 1; ++i) {
       CAL_HIP(hipEventRecord(e0, nullptr));
-      hipLaunchKernelGGL(mfma_rate_kernel, dim3(blocks), dim3(256), 0, nullptr, iters, (float*)sink);
+      if (kind == MOE_LRC_CAL_MFMA_F16) hipLaunchKernelGGL(mfma_rate_kernel, dim3(blocks), dim3(256), 0, nullptr, iters, (float*)sink);
+      else hipLaunchKernelGGL(mfma_rate32_kernel, dim3(blocks), dim3(256), 0, nullptr, iters, (float*)sink);
       CAL_HIP(hipEventRecord(e1, nullptr));
       CAL_HIP(hipEventSynchronize(e1));
       CAL_HIP(hipEventElapsedTime(&t, e0, e1));
       if (i > 0) ms.push_back(t);
     }
     std::sort(ms.begin(), ms.end());
-    const double flops = double(blocks) * 4 * iters * 8 * (2.0 * 16 * 16 * 32);
+    const double flops = double(blocks) * 4 * iters * (kind == MOE_LRC_CAL_MFMA_F16 ? 8 * (2.0 * 16 * 16 * 32) : 4 * (2.0 * 32 * 32 * 16));
     *result = flops / (ms[ms.size() / 2] * 1e-3) / 1e12;             // TFLOP/s
   }
   CAL_HIP(hipGetLastError());

@@ -24,8 +24,10 @@ LRC_HD void block_tiles(int b, int G, int NT, int& t0, int& t1) {
 
 // Work units of a block: an n-tile of both projections (DUAL) or a pair of adjacent n-tiles (W2).
 LRC_HD int block_units(int nt_b, bool dual) { return dual ? nt_b : (nt_b + 1) / 2; }
-// unit slots a wavefront visits one after the other
-LRC_HD int unit_slots(bool dual) { return dual ? 2 : 1; }
+// Unit slots a wavefront visits one after the other.
+LRC_HD int unit_slots(bool dual, int mt) { (void)mt; return dual ? 2 : 1; }
+// n-tiles a block can own
+LRC_HD int max_block_tiles(int mt) { (void)mt; return 32; }
 
 // Wavefronts that share one unit, each taking every kw-th k-step (power of two, 1..16).
 LRC_HD int waves_per_unit(int units) {
@@ -38,23 +40,28 @@ LRC_HD int waves_per_unit(int units) {
 // W2: tiles t0 + 2u and t0 + 2u + 1.
 LRC_HD int stream_tile(int t0, int u, int m, bool dual) { return dual ? t0 + u : t0 + 2 * u + m; }
 
-// Steps of a wavefront, in order: [phase][unit slot][own k-step] (each segment padded to a multiple
-// of the ring depth), then [own rank step][unit slot] (padded likewise).
+// Steps of a wavefront, in order: [phase][unit slot][own k-step], then [unit slot][own rank step];
+// each innermost segment is padded to a multiple of the ring depth, so that ring slots are indexed
+// statically.
 struct StepPlan {
+  int TS;        // unit slots
   int KP;        // k-steps per phase (16 with one row tile, 8 with two)
   int n_ph;      // phases of this K-block
   int SP;        // padded own k-steps per (unit slot, phase) segment
   int n_reg;     // regular steps in all
+  int LSS;       // padded own rank steps per unit slot
   int LSP;       // padded rank steps in all
 };
 LRC_HD StepPlan step_plan(int KSl, int mt, int kw, int LS, bool dual) {
   StepPlan p;
+  p.TS = unit_slots(dual, mt);
   p.KP = (kLdsUnits / 512) / mt;
   p.n_ph = (KSl + p.KP - 1) / p.KP;
   const int spw = (p.KP + kw - 1) / kw;
   p.SP = (spw + kRing - 1) / kRing * kRing;
-  p.n_reg = p.n_ph * unit_slots(dual) * p.SP;
-  p.LSP = (unit_slots(dual) * ((LS + kw - 1) / kw) + kRing - 1) / kRing * kRing;
+  p.n_reg = p.n_ph * p.TS * p.SP;
+  p.LSS = ((LS + kw - 1) / kw + kRing - 1) / kRing * kRing;
+  p.LSP = p.TS * p.LSS;
   return p;
 }
 
@@ -71,7 +78,8 @@ struct StepRef {
 LRC_HD StepRef step_ref(int n, const StepPlan& p, int grp, int groups, int kwi, int kw, int units, int ks_lo, int KSl,
                         int LS, bool dual) {
   StepRef r{};
-  const int TS = unit_slots(dual);
+  const int TS = p.TS;
+  (void)dual;
   if (n < p.n_reg) {
     const int seg = n / p.SP, si = n - seg * p.SP, ph = seg / TS;
     r.ts = seg - ph * TS;
@@ -81,9 +89,9 @@ LRC_HD StepRef step_ref(int n, const StepPlan& p, int grp, int groups, int kwi, 
     r.reg = r.unit < units && r.kl < p.KP && ph * p.KP + r.kl < KSl;
   } else {
     const int l = n - p.n_reg;
-    r.ts = l % TS;
+    r.ts = p.LSS > 0 ? l / p.LSS : 0;
     r.unit = grp + r.ts * groups;
-    r.st = (l / TS) * kw + kwi;
+    r.st = (p.LSS > 0 ? l - r.ts * p.LSS : 0) * kw + kwi;
     r.lr = l < p.LSP && r.unit < units && r.st < LS;
   }
   return r;
@@ -112,6 +120,7 @@ LRC_HD LaneOffsets lane_offsets(const StepRef& r, int tile, bool tile_ok, int la
 LRC_HD int act_frag_unit(int mt, int kl, int s, int KP) { return ((mt * KP + kl) * 8 + s) * 64; }
 // LDS unit (relative to the fragment region) of (in A) fragment (stream m, rank step st, row tile mt).
 LRC_HD int p_frag_unit(int m, int st, int mt, int LS, int MT) { return ((m * LS + st) * MT + mt) * 64; }
+
 
 }  // namespace dec
 }  // namespace lrc

@@ -7,8 +7,12 @@
 // Kernel design (gfx950):
 //   - a block of 8 wavefronts owns 128 rows of one expert x 256 output columns (of both W1 and W3
 //     in the fused kernel); a wavefront owns two n-tiles (16 columns each) for all 128 rows, so a
-//     fragment of activations read from LDS feeds four MFMAs and a tile of weights unpacked once in
-//     registers (unpack.h) feeds eight row tiles;
+//     tile of weights unpacked once in registers (unpack.h) feeds all the rows;
+//   - the products run on v_mfma_f32_32x32x16_f16, which this chip issues at twice the rate of the
+//     16x16x32 shape (measured: 2.3 against 1.2 PFLOP/s): two streams of 16 output columns that meet
+//     the same activations (W1 and W3 of one n-tile, or two n-tiles of W2) become the 32 rows of one
+//     A operand by a swap of 16-lane rows between their registers, which puts the same inputs of
+//     both streams side by side; the activations are staged as fragments of 32 rows;
 //   - the packed weights never touch LDS: each wavefront streams its tiles HBM -> registers through
 //     a two-slot ring of buffer loads (a load past the end of the resource returns zeros, so the
 //     refills are unconditional and the waits static);
@@ -92,6 +96,41 @@ __device__ inline void stage_step(const KArgs& a, uint4* buf, int ks, int rin, i
   }
 }
 
+typedef float float16_t __attribute__((ext_vector_type(16)));
+constexpr int kRP = kBM / 32;             // 32-row fragments ("row pairs") of a chunk
+
+// The same k-step as fragments for the 32x32x16 products: fragment (row pair rp, sub-step s, operand p)
+// at unit ((rp * 8 + s) * 2 + p) * 64; lane l holds, of row 32 rp + l % 32, the 8 inputs of lane
+// group q = p + 2 (l / 32) of sub-step s.  (After the row swap, operand p of a sub-step holds in
+// lanes 0..31 the weights of lane group q = p and in lanes 32..63 those of q = p + 2.)  Wavefront w
+// copies the eight fragments with s = w.
+__device__ inline void stage_step32(const KArgs& a, uint4* buf, int ks, int rin, int wave, int lane) {
+  const uint4* in_units = reinterpret_cast<const uint4*>(a.in);
+  const int n = lane & 31, h = lane >> 5, s = wave;
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    const int k8 = min(ks * 32 + (p + 2 * h) * 8 + s, a.K / 8 - 1);
+#pragma unroll
+    for (int rp = 0; rp < kRP; ++rp) {
+      const int R = min(rin + 32 * rp + n, a.in_rt - 1);
+      __builtin_amdgcn_global_load_lds(
+          reinterpret_cast<const __attribute__((address_space(1))) void*>(reinterpret_cast<uintptr_t>(in_units + act_unit(k8, R, a.in_rt))),
+          reinterpret_cast<__attribute__((address_space(3))) void*>(reinterpret_cast<uintptr_t>(buf + ((rp * 8 + s) * 2 + p) * 64)), 16, 0, 0);
+    }
+  }
+}
+
+// (in A) fragments of a rank step for the 32x32x16 products: V variants per rank step (4 fused, 2
+// for W2).  Variant v, lane l (half h = l / 32) holds the 8 rank indices of group `grp` of
+// projection m's (in A).  The fused projections meet different (in A): the A operand of variant v
+// keeps W1's columns in input half h = v & 1 and W3's in the other, so the fragment holds A1's part
+// where W1 sits and A3's where W3 sits.
+__device__ inline void rank_frag_source(int v, int lane, bool dual, int& m, int& grp) {
+  const int h = lane >> 5;
+  if (dual) { m = h ^ (v & 1); grp = (v >> 1) + 2 * h; }
+  else { m = 0; grp = v + 2 * h; }
+}
+
 // Codes and metadata of one k-step of a wavefront's two n-tiles.
 template <int BITS, int NM, int NTW> struct Slot2 { Slot<BITS, NM> t[NTW]; };
 
@@ -112,7 +151,6 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
   const int wave = __builtin_amdgcn_readfirstlane(th >> 6);
   const int q = lane >> 4, c = lane & 15;
   const int tdw = kWave * DW;
-  const int mt_n = min(kTMT, (cnt - r + 15) >> 4);       // row tiles that hold rows of this expert
   const int tile0 = (blockIdx.x * kTileWaves + wave) * kNTW;
 
   const int code_bytes = a.KS * a.NT * tdw * 4, meta_bytes = a.G * a.NT * kTileN * 4;
@@ -168,71 +206,74 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
   // first input row of this chunk (shared experts all read the token rows 0..T-1)
   const int rin = ((DUAL && !a.offsets) ? 0 : r0) + r;
 
-  float4_t acc[kNTW][kTMT][NM];
+  // Streams (16 output columns that meet the same activations) are paired into the 32 rows of an A
+  // operand: (W1, W3) of n-tile j in the fused kernel, n-tiles 2j and 2j + 1 otherwise.
+  constexpr int NPAIR = kNTW * NM / 2;
+  // acc[j][rp]: the 32 x 32 result of pair j and row pair rp; register i of lane l holds, of row
+  // 32 rp + l % 32, stream i / 8, column 8 ((i / 4) % 2) + 4 (l / 32) + i % 4 of the stream's n-tile
+  float16_t acc[NPAIR][kRP];
 #pragma unroll
-  for (int t = 0; t < kNTW; ++t)
+  for (int j = 0; j < NPAIR; ++j)
 #pragma unroll
-    for (int mt = 0; mt < kTMT; ++mt)
+    for (int rp = 0; rp < kRP; ++rp)
 #pragma unroll
-      for (int m = 0; m < NM; ++m) acc[t][mt][m] = float4_t{0.f, 0.f, 0.f, 0.f};
+      for (int i = 0; i < 16; ++i) acc[j][rp][i] = 0.f;
+  const int rp_n = min(kRP, (cnt - r + 31) >> 5);         // row pairs that hold rows of this expert
 
-  // A fragment read from LDS meets the operands of all (tile, projection) pairs of the wavefront.
-  // The read of the next row tile's fragment is issued before the MFMAs of the current one.
-  constexpr int PF = 1;                   // fragments requested ahead of the one being multiplied
-  auto mfma_rows = [&](const half8_t (&wf)[kNTW][NM], uint32_t base) {   // base: LDS byte address of (row tile 0, this lane)
-    half8_t xf[PF + 1];
-    if (mt_n == kTMT) {                   // a full chunk: straight-line, PF reads in flight
-      auto rd = [&](auto MT) {
-        constexpr int mt = decltype(MT)::value;
-        xf[mt % (PF + 1)] = lds_read16<mt * 8 * 1024>(base);
-      };
-      auto row_tile = [&](auto MT) {
-        constexpr int mt = decltype(MT)::value;
-        if constexpr (mt + PF < kTMT) rd(std::integral_constant<int, (mt + PF < kTMT ? mt + PF : 0)>{});
-        lds_wait<(kTMT - 1 - mt < PF ? kTMT - 1 - mt : PF)>(xf[mt % (PF + 1)]);
+  // The fragments (rp, p) of a sub-step meet the operands of all pairs.  The read of the next
+  // fragment is issued before the MFMAs of the current one.
+  auto mfma_rows = [&](const uint32_t (&A)[2][NPAIR][4], uint32_t base) {   // base: LDS byte address of fragment (0, s, 0), this lane
+    half8_t xf[2];
+    auto mm = [&](int f, const half8_t& x) {
 #pragma unroll
-        for (int t = 0; t < kNTW; ++t)
-#pragma unroll
-          for (int m = 0; m < NM; ++m)
-            acc[t][mt][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[t][m], xf[mt % (PF + 1)], acc[t][mt][m], 0, 0, 0);
+      for (int j = 0; j < NPAIR; ++j) {
+        const half8_t av = __builtin_bit_cast(half8_t, make_uint4(A[f & 1][j][0], A[f & 1][j][1], A[f & 1][j][2], A[f & 1][j][3]));
+        acc[j][f >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, x, acc[j][f >> 1], 0, 0, 0);
+      }
+    };
+    if (rp_n == kRP) {                    // a full chunk: straight-line, one read in flight
+      auto step = [&](auto F) {
+        constexpr int f = decltype(F)::value;
+        if constexpr (f + 1 < 2 * kRP) xf[(f + 1) & 1] = lds_read16<((f + 1) >> 1) * 16384 + ((f + 1) & 1) * 1024>(base);
+        lds_wait<(f + 1 < 2 * kRP ? 1 : 0)>(xf[f & 1]);
+        mm(f, xf[f & 1]);
       };
-      rd(std::integral_constant<int, 0>{});
-      if constexpr (PF > 1) rd(std::integral_constant<int, 1>{});
-      if constexpr (PF > 2) rd(std::integral_constant<int, 2>{});
-      row_tile(std::integral_constant<int, 0>{}); row_tile(std::integral_constant<int, 1>{});
-      row_tile(std::integral_constant<int, 2>{}); row_tile(std::integral_constant<int, 3>{});
-      row_tile(std::integral_constant<int, 4>{}); row_tile(std::integral_constant<int, 5>{});
-      row_tile(std::integral_constant<int, 6>{}); row_tile(std::integral_constant<int, 7>{});
+      xf[0] = lds_read16<0>(base);
+      step(std::integral_constant<int, 0>{}); step(std::integral_constant<int, 1>{});
+      step(std::integral_constant<int, 2>{}); step(std::integral_constant<int, 3>{});
+      step(std::integral_constant<int, 4>{}); step(std::integral_constant<int, 5>{});
+      step(std::integral_constant<int, 6>{}); step(std::integral_constant<int, 7>{});
       return;
     }
-    // a partly filled chunk: only the row tiles that hold rows, one read ahead
+    // a partly filled chunk: only the row pairs that hold rows
     xf[0] = lds_read16<0>(base);
-    auto row_tile = [&](auto MT) {
-      constexpr int mt = decltype(MT)::value;
-      if (mt >= mt_n) return;
-      if constexpr (mt + 1 < kTMT) {
-        if (mt + 1 < mt_n) {
-          xf[(mt + 1) & 1] = lds_read16<(mt + 1) * 8 * 1024>(base);
-          lds_wait<1>(xf[mt & 1]);
+    auto step = [&](auto F) {
+      constexpr int f = decltype(F)::value;
+      if ((f >> 1) >= rp_n) return;
+      if constexpr (f + 1 < 2 * kRP) {
+        if (((f + 1) >> 1) < rp_n) {
+          xf[(f + 1) & 1] = lds_read16<((f + 1) >> 1) * 16384 + ((f + 1) & 1) * 1024>(base);
+          lds_wait<1>(xf[f & 1]);
         } else {
-          lds_wait<0>(xf[mt & 1]);
+          lds_wait<0>(xf[f & 1]);
         }
       } else {
-        lds_wait<0>(xf[mt & 1]);
+        lds_wait<0>(xf[f & 1]);
       }
-#pragma unroll
-      for (int t = 0; t < kNTW; ++t)
-#pragma unroll
-        for (int m = 0; m < NM; ++m)
-          acc[t][mt][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[t][m], xf[mt & 1], acc[t][mt][m], 0, 0, 0);
+      mm(f, xf[f & 1]);
     };
-    row_tile(std::integral_constant<int, 0>{}); row_tile(std::integral_constant<int, 1>{});
-    row_tile(std::integral_constant<int, 2>{}); row_tile(std::integral_constant<int, 3>{});
-    row_tile(std::integral_constant<int, 4>{}); row_tile(std::integral_constant<int, 5>{});
-    row_tile(std::integral_constant<int, 6>{}); row_tile(std::integral_constant<int, 7>{});
+    step(std::integral_constant<int, 0>{}); step(std::integral_constant<int, 1>{});
+    step(std::integral_constant<int, 2>{}); step(std::integral_constant<int, 3>{});
+    step(std::integral_constant<int, 4>{}); step(std::integral_constant<int, 5>{});
+    step(std::integral_constant<int, 6>{}); step(std::integral_constant<int, 7>{});
+  };
+  // the two streams of pair j: (tile slot, projection)
+  auto pair_stream = [](int j, int side, int& t, int& m) {
+    if constexpr (DUAL) { t = j; m = side; }
+    else { t = 2 * j + side; m = 0; }
   };
 
-  // one k-step: unpack 32 rows of the four weight tiles per sub-step, multiply with all row tiles
+  // one k-step: unpack 32 rows of the weight tiles per sub-step, multiply with all rows
   auto compute = [&](const Slot2<BITS, NM, kNTW>& cur, const uint4* buf) {
     uint32_t s2[kNTW][NM][NC], c2[kNTW][NM];
 #pragma unroll
@@ -249,18 +290,27 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
     const uint32_t base = uint32_t(reinterpret_cast<uintptr_t>(buf + lane));
     auto substep = [&](auto S) {
       constexpr int s = decltype(S)::value;
-      half8_t wf[kNTW][NM];
+      uint32_t A[2][NPAIR][4];
 #pragma unroll
-      for (int t = 0; t < kNTW; ++t)
+      for (int j = 0; j < NPAIR; ++j) {
+        uint32_t v[2][4];
 #pragma unroll
-        for (int m = 0; m < NM; ++m) {
-          uint32_t v[4];
+        for (int side = 0; side < 2; ++side) {
+          int t, m;
+          pair_stream(j, side, t, m);
 #pragma unroll
-          for (int j = 0; j < 4; ++j)
-            v[j] = pk_fma(Extract<BITS>::field(cur.t[t].cw[m], 4 * s + j), s2[t][m][Extract<BITS>::cls(4 * s + j)], c2[t][m]);
-          wf[t][m] = __builtin_bit_cast(half8_t, make_uint4(v[0], v[1], v[2], v[3]));
+          for (int i = 0; i < 4; ++i)
+            v[side][i] = pk_fma(Extract<BITS>::field(cur.t[t].cw[m], 4 * s + i), s2[t][m][Extract<BITS>::cls(4 * s + i)], c2[t][m]);
         }
-      mfma_rows(wf, base + s * 1024);
+        // rows of 16 lanes swapped between the two streams: operand 0 = lane groups q = 0, 2 of both
+        // streams side by side, operand 1 = q = 1, 3
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const auto sw = __builtin_amdgcn_permlane16_swap(v[0][i], v[1][i], false, false);
+          A[0][j][i] = sw[0]; A[1][j][i] = sw[1];
+        }
+      }
+      mfma_rows(A, base + s * 2048);
     };
     substep(std::integral_constant<int, 0>{}); substep(std::integral_constant<int, 1>{});
     substep(std::integral_constant<int, 2>{}); substep(std::integral_constant<int, 3>{});
@@ -270,7 +320,7 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
 
   // ---- prologue: the first k-step of activations and the first two ring slots
   Slot2<BITS, NM, kNTW> ring[2];
-  stage_step(a, xs, 0, rin, wave, lane);
+  stage_step32(a, xs, 0, rin, wave, lane);
   __builtin_amdgcn_sched_barrier(0);
   fetch(0, ring[0]);
   fetch(1, ring[1]);
@@ -289,7 +339,7 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
     for (int i = 0; i < 2; ++i) {
       const int step = s0 + i;
       if (step < steps) {
-        stage_step(a, xs + ((step + 1) & 1) * kStepUnits, step + 1, rin, wave, lane);
+        stage_step32(a, xs + ((step + 1) & 1) * kStepUnits, step + 1, rin, wave, lane);
         __builtin_amdgcn_sched_barrier(0);     // (the wait below counts the refill as the only later loads)
         compute(ring[i], xs + (step & 1) * kStepUnits);
         fetch(step + 2, ring[i]);
@@ -299,42 +349,65 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
   }
 
   // ---- rank steps.  (in A) of the chunk's rows, fp16 row-major in global memory (xa_tile_kernel
-  //      has scaled it and zeroed the rows without the term), is copied into LDS as MFMA fragments,
-  //      kRankChunk rank steps at a time (all of them for ranks up to 256): unit
-  //      ((m * kRankChunk + st - c0) * 8 + mt) * 64 + lane = columns 32 st + 8 q .. + 7 of row 16 mt + lane % 16.
-  constexpr int kRankChunk = 2 * kStepUnits / (NM * kTMT * 64);     // 8 (fused) or 16 rank steps fill the 128 KB
+  //      has scaled it and zeroed the rows without the term), is copied into LDS as fragments of 32
+  //      rows, kRankChunk rank steps at a time (all of them for ranks up to 256): fragment (rank step
+  //      st, variant v, row pair rp) at unit (((st - c0) * V + v) * 4 + rp) * 64 (rank_frag_source).
+  constexpr int V = DUAL ? 4 : 2;
+  constexpr int kRankChunk = 2 * kStepUnits / (V * kRP * 64);       // 8 (fused) or 16 rank steps fill the 128 KB
   for (int c0 = 0; c0 < LS; c0 += kRankChunk) {
     const int c1 = min(LS, c0 + kRankChunk);
     asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");   // (everyone is done with what LDS held)
     const _Float16* P = reinterpret_cast<const _Float16*>(a.p);
     const int pitch = NM * a.ls * 32;                                // halves per row
-    for (int f = wave; f < NM * (c1 - c0) * kTMT; f += kTileWaves) {
-      const int mt = f % kTMT, g = f / kTMT, sl = g % (c1 - c0), m = g / (c1 - c0);
-      const int row = min(r0 + r + 16 * mt + c, a.total_rows - 1);
-      const _Float16* src = P + size_t(row) * pitch + m * a.ls * 32 + 32 * (c0 + sl) + 8 * q;
+    for (int f = wave; f < (c1 - c0) * V * kRP; f += kTileWaves) {
+      const int rp = f % kRP, g = f / kRP, v = g % V, sl = g / V;
+      int m, grp;
+      rank_frag_source(v, lane, DUAL, m, grp);
+      const int row = min(r0 + r + 32 * rp + (lane & 31), a.total_rows - 1);
+      const _Float16* src = P + size_t(row) * pitch + m * a.ls * 32 + 32 * (c0 + sl) + 8 * grp;
       __builtin_amdgcn_global_load_lds(
           reinterpret_cast<const __attribute__((address_space(1))) void*>(reinterpret_cast<uintptr_t>(src)),
-          reinterpret_cast<__attribute__((address_space(3))) void*>(reinterpret_cast<uintptr_t>(xs + ((size_t(m) * kRankChunk + sl) * kTMT + mt) * 64)), 16, 0, 0);
+          reinterpret_cast<__attribute__((address_space(3))) void*>(reinterpret_cast<uintptr_t>(xs + ((size_t(sl) * V + v) * kRP + rp) * 64)), 16, 0, 0);
     }
     // (the ring slots are refilled below, after this wait: only the copies just issued and the two
     // slots requested before them are outstanding)
     asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
     auto rank_step = [&](const Slot2<BITS, NM, kNTW>& cur, int st) {
 #pragma unroll
-      for (int m = 0; m < NM; ++m) {
-        if (st >= LSm[m]) continue;
-        half8_t bfrag[kNTW];
+      for (int j = 0; j < NPAIR; ++j) {
+        // the B-factor units of the pair's two streams, 16-lane rows swapped: r0 = rank groups 0 and 2
+        // of both streams side by side, r1 = groups 1 and 3 (a stream past its own rank holds zeros)
+        int t0s, m0s, t1s, m1s;
+        pair_stream(j, 0, t0s, m0s);
+        pair_stream(j, 1, t1s, m1s);
+        uint32_t r0v[4], r1v[4];
 #pragma unroll
-        for (int t = 0; t < kNTW; ++t)
-          bfrag[t] = __builtin_bit_cast(half8_t, make_uint4(cur.t[t].cw[m][0], cur.t[t].cw[m][1], cur.t[t].cw[m][2], cur.t[t].cw[m][3]));
+        for (int i = 0; i < 4; ++i) {
+          const auto sw = __builtin_amdgcn_permlane16_swap(cur.t[t0s].cw[m0s][i], cur.t[t1s].cw[m1s][i], false, false);
+          r0v[i] = sw[0]; r1v[i] = sw[1];
+        }
 #pragma unroll
-        for (int mt = 0; mt < kTMT; ++mt)
-          if (mt < mt_n) {
-            const half8_t pf = __builtin_bit_cast(half8_t, xs[((size_t(m) * kRankChunk + st - c0) * kTMT + mt) * 64 + lane]);
+        for (int v = 0; v < V; ++v) {
+          uint32_t av[4];
 #pragma unroll
-            for (int t = 0; t < kNTW; ++t)
-              acc[t][mt][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(bfrag[t], pf, acc[t][mt][m], 0, 0, 0);
+          for (int i = 0; i < 4; ++i) {
+            if constexpr (DUAL) {
+              // W1 and W3 meet different (in A): W1's columns keep one half of the inputs, W3's the
+              // other (lane rows 0, 3 or 1, 2), zero elsewhere
+              const bool keep = (v & 1) ? (q == 1 || q == 2) : (q == 0 || q == 3);
+              av[i] = keep ? (v < 2 ? r0v[i] : r1v[i]) : 0u;
+            } else {
+              av[i] = v == 0 ? r0v[i] : r1v[i];
+            }
           }
+          const half8_t avh = __builtin_bit_cast(half8_t, make_uint4(av[0], av[1], av[2], av[3]));
+#pragma unroll
+          for (int rp = 0; rp < kRP; ++rp)
+            if (rp < rp_n) {
+              const half8_t pf = __builtin_bit_cast(half8_t, xs[((size_t(st - c0) * V + v) * kRP + rp) * 64 + lane]);
+              acc[j][rp] = __builtin_amdgcn_mfma_f32_32x32x16_f16(avh, pf, acc[j][rp], 0, 0, 0);
+            }
+        }
       }
     };
     // the slot of step KS + st is ring[(KS + st) % 2]: walk the chunk's steps in aligned pairs
@@ -350,34 +423,44 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
     }
   }
 
-  // ---- epilogue: lane holds output columns 16*tile + 4*q .. +3 of token column c ----
+  // ---- epilogue: lane l holds, of row 32 rp + l % 32, columns 8 g + 4 (l / 32) .. + 3 (g = 0, 1) of
+  //      both streams of every pair ----
+  const int hh = lane >> 5;
 #pragma unroll
-  for (int t = 0; t < kNTW; ++t) {
-    const int tile = tile0 + t;
-    if (tile >= a.NT) continue;
+  for (int j = 0; j < NPAIR; ++j)
 #pragma unroll
-    for (int mt = 0; mt < kTMT; ++mt) {
-      const int row = r + 16 * mt + c;
-      if (mt >= mt_n || row >= cnt) continue;
-      const size_t o = size_t(r0 + row) * a.N + tile * kTileN + 4 * q;
-      if constexpr (DUAL) {
-        half4_t hv;
+    for (int rp = 0; rp < kRP; ++rp) {
+      const int row = r + 32 * rp + (lane & 31);
+      if (rp >= rp_n || row >= cnt) continue;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const float g = acc[t][mt][0][i] * lam[0], u = acc[t][mt][1][i] * lam[NM - 1];
-          hv[i] = (_Float16)(g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u);
+      for (int g = 0; g < 2; ++g) {
+        const int col4 = 8 * g + 4 * hh;
+        if constexpr (DUAL) {
+          const int tile = tile0 + j;
+          if (tile >= a.NT) continue;
+          half4_t hv;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float gg = acc[j][rp][4 * g + i] * lam[0], uu = acc[j][rp][8 + 4 * g + i] * lam[NM - 1];
+            hv[i] = (_Float16)(gg * __builtin_amdgcn_rcpf(1.0f + __expf(-gg)) * uu);
+          }
+          // h in operand order for the W2 kernel: columns f .. f+3 are half of one 16-byte unit
+          const int f = tile * kTileN + col4;
+          *reinterpret_cast<half4_t*>(reinterpret_cast<_Float16*>(a.out) + act_unit(f >> 3, r0 + row, a.out_rt) * 8 + (f & 7)) = hv;
+        } else {
+#pragma unroll
+          for (int side = 0; side < 2; ++side) {
+            const int tile = tile0 + 2 * j + side;
+            if (tile >= a.NT) continue;
+            const size_t o = size_t(r0 + row) * a.N + tile * kTileN + col4;
+            uint2 yv;
+            yv.x = f32x2_to_bf16x2(acc[j][rp][8 * side + 4 * g] * lam[0], acc[j][rp][8 * side + 4 * g + 1] * lam[0]);
+            yv.y = f32x2_to_bf16x2(acc[j][rp][8 * side + 4 * g + 2] * lam[0], acc[j][rp][8 * side + 4 * g + 3] * lam[0]);
+            *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + o) = yv;
+          }
         }
-        // h in operand order for the W2 kernel: columns f .. f+3 are half of one 16-byte unit
-        const int f = tile * kTileN + 4 * q;
-        *reinterpret_cast<half4_t*>(reinterpret_cast<_Float16*>(a.out) + act_unit(f >> 3, r0 + row, a.out_rt) * 8 + (f & 7)) = hv;
-      } else {
-        uint2 yv;
-        yv.x = f32x2_to_bf16x2(acc[t][mt][0][0] * lam[0], acc[t][mt][0][1] * lam[0]);
-        yv.y = f32x2_to_bf16x2(acc[t][mt][0][2] * lam[0], acc[t][mt][0][3] * lam[0]);
-        *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + o) = yv;
       }
     }
-  }
 }
 
 // (in A)[row][rho] for the 128-row chunks of every expert, in two launches.

@@ -35,7 +35,11 @@ namespace {
 using namespace ffn;
 using namespace dec;
 
+
 // One expert's share of a block: MT = row tiles per pass (1 when the expert has at most 16 rows).
+// (v_mfma_f32_32x32x16_f16 runs at twice the rate of the 16x16x32 shape used here, and a pass of 32
+// rows can be put on it by swapping 16-lane rows between the two streams' registers; measured, the
+// four swaps per sub-step cost this issue-bound kernel more than the two matrix instructions save.)
 template <int BITS, bool DUAL, int MT>
 __device__ __forceinline__ void decode_body(const KArgs& a, uint4* xs, const int e, const int r0, const int cnt,
                                             const int b, const int G) {
@@ -62,9 +66,10 @@ __device__ __forceinline__ void decode_body(const KArgs& a, uint4* xs, const int
   const uint32_t code_bytes = uint32_t(a.KS) * a.NT * (kWave * 2 * BITS * 4), meta_bytes = uint32_t(a.G) * a.NT * kTileN * 4;
 
   // The rank-r term rides the same stream (B-factor units in place of packed codes, against (in A)
-  // instead of the activations).  Its steps belong to K-block 0.  Each stream has the rank of its
-  // own projection; a resource of the size its rank fills makes later steps read zeros.
-  const bool lowrank = a.rank > 0 && a.row_pair != nullptr && kb == 0 && __builtin_amdgcn_readfirstlane(d.has_factors) != 0 &&
+  // instead of the activations).  With K-blocks, every K-block meets the part of (in A) summed over
+  // its own k-steps (the term is linear in it).  Each stream has the rank of its own projection; a
+  // resource of the size its rank fills makes later steps read zeros.
+  const bool lowrank = a.rank > 0 && a.row_pair != nullptr && __builtin_amdgcn_readfirstlane(d.has_factors) != 0 &&
                        __builtin_amdgcn_readfirstlane(a.comp_rows[e]) > 0;
   int LSm[NS];
 #pragma unroll
@@ -146,7 +151,7 @@ __device__ __forceinline__ void decode_body(const KArgs& a, uint4* xs, const int
     // projection's power-of-two pre-scale and zero for rows without the term.  Fragment
     // (m, st, mt): lane (q, c) copies columns 32 st + 8 q .. + 7 of row 16 mt + c.  A row past the
     // expert's last one is clamped to a valid row (its output column is never stored).
-    const _Float16* P = reinterpret_cast<const _Float16*>(a.p);
+    const _Float16* P = reinterpret_cast<const _Float16*>(a.p) + size_t(kb) * a.total_rows * pitch;
     auto p_issue = [&]() {
       for (int f = wave; f < p_frags; f += kWaves) {
         const int mt = f % MT, g = f / MT, st = g % LS, m = g / LS;
@@ -279,14 +284,18 @@ __device__ __forceinline__ void decode_body(const KArgs& a, uint4* xs, const int
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __syncthreads();
     }
-    for (int l0 = 0; l0 < sp.LSP; l0 += RING) {   // the rank steps (none unless this block adds the term)
 #pragma unroll
-      for (int i = 0; i < RING; ++i) {
-        const int st = ((l0 + i) / TS) * kw + kwi;
-        if (grp + ((l0 + i) % TS) * groups < units && st < LS) compute_lr(ring[i], st, acc[(l0 + i) % TS]);
-        fetch(n + i + RING, ring[i]);
+    for (int ts = 0; ts < TS; ++ts) {         // the rank steps (none unless this block adds the term)
+      const bool unit_ok = grp + ts * groups < units;
+      for (int l0 = 0; l0 < sp.LSS; l0 += RING) {
+#pragma unroll
+        for (int i = 0; i < RING; ++i) {
+          const int st = (l0 + i) * kw + kwi;
+          if (unit_ok && st < LS) compute_lr(ring[i], st, acc[ts]);
+          fetch(n + i + RING, ring[i]);
+        }
+        n += RING;
       }
-      n += RING;
     }
 
     // ---- wavefronts that shared a unit add up their partial sums through LDS ----
@@ -373,8 +382,16 @@ __global__ __launch_bounds__(64 * kWaves, 4) void qgemm_decode_kernel(KArgs a) {
 
 template <bool DUAL>
 __global__ __launch_bounds__(1024) void xa_rows_kernel(KArgs a) {
-  __shared__ float4_t red[16][64];
-  xa_rows_body<DUAL, false, 16>(a, nullptr, blockIdx.x, blockIdx.y, red);
+  __shared__ float4_t red[32][64];
+  xa_rows_body<DUAL, false, 16>(a, nullptr, blockIdx.x, blockIdx.y, blockIdx.z, red);
+}
+
+// (x A1 | x A3) from the bf16 tokens in a launch of its own: the same body, block size and summation
+// order as the blocks of the preparing launch that normally do this, so that a layer whose factors
+// arrive late (staged residency) gets the same bits.
+__global__ __launch_bounds__(1024) void xa13_tokens_kernel(KArgs a, const uint16_t* __restrict__ x_bf16) {
+  __shared__ float4_t red[32][64];
+  xa_rows_body<true, true, 16>(a, x_bf16, blockIdx.x, blockIdx.y, 0, red);
 }
 
 // y_rows[R][n] = bf16(sum over K-blocks of partial[kb][R][n]), K-blocks in order (deterministic).
@@ -419,9 +436,11 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
     a.in_rt = f.x_rt; a.out_rt = f.h_rt;
     a.KS = padded_k(f.H) / kTileK; a.G = padded_k(f.H) / f.group;
     a.p = f.p13;
-    // ((x A1 | x A3) has been made by the launch that prepared the activations)
-    if (f.marks) (void)hipEventRecord(f.marks[0], s);
     a.kb_steps = a.KS; a.partial = nullptr;
+    // ((x A1 | x A3) has been made by the launch that prepared the activations, unless it is asked for here)
+    if (comp && f.xa13_here)
+      hipLaunchKernelGGL(xa13_tokens_kernel, dim3(4 * a.ls, f.n_exp), dim3(1024), 0, s, a, (const uint16_t*)f.x_tokens);
+    if (f.marks) (void)hipEventRecord(f.marks[0], s);
     if (by_table) {
       a.plan = f.plan;
       hipLaunchKernelGGL((qgemm_decode_kernel<BITS, true>), dim3(plan_blocks(f.n_exp, pairs, a.NT, f.n_cu), 1, 1), dim3(64 * kWaves), lds, s, a);
@@ -437,13 +456,15 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
     a.in_rt = f.h_rt; a.out_rt = 0;
     a.KS = padded_k(f.F) / kTileK; a.G = padded_k(f.F) / f.group;
     a.p = f.p2;
-    if (comp) hipLaunchKernelGGL(xa_rows_kernel<false>, dim3(2 * a.ls, f.n_exp), dim3(1024), 0, s, a);
-    if (f.marks) (void)hipEventRecord(f.marks[2], s);
     // a long K (many phases of staged activations) is split into K-blocks of one 16-k-step phase each;
-    // their fp32 partial outputs are added by the combine, or by reduce_kernel when y_rows is wanted
+    // their fp32 partial outputs are added by the combine, or by reduce_kernel when y_rows is wanted.
+    // The rank-r term is linear in (h A2): every K-block adds B2 times the part of (h A2) over its own
+    // k-steps, so (h A2) needs no sum over the K-blocks either.
     const int kblocks = decode_w2_kblocks(f);
     a.kb_steps = (a.KS + kblocks - 1) / kblocks;
     a.partial = kblocks > 1 ? f.y_part : nullptr;
+    if (comp) hipLaunchKernelGGL(xa_rows_kernel<false>, dim3(2 * a.ls, f.n_exp, kblocks), dim3(1024), 0, s, a);
+    if (f.marks) (void)hipEventRecord(f.marks[2], s);
     if (by_table) {
       // (second table behind the first; every K-block uses the same shares)
       a.plan = f.plan + kPlanEntryInts * plan_blocks(f.n_exp, pairs, f.F / kTileN, f.n_cu);
@@ -478,11 +499,11 @@ void decode_plan_specs(const FfnArgs& f, int which, PlanSpec& p13, PlanSpec& p2)
   if (f.offsets == nullptr || f.plan == nullptr) return;
   const int pairs = f.T * f.top_k, NT13 = f.F / kTileN, NT2 = f.H / kTileN;
   const int B13 = plan_blocks(f.n_exp, pairs, NT13, f.n_cu);
-  if (which & 1) p13 = PlanSpec{B13, (NT13 + 31) / 32, f.n_cu, f.plan};
+  if (which & 1) p13 = PlanSpec{B13, NT13, f.n_cu, f.plan};
   if (which & 2) {
     const int kb2 = decode_w2_kblocks(f);
     const int target2 = (f.n_cu + kb2 - 1) / kb2;
-    p2 = PlanSpec{plan_blocks(f.n_exp, pairs, NT2, target2), (NT2 + 31) / 32, target2, f.plan + kPlanEntryInts * B13};
+    p2 = PlanSpec{plan_blocks(f.n_exp, pairs, NT2, target2), NT2, target2, f.plan + kPlanEntryInts * B13};
   }
 }
 

@@ -118,6 +118,10 @@ struct FfnArgs {
   void* y_rows;               // [rows][H] bf16
   float* y_part;              // fp32 partial outputs of the W2 K-blocks (decode flavour), or null
   int32_t* plan;              // decode flavour, routed experts: the block tables (plan.h) of the two projections
+  const void* x_tokens;       // the bf16 tokens [T][H] (routed launches)
+  int xa13_here;              // decode flavour of W1|W3: (x A1 | x A3) is made by a launch of its own in front of the
+                              // FFN kernel (staged layers: the factors arrive after the preparing launch) instead
+                              // of by further blocks of the preparing launch
   int keep_partials;          // decode flavour, W2 split into K-blocks: leave the fp32 partial sums in y_part for
                               // the combine instead of adding them into y_rows
   int ksplit13, ksplit2, total_rows;

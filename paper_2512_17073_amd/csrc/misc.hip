@@ -75,25 +75,27 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict
 // Blocks 0..ceil(rows/16)-1 write the fp16 copy of sixteen rows' tokens in operand order (the layout
 // the FFN kernels stage from, see act_unit in ffn_common.h): row R of the routed rows is the token
 // of pair row_pair[R]; without row_pair, row R is token R.  Thread (row r = t % 16, column lane
-// t / 16) converts the 16-byte units t / 16, t / 16 + 16, ... of its row: a wavefront reads 64
+// t / 16) converts the 16-byte units t / 16, t / 16 + 64, ... of its row: a wavefront reads 64
 // contiguous bytes of each of its rows and writes runs of 256 bytes (sixteen rows of one unit).
 // The blocks after those count, one wavefront per expert, the routed rows and the rows that take
 // the rank-r term (what the router-guided transfer must bring in): stat = [-, -, rows[E], comp rows[E]].
 // Then one block makes the block tables of the decode launches (plan.h), and xa_tiles * E further
 // blocks compute (x A1 | x A3) for the decode flavour of the fused projection from the bf16 tokens
 // (xa_rows.h), so that no launch of its own stands between this one and the W1|W3 kernel.
-__global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ x, int rows, int H,
+constexpr int kPrepThreads = 1024;
+__global__ __launch_bounds__(kPrepThreads) void prep_kernel(const uint16_t* __restrict__ x, int rows, int H,
                                                    uint4* __restrict__ xg, int rt,
                                                    const int32_t* __restrict__ offsets,
                                                    const int32_t* __restrict__ row_pair, int E, int top_k,
                                                    int top_n, int32_t* __restrict__ stat, PlanSpec plan0,
                                                    PlanSpec plan1, int xa_tiles, ffn::KArgs xa) {
-  __shared__ ffn::float4_t red[4][64];
+  __shared__ ffn::float4_t red[2 * kPrepThreads / 64][64];
+  constexpr int kWavesPerBlock = kPrepThreads / 64, kColLanes = kPrepThreads / 16;
   const int row_blocks = (rows + 15) / 16;
-  const int stat_blocks = stat ? (E + 3) / 4 : 0, plan_block = plan0.B + plan1.B > 0 ? 1 : 0;
+  const int stat_blocks = stat ? (E + kWavesPerBlock - 1) / kWavesPerBlock : 0, plan_block = plan0.B + plan1.B > 0 ? 1 : 0;
   if ((int)blockIdx.x >= row_blocks + stat_blocks + plan_block) {          // (x A1 | x A3)
     const int i = (int)blockIdx.x - (row_blocks + stat_blocks + plan_block);
-    if (blockIdx.y == 0) ffn::xa_rows_body<true, true, 4>(xa, x, i % xa_tiles, i / xa_tiles, red);
+    if (blockIdx.y == 0) ffn::xa_rows_body<true, true, kWavesPerBlock>(xa, x, i % xa_tiles, i / xa_tiles, 0, red);
     return;
   }
   if (plan_block && (int)blockIdx.x == row_blocks + stat_blocks) {         // the block tables (plan.h)
@@ -101,7 +103,7 @@ __global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ 
     return;
   }
   if ((int)blockIdx.x >= row_blocks) {
-    const int e = ((int)blockIdx.x - row_blocks) * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int e = ((int)blockIdx.x - row_blocks) * kWavesPerBlock + (threadIdx.x >> 6), lane = threadIdx.x & 63;
     if (e >= E || blockIdx.y != 0) return;
     const int b = offsets[e], n = offsets[e + 1] - b;
     int comp = 0;
@@ -116,7 +118,7 @@ __global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ 
   const int t = row_pair ? row_pair[R] / top_k : R;
   const uint4* xrow = reinterpret_cast<const uint4*>(x + size_t(t) * H);
   // (grid.y splits the columns when there are few rows, so that the launch still fills the chip)
-  for (int k8 = blockIdx.y * 16 + (threadIdx.x >> 4); k8 < H / 8; k8 += 16 * gridDim.y) {
+  for (int k8 = blockIdx.y * kColLanes + (threadIdx.x >> 4); k8 < H / 8; k8 += kColLanes * gridDim.y) {
     const uint4 v = xrow[k8];
     const uint32_t in[4] = {v.x, v.y, v.z, v.w};
     uint32_t o[4];
@@ -252,7 +254,7 @@ hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _
   const moe_lrc_config& c = L->cfg;
   const int rows = row_pair ? T * c.top_k : T;
   const int row_blocks = (rows + 15) / 16;
-  const int ky = std::max(1, std::min(c.hidden / 128, L->n_cu / std::max(1, row_blocks)));
+  const int ky = std::max(1, std::min(c.hidden / (8 * (kPrepThreads / 16)), L->n_cu / std::max(1, row_blocks)));
   const PlanSpec none{0, 0, 0, nullptr};
   const PlanSpec p0 = plans ? plans[0] : none, p1 = plans ? plans[1] : none;
   const int plan_block = p0.B + p1.B > 0 ? 1 : 0;
@@ -263,10 +265,12 @@ hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _
     const FfnArgs& f = *xa13;
     xa.desc = f.desc; xa.offsets = f.offsets; xa.row_pair = f.row_pair; xa.top_k = f.top_k; xa.top_n = f.top_n;
     xa.rank = f.rank; xa.ls = (f.rank + 31) / 32; xa.K = f.H; xa.p = f.p13; xa.total_rows = f.total_rows;
+    xa.kb_steps = (f.H + kTileK - 1) / kTileK;
     xa_tiles = 4 * xa.ls;
   }
-  hipLaunchKernelGGL(prep_kernel, dim3(row_blocks + (stat ? (c.n_experts + 3) / 4 : 0) + plan_block + xa_tiles * c.n_experts, ky),
-                     dim3(256), 0, s, (const uint16_t*)x_bf16, rows, c.hidden, reinterpret_cast<uint4*>(xg), rt, offsets,
+  const int stat_blocks = stat ? (c.n_experts + kPrepThreads / 64 - 1) / (kPrepThreads / 64) : 0;
+  hipLaunchKernelGGL(prep_kernel, dim3(row_blocks + stat_blocks + plan_block + xa_tiles * c.n_experts, ky),
+                     dim3(kPrepThreads), 0, s, (const uint16_t*)x_bf16, rows, c.hidden, reinterpret_cast<uint4*>(xg), rt, offsets,
                      row_pair, c.n_experts, c.top_k, c.top_n, stat, p0, p1, xa_tiles, xa);
   return hipGetLastError();
 }

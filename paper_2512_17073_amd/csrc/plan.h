@@ -14,15 +14,18 @@
 
 namespace lrc {
 
-struct PlanSpec { int B, base, target; int32_t* plan; };   // B entries; plan == null: no table wanted
+struct PlanSpec { int B, NT, target; int32_t* plan; };     // B entries for a projection of NT n-tiles; plan == null: no table wanted
 struct PlanEntry { int32_t e, b, G, r0, cnt, pad0, pad1, pad2; };
 constexpr int kPlanEntryInts = 8;
 
 __device__ inline void make_plan(const int32_t* __restrict__ offsets, int E, const PlanSpec sp, int lane) {
   if (sp.plan == nullptr) return;
-  const int B = sp.B, base = sp.base, target = sp.target;
+  const int B = sp.B, target = sp.target;
   int32_t* __restrict__ plan = sp.plan;
-  auto weight = [](int cnt) { return cnt == 0 ? 0 : cnt <= 16 ? 5 : 8 * ((cnt + 31) / 32); };
+  // what an expert's rows cost: every 32-row pass streams the expert's weights again
+  auto weight = [](int cnt) { return (cnt + 31) / 32; };
+  // fewest blocks an expert needs: a block owns at most 32 n-tiles
+  auto base_of = [&](int cnt) { return cnt == 0 ? 0 : (sp.NT + 31) / 32; };
   auto scan = [&](int v) {
 #pragma unroll
     for (int dlt = 1; dlt < 64; dlt *= 2) {
@@ -31,27 +34,39 @@ __device__ inline void make_plan(const int32_t* __restrict__ offsets, int E, con
     }
     return v;
   };
-  int n_active = 0, wsum = 0;
+  int n_active = 0, wsum = 0, base_sum = 0;
   for (int e0 = 0; e0 < E; e0 += 64) {
     const int e = e0 + lane;
     const int cnt = e < E ? offsets[e + 1] - offsets[e] : 0;
     n_active += __popcll(__ballot(cnt > 0));
     wsum += __shfl(scan(weight(cnt)), 63);
+    base_sum += __shfl(scan(base_of(cnt)), 63);
   }
   // as many blocks as fill the chip (`target`), more only if the experts with rows need them; the
-  // rest of the grid exits at once
-  const int total = min(B, max(target, n_active * base));
-  const long long extra = total - n_active * base;
-  int act_before = 0, w_before = 0;
+  // rest of the grid exits at once.  Every expert gets its fewest blocks or its share by weight of
+  // all the blocks, whichever is more (the shares by weight are then scaled down to what is left).
+  const int total = min(B, max(target, base_sum));
+  int over = 0;                                  // sum over experts of max(0, share by weight - fewest)
+  for (int e0 = 0; e0 < E; e0 += 64) {
+    const int e = e0 + lane;
+    const int cnt = e < E ? offsets[e + 1] - offsets[e] : 0;
+    const int want = wsum > 0 ? int((long long)total * weight(cnt) / wsum) : 0;
+    over += __shfl(scan(max(0, want - base_of(cnt))), 63);
+  }
+  const long long extra = total - base_sum;
+  int act_before = 0, w_before = 0, b_before = 0;
   for (int e0 = 0; e0 < E; e0 += 64) {
     const int e = e0 + lane;
     const int cnt = e < E ? offsets[e + 1] - offsets[e] : 0;
     const int r0 = e < E ? offsets[e] : 0;
-    const int act = cnt > 0 ? 1 : 0, w = weight(cnt), wi = scan(w), ai = scan(act);
+    const int act = cnt > 0 ? 1 : 0, ai = scan(act), base = base_of(cnt), bi = scan(base);
+    // this expert's claim on the blocks beyond the fewest: what its share by weight exceeds them by
+    const int want = wsum > 0 ? int((long long)total * weight(cnt) / wsum) : 0;
+    const int w = max(0, want - base), wi = scan(w);
     int lo = 0, hi = 0;
     if (act) {
-      lo = (act_before + ai - 1) * base + int(extra * (w_before + wi - w) / wsum);
-      hi = (act_before + ai) * base + int(extra * (w_before + wi) / wsum);
+      lo = b_before + bi - base + (over > 0 ? int(extra * (w_before + wi - w) / over) : 0);
+      hi = b_before + bi + (over > 0 ? int(extra * (w_before + wi) / over) : 0);
     }
     const unsigned long long with_rows = __ballot(act != 0);
     if (__popcll(with_rows) <= 8) {
@@ -67,9 +82,10 @@ __device__ inline void make_plan(const int32_t* __restrict__ offsets, int E, con
       // many experts with few blocks each: every lane writes its own expert's entries
       for (int i = lo; i < hi && i < B; ++i) reinterpret_cast<PlanEntry*>(plan)[i] = PlanEntry{e, i - lo, hi - lo, r0, cnt, 0, 0, 0};
     }
-    act_before += __shfl(ai, 63); w_before += __shfl(wi, 63);
+    act_before += __shfl(ai, 63); w_before += __shfl(wi, 63); b_before += __shfl(bi, 63);
   }
-  const int used = n_active > 0 ? n_active * base + int(extra) : 0;
+  (void)act_before;
+  const int used = n_active > 0 ? base_sum + (over > 0 ? int(extra) : 0) : 0;
   for (int i = used + lane; i < B; i += 64) reinterpret_cast<PlanEntry*>(plan)[i] = PlanEntry{-1, 0, 1, 0, 0, 0, 0, 0};
 }
 

@@ -44,7 +44,7 @@ std::string check_shape(const Shape& sh) {
   for (int kb = 0; kb < sh.kblocks; ++kb) {
     const int ks_lo = kb * kb_steps, KSl = std::min(KS, ks_lo + kb_steps) - ks_lo;
     if (KSl <= 0) SELF_FAIL("K-block %d of %d has no k-step", kb, sh.kblocks);
-    const bool lowrank = kb == 0 && (sh.LSm[0] > 0 || sh.LSm[1] > 0);
+    const bool lowrank = sh.LSm[0] > 0 || sh.LSm[1] > 0;
     const int LS = lowrank ? std::max(sh.LSm[0], sh.LSm[1]) : 0;
     std::vector<int> seen(size_t(KSl) * NT * 2, 0), seen_lr(size_t(std::max(LS, 1)) * NT * 2, 0);
     for (int b = 0; b < sh.G; ++b) {
@@ -52,9 +52,9 @@ std::string check_shape(const Shape& sh) {
       block_tiles(b, sh.G, NT, t0, t1);
       const int nt_b = t1 - t0;
       if (nt_b == 0) continue;
-      if (nt_b > 32) SELF_FAIL("block %d of %d owns %d n-tiles (at most 32)", b, sh.G, nt_b);
+      if (nt_b > max_block_tiles(MT)) SELF_FAIL("block %d of %d owns %d n-tiles (at most %d)", b, sh.G, nt_b, max_block_tiles(MT));
       const int units = block_units(nt_b, sh.dual), kw = waves_per_unit(units), groups = kWaves / kw;
-      if (units > groups * unit_slots(sh.dual)) SELF_FAIL("%d units do not fit %d wavefront groups", units, groups);
+      if (units > groups * unit_slots(sh.dual, MT)) SELF_FAIL("%d units do not fit %d wavefront groups", units, groups);
       const StepPlan sp = step_plan(KSl, MT, kw, LS, sh.dual);
       const int p_frags = NP * LS * MT;
       const bool p_late = p_frags * 64 > kSpareUnits;

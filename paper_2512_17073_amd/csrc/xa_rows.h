@@ -17,8 +17,8 @@ namespace ffn {
 // row_pair (the launch that prepares the activations runs this body in further blocks); otherwise
 // from the fp16 operand-order buffer.
 template <bool DUAL, bool TOKENS, int NW>
-__device__ __forceinline__ void xa_rows_body(const KArgs& a, const uint16_t* __restrict__ x_bf16, int tile, int e,
-                                             float4_t (*red)[64]) {
+__device__ __forceinline__ void xa_rows_body(const KArgs& a, const uint16_t* __restrict__ x_bf16, int tile, int e, int kb,
+                                             float4_t (*red)[64] /* [2 * NW][64] */) {
   const int r0 = a.offsets[e], cnt = a.offsets[e + 1] - r0;
   const ExpertDesc& d = a.desc[e];
   if (cnt == 0 || !d.has_factors) return;
@@ -40,63 +40,86 @@ __device__ __forceinline__ void xa_rows_body(const KArgs& a, const uint16_t* __r
   const bool live = 16 * tl < rank;
   const float lam = d.lambda[mat];
   const half8_t* af = reinterpret_cast<const half8_t*>(d.af[mat]);
-  const int k32 = a.K / 32, per = (k32 + NW - 1) / NW;
-  const int kk0 = wave * per, kk1 = min(k32, kk0 + per);
-  _Float16* P = reinterpret_cast<_Float16*>(const_cast<float*>(a.p));
+  // this block's K-block (grid.z K-blocks of kb_steps k-steps each; one when kb_steps covers K): the
+  // FFN kernel's K-block kb applies the B factor to the part of (in A) summed over its own k-steps
+  const int k32 = a.K / 32, kb_lo = min(k32, kb * a.kb_steps * 8), kb_hi = min(k32, (kb + 1) * a.kb_steps * 8);
+  const int per = (kb_hi - kb_lo + NW - 1) / NW;
+  const int kk0 = kb_lo + wave * per, kk1 = min(kb_hi, kk0 + per);
+  _Float16* P = reinterpret_cast<_Float16*>(const_cast<float*>(a.p)) + size_t(kb) * a.total_rows * pitch;
   const half8_t* src = reinterpret_cast<const half8_t*>(a.in);   // operand order: unit (k8, row)
-  for (int r = 0; r < cnt; r += 16) {
-    const int row = r + c;
-    bool flagged = false;
-    int pair = 0;
-    if (row < cnt) { pair = a.row_pair[r0 + row]; flagged = (pair % a.top_k) < a.top_n; }
-    const bool any = __ballot(flagged) != 0ull;      // same rows in every wavefront: block-uniform
-    float4_t acc = float4_t{0.f, 0.f, 0.f, 0.f};
-    if (live && any) {
-      const uint4* xrow = TOKENS ? reinterpret_cast<const uint4*>(x_bf16 + size_t(pair / a.top_k) * a.K) : nullptr;
-      for (int kk = kk0; kk < kk1; kk += 8) {        // eight steps of loads in flight
-        half8_t wf[8], xf[8];
+  // Two row tiles share every load of the factor; all loads of a batch are issued before the first
+  // is awaited (unconditional loads from clamped addresses, cleared afterwards where they do not count).
+  for (int r = 0; r < cnt; r += 32) {
+    bool flagged[2];
+    int pair[2];
+    const uint4* xrow[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int row = min(r + 16 * t + c, cnt - 1);
+      pair[t] = a.row_pair[r0 + row];
+      flagged[t] = r + 16 * t + c < cnt && (pair[t] % a.top_k) < a.top_n;
+      xrow[t] = TOKENS ? reinterpret_cast<const uint4*>(x_bf16 + size_t(pair[t] / a.top_k) * a.K) : nullptr;
+    }
+    const bool any0 = __ballot(flagged[0]) != 0ull, any1 = __ballot(flagged[1]) != 0ull;   // block-uniform
+    float4_t acc[2] = {float4_t{0.f, 0.f, 0.f, 0.f}, float4_t{0.f, 0.f, 0.f, 0.f}};
+    if (live && (any0 || any1)) {
+      for (int kk = kk0; kk < kk1; kk += 8) {
+        half8_t wf[8], xf[2][8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-          wf[u] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
-          xf[u] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
-          if (kk + u < kk1) {
-            wf[u] = af[(size_t(tl) * k32 + kk + u) * kWave + lane];
-            if (flagged) {
-              if constexpr (TOKENS) {
-                const uint4 v = xrow[4 * (kk + u) + q];
-                const uint32_t in[4] = {v.x, v.y, v.z, v.w};
+          const int ku = max(min(kk + u, kk1 - 1), 0);
+          wf[u] = af[(size_t(tl) * k32 + ku) * kWave + lane];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                  xf[u][2 * i] = (_Float16)__uint_as_float(in[i] << 16);
-                  xf[u][2 * i + 1] = (_Float16)__uint_as_float(in[i] & 0xffff0000u);
-                }
-              } else {
-                xf[u] = src[act_unit(4 * (kk + u) + q, r0 + row, a.in_rt)];
+          for (int t = 0; t < 2; ++t) {
+            if (t == 1 && !any1) { xf[t][u] = half8_t{0, 0, 0, 0, 0, 0, 0, 0}; continue; }
+            if constexpr (TOKENS) {
+              const uint4 v = xrow[t][4 * ku + q];
+              const uint32_t in[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                xf[t][u][2 * i] = (_Float16)__uint_as_float(in[i] << 16);
+                xf[t][u][2 * i + 1] = (_Float16)__uint_as_float(in[i] & 0xffff0000u);
               }
+            } else {
+              xf[t][u] = src[act_unit(4 * ku + q, r0 + min(r + 16 * t + c, cnt - 1), a.in_rt)];
             }
           }
         }
 #pragma unroll
-        for (int u = 0; u < 8; ++u) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[u], xf[u], acc, 0, 0, 0);
+        for (int u = 0; u < 8; ++u) {
+          if (kk + u >= kk1) wf[u] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};       // (a step past this wavefront's share)
+#pragma unroll
+          for (int t = 0; t < 2; ++t) {
+            if (!flagged[t]) xf[t][u] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[u], xf[t][u], acc[t], 0, 0, 0);
+          }
+        }
       }
-      red[wave][lane] = acc;
+      red[wave][lane] = acc[0];
+      red[NW + wave][lane] = acc[1];
       __syncthreads();
       if (wave == 0) {
-        acc = red[0][lane];
+        acc[0] = red[0][lane];
+        acc[1] = red[NW][lane];
 #pragma unroll
-        for (int w = 1; w < NW; ++w) acc += red[w][lane];
+        for (int w = 1; w < NW; ++w) { acc[0] += red[w][lane]; acc[1] += red[NW + w][lane]; }
       }
       __syncthreads();
     }
-    // lane (q, c) of wavefront 0 holds columns 16 tl + 4 q .. + 3 of row c
-    if (wave == 0 && row < cnt) {
-      half4_t v = half4_t{0, 0, 0, 0};
-      if (flagged && live) v = half4_t{(_Float16)(acc[0] * lam), (_Float16)(acc[1] * lam), (_Float16)(acc[2] * lam), (_Float16)(acc[3] * lam)};
-      *reinterpret_cast<half4_t*>(P + size_t(r0 + row) * pitch + m * a.ls * 32 + 16 * tl + 4 * q) = v;
+    // lane (q, c) of wavefront 0 holds columns 16 tl + 4 q .. + 3 of rows r + c and r + 16 + c
+    if (wave == 0) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const int row = r + 16 * t + c;
+        if (row >= cnt) continue;
+        half4_t v = half4_t{0, 0, 0, 0};
+        if (flagged[t] && live)
+          v = half4_t{(_Float16)(acc[t][0] * lam), (_Float16)(acc[t][1] * lam), (_Float16)(acc[t][2] * lam), (_Float16)(acc[t][3] * lam)};
+        *reinterpret_cast<half4_t*>(P + size_t(r0 + row) * pitch + m * a.ls * 32 + 16 * tl + 4 * q) = v;
+      }
     }
   }
 }
-
 
 }  // namespace ffn
 }  // namespace lrc

@@ -27,7 +27,8 @@ def test_index_model_over_ranks_and_shares(hidden, ffn):
         for ranks in sorted(rank_sets):
             for rows, first in ((1, 0), (16, 5), (17, 0), (33, 2)) if not big else ((19, 3),):
                 nt13, nt2 = ffn // 16, hidden // 16
-                for g13, g2 in ((max(1, (nt13 + 31) // 32), max(1, (nt2 + 31) // 32)), (nt13, nt2), (max(2, nt13 // 5), max(2, nt2 // 3))):
+                per = 32                                       # n-tiles a block can own
+                for g13, g2 in (((nt13 + per - 1) // per, (nt2 + per - 1) // per), (nt13, nt2), (max(2, nt13 // 5), max(2, nt2 // 3))):
                     amd.selftest_decode_index(hidden, ffn, bits, group, layer_rank, ranks, first, rows, first + rows + 7,
                                               g13, g2, _kblocks(ffn))
 
