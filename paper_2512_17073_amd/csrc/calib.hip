@@ -40,17 +40,22 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restric
 }
 
 // Dense f16 matrix-core rate: every wavefront issues `iters` rounds of eight independent
-// v_mfma_f32_16x16x32_f16 on registers (no memory traffic).
+// v_mfma_f32_16x16x32_f16 on registers (no memory traffic).  The scheduling barriers keep the eight
+// accumulators apart (left alone, the compiler rotates them through overlapping registers, which
+// chains the instructions and halves the rate).
 __global__ __launch_bounds__(256) void mfma_rate_kernel(int iters, float* __restrict__ sink) {
   half8_t a, b;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) { a[i] = (_Float16)(0.001f * float(threadIdx.x + i)); b[i] = (_Float16)(0.002f * float(i + 1)); }
+  for (int i = 0; i < 8; ++i) { a[i] = (_Float16)(0.001f * float((threadIdx.x + i) & 63)); b[i] = (_Float16)(0.002f * float(i + 1)); }
   float4_t acc[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) acc[j] = float4_t{0.f, 0.f, 0.f, 0.f};
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, acc[j], 0, 0, 0);
+    for (int j = 0; j < 8; ++j) {
+      acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, acc[j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   }
   float s = 0.f;
 #pragma unroll
@@ -63,7 +68,7 @@ typedef float float16_t __attribute__((ext_vector_type(16)));
 __global__ __launch_bounds__(256) void mfma_rate32_kernel(int iters, float* __restrict__ sink) {
   half8_t a, b;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) { a[i] = (_Float16)(0.001f * float(threadIdx.x + i)); b[i] = (_Float16)(0.002f * float(i + 1)); }
+  for (int i = 0; i < 8; ++i) { a[i] = (_Float16)(0.001f * float((threadIdx.x + i) & 63)); b[i] = (_Float16)(0.002f * float(i + 1)); }
   float16_t acc[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j)
@@ -71,7 +76,10 @@ __global__ __launch_bounds__(256) void mfma_rate32_kernel(int iters, float* __re
     for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[j], 0, 0, 0);
+    for (int j = 0; j < 4; ++j) {
+      acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   }
   float s = 0.f;
 #pragma unroll

@@ -8,11 +8,13 @@
 //   - a block of 8 wavefronts owns 128 rows of one expert x 256 output columns (of both W1 and W3
 //     in the fused kernel); a wavefront owns two n-tiles (16 columns each) for all 128 rows, so a
 //     tile of weights unpacked once in registers (unpack.h) feeds all the rows;
-//   - the products run on v_mfma_f32_32x32x16_f16, which this chip issues at twice the rate of the
-//     16x16x32 shape (measured: 2.3 against 1.2 PFLOP/s): two streams of 16 output columns that meet
-//     the same activations (W1 and W3 of one n-tile, or two n-tiles of W2) become the 32 rows of one
-//     A operand by a swap of 16-lane rows between their registers, which puts the same inputs of
-//     both streams side by side; the activations are staged as fragments of 32 rows;
+//   - the products run on v_mfma_f32_32x32x16_f16 (the same peak rate as the 16x16x32 shape, half
+//     as many MFMA and LDS-read instructions per flop, and on this chip the matrix pipe and the
+//     vector ALU share the wavefront's issue slots, so instructions saved are time saved): two
+//     streams of 16 output columns that meet the same activations (W1 and W3 of one n-tile, or two
+//     n-tiles of W2) become the 32 rows of one A operand by a swap of 16-lane rows between their
+//     registers, which puts the same inputs of both streams side by side; the activations are
+//     staged as fragments of 32 rows;
 //   - the packed weights never touch LDS: each wavefront streams its tiles HBM -> registers through
 //     a two-slot ring of buffer loads (a load past the end of the resource returns zeros, so the
 //     refills are unconditional and the waits static);
@@ -25,6 +27,7 @@
 // Experts with few rows (decode) take the other flavour, ffn_decode.hip.
 #include <algorithm>
 #include <type_traits>
+#include <utility>
 
 #include "ffn_common.h"
 #include "plan.h"
@@ -98,6 +101,15 @@ __device__ inline void stage_step(const KArgs& a, uint4* buf, int ks, int rin, i
 
 typedef float float16_t __attribute__((ext_vector_type(16)));
 constexpr int kRP = kBM / 32;             // 32-row fragments ("row pairs") of a chunk
+#ifndef TILE_LDS_PF
+#define TILE_LDS_PF 2                     // LDS fragment reads in flight ahead of the MFMAs
+#endif
+
+// fn(std::integral_constant<int, 0>{}) ... fn(std::integral_constant<int, N - 1>{})
+template <int... I, class Fn> __device__ inline void static_for_impl(std::integer_sequence<int, I...>, Fn&& fn) {
+  (fn(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class Fn> __device__ inline void static_for(Fn&& fn) { static_for_impl(std::make_integer_sequence<int, N>{}, fn); }
 
 // The same k-step as fragments for the 32x32x16 products: fragment (row pair rp, sub-step s, operand p)
 // at unit ((rp * 8 + s) * 2 + p) * 64; lane l holds, of row 32 rp + l % 32, the 8 inputs of lane
@@ -220,61 +232,21 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
       for (int i = 0; i < 16; ++i) acc[j][rp][i] = 0.f;
   const int rp_n = min(kRP, (cnt - r + 31) >> 5);         // row pairs that hold rows of this expert
 
-  // The fragments (rp, p) of a sub-step meet the operands of all pairs.  The read of the next
-  // fragment is issued before the MFMAs of the current one.
-  auto mfma_rows = [&](const uint32_t (&A)[2][NPAIR][4], uint32_t base) {   // base: LDS byte address of fragment (0, s, 0), this lane
-    half8_t xf[2];
-    auto mm = [&](int f, const half8_t& x) {
-#pragma unroll
-      for (int j = 0; j < NPAIR; ++j) {
-        const half8_t av = __builtin_bit_cast(half8_t, make_uint4(A[f & 1][j][0], A[f & 1][j][1], A[f & 1][j][2], A[f & 1][j][3]));
-        acc[j][f >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, x, acc[j][f >> 1], 0, 0, 0);
-      }
-    };
-    if (rp_n == kRP) {                    // a full chunk: straight-line, one read in flight
-      auto step = [&](auto F) {
-        constexpr int f = decltype(F)::value;
-        if constexpr (f + 1 < 2 * kRP) xf[(f + 1) & 1] = lds_read16<((f + 1) >> 1) * 16384 + ((f + 1) & 1) * 1024>(base);
-        lds_wait<(f + 1 < 2 * kRP ? 1 : 0)>(xf[f & 1]);
-        mm(f, xf[f & 1]);
-      };
-      xf[0] = lds_read16<0>(base);
-      step(std::integral_constant<int, 0>{}); step(std::integral_constant<int, 1>{});
-      step(std::integral_constant<int, 2>{}); step(std::integral_constant<int, 3>{});
-      step(std::integral_constant<int, 4>{}); step(std::integral_constant<int, 5>{});
-      step(std::integral_constant<int, 6>{}); step(std::integral_constant<int, 7>{});
-      return;
-    }
-    // a partly filled chunk: only the row pairs that hold rows
-    xf[0] = lds_read16<0>(base);
-    auto step = [&](auto F) {
-      constexpr int f = decltype(F)::value;
-      if ((f >> 1) >= rp_n) return;
-      if constexpr (f + 1 < 2 * kRP) {
-        if (((f + 1) >> 1) < rp_n) {
-          xf[(f + 1) & 1] = lds_read16<((f + 1) >> 1) * 16384 + ((f + 1) & 1) * 1024>(base);
-          lds_wait<1>(xf[f & 1]);
-        } else {
-          lds_wait<0>(xf[f & 1]);
-        }
-      } else {
-        lds_wait<0>(xf[f & 1]);
-      }
-      mm(f, xf[f & 1]);
-    };
-    step(std::integral_constant<int, 0>{}); step(std::integral_constant<int, 1>{});
-    step(std::integral_constant<int, 2>{}); step(std::integral_constant<int, 3>{});
-    step(std::integral_constant<int, 4>{}); step(std::integral_constant<int, 5>{});
-    step(std::integral_constant<int, 6>{}); step(std::integral_constant<int, 7>{});
-  };
   // the two streams of pair j: (tile slot, projection)
   auto pair_stream = [](int j, int side, int& t, int& m) {
     if constexpr (DUAL) { t = j; m = side; }
     else { t = 2 * j + side; m = 0; }
   };
 
-  // one k-step: unpack 32 rows of the weight tiles per sub-step, multiply with all rows
-  auto compute = [&](const Slot2<BITS, NM, kNTW>& cur, const uint4* buf) {
+  // One k-step for a chunk with RPN row pairs that hold rows.  A sub-step (32 inputs per lane
+  // group) has F = 2 RPN fragments of activations, operand p major; fragment g of the k-step's
+  // 8 F is read from LDS kPF fragments ahead of its two MFMAs (one per pair), and the weights of
+  // the next sub-step are unpacked, a piece per fragment, behind the MFMAs of the current one, so
+  // that the matrix pipe, the LDS reads and the unpacking run side by side within a wavefront.
+  constexpr int kPF = TILE_LDS_PF;
+  auto compute = [&](auto RPN_, const Slot2<BITS, NM, kNTW>& cur, const uint4* buf) {
+    constexpr int RPN = decltype(RPN_)::value;
+    constexpr int F = 2 * RPN, G = 8 * F;
     uint32_t s2[kNTW][NM][NC], c2[kNTW][NM];
 #pragma unroll
     for (int t = 0; t < kNTW; ++t)
@@ -288,34 +260,52 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
         for (int p = 1; p < NC; ++p) s2[t][m][p] = pk_mul(s2[t][m][p - 1], step);
       }
     const uint32_t base = uint32_t(reinterpret_cast<uintptr_t>(buf + lane));
-    auto substep = [&](auto S) {
+    // LDS byte offset of fragment g: sub-step g / F, operand (g % F) / RPN, row pair (g % F) % RPN
+    auto frag_off = [](int g) constexpr { return (g / F) * 2048 + ((g % F) % RPN) * 16384 + ((g % F) / RPN) * 1024; };
+    half8_t xf[kPF + 1];
+    static_for<(kPF < G ? kPF : G)>([&](auto g) { xf[g] = lds_read16<frag_off(g)>(base); });
+    // piece (j, i) of a sub-step: operand register i of the two streams of pair j, before the swap
+    uint32_t v[NPAIR][2][4];
+    auto unpack_piece = [&](int s, int piece) {
+      const int j = piece / 4, i = piece % 4;
+#pragma unroll
+      for (int side = 0; side < 2; ++side) {
+        int t, m;
+        pair_stream(j, side, t, m);
+        v[j][side][i] = pk_fma(Extract<BITS>::field(cur.t[t].cw[m], 4 * s + i), s2[t][m][Extract<BITS>::cls(4 * s + i)], c2[t][m]);
+      }
+    };
+    constexpr int PIECES = NPAIR * 4;
+    static_for<PIECES>([&](auto pc) { unpack_piece(0, pc); });
+    static_for<8>([&](auto S) {
       constexpr int s = decltype(S)::value;
+      // rows of 16 lanes swapped between the two streams of a pair: operand 0 = lane groups q = 0, 2
+      // of both streams side by side, operand 1 = q = 1, 3
       uint32_t A[2][NPAIR][4];
 #pragma unroll
-      for (int j = 0; j < NPAIR; ++j) {
-        uint32_t v[2][4];
-#pragma unroll
-        for (int side = 0; side < 2; ++side) {
-          int t, m;
-          pair_stream(j, side, t, m);
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            v[side][i] = pk_fma(Extract<BITS>::field(cur.t[t].cw[m], 4 * s + i), s2[t][m][Extract<BITS>::cls(4 * s + i)], c2[t][m]);
-        }
-        // rows of 16 lanes swapped between the two streams: operand 0 = lane groups q = 0, 2 of both
-        // streams side by side, operand 1 = q = 1, 3
+      for (int j = 0; j < NPAIR; ++j)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const auto sw = __builtin_amdgcn_permlane16_swap(v[0][i], v[1][i], false, false);
+          const auto sw = __builtin_amdgcn_permlane16_swap(v[j][0][i], v[j][1][i], false, false);
           A[0][j][i] = sw[0]; A[1][j][i] = sw[1];
         }
-      }
-      mfma_rows(A, base + s * 2048);
-    };
-    substep(std::integral_constant<int, 0>{}); substep(std::integral_constant<int, 1>{});
-    substep(std::integral_constant<int, 2>{}); substep(std::integral_constant<int, 3>{});
-    substep(std::integral_constant<int, 4>{}); substep(std::integral_constant<int, 5>{});
-    substep(std::integral_constant<int, 6>{}); substep(std::integral_constant<int, 7>{});
+      __builtin_amdgcn_sched_barrier(0);
+      static_for<F>([&](auto Fi) {
+        constexpr int f = decltype(Fi)::value, g = s * F + f, p = f / RPN, rp = f % RPN;
+        if constexpr (g + kPF < G) xf[(g + kPF) % (kPF + 1)] = lds_read16<frag_off(g + kPF)>(base);
+        lds_wait<(G - 1 - g < kPF ? G - 1 - g : kPF)>(xf[g % (kPF + 1)]);
+#pragma unroll
+        for (int j = 0; j < NPAIR; ++j) {
+          const half8_t av = __builtin_bit_cast(half8_t, make_uint4(A[p][j][0], A[p][j][1], A[p][j][2], A[p][j][3]));
+          acc[j][rp] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, xf[g % (kPF + 1)], acc[j][rp], 0, 0, 0);
+        }
+        if constexpr (s < 7) {
+#pragma unroll
+          for (int pc = PIECES * f / F; pc < PIECES * (f + 1) / F; ++pc) unpack_piece(s + 1, pc);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      });
+    });
   };
 
   // ---- prologue: the first k-step of activations and the first two ring slots
@@ -332,21 +322,27 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
   //      copy of the next step's activations is issued into the other half of LDS (free since the
   //      barrier that ended the previous step), the current step is multiplied, its slot refilled;
   //      then only that refill may still be in flight (the copy has landed) and the barrier ends
-  //      the step.
+  //      the step.  One copy of the loop per number of row pairs, so that every count is static.
   const int steps = a.KS;
-  for (int s0 = 0; s0 < steps; s0 += 2) {
+  auto k_loop = [&](auto RPN_) {
+    for (int s0 = 0; s0 < steps; s0 += 2) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int step = s0 + i;
-      if (step < steps) {
-        stage_step32(a, xs + ((step + 1) & 1) * kStepUnits, step + 1, rin, wave, lane);
-        __builtin_amdgcn_sched_barrier(0);     // (the wait below counts the refill as the only later loads)
-        compute(ring[i], xs + (step & 1) * kStepUnits);
-        fetch(step + 2, ring[i]);
-        asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(kSlotOps) : "memory");
+      for (int i = 0; i < 2; ++i) {
+        const int step = s0 + i;
+        if (step < steps) {
+          stage_step32(a, xs + ((step + 1) & 1) * kStepUnits, step + 1, rin, wave, lane);
+          __builtin_amdgcn_sched_barrier(0);     // (the wait below counts the refill as the only later loads)
+          compute(RPN_, ring[i], xs + (step & 1) * kStepUnits);
+          fetch(step + 2, ring[i]);
+          asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(kSlotOps) : "memory");
+        }
       }
     }
-  }
+  };
+  if (rp_n == 4) k_loop(std::integral_constant<int, 4>{});
+  else if (rp_n == 3) k_loop(std::integral_constant<int, 3>{});
+  else if (rp_n == 2) k_loop(std::integral_constant<int, 2>{});
+  else k_loop(std::integral_constant<int, 1>{});
 
   // ---- rank steps.  (in A) of the chunk's rows, fp16 row-major in global memory (xa_tile_kernel
   //      has scaled it and zeroed the rows without the term), is copied into LDS as fragments of 32
