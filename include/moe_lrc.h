@@ -32,6 +32,15 @@
  *     [H][F]), 1 = W3 (up projection, [H][F]), 2 = W2 (down projection, [F][H]);
  *     E_i(x) = (silu(x W1) * (x W3)) W2.
  *   - bf16 / fp16 values cross the ABI as their uint16_t bit patterns.
+ *   - range: activations and outputs are bf16; inside, the matrix cores take fp16 operands and
+ *     accumulate in fp32.  Every input row x is multiplied by a power of two 2^s (s an integer within
+ *     +-60) that brings its largest magnitude into [1, 2), the fp32 results are multiplied by 2^-s
+ *     again, and the SwiGLU output h = silu(x W1) * (x W3) is held as fp16(h * 2^(2s)).  Consequences:
+ *     a row scaled by any power of two gives the correspondingly exact result while its largest
+ *     magnitude is between 2^-60 and 2^60; elements below 2^-14 of their row's largest magnitude lose
+ *     bits and those below 2^-24 of it count as zero; |h| * 2^(2s) saturates at 65504 (so with inputs of
+ *     order one, |h| up to 6e4; not reached by weights of the magnitudes of Section 4.1's models);
+ *     non-finite inputs give unspecified finite or non-finite outputs.
  */
 #ifndef MOE_LRC_H
 #define MOE_LRC_H
@@ -53,6 +62,10 @@ extern "C" {
 #define MOE_LRC_RESIDENT 0   /* packed experts live in device memory                      */
 #define MOE_LRC_STAGED   1   /* packed experts live in pinned host memory and are copied  */
                              /* per call through a device slot pool on a side stream      */
+#define MOE_LRC_POOLED   2   /* packed experts live in pinned host memory; the layer owns  */
+                             /* no device slots: it runs only as a member of a             */
+                             /* moe_lrc_stack, whose slot pool its experts share with the  */
+                             /* other layers and keep across calls                         */
 
 typedef struct {
   int32_t hidden;       /* H, multiple of 64, at most 16384                               */
@@ -70,7 +83,7 @@ typedef struct {
   int32_t renormalize;  /* 0: routing weights are the softmax-over-all scores (Section 2.1)
                            1: divided by their sum over the k selected                    */
   int32_t max_tokens;   /* largest T any call will pass                                   */
-  int32_t residency;    /* MOE_LRC_RESIDENT or MOE_LRC_STAGED                             */
+  int32_t residency;    /* MOE_LRC_RESIDENT, MOE_LRC_STAGED or MOE_LRC_POOLED             */
 } moe_lrc_config;
 
 typedef struct moe_lrc_layer moe_lrc_layer;
@@ -174,6 +187,56 @@ int moe_lrc_forward(moe_lrc_layer* layer, const void* x_bf16, int T, void* out_b
  * stream.  Same result as moe_lrc_forward, bit for bit. */
 #define MOE_LRC_NOALLOC_WS_BYTES (32u << 20)
 int moe_lrc_forward_noalloc(moe_lrc_layer* layer, const void* x_bf16, int T, void* out_bf16, void* stream);
+
+/* ---- a stack of layers decoding from host-resident experts (Section 4.3, case study 1) -------- */
+
+/* The regime of the paper's GPU-only offloading figures: the packed experts and compensators of
+ * every layer stay in (pinned) host memory, the device holds `slots` expert-sized slots shared by
+ * all layers, and a decode step walks the layers in order, bringing in what each layer's router
+ * selects: the packed codes of every expert that received a row, the factor pair only of experts
+ * that received a Top-n row (Section 3.2).  An expert found in a slot is not copied again (slots are
+ * kept across layers and steps, least recently used first out).  With MOE_LRC_STACK_PREFETCH, while
+ * layer l computes, layer l+1's gate is applied to layer l's input as a guess of its routing and the
+ * guessed experts are copied ahead on the copy stream; the guess never decides what is computed
+ * (the layer's own routing does), only what is already in a slot when it is needed.
+ * With MOE_LRC_STACK_RESIDUAL layer l+1's input is x_l + layer_l(x_l) (rounded once to bf16), else
+ * layer_l(x_l). */
+typedef struct moe_lrc_stack moe_lrc_stack;
+#define MOE_LRC_STACK_PREFETCH 1
+#define MOE_LRC_STACK_RESIDUAL 2
+
+/* layers: host array of n_layers (1..1024) layer handles created with residency MOE_LRC_POOLED on
+ * the current device, all with the same hidden size and max_tokens; a layer belongs to one stack.
+ * The stack does not own them: destroy the stack first, then the layers.  slots: device slots, at
+ * least min(n_experts, max_tokens * top_k) of the widest layer (what one layer can need at once);
+ * each holds one expert's packed codes, scales and zeros and its factor pair.  Allocates the slot
+ * pool, a workspace and two activation buffers on the device. */
+int moe_lrc_stack_create(moe_lrc_layer* const* layers, int n_layers, int slots, int flags, moe_lrc_stack** out);
+int moe_lrc_stack_destroy(moe_lrc_stack* stack);
+
+/* One decode step: x [T][hidden] bf16 (device) through every layer, result to out [T][hidden] bf16
+ * (device).  layer_inputs (device, [n_layers][T][hidden] bf16, or NULL) receives the input of every
+ * layer (layer 0's is x).  Synchronises `stream` once per layer (the read-back of the per-expert
+ * counts that decides the copies); all kernels run on `stream`, the copies on the stack's own stream.
+ * MOE_LRC_ESTATE if a layer's gate or an expert is not uploaded or T exceeds max_tokens. */
+int moe_lrc_stack_step(moe_lrc_stack* stack, const void* x_bf16, int T, void* out_bf16, void* layer_inputs, void* stream);
+
+typedef struct {
+  uint64_t steps;
+  uint64_t expert_uses;     /* (layer, expert) pairs that received a row, over all layers and steps      */
+  uint64_t hits;            /* ... whose packed weights were already in a slot                            */
+  uint64_t misses;          /* ... copied on demand, the layer's kernels waiting                          */
+  uint64_t prefetched;      /* experts copied ahead on the guess                                          */
+  uint64_t prefetch_hits;   /* hits on a slot that such a copy had filled and nothing had used yet        */
+  uint64_t factor_copies;   /* factor pairs copied, on demand or ahead                                    */
+  uint64_t bytes_h2d;       /* bytes copied host -> device by all of the above                            */
+  float    last_step_ms;    /* host wall time of the last step, read-backs included                       */
+  float    last_copy_ms;    /* first to last copy of the last step on the copy stream (0: none)           */
+} moe_lrc_stack_stats;
+/* Counters since moe_lrc_stack_create (or the last reset); waits for the last step's copies. */
+int moe_lrc_stack_get_stats(moe_lrc_stack* stack, moe_lrc_stack_stats* out);
+/* Empties every slot and zeroes the counters (a cold start). */
+int moe_lrc_stack_reset(moe_lrc_stack* stack);
 
 /* ---- evidence and test hooks ------------------------------------------------------------- */
 

@@ -1,5 +1,5 @@
 """MI355X-native MoE layer with router-guided low-rank compensation: HIP kernels behind a C ABI
 (libmoe_lrc.so) and a thin ctypes binding.  Importing the package does not load the library;
 the first call does, and raises if it has not been built."""
-from .binding import (RESIDENT, STAGED, Config, Layer, MoeLrcError, Stats, bf16_tensor, lib,  # noqa: F401
+from .binding import (RESIDENT, STAGED, POOLED, Stack, StackStats, Config, Layer, MoeLrcError, Stats, bf16_tensor, lib,  # noqa: F401
                       pack_codes, unpack_codes, calibrate, selftest_decode_index, CAL_HBM_READ, CAL_H2D, CAL_MFMA_F16, CAL_MFMA_F16_32)

@@ -15,7 +15,8 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmoe_lrc.so")
 
-RESIDENT, STAGED = 0, 1
+RESIDENT, STAGED, POOLED = 0, 1, 2
+STACK_PREFETCH, STACK_RESIDUAL = 1, 2
 
 # every symbol include/moe_lrc.h declares
 EXPORTS = [
@@ -25,6 +26,7 @@ EXPORTS = [
     "moe_lrc_packed_bytes", "moe_lrc_pack_codes", "moe_lrc_unpack_codes", "moe_lrc_get_stats",
     "moe_lrc_profile_enable", "moe_lrc_profile_read", "moe_lrc_calibrate",
     "moe_lrc_selftest_decode_index",
+    "moe_lrc_stack_create", "moe_lrc_stack_destroy", "moe_lrc_stack_step", "moe_lrc_stack_get_stats", "moe_lrc_stack_reset",
 ]
 STAGES = ["route", "permute", "prep", "xa13", "w13", "xa2", "w2", "shared", "combine"]
 
@@ -39,6 +41,11 @@ class Stats(C.Structure):
     _fields_ = [("bytes_codes", C.c_uint64), ("bytes_meta", C.c_uint64), ("bytes_factors", C.c_uint64),
                 ("active_experts", C.c_int32), ("comp_experts", C.c_int32), ("path", C.c_int32),
                 ("stage_ms", C.c_float)]
+
+
+class StackStats(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in ("steps", "expert_uses", "hits", "misses", "prefetched", "prefetch_hits",
+                                          "factor_copies", "bytes_h2d")] + [("last_step_ms", C.c_float), ("last_copy_ms", C.c_float)]
 
 
 class MoeLrcError(RuntimeError):
@@ -87,6 +94,11 @@ def lib() -> C.CDLL:
         L.moe_lrc_profile_read.argtypes = [vp, C.POINTER(C.c_float)]
         L.moe_lrc_calibrate.argtypes = [i32, sz, i32, C.POINTER(C.c_double)]
         L.moe_lrc_selftest_decode_index.argtypes = [i32] * 14
+        L.moe_lrc_stack_create.argtypes = [C.POINTER(vp), i32, i32, i32, C.POINTER(vp)]
+        L.moe_lrc_stack_destroy.argtypes = [vp]
+        L.moe_lrc_stack_step.argtypes = [vp, vp, i32, vp, vp, vp]
+        L.moe_lrc_stack_get_stats.argtypes = [vp, C.POINTER(StackStats)]
+        L.moe_lrc_stack_reset.argtypes = [vp]
         _lib = L
     return _lib
 
@@ -303,6 +315,48 @@ class Layer:
         s = Stats()
         _check(lib().moe_lrc_get_stats(self._h, C.byref(s)))
         return {n: getattr(s, n) for n, _ in Stats._fields_}
+
+
+class Stack:
+    """moe_lrc_stack: layers of residency POOLED decoding from host-resident experts through one
+    device slot pool.  Keeps the Layer objects alive; closes before them."""
+
+    def __init__(self, layers, slots: int, prefetch: bool = True, residual: bool = True):
+        self.layers = list(layers)
+        arr = (C.c_void_p * len(self.layers))(*[l._h for l in self.layers])
+        self._h = C.c_void_p()
+        flags = (STACK_PREFETCH if prefetch else 0) | (STACK_RESIDUAL if residual else 0)
+        _check(lib().moe_lrc_stack_create(arr, len(self.layers), int(slots), flags, C.byref(self._h)))
+
+    def close(self) -> None:
+        if self._h:
+            lib().moe_lrc_stack_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def step(self, x, out=None, layer_inputs=None):
+        """x [T][hidden] bf16 (device).  layer_inputs: optional [n_layers][T][hidden] bf16 tensor that
+        receives every layer's input."""
+        import torch
+        T = x.shape[0]
+        if out is None:
+            out = torch.empty_like(x)
+        li = layer_inputs.data_ptr() if layer_inputs is not None else None
+        _check(lib().moe_lrc_stack_step(self._h, x.data_ptr(), T, out.data_ptr(), li, _stream()))
+        return out
+
+    def stats(self) -> dict:
+        s = StackStats()
+        _check(lib().moe_lrc_stack_get_stats(self._h, C.byref(s)))
+        return {n: getattr(s, n) for n, _ in StackStats._fields_}
+
+    def reset(self) -> None:
+        _check(lib().moe_lrc_stack_reset(self._h))
 
 
 def bf16_tensor(bits: np.ndarray, device="cuda"):

@@ -21,13 +21,6 @@ int set_error(int code, const std::string& msg) {
   return code;
 }
 
-#define LRC_HIP(expr)                                                                       \
-  do {                                                                                      \
-    hipError_t e_ = (expr);                                                                 \
-    if (e_ != hipSuccess)                                                                   \
-      return set_error(MOE_LRC_EHIP, std::string(#expr) + ": " + hipGetErrorString(e_));    \
-  } while (0)
-
 static BlobLayout make_blob(const moe_lrc_config& c, int bits, int rank) {
   BlobLayout b{};
   size_t w = 0, f = 0;
@@ -60,7 +53,8 @@ static int check_config(const moe_lrc_config& c) {
   if (c.rank < 0 || c.rank > 1024 || c.rank % 8) return bad("rank must be a multiple of 8 in 0..1024");
   if (c.renormalize != 0 && c.renormalize != 1) return bad("renormalize must be 0 or 1");
   if (c.max_tokens < 1 || (long long)c.max_tokens * c.top_k > (1 << 24)) return bad("max_tokens out of range");
-  if (c.residency != MOE_LRC_RESIDENT && c.residency != MOE_LRC_STAGED) return bad("residency must be 0 or 1");
+  if (c.residency != MOE_LRC_RESIDENT && c.residency != MOE_LRC_STAGED && c.residency != MOE_LRC_POOLED)
+    return bad("residency must be MOE_LRC_RESIDENT, MOE_LRC_STAGED or MOE_LRC_POOLED");
   if (c.group != 64 && c.group != 128 && c.group != 256) return shape("group must be 64, 128 or 256");
   if (c.hidden % 64 || c.ffn % 64) return shape("hidden and ffn must be multiples of 64");
   if (c.hidden % c.group || c.ffn % c.group) return shape("hidden and ffn must be multiples of group");
@@ -92,12 +86,15 @@ Workspace plan_workspace(const moe_lrc_layer* L, int T) {
   w.sh_y_part = take(size_t(kMaxKBlocks) * c.n_shared * T * c.hidden * 4);   // (shared experts run beside the routed ones)
   w.sh_h = take(c.n_shared ? (size_t(c.n_shared) * T + kActPadRows) * Fp * 2 : 0);
   w.sh_y = take(size_t(c.n_shared) * T * c.hidden * 2);
+  w.tok_exp = take(size_t(T) * 4);
+  w.row_exp = take((P + kActPadRows) * 4);
+  w.row_exp_sh = take(c.n_shared ? (size_t(T) + kActPadRows) * 4 : 0);
   w.plan = take(size_t(plan_blocks(c.n_experts, int(P), c.ffn / 16, L->n_cu) + plan_blocks(c.n_experts, int(P), c.hidden / 16, L->n_cu)) * kPlanEntryInts * 4);
   w.total = o;
   return w;
 }
 
-static const BlobLayout& blob_of(const moe_lrc_layer* L, int expert) {
+const BlobLayout& blob_of(const moe_lrc_layer* L, int expert) {
   return expert < L->cfg.n_experts ? L->routed : L->shared;
 }
 
@@ -126,7 +123,7 @@ static int check_ws(const moe_lrc_layer* L, int T, const void* ws, size_t ws_byt
   return MOE_LRC_OK;
 }
 
-static void fill_algorithmic_stats(moe_lrc_layer* L, const int32_t* stat) {
+void fill_algorithmic_stats(moe_lrc_layer* L, const int32_t* stat) {
   const moe_lrc_config& c = L->cfg;
   const uint64_t P = 3ull * c.hidden * c.ffn;
   moe_lrc_stats& s = L->stats;
@@ -219,7 +216,8 @@ static int stage_selected(moe_lrc_layer* L, hipStream_t stream) {
 
 static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t* offsets,
                           const int32_t* row_pair, void* y_rows, uint8_t* ws, hipStream_t stream,
-                          bool mark = false, bool keep_partials = false, int* kblocks_out = nullptr) {
+                          bool mark = false, bool keep_partials = false, int* kblocks_out = nullptr,
+                          const int32_t* tok_exp = nullptr) {
   const moe_lrc_config& c = L->cfg;
   const Workspace w = plan_workspace(L, T);
   _Float16* xh = reinterpret_cast<_Float16*>(ws + w.xh);
@@ -237,6 +235,8 @@ static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t*
   a.plan = reinterpret_cast<int32_t*>(ws + w.plan);
   a.y_rows = y_rows; a.ksplit13 = L->ksplit13; a.ksplit2 = L->ksplit2; a.total_rows = T * c.top_k;
   a.n_cu = L->n_cu;
+  a.row_exp = reinterpret_cast<int32_t*>(ws + w.row_exp);
+  a.tok_exp = tok_exp;
   const int path = expert_ffn_path(a);
   // the combine can add the K-block partial sums of a decode-flavour W2 itself
   const int kblocks = (path & 2) ? 1 : decode_w2_kblocks(a);
@@ -246,14 +246,18 @@ static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t*
   // and, for the decode flavour of the fused projection, (x A1 | x A3)
   PlanSpec plans[2];
   expert_ffn_plan_specs(a, plans[0], plans[1]);
-  a.xa13_here = c.residency == MOE_LRC_STAGED;
+  // ((x A1 | x A3) from the tokens inside the preparing launch needs the exponents beforehand)
+  a.xa13_here = c.residency != MOE_LRC_RESIDENT || tok_exp == nullptr;
   a.x_tokens = x;
   LRC_HIP(launch_convert_x(L, x, T, xh, P + kActPadRows, offsets, row_pair, L->d_stat, plans,
-                           ((path & 1) || a.xa13_here) ? nullptr : &a, stream));
+                           ((path & 1) || a.xa13_here) ? nullptr : &a, tok_exp, a.row_exp, stream));
   L->stats_valid = false;
   L->stats.stage_ms = 0.f;
   if (c.residency == MOE_LRC_STAGED) {
     const int rc = stage_selected(L, stream);
+    if (rc) return rc;
+  } else if (c.residency == MOE_LRC_POOLED) {
+    const int rc = pool_stage(L, x, T, stream);
     if (rc) return rc;
   }
   if (mark) LRC_HIP(hipEventRecord(L->marks[MOE_LRC_STAGE_XA13], stream));
@@ -267,7 +271,8 @@ static int run_shared(moe_lrc_layer* L, const void* x, int T, uint8_t* ws, hipSt
   const moe_lrc_config& c = L->cfg;
   const Workspace w = plan_workspace(L, T);
   _Float16* xh = reinterpret_cast<_Float16*>(ws + w.xh_sh);
-  LRC_HIP(launch_convert_x(L, x, T, xh, T + kActPadRows, nullptr, nullptr, nullptr, nullptr, nullptr, stream));
+  int32_t* row_exp = reinterpret_cast<int32_t*>(ws + w.row_exp_sh);
+  LRC_HIP(launch_convert_x(L, x, T, xh, T + kActPadRows, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, row_exp, stream));
   FfnArgs a{};
   a.desc = L->d_desc + c.n_experts; a.n_exp = c.n_shared; a.bits = c.shared_bits; a.group = c.group;
   a.rank = 0; a.rpad = 0; a.H = c.hidden; a.F = c.ffn; a.top_k = c.top_k; a.top_n = 0; a.T = T;
@@ -277,6 +282,7 @@ static int run_shared(moe_lrc_layer* L, const void* x, int T, uint8_t* ws, hipSt
   a.y_part = reinterpret_cast<float*>(ws + w.sh_y_part);
   a.y_rows = ws + w.sh_y; a.ksplit13 = 1; a.ksplit2 = 1; a.total_rows = T * c.n_shared;
   a.n_cu = L->n_cu;
+  a.row_exp = row_exp; a.tok_exp = nullptr;
   LRC_HIP(launch_expert_ffn(a, stream));
   return MOE_LRC_OK;
 }
@@ -328,6 +334,10 @@ int moe_lrc_layer_create(const moe_lrc_config* cfg, moe_lrc_layer** out) {
     L->w_off.push_back(w); L->f_off.push_back(f);
     w += blob_of(L, e).w_bytes; f += blob_of(L, e).f_bytes;
   }
+  const bool pooled = cfg->residency == MOE_LRC_POOLED, host_homed = cfg->residency != MOE_LRC_RESIDENT;
+  // pooled residency: only the shared experts (always on) own device memory here
+  L->dev_w_base = !pooled ? 0 : cfg->n_shared > 0 ? L->w_off[cfg->n_experts] : w;
+  const size_t w_dev = w - L->dev_w_base, f_dev = pooled ? 0 : f;
   auto fail = [&](int code) { moe_lrc_layer_destroy(L); return code; };
 #define LRC_TRY(expr)                                                                             \
   do {                                                                                            \
@@ -336,14 +346,16 @@ int moe_lrc_layer_create(const moe_lrc_config* cfg, moe_lrc_layer** out) {
       return fail(set_error(e_ == hipErrorOutOfMemory ? MOE_LRC_ENOMEM : MOE_LRC_EHIP,            \
                             std::string(#expr) + ": " + hipGetErrorString(e_)));                  \
   } while (0)
-  LRC_TRY(hipMalloc((void**)&L->d_w, std::max<size_t>(w, 256)));
+  LRC_TRY(hipMalloc((void**)&L->d_w, std::max<size_t>(w_dev, 256)));
   L->f_total = std::max<size_t>(f, 256);
-  LRC_TRY(hipMalloc((void**)&L->d_f, std::max<size_t>(f, 256)));
+  LRC_TRY(hipMalloc((void**)&L->d_f, std::max<size_t>(f_dev, 256)));
   // (a projection uploaded with a smaller rank fills a prefix of its sections: the rest stays zero)
-  LRC_TRY(hipMemset(L->d_f, 0, std::max<size_t>(f, 256)));
-  if (cfg->residency == MOE_LRC_STAGED) {
+  LRC_TRY(hipMemset(L->d_f, 0, std::max<size_t>(f_dev, 256)));
+  if (host_homed) {
     LRC_TRY(hipHostMalloc((void**)&L->h_w, std::max<size_t>(w, 256), hipHostMallocDefault));
     LRC_TRY(hipHostMalloc((void**)&L->h_f, std::max<size_t>(f, 256), hipHostMallocDefault));
+    // (pooled residency copies an expert's factor blob whole: what lies behind a smaller rank's prefix is zero)
+    std::memset(L->h_f, 0, std::max<size_t>(f, 256));
     LRC_TRY(hipEventCreate(&L->ev_t0));
     LRC_TRY(hipEventCreate(&L->ev_t1));
   }
@@ -366,8 +378,12 @@ int moe_lrc_layer_create(const moe_lrc_config* cfg, moe_lrc_layer** out) {
     ExpertDesc& d = L->h_desc[e];
     std::memset(&d, 0, sizeof(d));
     for (int m = 0; m < 3; ++m) {
-      d.codes[m] = reinterpret_cast<const uint32_t*>(L->d_w + L->w_off[e] + b.off_codes[m]);
-      d.meta[m] = reinterpret_cast<const uint32_t*>(L->d_w + L->w_off[e] + b.off_meta[m]);
+      if (pooled && e < cfg->n_experts) {        // pointers come from the stack's slots, call by call
+        d.lambda[m] = d.inv_lambda[m] = 1.f;
+        continue;
+      }
+      d.codes[m] = reinterpret_cast<const uint32_t*>(L->d_w + L->w_off[e] - L->dev_w_base + b.off_codes[m]);
+      d.meta[m] = reinterpret_cast<const uint32_t*>(L->d_w + L->w_off[e] - L->dev_w_base + b.off_meta[m]);
       if (b.f_bytes) {
         d.af[m] = reinterpret_cast<const _Float16*>(L->d_f + L->f_off[e] + b.off_af[m]);
         d.bf[m] = reinterpret_cast<const _Float16*>(L->d_f + L->f_off[e] + b.off_bf[m]);
@@ -444,8 +460,9 @@ int moe_lrc_set_expert_ranked(moe_lrc_layer* L, int expert, int mat, const uint8
   // (shared experts serve every token of every call: their slots are filled here, once, also in
   // staged residency; only routed experts live in the pinned pool)
   const size_t woff = L->w_off[expert] + b.off_codes[mat];
-  if (c.residency == MOE_LRC_STAGED && expert < c.n_experts) std::memcpy(L->h_w + woff, wbuf.data(), wbuf.size());
-  else LRC_HIP(hipMemcpy(L->d_w + woff, wbuf.data(), wbuf.size(), hipMemcpyHostToDevice));
+  const bool host_homed = c.residency != MOE_LRC_RESIDENT, pooled = c.residency == MOE_LRC_POOLED;
+  if (host_homed && expert < c.n_experts) std::memcpy(L->h_w + woff, wbuf.data(), wbuf.size());
+  else LRC_HIP(hipMemcpy(L->d_w + woff - L->dev_w_base, wbuf.data(), wbuf.size(), hipMemcpyHostToDevice));
 
   // Factors: the layouts are rank-major, so the pair of rank `rank` is a prefix of the projection's A
   // section and a prefix of its B section; the rest of both sections is kept zero in the device slot
@@ -458,15 +475,19 @@ int moe_lrc_set_expert_ranked(moe_lrc_layer* L, int expert, int mat, const uint8
       pack_factor_a(fm, rank, A, reinterpret_cast<uint16_t*>(abuf.data()));
       pack_factor_b(fm, rank, B, reinterpret_cast<uint16_t*>(bbuf.data()));
     }
-    if (c.residency == MOE_LRC_STAGED) {
+    if (host_homed) {
       if (wants) { std::memcpy(L->h_f + aoff, abuf.data(), abuf.size()); std::memcpy(L->h_f + boff, bbuf.data(), bbuf.size()); }
+      if (pooled) {                    // (the blob is copied whole: keep what lies behind the prefixes zero)
+        std::memset(L->h_f + aoff + fm.af_bytes, 0, m.af_bytes - fm.af_bytes);
+        std::memset(L->h_f + boff + fm.bf_bytes, 0, m.bf_bytes - fm.bf_bytes);
+      }
     } else if (wants) {
       LRC_HIP(hipMemcpy(L->d_f + aoff, abuf.data(), abuf.size(), hipMemcpyHostToDevice));
       LRC_HIP(hipMemcpy(L->d_f + boff, bbuf.data(), bbuf.size(), hipMemcpyHostToDevice));
     }
     // what an earlier upload with a larger rank may have left behind the prefixes
-    if (m.af_bytes > fm.af_bytes) LRC_HIP(hipMemset(L->d_f + aoff + fm.af_bytes, 0, m.af_bytes - fm.af_bytes));
-    if (m.bf_bytes > fm.bf_bytes) LRC_HIP(hipMemset(L->d_f + boff + fm.bf_bytes, 0, m.bf_bytes - fm.bf_bytes));
+    if (!pooled && m.af_bytes > fm.af_bytes) LRC_HIP(hipMemset(L->d_f + aoff + fm.af_bytes, 0, m.af_bytes - fm.af_bytes));
+    if (!pooled && m.bf_bytes > fm.bf_bytes) LRC_HIP(hipMemset(L->d_f + boff + fm.bf_bytes, 0, m.bf_bytes - fm.bf_bytes));
   }
   L->mat_rank[expert * 3 + mat] = rank;
   L->mat_q3[expert * 3 + mat] = 0;
@@ -492,6 +513,8 @@ int moe_lrc_set_expert_factors_quantized(moe_lrc_layer* L, int expert, int mat, 
     return set_error(MOE_LRC_EINVAL, "set_expert_factors_quantized: null argument");
   const moe_lrc_config& c = L->cfg;
   if (expert < 0 || expert >= c.n_experts) return set_error(MOE_LRC_EINVAL, "set_expert_factors_quantized: not a routed expert");
+  if (c.residency == MOE_LRC_POOLED)
+    return set_error(MOE_LRC_ESTATE, "set_expert_factors_quantized: a pooled layer takes its factors as fp16 pairs");
   if (mat < 0 || mat > 2) return set_error(MOE_LRC_EINVAL, "set_expert_factors_quantized: mat must be 0, 1 or 2");
   if (rank <= 0 || rank > c.rank || rank % 8)
     return set_error(MOE_LRC_EINVAL, "set_expert_factors_quantized: rank must be a multiple of 8 in 8..layer rank");
@@ -547,7 +570,7 @@ int moe_lrc_route(moe_lrc_layer* L, const void* x, int T, int32_t* idx, float* w
   if (!x || !idx || !w) return set_error(MOE_LRC_EINVAL, "route: null argument");
   if (!L->gate_set) return set_error(MOE_LRC_ESTATE, "route: gate not uploaded");
   if (T == 0) return MOE_LRC_OK;
-  LRC_HIP(launch_route(L, x, T, idx, w, nullptr, (hipStream_t)stream));
+  LRC_HIP(launch_route(L, x, T, idx, w, nullptr, nullptr, (hipStream_t)stream));
   return MOE_LRC_OK;
 }
 
@@ -568,6 +591,8 @@ int moe_lrc_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t* of
   if (!x || !offsets || !row_pair || !y_rows) return set_error(MOE_LRC_EINVAL, "expert_ffn: null argument");
   if ((rc = check_ws(L, T, ws, ws_bytes, "expert_ffn"))) return rc;
   if ((rc = check_uploaded(L, "expert_ffn", true, false))) return rc;
+  if (L->cfg.residency == MOE_LRC_POOLED)
+    return set_error(MOE_LRC_ESTATE, "expert_ffn: a pooled layer runs through moe_lrc_stack_step only");
   if (T == 0) return MOE_LRC_OK;
   return run_expert_ffn(L, x, T, offsets, row_pair, y_rows, (uint8_t*)ws, (hipStream_t)stream);
 }
@@ -586,11 +611,11 @@ int moe_lrc_combine(moe_lrc_layer* L, const void* y_rows, const float* w, const 
   if (T == 0) return MOE_LRC_OK;
   const void* y_shared = nullptr;
   if (shared) {
-    if (L->cfg.residency == MOE_LRC_STAGED && (rc = check_uploaded(L, "combine", true, true))) return rc;
+    if (L->cfg.residency != MOE_LRC_RESIDENT && (rc = check_uploaded(L, "combine", true, true))) return rc;
     if ((rc = run_shared(L, x, T, (uint8_t*)ws, (hipStream_t)stream))) return rc;
     y_shared = (uint8_t*)ws + plan_workspace(L, T).sh_y;
   }
-  LRC_HIP(launch_combine(L, y_rows, nullptr, 1, w, pair_row, y_shared, T, out, (hipStream_t)stream));
+  LRC_HIP(launch_combine(L, y_rows, nullptr, 1, w, pair_row, y_shared, nullptr, T, out, (hipStream_t)stream));
   return MOE_LRC_OK;
 }
 
@@ -601,8 +626,17 @@ int moe_lrc_forward(moe_lrc_layer* L, const void* x, int T, void* out, void* ws,
   if ((rc = check_ws(L, T, ws, ws_bytes, "forward"))) return rc;
   if (!L->gate_set) return set_error(MOE_LRC_ESTATE, "forward: gate not uploaded");
   if ((rc = check_uploaded(L, "forward", true, true))) return rc;
+  if (L->cfg.residency == MOE_LRC_POOLED)
+    return set_error(MOE_LRC_ESTATE, "forward: a pooled layer runs through moe_lrc_stack_step only");
   if (T == 0) return MOE_LRC_OK;
-  hipStream_t s = (hipStream_t)stream;
+  return forward_impl(L, x, T, out, ws, (hipStream_t)stream, nullptr);
+}
+
+}  // extern "C"
+
+namespace lrc {
+int forward_impl(moe_lrc_layer* L, const void* x, int T, void* out, void* ws, hipStream_t s, const void* residual) {
+  int rc = MOE_LRC_OK;
   uint8_t* b = (uint8_t*)ws;
   const Workspace w = plan_workspace(L, T);
   int32_t* idx = (int32_t*)(b + w.topk_idx);
@@ -613,7 +647,8 @@ int moe_lrc_forward(moe_lrc_layer* L, const void* x, int T, void* out, void* ws,
   const bool mk = L->profile;
   L->profile_valid = false;
   if (mk) LRC_HIP(hipEventRecord(L->marks[MOE_LRC_STAGE_ROUTE], s));
-  LRC_HIP(launch_route(L, x, T, idx, tw, nullptr, s));
+  int32_t* tok_exp = route_writes_exponents(L, T) ? (int32_t*)(b + w.tok_exp) : nullptr;
+  LRC_HIP(launch_route(L, x, T, idx, tw, nullptr, tok_exp, s));
   if (mk) LRC_HIP(hipEventRecord(L->marks[MOE_LRC_STAGE_PERMUTE], s));
   LRC_HIP(launch_permute(L, idx, T, (int32_t*)(b + w.counts), offsets, row_pair, pair_row,
                          (int32_t*)(b + w.comp_counts), s));
@@ -632,17 +667,21 @@ int moe_lrc_forward(moe_lrc_layer* L, const void* x, int T, void* out, void* ws,
   // (the K-block partial sums of a decode-flavour W2 go to the combine as they are: no pass that
   // adds them into bf16 rows first)
   int kblocks = 1;
-  if ((rc = run_expert_ffn(L, x, T, offsets, row_pair, b + w.y_rows, b, s, mk, true, &kblocks))) return rc;
+  if ((rc = run_expert_ffn(L, x, T, offsets, row_pair, b + w.y_rows, b, s, mk, true, &kblocks, tok_exp))) return rc;
   if (fork) LRC_HIP(hipStreamWaitEvent(s, L->ev_join, 0));
   else if (L->cfg.n_shared > 0 && (rc = run_shared(L, x, T, b, s))) return rc;
   if (mk) LRC_HIP(hipEventRecord(L->marks[MOE_LRC_STAGE_COMBINE], s));
-  LRC_HIP(launch_combine(L, b + w.y_rows, kblocks > 1 ? (const float*)(b + w.y_part) : nullptr, kblocks, tw, pair_row, y_shared, T, out, s));
+  LRC_HIP(launch_combine(L, b + w.y_rows, kblocks > 1 ? (const float*)(b + w.y_part) : nullptr, kblocks, tw, pair_row, y_shared,
+                         residual, T, out, s));
   if (mk) {
     LRC_HIP(hipEventRecord(L->marks[MOE_LRC_N_STAGES], s));
     L->profile_valid = true;
   }
   return MOE_LRC_OK;
 }
+}  // namespace lrc
+
+extern "C" {
 
 // ---- the entry point that allocates nothing --------------------------------------------------
 // moe_lrc_forward with its workspace in a fixed device array of this library instead of a caller
@@ -692,8 +731,10 @@ int moe_lrc_debug_unpack(moe_lrc_layer* L, int expert, int mat, uint8_t* codes_d
   if (expert < 0 || expert >= L->n_total || mat < 0 || mat > 2)
     return set_error(MOE_LRC_EINVAL, "debug_unpack: expert or mat out of range");
   if (!L->mat_set[expert * 3 + mat]) return set_error(MOE_LRC_ESTATE, "debug_unpack: projection not uploaded");
+  if (L->cfg.residency == MOE_LRC_POOLED && expert < L->cfg.n_experts)
+    return set_error(MOE_LRC_ESTATE, "debug_unpack: a pooled layer's routed experts have no device copy of their own");
   const BlobLayout& b = blob_of(L, expert);
-  const size_t off = L->w_off[expert] + b.off_codes[mat];
+  const size_t off = L->w_off[expert] - L->dev_w_base + b.off_codes[mat];
   if (L->cfg.residency == MOE_LRC_STAGED)   // bring the packed codes into the expert's slot first
     LRC_HIP(hipMemcpyAsync(L->d_w + off, L->h_w + off, b.mat[mat].codes_bytes, hipMemcpyHostToDevice,
                            (hipStream_t)stream));
@@ -742,7 +783,9 @@ int moe_lrc_profile_read(moe_lrc_layer* L, float* ms) {
 
 int moe_lrc_get_stats(moe_lrc_layer* L, moe_lrc_stats* out) {
   if (!L || !out) return set_error(MOE_LRC_EINVAL, "get_stats: null argument");
-  if (L->cfg.residency == MOE_LRC_STAGED && L->stats_valid) {
+  if (L->cfg.residency == MOE_LRC_POOLED && L->stats_valid) {
+    L->stats.stage_ms = 0.f;                 // (the stack's own counters hold the copy time)
+  } else if (L->cfg.residency == MOE_LRC_STAGED && L->stats_valid) {
     float ms = 0.f;
     if (hipEventSynchronize(L->ev_t1) == hipSuccess && hipEventElapsedTime(&ms, L->ev_t0, L->ev_t1) == hipSuccess)
       L->stats.stage_ms = ms;

@@ -428,6 +428,8 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
     for (int rp = 0; rp < kRP; ++rp) {
       const int row = r + 32 * rp + (lane & 31);
       if (rp >= rp_n || row >= cnt) continue;
+      const int se = a.row_exp[(a.offsets ? r0 : 0) + row];        // the row's inputs were scaled by 2^se
+      const float dn = pow2i(DUAL ? -se : -2 * se), up = pow2i(2 * se);
 #pragma unroll
       for (int g = 0; g < 2; ++g) {
         const int col4 = 8 * g + 4 * hh;
@@ -437,8 +439,8 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
           half4_t hv;
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            const float gg = acc[j][rp][4 * g + i] * lam[0], uu = acc[j][rp][8 + 4 * g + i] * lam[NM - 1];
-            hv[i] = (_Float16)(gg * __builtin_amdgcn_rcpf(1.0f + __expf(-gg)) * uu);
+            const float gg = acc[j][rp][4 * g + i] * (lam[0] * dn), uu = acc[j][rp][8 + 4 * g + i] * (lam[NM - 1] * dn);
+            hv[i] = to_f16_sat(gg * __builtin_amdgcn_rcpf(1.0f + __expf(-gg)) * uu * up);
           }
           // h in operand order for the W2 kernel: columns f .. f+3 are half of one 16-byte unit
           const int f = tile * kTileN + col4;
@@ -450,8 +452,9 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
             if (tile >= a.NT) continue;
             const size_t o = size_t(r0 + row) * a.N + tile * kTileN + col4;
             uint2 yv;
-            yv.x = f32x2_to_bf16x2(acc[j][rp][8 * side + 4 * g] * lam[0], acc[j][rp][8 * side + 4 * g + 1] * lam[0]);
-            yv.y = f32x2_to_bf16x2(acc[j][rp][8 * side + 4 * g + 2] * lam[0], acc[j][rp][8 * side + 4 * g + 3] * lam[0]);
+            const float l2 = lam[0] * dn;
+            yv.x = f32x2_to_bf16x2(acc[j][rp][8 * side + 4 * g] * l2, acc[j][rp][8 * side + 4 * g + 1] * l2);
+            yv.y = f32x2_to_bf16x2(acc[j][rp][8 * side + 4 * g + 2] * l2, acc[j][rp][8 * side + 4 * g + 3] * l2);
             *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + o) = yv;
           }
         }
@@ -604,6 +607,7 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
   while ((1 << gs) < f.group) ++gs;
   KArgs a{};
   a.desc = f.desc; a.offsets = f.offsets; a.row_pair = f.row_pair; a.comp_rows = f.comp_rows; a.n_exp = f.n_exp;
+  a.row_exp = f.row_exp; a.tok_exp = f.tok_exp;
   a.group_shift = gs; a.top_k = f.top_k; a.top_n = f.top_n; a.T = f.T;
   a.rank = f.rank; a.rpad = f.rpad; a.ls = (f.rank + 31) / 32; a.total_rows = f.total_rows;
   const bool comp = f.rank > 0 && f.top_n > 0 && f.row_pair != nullptr;

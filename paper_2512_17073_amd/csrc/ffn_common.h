@@ -43,7 +43,25 @@ struct KArgs {
   float* partial;            // decode flavour, more than one K-block: fp32 partial outputs [kb][rows][N]
   const int32_t* plan;       // decode flavour: null (grid = blocks per expert x experts), or the block table
                              // (PlanEntry per block, plan.h)
+  const int32_t* row_exp;    // per input row: the exponent s of its power-of-two pre-scale (row_exponent below);
+                             // routed launches: one per routed row; shared experts: one per token
+  const int32_t* tok_exp;    // the same per token, where a kernel reads the bf16 tokens itself (or null)
 };
+
+// Range of the fp16 operands.  The activations cross the ABI as bf16 (8 exponent bits); the matrix
+// cores take fp16 (5).  Every input row is therefore multiplied by 2^s, s chosen so that its largest
+// magnitude lands in [1, 2) (exact: a power of two), the fused projection's fp32 results are
+// multiplied by 2^-s before the SwiGLU, its output h (at most quadratic in the scale, since
+// |silu(g)| <= |g|) is stored times 2^(2s), and the down projection's fp32 results are multiplied
+// by 2^(-2s).  s is clamped to +-60, which covers inputs from 2^-60 to 2^60.
+__device__ inline float pow2i(int k) { return __uint_as_float(uint32_t(127 + k) << 23); }   // 2^k, -126 <= k <= 127
+// from the largest (bits & 0x7fff) over a row of bf16 values
+__device__ inline int row_exponent(uint32_t max_abs_bits) {
+  const int e = int(max_abs_bits >> 7);          // biased exponent of the largest magnitude (0: zero or subnormal)
+  return e == 0 ? 0 : min(60, max(-60, 127 - e));
+}
+// fp32 -> fp16 that saturates at the largest finite value instead of giving infinity
+__device__ inline _Float16 to_f16_sat(float v) { return (_Float16)__builtin_fminf(__builtin_fmaxf(v, -65504.f), 65504.f); }
 
 __device__ inline uint32_t f32x2_to_bf16x2(float a, float b) {
   uint32_t ua = __float_as_uint(a), ub = __float_as_uint(b);

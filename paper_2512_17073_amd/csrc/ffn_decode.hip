@@ -328,20 +328,22 @@ __device__ __forceinline__ void decode_body(const KArgs& a, uint4* xs, const int
       for (int mt = 0; mt < MT; ++mt) {
         const int row = r + 16 * mt + c;
         if (row >= cnt) continue;
+        const int se = a.row_exp[(a.offsets ? r0 : 0) + row];      // the row's inputs were scaled by 2^se
         if constexpr (DUAL) {
           const int tile = t0 + unit;
-          const float i1 = d.inv_lambda[0], i3 = d.inv_lambda[1];
+          const float dn = pow2i(-se), up = pow2i(2 * se);
+          const float i1 = d.inv_lambda[0] * dn, i3 = d.inv_lambda[1] * dn;
           half4_t hv;
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const float g = acc[ts][mt][0][i] * i1, u = acc[ts][mt][1][i] * i3;
-            hv[i] = (_Float16)(g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u);
+            hv[i] = to_f16_sat(g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u * up);
           }
           // h in operand order for the W2 kernel: columns f .. f+3 are half of one 16-byte unit
           const int f = tile * kTileN + 4 * q;
           *reinterpret_cast<half4_t*>(reinterpret_cast<_Float16*>(a.out) + act_unit(f >> 3, r0 + row, a.out_rt) * 8 + (f & 7)) = hv;
         } else {
-          const float i2 = d.inv_lambda[2];
+          const float i2 = d.inv_lambda[2] * pow2i(-2 * se);       // (h was stored times 2^(2 se))
 #pragma unroll
           for (int m = 0; m < NS; ++m) {
             const int tile = t0 + 2 * unit + m;
@@ -413,6 +415,7 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
   while ((1 << gs) < f.group) ++gs;
   KArgs a{};
   a.desc = f.desc; a.offsets = f.offsets; a.row_pair = f.row_pair; a.comp_rows = f.comp_rows;
+  a.row_exp = f.row_exp; a.tok_exp = f.tok_exp;
   a.group_shift = gs; a.top_k = f.top_k; a.top_n = f.top_n; a.T = f.T;
   a.rank = f.rank; a.rpad = f.rpad; a.ls = (f.rank + 31) / 32; a.total_rows = f.total_rows;
   const bool comp = f.rank > 0 && f.top_n > 0 && f.row_pair != nullptr;

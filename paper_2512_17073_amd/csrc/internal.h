@@ -32,14 +32,20 @@ struct BlobLayout {
 
 struct Workspace {       // carved out of the caller's buffer; all offsets 256-byte aligned
   size_t topk_idx, topk_w, counts, offsets, comp_counts, row_pair, pair_row;
-  size_t y_rows, xh, xh_sh, h, p13, p2, y_part, sh_y_part, sh_h, sh_y, plan, total;
+  size_t y_rows, xh, xh_sh, h, p13, p2, y_part, sh_y_part, sh_h, sh_y, plan, tok_exp, row_exp, row_exp_sh, total;
 };
 
 }  // namespace lrc
 
+struct moe_lrc_stack;
+
 struct moe_lrc_layer {
   moe_lrc_config cfg;
   int device;
+  moe_lrc_stack* pool = nullptr;       // pooled residency: the stack whose slot pool serves this layer
+  int pool_index = -1;                 // ... and the layer's place in it
+  size_t dev_w_base = 0;               // device pointer of expert e's weights: d_w + w_off[e] - dev_w_base (pooled
+                                       // residency keeps only the shared experts on the device)
   int n_cu = 0;                        // compute units of `device`
   lrc::BlobLayout routed, shared;
   int n_total;                         // E + S
@@ -75,23 +81,36 @@ struct moe_lrc_layer {
 namespace lrc {
 
 int set_error(int code, const std::string& msg);
+// returns MOE_LRC_EHIP (with the call's text and HIP's message as the last error) if a HIP call fails
+#define LRC_HIP(expr)                                                                       \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess)                                                                   \
+      return lrc::set_error(MOE_LRC_EHIP, std::string(#expr) + ": " + hipGetErrorString(e_)); \
+  } while (0)
 Workspace plan_workspace(const moe_lrc_layer* L, int T);
 
 // ---- kernel launchers (each returns hipError_t of the launch) ------------------------------
+// tok_exp (may be null): receives every token's pre-scale exponent (ffn_common.h) if
+// route_writes_exponents(L, T), else it is left untouched
 hipError_t launch_route(const moe_lrc_layer* L, const void* x, int T, int32_t* idx, float* w,
-                        _Float16* xh /*may be null*/, hipStream_t s);
+                        _Float16* xh /*may be null*/, int32_t* tok_exp, hipStream_t s);
+bool route_writes_exponents(const moe_lrc_layer* L, int T);
 hipError_t launch_permute(const moe_lrc_layer* L, const int32_t* idx, int T, int32_t* counts,
                           int32_t* offsets, int32_t* row_pair, int32_t* pair_row,
                           int32_t* comp_counts, hipStream_t s);
 struct PlanSpec;   // plan.h
-// fp16 copy of the activations in operand order: one row per routed pair (row_pair given) or one
-// per token (row_pair null); with `stat`, one more block counts the per-expert rows
+// fp16 copy of the activations in operand order, every row times its power-of-two pre-scale
+// (ffn_common.h; exponents to row_exp, taken from tok_exp per token if given): one row per routed
+// pair (row_pair given) or one per token (row_pair null); with `stat`, one more block counts the
+// per-expert rows
 struct FfnArgs;
 // xa13: the arguments of the expert-FFN launches that follow, when their fused W1|W3 projection takes
 // the decode flavour and wants (x A1 | x A3) made by further blocks of this launch; else null
 hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _Float16* xg, int rt,
                             const int32_t* offsets, const int32_t* row_pair, int32_t* stat,
-                            const PlanSpec* plans /* two, or null */, const FfnArgs* xa13, hipStream_t s);
+                            const PlanSpec* plans /* two, or null */, const FfnArgs* xa13,
+                            const int32_t* tok_exp /* or null */, int32_t* row_exp, hipStream_t s);
 constexpr int kMaxKBlocks = 8;    // most K-blocks the decode W2 kernel splits into
 // blocks (per K-block) of a decode launch that shares its blocks out by a table: `target` (the
 // device's CUs over the K-blocks), or enough for ceil(NT / 32) blocks per expert that can be active
@@ -126,6 +145,8 @@ struct FfnArgs {
                               // the combine instead of adding them into y_rows
   int ksplit13, ksplit2, total_rows;
   int n_cu;                   // compute units of the device (the launches size their grids to fill them)
+  int32_t* row_exp;           // per input row (routed: per routed row; shared: per token): pre-scale exponent
+  const int32_t* tok_exp;     // per token, from the routing kernel, or null
   hipEvent_t* marks;          // null, or 4 events recorded after xa13, w13, xa2, w2
 };
 hipError_t launch_expert_ffn(const FfnArgs& a, hipStream_t s);
@@ -141,9 +162,19 @@ hipError_t decode_init_device();
 void expert_ffn_plan_specs(const FfnArgs& a, PlanSpec& p13, PlanSpec& p2);
 // y_part != null: the expert outputs are the sums over `kblocks` fp32 partial sums [kb][T*k][H]
 // (the decode flavour's W2 K-blocks) instead of the bf16 rows y_rows
+// residual != null: out = residual + (the weighted sum), rounded once
 hipError_t launch_combine(const moe_lrc_layer* L, const void* y_rows, const float* y_part, int kblocks, const float* w,
-                          const int32_t* pair_row, const void* y_shared, int T, void* out,
+                          const int32_t* pair_row, const void* y_shared, const void* residual, int T, void* out,
                           hipStream_t s);
+// ---- host API internals shared with the layer stack (stack.hip) ----
+const BlobLayout& blob_of(const moe_lrc_layer* L, int expert);
+void fill_algorithmic_stats(moe_lrc_layer* L, const int32_t* stat);
+// moe_lrc_forward after its argument checks; residual as in launch_combine
+int forward_impl(moe_lrc_layer* L, const void* x, int T, void* out, void* ws, hipStream_t s, const void* residual);
+// pooled residency, inside the expert FFN after the preparing launch: reads the per-expert counts
+// back, brings the experts that received rows into slots of the stack's pool, points the layer's
+// expert table at them and makes `s` wait for the copies
+int pool_stage(moe_lrc_layer* L, const void* x, int T, hipStream_t s);
 hipError_t launch_debug_unpack(const uint32_t* packed, const MatLayout& m, uint8_t* codes_dev,
                                hipStream_t s);
 // 3-bit factor blob (q3_blob_bytes) -> the fp16 factor sections of one projection (rank-major layouts)

@@ -28,7 +28,8 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict
                                                       const float* __restrict__ y_part, int kblocks, size_t kb_stride,
                                                       const float* __restrict__ w,
                                                       const int32_t* __restrict__ pair_row,
-                                                      const uint16_t* __restrict__ y_shared, int T, int H,
+                                                      const uint16_t* __restrict__ y_shared,
+                                                      const uint16_t* __restrict__ residual, int T, int H,
                                                       int top_k, int n_shared, uint16_t* __restrict__ out) {
   const int t = blockIdx.x;
   for (int ch = threadIdx.x; ch < H / 8; ch += 256) {
@@ -66,6 +67,15 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict
         acc[2 * i + 1] += bf16_hi(a[i]);
       }
     }
+    if (residual != nullptr) {                 // a stack of layers: out = x + layer(x)
+      const uint4 v = reinterpret_cast<const uint4*>(residual + size_t(t) * H)[ch];
+      const uint32_t a[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        acc[2 * i] += bf16_lo(a[i]);
+        acc[2 * i + 1] += bf16_hi(a[i]);
+      }
+    }
     reinterpret_cast<uint4*>(out + size_t(t) * H)[ch] =
         make_uint4(pack_bf16(acc[0], acc[1]), pack_bf16(acc[2], acc[3]), pack_bf16(acc[4], acc[5]),
                    pack_bf16(acc[6], acc[7]));
@@ -88,8 +98,10 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(const uint16_t* __re
                                                    const int32_t* __restrict__ offsets,
                                                    const int32_t* __restrict__ row_pair, int E, int top_k,
                                                    int top_n, int32_t* __restrict__ stat, PlanSpec plan0,
-                                                   PlanSpec plan1, int xa_tiles, ffn::KArgs xa) {
+                                                   PlanSpec plan1, int xa_tiles, ffn::KArgs xa,
+                                                   const int32_t* __restrict__ tok_exp, int32_t* __restrict__ row_exp) {
   __shared__ ffn::float4_t red[2 * kPrepThreads / 64][64];
+  __shared__ uint32_t row_max[16];
   constexpr int kWavesPerBlock = kPrepThreads / 64, kColLanes = kPrepThreads / 16;
   const int row_blocks = (rows + 15) / 16;
   const int stat_blocks = stat ? (E + kWavesPerBlock - 1) / kWavesPerBlock : 0, plan_block = plan0.B + plan1.B > 0 ? 1 : 0;
@@ -114,9 +126,31 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(const uint16_t* __re
     return;
   }
   const int R = blockIdx.x * 16 + (threadIdx.x & 15);
-  if (R >= rows) return;
-  const int t = row_pair ? row_pair[R] / top_k : R;
+  const int t = R < rows ? (row_pair ? row_pair[R] / top_k : R) : 0;
   const uint4* xrow = reinterpret_cast<const uint4*>(x + size_t(t) * H);
+  // The row's power-of-two pre-scale (ffn_common.h): from the routing kernel's per-token exponents,
+  // or, without them, from a pass of this block over its sixteen rows.
+  int se = 0;
+  if (tok_exp != nullptr) {
+    se = tok_exp[t];
+  } else {
+    if (threadIdx.x < 16) row_max[threadIdx.x] = 0;
+    __syncthreads();
+    uint32_t m = 0;
+    if (R < rows)
+      for (int k8 = threadIdx.x >> 4; k8 < H / 8; k8 += kColLanes) {
+        const uint4 v = xrow[k8];
+        const uint32_t in[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) m = max(m, max(in[i] & 0x7fffu, (in[i] >> 16) & 0x7fffu));
+      }
+    atomicMax(&row_max[threadIdx.x & 15], m);
+    __syncthreads();
+    se = ffn::row_exponent(row_max[threadIdx.x & 15]);
+  }
+  if (R >= rows) return;
+  if (blockIdx.y == 0 && (threadIdx.x >> 4) == 0) row_exp[R] = se;
+  const float sc = ffn::pow2i(se);
   // (grid.y splits the columns when there are few rows, so that the launch still fills the chip)
   for (int k8 = blockIdx.y * kColLanes + (threadIdx.x >> 4); k8 < H / 8; k8 += kColLanes * gridDim.y) {
     const uint4 v = xrow[k8];
@@ -124,8 +158,8 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(const uint16_t* __re
     uint32_t o[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const _Float16 lo = (_Float16)bf16_lo(in[i]);
-      const _Float16 hi = (_Float16)bf16_hi(in[i]);
+      const _Float16 lo = (_Float16)(bf16_lo(in[i]) * sc);
+      const _Float16 hi = (_Float16)(bf16_hi(in[i]) * sc);
       o[i] = uint32_t(__builtin_bit_cast(uint16_t, lo)) | (uint32_t(__builtin_bit_cast(uint16_t, hi)) << 16);
     }
     const int ks = k8 >> 5, q = (k8 >> 3) & 3, s = k8 & 7;
@@ -239,18 +273,19 @@ hipError_t launch_expand_q3(int n, const Q3Expand* jobs, hipStream_t s) {
 }
 
 hipError_t launch_combine(const moe_lrc_layer* L, const void* y_rows, const float* y_part, int kblocks, const float* w,
-                          const int32_t* pair_row, const void* y_shared, int T, void* out,
+                          const int32_t* pair_row, const void* y_shared, const void* residual, int T, void* out,
                           hipStream_t s) {
   const moe_lrc_config& c = L->cfg;
   hipLaunchKernelGGL(combine_kernel, dim3(T), dim3(256), 0, s, (const uint16_t*)y_rows, y_part, kblocks,
                      size_t(T) * c.top_k * c.hidden, w, pair_row,
-                     (const uint16_t*)y_shared, T, c.hidden, c.top_k, c.n_shared, (uint16_t*)out);
+                     (const uint16_t*)y_shared, (const uint16_t*)residual, T, c.hidden, c.top_k, c.n_shared, (uint16_t*)out);
   return hipGetLastError();
 }
 
 hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _Float16* xg, int rt,
                             const int32_t* offsets, const int32_t* row_pair, int32_t* stat,
-                            const PlanSpec* plans, const FfnArgs* xa13, hipStream_t s) {
+                            const PlanSpec* plans, const FfnArgs* xa13, const int32_t* tok_exp, int32_t* row_exp,
+                            hipStream_t s) {
   const moe_lrc_config& c = L->cfg;
   const int rows = row_pair ? T * c.top_k : T;
   const int row_blocks = (rows + 15) / 16;
@@ -266,12 +301,13 @@ hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _
     xa.desc = f.desc; xa.offsets = f.offsets; xa.row_pair = f.row_pair; xa.top_k = f.top_k; xa.top_n = f.top_n;
     xa.rank = f.rank; xa.ls = (f.rank + 31) / 32; xa.K = f.H; xa.p = f.p13; xa.total_rows = f.total_rows;
     xa.kb_steps = (f.H + kTileK - 1) / kTileK;
+    xa.tok_exp = tok_exp; xa.row_exp = row_exp;
     xa_tiles = 4 * xa.ls;
   }
   const int stat_blocks = stat ? (c.n_experts + kPrepThreads / 64 - 1) / (kPrepThreads / 64) : 0;
   hipLaunchKernelGGL(prep_kernel, dim3(row_blocks + stat_blocks + plan_block + xa_tiles * c.n_experts, ky),
                      dim3(kPrepThreads), 0, s, (const uint16_t*)x_bf16, rows, c.hidden, reinterpret_cast<uint4*>(xg), rt, offsets,
-                     row_pair, c.n_experts, c.top_k, c.top_n, stat, p0, p1, xa_tiles, xa);
+                     row_pair, c.n_experts, c.top_k, c.top_n, stat, p0, p1, xa_tiles, xa, tok_exp, row_exp);
   return hipGetLastError();
 }
 

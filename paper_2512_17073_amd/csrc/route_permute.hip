@@ -74,7 +74,8 @@ __global__ __launch_bounds__(64 * NW) void route_kernel(const uint16_t* __restri
                                                     const uint16_t* __restrict__ wg,
                                                     const float* __restrict__ bias, int T, int H, int E,
                                                     int top_k, int renorm, int32_t* __restrict__ idx,
-                                                    float* __restrict__ w, _Float16* __restrict__ xh) {
+                                                    float* __restrict__ w, _Float16* __restrict__ xh,
+                                                    int32_t* __restrict__ tok_exp) {
   __shared__ double logit[kMaxExperts];
   const int t = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint4* xrow = reinterpret_cast<const uint4*>(x + size_t(t) * H);
@@ -100,6 +101,21 @@ __global__ __launch_bounds__(64 * NW) void route_kernel(const uint16_t* __restri
   for (int j = 0; j < CH; ++j) {
     const int c = lane + 64 * j;
     xv[j] = c < chunks ? xrow[c] : make_uint4(0, 0, 0, 0);
+  }
+  if (tok_exp != nullptr && wave == 0) {
+    // exponent of the token's power-of-two pre-scale for the expert kernels: 2^s brings its largest
+    // magnitude into [1, 2), s within +-60, 0 for a token of zeros
+    uint32_t m = 0;
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+      const uint32_t xa[4] = {xv[j].x, xv[j].y, xv[j].z, xv[j].w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) m = max(m, max(xa[i] & 0x7fffu, (xa[i] >> 16) & 0x7fffu));
+    }
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, d));
+    const int eb = int(m >> 7);
+    if (lane == 0) tok_exp[t] = eb == 0 ? 0 : min(60, max(-60, 127 - eb));
   }
   auto load_row = [&](int e, uint4 (&wv)[CH]) {
     const uint4* wrow = reinterpret_cast<const uint4*>(wg + size_t(min(e, E - 1)) * H);
@@ -282,8 +298,12 @@ __global__ __launch_bounds__(1024) void permute_kernel(const int32_t* __restrict
 
 }  // namespace
 
+bool route_writes_exponents(const moe_lrc_layer* L, int T) {
+  return !(T >= 1024 && L->cfg.n_experts >= 128 && L->d_logits != nullptr);
+}
+
 hipError_t launch_route(const moe_lrc_layer* L, const void* x, int T, int32_t* idx, float* w,
-                        _Float16* xh, hipStream_t s) {
+                        _Float16* xh, int32_t* tok_exp, hipStream_t s) {
   const moe_lrc_config& c = L->cfg;
   // Many tokens and many experts: tiled on the fp64 matrix cores.  (With few expert tiles a tile's
   // chain of H / 4 dependent 64-cycle MFMAs is longer than the per-token kernel takes: measured
@@ -299,7 +319,7 @@ hipError_t launch_route(const moe_lrc_layer* L, const void* x, int T, int32_t* i
   auto go = [&](auto kernel, int nw) {
     hipLaunchKernelGGL(kernel, dim3(T), dim3(64 * nw), 0, s, (const uint16_t*)x, L->d_wg,
                        L->has_bias ? L->d_bias : nullptr, T, c.hidden, c.n_experts, c.top_k,
-                       c.renormalize, idx, w, xh);
+                       c.renormalize, idx, w, xh, tok_exp);
   };
   // 16 wavefronts per token when every wavefront would otherwise walk 16 or more gate rows one
   // after the other, the chunks of a row fit the smaller register budget, and the launch is bound

@@ -53,12 +53,15 @@ __device__ __forceinline__ void xa_rows_body(const KArgs& a, const uint16_t* __r
     bool flagged[2];
     int pair[2];
     const uint4* xrow[2];
+    float xs2[2] = {1.f, 1.f};
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       const int row = min(r + 16 * t + c, cnt - 1);
       pair[t] = a.row_pair[r0 + row];
       flagged[t] = r + 16 * t + c < cnt && (pair[t] % a.top_k) < a.top_n;
       xrow[t] = TOKENS ? reinterpret_cast<const uint4*>(x_bf16 + size_t(pair[t] / a.top_k) * a.K) : nullptr;
+      // the row's power-of-two pre-scale (the fp16 operand-order buffer holds the rows already scaled)
+      if constexpr (TOKENS) xs2[t] = pow2i(a.tok_exp ? a.tok_exp[pair[t] / a.top_k] : a.row_exp[r0 + row]);
     }
     const bool any0 = __ballot(flagged[0]) != 0ull, any1 = __ballot(flagged[1]) != 0ull;   // block-uniform
     float4_t acc[2] = {float4_t{0.f, 0.f, 0.f, 0.f}, float4_t{0.f, 0.f, 0.f, 0.f}};
@@ -77,8 +80,8 @@ __device__ __forceinline__ void xa_rows_body(const KArgs& a, const uint16_t* __r
               const uint32_t in[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
               for (int i = 0; i < 4; ++i) {
-                xf[t][u][2 * i] = (_Float16)__uint_as_float(in[i] << 16);
-                xf[t][u][2 * i + 1] = (_Float16)__uint_as_float(in[i] & 0xffff0000u);
+                xf[t][u][2 * i] = (_Float16)(__uint_as_float(in[i] << 16) * xs2[t]);
+                xf[t][u][2 * i + 1] = (_Float16)(__uint_as_float(in[i] & 0xffff0000u) * xs2[t]);
               }
             } else {
               xf[t][u] = src[act_unit(4 * ku + q, r0 + min(r + 16 * t + c, cnt - 1), a.in_rt)];
@@ -114,7 +117,7 @@ __device__ __forceinline__ void xa_rows_body(const KArgs& a, const uint16_t* __r
         if (row >= cnt) continue;
         half4_t v = half4_t{0, 0, 0, 0};
         if (flagged[t] && live)
-          v = half4_t{(_Float16)(acc[t][0] * lam), (_Float16)(acc[t][1] * lam), (_Float16)(acc[t][2] * lam), (_Float16)(acc[t][3] * lam)};
+          v = half4_t{to_f16_sat(acc[t][0] * lam), to_f16_sat(acc[t][1] * lam), to_f16_sat(acc[t][2] * lam), to_f16_sat(acc[t][3] * lam)};
         *reinterpret_cast<half4_t*>(P + size_t(r0 + row) * pitch + m * a.ls * 32 + 16 * tl + 4 * q) = v;
       }
     }

@@ -38,7 +38,7 @@ def _cfg(**kw):
 @pytest.mark.parametrize("kw,code", [
     (dict(bits=5), -1), (dict(bits=1), -1), (dict(top_n=3), -1), (dict(top_k=0), -1), (dict(top_k=9), -1),
     (dict(rank=12), -1), (dict(rank=1032), -1), (dict(n_experts=0), -1), (dict(n_experts=300), -1),
-    (dict(max_tokens=0), -1), (dict(residency=2), -1), (dict(renormalize=2), -1), (dict(n_shared=9), -1),
+    (dict(max_tokens=0), -1), (dict(residency=3), -1), (dict(renormalize=2), -1), (dict(n_shared=9), -1),
     (dict(n_shared=1, shared_bits=7), -1),
     (dict(group=32), -2), (dict(hidden=200), -2), (dict(ffn=500), -2), (dict(group=128, hidden=320), -2),
     (dict(hidden=16448), -2), (dict(ffn=65600), -2),
