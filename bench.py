@@ -86,6 +86,62 @@ def cpu_baseline(cfg, layer, x_bits, budget_tokens=8):
             "active_experts_full_batch": int((np.bincount(r['idx'].ravel(), minlength=cfg.n_experts) > 0).sum())}
 
 
+def stack_bench(args, cfg):
+    """Decode steps through a stack of layers whose experts live in pinned host memory and share a
+    device slot pool (Section 4.3, case study 1).  Prints its own JSON line; never the headline value."""
+    import torch
+    import paper_2512_17073_amd as amd
+    from workload import synth
+    T, nl, E = cfg.tokens, args.stack, cfg.n_experts
+    slots = args.slots or nl * E
+    print(f"[bench] stack of {nl} x {cfg.name}, {slots} slots: generating artefacts", file=sys.stderr, flush=True)
+    experts = [{m: synth.sample_artifacts(cfg, e, m) for m in (0, 1, 2)} for e in range(E + cfg.n_shared)]
+    layers = []
+    for i in range(nl):
+        wg, bias = synth.make_gate(cfg.with_(seed=cfg.seed + 17 * i))          # a gate of its own per layer
+        L = amd.Layer.from_config(cfg, residency=amd.POOLED)
+        L.set_gate(wg, bias)
+        for e in range(E + cfg.n_shared):
+            src = experts[(e + i) % E] if e < E else experts[e]
+            for m in (0, 1, 2):
+                a = src[m]
+                L.set_expert(e, m, a["codes"], a["scale"], a["zero"], a["A"], a["B"])
+        layers.append(L)
+        print(f"[bench] layer {i + 1}/{nl} packed into pinned memory", file=sys.stderr, flush=True)
+    st = amd.Stack(layers, slots=slots, prefetch=not args.no_prefetch, residual=True)
+    xs = [amd.bf16_tensor(synth.make_tokens(cfg.with_(seed=cfg.seed + 1000 + i))) for i in range(8)]
+    out = torch.empty_like(xs[0])
+    for i in range(args.warmup if args.warmup < 5 else 2):
+        st.step(xs[i % 8], out)
+    torch.cuda.synchronize()
+    s0 = st.stats()
+    step_ms, copy_ms = [], 0.0
+    t0 = time.perf_counter()
+    for i in range(args.steps if args.steps < 200 else 20):
+        st.step(xs[(i + 3) % 8], out)
+        s = st.stats()                       # (waits for the step's copies)
+        step_ms.append(s["last_step_ms"]); copy_ms += s["last_copy_ms"]
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    s1 = st.stats()
+    d = {k: s1[k] - s0[k] for k in ("expert_uses", "hits", "misses", "prefetched", "prefetch_hits", "factor_copies", "bytes_h2d")}
+    n = len(step_ms)
+    print(json.dumps({
+        "metric": "stack_decode_tokens_per_s", "value": T * n / dt, "unit": "tokens/s", "n_gpus": 1, "steps": n,
+        "ms_per_step": dt / n * 1e3, "ms_per_layer": dt / n / nl * 1e3, "higher_is_better": True, "data": "synthetic",
+        "config": {"workload": cfg.name, "layers": nl, "slots": slots, "experts_per_layer": E, "tokens": T,
+                   "prefetch": not args.no_prefetch, "residency": "pooled (pinned host memory)"},
+        "transfers": dict(d, hit_rate=d["hits"] / max(1, d["expert_uses"]),
+                          h2d_gb_per_s_while_copying=d["bytes_h2d"] / max(copy_ms, 1e-9) / 1e6 if copy_ms else None,
+                          h2d_gb_per_s_over_the_run=d["bytes_h2d"] / dt / 1e9),
+        "step_ms_median": float(np.median(step_ms)), "step_ms_p10": float(np.percentile(step_ms, 10)),
+        "step_ms_p90": float(np.percentile(step_ms, 90)),
+    }))
+    st.close()
+    for L in layers:
+        L.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -108,6 +164,11 @@ def main():
     ap.add_argument("--calib-copy", action="store_true",
                     help="after the timed region run an elementwise kernel that reads and writes 256 MiB, "
                          "so that a counter run can scale FETCH_SIZE / WRITE_SIZE by a known transfer")
+    ap.add_argument("--stack", type=int, default=0,
+                    help="instead of the single layer: decode steps through a stack of this many layers whose experts "
+                         "live in pinned host memory (a line of its own, metric stack_decode_tokens_per_s)")
+    ap.add_argument("--slots", type=int, default=0, help="with --stack: device slots of the shared pool (0: every expert fits)")
+    ap.add_argument("--no-prefetch", action="store_true", help="with --stack: no copies ahead for the next layer")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1", file=sys.stderr)
@@ -121,6 +182,9 @@ def main():
     torch.cuda.set_device(0)
 
     cfg = configs.get(args.workload)
+    if args.stack > 0:
+        stack_bench(args, cfg)
+        return
     T = cfg.tokens
     t_setup = time.time()
     print(f"[bench] workload {cfg.name}: generating artefacts", file=sys.stderr, flush=True)

@@ -238,6 +238,41 @@ int moe_lrc_stack_get_stats(moe_lrc_stack* stack, moe_lrc_stack_stats* out);
 /* Empties every slot and zeroes the counters (a cold start). */
 int moe_lrc_stack_reset(moe_lrc_stack* stack);
 
+/* ---- the offline half of the method on the device (Sections 2.3 and 3.1) ---------------------- */
+
+/* These calls prepare a model once; they are not part of the hot path: moe_lrc_offline_factors and
+ * moe_lrc_offline_kurtosis allocate their own device buffers, run on the default stream and
+ * synchronise.  All arithmetic is fp64.
+ *
+ * moe_lrc_offline_quantize: Q(W) of Section 2.3 for W [K][N] (device, fp64, input-dim-major): per
+ * group of `group` consecutive input rows of one output column, scale = fp16((max - min) / (2^bits - 1)),
+ * zero = fp16(-min / scale), code = clamp(round-half-even(w / scale + zero), 0, 2^bits - 1) with the
+ * scale and zero already rounded; a constant group (or a scale that leaves fp16's range) gets
+ * scale 1, zero = fp16(-min), codes 0.  codes_dev [K][N] one code per byte, scale_dev / zero_dev
+ * [K/group][N] fp16 bit patterns: the arrays moe_lrc_set_expert takes.  residual_dev (or NULL)
+ * receives E = W - (code - zero) * scale, [K][N] fp64.  Asynchronous on `stream`. */
+int moe_lrc_offline_quantize(const double* W_dev, int K, int N, int bits, int group, uint8_t* codes_dev,
+                             uint16_t* scale_dev, uint16_t* zero_dev, double* residual_dev, void* stream);
+
+/* Rank-`rank` factors of E [K][N] (device, fp64), Section 3.1 step 2: A = U sqrt(S) [K][rank] and
+ * B = sqrt(S) V^T [rank][N] (device, fp64) for the `rank` leading singular triplets, found by a
+ * subspace iteration from the test matrix omega_dev [N][l] (device, fp64; standard normal entries,
+ * rank <= l <= min(K, N, 1088), l = rank + 8 is the usual choice) with `power_iters` (0..8) passes over
+ * E and E^T; the singular values go to sigma_host [rank] (or NULL), in descending order.  The signs
+ * of a pair (column i of A, row i of B) are arbitrary; their product is not.  A_bf16_dev /
+ * B_bf16_dev (or NULL) receive the factors rounded to bf16, the form moe_lrc_set_expert takes.
+ * MOE_LRC_ESHAPE if the sketch loses rank (E of rank below l) or the rotations do not converge. */
+int moe_lrc_offline_factors(const double* E_dev, int K, int N, int rank, const double* omega_dev, int l, int power_iters,
+                            double* A_dev, double* B_dev, double* sigma_host, uint16_t* A_bf16_dev, uint16_t* B_bf16_dev);
+
+/* Kurtosis of the n entries of a matrix (device, fp64), Section 3.1 step 1:
+ * kappa = mean((w - mu)^4) / mean((w - mu)^2)^2, to *kappa (host). */
+int moe_lrc_offline_kurtosis(const double* W_dev, size_t n, double* kappa);
+
+/* Host-only: the quantizer's fp64 -> fp16 rounding (to nearest, ties to even, one rounding) of n
+ * values, for checking against another implementation. */
+int moe_lrc_selftest_half_rounding(const double* in_host, size_t n, uint16_t* out_host);
+
 /* ---- evidence and test hooks ------------------------------------------------------------- */
 
 /* Unpacks the layer's private copy of one projection back to one code per byte, device [K][N]. */

@@ -10,14 +10,15 @@ this build states in its design notes, written out step by step:
     1. every expert with rows that sits in a slot is a hit: its slot is pinned for this layer and
        becomes the most recently used; a slot filled ahead of time and not used since counts as a
        prefetch hit;
-    2. every expert with rows that sits in no slot is a miss: it takes the least recently used slot
-       that is not pinned (never-used slots first, lowest index on ties), which is pinned and
-       becomes the most recently used; its packed weights are copied;
+    2. every expert with rows that sits in no slot is a miss: it takes, among the slots that are not
+       pinned, an empty one, else the least recently used (lowest index on ties), which is pinned
+       and becomes the most recently used; its packed weights are copied;
     3. an expert with Top-n rows whose slot lacks the factor pair gets the pair copied;
     4. with prefetching, the experts that layer l+1's gate selects on layer l's input are treated
        likewise in ascending order, as long as an unpinned slot is left: absent ones take a slot
-       (pinned, most recently used, marked as filled ahead) and are copied, with the factor pair if
-       the guess puts them in a token's first n slots.
+       (pinned for this layer, marked as filled ahead, and ranked as never used until their own layer
+       uses them, so that a wrong guess is the first to be evicted) and are copied, with the factor
+       pair if the guess puts them in a token's first n slots.
 
 Nothing here is shared with the HIP library; the tests compare the library's counters with this.
 """
@@ -47,7 +48,8 @@ class SlotCache:
         for i in range(self.n):
             if self.pin[i] == self.epoch:
                 continue
-            if best is None or self.tick[i] < self.tick[best]:
+            rank = (self.key[i] is not None, self.tick[i])          # empty slots first, then by last use
+            if best is None or rank < (self.key[best] is not None, self.tick[best]):
                 best = i
         return best
 
@@ -58,8 +60,11 @@ class SlotCache:
         self.has_f[slot] = False
         self.fresh[slot] = fresh
         self.pin[slot] = self.epoch
-        self.clock += 1
-        self.tick[slot] = self.clock
+        if fresh:                       # filled ahead: counts as never used until its layer uses it
+            self.tick[slot] = 0
+        else:
+            self.clock += 1
+            self.tick[slot] = self.clock
         self.where[key] = slot
         self.c["weight_copies"] += 1
 

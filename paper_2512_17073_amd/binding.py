@@ -26,6 +26,7 @@ EXPORTS = [
     "moe_lrc_packed_bytes", "moe_lrc_pack_codes", "moe_lrc_unpack_codes", "moe_lrc_get_stats",
     "moe_lrc_profile_enable", "moe_lrc_profile_read", "moe_lrc_calibrate",
     "moe_lrc_selftest_decode_index",
+    "moe_lrc_offline_quantize", "moe_lrc_offline_factors", "moe_lrc_offline_kurtosis", "moe_lrc_selftest_half_rounding",
     "moe_lrc_stack_create", "moe_lrc_stack_destroy", "moe_lrc_stack_step", "moe_lrc_stack_get_stats", "moe_lrc_stack_reset",
 ]
 STAGES = ["route", "permute", "prep", "xa13", "w13", "xa2", "w2", "shared", "combine"]
@@ -94,6 +95,10 @@ def lib() -> C.CDLL:
         L.moe_lrc_profile_read.argtypes = [vp, C.POINTER(C.c_float)]
         L.moe_lrc_calibrate.argtypes = [i32, sz, i32, C.POINTER(C.c_double)]
         L.moe_lrc_selftest_decode_index.argtypes = [i32] * 14
+        L.moe_lrc_offline_quantize.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp]
+        L.moe_lrc_offline_factors.argtypes = [vp, i32, i32, i32, vp, i32, i32, vp, vp, vp, vp, vp]
+        L.moe_lrc_offline_kurtosis.argtypes = [vp, sz, C.POINTER(C.c_double)]
+        L.moe_lrc_selftest_half_rounding.argtypes = [vp, sz, vp]
         L.moe_lrc_stack_create.argtypes = [C.POINTER(vp), i32, i32, i32, C.POINTER(vp)]
         L.moe_lrc_stack_destroy.argtypes = [vp]
         L.moe_lrc_stack_step.argtypes = [vp, vp, i32, vp, vp, vp]
@@ -315,6 +320,54 @@ class Layer:
         s = Stats()
         _check(lib().moe_lrc_get_stats(self._h, C.byref(s)))
         return {n: getattr(s, n) for n, _ in Stats._fields_}
+
+
+# ---- offline pipeline (device tensors in, device tensors out) ---------------------------------
+def offline_quantize(W, bits: int, group: int, want_residual: bool = True):
+    """moe_lrc_offline_quantize: W [K][N] torch.float64 on the device -> (codes uint8 [K][N],
+    scale, zero as int16 views of fp16 bits [K/group][N], residual float64 [K][N] or None)."""
+    import torch
+    K, N = W.shape
+    codes = torch.empty((K, N), dtype=torch.uint8, device=W.device)
+    scale = torch.empty((K // group, N), dtype=torch.int16, device=W.device)
+    zero = torch.empty((K // group, N), dtype=torch.int16, device=W.device)
+    resid = torch.empty((K, N), dtype=torch.float64, device=W.device) if want_residual else None
+    _check(lib().moe_lrc_offline_quantize(W.data_ptr(), K, N, bits, group, codes.data_ptr(), scale.data_ptr(),
+                                          zero.data_ptr(), resid.data_ptr() if want_residual else None, _stream()))
+    return codes, scale, zero, resid
+
+
+def offline_factors(E, rank: int, omega, power_iters: int = 2):
+    """moe_lrc_offline_factors: E [K][N], omega [N][l] torch.float64 on the device ->
+    (A [K][rank], B [rank][N] float64, sigma numpy [rank], A, B as int16 views of bf16 bits)."""
+    import torch
+    K, N = E.shape
+    l = omega.shape[1]
+    torch.cuda.synchronize()
+    A = torch.empty((K, rank), dtype=torch.float64, device=E.device)
+    B = torch.empty((rank, N), dtype=torch.float64, device=E.device)
+    Ab = torch.empty((K, rank), dtype=torch.int16, device=E.device)
+    Bb = torch.empty((rank, N), dtype=torch.int16, device=E.device)
+    sigma = np.zeros(rank, dtype=np.float64)
+    _check(lib().moe_lrc_offline_factors(E.data_ptr(), K, N, rank, omega.data_ptr(), l, power_iters, A.data_ptr(),
+                                         B.data_ptr(), _hp(sigma), Ab.data_ptr(), Bb.data_ptr()))
+    return A, B, sigma, Ab, Bb
+
+
+def offline_kurtosis(W) -> float:
+    import torch
+    torch.cuda.synchronize()
+    out = C.c_double(0.0)
+    _check(lib().moe_lrc_offline_kurtosis(W.data_ptr(), W.numel(), C.byref(out)))
+    return out.value
+
+
+def f64_to_f16_bits(a: np.ndarray) -> np.ndarray:
+    """moe_lrc_selftest_half_rounding (host only)."""
+    a = _host(a, np.float64).ravel()
+    out = np.empty(a.size, dtype=np.uint16)
+    _check(lib().moe_lrc_selftest_half_rounding(_hp(a), a.size, _hp(out)))
+    return out
 
 
 class Stack:

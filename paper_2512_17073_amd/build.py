@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoe_lrc.so")
-SOURCES = ["api.hip", "stack.hip", "route_permute.hip", "ffn.hip", "ffn_decode.hip", "misc.hip", "calib.hip", "pack.cpp", "selftest.cpp"]
+SOURCES = ["api.hip", "stack.hip", "route_permute.hip", "ffn.hip", "ffn_decode.hip", "misc.hip", "calib.hip", "offline.hip", "pack.cpp", "selftest.cpp"]
 # packed-fp32 instructions are switched off for every translation unit (device pass)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

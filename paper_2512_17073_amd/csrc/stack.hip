@@ -55,13 +55,18 @@ namespace {
 uint8_t* slot_w_ptr(const moe_lrc_stack* S, int slot) { return S->d_pool + size_t(slot) * (S->slot_w + S->slot_f); }
 uint8_t* slot_f_ptr(const moe_lrc_stack* S, int slot) { return slot_w_ptr(S, slot) + S->slot_w; }
 
-// least recently used slot that no need of this epoch holds; -1 if every slot is pinned
+// The slot to fill among those no need of this epoch holds: an empty one, else one filled ahead and
+// never used, else the least recently used (lowest index on ties); -1 if every slot is pinned.
 int pick_victim(moe_lrc_stack* S) {
   int best = -1;
+  auto older = [&](const moe_lrc_stack::Slot& a, const moe_lrc_stack::Slot& b) {
+    const bool ae = a.layer < 0, be = b.layer < 0;
+    return ae != be ? ae : a.tick < b.tick;
+  };
   for (int i = 0; i < S->n_slots; ++i) {
     const auto& sl = S->slots[i];
     if (sl.pin == S->epoch) continue;
-    if (best < 0 || sl.tick < S->slots[best].tick) best = i;
+    if (best < 0 || older(sl, S->slots[best])) best = i;
   }
   return best;
 }
@@ -189,7 +194,8 @@ int pool_stage(moe_lrc_layer* L, const void* x, int T, hipStream_t s) {
         if (slot < 0) break;                           // every slot is spoken for
         evict(S, slot);
         auto& sl = S->slots[slot];
-        sl.layer = li + 1; sl.expert = e; sl.fresh = true; sl.tick = ++S->tick;
+        // (least recently used until its layer really uses it: a wrong guess is the first to go)
+        sl.layer = li + 1; sl.expert = e; sl.fresh = true; sl.tick = 0;
         S->where[li + 1][e] = slot;
         S->st.prefetched++;
       }
