@@ -142,6 +142,40 @@ def stack_bench(args, cfg):
         L.close()
 
 
+def offline_bench(args, cfg):
+    """The offline pipeline (quantizer, residual, rank-r factors) on one W1-shaped matrix of the
+    workload, device against the oracle's numpy on the host.  A line of its own."""
+    import torch
+    import paper_2512_17073_amd as amd
+    from oracle import compress
+    K, N, r = cfg.hidden, cfg.ffn, max(cfg.rank, 8)
+    rng = np.random.default_rng(cfg.seed)
+    W = rng.standard_normal((K, N)) * 0.02
+    omega = np.random.default_rng(1).standard_normal((N, r + 8))
+    Wd, Od = torch.from_numpy(W).cuda(), torch.from_numpy(omega).cuda()
+    res = {}
+    for rep in range(2):                                       # (first pass untimed)
+        torch.cuda.synchronize(); t0 = time.perf_counter()
+        codes, scale, zero, E = amd.offline_quantize(Wd, cfg.bits, cfg.group)
+        torch.cuda.synchronize(); t1 = time.perf_counter()
+        A, B, sigma, Ab, Bb = amd.offline_factors(E, r, Od, power_iters=2)
+        t2 = time.perf_counter()
+        res = {"quantize_ms": (t1 - t0) * 1e3, "factors_ms": (t2 - t1) * 1e3}
+    t0 = time.perf_counter()
+    q = compress.quantize_groupwise(W, cfg.bits, cfg.group)
+    Eo = W - compress.dequantize(q, cfg.group)
+    t1 = time.perf_counter()
+    A0, B0, S0 = compress.residual_factors(Eo, r, method="randomized", seed=1, power_iters=2)
+    t2 = time.perf_counter()
+    same = bool((codes.cpu().numpy() == q["codes"]).all())
+    print(json.dumps({
+        "metric": "offline_matrices_per_s", "value": 1e3 / (res["quantize_ms"] + res["factors_ms"]), "unit": "matrices/s",
+        "config": {"workload": cfg.name, "K": K, "N": N, "bits": cfg.bits, "group": cfg.group, "rank": r, "sketch": r + 8, "power_iters": 2},
+        "device_ms": res, "oracle_ms": {"quantize_ms": (t1 - t0) * 1e3, "factors_ms": (t2 - t1) * 1e3},
+        "codes_equal_oracle": same, "sigma_rel_diff_max": float(np.max(np.abs(sigma - S0) / S0)),
+        "dtype": "f64", "data": "synthetic"}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -169,6 +203,9 @@ def main():
                          "live in pinned host memory (a line of its own, metric stack_decode_tokens_per_s)")
     ap.add_argument("--slots", type=int, default=0, help="with --stack: device slots of the shared pool (0: every expert fits)")
     ap.add_argument("--no-prefetch", action="store_true", help="with --stack: no copies ahead for the next layer")
+    ap.add_argument("--offline", action="store_true",
+                    help="instead of the layer: time the offline pipeline (quantizer + residual factors) on one "
+                         "W1-shaped matrix of the workload, device against the oracle on the host")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1", file=sys.stderr)
@@ -184,6 +221,9 @@ def main():
     cfg = configs.get(args.workload)
     if args.stack > 0:
         stack_bench(args, cfg)
+        return
+    if args.offline:
+        offline_bench(args, cfg)
         return
     T = cfg.tokens
     t_setup = time.time()
