@@ -340,11 +340,15 @@ int moe_lrc_selftest_decode_index(int hidden, int ffn, int bits, int group, int 
  *   MOE_LRC_CAL_H2D       copy of `bytes` from pinned host memory to the device, GB/s
  *   MOE_LRC_CAL_MFMA_F16  dense v_mfma_f32_16x16x32_f16 issue rate on registers, TFLOP/s (`bytes` unused)
  *   MOE_LRC_CAL_MFMA_F16_32  the same with v_mfma_f32_32x32x16_f16
+ *   MOE_LRC_CAL_MFMA_VALU  two wavefronts per SIMD issue v_mfma_f32_16x16x32_f16, each followed by
+ *                         `bytes` (0, 2, 4, 8 or 16) independent packed fp16 FMAs: *result = ns per
+ *                         MFMA with its FMAs on one SIMD (how far vector work hides behind MFMAs)
  * result: host pointer to one double. */
 #define MOE_LRC_CAL_HBM_READ 0
 #define MOE_LRC_CAL_H2D      1
 #define MOE_LRC_CAL_MFMA_F16 2
 #define MOE_LRC_CAL_MFMA_F16_32 3
+#define MOE_LRC_CAL_MFMA_VALU 4
 int moe_lrc_calibrate(int kind, size_t bytes, int reps, double* result);
 
 #ifdef __cplusplus

@@ -132,7 +132,7 @@ def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
 
 
-CAL_HBM_READ, CAL_H2D, CAL_MFMA_F16, CAL_MFMA_F16_32 = 0, 1, 2, 3
+CAL_HBM_READ, CAL_H2D, CAL_MFMA_F16, CAL_MFMA_F16_32, CAL_MFMA_VALU = 0, 1, 2, 3, 4
 
 
 def calibrate(kind: int, nbytes: int = 0, reps: int = 5) -> float:

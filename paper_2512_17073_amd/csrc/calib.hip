@@ -87,6 +87,35 @@ __global__ __launch_bounds__(256) void mfma_rate32_kernel(int iters, float* __re
   if (s == 12345.678f) sink[0] = s;
 }
 
+// How far vector ALU work hides behind MFMAs: two wavefronts per SIMD (512 threads, one block per
+// CU) issue rounds of eight independent v_mfma_f32_16x16x32_f16, each followed by NV independent
+// packed fp16 FMAs (the instruction the kernels dequantize with).
+template <int NV>
+__global__ __launch_bounds__(512) void mfma_valu_kernel(int iters, float* __restrict__ sink) {
+  half8_t a, b;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) { a[i] = (_Float16)(0.001f * float((threadIdx.x + i) & 63)); b[i] = (_Float16)(0.002f * float(i + 1)); }
+  float4_t acc[8];
+  uint32_t v[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) { acc[j] = float4_t{0.f, 0.f, 0.f, 0.f}; v[j] = threadIdx.x * 77u + j; }
+  const uint32_t c1 = 0x3c003c00u, c2 = 0x00010001u;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, acc[j], 0, 0, 0);
+#pragma unroll
+      for (int n = 0; n < NV; ++n) asm volatile("v_pk_fma_f16 %0, %0, %1, %2" : "+v"(v[(j * NV + n) & 7]) : "v"(c1), "v"(c2));
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  float s = 0.f;
+  uint32_t x = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) { s += acc[j][0] + acc[j][3]; x ^= v[j]; }
+  if (s == 12345.678f || x == 0x12345u) sink[0] = s;
+}
+
 }  // namespace
 
 }  // namespace lrc
@@ -104,7 +133,9 @@ using namespace lrc;
 
 extern "C" int moe_lrc_calibrate(int kind, size_t bytes, int reps, double* result) {
   if (!result || reps < 1 || reps > 1000) return set_error(MOE_LRC_EINVAL, "calibrate: result is null or reps outside 1..1000");
-  if (kind < MOE_LRC_CAL_HBM_READ || kind > MOE_LRC_CAL_MFMA_F16_32) return set_error(MOE_LRC_EINVAL, "calibrate: unknown kind");
+  if (kind < MOE_LRC_CAL_HBM_READ || kind > MOE_LRC_CAL_MFMA_VALU) return set_error(MOE_LRC_EINVAL, "calibrate: unknown kind");
+  if (kind == MOE_LRC_CAL_MFMA_VALU && bytes != 0 && bytes != 2 && bytes != 4 && bytes != 8 && bytes != 16)
+    return set_error(MOE_LRC_EINVAL, "calibrate: the number of FMAs per MFMA must be 0, 2, 4, 8 or 16");
   if (kind < MOE_LRC_CAL_MFMA_F16 && (bytes < (1u << 20) || bytes > (size_t(16) << 30)))
     return set_error(MOE_LRC_EINVAL, "calibrate: bytes must be between 1 MiB and 16 GiB");
   int rc = MOE_LRC_OK, dev = 0, n_cu = 0;
@@ -148,6 +179,24 @@ extern "C" int moe_lrc_calibrate(int kind, size_t bytes, int reps, double* resul
     }
     std::sort(ms.begin(), ms.end());
     *result = double(bytes) / (ms[ms.size() / 2] * 1e-3) / 1e9;      // GB/s
+  } else if (kind == MOE_LRC_CAL_MFMA_VALU) {
+    const int iters = 4096;
+    for (int i = 0; i < reps + 1; ++i) {
+      CAL_HIP(hipEventRecord(e0, nullptr));
+      switch (bytes) {
+        case 0: hipLaunchKernelGGL(mfma_valu_kernel<0>, dim3(n_cu), dim3(512), 0, nullptr, iters, (float*)sink); break;
+        case 2: hipLaunchKernelGGL(mfma_valu_kernel<2>, dim3(n_cu), dim3(512), 0, nullptr, iters, (float*)sink); break;
+        case 4: hipLaunchKernelGGL(mfma_valu_kernel<4>, dim3(n_cu), dim3(512), 0, nullptr, iters, (float*)sink); break;
+        case 8: hipLaunchKernelGGL(mfma_valu_kernel<8>, dim3(n_cu), dim3(512), 0, nullptr, iters, (float*)sink); break;
+        default: hipLaunchKernelGGL(mfma_valu_kernel<16>, dim3(n_cu), dim3(512), 0, nullptr, iters, (float*)sink); break;
+      }
+      CAL_HIP(hipEventRecord(e1, nullptr));
+      CAL_HIP(hipEventSynchronize(e1));
+      CAL_HIP(hipEventElapsedTime(&t, e0, e1));
+      if (i > 0) ms.push_back(t);
+    }
+    std::sort(ms.begin(), ms.end());
+    *result = ms[ms.size() / 2] * 1e6 / (double(iters) * 8 * 2);      // ns per MFMA (and its FMAs) on one SIMD
   } else {
     const int iters = 4096, blocks = n_cu * 8;
     for (int i = 0; i < reps + 1; ++i) {
