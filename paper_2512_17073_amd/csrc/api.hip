@@ -217,7 +217,7 @@ static int stage_selected(moe_lrc_layer* L, hipStream_t stream) {
 static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t* offsets,
                           const int32_t* row_pair, void* y_rows, uint8_t* ws, hipStream_t stream,
                           bool mark = false, bool keep_partials = false, int* kblocks_out = nullptr,
-                          const int32_t* tok_exp = nullptr) {
+                          const int32_t* tok_exp = nullptr, const PermuteArgs* perm = nullptr) {
   const moe_lrc_config& c = L->cfg;
   const Workspace w = plan_workspace(L, T);
   _Float16* xh = reinterpret_cast<_Float16*>(ws + w.xh);
@@ -250,7 +250,7 @@ static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t*
   a.xa13_here = c.residency != MOE_LRC_RESIDENT || tok_exp == nullptr;
   a.x_tokens = x;
   LRC_HIP(launch_convert_x(L, x, T, xh, P + kActPadRows, offsets, row_pair, L->d_stat, plans,
-                           ((path & 1) || a.xa13_here) ? nullptr : &a, tok_exp, a.row_exp, stream));
+                           ((path & 1) || a.xa13_here) ? nullptr : &a, tok_exp, a.row_exp, perm, stream));
   L->stats_valid = false;
   L->stats.stage_ms = 0.f;
   if (c.residency == MOE_LRC_STAGED) {
@@ -272,7 +272,7 @@ static int run_shared(moe_lrc_layer* L, const void* x, int T, uint8_t* ws, hipSt
   const Workspace w = plan_workspace(L, T);
   _Float16* xh = reinterpret_cast<_Float16*>(ws + w.xh_sh);
   int32_t* row_exp = reinterpret_cast<int32_t*>(ws + w.row_exp_sh);
-  LRC_HIP(launch_convert_x(L, x, T, xh, T + kActPadRows, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, row_exp, stream));
+  LRC_HIP(launch_convert_x(L, x, T, xh, T + kActPadRows, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, row_exp, nullptr, stream));
   FfnArgs a{};
   a.desc = L->d_desc + c.n_experts; a.n_exp = c.n_shared; a.bits = c.shared_bits; a.group = c.group;
   a.rank = 0; a.rpad = 0; a.H = c.hidden; a.F = c.ffn; a.top_k = c.top_k; a.top_n = 0; a.T = T;
@@ -650,8 +650,14 @@ int forward_impl(moe_lrc_layer* L, const void* x, int T, void* out, void* ws, hi
   int32_t* tok_exp = route_writes_exponents(L, T) ? (int32_t*)(b + w.tok_exp) : nullptr;
   LRC_HIP(launch_route(L, x, T, idx, tw, nullptr, tok_exp, s));
   if (mk) LRC_HIP(hipEventRecord(L->marks[MOE_LRC_STAGE_PERMUTE], s));
-  LRC_HIP(launch_permute(L, idx, T, (int32_t*)(b + w.counts), offsets, row_pair, pair_row,
-                         (int32_t*)(b + w.comp_counts), s));
+  // few pairs: every block of the preparing launch groups the pairs itself (one launch fewer)
+  const PermuteArgs perm{idx, (int32_t*)(b + w.counts), offsets, row_pair, pair_row, (int32_t*)(b + w.comp_counts), T * L->cfg.top_k};
+  // (every block repeats the grouping, so only where the preparing launch is one round of blocks
+  // and the tables are small: few experts)
+  const bool fused_permute = perm.P <= kFusedPermuteMaxPairs && L->cfg.n_experts <= 32;
+  if (!fused_permute)
+    LRC_HIP(launch_permute(L, idx, T, (int32_t*)(b + w.counts), offsets, row_pair, pair_row,
+                           (int32_t*)(b + w.comp_counts), s));
   if (mk) LRC_HIP(hipEventRecord(L->marks[MOE_LRC_STAGE_PREP], s));
   // Shared experts need nothing from the router: with resident weights they run on the layer's side
   // stream beside the routed experts (forked here, joined before the combine).  In staged mode the
@@ -667,7 +673,8 @@ int forward_impl(moe_lrc_layer* L, const void* x, int T, void* out, void* ws, hi
   // (the K-block partial sums of a decode-flavour W2 go to the combine as they are: no pass that
   // adds them into bf16 rows first)
   int kblocks = 1;
-  if ((rc = run_expert_ffn(L, x, T, offsets, row_pair, b + w.y_rows, b, s, mk, true, &kblocks, tok_exp))) return rc;
+  if ((rc = run_expert_ffn(L, x, T, offsets, row_pair, b + w.y_rows, b, s, mk, true, &kblocks, tok_exp,
+                           fused_permute ? &perm : nullptr))) return rc;
   if (fork) LRC_HIP(hipStreamWaitEvent(s, L->ev_join, 0));
   else if (L->cfg.n_shared > 0 && (rc = run_shared(L, x, T, b, s))) return rc;
   if (mk) LRC_HIP(hipEventRecord(L->marks[MOE_LRC_STAGE_COMBINE], s));

@@ -100,6 +100,10 @@ hipError_t launch_permute(const moe_lrc_layer* L, const int32_t* idx, int T, int
                           int32_t* offsets, int32_t* row_pair, int32_t* pair_row,
                           int32_t* comp_counts, hipStream_t s);
 struct PlanSpec;   // plan.h
+// the grouping of the pairs by expert run inside the preparing launch (few pairs): the routing
+// kernel's indices in, the five arrays of moe_lrc_permute out
+struct PermuteArgs { const int32_t* idx; int32_t *counts, *offsets, *row_pair, *pair_row, *comp_counts; int P; };
+constexpr int kFusedPermuteMaxPairs = 1024;
 // fp16 copy of the activations in operand order, every row times its power-of-two pre-scale
 // (ffn_common.h; exponents to row_exp, taken from tok_exp per token if given): one row per routed
 // pair (row_pair given) or one per token (row_pair null); with `stat`, one more block counts the
@@ -110,7 +114,8 @@ struct FfnArgs;
 hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _Float16* xg, int rt,
                             const int32_t* offsets, const int32_t* row_pair, int32_t* stat,
                             const PlanSpec* plans /* two, or null */, const FfnArgs* xa13,
-                            const int32_t* tok_exp /* or null */, int32_t* row_exp, hipStream_t s);
+                            const int32_t* tok_exp /* or null */, int32_t* row_exp,
+                            const PermuteArgs* perm /* or null: offsets and row_pair are ready */, hipStream_t s);
 constexpr int kMaxKBlocks = 8;    // most K-blocks the decode W2 kernel splits into
 // blocks (per K-block) of a decode launch that shares its blocks out by a table: `target` (the
 // device's CUs over the K-blocks), or enough for ceil(NT / 32) blocks per expert that can be active
@@ -145,6 +150,7 @@ struct FfnArgs {
                               // the combine instead of adding them into y_rows
   int ksplit13, ksplit2, total_rows;
   int n_cu;                   // compute units of the device (the launches size their grids to fill them)
+  const PermuteArgs* perm;    // forward with few pairs: the preparing launch groups the pairs itself (else null)
   int32_t* row_exp;           // per input row (routed: per routed row; shared: per token): pre-scale exponent
   const int32_t* tok_exp;     // per token, from the routing kernel, or null
   hipEvent_t* marks;          // null, or 4 events recorded after xa13, w13, xa2, w2

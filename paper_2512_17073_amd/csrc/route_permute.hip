@@ -1,6 +1,7 @@
 // Routing (Section 2.1: w = softmax(G(x)), Top-k; Section 3.2: Top-n = first n of the sorted list)
 // and the grouping of (token, slot) pairs by expert.
 #include "internal.h"
+#include "permute_body.h"
 
 namespace lrc {
 
@@ -67,7 +68,6 @@ __device__ inline void select_topk(const double (&v)[4], int lane, int E, int to
 // registers for all experts, and the chunks of the next expert's gate row are in flight while the
 // current one is multiplied.  Wavefront 0 then takes the Top-k with a shuffle arg-max (ties to the
 // lower index) and the softmax weights of the selected experts.
-constexpr int kMaxExperts = 256;
 
 template <int CH, int NW>
 __global__ __launch_bounds__(64 * NW) void route_kernel(const uint16_t* __restrict__ x,
@@ -220,11 +220,7 @@ __global__ __launch_bounds__(256) void topk_kernel(const double* __restrict__ lo
   select_topk(v, lane, E, top_k, renorm, idx + size_t(t) * top_k, w + size_t(t) * top_k);
 }
 
-// Grouping: one workgroup of 16 wavefronts.  Wavefront w owns a contiguous run of pair ids, so
-// pair order (= token order) is kept by walking the run in order and ranking equal experts inside
-// each 64-pair step with ballots; per-(wavefront, expert) counters in LDS carry the positions.
-constexpr int kPermWaves = 16;
-
+// Grouping: one workgroup of 16 wavefronts (permute_body.h).
 __global__ __launch_bounds__(1024) void permute_kernel(const int32_t* __restrict__ idx, int P, int E,
                                                        int top_k, int top_n,
                                                        int32_t* __restrict__ counts,
@@ -232,68 +228,8 @@ __global__ __launch_bounds__(1024) void permute_kernel(const int32_t* __restrict
                                                        int32_t* __restrict__ row_pair,
                                                        int32_t* __restrict__ pair_row,
                                                        int32_t* __restrict__ comp_counts) {
-  __shared__ int32_t hist[kPermWaves][kMaxExperts];
-  __shared__ int32_t comp[kMaxExperts];
-  __shared__ int32_t total[kMaxExperts];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  for (int i = threadIdx.x; i < kPermWaves * kMaxExperts; i += 1024) (&hist[0][0])[i] = 0;
-  for (int i = threadIdx.x; i < kMaxExperts; i += 1024) comp[i] = 0;
-  __syncthreads();
-
-  const int per_wave = ((P + kPermWaves - 1) / kPermWaves + 63) / 64 * 64;
-  const int begin = wave * per_wave, end = min(P, begin + per_wave);
-  for (int i = begin + lane; i < end; i += 64) {
-    const int e = min(max(idx[i], 0), E - 1);     // out-of-range ids cannot leave the LDS tables
-    atomicAdd(&hist[wave][e], 1);
-    if (i % top_k < top_n) atomicAdd(&comp[e], 1);
-  }
-  __syncthreads();
-
-  if (threadIdx.x < E) {
-    int run = 0;
-    for (int wv = 0; wv < kPermWaves; ++wv) {
-      const int c = hist[wv][threadIdx.x];
-      hist[wv][threadIdx.x] = run;
-      run += c;
-    }
-    total[threadIdx.x] = run;
-    counts[threadIdx.x] = run;
-    comp_counts[threadIdx.x] = comp[threadIdx.x];
-  }
-  __syncthreads();
-  if (threadIdx.x < E) {
-    int off = 0;
-    for (int e = 0; e < (int)threadIdx.x; ++e) off += total[e];
-    offsets[threadIdx.x] = off;
-    if ((int)threadIdx.x == E - 1) offsets[E] = off + total[threadIdx.x];
-    for (int wv = 0; wv < kPermWaves; ++wv) hist[wv][threadIdx.x] += off;
-  }
-  __syncthreads();
-
-  int nbits = 0;
-  while ((1 << nbits) < E) ++nbits;
-  for (int base = begin; base < end; base += 64) {
-    const int i = base + lane;
-    const bool valid = i < end;
-    const int e = valid ? min(max(idx[i], 0), E - 1) : 0;
-    unsigned long long same = __ballot(valid);
-    for (int b = 0; b < nbits; ++b) {
-      const bool bit = (e >> b) & 1;
-      const unsigned long long bb = __ballot(valid && bit);
-      same &= bit ? bb : ~bb;
-    }
-    const int rank = __popcll(same & ((1ull << lane) - 1ull));
-    const int cnt = __popcll(same);
-    int pos = 0;
-    if (valid) pos = hist[wave][e] + rank;
-    __builtin_amdgcn_wave_barrier();
-    if (valid && rank == 0) hist[wave][e] = pos + cnt;
-    __builtin_amdgcn_wave_barrier();
-    if (valid) {
-      row_pair[pos] = i;
-      pair_row[i] = pos;
-    }
-  }
+  __shared__ PermuteLds lds;
+  permute_body(lds, idx, P, E, top_k, top_n, counts, offsets, row_pair, pair_row, comp_counts);
 }
 
 }  // namespace

@@ -4,6 +4,10 @@
 #pragma once
 #include "ffn_common.h"
 
+#ifndef XA_BATCH
+#define XA_BATCH 4
+#endif
+
 namespace lrc {
 namespace ffn {
 
@@ -16,7 +20,7 @@ namespace ffn {
 // of every rank step its expert runs).  TOKENS: the rows are read from the bf16 tokens through
 // row_pair (the launch that prepares the activations runs this body in further blocks); otherwise
 // from the fp16 operand-order buffer.
-template <bool DUAL, bool TOKENS, int NW>
+template <bool DUAL, bool TOKENS, int NW, int BATCH = XA_BATCH>
 __device__ __forceinline__ void xa_rows_body(const KArgs& a, const uint16_t* __restrict__ x_bf16, int tile, int e, int kb,
                                              float4_t (*red)[64] /* [2 * NW][64] */) {
   const int r0 = a.offsets[e], cnt = a.offsets[e + 1] - r0;
@@ -66,10 +70,10 @@ __device__ __forceinline__ void xa_rows_body(const KArgs& a, const uint16_t* __r
     const bool any0 = __ballot(flagged[0]) != 0ull, any1 = __ballot(flagged[1]) != 0ull;   // block-uniform
     float4_t acc[2] = {float4_t{0.f, 0.f, 0.f, 0.f}, float4_t{0.f, 0.f, 0.f, 0.f}};
     if (live && (any0 || any1)) {
-      for (int kk = kk0; kk < kk1; kk += 8) {
-        half8_t wf[8], xf[2][8];
+      for (int kk = kk0; kk < kk1; kk += BATCH) {
+        half8_t wf[BATCH], xf[2][BATCH];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < BATCH; ++u) {
           const int ku = max(min(kk + u, kk1 - 1), 0);
           wf[u] = af[(size_t(tl) * k32 + ku) * kWave + lane];
 #pragma unroll
@@ -89,7 +93,7 @@ __device__ __forceinline__ void xa_rows_body(const KArgs& a, const uint16_t* __r
           }
         }
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < BATCH; ++u) {
           if (kk + u >= kk1) wf[u] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};       // (a step past this wavefront's share)
 #pragma unroll
           for (int t = 0; t < 2; ++t) {
