@@ -101,9 +101,7 @@ __device__ inline void stage_step(const KArgs& a, uint4* buf, int ks, int rin, i
 
 typedef float float16_t __attribute__((ext_vector_type(16)));
 constexpr int kRP = kBM / 32;             // 32-row fragments ("row pairs") of a chunk
-#ifndef TILE_LDS_PF
-#define TILE_LDS_PF 2                     // LDS fragment reads in flight ahead of the MFMAs
-#endif
+constexpr int kTileLdsAhead = 2;          // LDS fragment reads in flight ahead of the MFMAs (1 to 4 measured alike)
 
 // fn(std::integral_constant<int, 0>{}) ... fn(std::integral_constant<int, N - 1>{})
 template <int... I, class Fn> __device__ inline void static_for_impl(std::integer_sequence<int, I...>, Fn&& fn) {
@@ -243,7 +241,7 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
   // 8 F is read from LDS kPF fragments ahead of its two MFMAs (one per pair), and the weights of
   // the next sub-step are unpacked, a piece per fragment, behind the MFMAs of the current one, so
   // that the matrix pipe, the LDS reads and the unpacking run side by side within a wavefront.
-  constexpr int kPF = TILE_LDS_PF;
+  constexpr int kPF = kTileLdsAhead;
   auto compute = [&](auto RPN_, const Slot2<BITS, NM, kNTW>& cur, const uint4* buf) {
     constexpr int RPN = decltype(RPN_)::value;
     constexpr int F = 2 * RPN, G = 8 * F;

@@ -4,12 +4,10 @@
 #pragma once
 #include "ffn_common.h"
 
-#ifndef XA_BATCH
-#define XA_BATCH 4
-#endif
-
 namespace lrc {
 namespace ffn {
+
+constexpr int kXaBatch = 4;     // factor and activation units requested together (8 spill in a 1024-thread block)
 
 // (in A)[row][rho] for the rows of the decode flavour, finished in one launch:
 //   P[row][m * ls * 32 + rho] = fp16(lambda_m * sum_k in[row][k] * A_m[k][rho]) for rows that take the
@@ -20,7 +18,7 @@ namespace ffn {
 // of every rank step its expert runs).  TOKENS: the rows are read from the bf16 tokens through
 // row_pair (the launch that prepares the activations runs this body in further blocks); otherwise
 // from the fp16 operand-order buffer.
-template <bool DUAL, bool TOKENS, int NW, int BATCH = XA_BATCH>
+template <bool DUAL, bool TOKENS, int NW, int BATCH = kXaBatch>
 __device__ __forceinline__ void xa_rows_body(const KArgs& a, const uint16_t* __restrict__ x_bf16, int tile, int e, int kb,
                                              float4_t (*red)[64] /* [2 * NW][64] */) {
   const int r0 = a.offsets[e], cnt = a.offsets[e + 1] - r0;
