@@ -113,19 +113,24 @@ template <int N, class Fn> __device__ inline void static_for(Fn&& fn) { static_f
 // at unit ((rp * 8 + s) * 2 + p) * 64; lane l holds, of row 32 rp + l % 32, the 8 inputs of lane
 // group q = p + 2 (l / 32) of sub-step s.  (After the row swap, operand p of a sub-step holds in
 // lanes 0..31 the weights of lane group q = p and in lanes 32..63 those of q = p + 2.)  Wavefront w
-// copies the eight fragments with s = w.
+// of the block's WAVES copies the fragments of sub-steps s = w, w + WAVES, ...
+template <int WAVES>
 __device__ inline void stage_step32(const KArgs& a, uint4* buf, int ks, int rin, int wave, int lane) {
   const uint4* in_units = reinterpret_cast<const uint4*>(a.in);
-  const int n = lane & 31, h = lane >> 5, s = wave;
+  const int n = lane & 31, h = lane >> 5;
 #pragma unroll
-  for (int p = 0; p < 2; ++p) {
-    const int k8 = min(ks * 32 + (p + 2 * h) * 8 + s, a.K / 8 - 1);
+  for (int s0 = 0; s0 < 8; s0 += WAVES) {
+    const int s = s0 + wave;
 #pragma unroll
-    for (int rp = 0; rp < kRP; ++rp) {
-      const int R = min(rin + 32 * rp + n, a.in_rt - 1);
-      __builtin_amdgcn_global_load_lds(
-          reinterpret_cast<const __attribute__((address_space(1))) void*>(reinterpret_cast<uintptr_t>(in_units + act_unit(k8, R, a.in_rt))),
-          reinterpret_cast<__attribute__((address_space(3))) void*>(reinterpret_cast<uintptr_t>(buf + ((rp * 8 + s) * 2 + p) * 64)), 16, 0, 0);
+    for (int p = 0; p < 2; ++p) {
+      const int k8 = min(ks * 32 + (p + 2 * h) * 8 + s, a.K / 8 - 1);
+#pragma unroll
+      for (int rp = 0; rp < kRP; ++rp) {
+        const int R = min(rin + 32 * rp + n, a.in_rt - 1);
+        __builtin_amdgcn_global_load_lds(
+            reinterpret_cast<const __attribute__((address_space(1))) void*>(reinterpret_cast<uintptr_t>(in_units + act_unit(k8, R, a.in_rt))),
+            reinterpret_cast<__attribute__((address_space(3))) void*>(reinterpret_cast<uintptr_t>(buf + ((rp * 8 + s) * 2 + p) * 64)), 16, 0, 0);
+      }
     }
   }
 }
@@ -144,8 +149,11 @@ __device__ inline void rank_frag_source(int v, int lane, bool dual, int& m, int&
 // Codes and metadata of one k-step of a wavefront's two n-tiles.
 template <int BITS, int NM, int NTW> struct Slot2 { Slot<BITS, NM> t[NTW]; };
 
-template <int BITS, bool DUAL, int NTW>
-__global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a) {
+// WAVES wavefronts per block.  8 (two per SIMD, 256 registers each) is what the launches use: with 4
+// (one per SIMD with 512 registers and twice the n-tiles, so that a fragment read from LDS feeds
+// twice the MFMAs) the fused kernel measured 19 % slower: nothing fills a wavefront's waits.
+template <int BITS, bool DUAL, int NTW, int WAVES = kTileWaves>
+__global__ __launch_bounds__(64 * WAVES, WAVES == 4 ? 1 : 2) void qgemm_tile_kernel(KArgs a) {
   extern __shared__ uint4 xs[];           // two k-steps of activations; afterwards the (in A) fragments
   constexpr int NM = DUAL ? 2 : 1;
   constexpr int kNTW = NTW;                              // n-tiles per wavefront
@@ -161,7 +169,7 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
   const int wave = __builtin_amdgcn_readfirstlane(th >> 6);
   const int q = lane >> 4, c = lane & 15;
   const int tdw = kWave * DW;
-  const int tile0 = (blockIdx.x * kTileWaves + wave) * kNTW;
+  const int tile0 = (blockIdx.x * WAVES + wave) * kNTW;
 
   const int code_bytes = a.KS * a.NT * tdw * 4, meta_bytes = a.G * a.NT * kTileN * 4;
   const bool lowrank = a.rank > 0 && __builtin_amdgcn_readfirstlane(d.has_factors) != 0 && a.row_pair != nullptr &&
@@ -308,7 +316,7 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
 
   // ---- prologue: the first k-step of activations and the first two ring slots
   Slot2<BITS, NM, kNTW> ring[2];
-  stage_step32(a, xs, 0, rin, wave, lane);
+  stage_step32<WAVES>(a, xs, 0, rin, wave, lane);
   __builtin_amdgcn_sched_barrier(0);
   fetch(0, ring[0]);
   fetch(1, ring[1]);
@@ -328,7 +336,7 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
       for (int i = 0; i < 2; ++i) {
         const int step = s0 + i;
         if (step < steps) {
-          stage_step32(a, xs + ((step + 1) & 1) * kStepUnits, step + 1, rin, wave, lane);
+          stage_step32<WAVES>(a, xs + ((step + 1) & 1) * kStepUnits, step + 1, rin, wave, lane);
           __builtin_amdgcn_sched_barrier(0);     // (the wait below counts the refill as the only later loads)
           compute(RPN_, ring[i], xs + (step & 1) * kStepUnits);
           fetch(step + 2, ring[i]);
@@ -353,7 +361,7 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void qgemm_tile_kernel(KArgs a)
     asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");   // (everyone is done with what LDS held)
     const _Float16* P = reinterpret_cast<const _Float16*>(a.p);
     const int pitch = NM * a.ls * 32;                                // halves per row
-    for (int f = wave; f < (c1 - c0) * V * kRP; f += kTileWaves) {
+    for (int f = wave; f < (c1 - c0) * V * kRP; f += WAVES) {
       const int rp = f % kRP, g = f / kRP, v = g % V, sl = g / V;
       int m, grp;
       rank_frag_source(v, lane, DUAL, m, grp);
