@@ -70,6 +70,38 @@ def test_null_arguments(lib):
     assert lib.moe_lrc_pack_codes(2, 64, 16, None, None) == -1
 
 
+def test_stack_offline_and_hook_argument_errors_need_no_device(lib):
+    # every one of these is refused on its arguments, before any device call
+    h = C.c_void_p()
+    one = (C.c_void_p * 1)(None)
+    assert lib.moe_lrc_stack_create(None, 1, 8, 0, C.byref(h)) == -1
+    assert lib.moe_lrc_stack_create(one, 1, 8, 0, None) == -1
+    assert lib.moe_lrc_stack_create(one, 0, 8, 0, C.byref(h)) == -1          # no layers
+    assert lib.moe_lrc_stack_create(one, 1, 8, 4, C.byref(h)) == -1          # unknown flag
+    assert not h.value
+    assert lib.moe_lrc_stack_destroy(None) == 0
+    assert lib.moe_lrc_stack_step(None, None, 1, None, None, None) == -1
+    assert lib.moe_lrc_stack_get_stats(None, None) == -1
+    assert lib.moe_lrc_stack_reset(None) == -1
+    assert lib.moe_lrc_forward_noalloc(None, None, 1, None, None) == -1
+    assert lib.moe_lrc_offline_quantize(None, 64, 16, 2, 64, None, None, None, None, None) == -1
+    dummy = C.c_void_p(256)                                                  # never dereferenced: shape errors come first
+    assert lib.moe_lrc_offline_quantize(dummy, 64, 16, 5, 64, dummy, dummy, dummy, None, None) == -1     # bits
+    assert lib.moe_lrc_offline_quantize(dummy, 100, 16, 2, 64, dummy, dummy, dummy, None, None) == -2    # K not a multiple of group
+    assert lib.moe_lrc_offline_factors(None, 64, 64, 8, None, 16, 2, None, None, None, None, None) == -1
+    assert lib.moe_lrc_offline_factors(dummy, 64, 64, 8, dummy, 4, 2, dummy, dummy, None, None, None) == -2   # sketch narrower than the rank
+    assert lib.moe_lrc_offline_factors(dummy, 64, 64, 8, dummy, 80, 2, dummy, dummy, None, None, None) == -2  # sketch wider than the matrix
+    assert lib.moe_lrc_offline_factors(dummy, 64, 64, 8, dummy, 16, 9, dummy, dummy, None, None, None) == -1  # power iterations
+    assert lib.moe_lrc_offline_kurtosis(None, 10, None) == -1
+    k = C.c_double()
+    assert lib.moe_lrc_offline_kurtosis(dummy, 0, C.byref(k)) == -1
+    assert lib.moe_lrc_calibrate(9, 1 << 20, 1, C.byref(k)) == -1            # unknown kind
+    assert lib.moe_lrc_calibrate(4, 3, 1, C.byref(k)) == -1                  # FMAs per MFMA not in {0, 2, 4, 8, 16}
+    assert lib.moe_lrc_calibrate(0, 1 << 20, 0, C.byref(k)) == -1            # reps
+    assert lib.moe_lrc_selftest_half_rounding(None, 1, None) == -1
+    assert binding.last_error()
+
+
 @pytest.mark.parametrize("bits", [2, 3, 4])
 def test_pack_roundtrip_exhaustive_block(lib, bits):
     # one packing block is 256 x 16: put every code value at every lane-local position
