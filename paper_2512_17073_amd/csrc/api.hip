@@ -465,8 +465,9 @@ int moe_lrc_set_expert_ranked(moe_lrc_layer* L, int expert, int mat, const uint8
   else LRC_HIP(hipMemcpy(L->d_w + woff - L->dev_w_base, wbuf.data(), wbuf.size(), hipMemcpyHostToDevice));
 
   // Factors: the layouts are rank-major, so the pair of rank `rank` is a prefix of the projection's A
-  // section and a prefix of its B section; the rest of both sections is kept zero in the device slot
-  // (the kernels run the layer's rank on every expert), and only the prefixes are staged.
+  // section and a prefix of its B section; only the prefixes are staged.  (The kernels take each
+  // projection's own rank from the expert table and read nothing past it; the rest of both sections
+  // is kept zero in the device slot all the same.)
   if (b.f_bytes > 0) {
     const MatLayout fm = make_layout(m.K, m.N, m.bits, m.group, rank);     // sizes of the prefixes
     const size_t aoff = L->f_off[expert] + b.off_af[mat], boff = L->f_off[expert] + b.off_bf[mat];

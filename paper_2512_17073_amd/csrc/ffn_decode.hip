@@ -4,7 +4,7 @@
 //   - one block of 16 wavefronts per CU.  For routed experts every block reads which expert it
 //     serves, which share of the expert's n-tiles and where the expert's rows are from one 32-byte
 //     entry of a table the preparing launch has made (plan.h): experts without rows get no blocks,
-//     experts whose rows need two row tiles or several passes get more;
+//     experts whose rows need several 32-row passes get more;
 //   - the activations of the expert (up to 32 rows) are staged into 128 KB of LDS once per phase of
 //     16 (or 8) k-steps by direct global -> LDS copies, issued together with the first packed tiles
 //     and the (in A) fragments: one memory round trip before the first multiply;
@@ -37,9 +37,10 @@ using namespace dec;
 
 
 // One expert's share of a block: MT = row tiles per pass (1 when the expert has at most 16 rows).
-// (v_mfma_f32_32x32x16_f16 runs at twice the rate of the 16x16x32 shape used here, and a pass of 32
-// rows can be put on it by swapping 16-lane rows between the two streams' registers; measured, the
-// four swaps per sub-step cost this issue-bound kernel more than the two matrix instructions save.)
+// (A pass of 32 rows can be put on v_mfma_f32_32x32x16_f16, which has the same peak rate as the
+// 16x16x32 shape used here and needs half as many instructions, by swapping 16-lane rows between the
+// two streams' registers; measured, the four swaps per sub-step cost this kernel more than the two
+// matrix instructions save.)
 template <int BITS, bool DUAL, int MT>
 __device__ __forceinline__ void decode_body(const KArgs& a, uint4* xs, const int e, const int r0, const int cnt,
                                             const int b, const int G) {

@@ -4,8 +4,8 @@
 // several 32-row passes finish last.  One wavefront (part of the launch that prepares the
 // activations) writes, for every block of the later launch, which expert it serves: each expert with
 // rows gets `base` blocks (enough for 32 n-tiles per block), the rest of `target` blocks go by
-// weight (5 for up to 16 rows, 8 per 32-row pass beyond: what they cost), dealt by the running
-// sum of the weights.  Entry i of the table (PlanEntry, 32 bytes, read by block i with one scalar
+// weight (the number of 32-row passes the expert's rows need: every pass streams its weights
+// again), dealt by the running sum of the weights.  Entry i of the table (PlanEntry, 32 bytes, read by block i with one scalar
 // load): expert (or -1: the block exits), index of the block within the expert, blocks of the expert,
 // first row and number of rows of the expert.
 #pragma once
