@@ -269,6 +269,13 @@ int moe_lrc_offline_factors(const double* E_dev, int K, int N, int rank, const d
  * kappa = mean((w - mu)^4) / mean((w - mu)^2)^2, to *kappa (host). */
 int moe_lrc_offline_kurtosis(const double* W_dev, size_t n, double* kappa);
 
+/* Host-only (no device): the greedy bucketed rank allocation of Section 3.1 step 1.  In descending
+ * order of kurtosis (kappa_host [n]; equal values in index order) every matrix takes the largest
+ * value of buckets_host [n_buckets] (the paper's {0, 16, 32, 128, 256, 512, 1024}) that keeps the sum
+ * of the ranks given out so far within n * r_avg; ranks_host [n] receives them (0 if none fits). */
+int moe_lrc_offline_allocate_ranks(const double* kappa_host, int n, int r_avg, const int32_t* buckets_host, int n_buckets,
+                                   int32_t* ranks_host);
+
 /* Host-only: the quantizer's fp64 -> fp16 rounding (to nearest, ties to even, one rounding) of n
  * values, for checking against another implementation. */
 int moe_lrc_selftest_half_rounding(const double* in_host, size_t n, uint16_t* out_host);

@@ -26,7 +26,7 @@ EXPORTS = [
     "moe_lrc_packed_bytes", "moe_lrc_pack_codes", "moe_lrc_unpack_codes", "moe_lrc_get_stats",
     "moe_lrc_profile_enable", "moe_lrc_profile_read", "moe_lrc_calibrate",
     "moe_lrc_selftest_decode_index",
-    "moe_lrc_offline_quantize", "moe_lrc_offline_factors", "moe_lrc_offline_kurtosis", "moe_lrc_selftest_half_rounding",
+    "moe_lrc_offline_quantize", "moe_lrc_offline_factors", "moe_lrc_offline_kurtosis", "moe_lrc_offline_allocate_ranks", "moe_lrc_selftest_half_rounding",
     "moe_lrc_stack_create", "moe_lrc_stack_destroy", "moe_lrc_stack_step", "moe_lrc_stack_get_stats", "moe_lrc_stack_reset",
 ]
 STAGES = ["route", "permute", "prep", "xa13", "w13", "xa2", "w2", "shared", "combine"]
@@ -99,6 +99,7 @@ def lib() -> C.CDLL:
         L.moe_lrc_offline_factors.argtypes = [vp, i32, i32, i32, vp, i32, i32, vp, vp, vp, vp, vp]
         L.moe_lrc_offline_kurtosis.argtypes = [vp, sz, C.POINTER(C.c_double)]
         L.moe_lrc_selftest_half_rounding.argtypes = [vp, sz, vp]
+        L.moe_lrc_offline_allocate_ranks.argtypes = [vp, i32, i32, vp, i32, vp]
         L.moe_lrc_stack_create.argtypes = [C.POINTER(vp), i32, i32, i32, C.POINTER(vp)]
         L.moe_lrc_stack_destroy.argtypes = [vp]
         L.moe_lrc_stack_step.argtypes = [vp, vp, i32, vp, vp, vp]
@@ -360,6 +361,15 @@ def offline_kurtosis(W) -> float:
     out = C.c_double(0.0)
     _check(lib().moe_lrc_offline_kurtosis(W.data_ptr(), W.numel(), C.byref(out)))
     return out.value
+
+
+def allocate_ranks(kappas, r_avg: int, buckets=(0, 16, 32, 128, 256, 512, 1024)) -> np.ndarray:
+    """moe_lrc_offline_allocate_ranks (host only)."""
+    k = _host(np.asarray(kappas, dtype=np.float64).ravel(), np.float64)
+    bk = _host(np.asarray(buckets), np.int32)
+    out = np.zeros(k.size, dtype=np.int32)
+    _check(lib().moe_lrc_offline_allocate_ranks(_hp(k), k.size, int(r_avg), _hp(bk), bk.size, _hp(out)))
+    return out
 
 
 def f64_to_f16_bits(a: np.ndarray) -> np.ndarray:

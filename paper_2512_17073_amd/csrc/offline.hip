@@ -429,6 +429,30 @@ done:
   return rc;
 }
 
+int moe_lrc_offline_allocate_ranks(const double* kappa_host, int n, int r_avg, const int32_t* buckets_host, int n_buckets,
+                                   int32_t* ranks_host) {
+  if (!kappa_host || !buckets_host || !ranks_host) return set_error(MOE_LRC_EINVAL, "offline_allocate_ranks: null argument");
+  if (n <= 0 || n_buckets <= 0 || r_avg < 0) return set_error(MOE_LRC_EINVAL, "offline_allocate_ranks: n, n_buckets must be positive, r_avg not negative");
+  for (int i = 0; i < n_buckets; ++i)
+    if (buckets_host[i] < 0) return set_error(MOE_LRC_EINVAL, "offline_allocate_ranks: negative bucket value");
+  // in descending kurtosis order (equal values: lower index first), every matrix takes the largest
+  // bucket value that keeps the running total within n * r_avg
+  std::vector<int> order(n);
+  std::iota(order.begin(), order.end(), 0);
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return kappa_host[a] > kappa_host[b]; });
+  const long long budget = (long long)n * r_avg;
+  long long used = 0;
+  for (int i : order) {
+    int best = 0;
+    bool any = false;
+    for (int j = 0; j < n_buckets; ++j)
+      if (used + buckets_host[j] <= budget && (!any || buckets_host[j] > best)) { best = buckets_host[j]; any = true; }
+    ranks_host[i] = any ? best : 0;
+    used += ranks_host[i];
+  }
+  return MOE_LRC_OK;
+}
+
 int moe_lrc_selftest_half_rounding(const double* in_host, size_t n, uint16_t* out_host) {
   if (!in_host || !out_host) return set_error(MOE_LRC_EINVAL, "selftest_half_rounding: null argument");
   for (size_t i = 0; i < n; ++i) out_host[i] = f64_to_f16_bits(in_host[i]);

@@ -26,3 +26,22 @@ def test_f64_to_f16_rounding_matches_numpy():
     bad = np.flatnonzero(got != want)
     assert bad.size == 0, (a[bad[:5]], got[bad[:5]], want[bad[:5]])
     assert amd.f64_to_f16_bits(np.array([np.nan]))[0] & 0x7c00 == 0x7c00
+
+
+def test_rank_allocation_matches_the_oracle_and_the_literal_example():
+    from oracle import compress
+    # Section 3.1 step 1, taken literally: N = 8 matrices, R_avg = 32, the paper's bucket -> the matrix
+    # with the largest kurtosis takes 256 = the whole budget, the others nothing
+    kap = np.array([3.1, 9.0, 3.0, 4.5, 3.3, 2.9, 5.0, 3.2])
+    got = amd.allocate_ranks(kap, 32)
+    assert got.tolist() == [0, 256, 0, 0, 0, 0, 0, 0]
+    assert got.tolist() == compress.allocate_ranks(kap, 32).tolist()
+    rng = np.random.default_rng(0)
+    for n, r_avg, buckets in ((24, 32, compress.RANK_BUCKETS), (24, 100, compress.RANK_BUCKETS), (7, 16, (0, 8, 16, 32)),
+                              (192, 40, compress.RANK_BUCKETS), (5, 0, compress.RANK_BUCKETS)):
+        kap = rng.gamma(2.0, 2.0, n) + 1.8
+        kap[rng.integers(0, n, 3)] = kap[0]                  # ties: index order
+        want = compress.allocate_ranks(kap, r_avg, buckets)
+        got = amd.allocate_ranks(kap, r_avg, buckets)
+        assert got.tolist() == want.tolist()
+        assert got.sum() <= n * r_avg and set(got.tolist()) <= set(buckets)
