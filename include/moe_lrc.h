@@ -254,6 +254,17 @@ int moe_lrc_stack_reset(moe_lrc_stack* stack);
 int moe_lrc_offline_quantize(const double* W_dev, int K, int N, int bits, int group, uint8_t* codes_dev,
                              uint16_t* scale_dev, uint16_t* zero_dev, double* residual_dev, void* stream);
 
+/* moe_lrc_offline_quantize with the zero points refined by a half-quadratic solver (Section 3.1
+ * step 2: "HQQ-style weight optimization"; the paper gives no parameters, the customary ones are
+ * iters = 20, p = 0.7, beta = 10, kappa = 1.01).  Per group, with the min/max scale kept and a
+ * real-valued zero point z, `iters` times: q = clamp(round(w / scale + z)); e = shrink(w - (q - z) scale)
+ * with shrink(x) = sign(x) max(|x| - |x|^(p-1) / beta, 0); z = mean over the group of
+ * (q - (w - e) / scale); beta *= kappa.  Then z is rounded to fp16 and the codes are chosen for the
+ * stored values.  iters = 0 gives moe_lrc_offline_quantize.  Same outputs; asynchronous on `stream`. */
+int moe_lrc_offline_quantize_refined(const double* W_dev, int K, int N, int bits, int group, int iters, double p, double beta,
+                                     double kappa, uint8_t* codes_dev, uint16_t* scale_dev, uint16_t* zero_dev,
+                                     double* residual_dev, void* stream);
+
 /* Rank-`rank` factors of E [K][N] (device, fp64), Section 3.1 step 2: A = U sqrt(S) [K][rank] and
  * B = sqrt(S) V^T [rank][N] (device, fp64) for the `rank` leading singular triplets, found by a
  * subspace iteration from the test matrix omega_dev [N][l] (device, fp64; standard normal entries,

@@ -53,6 +53,53 @@ def quantize_groupwise(W: np.ndarray, bits: int, group: int) -> dict:
     return {"codes": codes, "scale": s.view(np.uint16), "zero": z.view(np.uint16)}
 
 
+def shrink_lp(x: np.ndarray, beta: float, p: float) -> np.ndarray:
+    """Generalised soft threshold of the half-quadratic solver: sign(x) max(|x| - |x|^(p-1) / beta, 0)
+    (0 at x = 0).  For p = 1 this is the ordinary soft threshold with width 1 / beta."""
+    ax = np.abs(x)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        t = np.where(ax > 0, ax - ax ** (p - 1.0) / beta, 0.0)
+    return np.sign(x) * np.maximum(t, 0.0)
+
+
+def quantize_refined(W: np.ndarray, bits: int, group: int, iters: int = 20, p: float = 0.7, beta: float = 10.0,
+                     kappa: float = 1.01) -> dict:
+    """Q(W) with the zero points refined by a half-quadratic solver (Section 3.1 step 2 names an
+    "HQQ-style weight optimization" without parameters; this is the published half-quadratic scheme
+    with its customary settings: l_p error with p = 0.7, penalty 10 growing by 1 % per step, 20 steps).
+    Per group, with the min/max scale s (rounded to fp16) kept fixed and the zero point z real-valued:
+        q  = clamp(round(w / s + z), 0, 2^bits - 1)
+        e  = shrink_lp(w - (q - z) s, beta, p)          (the part of the error the l_p term keeps)
+        z  = mean over the group of (q - (w - e) / s)   (least squares for what is left)
+        beta <- kappa beta
+    then z is rounded to fp16 and the codes are chosen once more for the stored values.  iters = 0 is
+    quantize_groupwise.  Degenerate groups are handled as there."""
+    K, N = W.shape
+    if K % group:
+        raise ValueError("K must be a multiple of the group size")
+    levels = (1 << bits) - 1
+    Wg = np.asarray(W, dtype=np.float64).reshape(K // group, group, N)
+    lo, hi = Wg.min(axis=1), Wg.max(axis=1)
+    with np.errstate(divide="ignore", invalid="ignore", over="ignore"):
+        s16 = ((hi - lo) / levels).astype(np.float16)
+        degenerate = ~(s16.astype(np.float64) > 0) | ~np.isfinite(s16.astype(np.float64))
+        s16 = np.where(degenerate, np.float16(1.0), s16)
+        s = s16.astype(np.float64)
+        z = np.where(degenerate, -lo, -lo / s)
+        b = float(beta)
+        for _ in range(iters):
+            q = np.clip(np.rint(Wg / s[:, None, :] + z[:, None, :]), 0, levels)
+            e = shrink_lp(Wg - (q - z[:, None, :]) * s[:, None, :], b, p)
+            z_new = (q - (Wg - e) / s[:, None, :]).mean(axis=1)
+            z = np.where(degenerate, z, z_new)
+            b *= kappa
+        z16 = z.astype(np.float16)
+        q = np.rint(Wg / s[:, None, :] + z16.astype(np.float64)[:, None, :])
+    q = np.where(degenerate[:, None, :], 0.0, q)
+    codes = np.clip(q, 0, levels).astype(np.uint8).reshape(K, N)
+    return {"codes": codes, "scale": s16.view(np.uint16), "zero": z16.view(np.uint16)}
+
+
 def dequantize(q: dict, group: int) -> np.ndarray:
     """Qinv(Q(W)) in fp64 from the stored values."""
     s = np.repeat(q["scale"].view(np.float16).astype(np.float64), group, axis=0)

@@ -26,7 +26,7 @@ EXPORTS = [
     "moe_lrc_packed_bytes", "moe_lrc_pack_codes", "moe_lrc_unpack_codes", "moe_lrc_get_stats",
     "moe_lrc_profile_enable", "moe_lrc_profile_read", "moe_lrc_calibrate",
     "moe_lrc_selftest_decode_index",
-    "moe_lrc_offline_quantize", "moe_lrc_offline_factors", "moe_lrc_offline_kurtosis", "moe_lrc_offline_allocate_ranks", "moe_lrc_selftest_half_rounding",
+    "moe_lrc_offline_quantize", "moe_lrc_offline_quantize_refined", "moe_lrc_offline_factors", "moe_lrc_offline_kurtosis", "moe_lrc_offline_allocate_ranks", "moe_lrc_selftest_half_rounding",
     "moe_lrc_stack_create", "moe_lrc_stack_destroy", "moe_lrc_stack_step", "moe_lrc_stack_get_stats", "moe_lrc_stack_reset",
 ]
 STAGES = ["route", "permute", "prep", "xa13", "w13", "xa2", "w2", "shared", "combine"]
@@ -96,6 +96,7 @@ def lib() -> C.CDLL:
         L.moe_lrc_calibrate.argtypes = [i32, sz, i32, C.POINTER(C.c_double)]
         L.moe_lrc_selftest_decode_index.argtypes = [i32] * 14
         L.moe_lrc_offline_quantize.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp]
+        L.moe_lrc_offline_quantize_refined.argtypes = [vp, i32, i32, i32, i32, i32, C.c_double, C.c_double, C.c_double, vp, vp, vp, vp, vp]
         L.moe_lrc_offline_factors.argtypes = [vp, i32, i32, i32, vp, i32, i32, vp, vp, vp, vp, vp]
         L.moe_lrc_offline_kurtosis.argtypes = [vp, sz, C.POINTER(C.c_double)]
         L.moe_lrc_selftest_half_rounding.argtypes = [vp, sz, vp]
@@ -324,17 +325,25 @@ class Layer:
 
 
 # ---- offline pipeline (device tensors in, device tensors out) ---------------------------------
-def offline_quantize(W, bits: int, group: int, want_residual: bool = True):
+def offline_quantize(W, bits: int, group: int, want_residual: bool = True, refine: Optional[dict] = None):
     """moe_lrc_offline_quantize: W [K][N] torch.float64 on the device -> (codes uint8 [K][N],
-    scale, zero as int16 views of fp16 bits [K/group][N], residual float64 [K][N] or None)."""
+    scale, zero as int16 views of fp16 bits [K/group][N], residual float64 [K][N] or None).
+    refine = {"iters", "p", "beta", "kappa"} (any subset): moe_lrc_offline_quantize_refined."""
     import torch
     K, N = W.shape
     codes = torch.empty((K, N), dtype=torch.uint8, device=W.device)
     scale = torch.empty((K // group, N), dtype=torch.int16, device=W.device)
     zero = torch.empty((K // group, N), dtype=torch.int16, device=W.device)
     resid = torch.empty((K, N), dtype=torch.float64, device=W.device) if want_residual else None
-    _check(lib().moe_lrc_offline_quantize(W.data_ptr(), K, N, bits, group, codes.data_ptr(), scale.data_ptr(),
-                                          zero.data_ptr(), resid.data_ptr() if want_residual else None, _stream()))
+    rp = resid.data_ptr() if want_residual else None
+    if refine is None:
+        _check(lib().moe_lrc_offline_quantize(W.data_ptr(), K, N, bits, group, codes.data_ptr(), scale.data_ptr(),
+                                              zero.data_ptr(), rp, _stream()))
+    else:
+        _check(lib().moe_lrc_offline_quantize_refined(W.data_ptr(), K, N, bits, group, int(refine.get("iters", 20)),
+                                                      float(refine.get("p", 0.7)), float(refine.get("beta", 10.0)),
+                                                      float(refine.get("kappa", 1.01)), codes.data_ptr(), scale.data_ptr(),
+                                                      zero.data_ptr(), rp, _stream()))
     return codes, scale, zero, resid
 
 

@@ -67,6 +67,69 @@ __global__ __launch_bounds__(256) void quantize_kernel(const double* __restrict_
   }
 }
 
+// The same with the zero points refined by a half-quadratic solver ("HQQ-style weight optimization",
+// Section 3.1 step 2; the published scheme: l_p error, p < 1, penalty beta growing by kappa per step).
+// Per group, scale fixed, zero point z real-valued:
+//   q = clamp(round(w / s + z));  e = shrink(w - (q - z) s);  z = mean(q - (w - e) / s);  beta *= kappa
+// with shrink(x) = sign(x) max(|x| - |x|^(p-1) / beta, 0); then z is rounded to fp16 and the codes are
+// chosen for the stored values.  The group's entries are re-read from memory in every step (they stay
+// in cache); sums run in index order.
+__global__ __launch_bounds__(256) void quantize_refined_kernel(const double* __restrict__ W, int K, int N, int bits, int group,
+                                                               int iters, double p, double beta, double kappa,
+                                                               uint8_t* __restrict__ codes, uint16_t* __restrict__ scale,
+                                                               uint16_t* __restrict__ zero, double* __restrict__ resid) {
+#pragma clang fp contract(off)
+  const int n = blockIdx.x * 256 + threadIdx.x, g = blockIdx.y;
+  if (n >= N) return;
+  const double* w = W + size_t(g) * group * N + n;
+  double lo = w[0], hi = w[0];
+  for (int i = 1; i < group; ++i) {
+    const double v = w[size_t(i) * N];
+    lo = v < lo ? v : lo;
+    hi = v > hi ? v : hi;
+  }
+  const int levels = (1 << bits) - 1;
+  uint16_t sb = f64_to_f16_bits((hi - lo) / double(levels));
+  double s = f16_bits_to_f64(sb);
+  const bool degenerate = !(s > 0.0) || (sb & 0x7fffu) >= 0x7c00u;
+  double z;
+  if (degenerate) { sb = 0x3c00u; s = 1.0; z = -lo; }
+  else z = -lo / s;
+  if (!degenerate) {
+    double b = beta;
+    for (int it = 0; it < iters; ++it) {
+      double sum = 0.0;
+      for (int i = 0; i < group; ++i) {
+        const double v = w[size_t(i) * N];
+        double q = __builtin_rint(v / s + z);
+        q = q < 0.0 ? 0.0 : (q > double(levels) ? double(levels) : q);
+        const double x = v - (q - z) * s, ax = fabs(x);
+        double e = 0.0;
+        if (ax > 0.0) {
+          const double t = ax - pow(ax, p - 1.0) / b;
+          e = t > 0.0 ? (x < 0.0 ? -t : t) : 0.0;
+        }
+        sum += q - (v - e) / s;
+      }
+      z = sum / double(group);
+      b *= kappa;
+    }
+  }
+  const uint16_t zb = f64_to_f16_bits(z);
+  z = f16_bits_to_f64(zb);
+  scale[size_t(g) * N + n] = sb;
+  zero[size_t(g) * N + n] = zb;
+  for (int i = 0; i < group; ++i) {
+    const size_t at = (size_t(g) * group + i) * N + n;
+    const double v = w[size_t(i) * N];
+    double q = degenerate ? 0.0 : __builtin_rint(v / s + z);
+    q = q < 0.0 ? 0.0 : (q > double(levels) ? double(levels) : q);
+    if (!(q == q)) q = 0.0;
+    codes[at] = uint8_t(int(q));
+    if (resid) resid[at] = v - (q - z) * s;
+  }
+}
+
 // ---------------------------------------------------------------------------------- kurtosis
 // Partial sums of one pass in fp64: blocks of 256 threads over a grid-stride range, one partial per
 // block, added up on the host in block order (deterministic).
@@ -295,6 +358,20 @@ int moe_lrc_offline_quantize(const double* W_dev, int K, int N, int bits, int gr
   if (K <= 0 || N <= 0 || group <= 0 || K % group) return set_error(MOE_LRC_ESHAPE, "offline_quantize: K must be a positive multiple of group");
   hipLaunchKernelGGL(quantize_kernel, dim3((N + 255) / 256, K / group), dim3(256), 0, (hipStream_t)stream, W_dev, K, N, bits, group,
                      codes_dev, scale_dev, zero_dev, residual_dev);
+  LRC_HIP(hipGetLastError());
+  return MOE_LRC_OK;
+}
+
+int moe_lrc_offline_quantize_refined(const double* W_dev, int K, int N, int bits, int group, int iters, double p, double beta,
+                                     double kappa, uint8_t* codes_dev, uint16_t* scale_dev, uint16_t* zero_dev,
+                                     double* residual_dev, void* stream) {
+  if (!W_dev || !codes_dev || !scale_dev || !zero_dev) return set_error(MOE_LRC_EINVAL, "offline_quantize_refined: null argument");
+  if (bits < 2 || bits > 4) return set_error(MOE_LRC_EINVAL, "offline_quantize_refined: bits must be 2, 3 or 4");
+  if (iters < 0 || iters > 1000 || !(p > 0.0 && p <= 1.0) || !(beta > 0.0) || !(kappa >= 1.0))
+    return set_error(MOE_LRC_EINVAL, "offline_quantize_refined: need 0 <= iters <= 1000, 0 < p <= 1, beta > 0, kappa >= 1");
+  if (K <= 0 || N <= 0 || group <= 0 || K % group) return set_error(MOE_LRC_ESHAPE, "offline_quantize_refined: K must be a positive multiple of group");
+  hipLaunchKernelGGL(quantize_refined_kernel, dim3((N + 255) / 256, K / group), dim3(256), 0, (hipStream_t)stream, W_dev, K, N, bits, group,
+                     iters, p, beta, kappa, codes_dev, scale_dev, zero_dev, residual_dev);
   LRC_HIP(hipGetLastError());
   return MOE_LRC_OK;
 }

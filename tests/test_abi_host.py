@@ -88,6 +88,13 @@ def test_stack_offline_and_hook_argument_errors_need_no_device(lib):
     dummy = C.c_void_p(256)                                                  # never dereferenced: shape errors come first
     assert lib.moe_lrc_offline_quantize(dummy, 64, 16, 5, 64, dummy, dummy, dummy, None, None) == -1     # bits
     assert lib.moe_lrc_offline_quantize(dummy, 100, 16, 2, 64, dummy, dummy, dummy, None, None) == -2    # K not a multiple of group
+    qr = lib.moe_lrc_offline_quantize_refined
+    assert qr(None, 64, 16, 2, 64, 20, 0.7, 10.0, 1.01, None, None, None, None, None) == -1
+    assert qr(dummy, 64, 16, 2, 64, -1, 0.7, 10.0, 1.01, dummy, dummy, dummy, None, None) == -1         # steps
+    assert qr(dummy, 64, 16, 2, 64, 20, 1.5, 10.0, 1.01, dummy, dummy, dummy, None, None) == -1         # p
+    assert qr(dummy, 64, 16, 2, 64, 20, 0.7, 0.0, 1.01, dummy, dummy, dummy, None, None) == -1          # beta
+    assert qr(dummy, 64, 16, 2, 64, 20, 0.7, 10.0, 0.5, dummy, dummy, dummy, None, None) == -1          # kappa
+    assert qr(dummy, 100, 16, 2, 64, 20, 0.7, 10.0, 1.01, dummy, dummy, dummy, None, None) == -2        # K not a multiple of group
     assert lib.moe_lrc_offline_factors(None, 64, 64, 8, None, 16, 2, None, None, None, None, None) == -1
     assert lib.moe_lrc_offline_factors(dummy, 64, 64, 8, dummy, 4, 2, dummy, dummy, None, None, None) == -2   # sketch narrower than the rank
     assert lib.moe_lrc_offline_factors(dummy, 64, 64, 8, dummy, 80, 2, dummy, dummy, None, None, None) == -2  # sketch wider than the matrix

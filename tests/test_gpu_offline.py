@@ -58,6 +58,36 @@ def test_quantizer_bit_exact(amd, bits, group, K, N):
     assert (np.abs(E)[regular] <= 0.5 * s[regular] * (1 + 2e-3) + 1e-12).all()
 
 
+@pytest.mark.parametrize("bits,group", [(2, 64), (3, 64), (4, 128)])
+def test_refined_quantizer_against_the_oracle(amd, bits, group):
+    rng = np.random.default_rng(40 + bits)
+    K, N = 512, 320
+    W = rng.standard_normal((K, N)) * 0.02
+    W *= 1.0 + 9.0 * (rng.random((K, N)) < 0.01)
+    W[:group, 0] = 0.25                                     # a constant group
+    want = compress.quantize_refined(W, bits, group)
+    codes, scale, zero, resid = amd.offline_quantize(_dev(W), bits, group, refine={})
+    codes, scale, zero = codes.cpu().numpy(), _bits(scale), _bits(zero)
+    np.testing.assert_array_equal(scale, want["scale"])
+    # The zero point comes out of twenty steps that call pow(); the two libraries' pow may differ in
+    # the last bit, which can move a zero point that sits on a rounding boundary: allow one group in
+    # ten thousand to differ by one fp16 step (and its codes by one), nothing else.
+    dz = zero.astype(np.int64) - want["zero"].astype(np.int64)
+    assert (np.abs(dz) <= 1).all() and (dz != 0).mean() <= 1e-4
+    dc = codes.astype(np.int64) - want["codes"].astype(np.int64)
+    assert (np.abs(dc) <= 1).all() and (dc != 0).mean() <= 1e-4
+    got = {"codes": codes, "scale": scale, "zero": zero}
+    lp = lambda q: (np.abs(W - compress.dequantize(q, group)) ** 0.7).sum()
+    assert abs(lp(got) - lp(want)) <= 1e-6 * lp(want)
+    assert lp(got) < lp(compress.quantize_groupwise(W, bits, group))
+    np.testing.assert_array_equal(resid.cpu().numpy(), W - compress.dequantize(got, group))
+    # no steps: the plain quantizer, bit for bit
+    c0, s0, z0, _ = amd.offline_quantize(_dev(W), bits, group, refine={"iters": 0})
+    base = compress.quantize_groupwise(W, bits, group)
+    np.testing.assert_array_equal(c0.cpu().numpy(), base["codes"])
+    np.testing.assert_array_equal(_bits(z0), base["zero"])
+
+
 def test_kurtosis(amd):
     rng = np.random.default_rng(3)
     for W in (rng.standard_normal((700, 513)), rng.laplace(size=(300, 1001)) * 0.05 + 0.01, rng.random((257, 129))):

@@ -7,6 +7,7 @@ import numpy as np
 import pytest
 
 from oracle import compress
+from oracle import moe_lrc_oracle as orc
 from workload import configs, synth
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
@@ -157,3 +158,46 @@ def test_staged_bytes_only_selected_experts():
     assert s["bytes_codes"] == 2 * 3 * 256 * 512 * 3 // 8
     assert s["bytes_meta"] == 2 * 3 * 256 * 512 // 64 * 4
     assert s["bytes_factors"] == 3 * 8 * (256 + 512) * 2
+
+
+def test_shrink_operator_closed_forms():
+    x = np.array([-3.0, -0.05, 0.0, 0.05, 0.2, 3.0])
+    # p = 1: the ordinary soft threshold of width 1 / beta
+    np.testing.assert_allclose(compress.shrink_lp(x, 10.0, 1.0), np.sign(x) * np.maximum(np.abs(x) - 0.1, 0.0), atol=1e-15)
+    # p = 0.5, beta = 4 at x = 1: 1 - 1^(-0.5) / 4 = 0.75; at x = 0.25: 0.25 - 2 / 4 < 0 -> 0; odd; zero at zero
+    got = compress.shrink_lp(np.array([1.0, 0.25, -1.0, 0.0]), 4.0, 0.5)
+    np.testing.assert_allclose(got, [0.75, 0.0, -0.75, 0.0], atol=1e-15)
+    # never grows a value, never flips its sign
+    r = np.random.default_rng(0).standard_normal(1000)
+    y = compress.shrink_lp(r, 10.0, 0.7)
+    assert (np.abs(y) <= np.abs(r)).all() and (y * r >= 0).all()
+
+
+def test_refined_quantizer_reduces_to_minmax_and_lowers_the_lp_error():
+    rng = np.random.default_rng(4)
+    W = rng.standard_normal((256, 48)) * 0.02
+    W *= 1.0 + 9.0 * (rng.random(W.shape) < 0.01)          # outliers stretch the min/max grid
+    W[:64, 0] = 0.5                                         # a constant group
+    for bits in (2, 3, 4):
+        base = compress.quantize_groupwise(W, bits, 64)
+        same = compress.quantize_refined(W, bits, 64, iters=0)
+        for k in ("codes", "scale", "zero"):
+            np.testing.assert_array_equal(same[k], base[k])
+        ref = compress.quantize_refined(W, bits, 64)
+        np.testing.assert_array_equal(ref["scale"], base["scale"])            # the scale is kept
+        assert ref["codes"].max() < (1 << bits)
+        lp = lambda q: (np.abs(W - compress.dequantize(q, 64)) ** 0.7).sum()
+        assert lp(ref) < lp(base)                                              # what the solver minimises
+        # the stored codes are the nearest ones for the stored zero and scale
+        s = np.repeat(orc.f16_to_f64(ref["scale"]), 64, axis=0)
+        z = np.repeat(orc.f16_to_f64(ref["zero"]), 64, axis=0)
+        want = np.clip(np.rint(W / s + z), 0, (1 << bits) - 1)
+        want[:64, 0] = 0
+        np.testing.assert_array_equal(ref["codes"], want.astype(np.uint8))
+    # a group whose bulk sits on a grid shifted against min/max's: one outlier pins the min/max zero
+    # point; the refinement moves the zero point to where the bulk is represented exactly
+    g = np.concatenate([[0.0], 0.26 + 0.5 * rng.integers(0, 2, 63)])[:, None]      # outlier 0; bulk at 0.26, 0.76
+    g[-1, 0] = 1.5                                                                   # max: scale = 0.5 at 2 bits
+    base, ref = compress.quantize_groupwise(g, 2, 64), compress.quantize_refined(g, 2, 64)
+    e0, e1 = np.abs(g - compress.dequantize(base, 64)), np.abs(g - compress.dequantize(ref, 64))
+    assert np.median(e1) < 0.02 < np.median(e0)
