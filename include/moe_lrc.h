@@ -129,9 +129,14 @@ int moe_lrc_set_expert_ranked(moe_lrc_layer* layer, int expert, int mat, const u
  *   a_codes [K][rank], b_codes [N][rank]   one code per byte, each < 8
  *   a_scale, a_zero  fp16 [K/64][rank];  b_scale, b_zero  fp16 [N/64][rank]
  * rank: multiple of 8 in 8..cfg.rank.  Call after moe_lrc_set_expert(_ranked) of the same projection
- * (with A = B = NULL, rank 0), which uploads the codes of the weights.  The pair is kept at 3 bits in
- * the pinned pool of a staged layer and expanded to fp16 on the device when it arrives (a resident
- * layer expands it once, here); the staged byte counters count 3 bits + scale/zero per value. */
+ * (with A = B = NULL, rank 0), which uploads the codes of the weights.  The pair stays at 3 bits
+ * everywhere: in the pinned pool of a staged or pooled layer, on the bus and in device memory; the
+ * kernels that consume it (the (in A) products and the rank steps of the expert FFN, both
+ * flavours) rebuild the fp16 operands in registers, one packed FMA per two elements.  On the device
+ * a code occupies a 4-bit cell (one dword per eight-element operand unit of a lane), so a pair
+ * takes 4 bits + scale/zero (0.5 bit) per value, 3.6 times fewer bytes than the fp16 pair; the byte
+ * counters of moe_lrc_get_stats count that.  Projections with fp16 pairs and projections with
+ * 3-bit pairs may share a layer, even an expert. */
 int moe_lrc_set_expert_factors_quantized(moe_lrc_layer* layer, int expert, int mat, int rank,
                                   const uint8_t* a_codes, const uint16_t* a_scale_f16, const uint16_t* a_zero_f16,
                                   const uint8_t* b_codes, const uint16_t* b_scale_f16, const uint16_t* b_zero_f16);
@@ -349,6 +354,14 @@ int moe_lrc_profile_read(moe_lrc_layer* layer, float* ms);
 int moe_lrc_selftest_decode_index(int hidden, int ffn, int bits, int group, int layer_rank, int rank1,
                                   int rank3, int rank2, int first_row, int rows, int total_rows,
                                   int blocks_w13, int blocks_w2, int kblocks_w2);
+
+/* Host-only model of how the kernels read a factor pair held at 3 bits (Section 3.1 step 2): packs
+ * the pair as moe_lrc_set_expert_factors_quantized does, then rebuilds every element the way the
+ * consuming kernels do (the same unit and metadata indices, the same field extraction, one fp16 FMA
+ * with a single rounding per element) into A_out [K][rank] and B_out [rank][N] (host, fp32). */
+int moe_lrc_selftest_factor_pair(int K, int N, int rank, const uint8_t* a_codes, const uint16_t* a_scale,
+                               const uint16_t* a_zero, const uint8_t* b_codes, const uint16_t* b_scale,
+                               const uint16_t* b_zero, float* A_out, float* B_out);
 
 /* What the current device sustains on the resources the roofline figures are priced against
  * (Section 2.2's roofline remark: offloaded MoE decoding is bound by moving expert weights).

@@ -25,7 +25,7 @@ EXPORTS = [
     "moe_lrc_expert_ffn", "moe_lrc_combine", "moe_lrc_forward", "moe_lrc_forward_noalloc", "moe_lrc_debug_unpack",
     "moe_lrc_packed_bytes", "moe_lrc_pack_codes", "moe_lrc_unpack_codes", "moe_lrc_get_stats",
     "moe_lrc_profile_enable", "moe_lrc_profile_read", "moe_lrc_calibrate",
-    "moe_lrc_selftest_decode_index",
+    "moe_lrc_selftest_decode_index", "moe_lrc_selftest_factor_pair",
     "moe_lrc_offline_quantize", "moe_lrc_offline_quantize_refined", "moe_lrc_offline_factors", "moe_lrc_offline_kurtosis", "moe_lrc_offline_allocate_ranks", "moe_lrc_selftest_half_rounding",
     "moe_lrc_stack_create", "moe_lrc_stack_destroy", "moe_lrc_stack_step", "moe_lrc_stack_get_stats", "moe_lrc_stack_reset",
 ]
@@ -100,6 +100,7 @@ def lib() -> C.CDLL:
         L.moe_lrc_offline_factors.argtypes = [vp, i32, i32, i32, vp, i32, i32, vp, vp, vp, vp, vp]
         L.moe_lrc_offline_kurtosis.argtypes = [vp, sz, C.POINTER(C.c_double)]
         L.moe_lrc_selftest_half_rounding.argtypes = [vp, sz, vp]
+        L.moe_lrc_selftest_factor_pair.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
         L.moe_lrc_offline_allocate_ranks.argtypes = [vp, i32, i32, vp, i32, vp]
         L.moe_lrc_stack_create.argtypes = [C.POINTER(vp), i32, i32, i32, C.POINTER(vp)]
         L.moe_lrc_stack_destroy.argtypes = [vp]
@@ -142,6 +143,19 @@ def calibrate(kind: int, nbytes: int = 0, reps: int = 5) -> float:
     out = C.c_double(0.0)
     _check(lib().moe_lrc_calibrate(kind, nbytes, reps, C.byref(out)))
     return out.value
+
+
+def selftest_factor_pair(Aq: dict, Bq: dict):
+    """moe_lrc_selftest_factor_pair (host only): (A [K][rank], B [rank][N]) float32 as the kernels rebuild a
+    pair held at 3 bits; Aq / Bq as for Layer.set_expert_factors_quantized."""
+    K, rank = Aq["codes"].shape
+    N = Bq["codes"].shape[0]
+    arrs = [_host(Aq["codes"], np.uint8), _host(Aq["scale"], np.uint16), _host(Aq["zero"], np.uint16),
+            _host(Bq["codes"], np.uint8), _host(Bq["scale"], np.uint16), _host(Bq["zero"], np.uint16)]
+    A = np.zeros((K, rank), np.float32)
+    B = np.zeros((rank, N), np.float32)
+    _check(lib().moe_lrc_selftest_factor_pair(K, N, rank, *[_hp(a) for a in arrs], _hp(A), _hp(B)))
+    return A, B
 
 
 def selftest_decode_index(hidden, ffn, bits, group, layer_rank, ranks, first_row, rows, total_rows,

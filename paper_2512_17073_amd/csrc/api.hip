@@ -140,19 +140,44 @@ void fill_algorithmic_stats(moe_lrc_layer* L, const int32_t* stat) {
   if (c.rank > 0 && c.top_n > 0)
     for (int e = 0; e < c.n_experts; ++e)
       if (stat[2 + c.n_experts + e] > 0)
-        for (int mat = 0; mat < 3; ++mat)      // A [K][r] and B [r][N] as bf16: r (K + N) values
+        for (int mat = 0; mat < 3; ++mat)      // A [K][r] and B [r][N]: r (K + N) values, as bf16 or as 3-bit codes
           s.bytes_factors += L->mat_q3[e * 3 + mat]
-                                 ? uint64_t(L->mat_rank[e * 3 + mat]) * (c.hidden + c.ffn) * 3 / 8 +      // 3-bit codes
+                                 ? uint64_t(L->mat_rank[e * 3 + mat]) * (c.hidden + c.ffn) * 4 / 8 +      // a code per 4-bit cell
                                        uint64_t(L->mat_rank[e * 3 + mat]) * (c.hidden + c.ffn) / 64 * 4     // fp16 scale + zero
                                  : uint64_t(L->mat_rank[e * 3 + mat]) * (c.hidden + c.ffn) * 2;
   L->stats_valid = true;
 }
 
-// offset of projection `mat`'s 3-bit blob inside an expert's factor region (room for rank `max_rank` each)
-static size_t q3_slot(const BlobLayout& b, int max_rank, int mat) {
-  size_t o = 0;
-  for (int j = 0; j < mat; ++j) o += (q3_blob_bytes(b.mat[j].K, b.mat[j].N, max_rank) + 255) & ~size_t(255);
-  return o;
+// Bytes of the A and of the B section of (expert, projection) that its factor pair fills: the
+// prefix its own rank takes, in the format it is held in.
+void factor_section_bytes(const moe_lrc_layer* L, int e, int mat, size_t& a_bytes, size_t& b_bytes) {
+  const MatLayout& m = blob_of(L, e).mat[mat];
+  const int r = L->mat_rank[e * 3 + mat];
+  a_bytes = b_bytes = 0;
+  if (r == 0) return;
+  if (L->mat_q3[e * 3 + mat]) {
+    a_bytes = q3_a_bytes(m.K, r); b_bytes = q3_b_bytes(m.N, r);
+  } else {
+    const MatLayout fm = make_layout(m.K, m.N, m.bits, m.group, r);
+    a_bytes = fm.af_bytes; b_bytes = fm.bf_bytes;
+  }
+}
+
+// Points projection `mat` of an expert table entry at its factor sections (a_base, b_base: the
+// starts of the projection's A and B sections on the device).
+void set_factor_ptrs(const moe_lrc_layer* L, int e, int mat, ExpertDesc& d, const uint8_t* a_base, const uint8_t* b_base) {
+  const MatLayout& m = blob_of(L, e).mat[mat];
+  const int r = L->mat_rank[e * 3 + mat];
+  d.afm[mat] = nullptr; d.bfc[mat] = nullptr;
+  if (L->mat_q3[e * 3 + mat]) {
+    d.af[mat] = reinterpret_cast<const _Float16*>(a_base);
+    d.afm[mat] = reinterpret_cast<const uint32_t*>(a_base + q3_a_codes_bytes(m.K, r));
+    d.bfc[mat] = reinterpret_cast<const uint32_t*>(b_base);
+    d.bf[mat] = reinterpret_cast<const _Float16*>(b_base + q3_b_codes_bytes(m.N, r));
+  } else {
+    d.af[mat] = reinterpret_cast<const _Float16*>(a_base);
+    d.bf[mat] = reinterpret_cast<const _Float16*>(b_base);
+  }
 }
 
 // Copies the packed blobs of every expert that received a row, and the factor blobs of every expert
@@ -171,40 +196,16 @@ static int stage_selected(moe_lrc_layer* L, hipStream_t stream) {
     if (b.f_bytes && c.top_n > 0 && L->h_stat[2 + E + e] > 0) {
       const int* r = &L->mat_rank[e * 3];
       const uint8_t* q3 = &L->mat_q3[e * 3];
-      if (q3[0] | q3[1] | q3[2]) {
-        // 3-bit blobs: one copy from the first to the last byte of the expert's blobs, one launch
-        // that expands them to fp16; projections uploaded as fp16 pairs copy their prefixes
-        size_t lo = ~size_t(0), hi = 0;
-        Q3Expand jobs[3];
-        for (int mat = 0; mat < 3; ++mat) {
-          const MatLayout& m = b.mat[mat];
-          const size_t aoff = L->f_off[e] + b.off_af[mat], boff = L->f_off[e] + b.off_bf[mat];
-          jobs[mat] = Q3Expand{nullptr, m.K, m.N, 0, nullptr, nullptr};
-          if (r[mat] == 0) continue;
-          if (q3[mat]) {
-            const size_t qoff = L->f_off[e] + q3_slot(b, c.rank, mat);
-            lo = std::min(lo, qoff); hi = std::max(hi, qoff + q3_blob_bytes(m.K, m.N, r[mat]));
-            jobs[mat] = Q3Expand{L->d_fq + qoff, m.K, m.N, r[mat], reinterpret_cast<_Float16*>(L->d_f + aoff),
-                                 reinterpret_cast<_Float16*>(L->d_f + boff)};
-          } else {
-            const MatLayout fm = make_layout(m.K, m.N, m.bits, m.group, r[mat]);
-            LRC_HIP(hipMemcpyAsync(L->d_f + aoff, L->h_f + aoff, fm.af_bytes, hipMemcpyHostToDevice, L->side));
-            LRC_HIP(hipMemcpyAsync(L->d_f + boff, L->h_f + boff, fm.bf_bytes, hipMemcpyHostToDevice, L->side));
-          }
-        }
-        if (hi > lo) {
-          LRC_HIP(hipMemcpyAsync(L->d_fq + lo, L->h_fq + lo, hi - lo, hipMemcpyHostToDevice, L->side));
-          LRC_HIP(launch_expand_q3(3, jobs, L->side));
-        }
-      } else if (r[0] == c.rank && r[1] == c.rank && r[2] == c.rank) {      // the whole factor blob in one piece
+      if (!(q3[0] | q3[1] | q3[2]) && r[0] == c.rank && r[1] == c.rank && r[2] == c.rank) {   // the whole factor blob in one piece
         LRC_HIP(hipMemcpyAsync(L->d_f + L->f_off[e], L->h_f + L->f_off[e], b.f_bytes, hipMemcpyHostToDevice, L->side));
       } else {
-        for (int mat = 0; mat < 3; ++mat) {                           // the prefixes the projection's rank fills
-          if (r[mat] == 0) continue;
-          const MatLayout fm = make_layout(b.mat[mat].K, b.mat[mat].N, b.mat[mat].bits, b.mat[mat].group, r[mat]);
+        for (int mat = 0; mat < 3; ++mat) {      // the prefixes the projection's rank fills, in the format it is held in
+          size_t ab, bb;
+          factor_section_bytes(L, e, mat, ab, bb);
+          if (ab == 0) continue;
           const size_t aoff = L->f_off[e] + b.off_af[mat], boff = L->f_off[e] + b.off_bf[mat];
-          LRC_HIP(hipMemcpyAsync(L->d_f + aoff, L->h_f + aoff, fm.af_bytes, hipMemcpyHostToDevice, L->side));
-          LRC_HIP(hipMemcpyAsync(L->d_f + boff, L->h_f + boff, fm.bf_bytes, hipMemcpyHostToDevice, L->side));
+          LRC_HIP(hipMemcpyAsync(L->d_f + aoff, L->h_f + aoff, ab, hipMemcpyHostToDevice, L->side));
+          LRC_HIP(hipMemcpyAsync(L->d_f + boff, L->h_f + boff, bb, hipMemcpyHostToDevice, L->side));
         }
       }
     }
@@ -235,6 +236,7 @@ static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t*
   a.plan = reinterpret_cast<int32_t*>(ws + w.plan);
   a.y_rows = y_rows; a.ksplit13 = L->ksplit13; a.ksplit2 = L->ksplit2; a.total_rows = T * c.top_k;
   a.n_cu = L->n_cu;
+  a.q3 = L->n_q3 > 0;
   a.row_exp = reinterpret_cast<int32_t*>(ws + w.row_exp);
   a.tok_exp = tok_exp;
   const int path = expert_ffn_path(a);
@@ -329,6 +331,7 @@ int moe_lrc_layer_create(const moe_lrc_config* cfg, moe_lrc_layer** out) {
   L->mat_set.assign(size_t(L->n_total) * 3, 0);
   L->mat_rank.assign(size_t(L->n_total) * 3, 0);
   L->mat_q3.assign(size_t(L->n_total) * 3, 0);
+  L->mat_inv_mu.assign(size_t(L->n_total) * 3, 1.f);
   size_t w = 0, f = 0;
   for (int e = 0; e < L->n_total; ++e) {
     L->w_off.push_back(w); L->f_off.push_back(f);
@@ -379,7 +382,7 @@ int moe_lrc_layer_create(const moe_lrc_config* cfg, moe_lrc_layer** out) {
     std::memset(&d, 0, sizeof(d));
     for (int m = 0; m < 3; ++m) {
       if (pooled && e < cfg->n_experts) {        // pointers come from the stack's slots, call by call
-        d.lambda[m] = d.inv_lambda[m] = 1.f;
+        d.lambda[m] = d.inv_lambda[m] = d.xa_scale[m] = 1.f;
         continue;
       }
       d.codes[m] = reinterpret_cast<const uint32_t*>(L->d_w + L->w_off[e] - L->dev_w_base + b.off_codes[m]);
@@ -388,7 +391,7 @@ int moe_lrc_layer_create(const moe_lrc_config* cfg, moe_lrc_layer** out) {
         d.af[m] = reinterpret_cast<const _Float16*>(L->d_f + L->f_off[e] + b.off_af[m]);
         d.bf[m] = reinterpret_cast<const _Float16*>(L->d_f + L->f_off[e] + b.off_bf[m]);
       }
-      d.lambda[m] = d.inv_lambda[m] = 1.f;
+      d.lambda[m] = d.inv_lambda[m] = d.xa_scale[m] = 1.f;
     }
     d.has_factors = b.f_bytes ? 1 : 0;
   }
@@ -403,10 +406,8 @@ int moe_lrc_layer_destroy(moe_lrc_layer* L) {
   (void)hipDeviceSynchronize();
   if (L->d_w) (void)hipFree(L->d_w);
   if (L->d_f) (void)hipFree(L->d_f);
-  if (L->d_fq) (void)hipFree(L->d_fq);
   if (L->h_w) (void)hipHostFree(L->h_w);
   if (L->h_f) (void)hipHostFree(L->h_f);
-  if (L->h_fq) (void)hipHostFree(L->h_fq);
   if (L->d_desc) (void)hipFree(L->d_desc);
   if (L->d_wg) (void)hipFree(L->d_wg);
   if (L->d_bias) (void)hipFree(L->d_bias);
@@ -491,11 +492,18 @@ int moe_lrc_set_expert_ranked(moe_lrc_layer* L, int expert, int mat, const uint8
     if (!pooled && m.bf_bytes > fm.bf_bytes) LRC_HIP(hipMemset(L->d_f + boff + fm.bf_bytes, 0, m.bf_bytes - fm.bf_bytes));
   }
   L->mat_rank[expert * 3 + mat] = rank;
+  L->n_q3 -= L->mat_q3[expert * 3 + mat];
   L->mat_q3[expert * 3 + mat] = 0;
-  L->h_desc[expert].rank[mat] = rank;
-  L->h_desc[expert].lambda[mat] = lambda;
-  L->h_desc[expert].inv_lambda[mat] = 1.0f / lambda;
-  LRC_HIP(hipMemcpy(L->d_desc + expert, &L->h_desc[expert], sizeof(ExpertDesc), hipMemcpyHostToDevice));
+  L->mat_inv_mu[expert * 3 + mat] = 1.f;
+  ExpertDesc& d = L->h_desc[expert];
+  d.rank[mat] = rank;
+  d.lambda[mat] = lambda;
+  d.inv_lambda[mat] = 1.0f / lambda;
+  d.xa_scale[mat] = lambda;
+  d.q3 &= ~(1 << mat);
+  if (b.f_bytes > 0 && !(pooled && expert < c.n_experts))
+    set_factor_ptrs(L, expert, mat, d, L->d_f + L->f_off[expert] + b.off_af[mat], L->d_f + L->f_off[expert] + b.off_bf[mat]);
+  LRC_HIP(hipMemcpy(L->d_desc + expert, &d, sizeof(ExpertDesc), hipMemcpyHostToDevice));
   L->mat_set[expert * 3 + mat] = 1;
   return MOE_LRC_OK;
 }
@@ -514,8 +522,6 @@ int moe_lrc_set_expert_factors_quantized(moe_lrc_layer* L, int expert, int mat, 
     return set_error(MOE_LRC_EINVAL, "set_expert_factors_quantized: null argument");
   const moe_lrc_config& c = L->cfg;
   if (expert < 0 || expert >= c.n_experts) return set_error(MOE_LRC_EINVAL, "set_expert_factors_quantized: not a routed expert");
-  if (c.residency == MOE_LRC_POOLED)
-    return set_error(MOE_LRC_ESTATE, "set_expert_factors_quantized: a pooled layer takes its factors as fp16 pairs");
   if (mat < 0 || mat > 2) return set_error(MOE_LRC_EINVAL, "set_expert_factors_quantized: mat must be 0, 1 or 2");
   if (rank <= 0 || rank > c.rank || rank % 8)
     return set_error(MOE_LRC_EINVAL, "set_expert_factors_quantized: rank must be a multiple of 8 in 8..layer rank");
@@ -523,40 +529,39 @@ int moe_lrc_set_expert_factors_quantized(moe_lrc_layer* L, int expert, int mat, 
     return set_error(MOE_LRC_ESTATE, "set_expert_factors_quantized: upload the projection's codes with set_expert first");
   const BlobLayout& b = L->routed;
   const MatLayout& m = b.mat[mat];
-  size_t off[6];
-  q3_offsets(m.K, m.N, rank, off);
-  std::vector<uint8_t> blob(off[5]);
-  if (!pack_q3_blob(m.K, m.N, rank, a_codes, a_scale, a_zero, b_codes, b_scale, b_zero, blob.data()))
-    return set_error(MOE_LRC_EINVAL, "set_expert_factors_quantized: code out of range (3 bits)");
-  if (!L->d_fq) {                          // landing area of the blobs, laid out like the fp16 sections (first use)
-    hipError_t e = hipMalloc((void**)&L->d_fq, L->f_total);
-    if (e != hipSuccess) return set_error(MOE_LRC_ENOMEM, std::string("set_expert_factors_quantized: ") + hipGetErrorString(e));
-  }
-  if (c.residency == MOE_LRC_STAGED && !L->h_fq) {   // pinned home of the 3-bit blobs: a region of its own, so that a
-    // projection held at 3 bits and one held as an fp16 pair can share an expert
-    hipError_t e = hipHostMalloc((void**)&L->h_fq, L->f_total, hipHostMallocDefault);
-    if (e != hipSuccess) return set_error(MOE_LRC_ENOMEM, std::string("set_expert_factors_quantized: ") + hipGetErrorString(e));
-  }
-  // the blobs of an expert's three projections (0.44 bytes per value) lie back to back at the start
-  // of the expert's range in that region and in the landing area, each with room for the layer's rank
-  const size_t qoff = L->f_off[expert] + q3_slot(b, c.rank, mat);
+  // The pair goes into the projection's own A and B sections, in the unit layout the kernels
+  // dequantize from (layout.h): smaller than the fp16 pair of the same rank, so it always fits.
+  std::vector<uint8_t> abuf(q3_a_bytes(m.K, rank)), bbuf(q3_b_bytes(m.N, rank));
+  const float mu_a = pack_factor_a_q3(m.K, rank, a_codes, a_scale, a_zero, abuf.data());
+  const float mu_b = pack_factor_b_q3(m.N, rank, b_codes, b_scale, b_zero, bbuf.data());
+  if (mu_a == 0.f || mu_b == 0.f) return set_error(MOE_LRC_EINVAL, "set_expert_factors_quantized: code out of range (3 bits)");
   const size_t aoff = L->f_off[expert] + b.off_af[mat], boff = L->f_off[expert] + b.off_bf[mat];
-  const MatLayout fm = make_layout(m.K, m.N, m.bits, m.group, rank);
-  if (c.residency == MOE_LRC_STAGED) {
-    std::memcpy(L->h_fq + qoff, blob.data(), blob.size());
-  } else {                                 // resident: expanded to fp16 once, here
-    LRC_HIP(hipMemcpy(L->d_fq + qoff, blob.data(), blob.size(), hipMemcpyHostToDevice));
-    const Q3Expand job{L->d_fq + qoff, m.K, m.N, rank, reinterpret_cast<_Float16*>(L->d_f + aoff),
-                       reinterpret_cast<_Float16*>(L->d_f + boff)};
-    LRC_HIP(launch_expand_q3(1, &job, nullptr));
-    LRC_HIP(hipDeviceSynchronize());
+  const bool host_homed = c.residency != MOE_LRC_RESIDENT, pooled = c.residency == MOE_LRC_POOLED;
+  if (host_homed) {
+    std::memcpy(L->h_f + aoff, abuf.data(), abuf.size());
+    std::memcpy(L->h_f + boff, bbuf.data(), bbuf.size());
+  } else {
+    LRC_HIP(hipMemcpy(L->d_f + aoff, abuf.data(), abuf.size(), hipMemcpyHostToDevice));
+    LRC_HIP(hipMemcpy(L->d_f + boff, bbuf.data(), bbuf.size(), hipMemcpyHostToDevice));
   }
-  if (m.af_bytes > fm.af_bytes) LRC_HIP(hipMemset(L->d_f + aoff + fm.af_bytes, 0, m.af_bytes - fm.af_bytes));
-  if (m.bf_bytes > fm.bf_bytes) LRC_HIP(hipMemset(L->d_f + boff + fm.bf_bytes, 0, m.bf_bytes - fm.bf_bytes));
+  // what an earlier upload may have left behind the pair
+  if (pooled) {
+    std::memset(L->h_f + aoff + abuf.size(), 0, m.af_bytes - abuf.size());
+    std::memset(L->h_f + boff + bbuf.size(), 0, m.bf_bytes - bbuf.size());
+  } else {
+    LRC_HIP(hipMemset(L->d_f + aoff + abuf.size(), 0, m.af_bytes - abuf.size()));
+    LRC_HIP(hipMemset(L->d_f + boff + bbuf.size(), 0, m.bf_bytes - bbuf.size()));
+  }
   L->mat_rank[expert * 3 + mat] = rank;
+  L->n_q3 += 1 - L->mat_q3[expert * 3 + mat];
   L->mat_q3[expert * 3 + mat] = 1;
-  L->h_desc[expert].rank[mat] = rank;
-  LRC_HIP(hipMemcpy(L->d_desc + expert, &L->h_desc[expert], sizeof(ExpertDesc), hipMemcpyHostToDevice));
+  L->mat_inv_mu[expert * 3 + mat] = 1.0f / (mu_a * mu_b);
+  ExpertDesc& d = L->h_desc[expert];
+  d.rank[mat] = rank;
+  d.xa_scale[mat] = d.lambda[mat] * L->mat_inv_mu[expert * 3 + mat];
+  d.q3 |= 1 << mat;
+  if (!pooled) set_factor_ptrs(L, expert, mat, d, L->d_f + aoff, L->d_f + boff);
+  LRC_HIP(hipMemcpy(L->d_desc + expert, &d, sizeof(ExpertDesc), hipMemcpyHostToDevice));
   return MOE_LRC_OK;
 }
 

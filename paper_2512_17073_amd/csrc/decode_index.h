@@ -99,9 +99,13 @@ LRC_HD StepRef step_ref(int n, const StepPlan& p, int grp, int groups, int kwi, 
 
 // Byte offsets of a lane's loads of one stream of a step (the hardware range-checks offset + size
 // against the resource; a step that reads nothing gets an offset at the end of every resource).
-struct LaneOffsets { uint32_t code0, code1, meta, bf; };
+// q3: the stream's factor pair is held at 3 bits (layout.h).  A rank step then reads, through `bf`,
+// the lane's half of the 32 bytes of metadata of (rank step, group of four n-tiles, lane group) from
+// a resource of (NT / 4) * LS * 128 bytes, and through `bc` the unit's code dword from a resource of
+// NT * LS * 256 bytes; `bc` of any other step lies past every resource.
+struct LaneOffsets { uint32_t code0, code1, meta, bf, bc; };
 LRC_HD LaneOffsets lane_offsets(const StepRef& r, int tile, bool tile_ok, int lane, int bits, int NT, int group_shift,
-                                uint32_t code_bytes, uint32_t meta_bytes, uint32_t bf_bytes_max) {
+                                uint32_t code_bytes, uint32_t meta_bytes, uint32_t bf_bytes_max, bool q3 = false) {
   const uint32_t tdw = kWave * 2 * bits, q = lane >> 4, c = lane & 15;
   const uint32_t gps = kTileK >> group_shift;
   const uint32_t meta_lane = ((q * kLaneK) >> group_shift) * (uint32_t(NT) * kTileN * 4) + c * 4;
@@ -113,6 +117,11 @@ LRC_HD LaneOffsets lane_offsets(const StepRef& r, int tile, bool tile_ok, int la
   o.code1 = (ok ? tile_base : code_bytes) + 1024 + lane * (bits == 3 ? 8 : 16);
   o.meta = (ok ? (uint32_t(r.ks) * gps * NT + tile) * (kTileN * 4) : meta_bytes) + meta_lane;
   o.bf = (lr ? (uint32_t(r.st) * NT + tile) * 1024 : past) + lane * 16;
+  o.bc = 0xfffffff0u;
+  if (q3 && lr) {
+    o.bf = ((uint32_t(r.st) * (NT / 4) + (tile >> 2)) * 4 + q) * 32 + (c & 1) * 16;
+    o.bc = (uint32_t(r.st) * NT + tile) * 256 + lane * 4;
+  }
   return o;
 }
 

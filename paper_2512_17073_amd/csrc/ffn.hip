@@ -29,6 +29,7 @@
 #include <type_traits>
 #include <utility>
 
+#include "factor_q3.h"
 #include "ffn_common.h"
 #include "plan.h"
 
@@ -152,7 +153,10 @@ template <int BITS, int NM, int NTW> struct Slot2 { Slot<BITS, NM> t[NTW]; };
 // WAVES wavefronts per block.  8 (two per SIMD, 256 registers each) is what the launches use: with 4
 // (one per SIMD with 512 registers and twice the n-tiles, so that a fragment read from LDS feeds
 // twice the MFMAs) the fused kernel measured 19 % slower: nothing fills a wavefront's waits.
-template <int BITS, bool DUAL, int NTW, int WAVES = kTileWaves>
+// Q3: some factor pair of the layer is held at 3 bits (layout.h): a rank step of such a pair brings
+// the unit's code dword in the slot's metadata register and the lane's half of the unit's metadata in
+// its first four code registers, and is dequantized into the fp16 unit before it is used.
+template <int BITS, bool DUAL, int NTW, int WAVES = kTileWaves, bool Q3 = false>
 __global__ __launch_bounds__(64 * WAVES, WAVES == 4 ? 1 : 2) void qgemm_tile_kernel(KArgs a) {
   extern __shared__ uint4 xs[];           // two k-steps of activations; afterwards the (in A) fragments
   constexpr int NM = DUAL ? 2 : 1;
@@ -178,15 +182,22 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 4 ? 1 : 2) void qgemm_tile_ker
   // steps of the larger one, a resource of the size its rank fills makes the other read zeros
   int LSm[NM];
   const int bf_bytes = a.NT * a.ls * 1024;
-  __amdgpu_buffer_rsrc_t code_rs[NM], meta_rs[NM], bf_rs[NM];
+  __amdgpu_buffer_rsrc_t code_rs[NM], meta_rs[NM], bf_rs[NM], bc_rs[NM];
+  bool q3m[NM];
   float lam[NM];
 #pragma unroll
   for (int m = 0; m < NM; ++m) {
     const int mat = DUAL ? m : 2;
     LSm[m] = lowrank ? (min(__builtin_amdgcn_readfirstlane(d.rank[mat]), a.rank) + 31) / 32 : 0;
+    q3m[m] = Q3 && __builtin_amdgcn_readfirstlane((d.q3 >> mat) & 1) != 0;
     code_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(uniform_ptr(d.codes[mat])), 0, code_bytes, 0x00020000);
     meta_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(uniform_ptr(d.meta[mat])), 0, meta_bytes, 0x00020000);
-    bf_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<_Float16*>(uniform_ptr(d.bf[mat])), 0, a.NT * LSm[m] * 1024, 0x00020000);
+    // (3-bit pair: the B section's metadata, 128 bytes per rank step and group of four n-tiles)
+    bf_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<_Float16*>(uniform_ptr(d.bf[mat])), 0,
+                                                 q3m[m] ? (a.NT / 4) * LSm[m] * 128 : a.NT * LSm[m] * 1024, 0x00020000);
+    if constexpr (Q3)     // the code dwords of a 3-bit pair's B units (no bytes for an fp16 pair: every read gives zero)
+      bc_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(uniform_ptr(q3m[m] ? d.bfc[mat] : d.codes[mat])), 0,
+                                                   q3m[m] ? a.NT * LSm[m] * 256 : 0, 0x00020000);
     lam[m] = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(d.inv_lambda[mat])));
   }
   const int LS = max(LSm[0], LSm[NM - 1]);
@@ -207,6 +218,26 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 4 ? 1 : 2) void qgemm_tile_ker
 #pragma unroll
       for (int m = 0; m < NM; ++m) {
         Slot<BITS, NM>& s1 = sl.t[t];
+        if constexpr (Q3) {
+          // a rank step of a 3-bit pair: the lane's half of the metadata of (rank step, group of four
+          // n-tiles, lane group), and the unit's code dword in place of the k-step's metadata
+          const int st = step - a.KS;
+          const bool lq = lr && q3m[m];
+          const int off0 = lq ? ((st * (a.NT / 4) + (tile >> 2)) * 4 + q) * 32 + (c & 1) * 16 : tile_off;
+          // (neither a k-step nor a rank step of a 3-bit pair: an offset past every resource)
+          const int offm = ok ? meta_off : lq ? (st * a.NT + tile) * 256 + lane * 4 : 0x7ffffff0;
+          const u32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(lr ? bf_rs[m] : code_rs[m], off0, 0, 0);
+          s1.cw[m][0] = v0[0]; s1.cw[m][1] = v0[1]; s1.cw[m][2] = v0[2]; s1.cw[m][3] = v0[3];
+          if constexpr (BITS == 3) {
+            const u32x2 v1 = __builtin_amdgcn_raw_buffer_load_b64(code_rs[m], tile_off2, 0, 0);
+            s1.cw[m][4] = v1[0]; s1.cw[m][5] = v1[1];
+          } else if constexpr (BITS == 4) {
+            const u32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(code_rs[m], tile_off2, 0, 0);
+            s1.cw[m][4] = v1[0]; s1.cw[m][5] = v1[1]; s1.cw[m][6] = v1[2]; s1.cw[m][7] = v1[3];
+          }
+          s1.mw[m] = __builtin_amdgcn_raw_buffer_load_b32(ok ? meta_rs[m] : bc_rs[m], offm, 0, 0);
+          continue;
+        }
         const u32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(lr ? bf_rs[m] : code_rs[m], tile_off, 0, 0);
         s1.cw[m][0] = v0[0]; s1.cw[m][1] = v0[1]; s1.cw[m][2] = v0[2]; s1.cw[m][3] = v0[3];
         if constexpr (BITS == 3) {
@@ -374,6 +405,18 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 4 ? 1 : 2) void qgemm_tile_ker
     // (the ring slots are refilled below, after this wait: only the copies just issued and the two
     // slots requested before them are outstanding)
     asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    // the fp16 B-factor unit of stream m of a slot that holds a rank step
+    auto b_unit = [&](const Slot<BITS, NM>& s1, int m, uint32_t (&u)[4]) {
+      const uint32_t own[4] = {s1.cw[m][0], s1.cw[m][1], s1.cw[m][2], s1.cw[m][3]};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) u[i] = own[i];
+      if constexpr (Q3) {
+        if (q3m[m]) {
+          const uint4 v = __builtin_bit_cast(uint4, q3_unit_b(s1.mw[m], own, (c & 1) != 0));
+          u[0] = v.x; u[1] = v.y; u[2] = v.z; u[3] = v.w;
+        }
+      }
+    };
     auto rank_step = [&](const Slot2<BITS, NM, kNTW>& cur, int st) {
 #pragma unroll
       for (int j = 0; j < NPAIR; ++j) {
@@ -382,10 +425,12 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 4 ? 1 : 2) void qgemm_tile_ker
         int t0s, m0s, t1s, m1s;
         pair_stream(j, 0, t0s, m0s);
         pair_stream(j, 1, t1s, m1s);
-        uint32_t r0v[4], r1v[4];
+        uint32_t u0[4], u1[4], r0v[4], r1v[4];
+        b_unit(cur.t[t0s], m0s, u0);
+        b_unit(cur.t[t1s], m1s, u1);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const auto sw = __builtin_amdgcn_permlane16_swap(cur.t[t0s].cw[m0s][i], cur.t[t1s].cw[m1s][i], false, false);
+          const auto sw = __builtin_amdgcn_permlane16_swap(u0[i], u1[i], false, false);
           r0v[i] = sw[0]; r1v[i] = sw[1];
         }
 #pragma unroll
@@ -477,7 +522,9 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 4 ? 1 : 2) void qgemm_tile_ker
 // grid.x splits K so that the launch fills the chip.
 // xa_finish_kernel: adds the K-blocks in order, zeroes the rows without the rank-r term and the
 // padding columns, writes fp16 row-major.
-template <bool DUAL, int NT>
+// Q3: some factor pair of the layer is held at 3 bits (layout.h); such a pair's units are fetched as
+// (codes, metadata) dwords and dequantized when their k-step comes up.
+template <bool DUAL, int NT, bool Q3>
 __global__ __launch_bounds__(64 * kTileWaves, 2) void xa_tile_kernel(KArgs a) {
   extern __shared__ uint4 xs[];
   constexpr int NM = DUAL ? 2 : 1;
@@ -505,14 +552,23 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void xa_tile_kernel(KArgs a) {
   // 256 ks + 64 q + 8 s + j: the factor unit that meets it is the one with those K rows, unit
   // (8 ks + 2 q + s / 4, tile) of the packed factor, lane (s % 4, c) of it.
   const half8_t* af[kMaxT];
+  const uint32_t* am[kMaxT];                 // 3-bit pairs: the tile's metadata, [group of 64 inputs][16 columns]
+  bool q3t[kMaxT], valid[kMaxT];             // (a tile past the projection's own rank holds nothing: its columns stay zero)
   int nmine = 0;
 #pragma unroll
   for (int t = 0; t < kMaxT; ++t) {
     const int tile = blockIdx.z * (kTileWaves * kMaxT) + wave + t * kTileWaves;
-    af[t] = nullptr;
+    af[t] = nullptr; am[t] = nullptr; q3t[t] = false; valid[t] = false;
     if (tile < tiles) {
-      const int m = tile / rt, tl = tile - m * rt;
-      af[t] = reinterpret_cast<const half8_t*>(uniform_ptr(d.af[DUAL ? m : 2])) + size_t(tl) * (a.K / 32) * kWave + c;
+      const int m = tile / rt, tl = tile - m * rt, mat = DUAL ? m : 2;
+      valid[t] = 16 * tl < __builtin_amdgcn_readfirstlane(d.rank[mat]);
+      q3t[t] = Q3 && __builtin_amdgcn_readfirstlane((d.q3 >> mat) & 1) != 0;
+      if (q3t[t]) {
+        af[t] = reinterpret_cast<const half8_t*>(reinterpret_cast<const uint32_t*>(uniform_ptr(d.af[mat])) + size_t(tl) * (a.K / 32) * kWave + c);
+        am[t] = uniform_ptr(d.afm[mat]) + size_t(tl) * (a.K / 64) * 16 + c;
+      } else {
+        af[t] = reinterpret_cast<const half8_t*>(uniform_ptr(d.af[mat])) + size_t(tl) * (a.K / 32) * kWave + c;
+      }
       nmine = t + 1;
     }
   }
@@ -523,11 +579,23 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void xa_tile_kernel(KArgs a) {
   // the factor units of sub-step s of k-step `step` for this lane (zero past K)
   auto load_unit = [&](int step, int s, int t) {
     const int kk = step * 8 + 2 * q + (s >> 2);          // this lane's 32-row unit of the factor
-    half8_t v = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
-    if (t < nmine && kk * 32 < a.K) v = af[t][size_t(kk) * kWave + (s & 3) * 16];
+    u32x4 v = u32x4{0, 0, 0, 0};
+    if (valid[t] && kk * 32 < a.K) {
+      if (Q3 && q3t[t]) {
+        v[0] = reinterpret_cast<const uint32_t*>(af[t])[size_t(kk) * kWave + (s & 3) * 16];
+        v[1] = am[t][(kk >> 1) * 16];
+      } else {
+        v = __builtin_bit_cast(u32x4, af[t][size_t(kk) * kWave + (s & 3) * 16]);
+      }
+    }
     return v;
   };
-  half8_t wnext[kAhead ? 8 : 1][kMaxT];
+  // the operand of a fetched unit (a unit that was not fetched is all zeros in either format)
+  auto operand = [&](const u32x4& v, int t) {
+    if (Q3 && q3t[t]) return q3_unit_a(v[0], v[1]);
+    return __builtin_bit_cast(half8_t, v);
+  };
+  u32x4 wnext[kAhead ? 8 : 1][kMaxT];
   if constexpr (kAhead) {
 #pragma unroll
     for (int s = 0; s < 8; ++s)
@@ -544,7 +612,7 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void xa_tile_kernel(KArgs a) {
 #pragma unroll
       for (int s = 0; s < 8; ++s)
 #pragma unroll
-        for (int t = 0; t < kMaxT; ++t) wcur[s][t] = wnext[s][t];
+        for (int t = 0; t < kMaxT; ++t) wcur[s][t] = operand(wnext[s][t], t);
 #pragma unroll
       for (int s = 0; s < 8; ++s)
 #pragma unroll
@@ -556,7 +624,7 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void xa_tile_kernel(KArgs a) {
 #pragma unroll
       for (int t = 0; t < kMaxT; ++t) {
         if constexpr (kAhead) wf[t] = wcur[s][t];
-        else wf[t] = load_unit(step, s, t);
+        else wf[t] = operand(load_unit(step, s, t), t);
       }
 #pragma unroll
       for (int mt = 0; mt < kTMT; ++mt)
@@ -578,7 +646,7 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void xa_tile_kernel(KArgs a) {
     const int tile = blockIdx.z * (kTileWaves * kMaxT) + wave + t * kTileWaves;
     if (tile >= tiles) continue;
     const int m = tile / rt, tl = tile - m * rt;
-    const float lam = d.lambda[DUAL ? m : 2];
+    const float lam = d.xa_scale[DUAL ? m : 2];
 #pragma unroll
     for (int mt = 0; mt < kTMT; ++mt) {
       const int row = r + 16 * mt + c;
@@ -642,9 +710,11 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
   a.in = f.xh; a.out = f.h; a.K = f.H; a.N = f.F; a.NT = f.F / kTileN;
   a.in_rt = f.x_rt; a.out_rt = f.h_rt;
   a.KS = padded_k(f.H) / kTileK; a.G = padded_k(f.H) / f.group;
-  if (comp) xa(xa_tile_kernel<true, 2>, xa_tile_kernel<true, 4>, f.p13, 2, f.ksplit13);
+  if (comp && f.q3) xa(xa_tile_kernel<true, 2, true>, xa_tile_kernel<true, 4, true>, f.p13, 2, f.ksplit13);
+  else if (comp) xa(xa_tile_kernel<true, 2, false>, xa_tile_kernel<true, 4, false>, f.p13, 2, f.ksplit13);
   if (f.marks) (void)hipEventRecord(f.marks[0], s);
-  hipLaunchKernelGGL((qgemm_tile_kernel<BITS, true, 2>), dim3((a.NT + 15) / 16, items), dim3(64 * kTileWaves), lds, s, a);
+  if (comp && f.q3) hipLaunchKernelGGL((qgemm_tile_kernel<BITS, true, 2, kTileWaves, true>), dim3((a.NT + 15) / 16, items), dim3(64 * kTileWaves), lds, s, a);
+  else hipLaunchKernelGGL((qgemm_tile_kernel<BITS, true, 2>), dim3((a.NT + 15) / 16, items), dim3(64 * kTileWaves), lds, s, a);
   if (f.marks) (void)hipEventRecord(f.marks[1], s);
   }
   if (which & 2) {
@@ -652,17 +722,22 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
   a.in = f.h; a.out = f.y_rows; a.K = f.F; a.N = f.H; a.NT = f.H / kTileN;
   a.in_rt = f.h_rt; a.out_rt = 0;
   a.KS = padded_k(f.F) / kTileK; a.G = padded_k(f.F) / f.group;
-  if (comp) xa(xa_tile_kernel<false, 2>, xa_tile_kernel<false, 4>, f.p2, 1, f.ksplit2);
+  if (comp && f.q3) xa(xa_tile_kernel<false, 2, true>, xa_tile_kernel<false, 4, true>, f.p2, 1, f.ksplit2);
+  else if (comp) xa(xa_tile_kernel<false, 2, false>, xa_tile_kernel<false, 4, false>, f.p2, 1, f.ksplit2);
   if (f.marks) (void)hipEventRecord(f.marks[2], s);
   // four n-tiles per wavefront use a fragment of activations twice as often as two, but make
   // blocks twice as large: take the one with fewer (weighted) rounds of blocks over the 256 CUs
   // (expected number of chunks: about half of the experts end with a partly filled one)
   const int chunks = std::max(1, f.offsets ? f.total_rows / kBM + (f.n_exp + 1) / 2 : f.n_exp * ((f.T + kBM - 1) / kBM));
   auto rounds = [&](int ntw) { return (chunks * ((a.NT + 8 * ntw - 1) / (8 * ntw)) + f.n_cu - 1) / f.n_cu * ntw; };
-  if (rounds(4) * 100 <= rounds(2) * 108)
-    hipLaunchKernelGGL((qgemm_tile_kernel<BITS, false, 4>), dim3((a.NT + 31) / 32, items), dim3(64 * kTileWaves), lds, s, a);
-  else
-    hipLaunchKernelGGL((qgemm_tile_kernel<BITS, false, 2>), dim3((a.NT + 15) / 16, items), dim3(64 * kTileWaves), lds, s, a);
+  const bool q3 = comp && f.q3;
+  if (rounds(4) * 100 <= rounds(2) * 108) {
+    if (q3) hipLaunchKernelGGL((qgemm_tile_kernel<BITS, false, 4, kTileWaves, true>), dim3((a.NT + 31) / 32, items), dim3(64 * kTileWaves), lds, s, a);
+    else hipLaunchKernelGGL((qgemm_tile_kernel<BITS, false, 4>), dim3((a.NT + 31) / 32, items), dim3(64 * kTileWaves), lds, s, a);
+  } else {
+    if (q3) hipLaunchKernelGGL((qgemm_tile_kernel<BITS, false, 2, kTileWaves, true>), dim3((a.NT + 15) / 16, items), dim3(64 * kTileWaves), lds, s, a);
+    else hipLaunchKernelGGL((qgemm_tile_kernel<BITS, false, 2>), dim3((a.NT + 15) / 16, items), dim3(64 * kTileWaves), lds, s, a);
+  }
   if (f.marks) (void)hipEventRecord(f.marks[3], s);
   }
   return hipGetLastError();
@@ -689,9 +764,12 @@ static int decode_parts(const FfnArgs& f) {
 }
 
 template <int BITS> static hipError_t tile_init_bits() {
-  const void* fns[3] = {reinterpret_cast<const void*>(&qgemm_tile_kernel<BITS, true, 2>),
+  const void* fns[6] = {reinterpret_cast<const void*>(&qgemm_tile_kernel<BITS, true, 2>),
                         reinterpret_cast<const void*>(&qgemm_tile_kernel<BITS, false, 4>),
-                        reinterpret_cast<const void*>(&qgemm_tile_kernel<BITS, false, 2>)};
+                        reinterpret_cast<const void*>(&qgemm_tile_kernel<BITS, false, 2>),
+                        reinterpret_cast<const void*>(&qgemm_tile_kernel<BITS, true, 2, kTileWaves, true>),
+                        reinterpret_cast<const void*>(&qgemm_tile_kernel<BITS, false, 4, kTileWaves, true>),
+                        reinterpret_cast<const void*>(&qgemm_tile_kernel<BITS, false, 2, kTileWaves, true>)};
   for (const void* fn : fns) {
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStepUnits * 16);
     if (e != hipSuccess) return e;
@@ -700,8 +778,10 @@ template <int BITS> static hipError_t tile_init_bits() {
 }
 
 hipError_t ffn_init_device() {
-  const void* fns[4] = {reinterpret_cast<const void*>(&xa_tile_kernel<true, 2>), reinterpret_cast<const void*>(&xa_tile_kernel<false, 2>),
-                        reinterpret_cast<const void*>(&xa_tile_kernel<true, 4>), reinterpret_cast<const void*>(&xa_tile_kernel<false, 4>)};
+  const void* fns[8] = {reinterpret_cast<const void*>(&xa_tile_kernel<true, 2, false>), reinterpret_cast<const void*>(&xa_tile_kernel<false, 2, false>),
+                        reinterpret_cast<const void*>(&xa_tile_kernel<true, 4, false>), reinterpret_cast<const void*>(&xa_tile_kernel<false, 4, false>),
+                        reinterpret_cast<const void*>(&xa_tile_kernel<true, 2, true>), reinterpret_cast<const void*>(&xa_tile_kernel<false, 2, true>),
+                        reinterpret_cast<const void*>(&xa_tile_kernel<true, 4, true>), reinterpret_cast<const void*>(&xa_tile_kernel<false, 4, true>)};
   for (const void* fn : fns) {
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStepUnits * 16);
     if (e != hipSuccess) return e;

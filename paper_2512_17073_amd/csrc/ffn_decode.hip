@@ -24,6 +24,7 @@
 #include <type_traits>
 
 #include "decode_index.h"
+#include "factor_q3.h"
 #include "ffn_common.h"
 #include "plan.h"
 #include "xa_rows.h"
@@ -41,7 +42,10 @@ using namespace dec;
 // 16x16x32 shape used here and needs half as many instructions, by swapping 16-lane rows between the
 // two streams' registers; measured, the four swaps per sub-step cost this kernel more than the two
 // matrix instructions save.)
-template <int BITS, bool DUAL, int MT>
+// Q3: some factor pair of the layer is held at 3 bits (layout.h): a rank step of such a pair brings
+// the unit's code dword in the slot's metadata register and the lane's half of the unit's metadata in
+// its first four code registers, and is dequantized into the fp16 unit before it is used.
+template <int BITS, bool DUAL, int MT, bool Q3>
 __device__ __forceinline__ void decode_body(const KArgs& a, uint4* xs, const int e, const int r0, const int cnt,
                                             const int b, const int G) {
   constexpr int NS = kStreams;
@@ -81,15 +85,21 @@ __device__ __forceinline__ void decode_body(const KArgs& a, uint4* xs, const int
   const int LS = max(LSm[0], LSm[1]);
   const uint32_t bf_bytes_max = uint32_t(a.NT) * a.ls * 1024;
 
-  __amdgpu_buffer_rsrc_t code_rs[NS], meta_rs[NS], bf_rs[NS];
+  __amdgpu_buffer_rsrc_t code_rs[NS], meta_rs[NS], bf_rs[NS], bc_rs[NS];
+  bool q3m[NS];
 #pragma unroll
   for (int m = 0; m < NS; ++m) {
     const int mat = DUAL ? m : 2;
+    q3m[m] = Q3 && __builtin_amdgcn_readfirstlane((d.q3 >> mat) & 1) != 0;
     // (the pointers are read once, into scalar registers: a buffer resource must be wave-uniform)
     code_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(uniform_ptr(d.codes[mat])), 0, code_bytes, 0x00020000);
     meta_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(uniform_ptr(d.meta[mat])), 0, meta_bytes, 0x00020000);
+    // (3-bit pair: the B section's metadata, 128 bytes per rank step and group of four n-tiles)
     bf_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<_Float16*>(uniform_ptr(d.bf[mat])), 0,
-                                                 uint32_t(a.NT) * LSm[m] * 1024, 0x00020000);
+                                                 q3m[m] ? uint32_t(a.NT / 4) * LSm[m] * 128 : uint32_t(a.NT) * LSm[m] * 1024, 0x00020000);
+    if constexpr (Q3)     // the code dwords of a 3-bit pair's B units (no bytes for an fp16 pair: every read gives zero)
+      bc_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(uniform_ptr(q3m[m] ? d.bfc[mat] : d.codes[mat])), 0,
+                                                   q3m[m] ? uint32_t(a.NT) * LSm[m] * 256 : 0u, 0x00020000);
   }
   // (in A) fragments: [projection][rank step][row tile][lane].  Up to 32 of them sit behind the staged
   // activations from the start of a pass; more (ranks above 256) take the place of the activations
@@ -111,7 +121,8 @@ __device__ __forceinline__ void decode_body(const KArgs& a, uint4* xs, const int
 #pragma unroll
       for (int m = 0; m < NS; ++m) {
         const int tile = stream_tile(t0, ref.unit, m, DUAL);
-        const LaneOffsets o = lane_offsets(ref, tile, tile < t1, lane, BITS, a.NT, a.group_shift, code_bytes, meta_bytes, bf_bytes_max);
+        const LaneOffsets o = lane_offsets(ref, tile, tile < t1, lane, BITS, a.NT, a.group_shift, code_bytes, meta_bytes, bf_bytes_max,
+                                           Q3 && q3m[m]);
         const bool lr = ref.lr;
         const u32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(lr ? bf_rs[m] : code_rs[m], lr ? o.bf : o.code0, 0, 0);
         sl.cw[m][0] = v0[0]; sl.cw[m][1] = v0[1]; sl.cw[m][2] = v0[2]; sl.cw[m][3] = v0[3];
@@ -122,7 +133,8 @@ __device__ __forceinline__ void decode_body(const KArgs& a, uint4* xs, const int
           const u32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(code_rs[m], o.code1, 0, 0);
           sl.cw[m][4] = v1[0]; sl.cw[m][5] = v1[1]; sl.cw[m][6] = v1[2]; sl.cw[m][7] = v1[3];
         }
-        sl.mw[m] = __builtin_amdgcn_raw_buffer_load_b32(meta_rs[m], o.meta, 0, 0);
+        if constexpr (Q3) sl.mw[m] = __builtin_amdgcn_raw_buffer_load_b32(lr ? bc_rs[m] : meta_rs[m], lr ? o.bc : o.meta, 0, 0);
+        else sl.mw[m] = __builtin_amdgcn_raw_buffer_load_b32(meta_rs[m], o.meta, 0, 0);
       }
     };
 
@@ -187,7 +199,13 @@ __device__ __forceinline__ void decode_body(const KArgs& a, uint4* xs, const int
 #pragma unroll
       for (int m = 0; m < NS; ++m) {
         if (st >= LSm[m]) continue;
-        const half8_t bfrag = __builtin_bit_cast(half8_t, make_uint4(cur.cw[m][0], cur.cw[m][1], cur.cw[m][2], cur.cw[m][3]));
+        half8_t bfrag = __builtin_bit_cast(half8_t, make_uint4(cur.cw[m][0], cur.cw[m][1], cur.cw[m][2], cur.cw[m][3]));
+        if constexpr (Q3) {
+          if (q3m[m]) {
+            const uint32_t own[4] = {cur.cw[m][0], cur.cw[m][1], cur.cw[m][2], cur.cw[m][3]};
+            bfrag = q3_unit_b(cur.mw[m], own, (c & 1) != 0);
+          }
+        }
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
           const half8_t pf = __builtin_bit_cast(half8_t, p_lds[p_frag_unit(DUAL ? m : 0, st, mt, LS, MT) + lane]);
@@ -365,7 +383,7 @@ __device__ __forceinline__ void decode_body(const KArgs& a, uint4* xs, const int
   }
 }
 
-template <int BITS, bool DUAL>
+template <int BITS, bool DUAL, bool Q3>
 __global__ __launch_bounds__(64 * kWaves, 4) void qgemm_decode_kernel(KArgs a) {
   extern __shared__ uint4 xs[];
   int e = blockIdx.y, b = blockIdx.x, G = gridDim.x, r0, cnt;
@@ -379,8 +397,8 @@ __global__ __launch_bounds__(64 * kWaves, 4) void qgemm_decode_kernel(KArgs a) {
     cnt = a.offsets ? a.offsets[e + 1] - r0 : a.T;
   }
   if (cnt == 0) return;
-  if (cnt <= 16) decode_body<BITS, DUAL, 1>(a, xs, e, r0, cnt, b, G);
-  else decode_body<BITS, DUAL, 2>(a, xs, e, r0, cnt, b, G);
+  if (cnt <= 16) decode_body<BITS, DUAL, 1, Q3>(a, xs, e, r0, cnt, b, G);
+  else decode_body<BITS, DUAL, 2, Q3>(a, xs, e, r0, cnt, b, G);
 }
 
 template <bool DUAL>
@@ -433,6 +451,10 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
   // launch that prepared the activations has left (plan.h)
   const bool by_table = f.offsets != nullptr && f.plan != nullptr;
   const int pairs = f.T * f.top_k;
+  // (the kernels that can dequantize 3-bit factor pairs, where the layer holds any)
+  const bool q3 = comp && f.q3;
+  auto k13 = q3 ? qgemm_decode_kernel<BITS, true, true> : qgemm_decode_kernel<BITS, true, false>;
+  auto k2 = q3 ? qgemm_decode_kernel<BITS, false, true> : qgemm_decode_kernel<BITS, false, false>;
 
   if (which & 1) {
     // W1 | W3 with the SwiGLU epilogue
@@ -447,10 +469,10 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
     if (f.marks) (void)hipEventRecord(f.marks[0], s);
     if (by_table) {
       a.plan = f.plan;
-      hipLaunchKernelGGL((qgemm_decode_kernel<BITS, true>), dim3(plan_blocks(f.n_exp, pairs, a.NT, f.n_cu), 1, 1), dim3(64 * kWaves), lds, s, a);
+      hipLaunchKernelGGL(k13, dim3(plan_blocks(f.n_exp, pairs, a.NT, f.n_cu), 1, 1), dim3(64 * kWaves), lds, s, a);
       a.plan = nullptr;
     } else {
-      hipLaunchKernelGGL((qgemm_decode_kernel<BITS, true>), dim3(blocks_per_expert(a.NT, 1), f.n_exp, 1), dim3(64 * kWaves), lds, s, a);
+      hipLaunchKernelGGL(k13, dim3(blocks_per_expert(a.NT, 1), f.n_exp, 1), dim3(64 * kWaves), lds, s, a);
     }
     if (f.marks) (void)hipEventRecord(f.marks[1], s);
   }
@@ -473,11 +495,10 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
       // (second table behind the first; every K-block uses the same shares)
       a.plan = f.plan + kPlanEntryInts * plan_blocks(f.n_exp, pairs, f.F / kTileN, f.n_cu);
       const int B = plan_blocks(f.n_exp, pairs, a.NT, (f.n_cu + kblocks - 1) / kblocks);
-      hipLaunchKernelGGL((qgemm_decode_kernel<BITS, false>), dim3(B, 1, kblocks), dim3(64 * kWaves), lds, s, a);
+      hipLaunchKernelGGL(k2, dim3(B, 1, kblocks), dim3(64 * kWaves), lds, s, a);
       a.plan = nullptr;
     } else {
-      hipLaunchKernelGGL((qgemm_decode_kernel<BITS, false>), dim3(blocks_per_expert(a.NT, kblocks), f.n_exp, kblocks),
-                         dim3(64 * kWaves), lds, s, a);
+      hipLaunchKernelGGL(k2, dim3(blocks_per_expert(a.NT, kblocks), f.n_exp, kblocks), dim3(64 * kWaves), lds, s, a);
     }
     if (kblocks > 1 && !f.keep_partials) {
       const size_t units = size_t(f.total_rows) * f.H / 4;
@@ -513,9 +534,13 @@ void decode_plan_specs(const FfnArgs& f, int which, PlanSpec& p13, PlanSpec& p2)
 
 hipError_t decode_init_device() {
   // 128 KB of activations + 32 KB of (in A) fragments = all 160 KB of a CU
-  const void* fns[6] = {reinterpret_cast<const void*>(&qgemm_decode_kernel<2, true>), reinterpret_cast<const void*>(&qgemm_decode_kernel<2, false>),
-                        reinterpret_cast<const void*>(&qgemm_decode_kernel<3, true>), reinterpret_cast<const void*>(&qgemm_decode_kernel<3, false>),
-                        reinterpret_cast<const void*>(&qgemm_decode_kernel<4, true>), reinterpret_cast<const void*>(&qgemm_decode_kernel<4, false>)};
+  const void* fns[12] = {
+      reinterpret_cast<const void*>(&qgemm_decode_kernel<2, true, false>), reinterpret_cast<const void*>(&qgemm_decode_kernel<2, false, false>),
+      reinterpret_cast<const void*>(&qgemm_decode_kernel<3, true, false>), reinterpret_cast<const void*>(&qgemm_decode_kernel<3, false, false>),
+      reinterpret_cast<const void*>(&qgemm_decode_kernel<4, true, false>), reinterpret_cast<const void*>(&qgemm_decode_kernel<4, false, false>),
+      reinterpret_cast<const void*>(&qgemm_decode_kernel<2, true, true>), reinterpret_cast<const void*>(&qgemm_decode_kernel<2, false, true>),
+      reinterpret_cast<const void*>(&qgemm_decode_kernel<3, true, true>), reinterpret_cast<const void*>(&qgemm_decode_kernel<3, false, true>),
+      reinterpret_cast<const void*>(&qgemm_decode_kernel<4, true, true>), reinterpret_cast<const void*>(&qgemm_decode_kernel<4, false, true>)};
   for (const void* fn : fns) {
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (kLdsUnits + kSpareUnits) * 16);
     if (e != hipSuccess) return e;

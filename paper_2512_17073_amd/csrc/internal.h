@@ -15,12 +15,17 @@ namespace lrc {
 struct ExpertDesc {
   const uint32_t* codes[3];
   const uint32_t* meta[3];
-  const _Float16* af[3];      // packed A factor (null if none)
-  const _Float16* bf[3];      // packed B factor
+  const _Float16* af[3];      // packed A factor (null if none); a pair held at 3 bits: the code dwords of its units
+  const _Float16* bf[3];      // packed B factor; at 3 bits: the metadata of its units
+  const uint32_t* afm[3];     // pairs held at 3 bits (layout.h): metadata of the A units ...
+  const uint32_t* bfc[3];     // ... and code dwords of the B units
   float lambda[3];            // power-of-two pre-scale folded into the metadata
   float inv_lambda[3];
+  float xa_scale[3];          // what (in A) is multiplied by: lambda, over the power-of-two factors folded into a
+                              // 3-bit pair's operands
   int32_t rank[3];            // rank of each projection's factor pair (0: none); a prefix of the factor sections
   int32_t has_factors;
+  int32_t q3;                 // bit m: projection m's pair is held at 3 bits
 };
 
 // Byte offsets of the sections of an expert's two blobs (weights: codes+meta; factors: A+B).
@@ -62,10 +67,11 @@ struct moe_lrc_layer {
   bool gate_set = false, has_bias = false;
   std::vector<uint8_t> mat_set;        // [n_total*3]
   std::vector<int> mat_rank;           // [n_total*3] rank of each projection's factor pair (Section 3.1: may differ)
-  std::vector<uint8_t> mat_q3;         // [n_total*3] 1: the pair is held at 3 bits (pinned pool / d_fq) and expanded to fp16
-  uint8_t* d_fq = nullptr;             // device: landing area of the 3-bit factor blobs, laid out like d_f (allocated on first use)
-  uint8_t* h_fq = nullptr;             // pinned home of the 3-bit factor blobs (staged only; allocated on first use)
-  size_t f_total = 0;                  // bytes of d_f (and of d_fq, h_f)
+  std::vector<uint8_t> mat_q3;         // [n_total*3] 1: the pair is held at 3 bits (layout.h), in the projection's own
+                                       // factor sections, and dequantized by the kernels that consume it
+  std::vector<float> mat_inv_mu;       // [n_total*3] 1 / (the power-of-two factors folded into a 3-bit pair's operands)
+  int n_q3 = 0;                        // projections held at 3 bits (0: the launches take the kernels without that path)
+  size_t f_total = 0;                  // bytes of d_f (and of h_f)
   int32_t* d_stat = nullptr;           // [2 + 2E]: active, comp-active, counts, comp counts
   int32_t* h_stat = nullptr;           // pinned mirror
   hipStream_t side = nullptr;
@@ -150,6 +156,8 @@ struct FfnArgs {
                               // the combine instead of adding them into y_rows
   int ksplit13, ksplit2, total_rows;
   int n_cu;                   // compute units of the device (the launches size their grids to fill them)
+  int q3;                     // some factor pair of the layer is held at 3 bits: the launches take the kernels that
+                              // can dequantize such pairs
   const PermuteArgs* perm;    // forward with few pairs: the preparing launch groups the pairs itself (else null)
   int32_t* row_exp;           // per input row (routed: per routed row; shared: per token): pre-scale exponent
   const int32_t* tok_exp;     // per token, from the routing kernel, or null
@@ -174,6 +182,8 @@ hipError_t launch_combine(const moe_lrc_layer* L, const void* y_rows, const floa
                           hipStream_t s);
 // ---- host API internals shared with the layer stack (stack.hip) ----
 const BlobLayout& blob_of(const moe_lrc_layer* L, int expert);
+void factor_section_bytes(const moe_lrc_layer* L, int e, int mat, size_t& a_bytes, size_t& b_bytes);
+void set_factor_ptrs(const moe_lrc_layer* L, int e, int mat, ExpertDesc& d, const uint8_t* a_base, const uint8_t* b_base);
 void fill_algorithmic_stats(moe_lrc_layer* L, const int32_t* stat);
 // moe_lrc_forward after its argument checks; residual as in launch_combine
 int forward_impl(moe_lrc_layer* L, const void* x, int T, void* out, void* ws, hipStream_t s, const void* residual);
@@ -183,10 +193,4 @@ int forward_impl(moe_lrc_layer* L, const void* x, int T, void* out, void* ws, hi
 int pool_stage(moe_lrc_layer* L, const void* x, int T, hipStream_t s);
 hipError_t launch_debug_unpack(const uint32_t* packed, const MatLayout& m, uint8_t* codes_dev,
                                hipStream_t s);
-// 3-bit factor blob (q3_blob_bytes) -> the fp16 factor sections of one projection (rank-major layouts)
-size_t q3_blob_bytes(int K, int N, int rank);
-struct Q3Expand { const uint8_t* blob; int K, N, rank; _Float16* af; _Float16* bf; };   // blob on the device; rank 0: skip
-// one launch for up to three projections
-hipError_t launch_expand_q3(int n, const Q3Expand* jobs, hipStream_t s);
-
 }  // namespace lrc

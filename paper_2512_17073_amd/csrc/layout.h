@@ -102,16 +102,20 @@ inline MatLayout make_layout(int K, int N, int bits, int group, int rank) {
   return m;
 }
 
-// Blob of one projection's factor pair held at 3 bits: A codes (dense 3-bit stream of [K][r], one
-// spare byte), A scale, A zero (fp16 [K/64][r]), then the same for B transposed ([N][r], groups of 64
-// along N); every section starts at a multiple of 16 bytes.  off = {A scale, A zero, B codes,
-// B scale, B zero, end}.
-inline void q3_offsets(int K, int N, int rank, size_t (&off)[6]) {
-  auto r16 = [](size_t x) { return (x + 15) & ~size_t(15); };
-  const size_t a_codes = r16(size_t(K) * rank * 3 / 8 + 1), a_meta = r16(size_t(K / 64) * rank * 2);
-  const size_t b_codes = r16(size_t(N) * rank * 3 / 8 + 1), b_meta = r16(size_t(N / 64) * rank * 2);
-  off[0] = a_codes; off[1] = off[0] + a_meta; off[2] = off[1] + a_meta;
-  off[3] = off[2] + b_codes; off[4] = off[3] + b_meta; off[5] = off[4] + b_meta;
-}
+// A factor pair held at 3 bits (Section 3.1 step 2) keeps the unit structure of the fp16 layouts
+// (pack_factor_a / pack_factor_b): every 16-byte unit of 8 fp16 values per lane becomes one dword
+// of 8 codes per lane, the code of element j at bits 3 (j / 2) .. + 2 of half j % 2 of the dword, plus
+// metadata from which one packed FMA per element pair rebuilds the fp16 operand
+// (mu (code - zero) scale, mu a power of two per factor that keeps the metadata finite in fp16):
+//   A [K][r], groups of 64 along K: per (16-column tile, group, column c) one dword
+//     lo = scale mu 2^17, hi = -zero scale mu   (every element of a lane shares the group and column)
+//   B transposed [N][r], groups of 64 along N: per (rank step, group of 4 n-tiles, lane group q)
+//     32 bytes: four pairs scale mu 2^17 of rank indices (8 q + 2 i, 8 q + 2 i + 1), then the four
+//     pairs -zero scale mu   (the elements of a lane differ in their rank index)
+// Both sections are rank-major like the fp16 ones: codes first, the metadata behind them.
+inline size_t q3_a_codes_bytes(int K, int rank) { return size_t((rank + 15) / 16) * (K / 32) * 256; }
+inline size_t q3_a_bytes(int K, int rank) { return q3_a_codes_bytes(K, rank) + size_t((rank + 15) / 16) * (K / 64) * 64; }
+inline size_t q3_b_codes_bytes(int N, int rank) { return size_t((rank + 31) / 32) * (N / 16) * 256; }
+inline size_t q3_b_bytes(int N, int rank) { return q3_b_codes_bytes(N, rank) + size_t((rank + 31) / 32) * (N / 64) * 128; }
 
 }  // namespace lrc

@@ -197,92 +197,7 @@ __global__ __launch_bounds__(64) void unpack_kernel(const uint32_t* __restrict__
   }
 }
 
-// Factor pairs stored at 3 bits (Section 3.1 step 2) are expanded to the fp16 MFMA units the FFN
-// kernels read.  Blob of one projection: A codes (dense 3-bit stream, code i of [K][r] at bit 3 i),
-// A scale, A zero (fp16 [K/64][r] each), then the same for B transposed ([N][r], groups of 64 along
-// N); sections start at multiples of 16 bytes.  One thread per 16-byte unit of the rank-major
-// layouts: A unit (tile, kk, lane (q, c)) = A[32 kk + 8 q + j][16 tile + c], B unit (st, nt, lane)
-// = B[32 st + 8 q + j][16 nt + c], j = 0..7; value = (code - zero) * scale, zero past the rank.
-__device__ inline uint32_t q3_code(const uint8_t* __restrict__ stream, size_t i) {
-  const size_t bit = 3 * i;
-  const uint32_t two = uint32_t(stream[bit >> 3]) | (uint32_t(stream[(bit >> 3) + 1]) << 8);   // (one spare byte follows)
-  return (two >> (bit & 7)) & 7u;
-}
-__device__ inline float f16_bits_to_f32(uint16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
-
-struct Q3Job { const uint8_t* blob; int K, N, rank; size_t off[5]; _Float16* af; _Float16* bf; };   // rank 0: nothing to do
-struct Q3Jobs { Q3Job j[3]; };
-
-__global__ __launch_bounds__(256) void expand_q3_kernel(Q3Jobs jobs) {
-  const Q3Job& jb = jobs.j[blockIdx.y];
-  const uint8_t* __restrict__ blob = jb.blob;
-  const int K = jb.K, N = jb.N, rank = jb.rank;
-  if (rank == 0) return;
-  _Float16* __restrict__ af = jb.af;
-  _Float16* __restrict__ bf = jb.bf;
-  const int rt = (rank + 15) / 16, ls = (rank + 31) / 32, k32 = K / 32, NT = N / 16;
-  const size_t a_units = size_t(rt) * k32 * 64, b_units = size_t(ls) * NT * 64;
-  const size_t u = size_t(blockIdx.x) * 256 + threadIdx.x;
-  if (u >= a_units + b_units) return;
-  _Float16 v[8];
-  if (u < a_units) {
-    const int lane = u & 63, c = lane & 15, q = lane >> 4;
-    const int kk = int((u >> 6) % k32), tile = int((u >> 6) / k32), rho = 16 * tile + c;
-    const uint16_t* sc = reinterpret_cast<const uint16_t*>(blob + jb.off[0]);
-    const uint16_t* zr = reinterpret_cast<const uint16_t*>(blob + jb.off[1]);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int k = 32 * kk + 8 * q + j;
-      float val = 0.f;
-      if (rho < rank) {
-        const size_t g = size_t(k >> 6) * rank + rho;
-        val = (float(q3_code(blob, size_t(k) * rank + rho)) - f16_bits_to_f32(zr[g])) * f16_bits_to_f32(sc[g]);
-      }
-      v[j] = (_Float16)val;
-    }
-    *reinterpret_cast<uint4*>(af + u * 8) = *reinterpret_cast<const uint4*>(v);
-  } else {
-    const size_t ub = u - a_units;
-    const int lane = ub & 63, c = lane & 15, q = lane >> 4;
-    const int nt = int((ub >> 6) % NT), st = int((ub >> 6) / NT), n = 16 * nt + c;
-    const uint16_t* sc = reinterpret_cast<const uint16_t*>(blob + jb.off[3]);
-    const uint16_t* zr = reinterpret_cast<const uint16_t*>(blob + jb.off[4]);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int rho = 32 * st + 8 * q + j;
-      float val = 0.f;
-      if (rho < rank) {
-        const size_t g = size_t(n >> 6) * rank + rho;
-        val = (float(q3_code(blob + jb.off[2], size_t(n) * rank + rho)) - f16_bits_to_f32(zr[g])) * f16_bits_to_f32(sc[g]);
-      }
-      v[j] = (_Float16)val;
-    }
-    *reinterpret_cast<uint4*>(bf + ub * 8) = *reinterpret_cast<const uint4*>(v);
-  }
-}
-
 }  // namespace
-
-size_t q3_blob_bytes(int K, int N, int rank) {
-  size_t off[6];
-  q3_offsets(K, N, rank, off);
-  return off[5];
-}
-
-hipError_t launch_expand_q3(int n, const Q3Expand* jobs, hipStream_t s) {
-  Q3Jobs jj{};
-  size_t most = 0;
-  for (int i = 0; i < n && i < 3; ++i) {
-    const Q3Expand& e = jobs[i];
-    size_t off[6];
-    q3_offsets(e.K, e.N, e.rank, off);
-    jj.j[i] = Q3Job{e.blob, e.K, e.N, e.rank, {off[0], off[1], off[2], off[3], off[4]}, e.af, e.bf};
-    most = std::max(most, (size_t((e.rank + 15) / 16) * (e.K / 32) + size_t((e.rank + 31) / 32) * (e.N / 16)) * 64);
-  }
-  if (most == 0) return hipSuccess;
-  hipLaunchKernelGGL(expand_q3_kernel, dim3((unsigned)((most + 255) / 256), 3), dim3(256), 0, s, jj);
-  return hipGetLastError();
-}
 
 hipError_t launch_combine(const moe_lrc_layer* L, const void* y_rows, const float* y_part, int kblocks, const float* w,
                           const int32_t* pair_row, const void* y_shared, const void* residual, int T, void* out,

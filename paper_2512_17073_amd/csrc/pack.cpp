@@ -159,27 +159,82 @@ void pack_factor_b(const MatLayout& m, int rank, const uint16_t* B_bf16, uint16_
       }
 }
 
-bool pack_q3_blob(int K, int N, int rank, const uint8_t* a_codes, const uint16_t* a_scale, const uint16_t* a_zero,
-                  const uint8_t* b_codes, const uint16_t* b_scale, const uint16_t* b_zero, uint8_t* out) {
-  size_t off[6];
-  q3_offsets(K, N, rank, off);
-  std::memset(out, 0, off[5]);
-  auto stream = [](const uint8_t* codes, size_t n, uint8_t* dst) {
-    for (size_t i = 0; i < n; ++i) {
-      if (codes[i] > 7) return false;
-      const size_t bit = 3 * i;
-      const uint32_t v = uint32_t(codes[i]) << (bit & 7);
-      dst[bit >> 3] |= uint8_t(v);
-      dst[(bit >> 3) + 1] |= uint8_t(v >> 8);
-    }
-    return true;
-  };
-  if (!stream(a_codes, size_t(K) * rank, out) || !stream(b_codes, size_t(N) * rank, out + off[2])) return false;
-  std::memcpy(out + off[0], a_scale, size_t(K / 64) * rank * 2);
-  std::memcpy(out + off[1], a_zero, size_t(K / 64) * rank * 2);
-  std::memcpy(out + off[3], b_scale, size_t(N / 64) * rank * 2);
-  std::memcpy(out + off[4], b_zero, size_t(N / 64) * rank * 2);
-  return true;
+namespace {
+// mu: the largest power of two <= 1 that keeps scale * mu * 2^17 finite in fp16
+double q3_mu(const uint16_t* scale, size_t n) {
+  double smax = 0;
+  for (size_t i = 0; i < n; ++i) {
+    const double s = std::fabs((double)f16_bits_to_float(scale[i]));
+    if (std::isfinite(s)) smax = std::max(smax, s);
+  }
+  int j = 0;
+  while (smax * std::ldexp(1.0, 17 - j) > 32768.0) ++j;
+  return std::ldexp(1.0, -j);
+}
+}  // namespace
+
+float pack_factor_a_q3(int K, int rank, const uint8_t* codes, const uint16_t* scale, const uint16_t* zero, uint8_t* out) {
+  const int rt = (rank + 15) / 16, k32 = K / 32, g64 = K / 64;
+  std::memset(out, 0, q3_a_bytes(K, rank));
+  for (size_t i = 0; i < size_t(K) * rank; ++i)
+    if (codes[i] > 7) return 0.f;
+  const double mu = q3_mu(scale, size_t(g64) * rank);
+  uint32_t* cw = reinterpret_cast<uint32_t*>(out);
+  uint32_t* mw = reinterpret_cast<uint32_t*>(out + q3_a_codes_bytes(K, rank));
+  for (int tile = 0; tile < rt; ++tile) {
+    for (int kk = 0; kk < k32; ++kk)
+      for (int lane = 0; lane < kWave; ++lane) {
+        const int c = lane & 15, q = lane >> 4, rho = 16 * tile + c;
+        if (rho >= rank) continue;
+        uint32_t w = 0;
+        for (int j = 0; j < 8; ++j)
+          w |= uint32_t(codes[size_t(32 * kk + 8 * q + j) * rank + rho]) << (16 * (j & 1) + 3 * (j >> 1));
+        cw[(size_t(tile) * k32 + kk) * kWave + lane] = w;
+      }
+    for (int g = 0; g < g64; ++g)
+      for (int c = 0; c < 16; ++c) {
+        const int rho = 16 * tile + c;
+        if (rho >= rank) continue;
+        const double s = f16_bits_to_float(scale[size_t(g) * rank + rho]), z = f16_bits_to_float(zero[size_t(g) * rank + rho]);
+        mw[(size_t(tile) * g64 + g) * 16 + c] =
+            uint32_t(float_to_f16_bits(s * mu * 131072.0)) | (uint32_t(float_to_f16_bits(-z * s * mu)) << 16);
+      }
+  }
+  return (float)mu;
+}
+
+float pack_factor_b_q3(int N, int rank, const uint8_t* codes, const uint16_t* scale, const uint16_t* zero, uint8_t* out) {
+  const int ls = (rank + 31) / 32, NT = N / 16, NG = N / 64;
+  std::memset(out, 0, q3_b_bytes(N, rank));
+  for (size_t i = 0; i < size_t(N) * rank; ++i)
+    if (codes[i] > 7) return 0.f;
+  const double mu = q3_mu(scale, size_t(NG) * rank);
+  uint32_t* cw = reinterpret_cast<uint32_t*>(out);
+  uint16_t* mh = reinterpret_cast<uint16_t*>(out + q3_b_codes_bytes(N, rank));
+  for (int st = 0; st < ls; ++st) {
+    for (int nt = 0; nt < NT; ++nt)
+      for (int lane = 0; lane < kWave; ++lane) {
+        const int c = lane & 15, q = lane >> 4;
+        uint32_t w = 0;
+        for (int j = 0; j < 8; ++j) {
+          const int rho = 32 * st + 8 * q + j;
+          if (rho < rank) w |= uint32_t(codes[size_t(nt * kTileN + c) * rank + rho]) << (16 * (j & 1) + 3 * (j >> 1));
+        }
+        cw[(size_t(st) * NT + nt) * kWave + lane] = w;
+      }
+    for (int ng = 0; ng < NG; ++ng)
+      for (int q = 0; q < 4; ++q) {
+        uint16_t* dst = mh + ((size_t(st) * NG + ng) * 4 + q) * 16;      // 8 halves of scales, then 8 of offsets
+        for (int j = 0; j < 8; ++j) {
+          const int rho = 32 * st + 8 * q + j;
+          if (rho >= rank) continue;
+          const double s = f16_bits_to_float(scale[size_t(ng) * rank + rho]), z = f16_bits_to_float(zero[size_t(ng) * rank + rho]);
+          dst[j] = float_to_f16_bits(s * mu * 131072.0);
+          dst[8 + j] = float_to_f16_bits(-z * s * mu);
+        }
+      }
+  }
+  return (float)mu;
 }
 
 }  // namespace lrc

@@ -11,8 +11,9 @@ float pack_meta(const MatLayout& m, const uint16_t* scale_f16, const uint16_t* z
 // factors bf16 -> fp16 MFMA-operand order
 void pack_factor_a(const MatLayout& m, int rank, const uint16_t* A_bf16, uint16_t* out);
 void pack_factor_b(const MatLayout& m, int rank, const uint16_t* B_bf16, uint16_t* out);
-// 3-bit factor pair -> transfer blob (q3_offsets in layout.h); codes one per byte, each < 8; returns
-// false if a code is out of range.  out: q3_offsets(...)[5] bytes
-bool pack_q3_blob(int K, int N, int rank, const uint8_t* a_codes, const uint16_t* a_scale, const uint16_t* a_zero,
-                  const uint8_t* b_codes, const uint16_t* b_scale, const uint16_t* b_zero, uint8_t* out);
+// factor pair at 3 bits (codes one per byte, fp16 scale/zero per group of 64 along K for A [K][rank],
+// along N for B transposed [N][rank]) -> the unit layout of layout.h, q3_a_bytes / q3_b_bytes bytes.
+// Return the power-of-two factor mu folded into the operands (0: a code is out of range).
+float pack_factor_a_q3(int K, int rank, const uint8_t* codes, const uint16_t* scale, const uint16_t* zero, uint8_t* out);
+float pack_factor_b_q3(int N, int rank, const uint8_t* codes, const uint16_t* scale, const uint16_t* zero, uint8_t* out);
 }  // namespace lrc

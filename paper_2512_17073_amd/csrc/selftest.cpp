@@ -7,9 +7,14 @@
 #include <string>
 #include <vector>
 
+#include <cmath>
+#include <cstring>
+
 #include "decode_index.h"
+#include "factor_q3.h"
 #include "ffn_common.h"
 #include "internal.h"
+#include "pack.h"
 
 namespace lrc {
 
@@ -122,6 +127,24 @@ std::string check_shape(const Shape& sh) {
                   if ((ref.st < (lowrank ? sh.LSm[sh.dual ? m : 0] : 0)) != inside) SELF_FAIL("rank step %d of stream %d: wrong side of the factor's end", ref.st, m);
                   if (inside && lane == 0) ++seen_lr[(size_t(ref.st) * NT + tile) * 2 + (sh.dual ? m : 0)];
                 }
+                // the same step of a stream whose pair is held at 3 bits: metadata through `bf`, codes through `bc`
+                {
+                  const int LSq = lowrank ? sh.LSm[sh.dual ? m : 0] : 0;
+                  const uint32_t bm_size = uint32_t(NT / 4) * LSq * 128, bc_size = uint32_t(NT) * LSq * 256;
+                  const LaneOffsets oq = lane_offsets(ref, tile, tile_ok, lane, sh.bits, NT, gs, code_bytes, meta_bytes, bf_bytes_max, true);
+                  if (oq.code0 != o.code0 || oq.code1 != o.code1 || oq.meta != o.meta) SELF_FAIL("3-bit pairs change the k-step offsets of step %d", n);
+                  if (ref.lr && tile_ok && ref.st < LSq) {
+                    const uint32_t q = lane >> 4, c = lane & 15;
+                    if (oq.bf != ((uint32_t(ref.st) * (NT / 4) + tile / 4) * 4 + q) * 32 + (c & 1) * 16 || oq.bf + 16 > bm_size)
+                      SELF_FAIL("rank step %d: metadata of a 3-bit unit at %u of %u", ref.st, oq.bf, bm_size);
+                    if (oq.bc != (uint32_t(ref.st) * NT + tile) * 256 + lane * 4 || oq.bc + 4 > bc_size)
+                      SELF_FAIL("rank step %d: codes of a 3-bit unit at %u of %u", ref.st, oq.bc, bc_size);
+                  } else {
+                    if (ref.lr && oq.bf < bm_size) SELF_FAIL("step %d reads 3-bit metadata it should not (offset %u of %u)", n, oq.bf, bm_size);
+                    // (the kernel reads through `bc` on rank steps only, from the codes' resource)
+                    if (ref.lr && oq.bc < bc_size) SELF_FAIL("step %d reads 3-bit codes it should not (offset %u of %u)", n, oq.bc, bc_size);
+                  }
+                }
               }
             }
           }
@@ -167,5 +190,64 @@ extern "C" int moe_lrc_selftest_decode_index(int hidden, int ffn, int bits, int 
   Shape b{ffn, hidden, bits, group, ls, {(rank2 + 31) / 32, (rank2 + 31) / 32}, first_row, rows, total_rows, blocks_w2, kblocks_w2, false};
   err = check_shape(b);
   if (!err.empty()) return set_error(MOE_LRC_ESHAPE, "selftest_decode_index (W2): " + err);
+  return MOE_LRC_OK;
+}
+
+namespace {
+// one half of a packed fp16 FMA as the device computes it: exact product and sum, one rounding
+float half_fma(uint16_t f, uint16_t s, uint16_t c) {
+  auto h = [](uint16_t b) { _Float16 v; std::memcpy(&v, &b, 2); return (double)v; };
+  return (float)(_Float16)std::fma(h(f), h(s), h(c));
+}
+uint32_t q3_field_rt(uint32_t v, int i) {
+  return i == 0 ? ffn::q3_field<0>(v) : i == 1 ? ffn::q3_field<1>(v) : i == 2 ? ffn::q3_field<2>(v) : ffn::q3_field<3>(v);
+}
+}  // namespace
+
+extern "C" int moe_lrc_selftest_factor_pair(int K, int N, int rank, const uint8_t* a_codes, const uint16_t* a_scale,
+                                          const uint16_t* a_zero, const uint8_t* b_codes, const uint16_t* b_scale,
+                                          const uint16_t* b_zero, float* A_out, float* B_out) {
+  if (!a_codes || !a_scale || !a_zero || !b_codes || !b_scale || !b_zero || !A_out || !B_out)
+    return set_error(MOE_LRC_EINVAL, "selftest_factor_pair: null argument");
+  if (K <= 0 || N <= 0 || K % 64 || N % 64 || rank <= 0 || rank > 1024 || rank % 8)
+    return set_error(MOE_LRC_ESHAPE, "selftest_factor_pair: K and N must be multiples of 64, rank a multiple of 8 in 8..1024");
+  std::vector<uint8_t> abuf(q3_a_bytes(K, rank)), bbuf(q3_b_bytes(N, rank));
+  const float mu_a = pack_factor_a_q3(K, rank, a_codes, a_scale, a_zero, abuf.data());
+  const float mu_b = pack_factor_b_q3(N, rank, b_codes, b_scale, b_zero, bbuf.data());
+  if (mu_a == 0.f || mu_b == 0.f) return set_error(MOE_LRC_EINVAL, "selftest_factor_pair: code out of range (3 bits)");
+  // A: the reads of the (in A) kernels: unit (tile, kk), lane (q, c); codes dword, metadata dword of (tile, kk / 2, c)
+  const int k32 = K / 32, g64 = K / 64, NT = N / 16, NG = N / 64;
+  const uint32_t* acw = reinterpret_cast<const uint32_t*>(abuf.data());
+  const uint32_t* amw = reinterpret_cast<const uint32_t*>(abuf.data() + q3_a_codes_bytes(K, rank));
+  for (int tile = 0; tile < (rank + 15) / 16; ++tile)
+    for (int kk = 0; kk < k32; ++kk)
+      for (int lane = 0; lane < 64; ++lane) {
+        const int q = lane >> 4, c = lane & 15, rho = 16 * tile + c;
+        const uint32_t codes = acw[(size_t(tile) * k32 + kk) * 64 + lane], meta = amw[(size_t(tile) * g64 + (kk >> 1)) * 16 + c];
+        for (int j = 0; j < 8; ++j) {
+          const uint32_t f = q3_field_rt(codes, j >> 1);
+          const float v = half_fma(uint16_t(j & 1 ? f >> 16 : f), uint16_t(meta), uint16_t(meta >> 16)) / mu_a;
+          if (rho < rank) A_out[size_t(32 * kk + 8 * q + j) * rank + rho] = v;
+          else if (v != 0.f) return set_error(MOE_LRC_ESHAPE, "selftest_factor_pair: a column of A past the rank is not zero");
+        }
+      }
+  // B: the reads of the FFN kernels' rank steps: unit (st, nt), lane (q, c); codes dword, 32 bytes of
+  // metadata of (st, nt / 4, q): eight scale halves, then eight offset halves
+  const uint32_t* bcw = reinterpret_cast<const uint32_t*>(bbuf.data());
+  const uint16_t* bmh = reinterpret_cast<const uint16_t*>(bbuf.data() + q3_b_codes_bytes(N, rank));
+  for (int st = 0; st < (rank + 31) / 32; ++st)
+    for (int nt = 0; nt < NT; ++nt)
+      for (int lane = 0; lane < 64; ++lane) {
+        const int q = lane >> 4, c = lane & 15;
+        const uint32_t codes = bcw[(size_t(st) * NT + nt) * 64 + lane];
+        const uint16_t* mh = bmh + ((size_t(st) * NG + nt / 4) * 4 + q) * 16;
+        for (int j = 0; j < 8; ++j) {
+          const uint32_t f = q3_field_rt(codes, j >> 1);
+          const float v = half_fma(uint16_t(j & 1 ? f >> 16 : f), mh[j], mh[8 + j]) / mu_b;
+          const int rho = 32 * st + 8 * q + j;
+          if (rho < rank) B_out[size_t(rho) * N + nt * 16 + c] = v;
+          else if (v != 0.f) return set_error(MOE_LRC_ESHAPE, "selftest_factor_pair: a row of B past the rank is not zero");
+        }
+      }
   return MOE_LRC_OK;
 }

@@ -92,8 +92,20 @@ int fill_slot(moe_lrc_stack* S, int li, int e, int slot, bool weights, bool fact
   }
   if (factors && b.f_bytes) {
     LRC_HIP(note_copy(S));
-    LRC_HIP(hipMemcpyAsync(slot_f_ptr(S, slot), L->h_f + L->f_off[e], b.f_bytes, hipMemcpyHostToDevice, S->copy));
-    S->st.bytes_h2d += b.f_bytes;
+    const uint8_t* q3 = &L->mat_q3[e * 3];
+    if (q3[0] | q3[1] | q3[2]) {             // pairs held at 3 bits fill a part of their sections only
+      for (int mat = 0; mat < 3; ++mat) {
+        size_t ab, bb;
+        factor_section_bytes(L, e, mat, ab, bb);
+        if (ab == 0) continue;
+        LRC_HIP(hipMemcpyAsync(slot_f_ptr(S, slot) + b.off_af[mat], L->h_f + L->f_off[e] + b.off_af[mat], ab, hipMemcpyHostToDevice, S->copy));
+        LRC_HIP(hipMemcpyAsync(slot_f_ptr(S, slot) + b.off_bf[mat], L->h_f + L->f_off[e] + b.off_bf[mat], bb, hipMemcpyHostToDevice, S->copy));
+        S->st.bytes_h2d += ab + bb;
+      }
+    } else {
+      LRC_HIP(hipMemcpyAsync(slot_f_ptr(S, slot), L->h_f + L->f_off[e], b.f_bytes, hipMemcpyHostToDevice, S->copy));
+      S->st.bytes_h2d += b.f_bytes;
+    }
     S->st.factor_copies++;
     S->slots[slot].has_f = true;
   }
@@ -167,8 +179,8 @@ int pool_stage(moe_lrc_layer* L, const void* x, int T, hipStream_t s) {
     for (int m = 0; m < 3; ++m) {
       d.codes[m] = reinterpret_cast<const uint32_t*>(slot_w_ptr(S, slot) + b.off_codes[m]);
       d.meta[m] = reinterpret_cast<const uint32_t*>(slot_w_ptr(S, slot) + b.off_meta[m]);
-      d.af[m] = b.f_bytes ? reinterpret_cast<const _Float16*>(slot_f_ptr(S, slot) + b.off_af[m]) : nullptr;
-      d.bf[m] = b.f_bytes ? reinterpret_cast<const _Float16*>(slot_f_ptr(S, slot) + b.off_bf[m]) : nullptr;
+      d.af[m] = d.bf[m] = nullptr;
+      if (b.f_bytes) set_factor_ptrs(L, e, m, d, slot_f_ptr(S, slot) + b.off_af[m], slot_f_ptr(S, slot) + b.off_bf[m]);
     }
     hd[e] = d;
   }

@@ -2,6 +2,9 @@
 // by the launch that prepares the activations (misc.hip), which runs it for the fused W1|W3
 // projections in further blocks.
 #pragma once
+#include <type_traits>
+
+#include "factor_q3.h"
 #include "ffn_common.h"
 
 namespace lrc {
@@ -40,8 +43,14 @@ __device__ __forceinline__ void xa_rows_body(const KArgs& a, const uint16_t* __r
   const int pitch = (DUAL ? 2 : 1) * a.ls * 32;
   const int rank = min(d.rank[mat], a.rank);
   const bool live = 16 * tl < rank;
-  const float lam = d.lambda[mat];
+  const float lam = d.xa_scale[mat];
   const half8_t* af = reinterpret_cast<const half8_t*>(d.af[mat]);
+  // a pair held at 3 bits (layout.h): one dword of codes per lane and unit, one of metadata per
+  // (tile, group of 64 inputs, column), dequantized here
+  const bool q3 = __builtin_amdgcn_readfirstlane((d.q3 >> mat) & 1) != 0;
+  const uint32_t* aq = reinterpret_cast<const uint32_t*>(d.af[mat]);
+  const uint32_t* am = d.afm[mat];
+  const int g64 = a.K / 64;
   // this block's K-block (grid.z K-blocks of kb_steps k-steps each; one when kb_steps covers K): the
   // FFN kernel's K-block kb applies the B factor to the part of (in A) summed over its own k-steps
   const int k32 = a.K / 32, kb_lo = min(k32, kb * a.kb_steps * 8), kb_hi = min(k32, (kb + 1) * a.kb_steps * 8);
@@ -68,12 +77,20 @@ __device__ __forceinline__ void xa_rows_body(const KArgs& a, const uint16_t* __r
     const bool any0 = __ballot(flagged[0]) != 0ull, any1 = __ballot(flagged[1]) != 0ull;   // block-uniform
     float4_t acc[2] = {float4_t{0.f, 0.f, 0.f, 0.f}, float4_t{0.f, 0.f, 0.f, 0.f}};
     if (live && (any0 || any1)) {
+      auto k_loop = [&](auto Q3_) {
+      constexpr bool Q3 = decltype(Q3_)::value;
       for (int kk = kk0; kk < kk1; kk += BATCH) {
         half8_t wf[BATCH], xf[2][BATCH];
+        uint32_t cq[BATCH], mq[BATCH];
 #pragma unroll
         for (int u = 0; u < BATCH; ++u) {
           const int ku = max(min(kk + u, kk1 - 1), 0);
-          wf[u] = af[(size_t(tl) * k32 + ku) * kWave + lane];
+          if constexpr (Q3) {
+            cq[u] = aq[(size_t(tl) * k32 + ku) * kWave + lane];
+            mq[u] = am[(size_t(tl) * g64 + (ku >> 1)) * 16 + c];
+          } else {
+            wf[u] = af[(size_t(tl) * k32 + ku) * kWave + lane];
+          }
 #pragma unroll
           for (int t = 0; t < 2; ++t) {
             if (t == 1 && !any1) { xf[t][u] = half8_t{0, 0, 0, 0, 0, 0, 0, 0}; continue; }
@@ -92,6 +109,7 @@ __device__ __forceinline__ void xa_rows_body(const KArgs& a, const uint16_t* __r
         }
 #pragma unroll
         for (int u = 0; u < BATCH; ++u) {
+          if constexpr (Q3) wf[u] = q3_unit_a(cq[u], mq[u]);
           if (kk + u >= kk1) wf[u] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};       // (a step past this wavefront's share)
 #pragma unroll
           for (int t = 0; t < 2; ++t) {
@@ -100,6 +118,9 @@ __device__ __forceinline__ void xa_rows_body(const KArgs& a, const uint16_t* __r
           }
         }
       }
+      };
+      if (q3) k_loop(std::true_type{});
+      else k_loop(std::false_type{});
       red[wave][lane] = acc[0];
       red[NW + wave][lane] = acc[1];
       __syncthreads();

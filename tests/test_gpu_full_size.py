@@ -81,7 +81,29 @@ def _with_rank(layer, rank):
     return {"wg": layer["wg"], "bias": layer["bias"], "experts": ex}
 
 
-def _check(amd, cfg, layer, L, sample_mats=((0, 0), (1, 2))):
+def _factors_at_3_bits(layer):
+    """The same layer with every factor pair quantized to INT3 (Section 3.1 step 2)."""
+    ex = []
+    for e in layer["experts"]:
+        d = {}
+        for m, a in e.items():
+            if a["A"] is None:
+                d[m] = a
+                continue
+            Aq, Bq = compress.quantize_factors(orc.bf16_to_f64(a["A"]), orc.bf16_to_f64(a["B"]))
+            d[m] = dict(a, A=None, B=None, Aq=Aq, Bq=Bq)
+        ex.append(d)
+    return {"wg": layer["wg"], "bias": layer["bias"], "experts": ex}
+
+
+def _upload_factors_at_3_bits(L, layer_q):
+    for e, ex in enumerate(layer_q["experts"]):
+        for m, a in ex.items():
+            if a.get("Aq") is not None:
+                L.set_expert_factors_quantized(e, m, a["Aq"]["codes"].shape[1], a["Aq"], a["Bq"])
+
+
+def _check(amd, cfg, layer, L, sample_mats=((0, 0), (1, 2)), q3=False):
     import torch
     T = cfg.tokens
     x_bits = synth.make_tokens(cfg)
@@ -123,7 +145,8 @@ def _check(amd, cfg, layer, L, sample_mats=((0, 0), (1, 2))):
     P = 3 * cfg.hidden * cfg.ffn
     assert st["active_experts"] == want["active_experts"] and st["comp_experts"] == want["comp_experts"]
     assert st["bytes_codes"] == want["bytes_codes"] + cfg.n_shared * P * cfg.shared_bits // 8
-    assert st["bytes_factors"] == want["bytes_factors"]
+    vals = 3 * cfg.rank * (cfg.hidden + cfg.ffn)
+    assert st["bytes_factors"] == (want["comp_experts"] * (vals * 4 // 8 + vals // 64 * 4) if q3 else want["bytes_factors"])
 
 
 def test_mixtral_decode_2bit(amd):
@@ -131,6 +154,11 @@ def test_mixtral_decode_2bit(amd):
     layer, L = _make(amd, base, max_tokens=64)
     for T in (1, 8, 32, 64):
         _check(amd, base.with_(tokens=T, name=f"mixtral_decode_T{T}_b2"), layer, L)
+    # the same layer with its factor pairs held at 3 bits and dequantized inside the kernels
+    layer_q = _factors_at_3_bits(layer)
+    _upload_factors_at_3_bits(L, layer_q)
+    for T in (8, 64):
+        _check(amd, base.with_(tokens=T, name=f"mixtral_decode_T{T}_b2_int3_factors"), layer_q, L, q3=True)
     L.close()
 
 
@@ -140,6 +168,10 @@ def test_mixtral_3bit_decode_and_prefill(amd):
     pre = configs.MIXTRAL_PREFILL
     layer64, L64 = _make(amd, pre, max_tokens=2048)
     _check(amd, pre, layer64, L64)
+    layer64_q = _factors_at_3_bits(layer64)
+    _upload_factors_at_3_bits(L64, layer64_q)
+    _check(amd, pre.with_(name=pre.name + "_int3_factors"), layer64_q, L64, q3=True)
+    del layer64_q
     L64.close()
     dec = configs.get("mixtral_decode_T64_b3").with_(seed=pre.seed, gate_kind=pre.gate_kind, gate_std=pre.gate_std)
     layer32 = _with_rank(layer64, 32)

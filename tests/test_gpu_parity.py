@@ -364,12 +364,13 @@ def test_rank_per_projection_from_kurtosis(amd, tokens):
     Lr.close(); Ls.close()
 
 
-@pytest.mark.parametrize("tokens,rank", [(16, 16), (300, 32), (40, 24)])
+@pytest.mark.parametrize("tokens,rank", [(16, 16), (300, 32), (40, 24), (24, 72), (700, 64)])
 def test_int3_factors(amd, tokens, rank):
     """Section 3.1 step 2 stores the factor pairs at INT3: uploaded as 3-bit codes + fp16 scale/zero
-    per group of 64, kept at 3 bits in the pinned pool, expanded to fp16 units on the device.
-    Resident and staged layers agree bit for bit and match the oracle on the quantized factors; the
-    staged byte counter counts 3 bits + scale/zero per value."""
+    per group of 64, kept at 3 bits in the pinned pool and on the device, and dequantized inside the
+    kernels that consume them (both flavours of the (in A) and of the FFN kernels are reached: 16 to
+    700 tokens).  Resident and staged layers agree bit for bit and match the oracle on the quantized
+    factors; the staged byte counter counts a 4-bit cell + scale/zero per value."""
     import torch
     cfg = configs.TINY.with_(rank=rank, tokens=tokens, bits=2, name=f"int3_T{tokens}_r{rank}")
     layer = fixtures.build_layer(cfg, int3_factors=True)
@@ -389,16 +390,17 @@ def test_int3_factors(amd, tokens, rank):
     assert torch.equal(out_r.view(torch.int16), out_s.view(torch.int16))
     n_comp = int((np.asarray(ref["perm"]["comp_counts"]) > 0).sum())
     vals = 3 * rank * (cfg.hidden + cfg.ffn)
-    assert Ls.stats()["bytes_factors"] == n_comp * (vals * 3 // 8 + vals // 64 * 4)
+    assert Ls.stats()["bytes_factors"] == n_comp * (vals * 4 // 8 + vals // 64 * 4)
     # the compensation is really there: without it the output differs by far more than the tolerance
     assert orc.rel_frobenius(_to_np(out_r), fixtures.oracle_forward(cfg.with_(top_n=0), layer, x_bits)["out"]) > 5 * TOL
     Lr.close(); Ls.close()
 
 
 def test_mixed_fp16_and_int3_projections_staged(amd):
-    """One expert may hold one projection's factors as an fp16 pair and the others at 3 bits: the
-    two kinds live in separate pinned regions, so neither upload disturbs the other.  Staged and
-    resident layers agree bit for bit and match the oracle."""
+    """One expert may hold one projection's factors as an fp16 pair and the others at 3 bits: each
+    pair lives in its own projection's factor sections, so neither upload disturbs the other, and
+    the kernels take the format per projection from the expert table.  Staged and resident layers
+    agree bit for bit and match the oracle."""
     import torch
     cfg = configs.TINY.with_(rank=32, tokens=24, bits=2, name="mixed_q3")
     bf = fixtures.build_layer(cfg)

@@ -139,6 +139,40 @@ def test_stack_is_bit_equal_to_resident_layers_and_reuses_slots(amd, stack_layer
         L.close()
 
 
+def test_stack_with_factor_pairs_held_at_3_bits(amd):
+    """Pooled layers whose factor pairs are stored at INT3 (Section 3.1 step 2): the pairs cross the
+    bus and sit in the slots at 3 bits and are dequantized inside the kernels; the stack gives the
+    bits of the resident layers, matches the oracle on the quantized factors, and moves fewer factor
+    bytes than with fp16 pairs."""
+    import torch
+    cfgs = [configs.TINY.with_(seed=4321 + 100 * l, tokens=6, rank=32, bits=2, name=f"stackq{l}") for l in range(2)]
+    layers = [fixtures.build_layer(c, int3_factors=True) for c in cfgs]
+    Lp = _make(amd, cfgs, layers, amd.POOLED)
+    Lr = _make(amd, cfgs, layers, amd.RESIDENT)
+    st = amd.Stack(Lp, slots=2 * cfgs[0].n_experts, prefetch=False, residual=False)
+    x_bits = synth.make_tokens(cfgs[0].with_(seed=78), 6)
+    x = amd.bf16_tensor(x_bits)
+    H = cfgs[0].hidden
+    li = torch.empty((2, 6, H), dtype=torch.bfloat16, device="cuda")
+    got = st.step(x, layer_inputs=li).clone()
+    want = x
+    for L in Lr:
+        want = L.forward(want).clone()
+    assert torch.equal(got.view(torch.int16), want.view(torch.int16))
+    ref = fixtures.oracle_forward(cfgs[1], layers[1], _bits(li[1]))
+    assert orc.rel_frobenius(_f64(got), ref["out"]) <= TOL
+    s = st.stats()
+    c0 = cfgs[0]
+    w_alg = compress.expert_code_bytes(c0.hidden, c0.ffn, c0.bits) + compress.expert_meta_bytes(c0.hidden, c0.ffn, c0.group)
+    vals = 3 * c0.rank * (c0.hidden + c0.ffn)
+    f_q3 = vals * 4 // 8 + vals // 64 * 4                     # a 4-bit cell per code, fp16 scale and zero per 64
+    assert s["factor_copies"] > 0
+    assert s["bytes_h2d"] <= s["misses"] * w_alg * 1.05 + s["factor_copies"] * f_q3 * 1.05
+    st.close()
+    for L in Lp + Lr:
+        L.close()
+
+
 def test_stack_argument_errors(amd, stack_layers):
     cfgs, layers = stack_layers
     Lp = _make(amd, cfgs[:1], layers[:1], amd.POOLED)
