@@ -44,16 +44,17 @@ def counter_traffic(workload):
     return None, None
 
 
-def algorithmic_bytes(cfg, T, active, comp):
+def algorithmic_bytes(cfg, T, active, comp, fb=2.0):
     """Bytes each kernel must move per launch: packed codes + fp16 scale/zero of active experts,
-    factor bytes of comp-active experts, activations in and out."""
+    factor bytes of comp-active experts (fb bytes per factor value: 2 as fp16, 0.5625 at 3 bits in
+    4-bit cells with fp16 scale/zero per 64), activations in and out."""
     H, F, b, g, r, k = cfg.hidden, cfg.ffn, cfg.bits, cfg.group, cfg.rank, cfg.top_k
     per_w = b / 8 + 4 / g                       # bytes per weight incl. scale/zero
     rows = T * k
-    w13 = active * 2 * H * F * per_w + comp * 2 * r * F * 2 + T * H * 2 + rows * F * 2
-    w2 = active * H * F * per_w + comp * r * H * 2 + rows * F * 2 + rows * H * 2
-    xa13 = comp * 2 * H * r * 2
-    xa2 = comp * F * r * 2
+    w13 = active * 2 * H * F * per_w + comp * 2 * r * F * fb + T * H * 2 + rows * F * 2
+    w2 = active * H * F * per_w + comp * r * H * fb + rows * F * 2 + rows * H * 2
+    xa13 = comp * 2 * H * r * fb
+    xa2 = comp * F * r * fb
     shared = cfg.n_shared * 3 * H * F * (cfg.shared_bits / 8 + 4 / g)
     total = w13 + w2 + xa13 + xa2 + shared + T * H * 2 * 2
     return {"w13": w13, "w2": w2, "xa13": xa13, "xa2": xa2, "shared": shared, "total": total}
@@ -105,7 +106,11 @@ def stack_bench(args, cfg):
             src = experts[(e + i) % E] if e < E else experts[e]
             for m in (0, 1, 2):
                 a = src[m]
-                L.set_expert(e, m, a["codes"], a["scale"], a["zero"], a["A"], a["B"])
+                if args.int3_factors and e < E and cfg.rank > 0:
+                    L.set_expert(e, m, a["codes"], a["scale"], a["zero"], None, None, 0)
+                    L.set_expert_factors_quantized(e, m, cfg.rank, *synth.sample_factor_codes(cfg, (e + i) % E, m))
+                else:
+                    L.set_expert(e, m, a["codes"], a["scale"], a["zero"], a["A"], a["B"])
         layers.append(L)
         print(f"[bench] layer {i + 1}/{nl} packed into pinned memory", file=sys.stderr, flush=True)
     st = amd.Stack(layers, slots=slots, prefetch=not args.no_prefetch, residual=True)
@@ -130,7 +135,8 @@ def stack_bench(args, cfg):
         "metric": "stack_decode_tokens_per_s", "value": T * n / dt, "unit": "tokens/s", "n_gpus": 1, "steps": n,
         "ms_per_step": dt / n * 1e3, "ms_per_layer": dt / n / nl * 1e3, "higher_is_better": True, "data": "synthetic",
         "config": {"workload": cfg.name, "layers": nl, "slots": slots, "experts_per_layer": E, "tokens": T,
-                   "prefetch": not args.no_prefetch, "residency": "pooled (pinned host memory)"},
+                   "prefetch": not args.no_prefetch, "residency": "pooled (pinned host memory)",
+                   "factors": "int3" if args.int3_factors else "bf16"},
         "transfers": dict(d, hit_rate=d["hits"] / max(1, d["expert_uses"]),
                           h2d_gb_per_s_while_copying=d["bytes_h2d"] / max(copy_ms, 1e-9) / 1e6 if copy_ms else None,
                           h2d_gb_per_s_over_the_run=d["bytes_h2d"] / dt / 1e9),
@@ -191,7 +197,10 @@ def main():
                          "pinned pool per call, chosen by the router) and report it under 'staging'; "
                          "never part of 'value'")
     ap.add_argument("--staged-int3", action="store_true",
-                    help="with --staged: the factor pairs are held at 3 bits in the pinned pool and expanded on the device")
+                    help="with --staged: the factor pairs are held at 3 bits (in the pinned pool, on the bus and on the device)")
+    ap.add_argument("--int3-factors", action="store_true",
+                    help="the timed layers hold their factor pairs at 3 bits, dequantized inside the kernels "
+                         "(config.factors says so; the default run keeps fp16 pairs)")
     ap.add_argument("--calibrate", action="store_true",
                     help="also measure what this device sustains (streaming read of 3 GiB, pinned host->device "
                          "copy, f16 MFMA rate) and report it as roofline.peak_measured beside the published peaks")
@@ -245,7 +254,11 @@ def main():
             src = experts[(e + i) % E] if e < E else experts[e]     # rotate the routed experts per instance
             for m in (0, 1, 2):
                 a = src[m]
-                L.set_expert(e, m, a["codes"], a["scale"], a["zero"], a["A"], a["B"])
+                if args.int3_factors and e < E and cfg.rank > 0:
+                    L.set_expert(e, m, a["codes"], a["scale"], a["zero"], None, None, 0)
+                    L.set_expert_factors_quantized(e, m, cfg.rank, *synth.sample_factor_codes(cfg, (e + i) % E, m))
+                else:
+                    L.set_expert(e, m, a["codes"], a["scale"], a["zero"], a["A"], a["B"])
         layers.append(L)
         print(f"[bench] layer instance {i + 1}/{n_layers} uploaded ({time.time() - t_setup:.0f}s)", file=sys.stderr, flush=True)
 
@@ -348,7 +361,7 @@ def main():
     stage_avg = {k: float(np.mean(v)) for k, v in stage_ms.items()}
 
     st = layers[0].stats()
-    ab = algorithmic_bytes(cfg, T, st["active_experts"], st["comp_experts"])
+    ab = algorithmic_bytes(cfg, T, st["active_experts"], st["comp_experts"], 0.5625 if args.int3_factors else 2.0)
     flops = algorithmic_flops(cfg, T)
     dom = "w13"
     # A stage is bracketed by two event records, and a record itself takes stream time: without shared
@@ -370,8 +383,8 @@ def main():
         achieved = ab[dom] / (dom_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": "packed W1|W3 product + SwiGLU (qgemm_decode_kernel<bits,true> at decode sizes)",
                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": counter_traffic(cfg.name)[0],
-                    "traffic_source": counter_traffic(cfg.name)[1],
+                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": counter_traffic(cfg.name + ("_int3_factors" if args.int3_factors else ""))[0],
+                    "traffic_source": counter_traffic(cfg.name + ("_int3_factors" if args.int3_factors else ""))[1],
                     "bytes_per_launch": int(ab[dom]), "avg_ms": round(dom_ms, 5),
                     "avg_ms_incl_event_pair": round(stage_avg[dom], 5), "event_pair_ms": round(ev_pair, 5)}
     if args.calibrate:
@@ -395,6 +408,7 @@ def main():
                    "experts": cfg.n_experts, "shared": cfg.n_shared, "top_k": cfg.top_k, "top_n": cfg.top_n,
                    "bits": cfg.bits, "group": cfg.group, "rank": cfg.rank, "layer_instances": n_layers,
                    "active_experts": st["active_experts"], "comp_experts": st["comp_experts"],
+                   "factors": "int3" if args.int3_factors else "bf16",
                    "launch": "hip_graph" if use_graph else "eager"},
         "roofline": roofline,
         "spread": spread,

@@ -148,15 +148,16 @@ void fill_algorithmic_stats(moe_lrc_layer* L, const int32_t* stat) {
   L->stats_valid = true;
 }
 
-// Bytes of the A and of the B section of (expert, projection) that its factor pair fills: the
-// prefix its own rank takes, in the format it is held in.
+// Bytes at the start of the A and of the B section of (expert, projection) that its factor pair
+// fills: the prefix its own rank takes, in the format it is held in.  (The A and B sections of a
+// projection are adjacent; a 3-bit pair is one piece that starts with the A section.)
 void factor_section_bytes(const moe_lrc_layer* L, int e, int mat, size_t& a_bytes, size_t& b_bytes) {
   const MatLayout& m = blob_of(L, e).mat[mat];
   const int r = L->mat_rank[e * 3 + mat];
   a_bytes = b_bytes = 0;
   if (r == 0) return;
-  if (L->mat_q3[e * 3 + mat]) {
-    a_bytes = q3_a_bytes(m.K, r); b_bytes = q3_b_bytes(m.N, r);
+  if (L->mat_q3[e * 3 + mat]) {      // one piece: the B part lies right behind the A part, at the start of the A section
+    a_bytes = align256(q3_a_bytes(m.K, r)) + q3_b_bytes(m.N, r);
   } else {
     const MatLayout fm = make_layout(m.K, m.N, m.bits, m.group, r);
     a_bytes = fm.af_bytes; b_bytes = fm.bf_bytes;
@@ -170,10 +171,11 @@ void set_factor_ptrs(const moe_lrc_layer* L, int e, int mat, ExpertDesc& d, cons
   const int r = L->mat_rank[e * 3 + mat];
   d.afm[mat] = nullptr; d.bfc[mat] = nullptr;
   if (L->mat_q3[e * 3 + mat]) {
+    const uint8_t* bq = a_base + align256(q3_a_bytes(m.K, r));      // (the B part follows the A part)
     d.af[mat] = reinterpret_cast<const _Float16*>(a_base);
     d.afm[mat] = reinterpret_cast<const uint32_t*>(a_base + q3_a_codes_bytes(m.K, r));
-    d.bfc[mat] = reinterpret_cast<const uint32_t*>(b_base);
-    d.bf[mat] = reinterpret_cast<const _Float16*>(b_base + q3_b_codes_bytes(m.N, r));
+    d.bfc[mat] = reinterpret_cast<const uint32_t*>(bq);
+    d.bf[mat] = reinterpret_cast<const _Float16*>(bq + q3_b_codes_bytes(m.N, r));
   } else {
     d.af[mat] = reinterpret_cast<const _Float16*>(a_base);
     d.bf[mat] = reinterpret_cast<const _Float16*>(b_base);
@@ -202,10 +204,9 @@ static int stage_selected(moe_lrc_layer* L, hipStream_t stream) {
         for (int mat = 0; mat < 3; ++mat) {      // the prefixes the projection's rank fills, in the format it is held in
           size_t ab, bb;
           factor_section_bytes(L, e, mat, ab, bb);
-          if (ab == 0) continue;
           const size_t aoff = L->f_off[e] + b.off_af[mat], boff = L->f_off[e] + b.off_bf[mat];
-          LRC_HIP(hipMemcpyAsync(L->d_f + aoff, L->h_f + aoff, ab, hipMemcpyHostToDevice, L->side));
-          LRC_HIP(hipMemcpyAsync(L->d_f + boff, L->h_f + boff, bb, hipMemcpyHostToDevice, L->side));
+          if (ab) LRC_HIP(hipMemcpyAsync(L->d_f + aoff, L->h_f + aoff, ab, hipMemcpyHostToDevice, L->side));
+          if (bb) LRC_HIP(hipMemcpyAsync(L->d_f + boff, L->h_f + boff, bb, hipMemcpyHostToDevice, L->side));
         }
       }
     }
@@ -535,23 +536,20 @@ int moe_lrc_set_expert_factors_quantized(moe_lrc_layer* L, int expert, int mat, 
   const float mu_a = pack_factor_a_q3(m.K, rank, a_codes, a_scale, a_zero, abuf.data());
   const float mu_b = pack_factor_b_q3(m.N, rank, b_codes, b_scale, b_zero, bbuf.data());
   if (mu_a == 0.f || mu_b == 0.f) return set_error(MOE_LRC_EINVAL, "set_expert_factors_quantized: code out of range (3 bits)");
-  const size_t aoff = L->f_off[expert] + b.off_af[mat], boff = L->f_off[expert] + b.off_bf[mat];
+  // one piece at the start of the projection's A section (the B section follows it in the blob): the
+  // A part, then the B part at the next multiple of 256 bytes; one copy brings it in
+  const size_t aoff = L->f_off[expert] + b.off_af[mat];
+  if (b.off_bf[mat] != b.off_af[mat] + m.af_bytes) return set_error(MOE_LRC_ESTATE, "set_expert_factors_quantized: factor sections not adjacent");
+  std::vector<uint8_t> piece(align256(abuf.size()) + bbuf.size(), 0);
+  std::memcpy(piece.data(), abuf.data(), abuf.size());
+  std::memcpy(piece.data() + align256(abuf.size()), bbuf.data(), bbuf.size());
+  const size_t span = m.af_bytes + m.bf_bytes;
   const bool host_homed = c.residency != MOE_LRC_RESIDENT, pooled = c.residency == MOE_LRC_POOLED;
-  if (host_homed) {
-    std::memcpy(L->h_f + aoff, abuf.data(), abuf.size());
-    std::memcpy(L->h_f + boff, bbuf.data(), bbuf.size());
-  } else {
-    LRC_HIP(hipMemcpy(L->d_f + aoff, abuf.data(), abuf.size(), hipMemcpyHostToDevice));
-    LRC_HIP(hipMemcpy(L->d_f + boff, bbuf.data(), bbuf.size(), hipMemcpyHostToDevice));
-  }
+  if (host_homed) std::memcpy(L->h_f + aoff, piece.data(), piece.size());
+  else LRC_HIP(hipMemcpy(L->d_f + aoff, piece.data(), piece.size(), hipMemcpyHostToDevice));
   // what an earlier upload may have left behind the pair
-  if (pooled) {
-    std::memset(L->h_f + aoff + abuf.size(), 0, m.af_bytes - abuf.size());
-    std::memset(L->h_f + boff + bbuf.size(), 0, m.bf_bytes - bbuf.size());
-  } else {
-    LRC_HIP(hipMemset(L->d_f + aoff + abuf.size(), 0, m.af_bytes - abuf.size()));
-    LRC_HIP(hipMemset(L->d_f + boff + bbuf.size(), 0, m.bf_bytes - bbuf.size()));
-  }
+  if (pooled) std::memset(L->h_f + aoff + piece.size(), 0, span - piece.size());
+  else LRC_HIP(hipMemset(L->d_f + aoff + piece.size(), 0, span - piece.size()));
   L->mat_rank[expert * 3 + mat] = rank;
   L->n_q3 += 1 - L->mat_q3[expert * 3 + mat];
   L->mat_q3[expert * 3 + mat] = 1;
@@ -560,7 +558,7 @@ int moe_lrc_set_expert_factors_quantized(moe_lrc_layer* L, int expert, int mat, 
   d.rank[mat] = rank;
   d.xa_scale[mat] = d.lambda[mat] * L->mat_inv_mu[expert * 3 + mat];
   d.q3 |= 1 << mat;
-  if (!pooled) set_factor_ptrs(L, expert, mat, d, L->d_f + aoff, L->d_f + boff);
+  if (!pooled) set_factor_ptrs(L, expert, mat, d, L->d_f + aoff, L->d_f + L->f_off[expert] + b.off_bf[mat]);
   LRC_HIP(hipMemcpy(L->d_desc + expert, &d, sizeof(ExpertDesc), hipMemcpyHostToDevice));
   return MOE_LRC_OK;
 }

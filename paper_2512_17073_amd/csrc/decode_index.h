@@ -116,12 +116,11 @@ LRC_HD LaneOffsets lane_offsets(const StepRef& r, int tile, bool tile_ok, int la
   o.code0 = (ok ? tile_base : past) + lane * 16;
   o.code1 = (ok ? tile_base : code_bytes) + 1024 + lane * (bits == 3 ? 8 : 16);
   o.meta = (ok ? (uint32_t(r.ks) * gps * NT + tile) * (kTileN * 4) : meta_bytes) + meta_lane;
-  o.bf = (lr ? (uint32_t(r.st) * NT + tile) * 1024 : past) + lane * 16;
-  o.bc = 0xfffffff0u;
-  if (q3 && lr) {
-    o.bf = ((uint32_t(r.st) * (NT / 4) + (tile >> 2)) * 4 + q) * 32 + (c & 1) * 16;
-    o.bc = (uint32_t(r.st) * NT + tile) * 256 + lane * 4;
-  }
+  // (selects on wave-uniform conditions rather than branches: the loads of a step stay in one block)
+  const bool lq = q3 && lr;
+  const uint32_t unit = uint32_t(r.st) * NT + tile, group4 = uint32_t(r.st) * (NT / 4) + (tile >> 2);
+  o.bf = (lq ? group4 * 128 : lr ? unit * 1024 : past) + (lq ? q * 32 + (c & 1) * 16 : lane * 16);
+  o.bc = (lq ? unit * 256 : 0xfffffe00u) + lane * 4;
   return o;
 }
 

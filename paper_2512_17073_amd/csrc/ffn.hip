@@ -153,9 +153,10 @@ template <int BITS, int NM, int NTW> struct Slot2 { Slot<BITS, NM> t[NTW]; };
 // WAVES wavefronts per block.  8 (two per SIMD, 256 registers each) is what the launches use: with 4
 // (one per SIMD with 512 registers and twice the n-tiles, so that a fragment read from LDS feeds
 // twice the MFMAs) the fused kernel measured 19 % slower: nothing fills a wavefront's waits.
-// Q3: some factor pair of the layer is held at 3 bits (layout.h): a rank step of such a pair brings
-// the unit's code dword in the slot's metadata register and the lane's half of the unit's metadata in
-// its first four code registers, and is dequantized into the fp16 unit before it is used.
+// Q3: some factor pair of the layer is held at 3 bits (layout.h): the rank steps of such a pair fetch
+// the unit's code dword and the lane's half of the unit's metadata with loads of their own, one rank
+// step ahead (the ring and the k-loop are those of the plain kernel), and dequantize them into the
+// fp16 unit before it is used.
 template <int BITS, bool DUAL, int NTW, int WAVES = kTileWaves, bool Q3 = false>
 __global__ __launch_bounds__(64 * WAVES, WAVES == 4 ? 1 : 2) void qgemm_tile_kernel(KArgs a) {
   extern __shared__ uint4 xs[];           // two k-steps of activations; afterwards the (in A) fragments
@@ -182,7 +183,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 4 ? 1 : 2) void qgemm_tile_ker
   // steps of the larger one, a resource of the size its rank fills makes the other read zeros
   int LSm[NM];
   const int bf_bytes = a.NT * a.ls * 1024;
-  __amdgpu_buffer_rsrc_t code_rs[NM], meta_rs[NM], bf_rs[NM], bc_rs[NM];
+  __amdgpu_buffer_rsrc_t code_rs[NM], meta_rs[NM], bf_rs[NM];
   bool q3m[NM];
   float lam[NM];
 #pragma unroll
@@ -192,12 +193,9 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 4 ? 1 : 2) void qgemm_tile_ker
     q3m[m] = Q3 && __builtin_amdgcn_readfirstlane((d.q3 >> mat) & 1) != 0;
     code_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(uniform_ptr(d.codes[mat])), 0, code_bytes, 0x00020000);
     meta_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(uniform_ptr(d.meta[mat])), 0, meta_bytes, 0x00020000);
-    // (3-bit pair: the B section's metadata, 128 bytes per rank step and group of four n-tiles)
+    // (a 3-bit pair does not ride the ring: its rank steps read zeros here and fetch their units themselves)
     bf_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<_Float16*>(uniform_ptr(d.bf[mat])), 0,
-                                                 q3m[m] ? (a.NT / 4) * LSm[m] * 128 : a.NT * LSm[m] * 1024, 0x00020000);
-    if constexpr (Q3)     // the code dwords of a 3-bit pair's B units (no bytes for an fp16 pair: every read gives zero)
-      bc_rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(uniform_ptr(q3m[m] ? d.bfc[mat] : d.codes[mat])), 0,
-                                                   q3m[m] ? a.NT * LSm[m] * 256 : 0, 0x00020000);
+                                                 q3m[m] ? 0 : a.NT * LSm[m] * 1024, 0x00020000);
     lam[m] = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(d.inv_lambda[mat])));
   }
   const int LS = max(LSm[0], LSm[NM - 1]);
@@ -218,26 +216,6 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 4 ? 1 : 2) void qgemm_tile_ker
 #pragma unroll
       for (int m = 0; m < NM; ++m) {
         Slot<BITS, NM>& s1 = sl.t[t];
-        if constexpr (Q3) {
-          // a rank step of a 3-bit pair: the lane's half of the metadata of (rank step, group of four
-          // n-tiles, lane group), and the unit's code dword in place of the k-step's metadata
-          const int st = step - a.KS;
-          const bool lq = lr && q3m[m];
-          const int off0 = lq ? ((st * (a.NT / 4) + (tile >> 2)) * 4 + q) * 32 + (c & 1) * 16 : tile_off;
-          // (neither a k-step nor a rank step of a 3-bit pair: an offset past every resource)
-          const int offm = ok ? meta_off : lq ? (st * a.NT + tile) * 256 + lane * 4 : 0x7ffffff0;
-          const u32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(lr ? bf_rs[m] : code_rs[m], off0, 0, 0);
-          s1.cw[m][0] = v0[0]; s1.cw[m][1] = v0[1]; s1.cw[m][2] = v0[2]; s1.cw[m][3] = v0[3];
-          if constexpr (BITS == 3) {
-            const u32x2 v1 = __builtin_amdgcn_raw_buffer_load_b64(code_rs[m], tile_off2, 0, 0);
-            s1.cw[m][4] = v1[0]; s1.cw[m][5] = v1[1];
-          } else if constexpr (BITS == 4) {
-            const u32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(code_rs[m], tile_off2, 0, 0);
-            s1.cw[m][4] = v1[0]; s1.cw[m][5] = v1[1]; s1.cw[m][6] = v1[2]; s1.cw[m][7] = v1[3];
-          }
-          s1.mw[m] = __builtin_amdgcn_raw_buffer_load_b32(ok ? meta_rs[m] : bc_rs[m], offm, 0, 0);
-          continue;
-        }
         const u32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(lr ? bf_rs[m] : code_rs[m], tile_off, 0, 0);
         s1.cw[m][0] = v0[0]; s1.cw[m][1] = v0[1]; s1.cw[m][2] = v0[2]; s1.cw[m][3] = v0[3];
         if constexpr (BITS == 3) {
@@ -387,8 +365,33 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 4 ? 1 : 2) void qgemm_tile_ker
   //      st, variant v, row pair rp) at unit (((st - c0) * V + v) * 4 + rp) * 64 (rank_frag_source).
   constexpr int V = DUAL ? 4 : 2;
   constexpr int kRankChunk = 2 * kStepUnits / (V * kRP * 64);       // 8 (fused) or 16 rank steps fill the 128 KB
+  // 3-bit pairs: the code dword and the lane's half of the metadata (layout.h) of every stream's unit
+  // of one rank step; zeros for fp16 pairs, past the stream's own rank and past the last n-tile
+  struct QUnits { uint32_t codes[kNTW][NM]; uint32_t meta[kNTW][NM][4]; };
+  auto q_load = [&](int st, QUnits& qu) {
+#pragma unroll
+    for (int t = 0; t < kNTW; ++t)
+#pragma unroll
+      for (int m = 0; m < NM; ++m) {
+        qu.codes[t][m] = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) qu.meta[t][m][i] = 0;
+        if constexpr (Q3) {
+          const int tile = tile0 + t;
+          if (q3m[m] && st < LSm[m] && tile < a.NT) {
+            const int mat = DUAL ? m : 2;
+            qu.codes[t][m] = uniform_ptr(d.bfc[mat])[(size_t(st) * a.NT + tile) * kWave + lane];
+            const uint4 v = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint8_t*>(uniform_ptr(d.bf[mat])) +
+                                                            ((size_t(st) * (a.NT / 4) + (tile >> 2)) * 4 + q) * 32 + (c & 1) * 16);
+            qu.meta[t][m][0] = v.x; qu.meta[t][m][1] = v.y; qu.meta[t][m][2] = v.z; qu.meta[t][m][3] = v.w;
+          }
+        }
+      }
+  };
+  QUnits qnext;
   for (int c0 = 0; c0 < LS; c0 += kRankChunk) {
     const int c1 = min(LS, c0 + kRankChunk);
+    q_load(c0, qnext);                       // (arrives with the copies below)
     asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");   // (everyone is done with what LDS held)
     const _Float16* P = reinterpret_cast<const _Float16*>(a.p);
     const int pitch = NM * a.ls * 32;                                // halves per row
@@ -405,19 +408,19 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 4 ? 1 : 2) void qgemm_tile_ker
     // (the ring slots are refilled below, after this wait: only the copies just issued and the two
     // slots requested before them are outstanding)
     asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-    // the fp16 B-factor unit of stream m of a slot that holds a rank step
-    auto b_unit = [&](const Slot<BITS, NM>& s1, int m, uint32_t (&u)[4]) {
-      const uint32_t own[4] = {s1.cw[m][0], s1.cw[m][1], s1.cw[m][2], s1.cw[m][3]};
+    // the fp16 B-factor unit of stream (t, m) of a rank step: from the slot, or rebuilt from a 3-bit unit
+    auto b_unit = [&](const Slot2<BITS, NM, kNTW>& cur, const QUnits& qu, int t, int m, uint32_t (&u)[4]) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) u[i] = own[i];
+      for (int i = 0; i < 4; ++i) u[i] = cur.t[t].cw[m][i];
       if constexpr (Q3) {
         if (q3m[m]) {
-          const uint4 v = __builtin_bit_cast(uint4, q3_unit_b(s1.mw[m], own, (c & 1) != 0));
+          const uint32_t own[4] = {qu.meta[t][m][0], qu.meta[t][m][1], qu.meta[t][m][2], qu.meta[t][m][3]};
+          const uint4 v = __builtin_bit_cast(uint4, q3_unit_b(qu.codes[t][m], own, (c & 1) != 0));
           u[0] = v.x; u[1] = v.y; u[2] = v.z; u[3] = v.w;
         }
       }
     };
-    auto rank_step = [&](const Slot2<BITS, NM, kNTW>& cur, int st) {
+    auto rank_step = [&](const Slot2<BITS, NM, kNTW>& cur, const QUnits& qu, int st) {
 #pragma unroll
       for (int j = 0; j < NPAIR; ++j) {
         // the B-factor units of the pair's two streams, 16-lane rows swapped: r0 = rank groups 0 and 2
@@ -426,8 +429,8 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 4 ? 1 : 2) void qgemm_tile_ker
         pair_stream(j, 0, t0s, m0s);
         pair_stream(j, 1, t1s, m1s);
         uint32_t u0[4], u1[4], r0v[4], r1v[4];
-        b_unit(cur.t[t0s], m0s, u0);
-        b_unit(cur.t[t1s], m1s, u1);
+        b_unit(cur, qu, t0s, m0s, u0);
+        b_unit(cur, qu, t1s, m1s, u1);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const auto sw = __builtin_amdgcn_permlane16_swap(u0[i], u1[i], false, false);
@@ -463,7 +466,9 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 4 ? 1 : 2) void qgemm_tile_ker
       for (int i = 0; i < 2; ++i) {
         const int step = s0 + i;
         if (step >= steps + c0 && step < steps + c1) {
-          rank_step(ring[i], step - steps);
+          const QUnits qcur = qnext;
+          q_load(step - steps + 1 < c1 ? step - steps + 1 : LS, qnext);   // (LS: nothing to fetch)
+          rank_step(ring[i], qcur, step - steps);
           fetch(step + 2, ring[i]);
         }
       }
@@ -583,19 +588,28 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void xa_tile_kernel(KArgs a) {
     if (valid[t] && kk * 32 < a.K) {
       if (Q3 && q3t[t]) {
         v[0] = reinterpret_cast<const uint32_t*>(af[t])[size_t(kk) * kWave + (s & 3) * 16];
-        v[1] = am[t][(kk >> 1) * 16];
       } else {
         v = __builtin_bit_cast(u32x4, af[t][size_t(kk) * kWave + (s & 3) * 16]);
       }
     }
     return v;
   };
+  // 3-bit pairs: a lane's eight units of a k-step lie in one group of 64 inputs (rows 256 step + 64 q ..):
+  // one dword of metadata per k-step and tile
+  auto load_meta = [&](int step, int t) {
+    uint32_t mv = 0;
+    if (Q3 && q3t[t] && valid[t] && (step * 4 + q) * 64 < a.K) mv = am[t][(step * 4 + q) * 16];
+    return mv;
+  };
   // the operand of a fetched unit (a unit that was not fetched is all zeros in either format)
-  auto operand = [&](const u32x4& v, int t) {
-    if (Q3 && q3t[t]) return q3_unit_a(v[0], v[1]);
+  auto operand = [&](const u32x4& v, uint32_t mv, int t) {
+    if (Q3 && q3t[t]) return q3_unit_a(v[0], mv);
     return __builtin_bit_cast(half8_t, v);
   };
   u32x4 wnext[kAhead ? 8 : 1][kMaxT];
+  uint32_t mnext[kMaxT];
+#pragma unroll
+  for (int t = 0; t < kMaxT; ++t) mnext[t] = load_meta(step_lo, t);
   if constexpr (kAhead) {
 #pragma unroll
     for (int s = 0; s < 8; ++s)
@@ -608,11 +622,14 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void xa_tile_kernel(KArgs a) {
     stage_step(a, xs + ((step + 1) & 1) * kStepUnits, step + 1, rin, wave, lane);
     const uint4* buf = xs + (step & 1) * kStepUnits;
     half8_t wcur[kAhead ? 8 : 1][kMaxT];
+    uint32_t mcur[kMaxT];
+#pragma unroll
+    for (int t = 0; t < kMaxT; ++t) { mcur[t] = mnext[t]; mnext[t] = load_meta(step + 1, t); }
     if constexpr (kAhead) {                  // this step's units have arrived; ask for the next step's
 #pragma unroll
       for (int s = 0; s < 8; ++s)
 #pragma unroll
-        for (int t = 0; t < kMaxT; ++t) wcur[s][t] = operand(wnext[s][t], t);
+        for (int t = 0; t < kMaxT; ++t) wcur[s][t] = operand(wnext[s][t], mcur[t], t);
 #pragma unroll
       for (int s = 0; s < 8; ++s)
 #pragma unroll
@@ -624,7 +641,7 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void xa_tile_kernel(KArgs a) {
 #pragma unroll
       for (int t = 0; t < kMaxT; ++t) {
         if constexpr (kAhead) wf[t] = wcur[s][t];
-        else wf[t] = operand(load_unit(step, s, t), t);
+        else wf[t] = operand(load_unit(step, s, t), mcur[t], t);
       }
 #pragma unroll
       for (int mt = 0; mt < kTMT; ++mt)

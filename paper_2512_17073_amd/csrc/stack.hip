@@ -97,9 +97,8 @@ int fill_slot(moe_lrc_stack* S, int li, int e, int slot, bool weights, bool fact
       for (int mat = 0; mat < 3; ++mat) {
         size_t ab, bb;
         factor_section_bytes(L, e, mat, ab, bb);
-        if (ab == 0) continue;
-        LRC_HIP(hipMemcpyAsync(slot_f_ptr(S, slot) + b.off_af[mat], L->h_f + L->f_off[e] + b.off_af[mat], ab, hipMemcpyHostToDevice, S->copy));
-        LRC_HIP(hipMemcpyAsync(slot_f_ptr(S, slot) + b.off_bf[mat], L->h_f + L->f_off[e] + b.off_bf[mat], bb, hipMemcpyHostToDevice, S->copy));
+        if (ab) LRC_HIP(hipMemcpyAsync(slot_f_ptr(S, slot) + b.off_af[mat], L->h_f + L->f_off[e] + b.off_af[mat], ab, hipMemcpyHostToDevice, S->copy));
+        if (bb) LRC_HIP(hipMemcpyAsync(slot_f_ptr(S, slot) + b.off_bf[mat], L->h_f + L->f_off[e] + b.off_bf[mat], bb, hipMemcpyHostToDevice, S->copy));
         S->st.bytes_h2d += ab + bb;
       }
     } else {
