@@ -90,6 +90,7 @@ Workspace plan_workspace(const moe_lrc_layer* L, int T) {
   w.row_exp = take((P + kActPadRows) * 4);
   w.row_exp_sh = take(c.n_shared ? (size_t(T) + kActPadRows) * 4 : 0);
   w.plan = take(size_t(plan_blocks(c.n_experts, int(P), c.ffn / 16, L->n_cu) + plan_blocks(c.n_experts, int(P), c.hidden / 16, L->n_cu)) * kPlanEntryInts * 4);
+  w.cmp_index = take(P * 4);  w.cmp_list = take(P * 4);
   w.total = o;
   return w;
 }
@@ -252,8 +253,12 @@ static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t*
   // ((x A1 | x A3) from the tokens inside the preparing launch needs the exponents beforehand)
   a.xa13_here = c.residency != MOE_LRC_RESIDENT || tok_exp == nullptr;
   a.x_tokens = x;
+  // (the grouped (in A) kernels work on the rows that take the rank-r term only: their compact order)
+  const bool comp = c.rank > 0 && c.top_n > 0 && path != 0;
+  const CompactArgs cmp{reinterpret_cast<int32_t*>(ws + w.cmp_index), reinterpret_cast<int32_t*>(ws + w.cmp_list)};
+  if (comp) { a.cmp_index = cmp.index; a.cmp_list = cmp.list; }
   LRC_HIP(launch_convert_x(L, x, T, xh, P + kActPadRows, offsets, row_pair, L->d_stat, plans,
-                           ((path & 1) || a.xa13_here) ? nullptr : &a, tok_exp, a.row_exp, perm, stream));
+                           ((path & 1) || a.xa13_here) ? nullptr : &a, tok_exp, a.row_exp, perm, comp ? &cmp : nullptr, stream));
   L->stats_valid = false;
   L->stats.stage_ms = 0.f;
   if (c.residency == MOE_LRC_STAGED) {
@@ -275,7 +280,7 @@ static int run_shared(moe_lrc_layer* L, const void* x, int T, uint8_t* ws, hipSt
   const Workspace w = plan_workspace(L, T);
   _Float16* xh = reinterpret_cast<_Float16*>(ws + w.xh_sh);
   int32_t* row_exp = reinterpret_cast<int32_t*>(ws + w.row_exp_sh);
-  LRC_HIP(launch_convert_x(L, x, T, xh, T + kActPadRows, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, row_exp, nullptr, stream));
+  LRC_HIP(launch_convert_x(L, x, T, xh, T + kActPadRows, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, row_exp, nullptr, nullptr, stream));
   FfnArgs a{};
   a.desc = L->d_desc + c.n_experts; a.n_exp = c.n_shared; a.bits = c.shared_bits; a.group = c.group;
   a.rank = 0; a.rpad = 0; a.H = c.hidden; a.F = c.ffn; a.top_k = c.top_k; a.top_n = 0; a.T = T;
@@ -373,6 +378,8 @@ int moe_lrc_layer_create(const moe_lrc_config* cfg, moe_lrc_layer** out) {
   LRC_TRY(hipMalloc((void**)&L->d_bias, size_t(cfg->n_experts) * 4));
   if (cfg->max_tokens >= 1024 && cfg->n_experts >= 128)
     LRC_TRY(hipMalloc((void**)&L->d_logits, size_t(cfg->max_tokens) * cfg->n_experts * 8));
+  LRC_TRY(hipMalloc((void**)&L->d_perm, kPermuteScratchInts * 4));
+  LRC_TRY(hipMemset(L->d_perm, 0, kPermuteScratchInts * 4));
   LRC_TRY(hipMalloc((void**)&L->d_stat, (2 + 2 * cfg->n_experts) * 4));
   LRC_TRY(hipMemset(L->d_stat, 0, (2 + 2 * cfg->n_experts) * 4));
   LRC_TRY(hipHostMalloc((void**)&L->h_stat, (2 + 2 * cfg->n_experts) * 4, hipHostMallocDefault));
@@ -413,6 +420,7 @@ int moe_lrc_layer_destroy(moe_lrc_layer* L) {
   if (L->d_wg) (void)hipFree(L->d_wg);
   if (L->d_bias) (void)hipFree(L->d_bias);
   if (L->d_stat) (void)hipFree(L->d_stat);
+  if (L->d_perm) (void)hipFree(L->d_perm);
   if (L->d_logits) (void)hipFree(L->d_logits);
   if (L->h_stat) (void)hipHostFree(L->h_stat);
   if (L->side) (void)hipStreamDestroy(L->side);

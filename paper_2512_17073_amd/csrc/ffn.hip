@@ -60,7 +60,7 @@ __device__ inline bool find_chunk(const KArgs& a, int item, Chunk& c) {
   for (int e0 = 0; e0 < a.n_exp; e0 += 64) {
     const int e = e0 + lane;
     int r0 = 0, cnt = 0;
-    if (e < a.n_exp) { r0 = a.offsets[e]; cnt = a.offsets[e + 1] - r0; }
+    if (e < a.n_exp) { r0 = a.offsets[e]; cnt = a.row_list ? a.comp_rows[e] : a.offsets[e + 1] - r0; }
     const int n = (cnt + kBM - 1) / kBM;
     int incl = n;
 #pragma unroll
@@ -98,6 +98,18 @@ __device__ inline void stage_step(const KArgs& a, uint4* buf, int ks, int rin, i
         reinterpret_cast<const __attribute__((address_space(1))) void*>(reinterpret_cast<uintptr_t>(in_units + act_unit(k8, R, a.in_rt))),
         reinterpret_cast<__attribute__((address_space(3))) void*>(reinterpret_cast<uintptr_t>(buf + (mt * 8 + s) * 64)), 16, 0, 0);
   }
+}
+
+// The same for rows given one by one: R[mt] is this lane's input row of row tile mt.
+__device__ inline void stage_step_rows(const KArgs& a, uint4* buf, int ks, const int (&R)[kTMT], int wave, int lane) {
+  const uint4* in_units = reinterpret_cast<const uint4*>(a.in);
+  const int q = lane >> 4, s = wave;
+  const int k8 = min(ks * 32 + q * 8 + s, a.K / 8 - 1);
+#pragma unroll
+  for (int mt = 0; mt < kTMT; ++mt)
+    __builtin_amdgcn_global_load_lds(
+        reinterpret_cast<const __attribute__((address_space(1))) void*>(reinterpret_cast<uintptr_t>(in_units + act_unit(k8, R[mt], a.in_rt))),
+        reinterpret_cast<__attribute__((address_space(3))) void*>(reinterpret_cast<uintptr_t>(buf + (mt * 8 + s) * 64)), 16, 0, 0);
 }
 
 typedef float float16_t __attribute__((ext_vector_type(16)));
@@ -527,6 +539,10 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 4 ? 1 : 2) void qgemm_tile_ker
 // grid.x splits K so that the launch fills the chip.
 // xa_finish_kernel: adds the K-blocks in order, zeroes the rows without the rank-r term and the
 // padding columns, writes fp16 row-major.
+// Only the rows that take the term are computed: the chunks run over the compact rows the preparing
+// launch has made of them (CompactArgs: the front of every expert's row range), the partial sums
+// are indexed by compact row, and the finish kernel puts every routed row's sum (or zeros) in its
+// place.
 // Q3: some factor pair of the layer is held at 3 bits (layout.h); such a pair's units are fetched as
 // (codes, metadata) dwords and dequantized when their k-step comes up.
 template <bool DUAL, int NT, bool Q3>
@@ -546,7 +562,15 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void xa_tile_kernel(KArgs a) {
   const int mt_n = min(kTMT, (cnt - r + 15) >> 4);
   const int rt = a.rpad / 16, tiles = NM * rt;           // 16-column factor tiles in all
   const int pitch = NM * a.ls * 32;
-  const int rin = r0 + r;
+  // The chunk's rows are compact rows (the rows of the expert that take the rank-r term, in row
+  // order): row_list names the routed row whose activations each one reads.  A row past the
+  // expert's last compact row reads the last one's (its results are never stored).
+  int Rm[kTMT];
+#pragma unroll
+  for (int mt = 0; mt < kTMT; ++mt) {
+    const int i = r0 + min(r + 16 * mt + c, cnt - 1);
+    Rm[mt] = a.row_list ? a.row_list[i] : i;
+  }
 
   float4_t acc[kMaxT][kTMT];
 #pragma unroll
@@ -616,10 +640,10 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void xa_tile_kernel(KArgs a) {
 #pragma unroll
       for (int t = 0; t < kMaxT; ++t) wnext[s][t] = load_unit(step_lo, s, t);
   }
-  stage_step(a, xs + (step_lo & 1) * kStepUnits, step_lo, rin, wave, lane);
+  stage_step_rows(a, xs + (step_lo & 1) * kStepUnits, step_lo, Rm, wave, lane);
   asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
   for (int step = step_lo; step < steps; ++step) {
-    stage_step(a, xs + ((step + 1) & 1) * kStepUnits, step + 1, rin, wave, lane);
+    stage_step_rows(a, xs + ((step + 1) & 1) * kStepUnits, step + 1, Rm, wave, lane);
     const uint4* buf = xs + (step & 1) * kStepUnits;
     half8_t wcur[kAhead ? 8 : 1][kMaxT];
     uint32_t mcur[kMaxT];
@@ -676,17 +700,18 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void xa_tile_kernel(KArgs a) {
 // P[row][col] = fp16(sum over K-blocks of part[kb][row][col]) for rows that take the rank-r term and
 // columns below the rank rounded up to 16; zero elsewhere.  One thread per four columns.
 __global__ __launch_bounds__(256) void xa_finish_kernel(const float* __restrict__ part, int kblocks, int rows, int pitch,
-                                                        int ls32, int rpad, const int32_t* __restrict__ row_pair,
-                                                        int top_k, int top_n, _Float16* __restrict__ P) {
+                                                        int ls32, int rpad, const int32_t* __restrict__ comp_index,
+                                                        int comp_rows, _Float16* __restrict__ P) {
   const size_t i = size_t(blockIdx.x) * 256 + threadIdx.x;       // index of a group of four columns
   const int per_row = pitch / 4;
   if (i >= size_t(rows) * per_row) return;
   const int row = int(i / per_row), col = int(i - size_t(row) * per_row) * 4;
   half4_t v = half4_t{0, 0, 0, 0};
-  if ((row_pair[row] % top_k) < top_n && (col % ls32) < rpad) {
-    float4_t sum = *reinterpret_cast<const float4_t*>(part + size_t(row) * pitch + col);
+  const int ci = comp_index[row];                                // the row's place among the rows with the term (-1: none)
+  if (ci >= 0 && (col % ls32) < rpad) {
+    float4_t sum = *reinterpret_cast<const float4_t*>(part + size_t(ci) * pitch + col);
     for (int kb = 1; kb < kblocks; ++kb)
-      sum += *reinterpret_cast<const float4_t*>(part + (size_t(kb) * rows + row) * pitch + col);
+      sum += *reinterpret_cast<const float4_t*>(part + (size_t(kb) * comp_rows + ci) * pitch + col);
     v = half4_t{(_Float16)sum[0], (_Float16)sum[1], (_Float16)sum[2], (_Float16)sum[3]};
   }
   *reinterpret_cast<half4_t*>(P + size_t(row) * pitch + col) = v;
@@ -713,14 +738,18 @@ hipError_t launch_bits(const FfnArgs& f, hipStream_t s, int which) {
     const int per_kb = (steps + std::max(1, ksplit) - 1) / std::max(1, ksplit);
     const int kblocks = (steps + per_kb - 1) / per_kb;      // no K-block without a k-step
     a.p = buf;
-    a.partial = buf + (size_t(f.total_rows) * pitch / 2 + 63) / 64 * 64;
+    // the kernel's rows are the compact rows of the pairs that take the term (T * top_n in all), at
+    // the front of every expert's row range
+    KArgs ax = a;
+    ax.row_list = f.cmp_list;
+    ax.partial = buf + (size_t(f.total_rows) * pitch / 2 + 63) / 64 * 64;
+    const int xitems = f.T * f.top_n / kBM + f.n_exp;
     // (more than 32 factor tiles, i.e. ranks above 256: further groups of 32 tiles in grid.z)
-    if (per_wave <= 2) hipLaunchKernelGGL(k2, dim3(kblocks, items), dim3(64 * kTileWaves), lds, s, a);
-    else hipLaunchKernelGGL(k4, dim3(kblocks, items, (per_wave + 3) / 4), dim3(64 * kTileWaves), lds, s, a);
+    if (per_wave <= 2) hipLaunchKernelGGL(k2, dim3(kblocks, xitems), dim3(64 * kTileWaves), lds, s, ax);
+    else hipLaunchKernelGGL(k4, dim3(kblocks, xitems, (per_wave + 3) / 4), dim3(64 * kTileWaves), lds, s, ax);
     const size_t groups = size_t(f.total_rows) * pitch / 4;
-    hipLaunchKernelGGL(xa_finish_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, s, a.partial, kblocks,
-                       f.total_rows, pitch, a.ls * 32, a.rpad, f.row_pair, f.top_k, f.top_n, reinterpret_cast<_Float16*>(buf));
-    a.partial = nullptr;
+    hipLaunchKernelGGL(xa_finish_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, s, ax.partial, kblocks,
+                       f.total_rows, pitch, a.ls * 32, a.rpad, f.cmp_index, f.total_rows, reinterpret_cast<_Float16*>(buf));
   };
   if (which & 1) {
   // W1 | W3 with the SwiGLU epilogue

@@ -46,6 +46,9 @@ struct KArgs {
   const int32_t* row_exp;    // per input row: the exponent s of its power-of-two pre-scale (row_exponent below);
                              // routed launches: one per routed row; shared experts: one per token
   const int32_t* tok_exp;    // the same per token, where a kernel reads the bf16 tokens itself (or null)
+  const int32_t* row_list;   // grouped (in A) kernel: an expert's rows are the first comp_rows[e] of its range, the
+                             // compact rows of the pairs that take the rank-r term; row_list names the routed row
+                             // of each (CompactArgs); null: the rows are the routed rows
 };
 
 // Range of the fp16 operands.  The activations cross the ABI as bf16 (8 exponent bits); the matrix

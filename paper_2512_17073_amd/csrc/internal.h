@@ -37,7 +37,8 @@ struct BlobLayout {
 
 struct Workspace {       // carved out of the caller's buffer; all offsets 256-byte aligned
   size_t topk_idx, topk_w, counts, offsets, comp_counts, row_pair, pair_row;
-  size_t y_rows, xh, xh_sh, h, p13, p2, y_part, sh_y_part, sh_h, sh_y, plan, tok_exp, row_exp, row_exp_sh, total;
+  size_t y_rows, xh, xh_sh, h, p13, p2, y_part, sh_y_part, sh_h, sh_y, plan, tok_exp, row_exp, row_exp_sh;
+  size_t cmp_index, cmp_list, total;
 };
 
 }  // namespace lrc
@@ -72,6 +73,7 @@ struct moe_lrc_layer {
   std::vector<float> mat_inv_mu;       // [n_total*3] 1 / (the power-of-two factors folded into a 3-bit pair's operands)
   int n_q3 = 0;                        // projections held at 3 bits (0: the launches take the kernels without that path)
   size_t f_total = 0;                  // bytes of d_f (and of h_f)
+  int32_t* d_perm = nullptr;           // block counters of the grouping of many pairs by several blocks (kPermuteScratchInts)
   int32_t* d_stat = nullptr;           // [2 + 2E]: active, comp-active, counts, comp counts
   int32_t* h_stat = nullptr;           // pinned mirror
   hipStream_t side = nullptr;
@@ -110,6 +112,15 @@ struct PlanSpec;   // plan.h
 // kernel's indices in, the five arrays of moe_lrc_permute out
 struct PermuteArgs { const int32_t* idx; int32_t *counts, *offsets, *row_pair, *pair_row, *comp_counts; int P; };
 constexpr int kFusedPermuteMaxPairs = 1024;
+// above this many pairs several blocks group them (two launches); their counters live in the layer
+constexpr int kPermuteOneBlockPairs = 8192, kPermuteMaxBlocks = 64;
+constexpr int kPermuteScratchInts = kPermuteMaxBlocks * 2 * 256 + 64;
+// The routed rows that take the rank-r term (Section 3.2: the Top-n pairs), compacted per expert in
+// row order by the preparing launch for the grouped (in A) kernels, which then touch only those
+// rows.  Expert e's compact rows are offsets[e] .. offsets[e] + (its number of such rows) - 1, i.e.
+// the front of its own row range: list [T * k] names the routed row of each compact row, index
+// [T * k] the compact row of each routed row (-1 for a row without the term).
+struct CompactArgs { int32_t *index, *list; };
 // fp16 copy of the activations in operand order, every row times its power-of-two pre-scale
 // (ffn_common.h; exponents to row_exp, taken from tok_exp per token if given): one row per routed
 // pair (row_pair given) or one per token (row_pair null); with `stat`, one more block counts the
@@ -121,7 +132,8 @@ hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _
                             const int32_t* offsets, const int32_t* row_pair, int32_t* stat,
                             const PlanSpec* plans /* two, or null */, const FfnArgs* xa13,
                             const int32_t* tok_exp /* or null */, int32_t* row_exp,
-                            const PermuteArgs* perm /* or null: offsets and row_pair are ready */, hipStream_t s);
+                            const PermuteArgs* perm /* or null: offsets and row_pair are ready */,
+                            const CompactArgs* cmp /* or null */, hipStream_t s);
 constexpr int kMaxKBlocks = 8;    // most K-blocks the decode W2 kernel splits into
 // blocks (per K-block) of a decode launch that shares its blocks out by a table: `target` (the
 // device's CUs over the K-blocks), or enough for ceil(NT / 32) blocks per expert that can be active
@@ -159,6 +171,7 @@ struct FfnArgs {
   int q3;                     // some factor pair of the layer is held at 3 bits: the launches take the kernels that
                               // can dequantize such pairs
   const PermuteArgs* perm;    // forward with few pairs: the preparing launch groups the pairs itself (else null)
+  const int32_t *cmp_index, *cmp_list;   // CompactArgs of this call (null: none made)
   int32_t* row_exp;           // per input row (routed: per routed row; shared: per token): pre-scale exponent
   const int32_t* tok_exp;     // per token, from the routing kernel, or null
   hipEvent_t* marks;          // null, or 4 events recorded after xa13, w13, xa2, w2

@@ -90,6 +90,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict
 // contiguous bytes of each of its rows and writes runs of 256 bytes (sixteen rows of one unit).
 // The blocks after those count, one wavefront per expert, the routed rows and the rows that take
 // the rank-r term (what the router-guided transfer must bring in): stat = [-, -, rows[E], comp rows[E]].
+// (and compact the latter for the grouped (in A) kernels, CompactArgs).
 // Then one block makes the block tables of the decode launches (plan.h), and xa_tiles * E further
 // blocks compute (x A1 | x A3) for the decode flavour of the fused projection from the bf16 tokens
 // (xa_rows.h), so that no launch of its own stands between this one and the W1|W3 kernel.
@@ -105,7 +106,7 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(const uint16_t* __re
                                                    int top_n, int32_t* __restrict__ stat, PlanSpec plan0,
                                                    PlanSpec plan1, int xa_tiles, ffn::KArgs xa,
                                                    const int32_t* __restrict__ tok_exp, int32_t* __restrict__ row_exp,
-                                                   PermuteArgs perm) {
+                                                   PermuteArgs perm, CompactArgs cmp) {
   __shared__ ffn::float4_t red[2 * kPrepThreads / 64][64];
   __shared__ uint32_t row_max[16];
   if (perm.idx != nullptr) {
@@ -130,10 +131,20 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(const uint16_t* __re
     const int e = ((int)blockIdx.x - row_blocks) * kWavesPerBlock + (threadIdx.x >> 6), lane = threadIdx.x & 63;
     if (e >= E || blockIdx.y != 0) return;
     const int b = offsets[e], n = offsets[e + 1] - b;
+    // the expert's rows that take the rank-r term, counted and (for the grouped (in A) kernels,
+    // CompactArgs) compacted in row order by ballot
     int comp = 0;
-    for (int r = lane; r < n; r += 64) comp += (row_pair[b + r] % top_k) < top_n;
-#pragma unroll
-    for (int d = 32; d > 0; d >>= 1) comp += __shfl_xor(comp, d);
+    for (int r0 = 0; r0 < n; r0 += 64) {
+      const int r = r0 + lane;
+      const bool f = r < n && (row_pair[b + min(r, n - 1)] % top_k) < top_n;
+      const unsigned long long m = __ballot(f);
+      if (cmp.index != nullptr) {
+        const int at = b + comp + __popcll(m & ((1ull << lane) - 1ull));
+        if (r < n) cmp.index[b + r] = f ? at : -1;
+        if (f) cmp.list[at] = b + r;
+      }
+      comp += __popcll(m);
+    }
     if (lane == 0) { stat[2 + e] = n; stat[2 + E + e] = comp; }
     return;
   }
@@ -212,7 +223,7 @@ hipError_t launch_combine(const moe_lrc_layer* L, const void* y_rows, const floa
 hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _Float16* xg, int rt,
                             const int32_t* offsets, const int32_t* row_pair, int32_t* stat,
                             const PlanSpec* plans, const FfnArgs* xa13, const int32_t* tok_exp, int32_t* row_exp,
-                            const PermuteArgs* perm, hipStream_t s) {
+                            const PermuteArgs* perm, const CompactArgs* cmp, hipStream_t s) {
   const moe_lrc_config& c = L->cfg;
   const int rows = row_pair ? T * c.top_k : T;
   const int row_blocks = (rows + 15) / 16;
@@ -232,10 +243,12 @@ hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _
     xa_tiles = 4 * xa.ls;
   }
   const int stat_blocks = stat ? (c.n_experts + kPrepThreads / 64 - 1) / (kPrepThreads / 64) : 0;
+  const int cmp_block = (cmp && row_pair && stat) ? 1 : 0;     // (the compaction rides the per-expert counting)
   hipLaunchKernelGGL(prep_kernel, dim3(row_blocks + stat_blocks + plan_block + xa_tiles * c.n_experts, ky),
                      dim3(kPrepThreads), 0, s, (const uint16_t*)x_bf16, rows, c.hidden, reinterpret_cast<uint4*>(xg), rt, offsets,
                      row_pair, c.n_experts, c.top_k, c.top_n, stat, p0, p1, xa_tiles, xa, tok_exp, row_exp,
-                     perm ? *perm : PermuteArgs{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0});
+                     perm ? *perm : PermuteArgs{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0},
+                     cmp_block ? *cmp : CompactArgs{nullptr, nullptr});
   return hipGetLastError();
 }
 

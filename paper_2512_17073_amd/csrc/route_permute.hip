@@ -232,6 +232,114 @@ __global__ __launch_bounds__(1024) void permute_kernel(const int32_t* __restrict
   permute_body(lds, idx, P, E, top_k, top_n, counts, offsets, row_pair, pair_row, comp_counts);
 }
 
+
+// Many pairs: the same grouping by several blocks, in two launches.  Block b owns the pairs
+// [b * slice, (b + 1) * slice).  The first launch counts every block's pairs per expert into
+// `scratch` ([block][2][E]: all pairs, pairs that take the rank-r term); the block that finishes last
+// adds them up (counts, offsets, comp_counts) and replaces every block's counts by the position of
+// its first pair of each expert.  The second launch scatters: inside a block as in permute_body
+// (wavefront w owns a contiguous run, equal experts of a 64-pair step are ranked by ballots), so
+// the order of the pairs (= token order) is kept.  The last entry of scratch counts the finished blocks
+// (left at zero).
+__global__ __launch_bounds__(1024) void permute_count_kernel(const int32_t* __restrict__ idx, int P, int E, int top_k, int top_n,
+                                                             int slice, int32_t* scratch, int32_t* __restrict__ counts,
+                                                             int32_t* __restrict__ offsets, int32_t* __restrict__ comp_counts) {
+  __shared__ int32_t hist[kMaxExperts], comp[kMaxExperts], total[kMaxExperts];
+  __shared__ int last;
+  const int b = blockIdx.x, nb = gridDim.x;
+  for (int e = threadIdx.x; e < E; e += 1024) { hist[e] = 0; comp[e] = 0; }
+  __syncthreads();
+  const int begin = b * slice, end = min(P, begin + slice);
+  for (int i = begin + (int)threadIdx.x; i < end; i += 1024) {
+    const int e = min(max(idx[i], 0), E - 1);
+    atomicAdd(&hist[e], 1);
+    if (i % top_k < top_n) atomicAdd(&comp[e], 1);
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < E; e += 1024) {
+    scratch[(b * 2 + 0) * E + e] = hist[e];
+    scratch[(b * 2 + 1) * E + e] = comp[e];
+  }
+  __threadfence();
+  __syncthreads();
+  if (threadIdx.x == 0) last = atomicAdd(&scratch[kPermuteMaxBlocks * 2 * kMaxExperts], 1) == nb - 1;
+  __syncthreads();
+  if (!last) return;
+  __threadfence();
+  if ((int)threadIdx.x < E) {
+    const int e = threadIdx.x;
+    int run = 0, crun = 0;
+    for (int bb = 0; bb < nb; ++bb) {
+      run += __hip_atomic_load(&scratch[(bb * 2 + 0) * E + e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      crun += __hip_atomic_load(&scratch[(bb * 2 + 1) * E + e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    total[e] = run;
+    counts[e] = run;
+    comp_counts[e] = crun;
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < E) {
+    const int e = threadIdx.x;
+    int off = 0;
+    for (int e2 = 0; e2 < e; ++e2) off += total[e2];
+    offsets[e] = off;
+    if (e == E - 1) offsets[E] = off + total[e];
+    for (int bb = 0; bb < nb; ++bb) {
+      const int c = __hip_atomic_load(&scratch[(bb * 2 + 0) * E + e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      scratch[(bb * 2 + 0) * E + e] = off;
+      off += c;
+    }
+  }
+  if (threadIdx.x == 0) scratch[kPermuteMaxBlocks * 2 * kMaxExperts] = 0;
+}
+
+__global__ __launch_bounds__(1024) void permute_scatter_kernel(const int32_t* __restrict__ idx, int P, int E, int slice,
+                                                               const int32_t* __restrict__ scratch,
+                                                               int32_t* __restrict__ row_pair, int32_t* __restrict__ pair_row) {
+  __shared__ int32_t hist[kPermWaves][kMaxExperts];
+  const int b = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int i = threadIdx.x; i < kPermWaves * kMaxExperts; i += 1024) (&hist[0][0])[i] = 0;
+  __syncthreads();
+  const int s_begin = b * slice, s_end = min(P, s_begin + slice);
+  const int per_wave = ((s_end - s_begin + kPermWaves - 1) / kPermWaves + 63) / 64 * 64;
+  const int begin = s_begin + wave * per_wave, end = min(s_end, begin + per_wave);
+  for (int i = begin + lane; i < end; i += 64) atomicAdd(&hist[wave][min(max(idx[i], 0), E - 1)], 1);
+  __syncthreads();
+  if ((int)threadIdx.x < E) {
+    int run = scratch[(b * 2 + 0) * E + threadIdx.x];       // position of this block's first pair of the expert
+    for (int wv = 0; wv < kPermWaves; ++wv) {
+      const int c = hist[wv][threadIdx.x];
+      hist[wv][threadIdx.x] = run;
+      run += c;
+    }
+  }
+  __syncthreads();
+  int nbits = 0;
+  while ((1 << nbits) < E) ++nbits;
+  for (int base = begin; base < end; base += 64) {
+    const int i = base + lane;
+    const bool valid = i < end;
+    const int e = valid ? min(max(idx[i], 0), E - 1) : 0;
+    unsigned long long same = __ballot(valid);
+    for (int bt = 0; bt < nbits; ++bt) {
+      const bool bit = (e >> bt) & 1;
+      const unsigned long long bb = __ballot(valid && bit);
+      same &= bit ? bb : ~bb;
+    }
+    const int rank = __popcll(same & ((1ull << lane) - 1ull));
+    const int cnt = __popcll(same);
+    int pos = 0;
+    if (valid) pos = hist[wave][e] + rank;
+    __builtin_amdgcn_wave_barrier();
+    if (valid && rank == 0) hist[wave][e] = pos + cnt;
+    __builtin_amdgcn_wave_barrier();
+    if (valid) {
+      row_pair[pos] = i;
+      pair_row[i] = pos;
+    }
+  }
+}
+
 }  // namespace
 
 bool route_writes_exponents(const moe_lrc_layer* L, int T) {
@@ -275,7 +383,18 @@ hipError_t launch_permute(const moe_lrc_layer* L, const int32_t* idx, int T, int
                           int32_t* offsets, int32_t* row_pair, int32_t* pair_row,
                           int32_t* comp_counts, hipStream_t s) {
   const moe_lrc_config& c = L->cfg;
-  hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(1024), 0, s, idx, T * c.top_k, c.n_experts,
+  const int P = T * c.top_k;
+  if (P > kPermuteOneBlockPairs && L->d_perm != nullptr) {
+    // several blocks (at most kPermuteMaxBlocks), each with a slice of at least 2048 pairs
+    const int slice = std::max(2048, ((P + kPermuteMaxBlocks - 1) / kPermuteMaxBlocks + 63) / 64 * 64);
+    const int nb = (P + slice - 1) / slice;
+    hipLaunchKernelGGL(permute_count_kernel, dim3(nb), dim3(1024), 0, s, idx, P, c.n_experts, c.top_k, c.top_n, slice,
+                       L->d_perm, counts, offsets, comp_counts);
+    hipLaunchKernelGGL(permute_scatter_kernel, dim3(nb), dim3(1024), 0, s, idx, P, c.n_experts, slice, L->d_perm, row_pair,
+                       pair_row);
+    return hipGetLastError();
+  }
+  hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(1024), 0, s, idx, P, c.n_experts,
                      c.top_k, c.top_n, counts, offsets, row_pair, pair_row, comp_counts);
   return hipGetLastError();
 }

@@ -103,6 +103,29 @@ def test_permute_bit_exact(case):
     np.testing.assert_array_equal(_to_np(comp), p["comp_counts"])
 
 
+@pytest.mark.parametrize("experts,top_k,top_n,tokens", [(8, 2, 1, 4097), (8, 2, 1, 20000), (128, 8, 2, 1025), (128, 8, 3, 7777),
+                                                         (61, 6, 2, 3000)])
+def test_permute_by_several_blocks(amd, experts, top_k, top_n, tokens):
+    """Above 8192 pairs the grouping runs as two launches of several blocks: bit-exact against the
+    oracle for ragged sizes, skewed expert loads and experts without rows, twice in a row (the block
+    counter is left at zero), then once more with a smaller batch (another number of blocks)."""
+    import torch
+    cfg = configs.TINY.with_(n_experts=experts, top_k=top_k, top_n=top_n, tokens=tokens, rank=0, name="perm_blocks")
+    L = amd.Layer.from_config(cfg, max_tokens=tokens)
+    rng = np.random.default_rng(experts * 1000 + tokens)
+    for T in (tokens, tokens, max(8192 // top_k + 1, tokens // 2)):
+        # distinct experts per token, skewed towards a few; expert 1 never chosen
+        pw = rng.random(experts) ** 4
+        pw[1 % experts] = 0.0
+        pw /= pw.sum()
+        idx = np.stack([rng.choice(experts, size=top_k, replace=False, p=pw) for _ in range(T)]).astype(np.int32)
+        p = orc.permute(idx, experts, top_n)
+        got = L.permute(torch.from_numpy(idx).cuda())
+        for g, key in zip(got, ("counts", "offsets", "row_pair", "pair_row", "comp_counts")):
+            np.testing.assert_array_equal(_to_np(g), p[key], err_msg=f"T={T} {key}")
+    L.close()
+
+
 def test_expert_ffn_and_combine(case):
     cfg, layer, L, x_bits, x, ref = case
     idx, w = L.route(x)
