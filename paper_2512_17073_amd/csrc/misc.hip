@@ -175,18 +175,22 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(const uint16_t* __re
   if (blockIdx.y == 0 && (threadIdx.x >> 4) == 0) row_exp[R] = se;
   const float sc = ffn::pow2i(se);
   // (grid.y splits the columns when there are few rows, so that the launch still fills the chip)
-  for (int k8 = blockIdx.y * kColLanes + (threadIdx.x >> 4); k8 < H / 8; k8 += kColLanes * gridDim.y) {
-    const uint4 v = xrow[k8];
-    const uint32_t in[4] = {v.x, v.y, v.z, v.w};
-    uint32_t o[4];
+  // (two adjacent units per thread: a wavefront reads 128 contiguous bytes of each of its rows; H / 8 is even)
+  for (int k8p = 2 * (blockIdx.y * kColLanes + (threadIdx.x >> 4)); k8p < H / 8; k8p += 2 * kColLanes * gridDim.y) {
+    const uint4 vv[2] = {xrow[k8p], xrow[k8p + 1]};
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const _Float16 lo = (_Float16)(bf16_lo(in[i]) * sc);
-      const _Float16 hi = (_Float16)(bf16_hi(in[i]) * sc);
-      o[i] = uint32_t(__builtin_bit_cast(uint16_t, lo)) | (uint32_t(__builtin_bit_cast(uint16_t, hi)) << 16);
+    for (int u = 0; u < 2; ++u) {
+      const uint32_t in[4] = {vv[u].x, vv[u].y, vv[u].z, vv[u].w};
+      uint32_t o[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const _Float16 lo = (_Float16)(bf16_lo(in[i]) * sc);
+        const _Float16 hi = (_Float16)(bf16_hi(in[i]) * sc);
+        o[i] = uint32_t(__builtin_bit_cast(uint16_t, lo)) | (uint32_t(__builtin_bit_cast(uint16_t, hi)) << 16);
+      }
+      const int k8 = k8p + u, ks = k8 >> 5, q = (k8 >> 3) & 3, s = k8 & 7;
+      xg[size_t((ks * 8 + s) * 4 + q) * rt + R] = make_uint4(o[0], o[1], o[2], o[3]);
     }
-    const int ks = k8 >> 5, q = (k8 >> 3) & 3, s = k8 & 7;
-    xg[size_t((ks * 8 + s) * 4 + q) * rt + R] = make_uint4(o[0], o[1], o[2], o[3]);
   }
 }
 
@@ -227,7 +231,8 @@ hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _
   const moe_lrc_config& c = L->cfg;
   const int rows = row_pair ? T * c.top_k : T;
   const int row_blocks = (rows + 15) / 16;
-  const int ky = std::max(1, std::min(c.hidden / (8 * (kPrepThreads / 16)), L->n_cu / std::max(1, row_blocks)));
+  // (a block pass covers 16 * kPrepThreads / 16 columns: two 8-column units per thread)
+  const int ky = std::max(1, std::min(c.hidden / (16 * (kPrepThreads / 16)), L->n_cu / std::max(1, row_blocks)));
   const PlanSpec none{0, 0, 0, nullptr};
   const PlanSpec p0 = plans ? plans[0] : none, p1 = plans ? plans[1] : none;
   const int plan_block = p0.B + p1.B > 0 ? 1 : 0;
