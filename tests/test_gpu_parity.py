@@ -419,6 +419,35 @@ def test_int3_factors(amd, tokens, rank):
     Lr.close(); Ls.close()
 
 
+@pytest.mark.parametrize("tokens", [16, 300, 700])
+def test_int3_factors_with_a_rank_per_projection(amd, tokens):
+    """Factor pairs at 3 bits whose ranks differ from matrix to matrix (Section 3.1 steps 1 and 2
+    together): W1 and W3 of an expert run different numbers of rank steps, some projections have no
+    pair at all, and the factor tiles past a projection's own rank are never read.  All three
+    flavour mixes (16, 300, 700 tokens), resident against staged bit for bit."""
+    import torch
+    cfg = configs.TINY.with_(rank=64, tokens=tokens, bits=2, name=f"int3_ranks_T{tokens}")
+    ranks = fixtures.kurtosis_ranks(cfg, 26, (0, 16, 32, 64))
+    assert len(set(ranks.ravel().tolist())) >= 3 and (ranks[:, 0] != ranks[:, 1]).any()
+    layer = fixtures.build_layer(cfg, ranks=ranks, int3_factors=True)
+    x_bits = synth.make_tokens(cfg)
+    x = amd.bf16_tensor(x_bits)
+    ref = fixtures.oracle_forward(cfg, layer, x_bits)
+    Lr = amd.Layer.from_config(cfg)
+    Ls = amd.Layer.from_config(cfg, residency=amd.STAGED)
+    Lr.load(layer); Ls.load(layer)
+    out_r = Lr.forward(x).clone()
+    torch.cuda.synchronize()
+    out_s = Ls.forward(x).clone()
+    torch.cuda.synchronize()
+    err = orc.rel_frobenius(_to_np(out_r), ref["out"])
+    print(f"\n[{cfg.name}] ranks {ranks.tolist()} out rel err {err:.2e}", flush=True)
+    assert err <= TOL
+    assert torch.equal(out_r.view(torch.int16), out_s.view(torch.int16))
+    assert orc.rel_frobenius(_to_np(out_r), fixtures.oracle_forward(cfg.with_(top_n=0), layer, x_bits)["out"]) > 3 * TOL
+    Lr.close(); Ls.close()
+
+
 def test_mixed_fp16_and_int3_projections_staged(amd):
     """One expert may hold one projection's factors as an fp16 pair and the others at 3 bits: each
     pair lives in its own projection's factor sections, so neither upload disturbs the other, and
