@@ -220,7 +220,7 @@ static int stage_selected(moe_lrc_layer* L, hipStream_t stream) {
 static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t* offsets,
                           const int32_t* row_pair, void* y_rows, uint8_t* ws, hipStream_t stream,
                           bool mark = false, bool keep_partials = false, int* kblocks_out = nullptr,
-                          const int32_t* tok_exp = nullptr, const PermuteArgs* perm = nullptr) {
+                          const int32_t* tok_exp = nullptr, const PermuteArgs* perm = nullptr, const RouteArgs* route = nullptr) {
   const moe_lrc_config& c = L->cfg;
   const Workspace w = plan_workspace(L, T);
   _Float16* xh = reinterpret_cast<_Float16*>(ws + w.xh);
@@ -258,7 +258,7 @@ static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t*
   const CompactArgs cmp{reinterpret_cast<int32_t*>(ws + w.cmp_index), reinterpret_cast<int32_t*>(ws + w.cmp_list)};
   if (comp) { a.cmp_index = cmp.index; a.cmp_list = cmp.list; }
   LRC_HIP(launch_convert_x(L, x, T, xh, P + kActPadRows, offsets, row_pair, L->d_stat, plans,
-                           ((path & 1) || a.xa13_here) ? nullptr : &a, tok_exp, a.row_exp, perm, comp ? &cmp : nullptr, stream));
+                           ((path & 1) || a.xa13_here) ? nullptr : &a, tok_exp, a.row_exp, perm, comp ? &cmp : nullptr, route, stream));
   L->stats_valid = false;
   L->stats.stage_ms = 0.f;
   if (c.residency == MOE_LRC_STAGED) {
@@ -280,7 +280,7 @@ static int run_shared(moe_lrc_layer* L, const void* x, int T, uint8_t* ws, hipSt
   const Workspace w = plan_workspace(L, T);
   _Float16* xh = reinterpret_cast<_Float16*>(ws + w.xh_sh);
   int32_t* row_exp = reinterpret_cast<int32_t*>(ws + w.row_exp_sh);
-  LRC_HIP(launch_convert_x(L, x, T, xh, T + kActPadRows, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, row_exp, nullptr, nullptr, stream));
+  LRC_HIP(launch_convert_x(L, x, T, xh, T + kActPadRows, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, row_exp, nullptr, nullptr, nullptr, stream));
   FfnArgs a{};
   a.desc = L->d_desc + c.n_experts; a.n_exp = c.n_shared; a.bits = c.shared_bits; a.group = c.group;
   a.rank = 0; a.rpad = 0; a.H = c.hidden; a.F = c.ffn; a.top_k = c.top_k; a.top_n = 0; a.T = T;
@@ -660,13 +660,16 @@ int forward_impl(moe_lrc_layer* L, const void* x, int T, void* out, void* ws, hi
   L->profile_valid = false;
   if (mk) LRC_HIP(hipEventRecord(L->marks[MOE_LRC_STAGE_ROUTE], s));
   int32_t* tok_exp = route_writes_exponents(L, T) ? (int32_t*)(b + w.tok_exp) : nullptr;
-  LRC_HIP(launch_route(L, x, T, idx, tw, nullptr, tok_exp, s));
-  if (mk) LRC_HIP(hipEventRecord(L->marks[MOE_LRC_STAGE_PERMUTE], s));
   // few pairs: every block of the preparing launch groups the pairs itself (one launch fewer)
   const PermuteArgs perm{idx, (int32_t*)(b + w.counts), offsets, row_pair, pair_row, (int32_t*)(b + w.comp_counts), T * L->cfg.top_k};
   // (every block repeats the grouping, so only where the preparing launch is one round of blocks
   // and the tables are small: few experts)
   const bool fused_permute = perm.P <= kFusedPermuteMaxPairs && L->cfg.n_experts <= 32;
+  // a token or two: the blocks of the preparing launch route them as well (another launch fewer)
+  const bool fused_route = fused_permute && T * L->cfg.n_experts <= kFusedRoutePairs && tok_exp != nullptr;
+  const RouteArgs route{L->d_wg, L->has_bias ? L->d_bias : nullptr, idx, tw, tok_exp, L->cfg.renormalize};
+  if (!fused_route) LRC_HIP(launch_route(L, x, T, idx, tw, nullptr, tok_exp, s));
+  if (mk) LRC_HIP(hipEventRecord(L->marks[MOE_LRC_STAGE_PERMUTE], s));
   if (!fused_permute)
     LRC_HIP(launch_permute(L, idx, T, (int32_t*)(b + w.counts), offsets, row_pair, pair_row,
                            (int32_t*)(b + w.comp_counts), s));
@@ -686,7 +689,7 @@ int forward_impl(moe_lrc_layer* L, const void* x, int T, void* out, void* ws, hi
   // adds them into bf16 rows first)
   int kblocks = 1;
   if ((rc = run_expert_ffn(L, x, T, offsets, row_pair, b + w.y_rows, b, s, mk, true, &kblocks, tok_exp,
-                           fused_permute ? &perm : nullptr))) return rc;
+                           fused_permute ? &perm : nullptr, fused_route ? &route : nullptr))) return rc;
   if (fork) LRC_HIP(hipStreamWaitEvent(s, L->ev_join, 0));
   else if (L->cfg.n_shared > 0 && (rc = run_shared(L, x, T, b, s))) return rc;
   if (mk) LRC_HIP(hipEventRecord(L->marks[MOE_LRC_STAGE_COMBINE], s));

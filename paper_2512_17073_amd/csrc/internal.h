@@ -112,6 +112,10 @@ struct PlanSpec;   // plan.h
 // kernel's indices in, the five arrays of moe_lrc_permute out
 struct PermuteArgs { const int32_t* idx; int32_t *counts, *offsets, *row_pair, *pair_row, *comp_counts; int P; };
 constexpr int kFusedPermuteMaxPairs = 1024;
+// the routing of a token or two run inside the preparing launch as well (forward only): gate
+// [E][H] bf16 and bias (or null) in, the outputs of moe_lrc_route and the tokens' pre-scale exponents out
+struct RouteArgs { const uint16_t* wg; const float* bias; int32_t* idx; float* w; int32_t* tok_exp; int renorm; };
+constexpr int kFusedRoutePairs = 16;      // (token, expert) gate products: one per wavefront of a block
 // above this many pairs several blocks group them (two launches); their counters live in the layer
 constexpr int kPermuteOneBlockPairs = 8192, kPermuteMaxBlocks = 64;
 constexpr int kPermuteScratchInts = kPermuteMaxBlocks * 2 * 256 + 64;
@@ -133,7 +137,8 @@ hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _
                             const PlanSpec* plans /* two, or null */, const FfnArgs* xa13,
                             const int32_t* tok_exp /* or null */, int32_t* row_exp,
                             const PermuteArgs* perm /* or null: offsets and row_pair are ready */,
-                            const CompactArgs* cmp /* or null */, hipStream_t s);
+                            const CompactArgs* cmp /* or null */, const RouteArgs* route /* or null: perm->idx is ready */,
+                            hipStream_t s);
 constexpr int kMaxKBlocks = 8;    // most K-blocks the decode W2 kernel splits into
 // blocks (per K-block) of a decode launch that shares its blocks out by a table: `target` (the
 // device's CUs over the K-blocks), or enough for ceil(NT / 32) blocks per expert that can be active

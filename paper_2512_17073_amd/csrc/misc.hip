@@ -5,6 +5,7 @@
 #include "internal.h"
 #include "permute_body.h"
 #include "plan.h"
+#include "route_body.h"
 #include "unpack.h"
 #include "xa_rows.h"
 
@@ -95,6 +96,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict
 // blocks compute (x A1 | x A3) for the decode flavour of the fused projection from the bf16 tokens
 // (xa_rows.h), so that no launch of its own stands between this one and the W1|W3 kernel.
 constexpr int kPrepThreads = 1024;
+// With a token or two every block first routes them itself (route.wg != null).
 // With few pairs, every block first groups the pairs by expert itself (perm.idx != null: the body of
 // the permute kernel, writing the same values from every block) instead of a launch of its own
 // doing it beforehand; offsets and row_pair are then this block's own writes, read back after a
@@ -105,10 +107,16 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(const uint16_t* __re
                                                    const int32_t* row_pair, int E, int top_k,
                                                    int top_n, int32_t* __restrict__ stat, PlanSpec plan0,
                                                    PlanSpec plan1, int xa_tiles, ffn::KArgs xa,
-                                                   const int32_t* __restrict__ tok_exp, int32_t* __restrict__ row_exp,
-                                                   PermuteArgs perm, CompactArgs cmp) {
+                                                   const int32_t* tok_exp, int32_t* __restrict__ row_exp,
+                                                   PermuteArgs perm, CompactArgs cmp, RouteArgs route) {
   __shared__ ffn::float4_t red[2 * kPrepThreads / 64][64];
   __shared__ uint32_t row_max[16];
+  if (route.wg != nullptr) {
+    // a token or two: every block routes them itself (route_body.h) instead of a launch of its
+    // own doing it beforehand; perm.idx and tok_exp are then this block's own writes
+    route_small_body(reinterpret_cast<double*>(&red[0][0]), x, route, perm.P / top_k, H, E, top_k);
+    __syncthreads();
+  }
   if (perm.idx != nullptr) {
     PermuteLds& pl = *reinterpret_cast<PermuteLds*>(&red[0][0]);     // (the reduction buffer is not in use yet)
     static_assert(sizeof(PermuteLds) <= sizeof(red), "the permutation tables must fit the reduction buffer");
@@ -227,7 +235,7 @@ hipError_t launch_combine(const moe_lrc_layer* L, const void* y_rows, const floa
 hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _Float16* xg, int rt,
                             const int32_t* offsets, const int32_t* row_pair, int32_t* stat,
                             const PlanSpec* plans, const FfnArgs* xa13, const int32_t* tok_exp, int32_t* row_exp,
-                            const PermuteArgs* perm, const CompactArgs* cmp, hipStream_t s) {
+                            const PermuteArgs* perm, const CompactArgs* cmp, const RouteArgs* route, hipStream_t s) {
   const moe_lrc_config& c = L->cfg;
   const int rows = row_pair ? T * c.top_k : T;
   const int row_blocks = (rows + 15) / 16;
@@ -253,7 +261,8 @@ hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _
                      dim3(kPrepThreads), 0, s, (const uint16_t*)x_bf16, rows, c.hidden, reinterpret_cast<uint4*>(xg), rt, offsets,
                      row_pair, c.n_experts, c.top_k, c.top_n, stat, p0, p1, xa_tiles, xa, tok_exp, row_exp,
                      perm ? *perm : PermuteArgs{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0},
-                     cmp_block ? *cmp : CompactArgs{nullptr, nullptr});
+                     cmp_block ? *cmp : CompactArgs{nullptr, nullptr},
+                     (route && perm) ? *route : RouteArgs{nullptr, nullptr, nullptr, nullptr, nullptr, 0});
   return hipGetLastError();
 }
 

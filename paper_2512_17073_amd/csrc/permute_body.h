@@ -20,7 +20,8 @@ struct PermuteLds {
 // each 64-pair step with ballots; per-(wavefront, expert) counters in LDS carry the positions.
 // Ends with every result written (by this block) but not yet fenced: callers that read them back
 // follow with __syncthreads().
-__device__ inline void permute_body(PermuteLds& L, const int32_t* __restrict__ idx, int P, int E, int top_k, int top_n,
+// (idx carries no __restrict__: the caller may have written it itself just before)
+__device__ inline void permute_body(PermuteLds& L, const int32_t* idx, int P, int E, int top_k, int top_n,
                                     int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
                                     int32_t* __restrict__ row_pair, int32_t* __restrict__ pair_row,
                                     int32_t* __restrict__ comp_counts) {

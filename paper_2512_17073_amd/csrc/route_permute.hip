@@ -2,63 +2,11 @@
 // and the grouping of (token, slot) pairs by expert.
 #include "internal.h"
 #include "permute_body.h"
+#include "route_body.h"
 
 namespace lrc {
 
 namespace {
-
-__device__ inline double bf16_to_double(uint32_t bits16) {
-  return (double)__uint_as_float(bits16 << 16);
-}
-
-__device__ inline double wave_sum(double v) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
-  return v;
-}
-
-// Top-k of one token's logits by a shuffle arg-max (value descending, ties to the lower index), and
-// the softmax weights of the selected experts (Section 2.1), by one wavefront: lane holds the
-// logits of experts lane, lane + 64, lane + 128, lane + 192.
-__device__ inline void select_topk(const double (&v)[4], int lane, int E, int top_k, int renorm,
-                                   int32_t* __restrict__ idx_t, float* __restrict__ w_t) {
-  uint32_t taken = 0;
-#pragma unroll
-  for (int m = 0; m < 4; ++m)
-    if (lane + 64 * m >= E) taken |= 1u << m;
-  double vmax = 0.0, den = 0.0, sel_sum = 0.0, my_w = 0.0;
-  int my_idx = 0;
-  for (int j = 0; j < top_k; ++j) {
-    double bv = 0.0;
-    int bi = 0x7fffffff;
-#pragma unroll
-    for (int m = 0; m < 4; ++m)
-      if (!(taken & (1u << m)) && (bi == 0x7fffffff || v[m] > bv)) { bv = v[m]; bi = lane + 64 * m; }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-      const double ov = __shfl_xor(bv, off);
-      const int oi = __shfl_xor(bi, off);
-      const bool take = oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi));
-      if (take) { bv = ov; bi = oi; }
-    }
-    if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
-    if (j == 0) {
-      vmax = bv;
-      double part = 0.0;
-#pragma unroll
-      for (int m = 0; m < 4; ++m)
-        if (lane + 64 * m < E) part += exp(v[m] - vmax);
-      den = wave_sum(part);
-    }
-    const double score = exp(bv - vmax) / den;
-    sel_sum += score;
-    if (lane == j) { my_w = score; my_idx = bi; }
-  }
-  if (lane < top_k) {
-    idx_t[lane] = my_idx;
-    w_t[lane] = (float)(renorm ? my_w / sel_sum : my_w);
-  }
-}
 
 // One workgroup (NW wavefronts: 4, or 16 when there are many experts) per token.  Wavefront w
 // accumulates, in fp64, the gate dot products of experts w, w+NW, ...: every bf16 x bf16 product is exact in fp64, so the logits differ from the
