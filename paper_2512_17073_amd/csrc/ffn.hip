@@ -82,31 +82,17 @@ __device__ inline bool find_chunk(const KArgs& a, int item, Chunk& c) {
   return false;
 }
 
-// Copy of the activations of k-step ks for the 128 rows from input row `rin` on into `buf`, as 64
-// fragments (row tile mt, sub-step s) of 64 units: wavefront w copies the eight fragments with
-// s = w, each lane its own 16 bytes from global memory straight to LDS.  Always eight copies per
-// wavefront (the waits count on that): a row or column past the end is clamped to a valid unit
-// (such rows are never stored; the padded weights of such columns are exact zeros).
-__device__ inline void stage_step(const KArgs& a, uint4* buf, int ks, int rin, int wave, int lane) {
-  const uint4* in_units = reinterpret_cast<const uint4*>(a.in);
-  const int q = lane >> 4, rowl = lane & 15, s = wave;
-  const int k8 = min(ks * 32 + q * 8 + s, a.K / 8 - 1);
-#pragma unroll
-  for (int mt = 0; mt < kTMT; ++mt) {
-    const int R = min(rin + 16 * mt + rowl, a.in_rt - 1);
-    __builtin_amdgcn_global_load_lds(
-        reinterpret_cast<const __attribute__((address_space(1))) void*>(reinterpret_cast<uintptr_t>(in_units + act_unit(k8, R, a.in_rt))),
-        reinterpret_cast<__attribute__((address_space(3))) void*>(reinterpret_cast<uintptr_t>(buf + (mt * 8 + s) * 64)), 16, 0, 0);
-  }
-}
-
-// The same for rows given one by one: R[mt] is this lane's input row of row tile mt.
-__device__ inline void stage_step_rows(const KArgs& a, uint4* buf, int ks, const int (&R)[kTMT], int wave, int lane) {
+// Copy of the activations of k-step ks for the 128 rows of a chunk into `buf`, as 64 fragments (row
+// tile mt, sub-step s) of 64 units: wavefront w copies the fragments with s = w, each lane its own 16
+// bytes from global memory straight to LDS; R[mt] is this lane's input row of row tile mt.  A column
+// past the end is clamped to a valid unit (the padded weights of such columns are exact zeros).
+__device__ inline void stage_step_rows(const KArgs& a, uint4* buf, int ks, const int (&R)[kTMT], int mt_n, int wave, int lane) {
   const uint4* in_units = reinterpret_cast<const uint4*>(a.in);
   const int q = lane >> 4, s = wave;
   const int k8 = min(ks * 32 + q * 8 + s, a.K / 8 - 1);
 #pragma unroll
   for (int mt = 0; mt < kTMT; ++mt)
+    if (mt < mt_n)        // (row tiles past the chunk's last row are not read)
     __builtin_amdgcn_global_load_lds(
         reinterpret_cast<const __attribute__((address_space(1))) void*>(reinterpret_cast<uintptr_t>(in_units + act_unit(k8, R[mt], a.in_rt))),
         reinterpret_cast<__attribute__((address_space(3))) void*>(reinterpret_cast<uintptr_t>(buf + (mt * 8 + s) * 64)), 16, 0, 0);
@@ -127,8 +113,9 @@ template <int N, class Fn> __device__ inline void static_for(Fn&& fn) { static_f
 // group q = p + 2 (l / 32) of sub-step s.  (After the row swap, operand p of a sub-step holds in
 // lanes 0..31 the weights of lane group q = p and in lanes 32..63 those of q = p + 2.)  Wavefront w
 // of the block's WAVES copies the fragments of sub-steps s = w, w + WAVES, ...
+// Only the first rp_n row pairs are copied (the others hold no rows of the expert and are not read).
 template <int WAVES>
-__device__ inline void stage_step32(const KArgs& a, uint4* buf, int ks, int rin, int wave, int lane) {
+__device__ inline void stage_step32(const KArgs& a, uint4* buf, int ks, int rin, int rp_n, int wave, int lane) {
   const uint4* in_units = reinterpret_cast<const uint4*>(a.in);
   const int n = lane & 31, h = lane >> 5;
 #pragma unroll
@@ -139,6 +126,7 @@ __device__ inline void stage_step32(const KArgs& a, uint4* buf, int ks, int rin,
       const int k8 = min(ks * 32 + (p + 2 * h) * 8 + s, a.K / 8 - 1);
 #pragma unroll
       for (int rp = 0; rp < kRP; ++rp) {
+        if (rp >= rp_n) continue;
         const int R = min(rin + 32 * rp + n, a.in_rt - 1);
         __builtin_amdgcn_global_load_lds(
             reinterpret_cast<const __attribute__((address_space(1))) void*>(reinterpret_cast<uintptr_t>(in_units + act_unit(k8, R, a.in_rt))),
@@ -337,7 +325,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 4 ? 1 : 2) void qgemm_tile_ker
 
   // ---- prologue: the first k-step of activations and the first two ring slots
   Slot2<BITS, NM, kNTW> ring[2];
-  stage_step32<WAVES>(a, xs, 0, rin, wave, lane);
+  stage_step32<WAVES>(a, xs, 0, rin, rp_n, wave, lane);
   __builtin_amdgcn_sched_barrier(0);
   fetch(0, ring[0]);
   fetch(1, ring[1]);
@@ -357,7 +345,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 4 ? 1 : 2) void qgemm_tile_ker
       for (int i = 0; i < 2; ++i) {
         const int step = s0 + i;
         if (step < steps) {
-          stage_step32<WAVES>(a, xs + ((step + 1) & 1) * kStepUnits, step + 1, rin, wave, lane);
+          stage_step32<WAVES>(a, xs + ((step + 1) & 1) * kStepUnits, step + 1, rin, decltype(RPN_)::value, wave, lane);
           __builtin_amdgcn_sched_barrier(0);     // (the wait below counts the refill as the only later loads)
           compute(RPN_, ring[i], xs + (step & 1) * kStepUnits);
           fetch(step + 2, ring[i]);
@@ -640,10 +628,10 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void xa_tile_kernel(KArgs a) {
 #pragma unroll
       for (int t = 0; t < kMaxT; ++t) wnext[s][t] = load_unit(step_lo, s, t);
   }
-  stage_step_rows(a, xs + (step_lo & 1) * kStepUnits, step_lo, Rm, wave, lane);
+  stage_step_rows(a, xs + (step_lo & 1) * kStepUnits, step_lo, Rm, mt_n, wave, lane);
   asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
   for (int step = step_lo; step < steps; ++step) {
-    stage_step_rows(a, xs + ((step + 1) & 1) * kStepUnits, step + 1, Rm, wave, lane);
+    stage_step_rows(a, xs + ((step + 1) & 1) * kStepUnits, step + 1, Rm, mt_n, wave, lane);
     const uint4* buf = xs + (step & 1) * kStepUnits;
     half8_t wcur[kAhead ? 8 : 1][kMaxT];
     uint32_t mcur[kMaxT];
