@@ -186,6 +186,10 @@ def test_deepseek_shape(amd):
     cfg = configs.DEEPSEEK
     layer, L = _make(amd, cfg, max_tokens=cfg.tokens)
     _check(amd, cfg, layer, L, sample_mats=((0, 0), (63, 2), (64, 1), (65, 2)))
+    # the routed experts' factor pairs at 3 bits, beside shared experts that have none
+    layer_q = _factors_at_3_bits(layer)
+    _upload_factors_at_3_bits(L, layer_q)
+    _check(amd, cfg.with_(name=cfg.name + "_int3_factors"), layer_q, L, sample_mats=((5, 1),), q3=True)
     L.close()
 
 
