@@ -395,6 +395,10 @@ def main():
             "mfma_f16_tflops": round(amd.calibrate(amd.CAL_MFMA_F16, 0, 5), 1),
             "mfma_f16_32x32x16_tflops": round(amd.calibrate(amd.CAL_MFMA_F16_32, 0, 5), 1),
             "ns_per_mfma_16x16x32_with_n_packed_fmas": {str(n): round(amd.calibrate(amd.CAL_MFMA_VALU, n, 5), 2) for n in (0, 2, 4, 8, 16)},
+            # a loop shaped like a sub-step of the decode kernel (16 vector operations make two operands,
+            # 2 MT MFMAs use them), four wavefronts per SIMD: ns of SIMD time per wavefront sub-step
+            "decode_substep_ns": {f"mt{mt}_{name}": round(amd.calibrate(amd.CAL_SUBSTEP, mt + 16 * mode, 5), 2)
+                                  for mt in (1, 2) for mode, name in ((0, "both"), (1, "mfma_only"), (2, "valu_only"))},
             "note": "moe_lrc_calibrate on this device: 3 GiB streaming read, 256 MiB pinned copy, register-only MFMA loops "
                     "(the last: two wavefronts per SIMD, every MFMA followed by n independent v_pk_fma_f16)"}
     path_kernel_ms = sum(stage_avg.values())

@@ -374,12 +374,18 @@ int moe_lrc_selftest_factor_pair(int K, int N, int rank, const uint8_t* a_codes,
  *   MOE_LRC_CAL_MFMA_VALU  two wavefronts per SIMD issue v_mfma_f32_16x16x32_f16, each followed by
  *                         `bytes` (0, 2, 4, 8 or 16) independent packed fp16 FMAs: *result = ns per
  *                         MFMA with its FMAs on one SIMD (how far vector work hides behind MFMAs)
+ *   MOE_LRC_CAL_SUBSTEP   four wavefronts per SIMD run a loop shaped like a sub-step of the decode
+ *                         flavour of the expert FFN: 8 mask and 8 packed-FMA operations make two
+ *                         operands, then 2 MT MFMAs use them.  bytes = MT (1 or 2 row tiles) + 16 *
+ *                         mode (0: both, 1: the MFMAs alone, 2: the vector operations alone);
+ *                         *result = ns of SIMD time per sub-step of one wavefront
  * result: host pointer to one double. */
 #define MOE_LRC_CAL_HBM_READ 0
 #define MOE_LRC_CAL_H2D      1
 #define MOE_LRC_CAL_MFMA_F16 2
 #define MOE_LRC_CAL_MFMA_F16_32 3
 #define MOE_LRC_CAL_MFMA_VALU 4
+#define MOE_LRC_CAL_SUBSTEP 5
 int moe_lrc_calibrate(int kind, size_t bytes, int reps, double* result);
 
 #ifdef __cplusplus

@@ -135,7 +135,7 @@ def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
 
 
-CAL_HBM_READ, CAL_H2D, CAL_MFMA_F16, CAL_MFMA_F16_32, CAL_MFMA_VALU = 0, 1, 2, 3, 4
+CAL_HBM_READ, CAL_H2D, CAL_MFMA_F16, CAL_MFMA_F16_32, CAL_MFMA_VALU, CAL_SUBSTEP = 0, 1, 2, 3, 4, 5
 
 
 def calibrate(kind: int, nbytes: int = 0, reps: int = 5) -> float:

@@ -116,6 +116,57 @@ __global__ __launch_bounds__(512) void mfma_valu_kernel(int iters, float* __rest
   if (s == 12345.678f || x == 0x12345u) sink[0] = s;
 }
 
+// A loop shaped like a sub-step of the decode-flavour FFN kernel, four wavefronts per SIMD (one
+// 1024-thread block per CU): 8 mask and 8 packed-FMA operations make the A operands of two streams,
+// then 2 MT MFMAs (v_mfma_f32_16x16x32_f16) multiply them with MT activation fragments.  MODE 0: both,
+// 1: the MFMAs alone, 2: the vector operations alone.
+template <int MT, int MODE>
+__global__ __launch_bounds__(1024) void substep_kernel(int iters, float* __restrict__ sink) {
+  half8_t b[MT];
+  float4_t acc[MT][2];
+  uint32_t cw[2][4], v[2][4];
+#pragma unroll
+  for (int t = 0; t < MT; ++t) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) b[t][i] = (_Float16)(0.001f * float((threadIdx.x & 15) + i + t));
+#pragma unroll
+    for (int m = 0; m < 2; ++m) acc[t][m] = float4_t{0.f, 0.f, 0.f, 0.f};
+  }
+#pragma unroll
+  for (int m = 0; m < 2; ++m)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { cw[m][j] = threadIdx.x * 2654435761u + 97u * (4 * m + j); v[m][j] = 0x3c003c00u; }
+  const uint32_t mask = 0x00300030u, c1 = 0x64006400u, c2 = 0x00010001u;
+  for (int it = 0; it < iters; ++it) {
+    if (MODE != 1) {
+#pragma unroll
+      for (int m = 0; m < 2; ++m)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          uint32_t f;
+          asm volatile("v_and_b32 %0, %1, %2" : "=v"(f) : "v"(cw[m][j]), "v"(mask));
+          asm volatile("v_pk_fma_f16 %0, %1, %2, %3" : "=v"(v[m][j]) : "v"(f), "v"(c1), "v"(c2));
+        }
+    }
+    if (MODE != 2) {
+#pragma unroll
+      for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int m = 0; m < 2; ++m)
+          acc[t][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, make_uint4(v[m][0], v[m][1], v[m][2], v[m][3])),
+                                                            b[t], acc[t][m], 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  float s = 0.f;
+  uint32_t x = 0;
+#pragma unroll
+  for (int t = 0; t < MT; ++t)
+#pragma unroll
+    for (int m = 0; m < 2; ++m) { s += acc[t][m][0] + acc[t][m][3]; x ^= v[m][t]; }
+  if (s == 12345.678f || x == 0x12345u) sink[0] = s;
+}
+
 }  // namespace
 
 }  // namespace lrc
@@ -133,7 +184,9 @@ using namespace lrc;
 
 extern "C" int moe_lrc_calibrate(int kind, size_t bytes, int reps, double* result) {
   if (!result || reps < 1 || reps > 1000) return set_error(MOE_LRC_EINVAL, "calibrate: result is null or reps outside 1..1000");
-  if (kind < MOE_LRC_CAL_HBM_READ || kind > MOE_LRC_CAL_MFMA_VALU) return set_error(MOE_LRC_EINVAL, "calibrate: unknown kind");
+  if (kind < MOE_LRC_CAL_HBM_READ || kind > MOE_LRC_CAL_SUBSTEP) return set_error(MOE_LRC_EINVAL, "calibrate: unknown kind");
+  if (kind == MOE_LRC_CAL_SUBSTEP && ((bytes & 15) < 1 || (bytes & 15) > 2 || (bytes >> 4) > 2))
+    return set_error(MOE_LRC_EINVAL, "calibrate: sub-step: bytes = row tiles (1 or 2) + 16 * mode (0, 1 or 2)");
   if (kind == MOE_LRC_CAL_MFMA_VALU && bytes != 0 && bytes != 2 && bytes != 4 && bytes != 8 && bytes != 16)
     return set_error(MOE_LRC_EINVAL, "calibrate: the number of FMAs per MFMA must be 0, 2, 4, 8 or 16");
   if (kind < MOE_LRC_CAL_MFMA_F16 && (bytes < (1u << 20) || bytes > (size_t(16) << 30)))
@@ -179,6 +232,24 @@ extern "C" int moe_lrc_calibrate(int kind, size_t bytes, int reps, double* resul
     }
     std::sort(ms.begin(), ms.end());
     *result = double(bytes) / (ms[ms.size() / 2] * 1e-3) / 1e9;      // GB/s
+  } else if (kind == MOE_LRC_CAL_SUBSTEP) {
+    const int iters = 8192, mt = int(bytes & 15), mode = int(bytes >> 4);
+    for (int i = 0; i < reps + 1; ++i) {
+      CAL_HIP(hipEventRecord(e0, nullptr));
+      const dim3 g(n_cu), b(1024);
+      if (mt == 1 && mode == 0) hipLaunchKernelGGL((substep_kernel<1, 0>), g, b, 0, nullptr, iters, (float*)sink);
+      else if (mt == 1 && mode == 1) hipLaunchKernelGGL((substep_kernel<1, 1>), g, b, 0, nullptr, iters, (float*)sink);
+      else if (mt == 1) hipLaunchKernelGGL((substep_kernel<1, 2>), g, b, 0, nullptr, iters, (float*)sink);
+      else if (mode == 0) hipLaunchKernelGGL((substep_kernel<2, 0>), g, b, 0, nullptr, iters, (float*)sink);
+      else if (mode == 1) hipLaunchKernelGGL((substep_kernel<2, 1>), g, b, 0, nullptr, iters, (float*)sink);
+      else hipLaunchKernelGGL((substep_kernel<2, 2>), g, b, 0, nullptr, iters, (float*)sink);
+      CAL_HIP(hipEventRecord(e1, nullptr));
+      CAL_HIP(hipEventSynchronize(e1));
+      CAL_HIP(hipEventElapsedTime(&t, e0, e1));
+      if (i > 0) ms.push_back(t);
+    }
+    std::sort(ms.begin(), ms.end());
+    *result = ms[ms.size() / 2] * 1e6 / (double(iters) * 4);         // ns of SIMD time per sub-step of one wavefront
   } else if (kind == MOE_LRC_CAL_MFMA_VALU) {
     const int iters = 4096;
     for (int i = 0; i < reps + 1; ++i) {

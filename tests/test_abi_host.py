@@ -104,6 +104,7 @@ def test_stack_offline_and_hook_argument_errors_need_no_device(lib):
     assert lib.moe_lrc_offline_kurtosis(dummy, 0, C.byref(k)) == -1
     assert lib.moe_lrc_calibrate(9, 1 << 20, 1, C.byref(k)) == -1            # unknown kind
     assert lib.moe_lrc_calibrate(4, 3, 1, C.byref(k)) == -1                  # FMAs per MFMA not in {0, 2, 4, 8, 16}
+    assert lib.moe_lrc_calibrate(5, 3, 1, C.byref(k)) == -1                  # sub-step: row tiles not 1 or 2
     assert lib.moe_lrc_calibrate(0, 1 << 20, 0, C.byref(k)) == -1            # reps
     assert lib.moe_lrc_selftest_half_rounding(None, 1, None) == -1
     assert binding.last_error()
