@@ -258,7 +258,8 @@ static int run_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t*
   const CompactArgs cmp{reinterpret_cast<int32_t*>(ws + w.cmp_index), reinterpret_cast<int32_t*>(ws + w.cmp_list)};
   if (comp) { a.cmp_index = cmp.index; a.cmp_list = cmp.list; }
   LRC_HIP(launch_convert_x(L, x, T, xh, P + kActPadRows, offsets, row_pair, L->d_stat, plans,
-                           ((path & 1) || a.xa13_here) ? nullptr : &a, tok_exp, a.row_exp, perm, comp ? &cmp : nullptr, route, stream));
+                           ((path & 1) || a.xa13_here) ? nullptr : &a, tok_exp, a.row_exp, perm, comp ? &cmp : nullptr, route,
+                           ZeroRowsArgs{reinterpret_cast<uint4*>(a.h), a.h_rt, padded_k(c.ffn)}, stream));
   L->stats_valid = false;
   L->stats.stage_ms = 0.f;
   if (c.residency == MOE_LRC_STAGED) {
@@ -280,7 +281,8 @@ static int run_shared(moe_lrc_layer* L, const void* x, int T, uint8_t* ws, hipSt
   const Workspace w = plan_workspace(L, T);
   _Float16* xh = reinterpret_cast<_Float16*>(ws + w.xh_sh);
   int32_t* row_exp = reinterpret_cast<int32_t*>(ws + w.row_exp_sh);
-  LRC_HIP(launch_convert_x(L, x, T, xh, T + kActPadRows, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, row_exp, nullptr, nullptr, nullptr, stream));
+  LRC_HIP(launch_convert_x(L, x, T, xh, T + kActPadRows, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, row_exp, nullptr, nullptr, nullptr,
+                           ZeroRowsArgs{reinterpret_cast<uint4*>(ws + w.sh_h), c.n_shared * T + kActPadRows, padded_k(c.ffn)}, stream));
   FfnArgs a{};
   a.desc = L->d_desc + c.n_experts; a.n_exp = c.n_shared; a.bits = c.shared_bits; a.group = c.group;
   a.rank = 0; a.rpad = 0; a.H = c.hidden; a.F = c.ffn; a.top_k = c.top_k; a.top_n = 0; a.T = T;

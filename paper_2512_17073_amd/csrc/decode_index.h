@@ -97,6 +97,43 @@ LRC_HD StepRef step_ref(int n, const StepPlan& p, int grp, int groups, int kwi, 
   return r;
 }
 
+// The same sequence walked one step at a time, without divisions: the kernel fetches the steps
+// 0, 1, 2, ... of a pass in order, two of them past the last one.  cursor_ref gives what step_ref
+// gives for the cursor's step (for a step that reads nothing only `reg` and `lr`, both false, are
+// meant to agree).
+struct StepCursor {
+  int part;      // 0: k-steps, 1: rank steps
+  int ph;        // phase (k-steps)
+  int ts;        // unit slot (past the last one: nothing left)
+  int si;        // index within the (phase, unit slot) or (unit slot) segment
+};
+LRC_HD StepCursor cursor_start() { return StepCursor{0, 0, 0, 0}; }
+LRC_HD StepRef cursor_ref(const StepCursor& c, const StepPlan& p, int grp, int groups, int kwi, int kw, int units, int ks_lo,
+                          int KSl, int LS) {
+  StepRef r{};
+  r.ts = c.ts;
+  r.unit = grp + c.ts * groups;
+  const int own = c.si * kw + kwi;
+  if (c.part == 0) {
+    r.kl = own;
+    r.ks = ks_lo + c.ph * p.KP + own;
+    r.reg = r.unit < units && own < p.KP && c.ph * p.KP + own < KSl;
+  } else {
+    r.st = own;
+    r.lr = c.ts < p.TS && c.si < p.LSS && r.unit < units && own < LS;
+  }
+  return r;
+}
+LRC_HD void cursor_advance(StepCursor& c, const StepPlan& p) {
+  ++c.si;
+  if (c.si == (c.part ? p.LSS : p.SP)) { c.si = 0; ++c.ts; }
+  if (c.part == 0 && c.ts == p.TS) {
+    c.ts = 0;
+    ++c.ph;
+    if (c.ph == p.n_ph) c.part = 1;
+  }
+}
+
 // Byte offsets of a lane's loads of one stream of a step (the hardware range-checks offset + size
 // against the resource; a step that reads nothing gets an offset at the end of every resource).
 // q3: the stream's factor pair is held at 3 bits (layout.h).  A rank step then reads, through `bf`,
@@ -122,6 +159,15 @@ LRC_HD LaneOffsets lane_offsets(const StepRef& r, int tile, bool tile_ok, int la
   o.bf = (lq ? group4 * 128 : lr ? unit * 1024 : past) + (lq ? q * 32 + (c & 1) * 16 : lane * 16);
   o.bc = (lq ? unit * 256 : 0xfffffe00u) + lane * 4;
   return o;
+}
+
+// Row of the operand-order activation buffer (in_rt rows) that lane row `rowl` of row tile mt stages
+// in the pass that starts at the expert's row r (rin: that row's index in the buffer).  Past the
+// expert's last row the MFMA columns are never stored: they read the buffer's last 16 rows, which
+// the preparing launch keeps at zero (multiplying zeros costs the matrix cores the least).
+constexpr int kZeroRows = 16;
+LRC_HD int staged_row(int rin, int r, int mt, int rowl, int cnt, int in_rt) {
+  return r + 16 * mt + rowl < cnt ? rin + 16 * mt + rowl : in_rt - kZeroRows + rowl;
 }
 
 // LDS unit of staged activation fragment (row tile mt, k-step kl of the phase, sub-step s).

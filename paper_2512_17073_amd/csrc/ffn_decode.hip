@@ -116,8 +116,11 @@ __device__ __forceinline__ void decode_body(const KArgs& a, uint4* xs, const int
     const StepPlan sp = step_plan(KSl, MT, kw, LS, DUAL);
     const int KP = sp.KP;
 
-    auto fetch = [&](int n, Slot<BITS, NS>& sl) {
-      const StepRef ref = step_ref(n, sp, grp, groups, kwi, kw, units, ks_lo, KSl, LS, DUAL);
+    // (the steps are fetched in order, RING of them ahead of their use and RING past the last one)
+    StepCursor cursor = cursor_start();
+    auto fetch = [&](Slot<BITS, NS>& sl) {
+      const StepRef ref = cursor_ref(cursor, sp, grp, groups, kwi, kw, units, ks_lo, KSl, LS);
+      cursor_advance(cursor, sp);
 #pragma unroll
       for (int m = 0; m < NS; ++m) {
         const int tile = stream_tile(t0, ref.unit, m, DUAL);
@@ -143,8 +146,8 @@ __device__ __forceinline__ void decode_body(const KArgs& a, uint4* xs, const int
 
     // A phase is MT * nk * 8 fragments of 64 units (16 rows x 4 column groups of one MFMA sub-step);
     // four 256-byte runs of the operand-order buffer become 1 KB of LDS, lane-linear.  Rows past the
-    // expert's last one read whatever follows (other rows or the padding): their output columns are
-    // never stored.  The copy is asynchronous and takes no registers: each lane's 16 bytes go from
+    // expert's last one read the zero rows at the end of the buffer (staged_row): their output
+    // columns are never stored.  The copy is asynchronous and takes no registers: each lane's 16 bytes go from
     // global memory straight to LDS (wave-uniform LDS base + 16 * lane), counted by vmcnt.
     const uint4* in_units = reinterpret_cast<const uint4*>(a.in);
     auto stage_issue = [&](int ph, int nk) {
@@ -156,7 +159,7 @@ __device__ __forceinline__ void decode_body(const KArgs& a, uint4* xs, const int
           uint4* dst = xs + act_frag_unit(mt, kl, s, KP);
           __builtin_amdgcn_global_load_lds(
               reinterpret_cast<const __attribute__((address_space(1))) void*>(
-                  reinterpret_cast<uintptr_t>(in_units + act_unit(k8, rin + 16 * mt + rowl, a.in_rt))),
+                  reinterpret_cast<uintptr_t>(in_units + act_unit(k8, staged_row(rin, r, mt, rowl, cnt, a.in_rt), a.in_rt))),
               reinterpret_cast<__attribute__((address_space(3))) void*>(reinterpret_cast<uintptr_t>(dst)), 16, 0, 0);
         }
     };
@@ -183,7 +186,7 @@ __device__ __forceinline__ void decode_body(const KArgs& a, uint4* xs, const int
     if (!p_late) p_issue();
     Slot<BITS, NS> ring[RING];
 #pragma unroll
-    for (int i = 0; i < RING; ++i) fetch(i, ring[i]);
+    for (int i = 0; i < RING; ++i) fetch(ring[i]);
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
     float4_t acc[TS][MT][NS];
@@ -275,7 +278,6 @@ __device__ __forceinline__ void decode_body(const KArgs& a, uint4* xs, const int
       substep(std::integral_constant<int, 6>{}); substep(std::integral_constant<int, 7>{});
     };
 
-    int n = 0;
     for (int ph = 0; ph < sp.n_ph; ++ph) {
       const int nk = min(KP, KSl - ph * KP);
       if (ph > 0) {
@@ -291,9 +293,8 @@ __device__ __forceinline__ void decode_body(const KArgs& a, uint4* xs, const int
 #pragma unroll
           for (int i = 0; i < RING; ++i) {   // slot i: consumed, then refilled RING steps ahead
             if (unit_ok && (si + i) * kw + kwi < nk) compute(ring[i], (si + i) * kw + kwi, acc[ts]);
-            fetch(n + i + RING, ring[i]);
+            fetch(ring[i]);
           }
-          n += RING;
         }
       }
     }
@@ -311,9 +312,8 @@ __device__ __forceinline__ void decode_body(const KArgs& a, uint4* xs, const int
         for (int i = 0; i < RING; ++i) {
           const int st = (l0 + i) * kw + kwi;
           if (unit_ok && st < LS) compute_lr(ring[i], st, acc[ts]);
-          fetch(n + i + RING, ring[i]);
+          fetch(ring[i]);
         }
-        n += RING;
       }
     }
 

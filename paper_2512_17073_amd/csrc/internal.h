@@ -125,6 +125,11 @@ constexpr int kPermuteScratchInts = kPermuteMaxBlocks * 2 * 256 + 64;
 // the front of its own row range: list [T * k] names the routed row of each compact row, index
 // [T * k] the compact row of each routed row (-1 for a row without the term).
 struct CompactArgs { int32_t *index, *list; };
+// The last rows of the operand-order buffers, which the decode flavour stages in place of rows past
+// an expert's last one (decode_index.h, staged_row), are kept at zero by one block of the preparing
+// launch: those of its own output and, if given, of the buffer `h` (h_rt rows, Fp columns) that the
+// fused projection writes next.
+struct ZeroRowsArgs { uint4* h; int h_rt, Fp; };
 // fp16 copy of the activations in operand order, every row times its power-of-two pre-scale
 // (ffn_common.h; exponents to row_exp, taken from tok_exp per token if given): one row per routed
 // pair (row_pair given) or one per token (row_pair null); with `stat`, one more block counts the
@@ -138,6 +143,7 @@ hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _
                             const int32_t* tok_exp /* or null */, int32_t* row_exp,
                             const PermuteArgs* perm /* or null: offsets and row_pair are ready */,
                             const CompactArgs* cmp /* or null */, const RouteArgs* route /* or null: perm->idx is ready */,
+                            const ZeroRowsArgs& zr,
                             hipStream_t s);
 constexpr int kMaxKBlocks = 8;    // most K-blocks the decode W2 kernel splits into
 // blocks (per K-block) of a decode launch that shares its blocks out by a table: `target` (the

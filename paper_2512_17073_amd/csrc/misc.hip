@@ -2,6 +2,7 @@
 // per-call expert statistics, and the unpack hook that reads the private packed layout back.
 #include <algorithm>
 
+#include "decode_index.h"
 #include "internal.h"
 #include "permute_body.h"
 #include "plan.h"
@@ -108,7 +109,7 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(const uint16_t* __re
                                                    int top_n, int32_t* __restrict__ stat, PlanSpec plan0,
                                                    PlanSpec plan1, int xa_tiles, ffn::KArgs xa,
                                                    const int32_t* tok_exp, int32_t* __restrict__ row_exp,
-                                                   PermuteArgs perm, CompactArgs cmp, RouteArgs route) {
+                                                   PermuteArgs perm, CompactArgs cmp, RouteArgs route, ZeroRowsArgs zr) {
   __shared__ ffn::float4_t red[2 * kPrepThreads / 64][64];
   __shared__ uint32_t row_max[16];
   if (route.wg != nullptr) {
@@ -126,6 +127,16 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(const uint16_t* __re
   constexpr int kWavesPerBlock = kPrepThreads / 64, kColLanes = kPrepThreads / 16;
   const int row_blocks = (rows + 15) / 16;
   const int stat_blocks = stat ? (E + kWavesPerBlock - 1) / kWavesPerBlock : 0, plan_block = plan0.B + plan1.B > 0 ? 1 : 0;
+  if ((int)blockIdx.x == (int)gridDim.x - 1) {                              // the zero rows (the last block)
+    const int n = blockIdx.y * kPrepThreads + threadIdx.x, step = kPrepThreads * gridDim.y;
+    const int xu = (H + kTileK - 1) / kTileK * (kTileK / 8);               // 16-byte units per row
+    for (int i = n; i < xu * dec::kZeroRows; i += step)
+      xg[size_t(i / dec::kZeroRows) * rt + rt - dec::kZeroRows + i % dec::kZeroRows] = make_uint4(0, 0, 0, 0);
+    if (zr.h != nullptr)
+      for (int i = n; i < zr.Fp / 8 * dec::kZeroRows; i += step)
+        zr.h[size_t(i / dec::kZeroRows) * zr.h_rt + zr.h_rt - dec::kZeroRows + i % dec::kZeroRows] = make_uint4(0, 0, 0, 0);
+    return;
+  }
   if ((int)blockIdx.x >= row_blocks + stat_blocks + plan_block) {          // (x A1 | x A3)
     const int i = (int)blockIdx.x - (row_blocks + stat_blocks + plan_block);
     if (blockIdx.y == 0) ffn::xa_rows_body<true, true, kWavesPerBlock>(xa, x, i % xa_tiles, i / xa_tiles, 0, red);
@@ -235,7 +246,8 @@ hipError_t launch_combine(const moe_lrc_layer* L, const void* y_rows, const floa
 hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _Float16* xg, int rt,
                             const int32_t* offsets, const int32_t* row_pair, int32_t* stat,
                             const PlanSpec* plans, const FfnArgs* xa13, const int32_t* tok_exp, int32_t* row_exp,
-                            const PermuteArgs* perm, const CompactArgs* cmp, const RouteArgs* route, hipStream_t s) {
+                            const PermuteArgs* perm, const CompactArgs* cmp, const RouteArgs* route, const ZeroRowsArgs& zr,
+                            hipStream_t s) {
   const moe_lrc_config& c = L->cfg;
   const int rows = row_pair ? T * c.top_k : T;
   const int row_blocks = (rows + 15) / 16;
@@ -257,12 +269,13 @@ hipError_t launch_convert_x(const moe_lrc_layer* L, const void* x_bf16, int T, _
   }
   const int stat_blocks = stat ? (c.n_experts + kPrepThreads / 64 - 1) / (kPrepThreads / 64) : 0;
   const int cmp_block = (cmp && row_pair && stat) ? 1 : 0;     // (the compaction rides the per-expert counting)
-  hipLaunchKernelGGL(prep_kernel, dim3(row_blocks + stat_blocks + plan_block + xa_tiles * c.n_experts, ky),
+  // (+ 1: the block that keeps the zero rows)
+  hipLaunchKernelGGL(prep_kernel, dim3(row_blocks + stat_blocks + plan_block + xa_tiles * c.n_experts + 1, ky),
                      dim3(kPrepThreads), 0, s, (const uint16_t*)x_bf16, rows, c.hidden, reinterpret_cast<uint4*>(xg), rt, offsets,
                      row_pair, c.n_experts, c.top_k, c.top_n, stat, p0, p1, xa_tiles, xa, tok_exp, row_exp,
                      perm ? *perm : PermuteArgs{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0},
                      cmp_block ? *cmp : CompactArgs{nullptr, nullptr},
-                     (route && perm) ? *route : RouteArgs{nullptr, nullptr, nullptr, nullptr, nullptr, 0});
+                     (route && perm) ? *route : RouteArgs{nullptr, nullptr, nullptr, nullptr, nullptr, 0}, zr);
   return hipGetLastError();
 }
 

@@ -76,8 +76,12 @@ std::string check_shape(const Shape& sh) {
                   const int q = lane >> 4, rowl = lane & 15, s = wave & 7;
                   const int k8 = std::min((ks_lo + ph * sp.KP + kl) * 32 + q * 8 + s, sh.K / 8 - 1);
                   if (act_frag_unit(mt, kl, s, sp.KP) + 64 > kLdsUnits) SELF_FAIL("staged fragment (mt %d, kl %d, s %d) leaves LDS", mt, kl, s);
-                  const size_t u = ffn::act_unit(k8, sh.r0 + r + 16 * mt + rowl, rt);
-                  if (u >= in_units) SELF_FAIL("staging reads unit %zu of %zu (row %d of %d)", u, in_units, sh.r0 + r + 16 * mt + rowl, rt);
+                  const int row = staged_row(sh.r0 + r, r, mt, rowl, sh.cnt, rt);
+                  if (row < 0 || row >= rt) SELF_FAIL("staging reads row %d of %d", row, rt);
+                  if (r + 16 * mt + rowl < sh.cnt ? row != sh.r0 + r + 16 * mt + rowl : row < sh.total_rows + kActPadRows - kZeroRows)
+                    SELF_FAIL("staging reads row %d for row %d of an expert with %d rows at %d", row, r + 16 * mt + rowl, sh.cnt, sh.r0);
+                  const size_t u = ffn::act_unit(k8, row, rt);
+                  if (u >= in_units) SELF_FAIL("staging reads unit %zu of %zu (row %d of %d)", u, in_units, row, rt);
                 }
         }
         // (in A) fragments
@@ -95,8 +99,17 @@ std::string check_shape(const Shape& sh) {
         if (r > 0) continue;                  // (the steps do not depend on the pass)
         for (int wave = 0; wave < kWaves; ++wave) {
           const int grp = wave / kw, kwi = wave % kw;
+          StepCursor cur = cursor_start();
           for (int n = 0; n < sp.n_reg + sp.LSP + kRing; ++n) {
-            const StepRef ref = step_ref(n, sp, grp, groups, kwi, kw, units, ks_lo, KSl, LS, sh.dual);
+            // the kernel walks the steps with the cursor; step_ref is the closed form it must agree with
+            const StepRef want = step_ref(n, sp, grp, groups, kwi, kw, units, ks_lo, KSl, LS, sh.dual);
+            const StepRef ref = cursor_ref(cur, sp, grp, groups, kwi, kw, units, ks_lo, KSl, LS);
+            cursor_advance(cur, sp);
+            if (ref.reg != want.reg || ref.lr != want.lr) SELF_FAIL("step %d: the cursor disagrees on what kind of step it is", n);
+            if (ref.reg && (ref.unit != want.unit || ref.ks != want.ks || ref.kl != want.kl || ref.ts != want.ts))
+              SELF_FAIL("step %d: the cursor is at k-step %d of unit %d, the closed form at %d of %d", n, ref.ks, ref.unit, want.ks, want.unit);
+            if (ref.lr && (ref.unit != want.unit || ref.st != want.st || ref.ts != want.ts))
+              SELF_FAIL("step %d: the cursor is at rank step %d of unit %d, the closed form at %d of %d", n, ref.st, ref.unit, want.st, want.unit);
             if (ref.reg && ref.lr) SELF_FAIL("step %d is both a k-step and a rank step", n);
             for (int m = 0; m < kStreams; ++m) {
               const int tile = stream_tile(t0, ref.unit, m, sh.dual);
