@@ -29,6 +29,7 @@
 #include <type_traits>
 #include <utility>
 
+#include "decode_index.h"
 #include "factor_q3.h"
 #include "ffn_common.h"
 #include "plan.h"
@@ -113,9 +114,10 @@ template <int N, class Fn> __device__ inline void static_for(Fn&& fn) { static_f
 // group q = p + 2 (l / 32) of sub-step s.  (After the row swap, operand p of a sub-step holds in
 // lanes 0..31 the weights of lane group q = p and in lanes 32..63 those of q = p + 2.)  Wavefront w
 // of the block's WAVES copies the fragments of sub-steps s = w, w + WAVES, ...
-// Only the first rp_n row pairs are copied (the others hold no rows of the expert and are not read).
+// Only the first rp_n row pairs are copied (the others hold no rows of the expert and are not read);
+// `rows` of the chunk's rows are the expert's.
 template <int WAVES>
-__device__ inline void stage_step32(const KArgs& a, uint4* buf, int ks, int rin, int rp_n, int wave, int lane) {
+__device__ inline void stage_step32(const KArgs& a, uint4* buf, int ks, int rin, int rows, int rp_n, int wave, int lane) {
   const uint4* in_units = reinterpret_cast<const uint4*>(a.in);
   const int n = lane & 31, h = lane >> 5;
 #pragma unroll
@@ -127,7 +129,8 @@ __device__ inline void stage_step32(const KArgs& a, uint4* buf, int ks, int rin,
 #pragma unroll
       for (int rp = 0; rp < kRP; ++rp) {
         if (rp >= rp_n) continue;
-        const int R = min(rin + 32 * rp + n, a.in_rt - 1);
+        // (a row past the chunk's last one: one of the zero rows at the end of the buffer, see staged_row)
+        const int R = 32 * rp + n < rows ? rin + 32 * rp + n : a.in_rt - dec::kZeroRows + (n & 15);
         __builtin_amdgcn_global_load_lds(
             reinterpret_cast<const __attribute__((address_space(1))) void*>(reinterpret_cast<uintptr_t>(in_units + act_unit(k8, R, a.in_rt))),
             reinterpret_cast<__attribute__((address_space(3))) void*>(reinterpret_cast<uintptr_t>(buf + ((rp * 8 + s) * 2 + p) * 64)), 16, 0, 0);
@@ -325,7 +328,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 4 ? 1 : 2) void qgemm_tile_ker
 
   // ---- prologue: the first k-step of activations and the first two ring slots
   Slot2<BITS, NM, kNTW> ring[2];
-  stage_step32<WAVES>(a, xs, 0, rin, rp_n, wave, lane);
+  stage_step32<WAVES>(a, xs, 0, rin, cnt - r, rp_n, wave, lane);
   __builtin_amdgcn_sched_barrier(0);
   fetch(0, ring[0]);
   fetch(1, ring[1]);
@@ -345,7 +348,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 4 ? 1 : 2) void qgemm_tile_ker
       for (int i = 0; i < 2; ++i) {
         const int step = s0 + i;
         if (step < steps) {
-          stage_step32<WAVES>(a, xs + ((step + 1) & 1) * kStepUnits, step + 1, rin, decltype(RPN_)::value, wave, lane);
+          stage_step32<WAVES>(a, xs + ((step + 1) & 1) * kStepUnits, step + 1, rin, cnt - r, decltype(RPN_)::value, wave, lane);
           __builtin_amdgcn_sched_barrier(0);     // (the wait below counts the refill as the only later loads)
           compute(RPN_, ring[i], xs + (step & 1) * kStepUnits);
           fetch(step + 2, ring[i]);
@@ -552,12 +555,13 @@ __global__ __launch_bounds__(64 * kTileWaves, 2) void xa_tile_kernel(KArgs a) {
   const int pitch = NM * a.ls * 32;
   // The chunk's rows are compact rows (the rows of the expert that take the rank-r term, in row
   // order): row_list names the routed row whose activations each one reads.  A row past the
-  // expert's last compact row reads the last one's (its results are never stored).
+  // expert's last compact row reads one of the zero rows at the end of the buffer (its results are
+  // never stored).
   int Rm[kTMT];
 #pragma unroll
   for (int mt = 0; mt < kTMT; ++mt) {
     const int i = r0 + min(r + 16 * mt + c, cnt - 1);
-    Rm[mt] = a.row_list ? a.row_list[i] : i;
+    Rm[mt] = r + 16 * mt + c < cnt ? (a.row_list ? a.row_list[i] : i) : a.in_rt - dec::kZeroRows + c;
   }
 
   float4_t acc[kMaxT][kTMT];
