@@ -34,18 +34,29 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict
                                                       const uint16_t* __restrict__ y_shared,
                                                       const uint16_t* __restrict__ residual, int T, int H,
                                                       int top_k, int n_shared, uint16_t* __restrict__ out) {
+  // (grid.y walks the 8-column chunks of a row in steps of the block size: few tokens still make many blocks)
   const int t = blockIdx.x;
-  for (int ch = threadIdx.x; ch < H / 8; ch += 256) {
+  for (int ch = blockIdx.y * 256 + threadIdx.x; ch < H / 8; ch += 256 * gridDim.y) {
     float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     for (int j = 0; j < top_k; ++j) {
       const int row = pair_row[t * top_k + j];
       const float wj = w[t * top_k + j];
       if (y_part != nullptr) {
-        const float4* src = reinterpret_cast<const float4*>(y_part + size_t(row) * H) + 2 * ch;
-        float4 lo = src[0], hi = src[1];
-        for (int kb = 1; kb < kblocks; ++kb) {
-          const float4* s2 = reinterpret_cast<const float4*>(y_part + kb * kb_stride + size_t(row) * H) + 2 * ch;
-          const float4 a = s2[0], b = s2[1];
+        // every K-block's part is requested before the first is added; the additions keep the
+        // order kb = 0, 1, ...
+        float4 pl[kMaxKBlocks], ph[kMaxKBlocks];
+#pragma unroll
+        for (int kb = 0; kb < kMaxKBlocks; ++kb) {
+          if (kb < kblocks) {
+            const float4* s2 = reinterpret_cast<const float4*>(y_part + kb * kb_stride + size_t(row) * H) + 2 * ch;
+            pl[kb] = s2[0]; ph[kb] = s2[1];
+          }
+        }
+        float4 lo = pl[0], hi = ph[0];
+#pragma unroll
+        for (int kb = 1; kb < kMaxKBlocks; ++kb) {
+          if (kb >= kblocks) break;
+          const float4 a = pl[kb], b = ph[kb];
           lo.x += a.x; lo.y += a.y; lo.z += a.z; lo.w += a.w;
           hi.x += b.x; hi.y += b.y; hi.z += b.z; hi.w += b.w;
         }
@@ -237,7 +248,9 @@ hipError_t launch_combine(const moe_lrc_layer* L, const void* y_rows, const floa
                           const int32_t* pair_row, const void* y_shared, const void* residual, int T, void* out,
                           hipStream_t s) {
   const moe_lrc_config& c = L->cfg;
-  hipLaunchKernelGGL(combine_kernel, dim3(T), dim3(256), 0, s, (const uint16_t*)y_rows, y_part, kblocks,
+  // enough blocks for the chip when there are few tokens: up to one per 256 chunks of 8 columns
+  const int gy = std::max(1, std::min((c.hidden / 8 + 255) / 256, (2 * L->n_cu + T - 1) / T));
+  hipLaunchKernelGGL(combine_kernel, dim3(T, gy), dim3(256), 0, s, (const uint16_t*)y_rows, y_part, kblocks,
                      size_t(T) * c.top_k * c.hidden, w, pair_row,
                      (const uint16_t*)y_shared, (const uint16_t*)residual, T, c.hidden, c.top_k, c.n_shared, (uint16_t*)out);
   return hipGetLastError();
