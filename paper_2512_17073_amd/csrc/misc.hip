@@ -27,6 +27,8 @@ __device__ inline uint32_t pack_bf16(float a, float b) {
 // then the shared experts: a fixed order, so two runs give identical bits.  With y_part, row R's
 // output is the sum over the K-blocks kb = 0.. of y_part[kb][R] (fp32, in that order) instead of
 // the bf16 row y_rows[R].
+// PARTS: the rows come as K-block parts (y_part); else as bf16 rows (y_rows).
+template <bool PARTS>
 __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict__ y_rows,
                                                       const float* __restrict__ y_part, int kblocks, size_t kb_stride,
                                                       const float* __restrict__ w,
@@ -41,7 +43,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict
     for (int j = 0; j < top_k; ++j) {
       const int row = pair_row[t * top_k + j];
       const float wj = w[t * top_k + j];
-      if (y_part != nullptr) {
+      if constexpr (PARTS) {
         // every K-block's part is requested before the first is added; the additions keep the
         // order kb = 0, 1, ...
         float4 pl[kMaxKBlocks], ph[kMaxKBlocks];
@@ -62,14 +64,14 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict
         }
         acc[0] = fmaf(wj, lo.x, acc[0]); acc[1] = fmaf(wj, lo.y, acc[1]); acc[2] = fmaf(wj, lo.z, acc[2]); acc[3] = fmaf(wj, lo.w, acc[3]);
         acc[4] = fmaf(wj, hi.x, acc[4]); acc[5] = fmaf(wj, hi.y, acc[5]); acc[6] = fmaf(wj, hi.z, acc[6]); acc[7] = fmaf(wj, hi.w, acc[7]);
-        continue;
-      }
-      const uint4 v = reinterpret_cast<const uint4*>(y_rows + size_t(row) * H)[ch];
-      const uint32_t a[4] = {v.x, v.y, v.z, v.w};
+      } else {
+        const uint4 v = reinterpret_cast<const uint4*>(y_rows + size_t(row) * H)[ch];
+        const uint32_t a[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        acc[2 * i] = fmaf(wj, bf16_lo(a[i]), acc[2 * i]);
-        acc[2 * i + 1] = fmaf(wj, bf16_hi(a[i]), acc[2 * i + 1]);
+        for (int i = 0; i < 4; ++i) {
+          acc[2 * i] = fmaf(wj, bf16_lo(a[i]), acc[2 * i]);
+          acc[2 * i + 1] = fmaf(wj, bf16_hi(a[i]), acc[2 * i + 1]);
+        }
       }
     }
     for (int s = 0; s < n_shared; ++s) {
@@ -250,7 +252,8 @@ hipError_t launch_combine(const moe_lrc_layer* L, const void* y_rows, const floa
   const moe_lrc_config& c = L->cfg;
   // enough blocks for the chip when there are few tokens: up to one per 256 chunks of 8 columns
   const int gy = std::max(1, std::min((c.hidden / 8 + 255) / 256, (2 * L->n_cu + T - 1) / T));
-  hipLaunchKernelGGL(combine_kernel, dim3(T, gy), dim3(256), 0, s, (const uint16_t*)y_rows, y_part, kblocks,
+  auto kernel = y_part != nullptr ? combine_kernel<true> : combine_kernel<false>;
+  hipLaunchKernelGGL(kernel, dim3(T, gy), dim3(256), 0, s, (const uint16_t*)y_rows, y_part, kblocks,
                      size_t(T) * c.top_k * c.hidden, w, pair_row,
                      (const uint16_t*)y_shared, (const uint16_t*)residual, T, c.hidden, c.top_k, c.n_shared, (uint16_t*)out);
   return hipGetLastError();
