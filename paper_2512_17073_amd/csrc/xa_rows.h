@@ -77,13 +77,15 @@ __device__ __forceinline__ void xa_rows_body(const KArgs& a, const uint16_t* __r
     const bool any0 = __ballot(flagged[0]) != 0ull, any1 = __ballot(flagged[1]) != 0ull;   // block-uniform
     float4_t acc[2] = {float4_t{0.f, 0.f, 0.f, 0.f}, float4_t{0.f, 0.f, 0.f, 0.f}};
     if (live && (any0 || any1)) {
-      auto k_loop = [&](auto Q3_) {
-      constexpr bool Q3 = decltype(Q3_)::value;
-      for (int kk = kk0; kk < kk1; kk += BATCH) {
-        half8_t wf[BATCH], xf[2][BATCH];
-        uint32_t cq[BATCH], mq[BATCH];
+      // (with rows in the first row tile only, twice as many units are in flight: the second tile's registers are free)
+      auto k_loop = [&](auto Q3_, auto TWO_) {
+      constexpr bool Q3 = decltype(Q3_)::value, TWO = decltype(TWO_)::value;
+      constexpr int NB = TWO ? BATCH : 2 * BATCH, NT = TWO ? 2 : 1;
+      for (int kk = kk0; kk < kk1; kk += NB) {
+        half8_t wf[NB], xf[NT][NB];
+        uint32_t cq[NB], mq[NB];
 #pragma unroll
-        for (int u = 0; u < BATCH; ++u) {
+        for (int u = 0; u < NB; ++u) {
           const int ku = max(min(kk + u, kk1 - 1), 0);
           if constexpr (Q3) {
             cq[u] = aq[(size_t(tl) * k32 + ku) * kWave + lane];
@@ -92,8 +94,7 @@ __device__ __forceinline__ void xa_rows_body(const KArgs& a, const uint16_t* __r
             wf[u] = af[(size_t(tl) * k32 + ku) * kWave + lane];
           }
 #pragma unroll
-          for (int t = 0; t < 2; ++t) {
-            if (t == 1 && !any1) { xf[t][u] = half8_t{0, 0, 0, 0, 0, 0, 0, 0}; continue; }
+          for (int t = 0; t < NT; ++t) {
             if constexpr (TOKENS) {
               const uint4 v = xrow[t][4 * ku + q];
               const uint32_t in[4] = {v.x, v.y, v.z, v.w};
@@ -108,19 +109,19 @@ __device__ __forceinline__ void xa_rows_body(const KArgs& a, const uint16_t* __r
           }
         }
 #pragma unroll
-        for (int u = 0; u < BATCH; ++u) {
+        for (int u = 0; u < NB; ++u) {
           if constexpr (Q3) wf[u] = q3_unit_a(cq[u], mq[u]);
           if (kk + u >= kk1) wf[u] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};       // (a step past this wavefront's share)
 #pragma unroll
-          for (int t = 0; t < 2; ++t) {
+          for (int t = 0; t < NT; ++t) {
             if (!flagged[t]) xf[t][u] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
             acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[u], xf[t][u], acc[t], 0, 0, 0);
           }
         }
       }
       };
-      if (q3) k_loop(std::true_type{});
-      else k_loop(std::false_type{});
+      if (q3) { if (any1) k_loop(std::true_type{}, std::true_type{}); else k_loop(std::true_type{}, std::false_type{}); }
+      else { if (any1) k_loop(std::false_type{}, std::true_type{}); else k_loop(std::false_type{}, std::false_type{}); }
       red[wave][lane] = acc[0];
       red[NW + wave][lane] = acc[1];
       __syncthreads();
