@@ -378,8 +378,9 @@ int moe_lrc_layer_create(const moe_lrc_config* cfg, moe_lrc_layer** out) {
   LRC_TRY(hipMalloc((void**)&L->d_desc, sizeof(ExpertDesc) * L->n_total));
   LRC_TRY(hipMalloc((void**)&L->d_wg, size_t(cfg->n_experts) * cfg->hidden * 2));
   LRC_TRY(hipMalloc((void**)&L->d_bias, size_t(cfg->n_experts) * 4));
-  if (cfg->max_tokens >= 1024 && cfg->n_experts >= 128)
+  if (cfg->n_experts >= 128) {
     LRC_TRY(hipMalloc((void**)&L->d_logits, size_t(cfg->max_tokens) * cfg->n_experts * 8));
+  }
   LRC_TRY(hipMalloc((void**)&L->d_perm, kPermuteScratchInts * 4));
   LRC_TRY(hipMemset(L->d_perm, 0, kPermuteScratchInts * 4));
   LRC_TRY(hipMalloc((void**)&L->d_stat, (2 + 2 * cfg->n_experts) * 4));

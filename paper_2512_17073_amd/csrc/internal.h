@@ -64,7 +64,7 @@ struct moe_lrc_layer {
   std::vector<lrc::ExpertDesc> h_desc;
   uint16_t* d_wg = nullptr;
   float* d_bias = nullptr;
-  double* d_logits = nullptr;          // [max_tokens][E] gate logits of the tiled routing path (many tokens and experts)
+  double* d_logits = nullptr;          // [max_tokens][E] gate logits of the routing paths that go through memory (many experts)
   bool gate_set = false, has_bias = false;
   std::vector<uint8_t> mat_set;        // [n_total*3]
   std::vector<int> mat_rank;           // [n_total*3] rank of each projection's factor pair (Section 3.1: may differ)

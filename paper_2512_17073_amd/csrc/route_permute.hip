@@ -17,19 +17,26 @@ namespace {
 // current one is multiplied.  Wavefront 0 then takes the Top-k with a shuffle arg-max (ties to the
 // lower index) and the softmax weights of the selected experts.
 
+constexpr int kRouteGroups = 8;     // most blocks that share a token
+
 template <int CH, int NW>
 __global__ __launch_bounds__(64 * NW) void route_kernel(const uint16_t* __restrict__ x,
                                                     const uint16_t* __restrict__ wg,
                                                     const float* __restrict__ bias, int T, int H, int E,
                                                     int top_k, int renorm, int32_t* __restrict__ idx,
                                                     float* __restrict__ w, _Float16* __restrict__ xh,
-                                                    int32_t* __restrict__ tok_exp) {
+                                                    int32_t* __restrict__ tok_exp, double* __restrict__ logits_g) {
   __shared__ double logit[kMaxExperts];
   const int t = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // Few tokens and many experts: gridDim.y blocks share a token's gate rows (block g takes experts
+  // g * epg .. + epg - 1) and leave their logits (without the bias) in logits_g [T][E]; topk_kernel
+  // follows in a launch of its own.
+  const int G = gridDim.y, g = blockIdx.y;
+  const int epg = (E + G - 1) / G, e_lo = g * epg, e_hi = min(E, e_lo + epg);
   const uint4* xrow = reinterpret_cast<const uint4*>(x + size_t(t) * H);
   const int chunks = H / 8;
 
-  if (xh != nullptr) {     // fp16 copy of the token for the expert kernels (exact for |x| < 65504)
+  if (xh != nullptr && g == 0) {     // fp16 copy of the token for the expert kernels (exact for |x| < 65504)
     for (int c = threadIdx.x; c < chunks; c += 64 * NW) {
       const uint4 v = xrow[c];
       const uint32_t in[4] = {v.x, v.y, v.z, v.w};
@@ -50,7 +57,7 @@ __global__ __launch_bounds__(64 * NW) void route_kernel(const uint16_t* __restri
     const int c = lane + 64 * j;
     xv[j] = c < chunks ? xrow[c] : make_uint4(0, 0, 0, 0);
   }
-  if (tok_exp != nullptr && wave == 0) {
+  if (tok_exp != nullptr && wave == 0 && g == 0) {
     // exponent of the token's power-of-two pre-scale for the expert kernels: 2^s brings its largest
     // magnitude into [1, 2), s within +-60, 0 for a token of zeros
     uint32_t m = 0;
@@ -74,8 +81,8 @@ __global__ __launch_bounds__(64 * NW) void route_kernel(const uint16_t* __restri
     }
   };
   uint4 wcur[CH], wnext[CH];
-  load_row(wave, wcur);
-  for (int e = wave; e < E; e += NW) {
+  load_row(e_lo + wave, wcur);
+  for (int e = e_lo + wave; e < e_hi; e += NW) {
     load_row(e + NW, wnext);                               // (clamped past the last row; unused then)
     double acc = 0.0;
 #pragma unroll
@@ -88,10 +95,14 @@ __global__ __launch_bounds__(64 * NW) void route_kernel(const uint16_t* __restri
       }
     }
     acc = wave_sum(acc);
-    if (lane == 0) logit[e] = acc + (bias ? (double)bias[e] : 0.0);
+    if (lane == 0) {
+      if (G == 1) logit[e] = acc + (bias ? (double)bias[e] : 0.0);
+      else logits_g[size_t(t) * E + e] = acc;
+    }
 #pragma unroll
     for (int j = 0; j < CH; ++j) wcur[j] = wnext[j];
   }
+  if (G > 1) return;
   __syncthreads();
   if (wave != 0) return;
 
@@ -308,15 +319,23 @@ hipError_t launch_route(const moe_lrc_layer* L, const void* x, int T, int32_t* i
     return hipGetLastError();
   }
   const int ch = (c.hidden / 8 + 63) / 64;      // 16-byte chunks of a row per lane
-  auto go = [&](auto kernel, int nw) {
-    hipLaunchKernelGGL(kernel, dim3(T), dim3(64 * nw), 0, s, (const uint16_t*)x, L->d_wg,
-                       L->has_bias ? L->d_bias : nullptr, T, c.hidden, c.n_experts, c.top_k,
-                       c.renormalize, idx, w, xh, tok_exp);
-  };
   // 16 wavefronts per token when every wavefront would otherwise walk 16 or more gate rows one
   // after the other, the chunks of a row fit the smaller register budget, and the launch is bound
   // by that latency rather than by throughput (few tokens)
   const bool wide = c.n_experts >= 64 && ch <= 8 && T <= 128;
+  // ... and, while the tokens alone leave CUs idle, several blocks per token, each with at least
+  // one gate row per wavefront (the fp64 dot products of a token's rows are what the launch takes)
+  int G = 1;
+  if (wide && L->d_logits != nullptr && T <= c.max_tokens)
+    while (G < kRouteGroups && T * G * 2 <= L->n_cu && c.n_experts / (G * 2) >= 16) G *= 2;
+  auto go = [&](auto kernel, int nw) {
+    hipLaunchKernelGGL(kernel, dim3(T, G), dim3(64 * nw), 0, s, (const uint16_t*)x, L->d_wg,
+                       L->has_bias ? L->d_bias : nullptr, T, c.hidden, c.n_experts, c.top_k,
+                       c.renormalize, idx, w, xh, tok_exp, L->d_logits);
+    if (G > 1)
+      hipLaunchKernelGGL(topk_kernel, dim3((T + 3) / 4), dim3(256), 0, s, L->d_logits,
+                         L->has_bias ? L->d_bias : nullptr, T, c.n_experts, c.top_k, c.renormalize, idx, w);
+  };
   if (ch <= 1) wide ? go(route_kernel<1, 16>, 16) : go(route_kernel<1, 4>, 4);
   else if (ch <= 2) wide ? go(route_kernel<2, 16>, 16) : go(route_kernel<2, 4>, 4);
   else if (ch <= 4) wide ? go(route_kernel<4, 16>, 16) : go(route_kernel<4, 4>, 4);

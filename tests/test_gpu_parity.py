@@ -372,6 +372,30 @@ def test_route_tiled_path_many_tokens_and_experts(amd):
     L.close()
 
 
+def test_route_with_several_blocks_per_token(amd):
+    """With few tokens and 128 experts or more, several blocks share a token's gate rows and leave
+    their logits in memory for the Top-k launch that follows.  Batches of different sizes, hence
+    different numbers of blocks per token, one after the other on one layer: indices bit-exact every
+    time, a duplicated gate row and a ragged expert count (136) included."""
+    for E in (128, 136):
+        cfg = configs.QWEN3.with_(hidden=512, ffn=256, group=64, n_experts=E, tokens=100, rank=0, top_n=0, name=f"route_split_{E}")
+        wg, bias = synth.make_gate(cfg)
+        wg = wg.copy()
+        wg[3] = wg[E - 2]                   # equal logits in different blocks' shares: the lower index wins
+        if bias is not None:
+            bias = bias.copy(); bias[3] = bias[E - 2]
+        x_bits = synth.make_tokens(cfg)
+        ref = orc.route(x_bits, wg, cfg.top_k, cfg.renormalize, bias)
+        L = amd.Layer.from_config(cfg)
+        L.set_gate(wg, bias)
+        x = amd.bf16_tensor(x_bits)
+        for T in (1, 100, 3, 16, 1, 64, 17, 100):
+            idx, w = L.route(x[:T])
+            np.testing.assert_array_equal(_to_np(idx), ref["idx"][:T], err_msg=f"E={E} T={T}")
+            np.testing.assert_allclose(_to_np(w), ref["w"][:T], rtol=2e-6, atol=1e-30)
+        L.close()
+
+
 @pytest.mark.parametrize("tokens", [16, 300])
 def test_rank_per_projection_from_kurtosis(amd, tokens):
     """Section 3.1 step 1: the rank budget is spread over the expert matrices by their kurtosis, so
