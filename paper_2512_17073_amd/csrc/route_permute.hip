@@ -194,18 +194,16 @@ __global__ __launch_bounds__(1024) void permute_kernel(const int32_t* __restrict
 
 // Many pairs: the same grouping by several blocks, in two launches.  Block b owns the pairs
 // [b * slice, (b + 1) * slice).  The first launch counts every block's pairs per expert into
-// `scratch` ([block][2][E]: all pairs, pairs that take the rank-r term); the block that finishes last
-// adds them up (counts, offsets, comp_counts) and replaces every block's counts by the position of
-// its first pair of each expert.  The second launch scatters: inside a block as in permute_body
-// (wavefront w owns a contiguous run, equal experts of a 64-pair step are ranked by ballots), so
-// the order of the pairs (= token order) is kept.  The last entry of scratch counts the finished blocks
-// (left at zero).
+// `scratch` ([block][2][E]: all pairs, pairs that take the rank-r term).  The second launch scatters:
+// every block first adds up all blocks' counts (block 0 writes counts, offsets and comp_counts) and
+// so finds where its own pairs of each expert begin; inside a block as in permute_body (wavefront
+// w owns a contiguous run, equal experts of a 64-pair step are ranked by ballots), so the order of
+// the pairs (= token order) is kept.  The launch boundary orders the two: no fence, no counter (a
+// device-scope fence writes back the whole L2 on this chip).
 __global__ __launch_bounds__(1024) void permute_count_kernel(const int32_t* __restrict__ idx, int P, int E, int top_k, int top_n,
-                                                             int slice, int32_t* scratch, int32_t* __restrict__ counts,
-                                                             int32_t* __restrict__ offsets, int32_t* __restrict__ comp_counts) {
-  __shared__ int32_t hist[kMaxExperts], comp[kMaxExperts], total[kMaxExperts];
-  __shared__ int last;
-  const int b = blockIdx.x, nb = gridDim.x;
+                                                             int slice, int32_t* __restrict__ scratch) {
+  __shared__ int32_t hist[kMaxExperts], comp[kMaxExperts];
+  const int b = blockIdx.x;
   for (int e = threadIdx.x; e < E; e += 1024) { hist[e] = 0; comp[e] = 0; }
   __syncthreads();
   const int begin = b * slice, end = min(P, begin + slice);
@@ -219,45 +217,29 @@ __global__ __launch_bounds__(1024) void permute_count_kernel(const int32_t* __re
     scratch[(b * 2 + 0) * E + e] = hist[e];
     scratch[(b * 2 + 1) * E + e] = comp[e];
   }
-  __threadfence();
-  __syncthreads();
-  if (threadIdx.x == 0) last = atomicAdd(&scratch[kPermuteMaxBlocks * 2 * kMaxExperts], 1) == nb - 1;
-  __syncthreads();
-  if (!last) return;
-  __threadfence();
-  if ((int)threadIdx.x < E) {
-    const int e = threadIdx.x;
-    int run = 0, crun = 0;
-    for (int bb = 0; bb < nb; ++bb) {
-      run += __hip_atomic_load(&scratch[(bb * 2 + 0) * E + e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      crun += __hip_atomic_load(&scratch[(bb * 2 + 1) * E + e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    total[e] = run;
-    counts[e] = run;
-    comp_counts[e] = crun;
-  }
-  __syncthreads();
-  if ((int)threadIdx.x < E) {
-    const int e = threadIdx.x;
-    int off = 0;
-    for (int e2 = 0; e2 < e; ++e2) off += total[e2];
-    offsets[e] = off;
-    if (e == E - 1) offsets[E] = off + total[e];
-    for (int bb = 0; bb < nb; ++bb) {
-      const int c = __hip_atomic_load(&scratch[(bb * 2 + 0) * E + e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      scratch[(bb * 2 + 0) * E + e] = off;
-      off += c;
-    }
-  }
-  if (threadIdx.x == 0) scratch[kPermuteMaxBlocks * 2 * kMaxExperts] = 0;
 }
 
 __global__ __launch_bounds__(1024) void permute_scatter_kernel(const int32_t* __restrict__ idx, int P, int E, int slice,
-                                                               const int32_t* __restrict__ scratch,
+                                                               const int32_t* __restrict__ scratch, int32_t* __restrict__ counts,
+                                                               int32_t* __restrict__ offsets, int32_t* __restrict__ comp_counts,
                                                                int32_t* __restrict__ row_pair, int32_t* __restrict__ pair_row) {
   __shared__ int32_t hist[kPermWaves][kMaxExperts];
-  const int b = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __shared__ int32_t total[kMaxExperts], before[kMaxExperts];
+  const int b = blockIdx.x, nb = gridDim.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   for (int i = threadIdx.x; i < kPermWaves * kMaxExperts; i += 1024) (&hist[0][0])[i] = 0;
+  // every block adds up the counts of all blocks (block 0 writes the sums out) ...
+  if ((int)threadIdx.x < E) {
+    const int e = threadIdx.x;
+    int run = 0, crun = 0, mine = 0;
+    for (int bb = 0; bb < nb; ++bb) {
+      if (bb == b) mine = run;                              // pairs of this expert in the blocks before this one
+      run += scratch[(bb * 2 + 0) * E + e];
+      crun += scratch[(bb * 2 + 1) * E + e];
+    }
+    total[e] = run;
+    before[e] = mine;
+    if (b == 0) { counts[e] = run; comp_counts[e] = crun; }
+  }
   __syncthreads();
   const int s_begin = b * slice, s_end = min(P, s_begin + slice);
   const int per_wave = ((s_end - s_begin + kPermWaves - 1) / kPermWaves + 63) / 64 * 64;
@@ -265,10 +247,18 @@ __global__ __launch_bounds__(1024) void permute_scatter_kernel(const int32_t* __
   for (int i = begin + lane; i < end; i += 64) atomicAdd(&hist[wave][min(max(idx[i], 0), E - 1)], 1);
   __syncthreads();
   if ((int)threadIdx.x < E) {
-    int run = scratch[(b * 2 + 0) * E + threadIdx.x];       // position of this block's first pair of the expert
+    // ... and finds where its own pairs of each expert begin: the expert's offset, then the blocks before it
+    const int e = threadIdx.x;
+    int off = 0;
+    for (int e2 = 0; e2 < e; ++e2) off += total[e2];
+    if (b == 0) {
+      offsets[e] = off;
+      if (e == E - 1) offsets[E] = off + total[e];
+    }
+    int run = off + before[e];
     for (int wv = 0; wv < kPermWaves; ++wv) {
-      const int c = hist[wv][threadIdx.x];
-      hist[wv][threadIdx.x] = run;
+      const int c = hist[wv][e];
+      hist[wv][e] = run;
       run += c;
     }
   }
@@ -356,9 +346,9 @@ hipError_t launch_permute(const moe_lrc_layer* L, const int32_t* idx, int T, int
     const int slice = std::max(2048, ((P + kPermuteMaxBlocks - 1) / kPermuteMaxBlocks + 63) / 64 * 64);
     const int nb = (P + slice - 1) / slice;
     hipLaunchKernelGGL(permute_count_kernel, dim3(nb), dim3(1024), 0, s, idx, P, c.n_experts, c.top_k, c.top_n, slice,
-                       L->d_perm, counts, offsets, comp_counts);
-    hipLaunchKernelGGL(permute_scatter_kernel, dim3(nb), dim3(1024), 0, s, idx, P, c.n_experts, slice, L->d_perm, row_pair,
-                       pair_row);
+                       L->d_perm);
+    hipLaunchKernelGGL(permute_scatter_kernel, dim3(nb), dim3(1024), 0, s, idx, P, c.n_experts, slice, L->d_perm, counts,
+                       offsets, comp_counts, row_pair, pair_row);
     return hipGetLastError();
   }
   hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(1024), 0, s, idx, P, c.n_experts,
