@@ -107,8 +107,8 @@ def test_permute_bit_exact(case):
                                                          (61, 6, 2, 3000)])
 def test_permute_by_several_blocks(amd, experts, top_k, top_n, tokens):
     """Above 8192 pairs the grouping runs as two launches of several blocks: bit-exact against the
-    oracle for ragged sizes, skewed expert loads and experts without rows, twice in a row (the block
-    counter is left at zero), then once more with a smaller batch (another number of blocks)."""
+    oracle for ragged sizes, skewed expert loads and experts without rows, twice in a row, then once
+    more with a smaller batch (another number of blocks)."""
     import torch
     cfg = configs.TINY.with_(n_experts=experts, top_k=top_k, top_n=top_n, tokens=tokens, rank=0, name="perm_blocks")
     L = amd.Layer.from_config(cfg, max_tokens=tokens)
