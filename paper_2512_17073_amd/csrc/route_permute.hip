@@ -329,7 +329,8 @@ hipError_t launch_route(const moe_lrc_layer* L, const void* x, int T, int32_t* i
   if (ch <= 1) wide ? go(route_kernel<1, 16>, 16) : go(route_kernel<1, 4>, 4);
   else if (ch <= 2) wide ? go(route_kernel<2, 16>, 16) : go(route_kernel<2, 4>, 4);
   else if (ch <= 4) wide ? go(route_kernel<4, 16>, 16) : go(route_kernel<4, 4>, 4);
-  else if (ch <= 8) wide ? go(route_kernel<8, 16>, 16) : go(route_kernel<8, 4>, 4);
+  // (eight wavefronts when that gives every gate row a wavefront of its own and the tokens are few)
+  else if (ch <= 8) wide ? go(route_kernel<8, 16>, 16) : (c.n_experts <= 8 && T <= 256) ? go(route_kernel<8, 8>, 8) : go(route_kernel<8, 4>, 4);
   else if (ch <= 16) go(route_kernel<16, 4>, 4);
   else if (ch <= 32) go(route_kernel<32, 4>, 4);
   else return hipErrorInvalidValue;             // hidden > 16384 (layer_create rejects it)
