@@ -144,6 +144,10 @@ int moe_lrc_set_expert_factors_quantized(moe_lrc_layer* layer, int expert, int m
 /* Bytes of device workspace the hot-path calls need for T tokens (the largest over all calls). */
 size_t moe_lrc_workspace_bytes(const moe_lrc_layer* layer, int T);
 
+/* An empty batch (T = 0) is accepted by every hot-path call: it launches nothing and returns
+ * MOE_LRC_OK; the per-token buffers (x, topk_idx, topk_w, row_pair, pair_row, y_rows, out, the
+ * workspace) are not touched and may be null.  moe_lrc_permute still writes counts, offsets and
+ * comp_counts (all zero). */
 /* Routing (Section 2.1) and Top-n order (Section 3.2).
  *   x_bf16    device [T][H]
  *   topk_idx  device [T][k] int32, experts in descending score order, ties to the lower index;

@@ -582,9 +582,9 @@ size_t moe_lrc_workspace_bytes(const moe_lrc_layer* L, int T) {
 int moe_lrc_route(moe_lrc_layer* L, const void* x, int T, int32_t* idx, float* w, void* stream) {
   int rc = check_hot(L, T, "route");
   if (rc) return rc;
-  if (!x || !idx || !w) return set_error(MOE_LRC_EINVAL, "route: null argument");
   if (!L->gate_set) return set_error(MOE_LRC_ESTATE, "route: gate not uploaded");
-  if (T == 0) return MOE_LRC_OK;
+  if (T == 0) return MOE_LRC_OK;                 // (an empty batch: the per-token buffers may be null)
+  if (!x || !idx || !w) return set_error(MOE_LRC_EINVAL, "route: null argument");
   LRC_HIP(launch_route(L, x, T, idx, w, nullptr, nullptr, (hipStream_t)stream));
   return MOE_LRC_OK;
 }
@@ -593,7 +593,7 @@ int moe_lrc_permute(moe_lrc_layer* L, const int32_t* idx, int T, int32_t* counts
                     int32_t* row_pair, int32_t* pair_row, int32_t* comp_counts, void* stream) {
   int rc = check_hot(L, T, "permute");
   if (rc) return rc;
-  if (!idx || !counts || !offsets || !row_pair || !pair_row || !comp_counts)
+  if (!counts || !offsets || !comp_counts || (T > 0 && (!idx || !row_pair || !pair_row)))
     return set_error(MOE_LRC_EINVAL, "permute: null argument");
   LRC_HIP(launch_permute(L, idx, T, counts, offsets, row_pair, pair_row, comp_counts, (hipStream_t)stream));
   return MOE_LRC_OK;
@@ -603,12 +603,12 @@ int moe_lrc_expert_ffn(moe_lrc_layer* L, const void* x, int T, const int32_t* of
                        const int32_t* row_pair, void* y_rows, void* ws, size_t ws_bytes, void* stream) {
   int rc = check_hot(L, T, "expert_ffn");
   if (rc) return rc;
-  if (!x || !offsets || !row_pair || !y_rows) return set_error(MOE_LRC_EINVAL, "expert_ffn: null argument");
-  if ((rc = check_ws(L, T, ws, ws_bytes, "expert_ffn"))) return rc;
   if ((rc = check_uploaded(L, "expert_ffn", true, false))) return rc;
   if (L->cfg.residency == MOE_LRC_POOLED)
     return set_error(MOE_LRC_ESTATE, "expert_ffn: a pooled layer runs through moe_lrc_stack_step only");
   if (T == 0) return MOE_LRC_OK;
+  if (!x || !offsets || !row_pair || !y_rows) return set_error(MOE_LRC_EINVAL, "expert_ffn: null argument");
+  if ((rc = check_ws(L, T, ws, ws_bytes, "expert_ffn"))) return rc;
   return run_expert_ffn(L, x, T, offsets, row_pair, y_rows, (uint8_t*)ws, (hipStream_t)stream);
 }
 
@@ -616,8 +616,9 @@ int moe_lrc_combine(moe_lrc_layer* L, const void* y_rows, const float* w, const 
                     const void* x, int T, void* out, void* ws, size_t ws_bytes, void* stream) {
   int rc = check_hot(L, T, "combine");
   if (rc) return rc;
-  if (!y_rows || !w || !pair_row || !out) return set_error(MOE_LRC_EINVAL, "combine: null argument");
   const bool shared = L->cfg.n_shared > 0;
+  if (T == 0) return (shared && (rc = check_uploaded(L, "combine", false, true))) ? rc : MOE_LRC_OK;
+  if (!y_rows || !w || !pair_row || !out) return set_error(MOE_LRC_EINVAL, "combine: null argument");
   if (shared) {
     if (!x) return set_error(MOE_LRC_EINVAL, "combine: x is required when the layer has shared experts");
     if ((rc = check_ws(L, T, ws, ws_bytes, "combine"))) return rc;
@@ -637,13 +638,13 @@ int moe_lrc_combine(moe_lrc_layer* L, const void* y_rows, const float* w, const 
 int moe_lrc_forward(moe_lrc_layer* L, const void* x, int T, void* out, void* ws, size_t ws_bytes, void* stream) {
   int rc = check_hot(L, T, "forward");
   if (rc) return rc;
-  if (!x || !out) return set_error(MOE_LRC_EINVAL, "forward: null argument");
-  if ((rc = check_ws(L, T, ws, ws_bytes, "forward"))) return rc;
   if (!L->gate_set) return set_error(MOE_LRC_ESTATE, "forward: gate not uploaded");
   if ((rc = check_uploaded(L, "forward", true, true))) return rc;
   if (L->cfg.residency == MOE_LRC_POOLED)
     return set_error(MOE_LRC_ESTATE, "forward: a pooled layer runs through moe_lrc_stack_step only");
   if (T == 0) return MOE_LRC_OK;
+  if (!x || !out) return set_error(MOE_LRC_EINVAL, "forward: null argument");
+  if ((rc = check_ws(L, T, ws, ws_bytes, "forward"))) return rc;
   return forward_impl(L, x, T, out, ws, (hipStream_t)stream, nullptr);
 }
 

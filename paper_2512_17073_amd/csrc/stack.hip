@@ -322,7 +322,7 @@ int moe_lrc_stack_reset(moe_lrc_stack* S) {
 }
 
 int moe_lrc_stack_step(moe_lrc_stack* S, const void* x, int T, void* out, void* layer_inputs, void* stream) {
-  if (!S || !x || !out) return set_error(MOE_LRC_EINVAL, "stack_step: null argument");
+  if (!S) return set_error(MOE_LRC_EINVAL, "stack_step: null argument");
   if (T < 0 || T > S->max_tokens) return set_error(MOE_LRC_ESTATE, "stack_step: T outside 0..max_tokens");
   int dev = 0;
   LRC_HIP(hipGetDevice(&dev));
@@ -332,7 +332,8 @@ int moe_lrc_stack_step(moe_lrc_stack* S, const void* x, int T, void* out, void* 
     for (size_t i = 0; i < L->mat_set.size(); ++i)
       if (!L->mat_set[i]) return set_error(MOE_LRC_ESTATE, "stack_step: an expert projection is not uploaded");
   }
-  if (T == 0) return MOE_LRC_OK;
+  if (T == 0) return MOE_LRC_OK;                 // (an empty batch: the per-token buffers may be null)
+  if (!x || !out) return set_error(MOE_LRC_EINVAL, "stack_step: null argument");
   hipStream_t s = (hipStream_t)stream;
   const auto t0 = std::chrono::steady_clock::now();
   S->c0_recorded = false;

@@ -292,6 +292,33 @@ def test_staged_mode_matches_resident(amd):
     Lr.close(); Ls.close()
 
 
+def test_empty_batch(amd):
+    """T = 0: every hot-path call returns without touching its per-token buffers (empty tensors have
+    null data pointers); the grouping still reports zero rows for every expert."""
+    import torch
+    cfg = configs.TINY
+    layer, L = _build(amd, cfg)
+    x0 = torch.empty((0, cfg.hidden), dtype=torch.bfloat16, device="cuda")
+    idx, w = L.route(x0)
+    assert idx.shape == (0, cfg.top_k) and w.shape == (0, cfg.top_k)
+    counts, offsets, row_pair, pair_row, comp = L.permute(idx)
+    torch.cuda.synchronize()
+    assert not counts.any() and not offsets.any() and not comp.any()
+    y = L.expert_ffn(x0, offsets, row_pair)
+    out = L.combine(y, w, pair_row, x0)
+    assert y.shape == (0, cfg.hidden) and out.shape == (0, cfg.hidden)
+    assert L.forward(x0).shape == (0, cfg.hidden)
+    sentinel = torch.full((4, cfg.hidden), 1.5, dtype=torch.bfloat16, device="cuda")
+    L.forward(x0, out=sentinel[:0])
+    torch.cuda.synchronize()
+    assert (sentinel == 1.5).all()
+    # and the layer still works afterwards
+    x_bits = synth.make_tokens(cfg)
+    ref = fixtures.oracle_forward(cfg, layer, x_bits)
+    assert orc.rel_frobenius(_to_np(L.forward(amd.bf16_tensor(x_bits))), ref["out"]) <= TOL
+    L.close()
+
+
 def test_hot_path_argument_errors(amd):
     import torch
     cfg = configs.TINY
