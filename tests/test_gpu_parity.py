@@ -55,6 +55,8 @@ SMALL = {
     # a single expert: every token routes to it with weight 1, k = n = 1
     "tiny_e1": configs.TINY.with_(n_experts=1, top_k=1, top_n=1, tokens=40, name="tiny_e1"),
     "tiny_T1": configs.TINY.with_(tokens=1, name="tiny_T1"),
+    # the limits of the configuration: 256 experts, k = 16 (n = 15), some experts without rows
+    "tiny_e256_k16": configs.TINY.with_(n_experts=256, top_k=16, top_n=15, tokens=40, ffn=256, rank=8, name="tiny_e256_k16"),
     "tiny_renorm": configs.TINY.with_(renormalize=1, tokens=33, name="tiny_renorm"),
     # DeepSeek-shaped: shared experts at 4 bit, FFN 1408 (not a multiple of the 256-row k-step), k=6
     "deepseek_small": configs.DEEPSEEK.with_(hidden=512, n_experts=16, tokens=70, name="deepseek_small"),
