@@ -401,6 +401,25 @@ def test_route_tiled_path_many_tokens_and_experts(amd):
     L.close()
 
 
+@pytest.mark.parametrize("hidden,experts", [(64, 8), (1024, 64), (2048, 8), (8192, 8), (8192, 64), (16384, 8), (16384, 130)])
+def test_route_over_hidden_sizes(amd, hidden, experts):
+    """Every variant of the per-token routing kernel (1 to 32 chunks of a row per lane, 4 or 16
+    wavefronts per token), up to the largest hidden size a layer accepts: indices bit-exact."""
+    cfg = configs.TINY.with_(hidden=hidden, ffn=64, group=64, n_experts=experts, top_k=min(6, experts), top_n=0, rank=0,
+                             tokens=9, name=f"route_h{hidden}_e{experts}")
+    wg, bias = synth.make_gate(cfg)
+    wg = wg.copy()
+    wg[1] = wg[experts - 1]             # equal logits: the lower index wins
+    x_bits = synth.make_tokens(cfg)
+    ref = orc.route(x_bits, wg, cfg.top_k, cfg.renormalize, bias)
+    L = amd.Layer.from_config(cfg)
+    L.set_gate(wg, bias)
+    idx, w = L.route(amd.bf16_tensor(x_bits))
+    np.testing.assert_array_equal(_to_np(idx), ref["idx"])
+    np.testing.assert_allclose(_to_np(w), ref["w"], rtol=2e-6, atol=1e-30)
+    L.close()
+
+
 def test_route_with_several_blocks_per_token(amd):
     """With few tokens and 128 experts or more, several blocks share a token's gate rows and leave
     their logits in memory for the Top-k launch that follows.  Batches of different sizes, hence
