@@ -15,9 +15,10 @@ def _kblocks(ffn):
     return min(8, (ks + 15) // 16)
 
 
-@pytest.mark.parametrize("hidden,ffn", [(256, 512), (512, 768), (2048, 1408), (2048, 768), (4096, 14336)])
+# (the last two: the longest K of either projection that a layer accepts: several staging phases per K-block)
+@pytest.mark.parametrize("hidden,ffn", [(256, 512), (512, 768), (2048, 1408), (2048, 768), (4096, 14336), (256, 65536), (16384, 512)])
 def test_index_model_over_ranks_and_shares(hidden, ffn):
-    big = hidden >= 4096
+    big = hidden >= 4096 or ffn >= 65536
     layer_ranks = (0, 8, 32, 40, 256, 1024) if not big else (32, 1024)
     for bits, group, layer_rank in itertools.product((2, 3, 4) if not big else (2, 3), (64, 128) if not big else (64,), layer_ranks):
         if hidden % group or ffn % group:

@@ -294,6 +294,23 @@ def test_staged_mode_matches_resident(amd):
     Lr.close(); Ls.close()
 
 
+def test_long_k_several_staging_phases(amd):
+    """An FFN width of 36864: the decode flavour's W2 launch splits its K into 8 K-blocks of 18
+    k-steps, i.e. two staging phases per block with one row tile and three with two (the Mixtral
+    shape has one and two).  Two experts, k = 2: each holds every token, so 20 tokens take the
+    two-row-tile body and their first 10 the one-row-tile body."""
+    cfg = configs.TINY.with_(n_experts=2, top_k=2, top_n=1, tokens=20, ffn=36864, bits=2, rank=8, name="long_k")
+    layer, L = _build(amd, cfg)
+    x_bits = synth.make_tokens(cfg)
+    for T in (20, 10):
+        ref = fixtures.oracle_forward(cfg.with_(tokens=T), layer, x_bits[:T])
+        out = L.forward(amd.bf16_tensor(x_bits[:T]))
+        err = orc.rel_frobenius(_to_np(out), ref["out"])
+        print(f"[long_k] T={T}: {err:.2e}")
+        assert err <= TOL
+    L.close()
+
+
 def test_empty_batch(amd):
     """T = 0: every hot-path call returns without touching its per-token buffers (empty tensors have
     null data pointers); the grouping still reports zero rows for every expert."""
