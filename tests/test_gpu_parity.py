@@ -299,16 +299,19 @@ def test_long_k_several_staging_phases(amd):
     k-steps, i.e. two staging phases per block with one row tile and three with two (the Mixtral
     shape has one and two).  Two experts, k = 2: each holds every token, so 20 tokens take the
     two-row-tile body and their first 10 the one-row-tile body."""
-    cfg = configs.TINY.with_(n_experts=2, top_k=2, top_n=1, tokens=20, ffn=36864, bits=2, rank=8, name="long_k")
-    layer, L = _build(amd, cfg)
-    x_bits = synth.make_tokens(cfg)
-    for T in (20, 10):
-        ref = fixtures.oracle_forward(cfg.with_(tokens=T), layer, x_bits[:T])
-        out = L.forward(amd.bf16_tensor(x_bits[:T]))
-        err = orc.rel_frobenius(_to_np(out), ref["out"])
-        print(f"[long_k] T={T}: {err:.2e}")
-        assert err <= TOL
-    L.close()
+    # the same for the fused projection, whose K is the hidden size and is not split into K-blocks:
+    # the largest hidden size a layer accepts gives four and eight phases
+    for cfg in (configs.TINY.with_(n_experts=2, top_k=2, top_n=1, tokens=20, ffn=36864, bits=2, rank=8, name="long_k"),
+                configs.TINY.with_(n_experts=2, top_k=2, top_n=1, tokens=20, hidden=16384, ffn=256, bits=3, rank=8, name="long_h")):
+        layer, L = _build(amd, cfg)
+        x_bits = synth.make_tokens(cfg)
+        for T in (20, 10):
+            ref = fixtures.oracle_forward(cfg.with_(tokens=T), layer, x_bits[:T])
+            out = L.forward(amd.bf16_tensor(x_bits[:T]))
+            err = orc.rel_frobenius(_to_np(out), ref["out"])
+            print(f"[{cfg.name}] T={T}: {err:.2e}")
+            assert err <= TOL
+        L.close()
 
 
 def test_empty_batch(amd):
