@@ -301,11 +301,12 @@ def test_long_k_several_staging_phases(amd):
     two-row-tile body and their first 10 the one-row-tile body."""
     # the same for the fused projection, whose K is the hidden size and is not split into K-blocks:
     # the largest hidden size a layer accepts gives four and eight phases
-    for cfg in (configs.TINY.with_(n_experts=2, top_k=2, top_n=1, tokens=20, ffn=36864, bits=2, rank=8, name="long_k"),
-                configs.TINY.with_(n_experts=2, top_k=2, top_n=1, tokens=20, hidden=16384, ffn=256, bits=3, rank=8, name="long_h")):
+    # (and 150 tokens: the grouped-GEMM flavour, two chunks per expert, over the same long K)
+    for cfg in (configs.TINY.with_(n_experts=2, top_k=2, top_n=1, tokens=150, ffn=36864, bits=2, rank=8, name="long_k"),
+                configs.TINY.with_(n_experts=2, top_k=2, top_n=1, tokens=150, hidden=16384, ffn=256, bits=3, rank=8, name="long_h")):
         layer, L = _build(amd, cfg)
         x_bits = synth.make_tokens(cfg)
-        for T in (20, 10):
+        for T in (20, 10, 150):
             ref = fixtures.oracle_forward(cfg.with_(tokens=T), layer, x_bits[:T])
             out = L.forward(amd.bf16_tensor(x_bits[:T]))
             err = orc.rel_frobenius(_to_np(out), ref["out"])
