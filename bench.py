@@ -182,6 +182,49 @@ def offline_bench(args, cfg):
         "dtype": "f64", "data": "synthetic"}))
 
 
+def sample_clocks(step, torch, seconds: float = 4.0) -> dict:
+    """Shader clock (MHz) as `rocm-smi --showclocks` reads it while `step` runs back to back for a few
+    seconds, and again after the device has been idle for a second (read-only queries from a thread)."""
+    import re
+    import subprocess
+    import threading
+
+    def read_sclk():
+        try:
+            r = subprocess.run(["/opt/rocm/bin/rocm-smi", "--showclocks", "--json"], capture_output=True, text=True, timeout=20)
+            m = re.search(r"sclk clock speed:\W+(\d+)Mhz", r.stdout)
+            return int(m.group(1)) if m else None
+        except Exception:
+            return None
+
+    busy, stop = [], threading.Event()
+
+    def poll():
+        while not stop.is_set():
+            v = read_sclk()
+            if v is not None:
+                busy.append(v)
+            time.sleep(0.1)
+
+    th = threading.Thread(target=poll, daemon=True)
+    t0 = time.time()
+    th.start()
+    i = 0
+    while time.time() - t0 < seconds:
+        for _ in range(200):
+            step(i)
+            i += 1
+        torch.cuda.synchronize()
+    stop.set()
+    th.join(timeout=30)
+    time.sleep(1.0)
+    idle = read_sclk()
+    busy = sorted(busy[1:])               # (the first reading may predate the loop)
+    return {"sclk_mhz_under_load_median": busy[len(busy) // 2] if busy else None,
+            "sclk_mhz_under_load_min": busy[0] if busy else None, "sclk_mhz_under_load_max": busy[-1] if busy else None,
+            "samples": len(busy), "sclk_mhz_after_the_loop": idle, "forwards": i, "source": "rocm-smi --showclocks"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -204,6 +247,9 @@ def main():
     ap.add_argument("--calibrate", action="store_true",
                     help="also measure what this device sustains (streaming read of 3 GiB, pinned host->device "
                          "copy, f16 MFMA rate) and report it as roofline.peak_measured beside the published peaks")
+    ap.add_argument("--clocks", action="store_true",
+                    help="also run the forward in a loop of a few seconds and report the shader clock rocm-smi reads meanwhile "
+                         "(and after the loop): the clock under this load is set by power")
     ap.add_argument("--calib-copy", action="store_true",
                     help="after the timed region run an elementwise kernel that reads and writes 256 MiB, "
                          "so that a counter run can scale FETCH_SIZE / WRITE_SIZE by a known transfer")
@@ -456,6 +502,8 @@ def main():
                    "experts_copied": int(sst["active_experts"]), "factor_sets_copied": int(sst["comp_experts"]),
                    "bytes_factors": int(sst["bytes_factors"]), "factors": "int3" if args.staged_int3 else "bf16"}
         Ls.close()
+    if args.clocks:
+        result["clocks"] = sample_clocks(eager_step, torch)
     if args.calib_copy:
         src = torch.zeros(64 << 20, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
